@@ -1,0 +1,413 @@
+"""Plain CPU oracle of the cache-gated transformer layer (LLMCache).
+
+TEST INFRASTRUCTURE ONLY.  This file is the slow, obviously-correct statement of
+what the path computes, written from the paper; it is imported by the tests, by
+the smoke check and by the benchmark's CPU-baseline leg, and by nothing else.
+It shares no code with the HIP library and never imports it.
+
+Everything is numpy in float64.  Inputs are the *stored* values of the run
+(fp32, or bf16 widened exactly to fp32/fp64); no intermediate rounding of the
+run dtype is emulated except where the method itself stores a rounded value
+(the fingerprint key, Section III-B: the bank holds the key that is compared).
+
+What follows the paper, and where:
+
+* fingerprint  -- Section IV-B: average of the token vectors, then a linear
+  dimensionality reduction; Section III-A: a fixed-length key.
+* match        -- Section III-C / Algorithm 1: "exists an entry with
+  sim > tau"  <=>  max_j sim_j > tau, sim = cosine similarity.
+* threshold    -- Section IV-A case equation and Algorithm 1: strict ">".
+* gated layer  -- Section IV-A case equation: cached h_l on a hit, f_l(h_{l-1})
+  otherwise; Algorithm 1: store the computed h_l on a miss.
+* eviction     -- Section IV-D, first policy: least recently used.
+* f_l          -- Section V-A names the model families; the blocks themselves
+  are the textbook post-LN encoder block and pre-LN causal decoder block.
+
+Pins (see tests/test_oracle_*.py): closed forms for the pooling/projection,
+brute-force nearest neighbour, threshold invariants, tau > 1 == plain forward,
+resubmission hits at similarity 1, torch.nn.functional cross-check of f_l in
+float64, scripted LRU trace against a list-based simulation.  The paper prints
+no worked numerical example, so absolute values rest on those pins alone.
+"""
+from __future__ import annotations
+
+import math
+from dataclasses import dataclass
+from typing import Dict, List, Optional, Sequence, Tuple
+
+import numpy as np
+from scipy.special import erf as _erf
+
+ENCODER_POST_LN = 0
+DECODER_PRE_LN = 1
+GELU_ERF = 0
+GELU_TANH = 1
+
+FLAG_INSERT_ON_MISS = 1
+FLAG_UPDATE_LRU = 2
+
+NORM_FLOOR = 1e-12
+
+
+# ----------------------------------------------------------------------------
+# rounding to the bank's storage type
+# ----------------------------------------------------------------------------
+
+def round_to_bf16(x: np.ndarray) -> np.ndarray:
+    """Round to the nearest bfloat16 (ties to even); result held in float32.
+
+    The value is first rounded to float32, the precision the device computes
+    the normalised vector in, then to bfloat16: the quantised code is decided
+    in the kernel's precision.
+    """
+    f = np.ascontiguousarray(x, dtype=np.float32)
+    u = f.view(np.uint32).astype(np.uint64)
+    lsb = (u >> np.uint64(16)) & np.uint64(1)
+    r = (u + np.uint64(0x7FFF) + lsb) & np.uint64(0xFFFF0000)
+    out = r.astype(np.uint32).view(np.float32).copy()
+    nan = np.isnan(f)
+    out[nan] = np.float32(np.nan)
+    return out.reshape(f.shape)
+
+
+def round_to_storage(x: np.ndarray, dtype: str) -> np.ndarray:
+    if dtype == "bf16":
+        return round_to_bf16(x)
+    if dtype == "f32":
+        return np.asarray(x, dtype=np.float32)
+    raise ValueError(dtype)
+
+
+# ----------------------------------------------------------------------------
+# step 1: fingerprint (Section IV-B)
+# ----------------------------------------------------------------------------
+
+def fingerprint(h: np.ndarray, P: np.ndarray, c: Optional[np.ndarray], dtype: str
+                ) -> Tuple[np.ndarray, np.ndarray]:
+    """Fingerprint of each sequence in ``h [B, S, d]``.
+
+    p = mean over tokens (embedding aggregation), v = P^T p + c (linear
+    dimensionality reduction), u = v / max(|v|, 1e-12), q = u rounded to the
+    bank's storage type, qinv = 1 / |q| of the *rounded* key (0 if q == 0).
+    Returns (q [B, k] float32 holding storage-type values, qinv [B] float32).
+    """
+    h = np.asarray(h, dtype=np.float64)
+    P = np.asarray(P, dtype=np.float64)
+    B, S, d = h.shape
+    p = h.sum(axis=1) / float(S)
+    v = p @ P
+    if c is not None:
+        v = v + np.asarray(c, dtype=np.float64)[None, :]
+    nrm = np.sqrt((v * v).sum(axis=1))
+    u = v / np.maximum(nrm, NORM_FLOOR)[:, None]
+    q = round_to_storage(u, dtype)
+    return q, inv_norm(q)
+
+
+def inv_norm(q: np.ndarray) -> np.ndarray:
+    """1 / |q| of stored keys (float64 arithmetic, stored as float32); 0 for a zero key."""
+    q64 = np.asarray(q, dtype=np.float64)
+    n = np.sqrt((q64 * q64).sum(axis=-1))
+    out = np.zeros_like(n)
+    nz = n > 0
+    out[nz] = 1.0 / n[nz]
+    return out.astype(np.float32)
+
+
+# ----------------------------------------------------------------------------
+# step 2: match (Section III-C) and step 3: threshold (Section IV-A)
+# ----------------------------------------------------------------------------
+
+def similarities(q: np.ndarray, qinv: np.ndarray, bank_fp: np.ndarray, bank_inv_norm: np.ndarray
+                 ) -> np.ndarray:
+    """Cosine similarity of every query with every bank key, float64 [B, N].
+
+    The cosine is that of the stored vectors: their dot product times both
+    stored inverse norms.
+    """
+    q64 = np.asarray(q, dtype=np.float64)
+    b64 = np.asarray(bank_fp, dtype=np.float64)
+    dots = q64 @ b64.T
+    return dots * np.asarray(qinv, dtype=np.float64)[:, None] * np.asarray(bank_inv_norm, dtype=np.float64)[None, :]
+
+
+def match(q: np.ndarray, qinv: np.ndarray, bank_fp: np.ndarray, bank_inv_norm: np.ndarray,
+          valid: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
+    """Best valid bank entry per query: (idx [B] int32, sim [B] float64).
+
+    Lowest slot wins exact ties.  With no valid entry idx = -1 and sim = -inf.
+    """
+    B = np.asarray(q).shape[0]
+    valid = np.asarray(valid).astype(bool)
+    if bank_fp is None or valid.size == 0 or not valid.any():
+        return np.full((B,), -1, dtype=np.int32), np.full((B,), -np.inf)
+    s = similarities(q, qinv, bank_fp, bank_inv_norm)
+    s[:, ~valid] = -np.inf
+    idx = np.argmax(s, axis=1)           # first occurrence of the maximum
+    sim = s[np.arange(B), idx]
+    return idx.astype(np.int32), sim
+
+
+def near_tie_sets(q, qinv, bank_fp, bank_inv_norm, valid, gap: float = 2e-6) -> List[np.ndarray]:
+    """Per query, the valid slots whose similarity lies within ``gap`` of the best."""
+    valid = np.asarray(valid).astype(bool)
+    s = similarities(q, qinv, bank_fp, bank_inv_norm)
+    s[:, ~valid] = -np.inf
+    best = s.max(axis=1)
+    return [np.nonzero(s[b] >= best[b] - gap)[0] for b in range(s.shape[0])]
+
+
+def threshold(sim: np.ndarray, tau: float) -> np.ndarray:
+    """Hit iff the best similarity strictly exceeds tau."""
+    return (np.asarray(sim) > float(tau))
+
+
+# ----------------------------------------------------------------------------
+# f_l: transformer blocks (textbook definitions)
+# ----------------------------------------------------------------------------
+
+def gelu(x: np.ndarray, kind: int) -> np.ndarray:
+    if kind == GELU_ERF:
+        return 0.5 * x * (1.0 + _erf(x / math.sqrt(2.0)))
+    if kind == GELU_TANH:
+        return 0.5 * x * (1.0 + np.tanh(math.sqrt(2.0 / math.pi) * (x + 0.044715 * x ** 3)))
+    raise ValueError(kind)
+
+
+def layer_norm(x: np.ndarray, g: np.ndarray, b: np.ndarray, eps: float) -> np.ndarray:
+    mu = x.mean(axis=-1, keepdims=True)
+    var = ((x - mu) ** 2).mean(axis=-1, keepdims=True)
+    return (x - mu) / np.sqrt(var + eps) * g + b
+
+
+def attention(x: np.ndarray, wqkv: np.ndarray, bqkv: np.ndarray, wo: np.ndarray, bo: np.ndarray,
+              n_heads: int, causal: bool) -> np.ndarray:
+    """Multi-head self-attention of one sequence ``x [S, d]`` -> [S, d].
+
+    Linear weights are [out, in].  Rows 0..d-1 of wqkv give Q, d..2d-1 K,
+    2d..3d-1 V; head h owns features h*dh..(h+1)*dh-1.  Scores are scaled by
+    1/sqrt(dh); a causal mask lets token t see tokens <= t only.
+    """
+    S, d = x.shape
+    dh = d // n_heads
+    qkv = x @ wqkv.T + bqkv
+    Q, K, V = qkv[:, :d], qkv[:, d:2 * d], qkv[:, 2 * d:]
+    ctx = np.empty((S, d), dtype=np.float64)
+    for hd in range(n_heads):
+        sl = slice(hd * dh, (hd + 1) * dh)
+        sc = (Q[:, sl] @ K[:, sl].T) / math.sqrt(dh)
+        if causal:
+            sc = np.where(np.tril(np.ones((S, S), dtype=bool)), sc, -np.inf)
+        sc = sc - sc.max(axis=1, keepdims=True)
+        e = np.exp(sc)
+        p = e / e.sum(axis=1, keepdims=True)
+        ctx[:, sl] = p @ V[:, sl]
+    return ctx @ wo.T + bo
+
+
+def _w64(w: Dict[str, np.ndarray]) -> Dict[str, np.ndarray]:
+    return {k: np.asarray(v, dtype=np.float64) for k, v in w.items()}
+
+
+def encoder_layer_post_ln(x: np.ndarray, w: Dict[str, np.ndarray], n_heads: int, eps: float,
+                          gelu_kind: int = GELU_ERF) -> np.ndarray:
+    """Post-LayerNorm encoder block on one sequence [S, d]:
+    x1 = LN1(x + MHA(x)); y = LN2(x1 + W2 gelu(W1 x1 + b1) + b2)."""
+    w = _w64(w)
+    x = np.asarray(x, dtype=np.float64)
+    a = attention(x, w["wqkv"], w["bqkv"], w["wo"], w["bo"], n_heads, causal=False)
+    x1 = layer_norm(x + a, w["ln1_g"], w["ln1_b"], eps)
+    ff = gelu(x1 @ w["w1"].T + w["b1"], gelu_kind) @ w["w2"].T + w["b2"]
+    return layer_norm(x1 + ff, w["ln2_g"], w["ln2_b"], eps)
+
+
+def decoder_layer_pre_ln(x: np.ndarray, w: Dict[str, np.ndarray], n_heads: int, eps: float,
+                         gelu_kind: int = GELU_TANH) -> np.ndarray:
+    """Pre-LayerNorm causal decoder block on one sequence [S, d]:
+    x1 = x + MHA_causal(LN1(x)); y = x1 + W2 gelu(W1 LN2(x1) + b1) + b2."""
+    w = _w64(w)
+    x = np.asarray(x, dtype=np.float64)
+    a = attention(layer_norm(x, w["ln1_g"], w["ln1_b"], eps), w["wqkv"], w["bqkv"], w["wo"], w["bo"],
+                  n_heads, causal=True)
+    x1 = x + a
+    ff = gelu(layer_norm(x1, w["ln2_g"], w["ln2_b"], eps) @ w["w1"].T + w["b1"], gelu_kind) @ w["w2"].T + w["b2"]
+    return x1 + ff
+
+
+def layer_forward(x: np.ndarray, w: Dict[str, np.ndarray], arch: int, n_heads: int, eps: float,
+                  gelu_kind: int) -> np.ndarray:
+    """f_l applied to one sequence [S, d] (float64 result)."""
+    if arch == ENCODER_POST_LN:
+        return encoder_layer_post_ln(x, w, n_heads, eps, gelu_kind)
+    if arch == DECODER_PRE_LN:
+        return decoder_layer_pre_ln(x, w, n_heads, eps, gelu_kind)
+    raise ValueError(arch)
+
+
+# ----------------------------------------------------------------------------
+# the bank C_l (Section III-B) with insertion and LRU (Sections III-E, IV-D)
+# ----------------------------------------------------------------------------
+
+class Bank:
+    """One layer's cache bank: keys ``fp [N, k]``, values ``act [A, S, d]``.
+
+    ``act_slot[j]`` names the value row of key j (identity when A == N).
+    ``last_used[j]`` is the tick of the entry's insertion or latest hit,
+    ``hits[j]`` its number of hits since insertion.
+    """
+
+    def __init__(self, n_slots: int, k: int, S: int, d: int, dtype: str,
+                 n_act_slots: Optional[int] = None, lru: bool = True):
+        A = n_slots if n_act_slots is None else n_act_slots
+        self.N, self.k, self.S, self.d, self.A = n_slots, k, S, d, A
+        self.dtype = dtype
+        self.lru = lru
+        self.fp = np.zeros((n_slots, k), dtype=np.float32)
+        self.inv_norm = np.zeros((n_slots,), dtype=np.float32)
+        self.act = np.zeros((A, S, d), dtype=np.float32)
+        self.act_slot = np.arange(n_slots, dtype=np.int32) if A == n_slots else np.zeros((n_slots,), np.int32)
+        self.last_used = np.zeros((n_slots,), dtype=np.uint64)
+        self.hits = np.zeros((n_slots,), dtype=np.uint32)
+        self.valid = np.zeros((n_slots,), dtype=np.uint8)
+
+    # -- selection -----------------------------------------------------------
+    def select_slots(self, m: int) -> List[int]:
+        """Slots that the next ``m`` insertions take, in order: free slots by
+        ascending index, then -- bank full -- valid entries by ascending
+        (last_used, slot).  Raises if the bank is full and eviction is off."""
+        free = [j for j in range(self.N) if not self.valid[j]]
+        out = free[:m]
+        if len(out) < m:
+            if not self.lru:
+                raise RuntimeError("bank full and eviction disabled")
+            order = sorted((j for j in range(self.N) if self.valid[j]),
+                           key=lambda j: (int(self.last_used[j]), j))
+            out += order[:m - len(out)]
+        return out
+
+    def lru_victims(self, m: int) -> List[int]:
+        """The ``m`` least recently used valid entries, ascending (last_used, slot)."""
+        order = sorted((j for j in range(self.N) if self.valid[j]),
+                       key=lambda j: (int(self.last_used[j]), j))
+        return order[:m]
+
+    # -- updates -------------------------------------------------------------
+    def insert(self, q: np.ndarray, qinv: np.ndarray, acts: np.ndarray, tick: int) -> Tuple[List[int], int]:
+        """Store ``m`` (key, value) pairs; returns (slots taken, number evicted)."""
+        m = q.shape[0]
+        slots = self.select_slots(m)
+        n_evicted = 0
+        for i, j in enumerate(slots):
+            n_evicted += int(self.valid[j])
+            self.fp[j] = q[i]
+            self.inv_norm[j] = qinv[i]
+            self.act[self.act_slot[j]] = acts[i]
+            self.last_used[j] = tick
+            self.hits[j] = 0
+            self.valid[j] = 1
+        return slots, n_evicted
+
+    def evict(self, m: int) -> List[int]:
+        """Invalidate the ``m`` least recently used entries; returns them in eviction order."""
+        v = self.lru_victims(m)
+        for j in v:
+            self.valid[j] = 0
+        return v
+
+    def touch(self, slots: Sequence[int], tick: int) -> None:
+        """Record hits: refresh recency and count the hit."""
+        for j in slots:
+            self.last_used[j] = tick
+            self.hits[j] += 1
+
+
+# ----------------------------------------------------------------------------
+# the gated layer (Section IV-A case equation, Algorithm 1 loop body)
+# ----------------------------------------------------------------------------
+
+@dataclass
+class GateResult:
+    h_out: np.ndarray          # [B, S, d] float64; hit rows hold the cached values exactly
+    q: np.ndarray              # [B, k] stored-type fingerprint
+    qinv: np.ndarray           # [B]
+    idx: np.ndarray            # [B] int32 best slot (-1: empty bank)
+    sim: np.ndarray            # [B] float64 best similarity
+    hit: np.ndarray            # [B] bool
+    slots: List[int]           # slots taken by this batch's insertions (ascending miss row order)
+    n_evicted: int
+
+
+def gated_layer(h_in: np.ndarray, bank: Optional[Bank], P: Optional[np.ndarray], c: Optional[np.ndarray],
+                w: Dict[str, np.ndarray], arch: int, n_heads: int, eps: float, gelu_kind: int,
+                tau: float, flags: int = 0, tick: int = 0, out_dtype: Optional[str] = None,
+                fp_override: Optional[Tuple[np.ndarray, np.ndarray]] = None) -> GateResult:
+    """One trip of Algorithm 1's loop body for a whole batch.
+
+    The batch is matched against the bank as it stands on entry; insertions
+    become visible to the next call.  ``bank is None`` means the layer is not
+    cached and is computed plainly (Section VI-D, layer selection).
+    ``out_dtype`` rounds the *stored* value on insertion (the bank holds
+    storage-type values); h_out itself is returned unrounded for miss rows.
+    ``fp_override`` supplies (q, qinv) instead of fingerprinting h_in
+    (Algorithm 1 taken literally: one fingerprint of the input for all layers).
+    """
+    h_in = np.asarray(h_in, dtype=np.float64)
+    B, S, d = h_in.shape
+    h_out = np.empty((B, S, d), dtype=np.float64)
+    if bank is None:
+        for b in range(B):
+            h_out[b] = layer_forward(h_in[b], w, arch, n_heads, eps, gelu_kind)
+        return GateResult(h_out, np.zeros((B, 0), np.float32), np.zeros((B,), np.float32),
+                          np.full((B,), -1, np.int32), np.full((B,), -np.inf), np.zeros((B,), bool), [], 0)
+    if fp_override is not None:
+        q, qinv = fp_override
+    else:
+        q, qinv = fingerprint(h_in, P, c, bank.dtype)
+    idx, sim = match(q, qinv, bank.fp, bank.inv_norm, bank.valid)
+    hit = threshold(sim, tau)
+    for b in range(B):
+        if hit[b]:
+            h_out[b] = bank.act[bank.act_slot[idx[b]]]
+        else:
+            h_out[b] = layer_forward(h_in[b], w, arch, n_heads, eps, gelu_kind)
+    if flags & FLAG_UPDATE_LRU:
+        bank.touch([int(idx[b]) for b in range(B) if hit[b]], tick)
+    slots: List[int] = []
+    n_evicted = 0
+    if flags & FLAG_INSERT_ON_MISS:
+        miss = [b for b in range(B) if not hit[b]]
+        if miss:
+            vals = h_out[miss]
+            if out_dtype is not None:
+                vals = round_to_storage(vals, out_dtype)
+            slots, n_evicted = bank.insert(q[miss], qinv[miss], vals, tick)
+    return GateResult(h_out, q, qinv, idx, sim, hit, slots, n_evicted)
+
+
+def infer(h0: np.ndarray, banks: Sequence[Optional[Bank]], Ps: Sequence[np.ndarray],
+          cs: Sequence[Optional[np.ndarray]], weights: Sequence[Dict[str, np.ndarray]], arch: int,
+          n_heads: int, eps: float, gelu_kind: int, tau: float, flags: int = 0, tick: int = 0,
+          out_dtype: Optional[str] = None, single_fingerprint: bool = False
+          ) -> Tuple[np.ndarray, List[GateResult]]:
+    """Algorithm 1 for a batch: h_0 through all L gated layers.
+
+    Default: layer l fingerprints its own input h_{l-1} with P_l.  With
+    ``single_fingerprint`` the fingerprint of h_0 (under P_1) is computed once
+    and reused at every layer, as the algorithm is printed.  If ``out_dtype``
+    is given, every layer's output is rounded to it before feeding the next
+    layer (the run stores activations in that type).
+    """
+    h = np.asarray(h0, dtype=np.float64)
+    results = []
+    fp0 = None
+    if single_fingerprint:
+        dt = next(b.dtype for b in banks if b is not None)
+        fp0 = fingerprint(h, Ps[0], cs[0], dt)
+    for l, w in enumerate(weights):
+        r = gated_layer(h, banks[l], Ps[l], cs[l], w, arch, n_heads, eps, gelu_kind, tau, flags, tick,
+                        out_dtype, fp_override=fp0)
+        results.append(r)
+        h = r.h_out
+        if out_dtype is not None:
+            h = round_to_storage(h, out_dtype).astype(np.float64)
+    return h, results

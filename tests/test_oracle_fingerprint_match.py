@@ -1,0 +1,195 @@
+"""Pins for the oracle's fingerprint, match and threshold steps (CPU only).
+
+The paper prints no worked example, so these pin the oracle to what the
+definitions fix: closed forms, brute force on tiny inputs, invariants.
+"""
+import math
+
+import numpy as np
+import pytest
+
+from oracle import llmc_oracle as O
+
+
+def rng(seed):
+    return np.random.Generator(np.random.PCG64(seed))
+
+
+# ---- bf16 rounding ----------------------------------------------------------
+
+def test_round_to_bf16_matches_torch_and_ties_to_even():
+    import torch
+    x = rng(0).standard_normal(20000).astype(np.float32) * np.float32(3.0)
+    want = torch.from_numpy(x).to(torch.bfloat16).to(torch.float32).numpy()
+    assert np.array_equal(O.round_to_bf16(x), want)
+    # exact halfway cases: 1 + 2^-8 lies between 1 and 1 + 2^-7 -> even mantissa (1.0)
+    assert O.round_to_bf16(np.array([1.0 + 2.0 ** -8]))[0] == np.float32(1.0)
+    # 1 + 3*2^-8 lies between 1+2^-7 (odd) and 1+2^-6 (even) -> 1 + 2^-6
+    assert O.round_to_bf16(np.array([1.0 + 3 * 2.0 ** -8]))[0] == np.float32(1.0 + 2.0 ** -6)
+    assert O.round_to_bf16(np.array([0.0, -0.0, 1.0, -2.5]))[3] == np.float32(-2.5)
+
+
+# ---- pooling + projection: closed forms (Section IV-B) -----------------------
+
+def test_fingerprint_single_token_is_that_token():
+    r = rng(1)
+    h = r.standard_normal((3, 1, 16))
+    q, qinv = O.fingerprint(h, np.eye(16), None, "f32")
+    want = h[:, 0, :] / np.linalg.norm(h[:, 0, :], axis=1, keepdims=True)
+    np.testing.assert_allclose(q, want, rtol=0, atol=1e-7)
+    np.testing.assert_allclose(qinv, 1.0, atol=1e-6)
+
+
+def test_fingerprint_identity_projection_is_normalised_mean():
+    r = rng(2)
+    h = r.standard_normal((4, 7, 12))
+    q, _ = O.fingerprint(h, np.eye(12), None, "f32")
+    for b in range(4):
+        m = np.zeros(12)
+        for t in range(7):          # explicit token loop: a dropped or doubled token shows here
+            m += h[b, t]
+        m /= 7.0
+        np.testing.assert_allclose(q[b], m / math.sqrt(float(m @ m)), atol=1e-7)
+
+
+def test_fingerprint_constant_rows_and_scale_invariance():
+    r = rng(3)
+    P = r.standard_normal((10, 6))
+    row = r.standard_normal(10)
+    h = np.broadcast_to(row, (2, 5, 10)).copy()
+    q, _ = O.fingerprint(h, P, None, "f32")
+    v = row @ P
+    np.testing.assert_allclose(q[0], v / np.linalg.norm(v), atol=1e-7)
+    h2 = r.standard_normal((3, 9, 10))
+    q1, _ = O.fingerprint(h2, P, None, "f32")
+    q2, _ = O.fingerprint(4.0 * h2, P, None, "f32")     # power of two: exact in fp
+    np.testing.assert_allclose(q1, q2, atol=1e-7)
+
+
+def test_fingerprint_projection_orientation_and_bias():
+    # P is [d, k]: v_j = sum_i p_i P[i, j].  A transposed operand fails (d != k).
+    r = rng(4)
+    d, k = 5, 3
+    h = r.standard_normal((2, 4, d))
+    P = r.standard_normal((d, k))
+    c = r.standard_normal(k)
+    q, _ = O.fingerprint(h, P, c, "f32")
+    for b in range(2):
+        p = h[b].mean(axis=0)
+        v = np.array([sum(p[i] * P[i, j] for i in range(d)) + c[j] for j in range(k)])
+        np.testing.assert_allclose(q[b], v / np.linalg.norm(v), atol=1e-7)
+    # centring bias c = -P^T mu removes the common component mu exactly
+    mu = r.standard_normal(d)
+    q_c, _ = O.fingerprint(h, P, -(mu @ P), "f32")
+    q_s, _ = O.fingerprint(h - mu, P, None, "f32")
+    np.testing.assert_allclose(q_c, q_s, atol=1e-6)
+
+
+def test_fingerprint_zero_vector_and_bf16_inverse_norm_of_rounded_key():
+    h = np.zeros((1, 3, 8))
+    q, qinv = O.fingerprint(h, np.eye(8), None, "bf16")
+    assert np.all(q == 0) and qinv[0] == 0
+    r = rng(5)
+    h = r.standard_normal((6, 5, 32))
+    P = r.standard_normal((32, 16))
+    q, qinv = O.fingerprint(h, P, None, "bf16")
+    # keys are bf16-representable, and qinv is the norm of the rounded key, not of the exact one
+    assert np.array_equal(q, O.round_to_bf16(q))
+    for b in range(6):
+        n = math.sqrt(sum(float(x) ** 2 for x in q[b]))
+        assert abs(float(qinv[b]) - 1.0 / n) < 1e-7
+        assert abs(n - 1.0) < 2.0 ** -8
+
+
+# ---- match: brute force, permutation, self-hit (Section III-C) ---------------
+
+def brute_force_match(q, qinv, bank, binv, valid):
+    B, k = q.shape
+    idx = np.full(B, -1, dtype=np.int32)
+    sim = np.full(B, -np.inf)
+    for b in range(B):
+        for j in range(bank.shape[0]):
+            if not valid[j]:
+                continue
+            dot = 0.0
+            for t in range(k):
+                dot += float(q[b, t]) * float(bank[j, t])
+            s = dot * float(qinv[b]) * float(binv[j])
+            if s > sim[b]:
+                sim[b], idx[b] = s, j
+    return idx, sim
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_match_equals_brute_force(seed):
+    r = rng(10 + seed)
+    N, B, k = 48, 9, 8
+    bank = O.round_to_bf16(r.standard_normal((N, k)))
+    q = O.round_to_bf16(r.standard_normal((B, k)))
+    valid = (r.random(N) > 0.2).astype(np.uint8)
+    binv, qinv = O.inv_norm(bank), O.inv_norm(q)
+    idx, sim = O.match(q, qinv, bank, binv, valid)
+    bidx, bsim = brute_force_match(q, qinv, bank, binv, valid)
+    assert np.array_equal(idx, bidx)
+    np.testing.assert_allclose(sim, bsim, rtol=0, atol=1e-12)
+    assert np.all(valid[idx] == 1)
+
+
+def test_match_uses_bank_norms_before_argmax():
+    # entry 0 has the larger dot product, entry 1 the larger cosine
+    bank = np.array([[3.0, 3.0], [1.0, 0.0]], dtype=np.float32)
+    q = np.array([[1.0, 0.0]], dtype=np.float32)
+    idx, sim = O.match(q, O.inv_norm(q), bank, O.inv_norm(bank), np.ones(2, np.uint8))
+    assert idx[0] == 1 and abs(sim[0] - 1.0) < 1e-7
+
+
+def test_match_permutation_ties_self_and_empty():
+    r = rng(20)
+    N, B, k = 40, 6, 16
+    bank = O.round_to_bf16(r.standard_normal((N, k)))
+    q = O.round_to_bf16(r.standard_normal((B, k)))
+    valid = np.ones(N, np.uint8)
+    binv, qinv = O.inv_norm(bank), O.inv_norm(q)
+    idx, sim = O.match(q, qinv, bank, binv, valid)
+    perm = r.permutation(N)
+    idx_p, sim_p = O.match(q, qinv, bank[perm], binv[perm], valid)
+    assert np.array_equal(perm[idx_p], idx)
+    np.testing.assert_allclose(sim_p, sim, atol=1e-15)
+    # scale invariance of the cosine: scaling a key (and its stored inverse norm) changes nothing
+    bank2 = bank.copy()
+    bank2[3] *= 2.0
+    idx2, sim2 = O.match(q, qinv, bank2, O.inv_norm(bank2), valid)
+    assert np.array_equal(idx2, idx)
+    np.testing.assert_allclose(sim2, sim, atol=1e-7)
+    # duplicates: lowest slot wins
+    bank3 = bank.copy()
+    bank3[17] = bank3[5]
+    bank3[30] = bank3[5]
+    qq = bank3[[30]]
+    i3, s3 = O.match(qq, O.inv_norm(qq), bank3, O.inv_norm(bank3), valid)
+    assert i3[0] == 5 and abs(s3[0] - 1.0) < 1e-6
+    # the query itself in the bank: similarity 1
+    i4, s4 = O.match(bank[[11]], binv[[11]], bank, binv, valid)
+    assert i4[0] == 11 and abs(s4[0] - 1.0) < 1e-6
+    # invalid slots are never returned; empty bank -> -1, -inf
+    v = valid.copy()
+    v[11] = 0
+    i5, _ = O.match(bank[[11]], binv[[11]], bank, binv, v)
+    assert i5[0] != 11
+    i6, s6 = O.match(q, qinv, bank, binv, np.zeros(N, np.uint8))
+    assert np.all(i6 == -1) and np.all(np.isneginf(s6))
+
+
+# ---- threshold (Section IV-A) -------------------------------------------------
+
+def test_threshold_strict_and_monotone():
+    sim = np.array([0.5, 0.95, 0.9500001, 1.0, -np.inf])
+    assert O.threshold(sim, 0.95).tolist() == [False, False, True, True, False]
+    assert not O.threshold(sim, 1.0 + 1e-3).any()
+    assert O.threshold(sim[:4], -2.0).all()
+    prev = None
+    for tau in [0.0, 0.5, 0.9, 0.95, 0.99, 1.0]:
+        h = set(np.nonzero(O.threshold(sim, tau))[0].tolist())
+        if prev is not None:
+            assert h <= prev
+        prev = h

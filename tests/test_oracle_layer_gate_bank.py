@@ -1,0 +1,284 @@
+"""Pins for the oracle's transformer blocks, gated layer and bank (CPU only)."""
+import math
+from collections import OrderedDict
+
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+from oracle import llmc_oracle as O
+from paper_2512_16843_amd import workloads as W
+
+
+def rng(seed):
+    return np.random.Generator(np.random.PCG64(seed))
+
+
+def np_weights(w):
+    return {k: v.float().numpy() for k, v in w.items()}
+
+
+# ---- f_l against library routines in float64 ---------------------------------
+
+def torch_block(x, w, arch, n_heads, eps, gelu_kind):
+    """The same block assembled from torch.nn.functional primitives (float64)."""
+    t = {k: torch.from_numpy(np.asarray(v, dtype=np.float64)) for k, v in w.items()}
+    x = torch.from_numpy(np.asarray(x, dtype=np.float64))
+    S, d = x.shape
+    approx = "none" if gelu_kind == O.GELU_ERF else "tanh"
+
+    def mha(inp, causal):
+        mask = None
+        if causal:
+            mask = torch.triu(torch.full((S, S), float("-inf"), dtype=torch.float64), diagonal=1)
+        out, _ = F.multi_head_attention_forward(
+            inp.unsqueeze(1), inp.unsqueeze(1), inp.unsqueeze(1), d, n_heads,
+            t["wqkv"], t["bqkv"], None, None, False, 0.0, t["wo"], t["bo"],
+            training=False, need_weights=False, attn_mask=mask)
+        return out.squeeze(1)
+
+    if arch == O.ENCODER_POST_LN:
+        x1 = F.layer_norm(x + mha(x, False), (d,), t["ln1_g"], t["ln1_b"], eps)
+        ff = F.linear(F.gelu(F.linear(x1, t["w1"], t["b1"]), approximate=approx), t["w2"], t["b2"])
+        return F.layer_norm(x1 + ff, (d,), t["ln2_g"], t["ln2_b"], eps).numpy()
+    x1 = x + mha(F.layer_norm(x, (d,), t["ln1_g"], t["ln1_b"], eps), True)
+    ff = F.linear(F.gelu(F.linear(F.layer_norm(x1, (d,), t["ln2_g"], t["ln2_b"], eps), t["w1"], t["b1"]),
+                         approximate=approx), t["w2"], t["b2"])
+    return (x1 + ff).numpy()
+
+
+@pytest.mark.parametrize("arch,gelu_kind,eps", [(O.ENCODER_POST_LN, O.GELU_ERF, 1e-12),
+                                                (O.DECODER_PRE_LN, O.GELU_TANH, 1e-5),
+                                                (O.ENCODER_POST_LN, O.GELU_TANH, 1e-5)])
+def test_layer_matches_torch_functional(arch, gelu_kind, eps):
+    cfg = W.scaled(W.TINY_ENCODER, d=48, n_heads=3, d_ff=80, S=11, n_layers=1)
+    w = np_weights(W.make_layer_weights(cfg, seed=3)[0])
+    # larger weights so that softmax and GELU are exercised away from their linear regime
+    for k in ("wqkv", "wo", "w1", "w2"):
+        w[k] = w[k] * 12.0
+    x = rng(1).standard_normal((cfg.S, cfg.d))
+    got = O.layer_forward(x, w, arch, cfg.n_heads, eps, gelu_kind)
+    want = torch_block(x, w, arch, cfg.n_heads, eps, gelu_kind)
+    np.testing.assert_allclose(got, want, rtol=1e-10, atol=1e-10)
+
+
+def test_gelu_layernorm_softmax_basics():
+    xs = np.array([-3.0, -1.0, 0.0, 0.5, 2.0])
+    for x, g in zip(xs, O.gelu(xs, O.GELU_ERF)):
+        assert abs(g - 0.5 * x * (1.0 + math.erf(x / math.sqrt(2.0)))) < 1e-15
+    assert O.gelu(np.array([0.0]), O.GELU_TANH)[0] == 0.0
+    assert abs(O.gelu(np.array([10.0]), O.GELU_TANH)[0] - 10.0) < 1e-12
+    # the tanh form differs from the erf form (by < 1e-3) -- they must not be confused
+    dlt = np.abs(O.gelu(xs, O.GELU_TANH) - O.gelu(xs, O.GELU_ERF))
+    assert 1e-5 < dlt.max() < 1e-3
+    x = rng(0).standard_normal((5, 64)) * 3 + 1
+    y = O.layer_norm(x, np.ones(64), np.zeros(64), 1e-12)
+    np.testing.assert_allclose(y.mean(axis=1), 0, atol=1e-12)
+    np.testing.assert_allclose(y.var(axis=1), 1, atol=1e-9)
+
+
+def test_decoder_is_causal_and_encoder_is_not():
+    cfg = W.scaled(W.TINY_ENCODER, d=32, n_heads=2, d_ff=64, S=10, n_layers=1)
+    w = np_weights(W.make_layer_weights(cfg, seed=5)[0])
+    for k in ("wqkv", "wo"):
+        w[k] = w[k] * 10.0
+    x = rng(2).standard_normal((cfg.S, cfg.d))
+    x2 = x.copy()
+    x2[6:] = rng(3).standard_normal((4, cfg.d))
+    yd = O.decoder_layer_pre_ln(x, w, 2, 1e-5)
+    yd2 = O.decoder_layer_pre_ln(x2, w, 2, 1e-5)
+    np.testing.assert_allclose(yd[:6], yd2[:6], atol=1e-13)
+    assert np.abs(yd[6:] - yd2[6:]).max() > 1e-3
+    ye = O.encoder_layer_post_ln(x, w, 2, 1e-12)
+    ye2 = O.encoder_layer_post_ln(x2, w, 2, 1e-12)
+    assert np.abs(ye[:6] - ye2[:6]).max() > 1e-6
+
+
+# ---- bank: LRU against a list-based simulation (Section IV-D) ----------------
+
+class ListLRU:
+    """Textbook LRU over a fixed number of slots: free slots first (lowest index),
+    then the least recently used entry; ties in recency broken by slot."""
+
+    def __init__(self, n):
+        self.n = n
+        self.entries = {}        # slot -> (last_used, payload)
+
+    def take(self):
+        for j in range(self.n):
+            if j not in self.entries:
+                return j
+        return min(self.entries, key=lambda j: (self.entries[j][0], j))
+
+
+def test_lru_scripted_trace():
+    bank = O.Bank(4, 2, 1, 1, "f32")
+    sim = ListLRU(4)
+    r = rng(7)
+    payload = 0
+    for tick in range(1, 40):
+        # a few hits on random valid entries, then 1-3 insertions, all at this tick
+        live = [j for j in range(4) if bank.valid[j]]
+        hit_slots = [int(r.choice(live)) for _ in range(int(r.integers(0, 3)))] if live else []
+        bank.touch(hit_slots, tick)
+        for j in hit_slots:
+            sim.entries[j] = (tick, sim.entries[j][1])
+        m = int(r.integers(1, 4))
+        # batch semantics: the m slots are chosen on the pre-insert state
+        want = []
+        snapshot = dict(sim.entries)
+        for i in range(m):
+            j = sim.take()
+            want.append(j)
+            sim.entries[j] = (math.inf, None)      # reserved: not chosen twice in a batch
+        sim.entries = snapshot
+        q = np.full((m, 2), 1.0, dtype=np.float32)
+        acts = np.arange(payload, payload + m, dtype=np.float32).reshape(m, 1, 1)
+        got, _ = bank.insert(q, O.inv_norm(q), acts, tick)
+        assert got == want
+        assert len(set(got)) == m
+        for i, j in enumerate(want):
+            sim.entries[j] = (tick, payload + i)
+        payload += m
+        for j, (lu, p) in sim.entries.items():
+            assert int(bank.last_used[j]) == lu and bank.act[j, 0, 0] == p and bank.valid[j]
+        assert bank.valid.sum() <= 4
+
+
+def test_lru_victims_are_m_smallest_and_evict_invalidates():
+    bank = O.Bank(6, 2, 1, 1, "f32")
+    q = np.ones((6, 2), np.float32)
+    bank.insert(q, O.inv_norm(q), np.zeros((6, 1, 1), np.float32), tick=1)
+    bank.touch([0, 3], 5)
+    bank.touch([4], 3)
+    assert bank.lru_victims(3) == [1, 2, 5]
+    assert bank.lru_victims(5) == [1, 2, 5, 4, 0]
+    assert bank.evict(2) == [1, 2]
+    assert bank.valid.tolist() == [1, 0, 0, 1, 1, 1]
+    assert bank.select_slots(3) == [1, 2, 5]       # free slots first, then oldest
+    assert int(bank.hits[0]) == 1 and int(bank.hits[4]) == 1
+    full = O.Bank(2, 2, 1, 1, "f32", lru=False)
+    full.insert(q[:2], O.inv_norm(q[:2]), np.zeros((2, 1, 1), np.float32), 1)
+    with pytest.raises(RuntimeError):
+        full.insert(q[:1], O.inv_norm(q[:1]), np.zeros((1, 1, 1), np.float32), 2)
+
+
+# ---- gated layer invariants (Section IV-A, Algorithm 1) ----------------------
+
+def tiny_setup(arch=O.ENCODER_POST_LN, n_src=12, dtype="f32"):
+    cfg = W.scaled(W.TINY_ENCODER, d=32, n_heads=2, d_ff=64, S=6, n_layers=2, B=5, n_bank=16, k=8,
+                   vocab=50, arch=arch, gelu=O.GELU_ERF if arch == 0 else O.GELU_TANH,
+                   ln_eps=1e-12 if arch == 0 else 1e-5)
+    ws = [np_weights(w) for w in W.make_layer_weights(cfg, seed=0)]
+    tok, pos = W.make_embeddings(cfg, seed=0)
+    Ps = [p.float().numpy() for p in W.make_projection(cfg.d, cfg.k, torch.float32, seed=3, n_layers=2)]
+    src = W.make_sources(cfg, n_src, seed=1)
+    h_src = W.embed(torch.from_numpy(src), tok, pos, torch.float32).numpy()
+    return cfg, ws, tok, pos, Ps, src, h_src
+
+
+def build_banks(cfg, ws, Ps, h_src, dtype="f32"):
+    banks = [O.Bank(cfg.n_bank, cfg.k, cfg.S, cfg.d, dtype) for _ in range(cfg.n_layers)]
+    h, res = O.infer(h_src, banks, Ps, [None] * cfg.n_layers, ws, cfg.arch, cfg.n_heads, cfg.ln_eps,
+                     cfg.gelu, tau=2.0, flags=O.FLAG_INSERT_ON_MISS, tick=1)
+    return banks, h, res
+
+
+@pytest.mark.parametrize("arch", [O.ENCODER_POST_LN, O.DECODER_PRE_LN])
+def test_tau_above_one_is_plain_forward(arch):
+    cfg, ws, tok, pos, Ps, src, h_src = tiny_setup(arch)
+    banks, _, _ = build_banks(cfg, ws, Ps, h_src)
+    ids, _ = W.make_substitution_queries(cfg, src, n_dup=3, n_subst=1, seed=2)
+    h0 = W.embed(torch.from_numpy(ids), tok, pos, torch.float32).numpy()
+    out, res = O.infer(h0, banks, Ps, [None, None], ws, cfg.arch, cfg.n_heads, cfg.ln_eps, cfg.gelu,
+                       tau=1.0 + 1e-3)
+    assert all(not r.hit.any() for r in res)
+    plain = h0.astype(np.float64)
+    for w in ws:
+        plain = np.stack([O.layer_forward(plain[b], w, cfg.arch, cfg.n_heads, cfg.ln_eps, cfg.gelu)
+                          for b in range(cfg.B)])
+    assert np.array_equal(out, plain)
+
+
+def test_resubmitted_sources_hit_at_similarity_one_with_stored_values():
+    cfg, ws, tok, pos, Ps, src, h_src = tiny_setup()
+    banks, h_built, res_b = build_banks(cfg, ws, Ps, h_src)
+    # insertion took free slots in ascending order, one per source row
+    assert res_b[0].slots == list(range(len(src))) and res_b[0].n_evicted == 0
+    out, res = O.infer(h_src[:5], banks, Ps, [None, None], ws, cfg.arch, cfg.n_heads, cfg.ln_eps, cfg.gelu,
+                       tau=0.95)
+    for l, r in enumerate(res):
+        assert r.hit.all()
+        assert r.idx.tolist() == [0, 1, 2, 3, 4]
+        np.testing.assert_allclose(r.sim, 1.0, atol=1e-6)
+        assert np.array_equal(r.h_out, banks[l].act[:5].astype(np.float64))
+    assert np.array_equal(out, banks[-1].act[:5].astype(np.float64))
+
+
+def test_gate_mixes_hits_and_misses_and_updates_lru():
+    cfg, ws, tok, pos, Ps, src, h_src = tiny_setup()
+    banks, _, _ = build_banks(cfg, ws, Ps, h_src)
+    ids, srcmap = W.make_dial_queries(cfg, src, rho=0.6, seed=4)
+    h0 = W.embed(torch.from_numpy(ids), tok, pos, torch.float32).numpy()
+    bank = banks[0]
+    r = O.gated_layer(h0, bank, Ps[0], None, ws[0], cfg.arch, cfg.n_heads, cfg.ln_eps, cfg.gelu, tau=0.999,
+                      flags=O.FLAG_INSERT_ON_MISS | O.FLAG_UPDATE_LRU, tick=9)
+    for b in range(cfg.B):
+        if srcmap[b] >= 0:
+            assert r.hit[b] and r.idx[b] == srcmap[b]
+            assert np.array_equal(r.h_out[b], bank.act[srcmap[b]].astype(np.float64))
+            assert int(bank.last_used[srcmap[b]]) == 9
+        else:
+            assert not r.hit[b]
+            np.testing.assert_array_equal(
+                r.h_out[b], O.layer_forward(h0[b], ws[0], cfg.arch, cfg.n_heads, cfg.ln_eps, cfg.gelu))
+    n_miss = int((~r.hit).sum())
+    assert r.slots == list(range(len(src), len(src) + n_miss))
+    # hit set shrinks as tau grows
+    prev = None
+    for tau in (0.0, 0.5, 0.9, 0.999, 1.001):
+        rr = O.gated_layer(h0, bank, Ps[0], None, ws[0], cfg.arch, cfg.n_heads, cfg.ln_eps, cfg.gelu, tau)
+        s = set(np.nonzero(rr.hit)[0].tolist())
+        assert prev is None or s <= prev
+        prev = s
+    # an uncached layer is the plain forward
+    r0 = O.gated_layer(h0, None, None, None, ws[0], cfg.arch, cfg.n_heads, cfg.ln_eps, cfg.gelu, tau=0.0)
+    np.testing.assert_array_equal(
+        r0.h_out[0], O.layer_forward(h0[0], ws[0], cfg.arch, cfg.n_heads, cfg.ln_eps, cfg.gelu))
+
+
+def test_single_fingerprint_mode_reuses_layer_one_key():
+    cfg, ws, tok, pos, Ps, src, h_src = tiny_setup()
+    banks = [O.Bank(cfg.n_bank, cfg.k, cfg.S, cfg.d, "f32") for _ in range(2)]
+    _, res = O.infer(h_src, banks, Ps, [None, None], ws, cfg.arch, cfg.n_heads, cfg.ln_eps, cfg.gelu, tau=2.0,
+                     flags=O.FLAG_INSERT_ON_MISS, tick=1, single_fingerprint=True)
+    assert np.array_equal(banks[0].fp, banks[1].fp)
+    assert np.array_equal(res[0].q, res[1].q)
+    _, res2 = O.infer(h_src[:3], banks, Ps, [None, None], ws, cfg.arch, cfg.n_heads, cfg.ln_eps, cfg.gelu,
+                      tau=0.99, single_fingerprint=True)
+    assert all(r.hit.all() for r in res2)
+
+
+def test_workload_generators_are_deterministic_and_shaped():
+    cfg = W.scaled(W.BERT_BASE, B=10, S=40, n_layers=1)
+    a = W.make_sources(cfg, 5, seed=1)
+    b = W.make_sources(cfg, 5, seed=1)
+    assert np.array_equal(a, b) and a.shape == (5, 40) and a.max() < cfg.vocab
+    ids, s = W.make_substitution_queries(cfg, a, n_dup=6, n_subst=2, seed=2)
+    for r_ in range(10):
+        if s[r_] >= 0:
+            assert (ids[r_] != a[s[r_]]).sum() <= 2
+    assert (s >= 0).sum() == 6
+    dcfg = W.scaled(W.GPT2_SMALL, B=4, S=64, n_layers=1)
+    srcs = W.make_sources(dcfg, 3, seed=1)
+    ids, s, plen = W.make_prefix_queries(dcfg, srcs, seed=2)
+    for r_ in range(4):
+        assert np.array_equal(ids[r_, :plen[r_]], srcs[s[r_], :plen[r_]]) and 16 <= plen[r_] <= 48
+    cl = W.make_clustered_bank(8, 4, 32, 0.05, 10, seed=5)
+    assert cl["bank"].shape == (32, 32) and cl["queries"].shape == (10, 32)
+    n = cl["bank"].float().norm(dim=1)
+    assert torch.all((n - 1).abs() < 1e-2)
+    st = W.StemStream(W.scaled(W.BERT_LARGE, B=8, S=20, n_layers=1), group=4, stem_len=12, n_stems=5)
+    ids, sid = st.next_batch()
+    assert np.array_equal(ids[0, :12], ids[3, :12]) and not np.array_equal(ids[0, 12:], ids[1, 12:])
