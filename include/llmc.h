@@ -1,0 +1,289 @@
+/*
+ * llmc -- the cache-gated transformer layer of LLMCache on one AMD MI355X (gfx950).
+ *
+ * C ABI of libllmc.so.  Plain pointers and sizes only.
+ *
+ * Conventions that hold for every call
+ * ------------------------------------
+ *  - A pointer whose name starts with d_ is DEVICE memory owned by the caller
+ *    (allocated by whatever the caller uses for device memory); every other
+ *    pointer is HOST memory.  The library never frees caller memory.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    Every call that takes a stream only ENQUEUES work on it and returns
+ *    without synchronising; results, including all counts, stay on the device.
+ *    No call with a stream argument allocates or frees device memory.
+ *  - Errors are return codes.  Arguments are validated before the first HIP
+ *    call, so argument errors are reported on a host without a GPU as well.
+ *    llmc_last_error() gives a thread-local description of the last failure.
+ *  - Matrices are row-major.  Element type is given by llmc_dtype_t: LLMC_F32
+ *    (IEEE binary32) or LLMC_BF16 (bfloat16, 2 bytes).  Device pointers must be
+ *    16-byte aligned; d (model width) must be a multiple of 64 and k
+ *    (fingerprint length) a multiple of 32.
+ *  - Batch semantics: all B sequences of a call are matched against the bank as
+ *    it stands when the call's kernels run; insertions of this batch are seen
+ *    by later calls on the same stream (Algorithm 1 applied batch-wise).
+ *  - Results for one sequence do not depend on its row in the batch, on B, or
+ *    on which other rows hit or miss: every reduction has a fixed order.
+ *  - Two calls that touch the same bank, or share a workspace, must not overlap
+ *    on different streams.
+ */
+#ifndef LLMC_H
+#define LLMC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct llmc_bank llmc_bank_t; /* opaque handle of one layer's bank C_l */
+typedef void* llmc_stream_t;          /* hipStream_t */
+
+typedef enum {
+  LLMC_OK = 0,
+  LLMC_ERR_INVALID_ARG = 1, /* null pointer, non-positive size, NaN threshold, tick out of range */
+  LLMC_ERR_SHAPE = 2,       /* k / S / d / alignment do not fit the bank, the layer or the kernels */
+  LLMC_ERR_DTYPE = 3,       /* unknown element type, or operands of different element types */
+  LLMC_ERR_BANK_FULL = 4,   /* reserved: a full bank with eviction off is reported on the device, see llmc_bank_insert */
+  LLMC_ERR_WORKSPACE = 5,   /* workspace missing or smaller than the matching *_workspace_bytes() */
+  LLMC_ERR_HIP = 6          /* a HIP runtime call failed; llmc_last_error() names it */
+} llmc_status_t;
+
+typedef enum { LLMC_F32 = 0, LLMC_BF16 = 1 } llmc_dtype_t;
+
+/* Replacement policy (Section III-E / IV-D of the paper).  LRU is the first
+ * policy the paper names: remove the entries unused for the longest time. */
+typedef enum { LLMC_EVICT_NONE = 0, LLMC_EVICT_LRU = 1 } llmc_evict_t;
+
+/* Flags of llmc_layer_forward_gated. */
+#define LLMC_INSERT_ON_MISS 1u /* Algorithm 1: store (f_X, h_l) of every computed row */
+#define LLMC_UPDATE_LRU 2u     /* record hits: last_used = tick, hits += 1 */
+
+/* Largest tick accepted (recency keys are packed into 32 bits on the device). */
+#define LLMC_MAX_TICK 0x7FFFFFFEull
+/* Largest number of rows one insert/evict call may place. */
+#define LLMC_MAX_UPDATE_ROWS 4096
+
+/* Layout of the device counters written by llmc_layer_forward_gated. */
+enum {
+  LLMC_CNT_HIT = 0,      /* rows answered from the bank */
+  LLMC_CNT_MISS = 1,     /* rows computed */
+  LLMC_CNT_NEAR_TAU = 2, /* rows with |sim - tau| < 1e-3 */
+  LLMC_CNT_NEAR_TIE = 3, /* rows whose two best candidate groups were re-evaluated exactly */
+  LLMC_CNT_INSERTED = 4,
+  LLMC_CNT_EVICTED = 5,  /* insertions that replaced a valid entry */
+  LLMC_CNT_DROPPED = 6,  /* insertions skipped: bank full and policy NONE */
+  LLMC_CNT_WORDS = 8
+};
+
+/*
+ * One layer's bank C_l = {(f, h_l)} (Section III-B): N keys of length k and
+ * the cached layer outputs, each [S, d].  All arrays are caller-owned device
+ * memory that the library reads and updates in place:
+ *   d_fp        [n_slots, k]        keys, element type `dtype`, k contiguous
+ *   d_inv_norm  [n_slots]           1 / |key| of the stored (rounded) key, 0 for a zero key
+ *   d_act       [n_act_slots, S, d] cached outputs, element type `dtype`
+ *   d_act_slot  [n_slots] or NULL   value row of each key; NULL = identity (needs n_act_slots == n_slots)
+ *   d_last_used [n_slots]           tick of insertion or latest hit
+ *   d_hits      [n_slots]           hits since insertion
+ *   d_valid     [n_slots]           1 = slot holds an entry, 0 = free
+ * n_act_slots < n_slots lets several keys share one value row (a bounded value
+ * store); such a bank is read-only: insertion into it is refused.
+ */
+typedef struct {
+  int32_t n_slots, k, S, d;
+  int32_t n_act_slots;
+  int32_t dtype;  /* llmc_dtype_t */
+  int32_t policy; /* llmc_evict_t */
+  void* d_fp;
+  void* d_act;
+  float* d_inv_norm;
+  int32_t* d_act_slot;
+  uint64_t* d_last_used;
+  uint32_t* d_hits;
+  uint8_t* d_valid;
+} llmc_bank_desc_t;
+
+/*
+ * One transformer block f_l (Section IV-A; model families of Section V-A).
+ * arch 0: encoder, post-LayerNorm, bidirectional attention:
+ *     x1 = LN1(x + MHA(x));  y = LN2(x1 + W2 act(W1 x1 + b1) + b2)
+ * arch 1: decoder, pre-LayerNorm, causal attention:
+ *     x1 = x + MHA(LN1(x));  y = x1 + W2 act(W1 LN2(x1) + b1) + b2
+ * Linear weights are [out_features, in_features] (input index contiguous):
+ * d_wqkv [3d, d] with rows 0..d-1 = Q, d..2d-1 = K, 2d..3d-1 = V and head h
+ * owning features h*dh..(h+1)*dh-1 of each; d_wo [d, d]; d_w1 [d_ff, d];
+ * d_w2 [d, d_ff].  Biases and LayerNorm parameters are vectors of the same
+ * element type.  Attention scores are scaled by 1/sqrt(dh), dh = d / n_heads
+ * (the kernels support dh = 64).  gelu 0 = exact erf form, 1 = tanh form.
+ */
+typedef struct {
+  int32_t arch;
+  int32_t d, n_heads, d_ff;
+  int32_t gelu;
+  float ln_eps;
+  int32_t dtype; /* llmc_dtype_t */
+  const void *d_wqkv, *d_bqkv, *d_wo, *d_bo, *d_w1, *d_b1, *d_w2, *d_b2;
+  const void *d_ln1_g, *d_ln1_b, *d_ln2_g, *d_ln2_b;
+} llmc_layer_desc_t;
+
+/* Fingerprint map of one layer (Section IV-B): projection P [d, k] (element
+ * type of the run, k contiguous) and optional fp32 offset c [k] (NULL = 0). */
+typedef struct {
+  const void* d_proj;
+  const float* d_bias;
+  int32_t k;
+} llmc_fp_desc_t;
+
+/* Optional per-row results of the gate; any pointer may be NULL. */
+typedef struct {
+  int32_t* d_idx;      /* [B] best slot, -1 if the bank has no valid entry */
+  float* d_sim;        /* [B] best cosine similarity, -inf if none */
+  uint8_t* d_hit;      /* [B] 1 = reused, 0 = computed */
+  int32_t* d_counters; /* [LLMC_CNT_WORDS], overwritten by the call */
+  int32_t* d_slots;    /* [B] slots taken by this call's insertions, in ascending miss-row order */
+} llmc_gate_out_t;
+
+/* ---- bank -------------------------------------------------------------- */
+
+/*
+ * Wrap caller-owned arrays as a bank (Section III-B).  Synchronous: allocates
+ * a small device mirror of the validity/norm arrays ([n_slots] floats), fills
+ * it from d_valid and d_inv_norm on the default stream and waits for that.
+ * The arrays must hold a consistent state (all-zero d_valid = empty bank).
+ * Errors: INVALID_ARG (null desc/out/array), SHAPE (sizes <= 0, k % 32, d % 64,
+ * n_act_slots > n_slots, identity map with n_act_slots != n_slots), DTYPE, HIP.
+ */
+llmc_status_t llmc_bank_create(const llmc_bank_desc_t* desc, llmc_bank_t** out);
+
+/* Free what llmc_bank_create allocated (never the caller's arrays).  Synchronous. */
+llmc_status_t llmc_bank_destroy(llmc_bank_t* bank);
+
+/*
+ * If the caller wrote the bank arrays directly (e.g. loaded keys), rebuild the
+ * library's mirror from d_valid / d_inv_norm.  Enqueued on `stream`.
+ */
+llmc_status_t llmc_bank_refresh(llmc_bank_t* bank, llmc_stream_t stream);
+
+/*
+ * Algorithm 1's store step, C_l[f_X] <- h_l, for a batch (Section III-C: a
+ * computed result is added to the cache), with the replacement of Section IV-D.
+ *   d_fp [*, k], d_inv_norm [*], d_act [*, S, d]: keys, their inverse norms and the values;
+ *          the i-th stored entry is row d_rows[i] of all three (d_rows NULL: row i)
+ *   d_m: device count m of rows to store (NULL: m = m_max); m is clamped to m_max
+ *   tick: recency stamp given to the new entries (<= LLMC_MAX_TICK)
+ *   d_slots_out [m_max]: slot taken by row i, -1 if the row was dropped
+ *   d_counters: optional [LLMC_CNT_WORDS]; INSERTED / EVICTED / DROPPED are ADDED to
+ * Rows take, in order, free slots by ascending index and then, the bank being
+ * full, the valid entries in ascending (last_used, slot) order; a replaced
+ * entry's hit count restarts at 0.  With policy NONE rows beyond the free
+ * slots are dropped and counted.  m_max <= LLMC_MAX_UPDATE_ROWS.
+ * Errors: INVALID_ARG, SHAPE (m_max out of range; bank with shared value rows).
+ */
+llmc_status_t llmc_bank_insert(llmc_bank_t* bank, const void* d_fp, const float* d_inv_norm,
+                               const void* d_act, const int32_t* d_rows, const int32_t* d_m,
+                               int32_t m_max, uint64_t tick, int32_t* d_slots_out,
+                               int32_t* d_counters, llmc_stream_t stream);
+
+/*
+ * Section IV-D, LRU: invalidate the m least recently used valid entries.
+ *   d_m: device count (NULL: m = m_max), clamped to m_max and to the number of valid entries
+ *   d_victims_out [m_max]: evicted slots in ascending (last_used, slot) order, -1 beyond the count
+ * The keys and values of evicted slots are left in place; only validity changes.
+ */
+llmc_status_t llmc_bank_evict(llmc_bank_t* bank, const int32_t* d_m, int32_t m_max,
+                              int32_t* d_victims_out, llmc_stream_t stream);
+
+/* ---- fingerprint --------------------------------------------------------- */
+
+/*
+ * Section IV-B: embedding aggregation then dimensionality reduction, giving the
+ * fixed-length key of Section III-A.  For each sequence b of d_h [B, S, d]:
+ *   p = (1/S) sum_t h[b,t,:];  v = P^T p + c;  u = v / max(|v|, 1e-12);
+ *   d_fp_out[b] = u rounded to `dtype` (nearest even);  d_inv_norm_out[b] = 1/|rounded u| (0 if 0).
+ * d_proj [d, k] has element type `dtype`; d_bias [k] fp32 or NULL.
+ * d_workspace: at least llmc_fingerprint_workspace_bytes(B, S, d) bytes.
+ * Accumulation is fp32 in a fixed order that depends on S and d only.
+ */
+llmc_status_t llmc_fingerprint(const void* d_h, int32_t B, int32_t S, int32_t d, int32_t dtype,
+                               const void* d_proj, const float* d_bias, int32_t k,
+                               void* d_fp_out, float* d_inv_norm_out, void* d_workspace,
+                               size_t workspace_bytes, llmc_stream_t stream);
+size_t llmc_fingerprint_workspace_bytes(int32_t B, int32_t S, int32_t d);
+
+/* d_inv_norm_out[i] = 1 / |d_fp[i]| for n stored keys [n, k] (0 for a zero key):
+ * the norm that the cosine of Section III-C divides by, for keys supplied directly. */
+llmc_status_t llmc_inv_norm(const void* d_fp, int64_t n, int32_t k, int32_t dtype,
+                            float* d_inv_norm_out, llmc_stream_t stream);
+
+/* ---- match ------------------------------------------------------------------ */
+
+/*
+ * Section III-C with the test of Section IV-A / Algorithm 1: for each query
+ * key, the valid bank entry of largest cosine similarity, and whether that
+ * similarity strictly exceeds tau.
+ *   d_fp [B, k] (bank's element type), d_inv_norm [B]
+ *   d_idx [B]: best slot, lowest slot on exact ties, -1 if no valid entry
+ *   d_sim [B]: its cosine (product of the stored vectors times both inverse norms), -inf if none
+ *   d_hit [B]: sim > tau        (d_sim, d_hit may be NULL)
+ *   d_near_tie: optional [B] flags, 1 where two candidate groups were compared exactly
+ * The bulk search runs on the matrix cores with fp32 accumulation; the winner
+ * is then decided, and d_sim computed, in fp64 among the best candidate group
+ * (and the runner-up group when the two are closer than 1e-5).
+ * d_workspace: at least llmc_match_workspace_bytes(bank, B) bytes.
+ * Errors: INVALID_ARG (null, B <= 0, tau NaN), WORKSPACE.
+ */
+llmc_status_t llmc_match(const llmc_bank_t* bank, const void* d_fp, const float* d_inv_norm,
+                         int32_t B, float tau, int32_t* d_idx, float* d_sim, uint8_t* d_hit,
+                         uint8_t* d_near_tie, void* d_workspace, size_t workspace_bytes,
+                         llmc_stream_t stream);
+size_t llmc_match_workspace_bytes(const llmc_bank_t* bank, int32_t B);
+
+/* ---- gather ----------------------------------------------------------------- */
+
+/*
+ * Algorithm 1's reuse step h_l <- h' (Section IV-A, first case): for i < n,
+ * copy the cached output of slot d_idx[d_rows[i]] into d_h_out[d_rows[i]].
+ *   d_rows [n_max] row numbers, d_n device count (NULL: n = n_max), d_idx [B] slots
+ * Exact copy.  d_h_out is [B, S, d] with the bank's S, d and element type.
+ */
+llmc_status_t llmc_gather_hits(const llmc_bank_t* bank, const int32_t* d_idx, const int32_t* d_rows,
+                               const int32_t* d_n, int32_t n_max, void* d_h_out, llmc_stream_t stream);
+
+/* ---- the gated layer ---------------------------------------------------------- */
+
+/*
+ * One trip of Algorithm 1's loop body for a batch (case equation of Section
+ * IV-A): fingerprint the layer input, match it against the layer's bank,
+ * reuse the cached output where sim > tau and compute f_l only for the other
+ * rows, then (by flag) record hits and store the computed rows.
+ *   layer: f_l;  bank: C_l, or NULL = the layer is not cached and every row is
+ *          computed (layer selection, Section VI-D);  fp: P_l, c_l (ignored if bank NULL)
+ *   d_h_in, d_h_out [B, S, d], element type of the layer; they must not overlap
+ *   d_fp_given / d_inv_norm_given: NULL, or keys [B, k] + norms to use instead of
+ *          fingerprinting d_h_in (Algorithm 1 taken literally: one fingerprint of X for all layers)
+ *   tau: threshold; flags: LLMC_INSERT_ON_MISS | LLMC_UPDATE_LRU; tick <= LLMC_MAX_TICK
+ *   out: optional per-row results and counters (NULL or any member NULL)
+ *   d_workspace: at least llmc_layer_workspace_bytes(layer, B, S, k) bytes
+ * The number of misses never visits the host: the miss-path kernels read it on
+ * the device.  Hit rows are exact copies of the cached values.
+ * Errors: INVALID_ARG, SHAPE (layer/bank/fp disagree on d, S, k or dtype; dh != 64), DTYPE, WORKSPACE.
+ */
+llmc_status_t llmc_layer_forward_gated(const llmc_layer_desc_t* layer, llmc_bank_t* bank,
+                                       const llmc_fp_desc_t* fp, const void* d_h_in, void* d_h_out,
+                                       int32_t B, int32_t S, float tau, uint32_t flags, uint64_t tick,
+                                       const void* d_fp_given, const float* d_inv_norm_given,
+                                       const llmc_gate_out_t* out, void* d_workspace,
+                                       size_t workspace_bytes, llmc_stream_t stream);
+size_t llmc_layer_workspace_bytes(const llmc_layer_desc_t* layer, int32_t B, int32_t S, int32_t k);
+
+/* ---- misc ---------------------------------------------------------------------- */
+
+const char* llmc_last_error(void); /* thread-local, never NULL */
+const char* llmc_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LLMC_H */

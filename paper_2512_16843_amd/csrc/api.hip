@@ -1,0 +1,299 @@
+// C ABI of libllmc.so: argument validation (before any HIP call) and the host-side
+// orchestration of the gated layer, which only enqueues kernels on the caller's stream.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+#include <new>
+#include "common.h"
+
+namespace llmc {
+
+static thread_local char g_err[512] = "";
+
+llmc_status_t set_error(llmc_status_t st, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return st;
+}
+llmc_status_t hip_error(hipError_t e, const char* what) {
+  return set_error(LLMC_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+static bool dtype_ok(int dt) { return dt == LLMC_F32 || dt == LLMC_BF16; }
+
+#define REQUIRE(cond, st, ...)                      \
+  do {                                              \
+    if (!(cond)) return set_error(st, __VA_ARGS__); \
+  } while (0)
+
+static llmc_status_t check_layer(const llmc_layer_desc_t* L) {
+  REQUIRE(L, LLMC_ERR_INVALID_ARG, "layer descriptor is NULL");
+  REQUIRE(dtype_ok(L->dtype), LLMC_ERR_DTYPE, "layer dtype %d unknown", L->dtype);
+  REQUIRE(L->arch == 0 || L->arch == 1, LLMC_ERR_INVALID_ARG, "layer arch %d unknown", L->arch);
+  REQUIRE(L->gelu == 0 || L->gelu == 1, LLMC_ERR_INVALID_ARG, "gelu kind %d unknown", L->gelu);
+  REQUIRE(L->d > 0 && L->n_heads > 0 && L->d_ff > 0, LLMC_ERR_SHAPE, "non-positive layer size");
+  REQUIRE(L->d % 64 == 0 && L->d_ff % 64 == 0, LLMC_ERR_SHAPE, "d=%d and d_ff=%d must be multiples of 64", L->d,
+          L->d_ff);
+  REQUIRE(L->d % L->n_heads == 0 && L->d / L->n_heads == 64, LLMC_ERR_SHAPE, "head size d/n_heads must be 64, got %d/%d",
+          L->d, L->n_heads);
+  REQUIRE(L->ln_eps > 0.f && L->ln_eps == L->ln_eps, LLMC_ERR_INVALID_ARG, "ln_eps must be positive");
+  const void* ptrs[] = {L->d_wqkv, L->d_bqkv, L->d_wo, L->d_bo, L->d_w1, L->d_b1, L->d_w2, L->d_b2,
+                        L->d_ln1_g, L->d_ln1_b, L->d_ln2_g, L->d_ln2_b};
+  for (const void* p : ptrs) {
+    REQUIRE(p, LLMC_ERR_INVALID_ARG, "a layer weight pointer is NULL");
+    REQUIRE(aligned16(p), LLMC_ERR_SHAPE, "layer weight pointers must be 16-byte aligned");
+  }
+  return LLMC_OK;
+}
+
+static size_t gate_small_bytes(int B, int k, int dtype) {
+  // keys, inverse norms, idx, sim, hit, tie, hit_rows, miss_rows, slots, counters
+  return align_up((size_t)B * k * elem_size(dtype), 256) + 6 * align_up((size_t)B * 4, 256) +
+         2 * align_up((size_t)B, 256) + 256;
+}
+
+}  // namespace llmc
+
+using namespace llmc;
+
+extern "C" {
+
+const char* llmc_last_error(void) { return g_err; }
+const char* llmc_version(void) { return "llmc 0.1 (gfx950)"; }
+
+llmc_status_t llmc_bank_create(const llmc_bank_desc_t* desc, llmc_bank_t** out) {
+  REQUIRE(desc && out, LLMC_ERR_INVALID_ARG, "desc/out is NULL");
+  *out = nullptr;
+  REQUIRE(dtype_ok(desc->dtype), LLMC_ERR_DTYPE, "bank dtype %d unknown", desc->dtype);
+  REQUIRE(desc->policy == LLMC_EVICT_NONE || desc->policy == LLMC_EVICT_LRU, LLMC_ERR_INVALID_ARG,
+          "eviction policy %d unknown", desc->policy);
+  REQUIRE(desc->n_slots > 0 && desc->k > 0 && desc->S > 0 && desc->d > 0 && desc->n_act_slots > 0, LLMC_ERR_SHAPE,
+          "non-positive bank size");
+  REQUIRE(desc->k % 32 == 0 && desc->k <= 1024, LLMC_ERR_SHAPE, "k=%d must be a multiple of 32, at most 1024", desc->k);
+  REQUIRE(desc->d % 64 == 0, LLMC_ERR_SHAPE, "d=%d must be a multiple of 64", desc->d);
+  REQUIRE(desc->n_act_slots <= desc->n_slots, LLMC_ERR_SHAPE, "n_act_slots > n_slots");
+  REQUIRE(desc->d_act_slot || desc->n_act_slots == desc->n_slots, LLMC_ERR_SHAPE,
+          "identity value map needs n_act_slots == n_slots");
+  REQUIRE(desc->d_fp && desc->d_act && desc->d_inv_norm && desc->d_last_used && desc->d_hits && desc->d_valid,
+          LLMC_ERR_INVALID_ARG, "a bank array pointer is NULL");
+  REQUIRE(aligned16(desc->d_fp) && aligned16(desc->d_act), LLMC_ERR_SHAPE, "bank arrays must be 16-byte aligned");
+  llmc_bank* b = new (std::nothrow) llmc_bank();
+  REQUIRE(b, LLMC_ERR_INVALID_ARG, "out of host memory");
+  b->desc = *desc;
+  b->d_binv_eff = nullptr;
+  hipError_t e = hipGetDevice(&b->device);
+  if (e == hipSuccess) e = hipMalloc((void**)&b->d_binv_eff, align_up((size_t)desc->n_slots, 256) * sizeof(float));
+  if (e != hipSuccess) {
+    delete b;
+    return hip_error(e, "llmc_bank_create: hipMalloc");
+  }
+  llmc_status_t st = launch_bank_refresh(b, nullptr);
+  if (st == LLMC_OK) {
+    e = hipStreamSynchronize(nullptr);
+    if (e != hipSuccess) st = hip_error(e, "llmc_bank_create: sync");
+  }
+  if (st != LLMC_OK) {
+    (void)hipFree(b->d_binv_eff);
+    delete b;
+    return st;
+  }
+  *out = b;
+  return LLMC_OK;
+}
+
+llmc_status_t llmc_bank_destroy(llmc_bank_t* bank) {
+  if (!bank) return LLMC_OK;
+  hipError_t e = hipDeviceSynchronize();
+  hipError_t e2 = hipFree(bank->d_binv_eff);
+  delete bank;
+  if (e != hipSuccess) return hip_error(e, "llmc_bank_destroy: sync");
+  if (e2 != hipSuccess) return hip_error(e2, "llmc_bank_destroy: hipFree");
+  return LLMC_OK;
+}
+
+llmc_status_t llmc_bank_refresh(llmc_bank_t* bank, llmc_stream_t stream) {
+  REQUIRE(bank, LLMC_ERR_INVALID_ARG, "bank is NULL");
+  return launch_bank_refresh(bank, (hipStream_t)stream);
+}
+
+llmc_status_t llmc_bank_insert(llmc_bank_t* bank, const void* d_fp, const float* d_inv_norm, const void* d_act,
+                               const int32_t* d_rows, const int32_t* d_m, int32_t m_max, uint64_t tick,
+                               int32_t* d_slots_out, int32_t* d_counters, llmc_stream_t stream) {
+  REQUIRE(bank && d_fp && d_inv_norm && d_act && d_slots_out, LLMC_ERR_INVALID_ARG, "NULL argument");
+  REQUIRE(m_max > 0 && m_max <= LLMC_MAX_UPDATE_ROWS, LLMC_ERR_SHAPE, "m_max=%d out of range 1..%d", m_max,
+          LLMC_MAX_UPDATE_ROWS);
+  REQUIRE(tick <= LLMC_MAX_TICK, LLMC_ERR_INVALID_ARG, "tick out of range");
+  REQUIRE(bank->desc.n_act_slots == bank->desc.n_slots, LLMC_ERR_SHAPE,
+          "insertion into a bank whose keys share value rows is refused");
+  REQUIRE(aligned16(d_fp) && aligned16(d_act), LLMC_ERR_SHAPE, "arrays must be 16-byte aligned");
+  return launch_bank_insert(bank, d_fp, d_inv_norm, d_act, d_rows, d_m, m_max, tick, d_slots_out, d_counters,
+                            (hipStream_t)stream);
+}
+
+llmc_status_t llmc_bank_evict(llmc_bank_t* bank, const int32_t* d_m, int32_t m_max, int32_t* d_victims_out,
+                              llmc_stream_t stream) {
+  REQUIRE(bank && d_victims_out, LLMC_ERR_INVALID_ARG, "NULL argument");
+  REQUIRE(m_max > 0 && m_max <= LLMC_MAX_UPDATE_ROWS, LLMC_ERR_SHAPE, "m_max=%d out of range 1..%d", m_max,
+          LLMC_MAX_UPDATE_ROWS);
+  return launch_bank_evict(bank, d_m, m_max, d_victims_out, (hipStream_t)stream);
+}
+
+size_t llmc_fingerprint_workspace_bytes(int32_t B, int32_t S, int32_t d) {
+  if (B <= 0 || S <= 0 || d <= 0) return 0;
+  return fingerprint_ws_bytes(B, S, d);
+}
+
+static llmc_status_t check_fp_shape(int B, int S, int d, int dtype, int k) {
+  REQUIRE(dtype_ok(dtype), LLMC_ERR_DTYPE, "dtype %d unknown", dtype);
+  REQUIRE(B > 0 && S > 0 && d > 0 && k > 0, LLMC_ERR_INVALID_ARG, "non-positive size");
+  REQUIRE(B <= 65535, LLMC_ERR_SHAPE, "B=%d exceeds 65535", B);
+  REQUIRE(d % 64 == 0 && d <= 8192, LLMC_ERR_SHAPE, "d=%d must be a multiple of 64, at most 8192", d);
+  REQUIRE(k % 32 == 0 && k <= 1024, LLMC_ERR_SHAPE, "k=%d must be a multiple of 32, at most 1024", k);
+  return LLMC_OK;
+}
+
+llmc_status_t llmc_fingerprint(const void* d_h, int32_t B, int32_t S, int32_t d, int32_t dtype, const void* d_proj,
+                               const float* d_bias, int32_t k, void* d_fp_out, float* d_inv_norm_out,
+                               void* d_workspace, size_t workspace_bytes, llmc_stream_t stream) {
+  REQUIRE(d_h && d_proj && d_fp_out && d_inv_norm_out, LLMC_ERR_INVALID_ARG, "NULL argument");
+  LLMC_TRY(check_fp_shape(B, S, d, dtype, k));
+  REQUIRE(aligned16(d_h) && aligned16(d_proj) && aligned16(d_fp_out), LLMC_ERR_SHAPE, "arrays must be 16-byte aligned");
+  REQUIRE(d_workspace && workspace_bytes >= fingerprint_ws_bytes(B, S, d), LLMC_ERR_WORKSPACE,
+          "fingerprint workspace needs %zu bytes", fingerprint_ws_bytes(B, S, d));
+  return launch_fingerprint(d_h, nullptr, B, S, d, dtype, d_proj, d_bias, k, d_fp_out, d_inv_norm_out, d_workspace,
+                            (hipStream_t)stream);
+}
+
+llmc_status_t llmc_inv_norm(const void* d_fp, int64_t n, int32_t k, int32_t dtype, float* d_inv_norm_out,
+                            llmc_stream_t stream) {
+  REQUIRE(d_fp && d_inv_norm_out, LLMC_ERR_INVALID_ARG, "NULL argument");
+  REQUIRE(dtype_ok(dtype), LLMC_ERR_DTYPE, "dtype %d unknown", dtype);
+  REQUIRE(n > 0 && k > 0 && n <= (int64_t)4 * 0x7FFFFFFF, LLMC_ERR_INVALID_ARG, "size out of range");
+  return launch_inv_norm(d_fp, n, k, dtype, d_inv_norm_out, (hipStream_t)stream);
+}
+
+size_t llmc_match_workspace_bytes(const llmc_bank_t* bank, int32_t B) {
+  if (!bank || B <= 0) return 0;
+  return match_ws_bytes(bank->desc.n_slots, bank->desc.k, bank->desc.dtype, B);
+}
+
+llmc_status_t llmc_match(const llmc_bank_t* bank, const void* d_fp, const float* d_inv_norm, int32_t B, float tau,
+                         int32_t* d_idx, float* d_sim, uint8_t* d_hit, uint8_t* d_near_tie, void* d_workspace,
+                         size_t workspace_bytes, llmc_stream_t stream) {
+  REQUIRE(bank && d_fp && d_inv_norm && d_idx, LLMC_ERR_INVALID_ARG, "NULL argument");
+  REQUIRE(B > 0, LLMC_ERR_INVALID_ARG, "B must be positive");
+  REQUIRE(B <= 65535 * 128, LLMC_ERR_SHAPE, "B=%d too large", B);
+  REQUIRE(tau == tau, LLMC_ERR_INVALID_ARG, "tau is NaN");
+  REQUIRE(aligned16(d_fp), LLMC_ERR_SHAPE, "query keys must be 16-byte aligned");
+  const size_t need = match_ws_bytes(bank->desc.n_slots, bank->desc.k, bank->desc.dtype, B);
+  REQUIRE(d_workspace && workspace_bytes >= need, LLMC_ERR_WORKSPACE, "match workspace needs %zu bytes", need);
+  return launch_match(bank, d_fp, d_inv_norm, B, tau, d_idx, d_sim, d_hit, d_near_tie, d_workspace,
+                      (hipStream_t)stream);
+}
+
+llmc_status_t llmc_gather_hits(const llmc_bank_t* bank, const int32_t* d_idx, const int32_t* d_rows, const int32_t* d_n,
+                               int32_t n_max, void* d_h_out, llmc_stream_t stream) {
+  REQUIRE(bank && d_idx && d_h_out, LLMC_ERR_INVALID_ARG, "NULL argument");
+  REQUIRE(n_max > 0 && n_max <= 65535, LLMC_ERR_SHAPE, "n_max=%d out of range 1..65535", n_max);
+  REQUIRE(aligned16(d_h_out), LLMC_ERR_SHAPE, "output must be 16-byte aligned");
+  return launch_gather(bank, d_idx, d_rows, d_n, n_max, d_h_out, (hipStream_t)stream);
+}
+
+size_t llmc_layer_workspace_bytes(const llmc_layer_desc_t* layer, int32_t B, int32_t S, int32_t k) {
+  if (!layer || B <= 0 || S <= 0 || k < 0 || !dtype_ok(layer->dtype)) return 0;
+  // the match scratch is bounded by 1024 splits of 16 bytes per row
+  return fingerprint_ws_bytes(B, S, layer->d) + gate_small_bytes(B, k > 0 ? k : 32, layer->dtype) +
+         align_up((size_t)1024 * B * 16, 256) + layer_ws_bytes(layer, B, S);
+}
+
+llmc_status_t llmc_layer_forward_gated(const llmc_layer_desc_t* layer, llmc_bank_t* bank, const llmc_fp_desc_t* fp,
+                                       const void* d_h_in, void* d_h_out, int32_t B, int32_t S, float tau,
+                                       uint32_t flags, uint64_t tick, const void* d_fp_given,
+                                       const float* d_inv_norm_given, const llmc_gate_out_t* out, void* d_workspace,
+                                       size_t workspace_bytes, llmc_stream_t stream) {
+  LLMC_TRY(check_layer(layer));
+  REQUIRE(d_h_in && d_h_out, LLMC_ERR_INVALID_ARG, "d_h_in/d_h_out is NULL");
+  REQUIRE(d_h_in != d_h_out, LLMC_ERR_INVALID_ARG, "d_h_in and d_h_out must not overlap");
+  REQUIRE(aligned16(d_h_in) && aligned16(d_h_out), LLMC_ERR_SHAPE, "activations must be 16-byte aligned");
+  REQUIRE(B > 0 && S > 0, LLMC_ERR_INVALID_ARG, "B and S must be positive");
+  REQUIRE(B <= 65535, LLMC_ERR_SHAPE, "B=%d exceeds 65535", B);
+  REQUIRE((int64_t)B * S <= 0x7FFFFFFF / 4, LLMC_ERR_SHAPE, "B*S too large");
+  REQUIRE(tau == tau, LLMC_ERR_INVALID_ARG, "tau is NaN");
+  REQUIRE(tick <= LLMC_MAX_TICK, LLMC_ERR_INVALID_ARG, "tick out of range");
+  REQUIRE((flags & ~(LLMC_INSERT_ON_MISS | LLMC_UPDATE_LRU)) == 0, LLMC_ERR_INVALID_ARG, "unknown flag bits");
+  int k = 0;
+  if (bank) {
+    const llmc_bank_desc_t& D = bank->desc;
+    REQUIRE(D.dtype == layer->dtype, LLMC_ERR_DTYPE, "bank and layer element types differ");
+    REQUIRE(D.d == layer->d && D.S == S, LLMC_ERR_SHAPE, "bank value shape [%d,%d] does not fit [S=%d,d=%d]", D.S, D.d,
+            S, layer->d);
+    k = D.k;
+    if (d_fp_given) {
+      REQUIRE(d_inv_norm_given, LLMC_ERR_INVALID_ARG, "given keys need their inverse norms");
+      REQUIRE(aligned16(d_fp_given), LLMC_ERR_SHAPE, "given keys must be 16-byte aligned");
+    } else {
+      REQUIRE(fp && fp->d_proj, LLMC_ERR_INVALID_ARG, "fingerprint descriptor is NULL");
+      REQUIRE(fp->k == D.k, LLMC_ERR_SHAPE, "fingerprint length %d does not fit the bank's %d", fp->k, D.k);
+      REQUIRE(aligned16(fp->d_proj), LLMC_ERR_SHAPE, "projection must be 16-byte aligned");
+      LLMC_TRY(check_fp_shape(B, S, layer->d, layer->dtype, k));
+    }
+    if (flags & LLMC_INSERT_ON_MISS) {
+      REQUIRE(B <= LLMC_MAX_UPDATE_ROWS, LLMC_ERR_SHAPE, "insertion handles at most %d rows per call",
+              LLMC_MAX_UPDATE_ROWS);
+      REQUIRE(D.n_act_slots == D.n_slots, LLMC_ERR_SHAPE,
+              "insertion into a bank whose keys share value rows is refused");
+    }
+  }
+  const size_t need = llmc_layer_workspace_bytes(layer, B, S, k);
+  REQUIRE(d_workspace && workspace_bytes >= need, LLMC_ERR_WORKSPACE, "layer workspace needs %zu bytes", need);
+  REQUIRE(aligned16(d_workspace), LLMC_ERR_SHAPE, "workspace must be 16-byte aligned");
+
+  hipStream_t st = (hipStream_t)stream;
+  char* p = (char*)d_workspace;
+  auto take = [&](size_t bytes) { char* r = p; p += align_up(bytes, 256); return (void*)r; };
+  void* ws_fp = take(fingerprint_ws_bytes(B, S, layer->d));
+  void* keys = take((size_t)B * (k > 0 ? k : 32) * elem_size(layer->dtype));
+  float* inv = (float*)take((size_t)B * 4);
+  int32_t* idx = (int32_t*)take((size_t)B * 4);
+  float* sim = (float*)take((size_t)B * 4);
+  int32_t* hit_rows = (int32_t*)take((size_t)B * 4);
+  int32_t* miss_rows = (int32_t*)take((size_t)B * 4);
+  int32_t* slots = (int32_t*)take((size_t)B * 4);
+  uint8_t* hit = (uint8_t*)take((size_t)B);
+  uint8_t* tie = (uint8_t*)take((size_t)B);
+  int32_t* counters = (int32_t*)take(LLMC_CNT_WORDS * 4);
+  void* ws_match = take((size_t)1024 * B * 16);
+  void* ws_layer = (void*)p;
+  if (out) {
+    if (out->d_idx) idx = out->d_idx;
+    if (out->d_sim) sim = out->d_sim;
+    if (out->d_hit) hit = out->d_hit;
+    if (out->d_counters) counters = out->d_counters;
+    if (out->d_slots) slots = out->d_slots;
+  }
+  if (!bank) {
+    LLMC_TRY(launch_all_miss(B, miss_rows, counters, out ? out->d_idx : nullptr, out ? out->d_sim : nullptr,
+                             out ? out->d_hit : nullptr, st));
+    return launch_layer(layer, d_h_in, d_h_out, B, S, miss_rows, counters + LLMC_CNT_MISS, ws_layer, st);
+  }
+  const void* q = d_fp_given;
+  const float* qinv = d_inv_norm_given;
+  if (!q) {
+    LLMC_TRY(launch_fingerprint(d_h_in, nullptr, B, S, layer->d, layer->dtype, fp->d_proj, fp->d_bias, k, keys, inv,
+                                ws_fp, st));
+    q = keys;
+    qinv = inv;
+  }
+  LLMC_TRY(launch_match(bank, q, qinv, B, tau, idx, sim, hit, tie, ws_match, st));
+  LLMC_TRY(launch_compact(hit, idx, sim, tie, B, tau, hit_rows, miss_rows, counters, bank, flags, tick, st));
+  LLMC_TRY(launch_gather(bank, idx, hit_rows, counters + LLMC_CNT_HIT, B, d_h_out, st));
+  LLMC_TRY(launch_layer(layer, d_h_in, d_h_out, B, S, miss_rows, counters + LLMC_CNT_MISS, ws_layer, st));
+  if (flags & LLMC_INSERT_ON_MISS)
+    LLMC_TRY(launch_bank_insert(bank, q, qinv, d_h_out, miss_rows, counters + LLMC_CNT_MISS, B, tick, slots, counters,
+                                st));
+  return LLMC_OK;
+}
+
+}  // extern "C"

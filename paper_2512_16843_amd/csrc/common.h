@@ -1,0 +1,175 @@
+// Internal helpers shared by the llmc kernels (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include <math.h>
+#include "../../include/llmc.h"
+
+namespace llmc {
+
+// ---- element types ---------------------------------------------------------
+// bf16 values travel as raw 16-bit patterns; arithmetic is always fp32.
+struct bf16_t {
+  uint16_t bits;
+};
+
+__device__ __forceinline__ float bf16_to_f32(uint16_t b) {
+  return __uint_as_float(((uint32_t)b) << 16);
+}
+// round to nearest, ties to even; NaN stays NaN
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x40u);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+  static constexpr int kVec = 4;  // elements per 16-byte vector
+  __device__ static __forceinline__ float load(const float* p) { return *p; }
+  __device__ static __forceinline__ void store(float* p, float v) { *p = v; }
+  __device__ static __forceinline__ float round(float v) { return v; }
+};
+template <> struct Elem<bf16_t> {
+  static constexpr int kVec = 8;
+  __device__ static __forceinline__ float load(const bf16_t* p) { return bf16_to_f32(p->bits); }
+  __device__ static __forceinline__ void store(bf16_t* p, float v) { p->bits = f32_to_bf16(v); }
+  __device__ static __forceinline__ float round(float v) { return bf16_to_f32(f32_to_bf16(v)); }
+};
+
+// 16-byte vector of T unpacked to fp32
+template <typename T> struct Vec16;
+template <> struct Vec16<float> {
+  static constexpr int N = 4;
+  __device__ static __forceinline__ void load(const float* p, float* out) {
+    float4 v = *reinterpret_cast<const float4*>(p);
+    out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w;
+  }
+  __device__ static __forceinline__ void store(float* p, const float* in) {
+    *reinterpret_cast<float4*>(p) = make_float4(in[0], in[1], in[2], in[3]);
+  }
+};
+template <> struct Vec16<bf16_t> {
+  static constexpr int N = 8;
+  __device__ static __forceinline__ void load(const bf16_t* p, float* out) {
+    uint4 v = *reinterpret_cast<const uint4*>(p);
+    uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      out[2 * i] = __uint_as_float(w[i] << 16);
+      out[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
+    }
+  }
+  __device__ static __forceinline__ void store(bf16_t* p, const float* in) {
+    uint32_t w[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      w[i] = (uint32_t)f32_to_bf16(in[2 * i]) | ((uint32_t)f32_to_bf16(in[2 * i + 1]) << 16);
+    *reinterpret_cast<uint4*>(p) = make_uint4(w[0], w[1], w[2], w[3]);
+  }
+};
+
+// ---- wavefront (64 lanes) reductions with a fixed order -------------------------
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+// ---- host-side error plumbing ------------------------------------------------------
+llmc_status_t set_error(llmc_status_t st, const char* fmt, ...);
+llmc_status_t hip_error(hipError_t e, const char* what);
+
+#define LLMC_HIP(call)                                   \
+  do {                                                   \
+    hipError_t e_ = (call);                              \
+    if (e_ != hipSuccess) return hip_error(e_, #call);   \
+  } while (0)
+#define LLMC_LAUNCH_CHECK(what)                          \
+  do {                                                   \
+    hipError_t e_ = hipGetLastError();                   \
+    if (e_ != hipSuccess) return hip_error(e_, what);    \
+  } while (0)
+#define LLMC_TRY(expr)                                   \
+  do {                                                   \
+    llmc_status_t s_ = (expr);                           \
+    if (s_ != LLMC_OK) return s_;                        \
+  } while (0)
+
+static inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+static inline size_t elem_size(int dtype) { return dtype == LLMC_F32 ? 4 : 2; }
+
+// ---- the bank object ------------------------------------------------------------------
+}  // namespace llmc
+
+struct llmc_bank {
+  llmc_bank_desc_t desc;
+  // Library-owned mirror [n_slots]: inv_norm of valid slots, NaN for free ones.  The match
+  // epilogue multiplies scores by it and takes maxima with NaN-ignoring max, so free
+  // slots never win and never mask a valid entry.
+  float* d_binv_eff;
+  int device;
+};
+
+namespace llmc {
+
+// ---- kernel launchers (one per translation unit) ------------------------------------------
+// fingerprint.hip
+size_t fingerprint_ws_bytes(int B, int S, int d);
+llmc_status_t launch_fingerprint(const void* d_h, const int32_t* d_rowmap_unused, int B, int S, int d, int dtype,
+                                 const void* d_proj, const float* d_bias, int k, void* d_fp, float* d_inv,
+                                 void* ws, hipStream_t st);
+llmc_status_t launch_inv_norm(const void* d_fp, int64_t n, int k, int dtype, float* d_out, hipStream_t st);
+
+// match.hip
+size_t match_ws_bytes(int n_slots, int k, int dtype, int B);
+llmc_status_t launch_match(const llmc_bank* bank, const void* d_fp, const float* d_inv, int B, float tau,
+                           int32_t* d_idx, float* d_sim, uint8_t* d_hit, uint8_t* d_near_tie, void* ws,
+                           hipStream_t st);
+
+// gate.hip
+llmc_status_t launch_compact(const uint8_t* d_hit, const int32_t* d_idx, const float* d_sim,
+                             const uint8_t* d_near_tie, int B, float tau, int32_t* d_hit_rows,
+                             int32_t* d_miss_rows, int32_t* d_counters, llmc_bank* bank, uint32_t flags,
+                             uint64_t tick, hipStream_t st);
+llmc_status_t launch_all_miss(int B, int32_t* d_miss_rows, int32_t* d_counters, int32_t* d_idx, float* d_sim,
+                              uint8_t* d_hit, hipStream_t st);
+llmc_status_t launch_gather(const llmc_bank* bank, const int32_t* d_idx, const int32_t* d_rows,
+                            const int32_t* d_n, int n_max, void* d_h_out, hipStream_t st);
+
+// bank.hip
+llmc_status_t launch_bank_refresh(llmc_bank* bank, hipStream_t st);
+llmc_status_t launch_bank_insert(llmc_bank* bank, const void* d_fp, const float* d_inv, const void* d_act,
+                                 const int32_t* d_rows, const int32_t* d_m, int m_max, uint64_t tick,
+                                 int32_t* d_slots_out, int32_t* d_counters, hipStream_t st);
+llmc_status_t launch_bank_evict(llmc_bank* bank, const int32_t* d_m, int m_max, int32_t* d_victims,
+                                hipStream_t st);
+
+// layer.hip
+struct LayerWs {
+  void* qkv;   // [T, 3d]
+  void* ctx;   // [T, d]
+  void* t0;    // [T, d]
+  void* t1;    // [T, d]
+  void* ff;    // [T, d_ff]
+};
+size_t layer_ws_bytes(const llmc_layer_desc_t* L, int B, int S);
+// Computes f_l for the sequences listed in d_rows[0 .. *d_count) of d_h_in and writes each
+// result to the same row of d_h_out.  d_count / d_rows live on the device.
+llmc_status_t launch_layer(const llmc_layer_desc_t* L, const void* d_h_in, void* d_h_out, int B, int S,
+                           const int32_t* d_rows, const int32_t* d_count, void* ws, hipStream_t st);
+
+}  // namespace llmc

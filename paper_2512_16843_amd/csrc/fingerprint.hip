@@ -1,0 +1,189 @@
+// Fingerprint of a layer input (Section IV-B of the paper): the average of the token
+// vectors, a linear dimensionality reduction, and normalisation to the fixed-length
+// key that the bank stores (Section III-A).
+//
+// Two kernels.  pool_kernel streams h once (HBM-bound): a workgroup owns one
+// (sequence, 32-token chunk) and leaves an fp32 partial sum per feature.
+// project_kernel adds the partials in chunk order, applies P and c, normalises,
+// rounds to the bank's element type and stores 1/|rounded key|.
+// Every reduction order depends on S, d and k only, so a sequence's key is the same
+// bits wherever it sits in whatever batch.
+#include "common.h"
+
+namespace llmc {
+
+constexpr int kTokChunk = 32;   // tokens per pooling workgroup
+constexpr int kProjSplit = 4;   // groups that split the d-loop of the projection
+
+static inline int pool_chunks(int S) { return (S + kTokChunk - 1) / kTokChunk; }
+
+// grid (chunks, B); block G*R threads, G = d / VEC column groups, R rows in flight
+template <typename T>
+__global__ void pool_kernel(const T* __restrict__ h, int S, int d, int G, int R, float* __restrict__ partial,
+                            int n_chunks) {
+  constexpr int VEC = Vec16<T>::N;
+  extern __shared__ float red[];  // [R][d]
+  const int b = blockIdx.y, chunk = blockIdx.x;
+  const int g = threadIdx.x % G, r = threadIdx.x / G;
+  const int t0 = chunk * kTokChunk;
+  const int t1 = min(S, t0 + kTokChunk);
+  const T* base = h + ((size_t)b * S) * d + (size_t)g * VEC;
+  float acc[VEC];
+#pragma unroll
+  for (int i = 0; i < VEC; ++i) acc[i] = 0.f;
+  int t = t0 + r;
+  // four rows in flight per thread, added in ascending token order
+  for (; t + 3 * R < t1; t += 4 * R) {
+    float v0[VEC], v1[VEC], v2[VEC], v3[VEC];
+    Vec16<T>::load(base + (size_t)t * d, v0);
+    Vec16<T>::load(base + (size_t)(t + R) * d, v1);
+    Vec16<T>::load(base + (size_t)(t + 2 * R) * d, v2);
+    Vec16<T>::load(base + (size_t)(t + 3 * R) * d, v3);
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) acc[i] = (((acc[i] + v0[i]) + v1[i]) + v2[i]) + v3[i];
+  }
+  for (; t < t1; t += R) {
+    float v0[VEC];
+    Vec16<T>::load(base + (size_t)t * d, v0);
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) acc[i] += v0[i];
+  }
+#pragma unroll
+  for (int i = 0; i < VEC; ++i) red[(size_t)r * d + g * VEC + i] = acc[i];
+  __syncthreads();
+  if (r == 0) {
+    float* out = partial + ((size_t)b * n_chunks + chunk) * d + g * VEC;
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) {
+      float s = acc[i];
+      for (int rr = 1; rr < R; ++rr) s += red[(size_t)rr * d + g * VEC + i];
+      out[i] = s;
+    }
+  }
+}
+
+// grid (B); block k * kProjSplit threads (k <= 256) -- thread (j, part) owns output j over a quarter of d
+template <typename T>
+__global__ void project_kernel(const float* __restrict__ partial, int n_chunks, int S, int d,
+                               const T* __restrict__ P, const float* __restrict__ bias, int k, int split,
+                               T* __restrict__ fp_out, float* __restrict__ inv_out) {
+  extern __shared__ float sm[];   // p[d] | v[split][k]
+  float* p = sm;
+  float* vpart = sm + d;
+  __shared__ double wsum[16];
+  __shared__ float s_scale;
+  const int b = blockIdx.x;
+  const int nthreads = blockDim.x;
+  const float inv_S = 1.0f / (float)S;
+  for (int i = threadIdx.x; i < d; i += nthreads) {
+    const float* src = partial + (size_t)b * n_chunks * d + i;
+    float s = 0.f;
+    for (int c = 0; c < n_chunks; ++c) s += src[(size_t)c * d];
+    p[i] = s * inv_S;
+  }
+  __syncthreads();
+  const int j = threadIdx.x % k, part = threadIdx.x / k;
+  {
+    const int per = (d + split - 1) / split;
+    const int i0 = part * per, i1 = min(d, i0 + per);
+    float v = 0.f;
+#pragma unroll 8
+    for (int i = i0; i < i1; ++i) v = fmaf(p[i], Elem<T>::load(P + (size_t)i * k + j), v);
+    vpart[part * k + j] = v;
+  }
+  __syncthreads();
+  float v = 0.f;
+  if (part == 0) {
+    v = vpart[j];
+    for (int s = 1; s < split; ++s) v += vpart[s * k + j];
+    if (bias) v += bias[j];
+  }
+  // |v|^2 in fp64: lanes of each wave, then waves in order
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int n_waves_k = (k + 63) / 64;
+  double sq = (part == 0) ? (double)v * (double)v : 0.0;
+  sq = wave_sum(sq);
+  if (lane == 0 && wave < 16) wsum[wave] = sq;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double tot = 0.0;
+    for (int w = 0; w < n_waves_k; ++w) tot += wsum[w];
+    float nrm = (float)sqrt(tot);
+    s_scale = 1.0f / fmaxf(nrm, 1e-12f);
+  }
+  __syncthreads();
+  float q = 0.f;
+  if (part == 0) {
+    q = Elem<T>::round(v * s_scale);
+    Elem<T>::store(fp_out + (size_t)b * k + j, q);
+  }
+  double sq2 = (part == 0) ? (double)q * (double)q : 0.0;
+  sq2 = wave_sum(sq2);
+  __syncthreads();
+  if (lane == 0 && wave < 16) wsum[wave] = sq2;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double tot = 0.0;
+    for (int w = 0; w < n_waves_k; ++w) tot += wsum[w];
+    inv_out[b] = tot > 0.0 ? (float)(1.0 / sqrt(tot)) : 0.f;
+  }
+}
+
+// one wavefront per key: 1/|key| with fp64 accumulation
+template <typename T>
+__global__ void inv_norm_kernel(const T* __restrict__ fp, int64_t n, int k, float* __restrict__ out) {
+  const int64_t row = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  if (row >= n) return;
+  const int lane = threadIdx.x & 63;
+  double s = 0.0;
+  for (int i = lane; i < k; i += 64) {
+    double x = (double)Elem<T>::load(fp + row * k + i);
+    s += x * x;
+  }
+  s = wave_sum(s);
+  if (lane == 0) out[row] = s > 0.0 ? (float)(1.0 / sqrt(s)) : 0.f;
+}
+
+size_t fingerprint_ws_bytes(int B, int S, int d) {
+  return align_up((size_t)B * pool_chunks(S) * d * sizeof(float), 256);
+}
+
+template <typename T>
+static llmc_status_t fingerprint_t(const T* h, int B, int S, int d, const T* P, const float* bias, int k,
+                                   T* fp, float* inv, float* partial, hipStream_t st) {
+  constexpr int VEC = Vec16<T>::N;
+  const int G = d / VEC;
+  const int R = G >= 256 ? 1 : 256 / G;
+  const int n_chunks = pool_chunks(S);
+  dim3 grid(n_chunks, B);
+  hipLaunchKernelGGL(pool_kernel<T>, grid, dim3(G * R), (size_t)R * d * sizeof(float), st, h, S, d, G, R, partial,
+                     n_chunks);
+  LLMC_LAUNCH_CHECK("pool_kernel");
+  const int split = k <= 256 ? kProjSplit : (k <= 512 ? 2 : 1);
+  hipLaunchKernelGGL(project_kernel<T>, dim3(B), dim3(k * split), (size_t)(d + split * k) * sizeof(float), st,
+                     partial, n_chunks, S, d, P, bias, k, split, fp, inv);
+  LLMC_LAUNCH_CHECK("project_kernel");
+  return LLMC_OK;
+}
+
+llmc_status_t launch_fingerprint(const void* d_h, const int32_t*, int B, int S, int d, int dtype, const void* d_proj,
+                                 const float* d_bias, int k, void* d_fp, float* d_inv, void* ws, hipStream_t st) {
+  if (dtype == LLMC_F32)
+    return fingerprint_t<float>((const float*)d_h, B, S, d, (const float*)d_proj, d_bias, k, (float*)d_fp, d_inv,
+                                (float*)ws, st);
+  return fingerprint_t<bf16_t>((const bf16_t*)d_h, B, S, d, (const bf16_t*)d_proj, d_bias, k, (bf16_t*)d_fp, d_inv,
+                               (float*)ws, st);
+}
+
+llmc_status_t launch_inv_norm(const void* d_fp, int64_t n, int k, int dtype, float* d_out, hipStream_t st) {
+  const int rows_per_block = 4;
+  const unsigned blocks = (unsigned)((n + rows_per_block - 1) / rows_per_block);
+  if (dtype == LLMC_F32)
+    hipLaunchKernelGGL(inv_norm_kernel<float>, dim3(blocks), dim3(256), 0, st, (const float*)d_fp, n, k, d_out);
+  else
+    hipLaunchKernelGGL(inv_norm_kernel<bf16_t>, dim3(blocks), dim3(256), 0, st, (const bf16_t*)d_fp, n, k, d_out);
+  LLMC_LAUNCH_CHECK("inv_norm_kernel");
+  return LLMC_OK;
+}
+
+}  // namespace llmc

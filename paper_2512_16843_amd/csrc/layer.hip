@@ -1,0 +1,399 @@
+// The miss path: one transformer block f_l (Section IV-A of the paper) applied to the
+// sequences that found no match, named by a device-side row list and count.
+//
+// Rows are processed in a compact token space: compact token r belongs to list entry
+// r / S and is token r % S of sequence rows[r / S].  Every kernel is launched for the
+// worst case (all B sequences) and reads the real count on the device; workgroups
+// beyond it exit at once, so the host never learns the number of misses.
+//
+// Kernels: linear layers on the bf16 matrix cores (fp32 accumulate) with bias, GELU,
+// residual and row gather/scatter fused into the epilogue; a plain fp32 FMA GEMM for
+// fp32 runs; LayerNorm with one wavefront per token; softmax attention with an online
+// softmax over 32-key tiles.
+#include "common.h"
+#include "mma.h"
+
+namespace llmc {
+
+// compact token -> row of a [B*S, *] array through an optional sequence list
+__device__ __forceinline__ int64_t map_row(const int32_t* rows, int r, int S) {
+  if (!rows) return r;
+  const int q = r / S;
+  return (int64_t)rows[q] * S + (r - q * S);
+}
+
+__device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752440f)); }
+__device__ __forceinline__ float gelu_tanh(float x) {
+  const float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
+  return 0.5f * x * (1.0f + tanhf(u));
+}
+
+struct GemmArgs {
+  const void* A; int lda;          // [rows, K]
+  const void* W;                   // [N, K]
+  const void* bias;                // [N] or null
+  const void* resid; int ldr;      // [rows, N] or null
+  void* out; int ldo;              // [rows, N]
+  int N, K, S;
+  const int32_t* count;            // device: number of sequences; null = max_seqs
+  int max_seqs;
+  const int32_t* a_rows;           // sequence list applied to A rows, or null
+  const int32_t* r_rows;           // ... to residual rows
+  const int32_t* o_rows;           // ... to output rows
+  int act;                         // 0 none, 1 GELU erf, 2 GELU tanh
+};
+
+__device__ __forceinline__ float apply_act(float v, int act) {
+  if (act == 1) return gelu_erf(v);
+  if (act == 2) return gelu_tanh(v);
+  return v;
+}
+
+// ---- bf16 GEMM on the matrix cores -------------------------------------------------------
+typedef MmaCfg<128, 128, 32, 2, 2> GemmCfg;
+
+__global__ __launch_bounds__(GemmCfg::THREADS) void gemm_bf16_kernel(GemmArgs g, int tiles_n) {
+  using C = GemmCfg;
+  __shared__ __attribute__((aligned(16))) uint16_t lds[C::LDS_BYTES / 2];
+  const int n_seq = g.count ? min(*g.count, g.max_seqs) : g.max_seqs;
+  const int M = n_seq * g.S;
+  const int tile_m = blockIdx.x / tiles_n, tile_n = blockIdx.x % tiles_n;
+  const int m0 = tile_m * C::BM, n0 = tile_n * C::BN;
+  if (m0 >= M) return;
+  const int tid = threadIdx.x;
+  const uint16_t* A = (const uint16_t*)g.A;
+  const uint16_t* W = (const uint16_t*)g.W;
+  const uint16_t* a_ptr[C::NLOAD_A];
+  const uint16_t* b_ptr[C::NLOAD_B];
+#pragma unroll
+  for (int i = 0; i < C::NLOAD_A; ++i) {
+    const int v = tid + i * C::THREADS;
+    const int r = min(m0 + v / C::VEC_PER_ROW, M - 1);
+    a_ptr[i] = A + map_row(g.a_rows, r, g.S) * g.lda + (v % C::VEC_PER_ROW) * 8;
+  }
+#pragma unroll
+  for (int i = 0; i < C::NLOAD_B; ++i) {
+    const int v = tid + i * C::THREADS;
+    const int r = min(n0 + v / C::VEC_PER_ROW, g.N - 1);
+    b_ptr[i] = W + (size_t)r * g.K + (v % C::VEC_PER_ROW) * 8;
+  }
+  f32x16_t acc[C::FM][C::FN];
+#pragma unroll
+  for (int i = 0; i < C::FM; ++i)
+#pragma unroll
+    for (int j = 0; j < C::FN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+  mma_block<C>(a_ptr, b_ptr, g.K, lds, acc);
+
+  const int lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / C::WN, wn = wave % C::WN;
+  const uint16_t* bias = (const uint16_t*)g.bias;
+  const uint16_t* resid = (const uint16_t*)g.resid;
+  uint16_t* out = (uint16_t*)g.out;
+#pragma unroll
+  for (int j = 0; j < C::FN; ++j) {
+    const int n = n0 + wn * (C::BN / C::WN) + j * 32 + (lane & 31);
+    if (n >= g.N) continue;
+    const float bv = bias ? bf16_to_f32(bias[n]) : 0.f;
+#pragma unroll
+    for (int i = 0; i < C::FM; ++i) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int m = m0 + wm * (C::BM / C::WM) + i * 32 + frag_row(lane, r);
+        if (m >= M) continue;
+        float v = apply_act(acc[i][j][r] + bv, g.act);
+        if (resid) v += bf16_to_f32(resid[map_row(g.r_rows, m, g.S) * g.ldr + n]);
+        out[map_row(g.o_rows, m, g.S) * g.ldo + n] = f32_to_bf16(v);
+      }
+    }
+  }
+}
+
+// ---- fp32 GEMM, plain FMA: 64x64 tile, 16-wide k step, 4x4 outputs per thread ------------------
+__global__ __launch_bounds__(256) void gemm_f32_kernel(GemmArgs g, int tiles_n) {
+  __shared__ float sA[16][64 + 4];
+  __shared__ float sB[16][64 + 4];
+  const int n_seq = g.count ? min(*g.count, g.max_seqs) : g.max_seqs;
+  const int M = n_seq * g.S;
+  const int tile_m = blockIdx.x / tiles_n, tile_n = blockIdx.x % tiles_n;
+  const int m0 = tile_m * 64, n0 = tile_n * 64;
+  if (m0 >= M) return;
+  const int tid = threadIdx.x;
+  const float* A = (const float*)g.A;
+  const float* W = (const float*)g.W;
+  // each thread loads one float4 of A and one of W per k step: row = tid / 4, k = (tid % 4) * 4
+  const int lr = tid >> 2, lk = (tid & 3) * 4;
+  const float* ap = A + map_row(g.a_rows, min(m0 + lr, M - 1), g.S) * g.lda + lk;
+  const float* wp = W + (size_t)min(n0 + lr, g.N - 1) * g.K + lk;
+  const int tm = (tid >> 4) * 4, tn = (tid & 15) * 4;
+  float acc[4][4] = {};
+  for (int k0 = 0; k0 < g.K; k0 += 16) {
+    const float4 va = *reinterpret_cast<const float4*>(ap + k0);
+    const float4 vw = *reinterpret_cast<const float4*>(wp + k0);
+    sA[lk + 0][lr] = va.x; sA[lk + 1][lr] = va.y; sA[lk + 2][lr] = va.z; sA[lk + 3][lr] = va.w;
+    sB[lk + 0][lr] = vw.x; sB[lk + 1][lr] = vw.y; sB[lk + 2][lr] = vw.z; sB[lk + 3][lr] = vw.w;
+    __syncthreads();
+#pragma unroll
+    for (int kk = 0; kk < 16; ++kk) {
+      float a[4], b[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) { a[i] = sA[kk][tm + i]; b[i] = sB[kk][tn + i]; }
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+    }
+    __syncthreads();
+  }
+  const float* bias = (const float*)g.bias;
+  const float* resid = (const float*)g.resid;
+  float* out = (float*)g.out;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int m = m0 + tm + i;
+    if (m >= M) continue;
+    const int64_t ro = map_row(g.o_rows, m, g.S) * g.ldo;
+    const int64_t rr = resid ? map_row(g.r_rows, m, g.S) * g.ldr : 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int n = n0 + tn + j;
+      if (n >= g.N) continue;
+      float v = apply_act(acc[i][j] + (bias ? bias[n] : 0.f), g.act);
+      if (resid) v += resid[rr + n];
+      out[ro + n] = v;
+    }
+  }
+}
+
+static llmc_status_t launch_gemm(const GemmArgs& g, int dtype, hipStream_t st) {
+  if (dtype == LLMC_BF16) {
+    const int tiles_n = (g.N + GemmCfg::BN - 1) / GemmCfg::BN;
+    const int tiles_m = (g.max_seqs * g.S + GemmCfg::BM - 1) / GemmCfg::BM;
+    hipLaunchKernelGGL(gemm_bf16_kernel, dim3((unsigned)tiles_m * tiles_n), dim3(GemmCfg::THREADS), 0, st, g, tiles_n);
+  } else {
+    const int tiles_n = (g.N + 63) / 64;
+    const int tiles_m = (g.max_seqs * g.S + 63) / 64;
+    hipLaunchKernelGGL(gemm_f32_kernel, dim3((unsigned)tiles_m * tiles_n), dim3(256), 0, st, g, tiles_n);
+  }
+  LLMC_LAUNCH_CHECK("gemm");
+  return LLMC_OK;
+}
+
+// ---- LayerNorm: one wavefront per token, two-pass statistics in fp32 -----------------------------
+template <typename T, int MAXV>
+__global__ __launch_bounds__(256) void layernorm_kernel(const T* __restrict__ in, int ld_in, const int32_t* in_rows,
+                                                        T* __restrict__ out, int ld_out, const int32_t* out_rows,
+                                                        const T* __restrict__ gamma, const T* __restrict__ beta,
+                                                        float eps, int d, int S, const int32_t* count, int max_seqs) {
+  constexpr int VEC = Vec16<T>::N;
+  const int n_seq = count ? min(*count, max_seqs) : max_seqs;
+  const int M = n_seq * S;
+  const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= M) return;
+  const int lane = threadIdx.x & 63;
+  const int nvec = d / VEC;
+  const T* src = in + map_row(in_rows, r, S) * ld_in;
+  float x[MAXV][VEC];
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < MAXV; ++i) {
+    const int v = lane + i * 64;
+    if (v < nvec) {
+      Vec16<T>::load(src + v * VEC, x[i]);
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) s += x[i][e];
+    }
+  }
+  const float mean = wave_sum(s) / (float)d;
+  float q = 0.f;
+#pragma unroll
+  for (int i = 0; i < MAXV; ++i) {
+    const int v = lane + i * 64;
+    if (v < nvec) {
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) {
+        const float c = x[i][e] - mean;
+        q += c * c;
+      }
+    }
+  }
+  const float rstd = 1.0f / sqrtf(wave_sum(q) / (float)d + eps);
+  T* dst = out + map_row(out_rows, r, S) * ld_out;
+#pragma unroll
+  for (int i = 0; i < MAXV; ++i) {
+    const int v = lane + i * 64;
+    if (v < nvec) {
+      float gv[VEC], bv[VEC], y[VEC];
+      Vec16<T>::load(gamma + v * VEC, gv);
+      Vec16<T>::load(beta + v * VEC, bv);
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) y[e] = (x[i][e] - mean) * rstd * gv[e] + bv[e];
+      Vec16<T>::store(dst + v * VEC, y);
+    }
+  }
+}
+
+template <typename T>
+static llmc_status_t launch_ln(const void* in, const int32_t* in_rows, void* out, const int32_t* out_rows,
+                               const void* gamma, const void* beta, float eps, int d, int S, const int32_t* count,
+                               int max_seqs, hipStream_t st) {
+  constexpr int VEC = Vec16<T>::N;
+  const int nvec = d / VEC;
+  const unsigned blocks = (unsigned)((max_seqs * S + 3) / 4);
+#define LN_CASE(MV)                                                                                          \
+  hipLaunchKernelGGL((layernorm_kernel<T, MV>), dim3(blocks), dim3(256), 0, st, (const T*)in, d, in_rows,  \
+                     (T*)out, d, out_rows, (const T*)gamma, (const T*)beta, eps, d, S, count, max_seqs)
+  if (nvec <= 64) LN_CASE(1);
+  else if (nvec <= 128) LN_CASE(2);
+  else if (nvec <= 256) LN_CASE(4);
+  else if (nvec <= 512) LN_CASE(8);
+  else return set_error(LLMC_ERR_SHAPE, "LayerNorm width %d too large", d);
+#undef LN_CASE
+  LLMC_LAUNCH_CHECK("layernorm");
+  return LLMC_OK;
+}
+
+// ---- attention: one thread per query row, online softmax over 32-key tiles ------------------------
+// qkv [T, 3d] compact; ctx [T, d] compact.  grid (ceil(S / 128), heads, max_seqs).
+template <typename T, bool CAUSAL>
+__global__ __launch_bounds__(128) void attention_kernel(const T* __restrict__ qkv, T* __restrict__ ctx, int S, int d,
+                                                        float scale, const int32_t* count, int max_seqs) {
+  constexpr int DH = 64, KT = 32, VEC = Vec16<T>::N;
+  __shared__ __attribute__((aligned(16))) float sK[KT][DH];
+  __shared__ __attribute__((aligned(16))) float sV[KT][DH];
+  const int n_seq = count ? min(*count, max_seqs) : max_seqs;
+  const int seq = blockIdx.z;
+  if (seq >= n_seq) return;
+  const int head = blockIdx.y;
+  const int q0 = blockIdx.x * 128;
+  const int qi = q0 + threadIdx.x;
+  const int qrow = min(qi, S - 1);
+  const size_t ld = 3 * (size_t)d;
+  const T* base = qkv + (size_t)seq * S * ld + head * DH;
+  float q[DH], o[DH];
+#pragma unroll
+  for (int c = 0; c < DH; c += VEC) Vec16<T>::load(base + (size_t)qrow * ld + c, &q[c]);
+#pragma unroll
+  for (int c = 0; c < DH; ++c) o[c] = 0.f;
+  float m = -INFINITY, l = 0.f;
+  const int kv_end = CAUSAL ? min(S, q0 + 128) : S;
+  for (int k0 = 0; k0 < kv_end; k0 += KT) {
+    __syncthreads();
+    for (int v = threadIdx.x; v < KT * DH / VEC; v += 128) {
+      const int j = v / (DH / VEC), c = (v % (DH / VEC)) * VEC;
+      const int kr = min(k0 + j, S - 1);
+      Vec16<T>::load(base + (size_t)kr * ld + d + c, &sK[j][c]);
+      Vec16<T>::load(base + (size_t)kr * ld + 2 * d + c, &sV[j][c]);
+    }
+    __syncthreads();
+    float s[KT];
+    float tmax = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < KT; ++j) {
+      float a = 0.f;
+#pragma unroll
+      for (int c = 0; c < DH; ++c) a = fmaf(q[c], sK[j][c], a);
+      a *= scale;
+      const int kv = k0 + j;
+      if (kv >= S || (CAUSAL && kv > qrow)) a = -INFINITY;
+      s[j] = a;
+      tmax = fmaxf(tmax, a);
+    }
+    const float m_new = fmaxf(m, tmax);
+    if (m_new == -INFINITY) continue;   // nothing visible yet in this tile (cannot happen for kv 0)
+    const float corr = __expf(m - m_new);
+    l *= corr;
+#pragma unroll
+    for (int c = 0; c < DH; ++c) o[c] *= corr;
+#pragma unroll
+    for (int j = 0; j < KT; ++j) {
+      const float p = __expf(s[j] - m_new);
+      l += p;
+#pragma unroll
+      for (int c = 0; c < DH; ++c) o[c] = fmaf(p, sV[j][c], o[c]);
+    }
+    m = m_new;
+  }
+  if (qi < S) {
+    const float inv = 1.0f / l;
+    T* dst = ctx + ((size_t)seq * S + qi) * d + head * DH;
+#pragma unroll
+    for (int c = 0; c < DH; c += VEC) {
+      float y[VEC];
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) y[e] = o[c + e] * inv;
+      Vec16<T>::store(dst + c, y);
+    }
+  }
+}
+
+template <typename T>
+static llmc_status_t launch_attention(const void* qkv, void* ctx, int S, int d, int n_heads, bool causal,
+                                      const int32_t* count, int max_seqs, hipStream_t st) {
+  const float scale = 1.0f / sqrtf((float)(d / n_heads));
+  dim3 grid((S + 127) / 128, n_heads, max_seqs);
+  if (causal)
+    hipLaunchKernelGGL((attention_kernel<T, true>), grid, dim3(128), 0, st, (const T*)qkv, (T*)ctx, S, d, scale, count,
+                       max_seqs);
+  else
+    hipLaunchKernelGGL((attention_kernel<T, false>), grid, dim3(128), 0, st, (const T*)qkv, (T*)ctx, S, d, scale,
+                       count, max_seqs);
+  LLMC_LAUNCH_CHECK("attention");
+  return LLMC_OK;
+}
+
+// ---- the block -----------------------------------------------------------------------------------
+size_t layer_ws_bytes(const llmc_layer_desc_t* L, int B, int S) {
+  const size_t T = (size_t)B * S, e = elem_size(L->dtype);
+  return align_up(T * 3 * L->d * e, 256) + 3 * align_up(T * L->d * e, 256) + align_up(T * L->d_ff * e, 256);
+}
+
+template <typename T>
+static llmc_status_t layer_t(const llmc_layer_desc_t* L, const void* h_in, void* h_out, int B, int S,
+                             const int32_t* rows, const int32_t* count, void* ws, hipStream_t st) {
+  const int d = L->d, dff = L->d_ff;
+  const size_t Tn = (size_t)B * S, e = sizeof(T);
+  char* p = (char*)ws;
+  void* qkv = p; p += align_up(Tn * 3 * d * e, 256);
+  void* ctx = p; p += align_up(Tn * d * e, 256);
+  void* t0 = p;  p += align_up(Tn * d * e, 256);
+  void* t1 = p;  p += align_up(Tn * d * e, 256);
+  void* ff = p;
+  const int act = L->gelu == 0 ? 1 : 2;
+  GemmArgs g{};
+  g.S = S; g.count = count; g.max_seqs = B;
+  auto gemm = [&](const void* A, int lda, const int32_t* a_rows, const void* W, const void* bias, int N, int K,
+                  int act_, const void* resid, const int32_t* r_rows, void* out, const int32_t* o_rows) {
+    GemmArgs a = g;
+    a.A = A; a.lda = lda; a.a_rows = a_rows; a.W = W; a.bias = bias; a.N = N; a.K = K; a.act = act_;
+    a.resid = resid; a.ldr = N; a.r_rows = r_rows; a.out = out; a.ldo = N; a.o_rows = o_rows;
+    return launch_gemm(a, L->dtype, st);
+  };
+  if (L->arch == 0) {
+    LLMC_TRY(gemm(h_in, d, rows, L->d_wqkv, L->d_bqkv, 3 * d, d, 0, nullptr, nullptr, qkv, nullptr));
+    LLMC_TRY(launch_attention<T>(qkv, ctx, S, d, L->n_heads, false, count, B, st));
+    LLMC_TRY(gemm(ctx, d, nullptr, L->d_wo, L->d_bo, d, d, 0, h_in, rows, t0, nullptr));
+    LLMC_TRY(launch_ln<T>(t0, nullptr, t1, nullptr, L->d_ln1_g, L->d_ln1_b, L->ln_eps, d, S, count, B, st));
+    LLMC_TRY(gemm(t1, d, nullptr, L->d_w1, L->d_b1, dff, d, act, nullptr, nullptr, ff, nullptr));
+    LLMC_TRY(gemm(ff, dff, nullptr, L->d_w2, L->d_b2, d, dff, 0, t1, nullptr, t0, nullptr));
+    LLMC_TRY(launch_ln<T>(t0, nullptr, h_out, rows, L->d_ln2_g, L->d_ln2_b, L->ln_eps, d, S, count, B, st));
+  } else {
+    LLMC_TRY(launch_ln<T>(h_in, rows, t1, nullptr, L->d_ln1_g, L->d_ln1_b, L->ln_eps, d, S, count, B, st));
+    LLMC_TRY(gemm(t1, d, nullptr, L->d_wqkv, L->d_bqkv, 3 * d, d, 0, nullptr, nullptr, qkv, nullptr));
+    LLMC_TRY(launch_attention<T>(qkv, ctx, S, d, L->n_heads, true, count, B, st));
+    LLMC_TRY(gemm(ctx, d, nullptr, L->d_wo, L->d_bo, d, d, 0, h_in, rows, t0, nullptr));
+    LLMC_TRY(launch_ln<T>(t0, nullptr, t1, nullptr, L->d_ln2_g, L->d_ln2_b, L->ln_eps, d, S, count, B, st));
+    LLMC_TRY(gemm(t1, d, nullptr, L->d_w1, L->d_b1, dff, d, act, nullptr, nullptr, ff, nullptr));
+    LLMC_TRY(gemm(ff, dff, nullptr, L->d_w2, L->d_b2, d, dff, 0, t0, nullptr, h_out, rows));
+  }
+  return LLMC_OK;
+}
+
+llmc_status_t launch_layer(const llmc_layer_desc_t* L, const void* d_h_in, void* d_h_out, int B, int S,
+                           const int32_t* d_rows, const int32_t* d_count, void* ws, hipStream_t st) {
+  if (L->dtype == LLMC_F32) return layer_t<float>(L, d_h_in, d_h_out, B, S, d_rows, d_count, ws, st);
+  return layer_t<bf16_t>(L, d_h_in, d_h_out, B, S, d_rows, d_count, ws, st);
+}
+
+}  // namespace llmc

@@ -1,0 +1,67 @@
+"""Harness around the C ABI: holds device weights, banks and buffers of an L-layer
+stack and calls ``llmc_layer_forward_gated`` once per layer (Algorithm 1's loop).
+
+Nothing is computed in Python: each layer is one library call that enqueues
+kernels on the current stream; hit/miss counts stay on the device.
+"""
+from __future__ import annotations
+
+from typing import List, Optional
+
+import torch
+
+from . import llmc
+from .workloads import ModelConfig
+
+
+class GatedStack:
+    def __init__(self, cfg: ModelConfig, weights, projections, device="cuda", cached_layers=None,
+                 biases: Optional[List[Optional[torch.Tensor]]] = None, n_bank: Optional[int] = None,
+                 policy: int = llmc.EVICT_LRU, B: Optional[int] = None):
+        self.cfg = cfg
+        self.device = device
+        self.B = cfg.B if B is None else B
+        self.layers = [llmc.layer_from_weights(cfg, w, device) for w in weights]
+        self.proj = [p.to(device).contiguous() for p in projections]
+        self.bias = [None if b is None else b.to(device).contiguous() for b in (biases or [None] * cfg.n_layers)]
+        n_bank = cfg.n_bank if n_bank is None else n_bank
+        cached = range(cfg.n_layers) if cached_layers is None else cached_layers
+        self.banks: List[Optional[llmc.Bank]] = [None] * cfg.n_layers
+        for l in cached:
+            self.banks[l] = llmc.Bank(n_bank, cfg.k, cfg.S, cfg.d, cfg.torch_dtype, device, policy=policy)
+        ws_bytes = llmc.llmc_layer_workspace_bytes(self.layers[0], self.B, cfg.S, cfg.k)
+        self.workspace = torch.empty((ws_bytes,), dtype=torch.uint8, device=device)
+        self.buf = [torch.empty((self.B, cfg.S, cfg.d), dtype=cfg.torch_dtype, device=device) for _ in range(2)]
+        self.gate = [llmc.GateBuffers(self.B, device) for _ in range(cfg.n_layers)]
+
+    def forward(self, h0: torch.Tensor, tau: float, flags: int = 0, tick: int = 0, keep_all: bool = False,
+                single_fingerprint: bool = False):
+        """Run all layers; returns h_L (a view of an internal buffer) or, with
+        ``keep_all``, the list [h_1 .. h_L] as fresh tensors."""
+        cfg = self.cfg
+        B = h0.shape[0]
+        assert B == self.B and h0.is_contiguous()
+        h = h0
+        outs = []
+        fp_given = inv_given = None
+        if single_fingerprint:
+            fp_given = torch.empty((B, cfg.k), dtype=cfg.torch_dtype, device=self.device)
+            inv_given = torch.empty((B,), dtype=torch.float32, device=self.device)
+            llmc.llmc_fingerprint(h0, self.proj[0], self.bias[0], fp_given, inv_given, self.workspace)
+        for l in range(cfg.n_layers):
+            out = torch.empty_like(h0) if keep_all else self.buf[l & 1]
+            llmc.llmc_layer_forward_gated(self.layers[l], self.banks[l], self.proj[l], self.bias[l], h, out, tau,
+                                          flags, tick, self.workspace, self.gate[l], fp_given, inv_given)
+            h = out
+            if keep_all:
+                outs.append(out)
+        return outs if keep_all else h
+
+    def hit_counts(self) -> torch.Tensor:
+        """[L, CNT_WORDS] device counters of the last forward (one host sync)."""
+        return torch.stack([g.counters for g in self.gate]).cpu()
+
+    def close(self):
+        for b in self.banks:
+            if b is not None:
+                b.close()

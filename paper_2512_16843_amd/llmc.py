@@ -1,0 +1,302 @@
+"""Thin ctypes binding over libllmc.so -- argument marshalling only.
+
+Every function has the name of the C entry point it calls (include/llmc.h) and
+passes torch tensors as raw device pointers.  Nothing is computed here; if the
+library is missing this module raises instead of falling back to anything.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Dict, Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libllmc.so")
+
+LLMC_OK = 0
+ERR_INVALID_ARG, ERR_SHAPE, ERR_DTYPE, ERR_BANK_FULL, ERR_WORKSPACE, ERR_HIP = 1, 2, 3, 4, 5, 6
+F32, BF16 = 0, 1
+EVICT_NONE, EVICT_LRU = 0, 1
+INSERT_ON_MISS, UPDATE_LRU = 1, 2
+CNT_HIT, CNT_MISS, CNT_NEAR_TAU, CNT_NEAR_TIE, CNT_INSERTED, CNT_EVICTED, CNT_DROPPED, CNT_WORDS = 0, 1, 2, 3, 4, 5, 6, 8
+MAX_UPDATE_ROWS = 4096
+
+EXPORTS = [
+    "llmc_bank_create", "llmc_bank_destroy", "llmc_bank_refresh", "llmc_bank_insert", "llmc_bank_evict",
+    "llmc_fingerprint", "llmc_fingerprint_workspace_bytes", "llmc_inv_norm", "llmc_match",
+    "llmc_match_workspace_bytes", "llmc_gather_hits", "llmc_layer_forward_gated",
+    "llmc_layer_workspace_bytes", "llmc_last_error", "llmc_version",
+]
+
+
+class BankDesc(C.Structure):
+    _fields_ = [("n_slots", C.c_int32), ("k", C.c_int32), ("S", C.c_int32), ("d", C.c_int32),
+                ("n_act_slots", C.c_int32), ("dtype", C.c_int32), ("policy", C.c_int32),
+                ("d_fp", C.c_void_p), ("d_act", C.c_void_p), ("d_inv_norm", C.c_void_p),
+                ("d_act_slot", C.c_void_p), ("d_last_used", C.c_void_p), ("d_hits", C.c_void_p),
+                ("d_valid", C.c_void_p)]
+
+
+class LayerDesc(C.Structure):
+    _fields_ = [("arch", C.c_int32), ("d", C.c_int32), ("n_heads", C.c_int32), ("d_ff", C.c_int32),
+                ("gelu", C.c_int32), ("ln_eps", C.c_float), ("dtype", C.c_int32),
+                ("d_wqkv", C.c_void_p), ("d_bqkv", C.c_void_p), ("d_wo", C.c_void_p), ("d_bo", C.c_void_p),
+                ("d_w1", C.c_void_p), ("d_b1", C.c_void_p), ("d_w2", C.c_void_p), ("d_b2", C.c_void_p),
+                ("d_ln1_g", C.c_void_p), ("d_ln1_b", C.c_void_p), ("d_ln2_g", C.c_void_p), ("d_ln2_b", C.c_void_p)]
+
+
+class FpDesc(C.Structure):
+    _fields_ = [("d_proj", C.c_void_p), ("d_bias", C.c_void_p), ("k", C.c_int32)]
+
+
+class GateOut(C.Structure):
+    _fields_ = [("d_idx", C.c_void_p), ("d_sim", C.c_void_p), ("d_hit", C.c_void_p),
+                ("d_counters", C.c_void_p), ("d_slots", C.c_void_p)]
+
+
+class LlmcError(RuntimeError):
+    def __init__(self, status: int, msg: str):
+        super().__init__("llmc status %d: %s" % (status, msg))
+        self.status = status
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Load libllmc.so (built in-tree by build.py); raises if it is not there."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("libllmc.so is not built: run `python -m paper_2512_16843_amd.build` "
+                               "(there is no fallback path)")
+        L = C.CDLL(LIB_PATH)
+        vp, i32, u32, u64, f32, sz, i64 = C.c_void_p, C.c_int32, C.c_uint32, C.c_uint64, C.c_float, C.c_size_t, C.c_int64
+        L.llmc_last_error.restype = C.c_char_p
+        L.llmc_version.restype = C.c_char_p
+        L.llmc_bank_create.argtypes = [C.POINTER(BankDesc), C.POINTER(vp)]
+        L.llmc_bank_destroy.argtypes = [vp]
+        L.llmc_bank_refresh.argtypes = [vp, vp]
+        L.llmc_bank_insert.argtypes = [vp, vp, vp, vp, vp, vp, i32, u64, vp, vp, vp]
+        L.llmc_bank_evict.argtypes = [vp, vp, i32, vp, vp]
+        L.llmc_fingerprint.argtypes = [vp, i32, i32, i32, i32, vp, vp, i32, vp, vp, vp, sz, vp]
+        L.llmc_fingerprint_workspace_bytes.argtypes = [i32, i32, i32]
+        L.llmc_fingerprint_workspace_bytes.restype = sz
+        L.llmc_inv_norm.argtypes = [vp, i64, i32, i32, vp, vp]
+        L.llmc_match.argtypes = [vp, vp, vp, i32, f32, vp, vp, vp, vp, vp, sz, vp]
+        L.llmc_match_workspace_bytes.argtypes = [vp, i32]
+        L.llmc_match_workspace_bytes.restype = sz
+        L.llmc_gather_hits.argtypes = [vp, vp, vp, vp, i32, vp, vp]
+        L.llmc_layer_forward_gated.argtypes = [C.POINTER(LayerDesc), vp, C.POINTER(FpDesc), vp, vp, i32, i32, f32,
+                                               u32, u64, vp, vp, C.POINTER(GateOut), vp, sz, vp]
+        L.llmc_layer_workspace_bytes.argtypes = [C.POINTER(LayerDesc), i32, i32, i32]
+        L.llmc_layer_workspace_bytes.restype = sz
+        for name in EXPORTS:
+            fn = getattr(L, name)
+            if fn.restype is C.c_int:
+                fn.restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def _check(st: int) -> None:
+    if st != LLMC_OK:
+        raise LlmcError(st, lib().llmc_last_error().decode())
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    if t is None:
+        return None
+    assert t.is_contiguous(), "llmc takes contiguous tensors"
+    return t.data_ptr()
+
+
+def _stream(stream: Optional[torch.cuda.Stream]) -> Optional[int]:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream or None
+
+
+def dtype_code(dt: torch.dtype) -> int:
+    if dt == torch.float32:
+        return F32
+    if dt == torch.bfloat16:
+        return BF16
+    raise LlmcError(ERR_DTYPE, "unsupported torch dtype %s" % dt)
+
+
+# ---------------------------------------------------------------------------
+# bank
+# ---------------------------------------------------------------------------
+
+class Bank:
+    """Device arrays of one layer's bank plus the library handle wrapping them."""
+
+    def __init__(self, n_slots: int, k: int, S: int, d: int, dtype: torch.dtype, device="cuda",
+                 n_act_slots: Optional[int] = None, policy: int = EVICT_LRU,
+                 act_slot: Optional[torch.Tensor] = None):
+        A = n_slots if n_act_slots is None else n_act_slots
+        self.n_slots, self.k, self.S, self.d, self.n_act_slots = n_slots, k, S, d, A
+        self.dtype = dtype
+        self.fp = torch.zeros((n_slots, k), dtype=dtype, device=device)
+        self.inv_norm = torch.zeros((n_slots,), dtype=torch.float32, device=device)
+        self.act = torch.zeros((A, S, d), dtype=dtype, device=device)
+        self.act_slot = act_slot
+        self.last_used = torch.zeros((n_slots,), dtype=torch.int64, device=device)   # uint64 bit pattern
+        self.hits = torch.zeros((n_slots,), dtype=torch.int32, device=device)        # uint32 bit pattern
+        self.valid = torch.zeros((n_slots,), dtype=torch.uint8, device=device)
+        self.policy = policy
+        self.handle = None
+        self.create()
+
+    def desc(self) -> BankDesc:
+        return BankDesc(self.n_slots, self.k, self.S, self.d, self.n_act_slots, dtype_code(self.dtype), self.policy,
+                        _ptr(self.fp), _ptr(self.act), _ptr(self.inv_norm), _ptr(self.act_slot),
+                        _ptr(self.last_used), _ptr(self.hits), _ptr(self.valid))
+
+    def create(self) -> None:
+        torch.cuda.synchronize()
+        self.handle = llmc_bank_create(self.desc())
+
+    def refresh(self, stream=None) -> None:
+        llmc_bank_refresh(self.handle, stream)
+
+    def close(self) -> None:
+        if self.handle is not None:
+            llmc_bank_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def llmc_bank_create(desc: BankDesc) -> int:
+    out = C.c_void_p()
+    _check(lib().llmc_bank_create(C.byref(desc), C.byref(out)))
+    return out.value
+
+
+def llmc_bank_destroy(handle: int) -> None:
+    _check(lib().llmc_bank_destroy(handle))
+
+
+def llmc_bank_refresh(handle: int, stream=None) -> None:
+    _check(lib().llmc_bank_refresh(handle, _stream(stream)))
+
+
+def llmc_bank_insert(bank: Bank, fp: torch.Tensor, inv_norm: torch.Tensor, act: torch.Tensor,
+                     rows: Optional[torch.Tensor], m: Optional[torch.Tensor], m_max: int, tick: int,
+                     slots_out: torch.Tensor, counters: Optional[torch.Tensor] = None, stream=None) -> None:
+    _check(lib().llmc_bank_insert(bank.handle, _ptr(fp), _ptr(inv_norm), _ptr(act), _ptr(rows), _ptr(m), m_max, tick,
+                                  _ptr(slots_out), _ptr(counters), _stream(stream)))
+
+
+def llmc_bank_evict(bank: Bank, m: Optional[torch.Tensor], m_max: int, victims_out: torch.Tensor, stream=None) -> None:
+    _check(lib().llmc_bank_evict(bank.handle, _ptr(m), m_max, _ptr(victims_out), _stream(stream)))
+
+
+# ---------------------------------------------------------------------------
+# fingerprint / match / gather
+# ---------------------------------------------------------------------------
+
+def llmc_fingerprint_workspace_bytes(B: int, S: int, d: int) -> int:
+    return lib().llmc_fingerprint_workspace_bytes(B, S, d)
+
+
+def llmc_fingerprint(h: torch.Tensor, proj: torch.Tensor, bias: Optional[torch.Tensor], fp_out: torch.Tensor,
+                     inv_norm_out: torch.Tensor, workspace: torch.Tensor, stream=None) -> None:
+    B, S, d = h.shape
+    _check(lib().llmc_fingerprint(_ptr(h), B, S, d, dtype_code(h.dtype), _ptr(proj), _ptr(bias), proj.shape[1],
+                                  _ptr(fp_out), _ptr(inv_norm_out), _ptr(workspace), workspace.numel(),
+                                  _stream(stream)))
+
+
+def llmc_inv_norm(fp: torch.Tensor, out: torch.Tensor, stream=None) -> None:
+    n, k = fp.shape
+    _check(lib().llmc_inv_norm(_ptr(fp), n, k, dtype_code(fp.dtype), _ptr(out), _stream(stream)))
+
+
+def llmc_match_workspace_bytes(bank: Bank, B: int) -> int:
+    return lib().llmc_match_workspace_bytes(bank.handle, B)
+
+
+def llmc_match(bank: Bank, fp: torch.Tensor, inv_norm: torch.Tensor, tau: float, idx: torch.Tensor,
+               sim: Optional[torch.Tensor], hit: Optional[torch.Tensor], near_tie: Optional[torch.Tensor],
+               workspace: torch.Tensor, stream=None) -> None:
+    _check(lib().llmc_match(bank.handle, _ptr(fp), _ptr(inv_norm), fp.shape[0], tau, _ptr(idx), _ptr(sim), _ptr(hit),
+                            _ptr(near_tie), _ptr(workspace), workspace.numel(), _stream(stream)))
+
+
+def llmc_gather_hits(bank: Bank, idx: torch.Tensor, rows: Optional[torch.Tensor], n: Optional[torch.Tensor],
+                     n_max: int, h_out: torch.Tensor, stream=None) -> None:
+    _check(lib().llmc_gather_hits(bank.handle, _ptr(idx), _ptr(rows), _ptr(n), n_max, _ptr(h_out), _stream(stream)))
+
+
+# ---------------------------------------------------------------------------
+# the gated layer
+# ---------------------------------------------------------------------------
+
+@dataclass
+class Layer:
+    """Device weights of one block and its descriptor."""
+    arch: int
+    d: int
+    n_heads: int
+    d_ff: int
+    gelu: int
+    ln_eps: float
+    dtype: torch.dtype
+    w: Dict[str, torch.Tensor]
+
+    def desc(self) -> LayerDesc:
+        w = self.w
+        return LayerDesc(self.arch, self.d, self.n_heads, self.d_ff, self.gelu, self.ln_eps, dtype_code(self.dtype),
+                         _ptr(w["wqkv"]), _ptr(w["bqkv"]), _ptr(w["wo"]), _ptr(w["bo"]), _ptr(w["w1"]), _ptr(w["b1"]),
+                         _ptr(w["w2"]), _ptr(w["b2"]), _ptr(w["ln1_g"]), _ptr(w["ln1_b"]), _ptr(w["ln2_g"]),
+                         _ptr(w["ln2_b"]))
+
+
+def llmc_layer_workspace_bytes(layer: Layer, B: int, S: int, k: int) -> int:
+    d = layer.desc()
+    return lib().llmc_layer_workspace_bytes(C.byref(d), B, S, k)
+
+
+class GateBuffers:
+    """Optional per-row outputs of the gate, allocated once per (B)."""
+
+    def __init__(self, B: int, device="cuda"):
+        self.idx = torch.empty((B,), dtype=torch.int32, device=device)
+        self.sim = torch.empty((B,), dtype=torch.float32, device=device)
+        self.hit = torch.empty((B,), dtype=torch.uint8, device=device)
+        self.counters = torch.zeros((CNT_WORDS,), dtype=torch.int32, device=device)
+        self.slots = torch.empty((B,), dtype=torch.int32, device=device)
+
+    def struct(self) -> GateOut:
+        return GateOut(_ptr(self.idx), _ptr(self.sim), _ptr(self.hit), _ptr(self.counters), _ptr(self.slots))
+
+
+def llmc_layer_forward_gated(layer: Layer, bank: Optional[Bank], proj: Optional[torch.Tensor],
+                             bias: Optional[torch.Tensor], h_in: torch.Tensor, h_out: torch.Tensor, tau: float,
+                             flags: int, tick: int, workspace: torch.Tensor, out: Optional[GateBuffers] = None,
+                             fp_given: Optional[torch.Tensor] = None, inv_norm_given: Optional[torch.Tensor] = None,
+                             stream=None) -> None:
+    B, S, _ = h_in.shape
+    ld = layer.desc()
+    fpd = FpDesc(_ptr(proj), _ptr(bias), proj.shape[1] if proj is not None else 0)
+    go = out.struct() if out is not None else None
+    _check(lib().llmc_layer_forward_gated(
+        C.byref(ld), bank.handle if bank is not None else None, C.byref(fpd), _ptr(h_in), _ptr(h_out), B, S, tau,
+        flags, tick, _ptr(fp_given), _ptr(inv_norm_given), C.byref(go) if go is not None else None,
+        _ptr(workspace), workspace.numel(), _stream(stream)))
+
+
+def layer_from_weights(cfg, w: Dict[str, torch.Tensor], device="cuda") -> Layer:
+    """Move one layer's weight dict (see workloads.make_layer_weights) to the device."""
+    return Layer(cfg.arch, cfg.d, cfg.n_heads, cfg.d_ff, cfg.gelu, cfg.ln_eps, cfg.torch_dtype,
+                 {k: v.to(device).contiguous() for k, v in w.items()})

@@ -1,0 +1,621 @@
+"""GPU parity: every step of the HIP path against the CPU oracle, through the C ABI.
+
+Bars (written out here): decisions and matched indices bit-exact except rows whose
+oracle similarity lies within 1e-3 of the threshold (counted); similarities within 1e-5;
+hit rows exact copies; computed rows within 1e-4 (fp32) / 2e-2 (bf16) relative, measured
+per sequence as max|gpu - oracle| / max|oracle|.
+"""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import llmc_oracle as O
+from paper_2512_16843_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+
+def say(msg):
+    print("[case] " + msg, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def L():
+    from paper_2512_16843_amd import llmc
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    llmc.lib()
+    return llmc
+
+
+def npf(t):
+    return t.detach().float().cpu().numpy()
+
+
+def f32(x):
+    return float(np.float32(x))
+
+
+def rel_err_rows(got, want):
+    got = np.asarray(got, dtype=np.float64).reshape(got.shape[0], -1)
+    want = np.asarray(want, dtype=np.float64).reshape(want.shape[0], -1)
+    return np.abs(got - want).max(axis=1) / np.maximum(np.abs(want).max(axis=1), 1e-30)
+
+
+def oracle_bank_from_gpu(bank, dtype):
+    ob = O.Bank(bank.n_slots, bank.k, bank.S, bank.d, dtype, n_act_slots=bank.n_act_slots)
+    ob.fp = npf(bank.fp)
+    ob.inv_norm = npf(bank.inv_norm)
+    ob.act = npf(bank.act)
+    if bank.act_slot is not None:
+        ob.act_slot = bank.act_slot.cpu().numpy()
+    ob.last_used = bank.last_used.cpu().numpy().astype(np.uint64)
+    ob.hits = bank.hits.cpu().numpy().astype(np.uint32)
+    ob.valid = bank.valid.cpu().numpy()
+    return ob
+
+
+# ---------------------------------------------------------------------------
+# step 1: fingerprint
+# ---------------------------------------------------------------------------
+
+def run_fingerprint(L, h, P, bias):
+    B, S, d = h.shape
+    k = P.shape[1]
+    fp = torch.empty((B, k), dtype=h.dtype, device="cuda")
+    inv = torch.empty((B,), dtype=torch.float32, device="cuda")
+    ws = torch.empty((L.llmc_fingerprint_workspace_bytes(B, S, d),), dtype=torch.uint8, device="cuda")
+    L.llmc_fingerprint(h, P, bias, fp, inv, ws)
+    torch.cuda.synchronize()
+    return fp, inv
+
+
+@pytest.mark.parametrize("dtype,B,S,d,k,use_bias", [
+    ("f32", 8, 32, 128, 64, False),      # tiny-encoder shape
+    ("f32", 3, 1, 64, 32, True),         # S = 1
+    ("bf16", 5, 33, 768, 256, True),     # ragged token chunk
+    ("bf16", 7, 384, 768, 256, False),   # BERT-base row shape, several chunks
+    ("bf16", 4, 1024, 768, 256, False),  # GPT-2 row shape
+    ("bf16", 9, 128, 1024, 256, False),  # BERT-large row shape
+])
+def test_fingerprint_matches_oracle(L, dtype, B, S, d, k, use_bias):
+    say(f"fingerprint {dtype} B={B} S={S} d={d} k={k} bias={use_bias}")
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    g = np.random.Generator(np.random.PCG64(B * 1000 + S))
+    h = torch.from_numpy(g.standard_normal((B, S, d)).astype(np.float32) + 0.3).to(tdt).cuda()
+    P = W.make_projection(d, k, tdt, seed=3)[0].cuda()
+    bias = torch.from_numpy(g.standard_normal(k).astype(np.float32) * 0.1).cuda() if use_bias else None
+    fp, inv = run_fingerprint(L, h, P, bias)
+    q, qinv = O.fingerprint(npf(h), npf(P), None if bias is None else npf(bias), dtype)
+    got = npf(fp)
+    if dtype == "f32":
+        np.testing.assert_allclose(got, q, rtol=0, atol=2e-6)
+    else:
+        # the key is a quantised code decided after an fp32 (device) / fp64 (oracle) sum: codes agree
+        # except where the value sits on a rounding boundary, and then they differ by one bf16 step
+        diff = got != q
+        assert diff.mean() < 5e-3, diff.mean()
+        step = np.maximum(np.abs(q), 2.0 ** -126) * 2.0 ** -7
+        assert np.all(np.abs(got - q)[diff] <= step[diff])
+    # the stored inverse norm is that of the key the device actually stored
+    np.testing.assert_allclose(npf(inv), O.inv_norm(got), rtol=3e-7, atol=0)
+    np.testing.assert_allclose(npf(inv), qinv, rtol=1e-4)
+
+
+def test_fingerprint_is_position_and_batch_independent(L):
+    say("fingerprint determinism across batch position and size")
+    g = np.random.Generator(np.random.PCG64(77))
+    h = torch.from_numpy(g.standard_normal((12, 384, 768)).astype(np.float32)).to(torch.bfloat16).cuda()
+    P = W.make_projection(768, 256, torch.bfloat16, seed=3)[0].cuda()
+    fp_a, inv_a = run_fingerprint(L, h, P, None)
+    perm = torch.from_numpy(g.permutation(12)).cuda()
+    fp_b, inv_b = run_fingerprint(L, h[perm].contiguous(), P, None)
+    assert torch.equal(fp_a[perm], fp_b) and torch.equal(inv_a[perm], inv_b)
+    fp_c, inv_c = run_fingerprint(L, h[3:4].contiguous(), P, None)
+    assert torch.equal(fp_c[0], fp_a[3]) and torch.equal(inv_c[0], inv_a[3])
+
+
+def test_fingerprint_zero_input(L):
+    say("fingerprint of an all-zero sequence")
+    h = torch.zeros((2, 5, 128), dtype=torch.float32, device="cuda")
+    P = W.make_projection(128, 64, torch.float32, seed=3)[0].cuda()
+    fp, inv = run_fingerprint(L, h, P, None)
+    assert torch.all(fp == 0) and torch.all(inv == 0)
+
+
+def test_inv_norm(L):
+    say("inv_norm")
+    g = np.random.Generator(np.random.PCG64(5))
+    x = torch.from_numpy(g.standard_normal((1001, 256)).astype(np.float32)).to(torch.bfloat16).cuda()
+    x[17] = 0
+    out = torch.empty((1001,), dtype=torch.float32, device="cuda")
+    L.llmc_inv_norm(x, out)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(npf(out), O.inv_norm(npf(x)))
+
+
+# ---------------------------------------------------------------------------
+# steps 2-3: match + threshold
+# ---------------------------------------------------------------------------
+
+def make_bank(L, keys, valid=None, S=1, d=64, dtype=torch.bfloat16, policy=None, act=None, act_slot=None, A=None):
+    N, k = keys.shape
+    bank = L.Bank(N, k, S, d, dtype, "cuda", n_act_slots=A, policy=L.EVICT_LRU if policy is None else policy,
+                  act_slot=act_slot)
+    bank.fp.copy_(keys)
+    L.llmc_inv_norm(bank.fp, bank.inv_norm)
+    bank.valid.copy_(torch.ones(N, dtype=torch.uint8) if valid is None else valid)
+    if act is not None:
+        bank.act.copy_(act)
+    bank.refresh()
+    torch.cuda.synchronize()
+    return bank
+
+
+def run_match(L, bank, q, qinv, tau):
+    B = q.shape[0]
+    idx = torch.empty((B,), dtype=torch.int32, device="cuda")
+    sim = torch.empty((B,), dtype=torch.float32, device="cuda")
+    hit = torch.empty((B,), dtype=torch.uint8, device="cuda")
+    tie = torch.empty((B,), dtype=torch.uint8, device="cuda")
+    ws = torch.empty((L.llmc_match_workspace_bytes(bank, B),), dtype=torch.uint8, device="cuda")
+    L.llmc_match(bank, q, qinv, tau, idx, sim, hit, tie, ws)
+    torch.cuda.synchronize()
+    return idx.cpu().numpy(), npf(sim), hit.cpu().numpy().astype(bool), tie.cpu().numpy().astype(bool)
+
+
+def check_match(L, bank, q, tau, dtype):
+    qinv = torch.empty((q.shape[0],), dtype=torch.float32, device="cuda")
+    L.llmc_inv_norm(q, qinv)
+    idx, sim, hit, tie = run_match(L, bank, q, qinv, tau)
+    ob = oracle_bank_from_gpu(bank, dtype)
+    oidx, osim = O.match(npf(q), npf(qinv), ob.fp, ob.inv_norm, ob.valid)
+    ohit = O.threshold(osim, f32(tau))
+    near_tau = np.abs(osim - f32(tau)) < 1e-3
+    assert np.array_equal(idx, oidx), (np.nonzero(idx != oidx)[0][:10], idx[idx != oidx][:10], oidx[idx != oidx][:10])
+    fin = np.isfinite(osim)
+    np.testing.assert_allclose(sim[fin], osim[fin], rtol=0, atol=1e-5)
+    assert np.all(np.isneginf(sim[~fin]))
+    assert np.array_equal(hit[~near_tau], ohit[~near_tau])
+    return dict(idx=idx, sim=sim, hit=hit, tie=tie, near_tau=int(near_tau.sum()), oracle_sim=osim)
+
+
+def unit_rows(g, n, k):
+    x = g.standard_normal((n, k))
+    return x / np.linalg.norm(x, axis=1, keepdims=True)
+
+
+@pytest.mark.parametrize("N,B,k", [(1000, 37, 64), (130, 5, 256), (4096, 200, 256), (64, 1, 32)])
+def test_match_bf16_random_bank_with_holes(L, N, B, k):
+    say(f"match bf16 random N={N} B={B} k={k}")
+    g = np.random.Generator(np.random.PCG64(N + B))
+    keys = torch.from_numpy(unit_rows(g, N, k).astype(np.float32)).to(torch.bfloat16).cuda()
+    valid = torch.from_numpy((g.random(N) > 0.15).astype(np.uint8))
+    bank = make_bank(L, keys, valid)
+    qn = unit_rows(g, B, k)
+    # a third of the queries are noisy copies of bank keys (some of them of FREE slots)
+    for b in range(0, B, 3):
+        j = int(g.integers(0, N))
+        qn[b] = npf(keys[j]) + 0.05 * g.standard_normal(k) / np.sqrt(k)
+    q = torch.from_numpy(qn.astype(np.float32)).to(torch.bfloat16).cuda()
+    r = check_match(L, bank, q, 0.9, "bf16")
+    assert np.all(valid.numpy()[r["idx"]] == 1)
+    bank.close()
+
+
+def test_match_duplicates_self_and_negative_best(L):
+    say("match bf16 duplicates across tiles / self hit / all-negative similarities")
+    g = np.random.Generator(np.random.PCG64(3))
+    N, k = 700, 128
+    kn = unit_rows(g, N, k).astype(np.float32)
+    keys = torch.from_numpy(kn).to(torch.bfloat16)
+    keys[650] = keys[20]
+    keys[333] = keys[20]
+    keys[334] = keys[200]
+    bank = make_bank(L, keys.cuda())
+    q = torch.stack([keys[650], keys[334], keys[5], -keys[7]]).cuda()
+    r = check_match(L, bank, q, 0.95, "bf16")
+    assert r["idx"].tolist()[:3] == [20, 200, 5]
+    np.testing.assert_allclose(r["sim"][:3], 1.0, atol=1e-6)
+    assert r["hit"].tolist()[:3] == [True, True, True] and r["tie"][0] and r["tie"][1]
+    # with only one key left valid, the best similarity of -key is negative, and it is still reported
+    v = torch.zeros(N, dtype=torch.uint8)
+    v[7] = 1
+    bank.valid.copy_(v)
+    bank.refresh()
+    r = check_match(L, bank, q[3:4].contiguous(), 0.0, "bf16")
+    assert r["idx"][0] == 7 and r["sim"][0] < -0.99 and not r["hit"][0]
+    bank.close()
+
+
+def test_match_empty_bank_and_zero_query(L):
+    say("match: empty bank, zero query")
+    g = np.random.Generator(np.random.PCG64(4))
+    keys = torch.from_numpy(unit_rows(g, 256, 64).astype(np.float32)).to(torch.bfloat16).cuda()
+    bank = make_bank(L, keys, torch.zeros(256, dtype=torch.uint8))
+    q = keys[:3].contiguous()
+    r = check_match(L, bank, q, -2.0, "bf16")
+    assert np.all(r["idx"] == -1) and not r["hit"].any()
+    v = torch.ones(256, dtype=torch.uint8)
+    v[:9] = 0
+    bank.valid.copy_(v)
+    bank.refresh()
+    z = torch.zeros((1, 64), dtype=torch.bfloat16, device="cuda")
+    r = check_match(L, bank, z, 0.0, "bf16")
+    assert r["idx"][0] == 9 and r["sim"][0] == 0 and not r["hit"][0]      # first valid slot, similarity 0, 0 > 0 false
+    bank.close()
+
+
+def test_match_f32(L):
+    say("match f32 N=256 k=64 (tiny-encoder bank shape)")
+    g = np.random.Generator(np.random.PCG64(6))
+    keys = torch.from_numpy(unit_rows(g, 256, 64).astype(np.float32)).cuda()
+    valid = torch.from_numpy((g.random(256) > 0.1).astype(np.uint8))
+    bank = make_bank(L, keys, valid, dtype=torch.float32)
+    qn = unit_rows(g, 8, 64)
+    qn[0] = npf(keys[100]) + 0.01 * g.standard_normal(64)
+    qn[1] = npf(keys[3])
+    q = torch.from_numpy(qn.astype(np.float32)).cuda()
+    r = check_match(L, bank, q, 0.95, "f32")
+    bank.close()
+
+
+def test_match_clustered_bank_scaled_stress(L):
+    say("match bf16 clustered bank 128 clusters x 256, 1024 queries (scaled copy of the stress config)")
+    data = W.make_clustered_bank(128, 256, 256, 0.05, 1024, seed=5)
+    bank = make_bank(L, data["bank"].cuda())
+    q = data["queries"].cuda()
+    r = check_match(L, bank, q, 0.95, "bf16")
+    inside = data["q_cluster"].numpy() >= 0
+    cl = data["cluster"].numpy()
+    assert np.array_equal(cl[r["idx"][inside]], data["q_cluster"].numpy()[inside])
+    assert r["hit"][inside].mean() > 0.99 and r["hit"][~inside].mean() < 0.01
+    say(f"  hit rate {r['hit'].mean():.3f}, near-tie rows {int(r['tie'].sum())}, near-tau rows {r['near_tau']}")
+    bank.close()
+
+
+# ---------------------------------------------------------------------------
+# step 4: gather
+# ---------------------------------------------------------------------------
+
+def test_gather_hits_is_exact_copy_with_shared_value_rows(L):
+    say("gather with an act_slot map")
+    g = np.random.Generator(np.random.PCG64(8))
+    N, A, S, d = 64, 8, 33, 128
+    keys = torch.from_numpy(unit_rows(g, N, 32).astype(np.float32)).to(torch.bfloat16).cuda()
+    act = torch.from_numpy(g.standard_normal((A, S, d)).astype(np.float32)).to(torch.bfloat16).cuda()
+    act_slot = torch.from_numpy((np.arange(N) % A).astype(np.int32)).cuda()
+    bank = make_bank(L, keys, S=S, d=d, act=act, act_slot=act_slot, A=A)
+    B = 10
+    idx = torch.from_numpy(g.integers(0, N, B).astype(np.int32)).cuda()
+    rows = torch.tensor([0, 2, 3, 7, 9, 1, 1, 1, 1, 1], dtype=torch.int32, device="cuda")
+    n = torch.tensor([5], dtype=torch.int32, device="cuda")
+    out = torch.full((B, S, d), -7.0, dtype=torch.bfloat16, device="cuda")
+    L.llmc_gather_hits(bank, idx, rows, n, B, out)
+    torch.cuda.synchronize()
+    for b in range(B):
+        if b in (0, 2, 3, 7, 9):
+            assert torch.equal(out[b], act[int(idx[b]) % A])
+        else:
+            assert torch.all(out[b] == -7.0)
+    bank.close()
+
+
+# ---------------------------------------------------------------------------
+# step 5: the block f_l on its own (uncached layer)
+# ---------------------------------------------------------------------------
+
+def small_cfg(arch, dtype, d=128, heads=2, dff=256, S=33, B=5, **kw):
+    return W.scaled(W.TINY_ENCODER, arch=arch, dtype=dtype, d=d, n_heads=heads, d_ff=dff, S=S, B=B, n_layers=1,
+                    gelu=O.GELU_ERF if arch == 0 else O.GELU_TANH, ln_eps=1e-12 if arch == 0 else 1e-5, **kw)
+
+
+@pytest.mark.parametrize("arch", [0, 1])
+@pytest.mark.parametrize("dtype,d,heads,dff,S,B", [
+    ("f32", 128, 2, 512, 32, 8),
+    ("f32", 64, 1, 64, 7, 3),
+    ("bf16", 128, 2, 256, 33, 5),      # 165 tokens: ragged against the 128-row tile
+    ("bf16", 768, 12, 3072, 130, 2),   # model-sized widths, several k steps, S past one query block
+])
+def test_uncached_layer_matches_oracle(L, arch, dtype, d, heads, dff, S, B):
+    say(f"plain layer arch={arch} {dtype} d={d} heads={heads} dff={dff} S={S} B={B}")
+    from paper_2512_16843_amd.engine import GatedStack
+    cfg = small_cfg(arch, dtype, d, heads, dff, S, B)
+    ws = W.make_layer_weights(cfg, seed=11)
+    g = np.random.Generator(np.random.PCG64(S))
+    h0 = torch.from_numpy(g.standard_normal((B, S, d)).astype(np.float32)).to(cfg.torch_dtype).cuda()
+    st = GatedStack(cfg, ws, W.make_projection(d, cfg.k, cfg.torch_dtype), cached_layers=[])
+    out = st.forward(h0, tau=0.5)
+    torch.cuda.synchronize()
+    wnp = {k: npf(v) for k, v in ws[0].items()}
+    want = np.stack([O.layer_forward(npf(h0[b]), wnp, arch, heads, cfg.ln_eps, cfg.gelu) for b in range(B)])
+    err = rel_err_rows(npf(out), want)
+    say(f"  max rel err {err.max():.3e}")
+    assert err.max() < TOL[dtype]
+    cnt = st.hit_counts()
+    assert cnt[0, L.CNT_MISS] == B and cnt[0, L.CNT_HIT] == 0
+
+
+# ---------------------------------------------------------------------------
+# the gated stack, free-running in fp32 (tiny-encoder config, whole run incl. bank build)
+# ---------------------------------------------------------------------------
+
+def build_banks_gpu(L, st, h_src, tick=1):
+    """All-miss pass with insertion over the source sequences, batch by batch."""
+    Bn = st.B
+    outs = []
+    for s in range(0, h_src.shape[0], Bn):
+        outs.append([o.clone() for o in st.forward(h_src[s:s + Bn].contiguous(), tau=2.0,
+                                                   flags=L.INSERT_ON_MISS, tick=tick, keep_all=True)])
+    torch.cuda.synchronize()
+    return outs
+
+
+def test_tiny_encoder_free_running_with_bank_build(L):
+    say("tiny encoder fp32: bank build + gated queries, free running")
+    from paper_2512_16843_amd.engine import GatedStack
+    cfg = W.TINY_ENCODER
+    ws = W.make_layer_weights(cfg, seed=0)
+    tok, pos = W.make_embeddings(cfg, seed=0)
+    Ps = W.make_projection(cfg.d, cfg.k, torch.float32, seed=3, n_layers=cfg.n_layers)
+    src = W.make_sources(cfg, cfg.n_bank, seed=1)
+    h_src = W.embed(torch.from_numpy(src), tok, pos, torch.float32)
+    st = GatedStack(cfg, ws, Ps)
+    build_banks_gpu(L, st, h_src.cuda())
+    # oracle builds its own banks from the same inputs
+    wnp = [{k: npf(v) for k, v in w.items()} for w in ws]
+    Pnp = [npf(p) for p in Ps]
+    obanks = [O.Bank(cfg.n_bank, cfg.k, cfg.S, cfg.d, "f32") for _ in range(cfg.n_layers)]
+    for s in range(0, cfg.n_bank, cfg.B):
+        O.infer(h_src[s:s + cfg.B].numpy(), obanks, Pnp, [None] * cfg.n_layers, wnp, cfg.arch, cfg.n_heads,
+                cfg.ln_eps, cfg.gelu, tau=2.0, flags=O.FLAG_INSERT_ON_MISS, tick=1)
+    for l in range(cfg.n_layers):
+        b = st.banks[l]
+        assert torch.all(b.valid == 1)
+        np.testing.assert_allclose(npf(b.fp), obanks[l].fp, atol=3e-6)
+        assert rel_err_rows(npf(b.act), obanks[l].act).max() < TOL["f32"]
+        assert torch.all(b.last_used == 1) and torch.all(b.hits == 0)
+    # queries: half near-duplicates (1-2 substitutions), half fresh
+    ids, srcmap = W.make_substitution_queries(cfg, src, n_dup=cfg.B // 2, n_subst=(1, 2), seed=2)
+    h0 = W.embed(torch.from_numpy(ids), tok, pos, torch.float32)
+    tau = 0.95
+    outs = st.forward(h0.cuda(), tau=tau, keep_all=True)
+    torch.cuda.synchronize()
+    _, res = O.infer(h0.numpy(), obanks, Pnp, [None] * cfg.n_layers, wnp, cfg.arch, cfg.n_heads, cfg.ln_eps,
+                     cfg.gelu, tau=f32(tau))
+    n_near = 0
+    for l in range(cfg.n_layers):
+        g = st.gate[l]
+        r = res[l]
+        near = np.abs(r.sim - f32(tau)) < 1e-3
+        n_near += int(near.sum())
+        hit = g.hit.cpu().numpy().astype(bool)
+        assert np.array_equal(hit[~near], r.hit[~near])
+        assert np.array_equal(g.idx.cpu().numpy()[~near], r.idx[~near])
+        np.testing.assert_allclose(npf(g.sim), r.sim, atol=1e-5)
+        ok = ~near
+        err = rel_err_rows(npf(outs[l])[ok], r.h_out[ok])
+        assert err.max() < TOL["f32"], err
+        cnt = st.hit_counts()[l]
+        assert cnt[L.CNT_HIT] == hit.sum() and cnt[L.CNT_MISS] == cfg.B - hit.sum()
+        say(f"  layer {l}: hits {int(hit.sum())}/{cfg.B}, near-threshold rows {int(near.sum())}, max err {err.max():.2e}")
+        if near.any():
+            break       # a row excused at this layer may legitimately diverge afterwards
+    st.close()
+
+
+def test_gated_invariants_on_gpu(L):
+    say("tau > 1 equals the uncached path bit for bit; resubmitted sources hit at 1 with stored values")
+    from paper_2512_16843_amd.engine import GatedStack
+    cfg = W.scaled(W.TINY_ENCODER, n_bank=64)
+    ws = W.make_layer_weights(cfg, seed=0)
+    tok, pos = W.make_embeddings(cfg, seed=0)
+    Ps = W.make_projection(cfg.d, cfg.k, torch.float32, seed=3, n_layers=cfg.n_layers)
+    src = W.make_sources(cfg, 64, seed=1)
+    h_src = W.embed(torch.from_numpy(src), tok, pos, torch.float32).cuda()
+    st = GatedStack(cfg, ws, Ps)
+    build_banks_gpu(L, st, h_src)
+    plain = GatedStack(cfg, ws, Ps, cached_layers=[])
+    ids, _ = W.make_substitution_queries(cfg, src, n_dup=4, n_subst=1, seed=9)
+    h0 = W.embed(torch.from_numpy(ids), tok, pos, torch.float32).cuda()
+    a = st.forward(h0, tau=1.0 + 1e-3).clone()
+    b = plain.forward(h0, tau=0.0).clone()
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)
+    assert st.hit_counts()[:, L.CNT_HIT].sum() == 0
+    outs = st.forward(h_src[8:16].contiguous(), tau=0.95, keep_all=True)
+    torch.cuda.synchronize()
+    for l in range(cfg.n_layers):
+        assert torch.all(st.gate[l].hit == 1)
+        assert st.gate[l].idx.cpu().tolist() == list(range(8, 16))
+        np.testing.assert_allclose(npf(st.gate[l].sim), 1.0, atol=1e-6)
+        assert torch.equal(outs[l], st.banks[l].act[8:16])
+    # a permuted, smaller batch gives the same rows bit for bit (row independence)
+    small = GatedStack(cfg, ws, Ps, cached_layers=[], B=3)
+    c = small.forward(h0[[5, 0, 2]].contiguous(), tau=0.0)
+    torch.cuda.synchronize()
+    assert torch.equal(c, b[[5, 0, 2]])
+    st.close(); plain.close(); small.close()
+
+
+# ---------------------------------------------------------------------------
+# step 6: insertion and LRU
+# ---------------------------------------------------------------------------
+
+def test_bank_insert_and_evict_direct(L):
+    say("bank insert / evict against the oracle bank, device-side counts")
+    g = np.random.Generator(np.random.PCG64(12))
+    N, k, S, d = 40, 32, 3, 64
+    bank = L.Bank(N, k, S, d, torch.bfloat16, "cuda")
+    ob = O.Bank(N, k, S, d, "bf16")
+    counters = torch.zeros((L.CNT_WORDS,), dtype=torch.int32, device="cuda")
+    for tick in range(1, 12):
+        mmax = 16
+        m = int(g.integers(0, mmax + 1))
+        keys = torch.from_numpy(unit_rows(g, mmax, k).astype(np.float32)).to(torch.bfloat16).cuda()
+        inv = torch.empty((mmax,), dtype=torch.float32, device="cuda")
+        L.llmc_inv_norm(keys, inv)
+        acts = torch.from_numpy(g.standard_normal((mmax, S, d)).astype(np.float32)).to(torch.bfloat16).cuda()
+        rows = torch.from_numpy(g.permutation(mmax).astype(np.int32)).cuda()
+        dm = torch.tensor([m], dtype=torch.int32, device="cuda")
+        slots = torch.full((mmax,), -5, dtype=torch.int32, device="cuda")
+        L.llmc_bank_insert(bank, keys, inv, acts, rows, dm, mmax, tick, slots, counters)
+        # touch a few random valid entries (what a hit does), same on both sides
+        torch.cuda.synchronize()
+        r = rows.cpu().numpy()[:m]
+        oslots, _ = ob.insert(npf(keys)[r], npf(inv)[r], npf(acts)[r], tick)
+        assert slots.cpu().tolist() == oslots + [-1] * (mmax - m)
+        live = np.nonzero(ob.valid)[0]
+        touched = g.choice(live, size=min(3, len(live)), replace=False)
+        ob.touch(touched.tolist(), tick + 100)
+        bank.last_used[torch.from_numpy(touched).cuda()] = tick + 100
+        bank.hits[torch.from_numpy(touched).cuda()] += 1
+        if tick % 4 == 0:
+            vm = int(g.integers(1, 6))
+            vic = torch.empty((8,), dtype=torch.int32, device="cuda")
+            L.llmc_bank_evict(bank, torch.tensor([vm], dtype=torch.int32, device="cuda"), 8, vic)
+            torch.cuda.synchronize()
+            assert vic.cpu().tolist() == ob.evict(vm) + [-1] * (8 - vm)
+        torch.cuda.synchronize()
+        assert np.array_equal(bank.valid.cpu().numpy(), ob.valid)
+        v = ob.valid.astype(bool)
+        assert np.array_equal(bank.last_used.cpu().numpy().astype(np.uint64)[v], ob.last_used[v])
+        assert np.array_equal(bank.hits.cpu().numpy().astype(np.uint32)[v], ob.hits[v])
+        assert np.array_equal(npf(bank.fp)[v], ob.fp[v])
+        assert np.array_equal(npf(bank.act)[v], ob.act[v])
+        assert np.array_equal(npf(bank.inv_norm)[v], ob.inv_norm[v])
+    assert int(counters[L.CNT_EVICTED]) > 0 and int(counters[L.CNT_INSERTED]) > N
+    bank.close()
+
+
+def test_insert_without_eviction_drops_and_counts(L):
+    say("insert into a full bank with policy NONE")
+    g = np.random.Generator(np.random.PCG64(13))
+    bank = L.Bank(6, 32, 1, 64, torch.float32, "cuda", policy=L.EVICT_NONE)
+    keys = torch.from_numpy(unit_rows(g, 8, 32).astype(np.float32)).cuda()
+    inv = torch.empty((8,), dtype=torch.float32, device="cuda")
+    L.llmc_inv_norm(keys, inv)
+    acts = torch.zeros((8, 1, 64), dtype=torch.float32, device="cuda")
+    slots = torch.empty((8,), dtype=torch.int32, device="cuda")
+    counters = torch.zeros((L.CNT_WORDS,), dtype=torch.int32, device="cuda")
+    L.llmc_bank_insert(bank, keys, inv, acts, None, None, 8, 1, slots, counters)
+    torch.cuda.synchronize()
+    assert slots.cpu().tolist() == [0, 1, 2, 3, 4, 5, -1, -1]
+    assert int(counters[L.CNT_INSERTED]) == 6 and int(counters[L.CNT_DROPPED]) == 2 and int(counters[L.CNT_EVICTED]) == 0
+    bank.close()
+
+
+def test_gated_stream_with_insertion_and_lru_eviction(L):
+    say("stream of batches with INSERT_ON_MISS | UPDATE_LRU on a small bank (eviction fires), fp32")
+    from paper_2512_16843_amd.engine import GatedStack
+    cfg = W.scaled(W.TINY_ENCODER, n_layers=1, n_bank=20, B=8)
+    ws = W.make_layer_weights(cfg, seed=0)
+    tok, pos = W.make_embeddings(cfg, seed=0)
+    Ps = W.make_projection(cfg.d, cfg.k, torch.float32, seed=3, n_layers=1)
+    pool = W.make_sources(cfg, 30, seed=1)
+    st = GatedStack(cfg, ws, Ps)
+    wnp = [{k: npf(v) for k, v in w.items()} for w in ws]
+    ob = O.Bank(cfg.n_bank, cfg.k, cfg.S, cfg.d, "f32")
+    g = np.random.Generator(np.random.PCG64(21))
+    flags = L.INSERT_ON_MISS | L.UPDATE_LRU
+    tau = 0.999
+    total_evicted = 0
+    for tick in range(1, 13):
+        # recurring sequences from a pool of 30: exact repeats hit, others miss and insert
+        pick = g.integers(0, 30, cfg.B)
+        h0 = W.embed(torch.from_numpy(pool[pick]), tok, pos, torch.float32)
+        out = st.forward(h0.cuda(), tau=tau, flags=flags, tick=tick).clone()
+        torch.cuda.synchronize()
+        r = O.gated_layer(h0.numpy(), ob, npf(Ps[0]), None, wnp[0], cfg.arch, cfg.n_heads, cfg.ln_eps, cfg.gelu,
+                          f32(tau), flags=O.FLAG_INSERT_ON_MISS | O.FLAG_UPDATE_LRU, tick=tick, out_dtype="f32")
+        gt = st.gate[0]
+        assert np.array_equal(gt.hit.cpu().numpy().astype(bool), r.hit)
+        assert np.array_equal(gt.idx.cpu().numpy(), r.idx)
+        n_miss = int((~r.hit).sum())
+        assert gt.slots.cpu().tolist()[:n_miss] == r.slots
+        cnt = st.hit_counts()[0]
+        assert cnt[L.CNT_INSERTED] == n_miss and cnt[L.CNT_EVICTED] == r.n_evicted
+        total_evicted += r.n_evicted
+        b = st.banks[0]
+        assert np.array_equal(b.valid.cpu().numpy(), ob.valid)
+        v = ob.valid.astype(bool)
+        assert np.array_equal(b.last_used.cpu().numpy().astype(np.uint64)[v], ob.last_used[v])
+        assert np.array_equal(b.hits.cpu().numpy().astype(np.uint32)[v], ob.hits[v])
+        assert rel_err_rows(npf(out), r.h_out).max() < TOL["f32"]
+        assert rel_err_rows(npf(b.act)[v], ob.act[v]).max() < TOL["f32"]
+        # keep the two banks' stored values identical so later hits copy the same numbers
+        ob.act[v] = npf(b.act)[v]
+        ob.fp[v] = npf(b.fp)[v]
+        ob.inv_norm[v] = npf(b.inv_norm)[v]
+    assert total_evicted > 10
+    st.close()
+
+
+# ---------------------------------------------------------------------------
+# bf16, model-sized rows, teacher-forced per layer
+# ---------------------------------------------------------------------------
+
+def teacher_forced_check(L, st, cfg, ws, Ps, h0, tau, dtype="bf16"):
+    outs = st.forward(h0, tau=tau, keep_all=True)
+    torch.cuda.synchronize()
+    stats = []
+    h_prev = h0
+    for l in range(cfg.n_layers):
+        wnp = {k: npf(v) for k, v in ws[l].items()}
+        ob = oracle_bank_from_gpu(st.banks[l], dtype)
+        r = O.gated_layer(npf(h_prev), ob, npf(Ps[l]), None, wnp, cfg.arch, cfg.n_heads, cfg.ln_eps, cfg.gelu, f32(tau))
+        g = st.gate[l]
+        hit = g.hit.cpu().numpy().astype(bool)
+        idx = g.idx.cpu().numpy()
+        near = np.abs(r.sim - f32(tau)) < 1e-3
+        ties = O.near_tie_sets(r.q, r.qinv, ob.fp, ob.inv_norm, ob.valid)
+        multi = np.array([len(t) > 1 for t in ties])
+        assert np.array_equal(hit[~near], r.hit[~near]), (l, hit, r.hit, r.sim)
+        strict = ~near & ~multi
+        assert np.array_equal(idx[strict], r.idx[strict]), (l, idx, r.idx)
+        for b in np.nonzero(multi)[0]:
+            assert idx[b] in ties[b]
+        np.testing.assert_allclose(npf(g.sim), r.sim, atol=2e-4)   # keys differ by a few bf16 steps at most
+        got = npf(outs[l])
+        for b in range(h0.shape[0]):
+            if hit[b]:
+                assert np.array_equal(got[b], ob.act[ob.act_slot[idx[b]]])
+        miss = ~hit & ~r.hit
+        err = rel_err_rows(got[miss], r.h_out[miss]) if miss.any() else np.zeros(1)
+        assert err.max() < TOL[dtype], (l, err)
+        stats.append(dict(layer=l, hits=int(hit.sum()), near_tau=int(near.sum()), near_tie=int(multi.sum()),
+                          max_err=float(err.max())))
+        h_prev = outs[l]
+    return stats
+
+
+@pytest.mark.parametrize("which", ["encoder", "decoder"])
+def test_model_sized_rows_bf16_teacher_forced(L, which):
+    from paper_2512_16843_amd.engine import GatedStack
+    if which == "encoder":
+        cfg = W.scaled(W.BERT_BASE, n_layers=2, B=6, n_bank=192)
+    else:
+        cfg = W.scaled(W.GPT2_SMALL, n_layers=2, B=3, S=320, n_bank=96)
+    say(f"{cfg.name} slice bf16: L=2 B={cfg.B} S={cfg.S} bank {cfg.n_bank}, teacher-forced")
+    ws = W.make_layer_weights(cfg, seed=0)
+    tok, pos = W.make_embeddings(cfg, seed=0)
+    Ps = W.make_projection(cfg.d, cfg.k, torch.bfloat16, seed=3, n_layers=cfg.n_layers)
+    src = W.make_sources(cfg, cfg.n_bank, seed=1)
+    st = GatedStack(cfg, ws, Ps)
+    h_src = W.embed(torch.from_numpy(src), tok, pos, torch.bfloat16).cuda()
+    build_banks_gpu(L, st, h_src)
+    assert all(torch.all(b.valid == 1) for b in st.banks)
+    if which == "encoder":
+        ids, _ = W.make_substitution_queries(cfg, src, n_dup=4, n_subst=12, seed=2)
+    else:
+        ids, _, _ = W.make_prefix_queries(cfg, src, seed=2)
+    h0 = W.embed(torch.from_numpy(ids), tok, pos, torch.bfloat16).cuda()
+    for tau in (0.98, 1.5):
+        stats = teacher_forced_check(L, st, cfg, ws, Ps, h0, tau)
+        for s in stats:
+            say(f"  tau={tau} {s}")
+    st.close()
