@@ -1,0 +1,275 @@
+#!/usr/bin/env python3
+"""Benchmark of the cache-gated forward on one MI355X.
+
+A step is one pass of the whole hot path -- fingerprint, bank match, threshold +
+compaction, gather of cached outputs, dense block for the misses -- through all
+layers of the BERT-base-shaped stack (12 layers, d = 768, batch 64 x 384 tokens,
+16,384-entry bank per layer) on one synthetic query batch resident in HBM.
+Banks are built first by the library's own all-miss + insert path.
+
+Prints ONE JSON line: whole-job sequences/s at the headline threshold, the sweep over
+thresholds with measured hit rates, the roofline of the dominant kernel (per-kernel
+durations from HIP events recorded on the launch stream), and the CPU oracle timed on
+a bounded sample of the same batch.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "seq/s cache-gated 12L d768 forward vs hit rate; match MFMA% + gather HBM GB/s"
+HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+FP32_VALU_PEAK_TFLOPS = 157.3
+
+
+def log(msg):
+    print("[bench] " + msg, file=sys.stderr, flush=True)
+
+
+def kernel_work(cfg, name, miss, hit, e=2):
+    """Algorithmic flops and bytes of ALL launches of `name` in one step, given per-layer miss/hit counts."""
+    d, dff, S, B, N, k = cfg.d, cfg.d_ff, cfg.S, cfg.B, cfg.n_bank, cfg.k
+    L = len(miss)
+    tok = [m * S for m in miss]
+    if name == "gemm_bf16_kernel":
+        fl = sum(2.0 * t * (4 * d * d + 2 * d * dff) for t in tok)
+        by = sum((4 * d * d + 2 * d * dff) * e + t * (d + 3 * d + d + d + d + dff + dff + d) * e for t in tok)
+        return fl, by, "mfma"
+    if name == "attention_kernel":
+        causal = 0.5 if cfg.arch == 1 else 1.0
+        fl = sum(4.0 * m * S * S * d * causal for m in miss)
+        by = sum(m * S * 4 * d * e for m in miss)
+        return fl, by, "alu"
+    if name == "layernorm_kernel":
+        return sum(8.0 * t * d * 2 for t in tok), sum(2 * 2 * t * d * e for t in tok), "hbm"
+    if name == "gather_kernel":
+        return 0.0, sum(2.0 * h * S * d * e for h in hit), "hbm"
+    if name == "pool_kernel":
+        return L * float(B) * S * d, L * float(B) * S * d * e, "hbm"
+    if name == "project_kernel":
+        return L * 2.0 * B * d * k, L * (d * k * e + B * k * e), "hbm"
+    if name == "match_bf16_kernel":
+        return L * 2.0 * B * N * k, L * float(N) * k * e, "hbm" if B < 300 else "mfma"
+    if name == "match_finalize_kernel":
+        return L * 2.0 * B * 32 * k, L * float(B) * 32 * k * e, "hbm"
+    if name == "insert_kernel":
+        return 0.0, sum(2.0 * m * S * d * e for m in miss), "hbm"
+    return 0.0, 0.0, "hbm"
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--tau", type=float, default=0.95, help="headline threshold")
+    ap.add_argument("--bank", type=int, default=None, help="bank entries per layer (default: the config's 16384)")
+    ap.add_argument("--layers", type=int, default=None, help="debug: fewer layers")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-rows", type=int, default=2, help="sequences of the batch the oracle is timed on")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the path is single-device); --gpus %d is not supported"
+              % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2512_16843_amd import llmc, workloads as W
+    from paper_2512_16843_amd.engine import GatedStack
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    torch.cuda.set_device(0)
+    llmc.lib()
+    cfg = W.BERT_BASE
+    if args.bank or args.layers:
+        cfg = W.scaled(cfg, n_bank=args.bank or cfg.n_bank, n_layers=args.layers or cfg.n_layers)
+    dev = "cuda"
+
+    t0 = time.time()
+    ws = W.make_layer_weights(cfg, seed=0)
+    tok, pos = W.make_embeddings(cfg, seed=0)
+    tok, pos = tok.to(dev), pos.to(dev)
+    Ps = W.make_projection(cfg.d, cfg.k, cfg.torch_dtype, seed=3, n_layers=cfg.n_layers)
+    src = W.make_sources(cfg, cfg.n_bank, seed=1)
+    st = GatedStack(cfg, ws, Ps)
+    log("inputs drawn and %d banks allocated in %.1f s" % (cfg.n_layers, time.time() - t0))
+
+    # ---- bank build: all-miss forward with insertion over the source sequences -------------------
+    torch.cuda.synchronize()
+    t0 = time.time()
+    src_t = torch.from_numpy(src).to(dev)
+    for s in range(0, cfg.n_bank, cfg.B):
+        h = W.embed(src_t[s:s + cfg.B], tok, pos, cfg.torch_dtype)
+        st.forward(h, tau=2.0, flags=llmc.INSERT_ON_MISS, tick=1)
+    torch.cuda.synchronize()
+    build_s = time.time() - t0
+    assert all(int(b.valid.sum()) == cfg.n_bank for b in st.banks)
+    log("banks built: %d sequences x %d layers in %.1f s (%.1f seq/s all-miss with insertion)"
+        % (cfg.n_bank, cfg.n_layers, build_s, cfg.n_bank / build_s))
+
+    # ---- query batch: 60 % perturbed copies of bank sources (3 % of tokens resampled), 40 % fresh ----
+    n_dup = int(round(0.6 * cfg.B))
+    n_sub = int(round(0.03 * cfg.S))
+    ids, srcmap = W.make_substitution_queries(cfg, src, n_dup=n_dup, n_subst=n_sub, seed=2)
+    h0 = W.embed(torch.from_numpy(ids).to(dev), tok, pos, cfg.torch_dtype)
+
+    def run(tau, steps, warmup):
+        for _ in range(warmup):
+            st.forward(h0, tau=tau)
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for _ in range(steps):
+            st.forward(h0, tau=tau)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t) / steps
+        cnt = st.hit_counts().numpy()
+        return dt, cnt
+
+    sweep = []
+    taus = sorted(set([0.90, 0.95, 0.98, args.tau])) + [2.0]
+    headline = None
+    for tau in taus:
+        dt, cnt = run(tau, args.steps, args.warmup)
+        hits = cnt[:, llmc.CNT_HIT]
+        row = {"tau": tau if tau <= 1.0 else "no-cache", "ms_per_step": round(dt * 1e3, 4),
+               "seq_per_s": round(cfg.B / dt, 2), "hit_rate": round(float(hits.sum()) / (cfg.B * cfg.n_layers), 4),
+               "hit_rate_first_layer": round(float(hits[0]) / cfg.B, 4),
+               "hit_rate_last_layer": round(float(hits[-1]) / cfg.B, 4),
+               "near_tau_rows": int(cnt[:, llmc.CNT_NEAR_TAU].sum()), "near_tie_rows": int(cnt[:, llmc.CNT_NEAR_TIE].sum())}
+        sweep.append(row)
+        log("tau=%s  %.3f ms/step  %.1f seq/s  hit rate %.3f (layer 1: %.3f, layer %d: %.3f)"
+            % (row["tau"], dt * 1e3, cfg.B / dt, row["hit_rate"], row["hit_rate_first_layer"], cfg.n_layers,
+               row["hit_rate_last_layer"]))
+        if tau == args.tau:
+            headline = (dt, cnt)
+    dt_head, cnt_head = headline
+
+    # ---- per-kernel durations: HIP events on the launch stream around every kernel --------------
+    def profile(tau, steps=5):
+        st.forward(h0, tau=tau)
+        torch.cuda.synchronize()
+        llmc.llmc_profile_begin(steps * cfg.n_layers * 24)
+        for _ in range(steps):
+            st.forward(h0, tau=tau)
+        rep = llmc.llmc_profile_report()
+        llmc.llmc_profile_end()
+        cnt = st.hit_counts().numpy()
+        miss = [int(x) for x in cnt[:, llmc.CNT_MISS]]
+        hit = [int(x) for x in cnt[:, llmc.CNT_HIT]]
+        out = {}
+        for name, (n, ms) in rep.items():
+            fl, by, bound = kernel_work(cfg, name, miss, hit)
+            t_step = ms * 1e-3 / steps
+            out[name] = {"launches_per_step": n // steps, "avg_us": round(ms * 1e3 / n, 3),
+                         "ms_per_step": round(ms / steps, 4), "bound": bound,
+                         "tflops": round(fl / t_step / 1e12, 3) if t_step > 0 else 0.0,
+                         "gbs": round(by / t_step / 1e9, 2) if t_step > 0 else 0.0}
+        return out
+
+    prof_head = profile(args.tau)
+    prof_nocache = profile(2.0)
+    for tag, pr in (("tau=%s" % args.tau, prof_head), ("no-cache", prof_nocache)):
+        for name, r in sorted(pr.items(), key=lambda kv: -kv[1]["ms_per_step"]):
+            log("%-9s %-24s %3d launches/step  avg %9.2f us  %8.4f ms/step  %8.2f TFLOP/s %9.1f GB/s"
+                % (tag, name, r["launches_per_step"], r["avg_us"], r["ms_per_step"], r["tflops"], r["gbs"]))
+
+    # the dominant kernel of the headline run decides the roofline object
+    dom = max(prof_head.items(), key=lambda kv: kv[1]["ms_per_step"])
+    name, r = dom
+    if r["bound"] == "mfma":
+        roof = {"kernel": name, "bound": "mfma", "achieved": r["tflops"], "peak": MFMA_BF16_PEAK_TFLOPS,
+                "unit": "TFLOP/s", "frac": round(r["tflops"] / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None}
+    elif r["bound"] == "alu":
+        roof = {"kernel": name, "bound": "alu", "achieved": r["tflops"], "peak": FP32_VALU_PEAK_TFLOPS,
+                "unit": "TFLOP/s", "frac": round(r["tflops"] / FP32_VALU_PEAK_TFLOPS, 4), "traffic": None}
+    else:
+        roof = {"kernel": name, "bound": "hbm", "achieved": r["gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(r["gbs"] / HBM_PEAK_GBS, 4), "traffic": None}
+    roof["avg_launch_us"] = r["avg_us"]
+
+    # ---- CPU oracle on a bounded sample of the same batch ------------------------------------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(cfg, st, ws, Ps, h0, args.tau, args.cpu_rows)
+        log("cpu oracle: %.3f seq/s on %d threads (%s)" % (cpu["value"], cpu["cores"], cpu["sample"]))
+
+    result = {
+        "metric": METRIC, "value": round(cfg.B / dt_head, 2), "unit": "seq/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(dt_head * 1e3, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "%s encoder: %d layers, d=%d, batch %d x %d tokens, bank %d x k=%d per layer, "
+                               "60%% perturbed copies (3%% tokens resampled) + 40%% fresh, static banks"
+                               % (cfg.name, cfg.n_layers, cfg.d, cfg.B, cfg.S, cfg.n_bank, cfg.k),
+                   "tau": args.tau,
+                   "hit_rate": round(float(cnt_head[:, llmc.CNT_HIT].sum()) / (cfg.B * cfg.n_layers), 4),
+                   "bank_build_s": round(build_s, 2)},
+        "sweep": sweep,
+        "roofline": roof,
+        "kernels": {"headline": prof_head, "no_cache": prof_nocache},
+        "cpu_baseline": cpu,
+    }
+    st.close()
+    print(json.dumps(result))
+
+
+def cpu_baseline(cfg, st, ws, Ps, h0, tau, n_rows):
+    """Time the oracle's gated forward (all layers) on the first rows of the batch.
+
+    The oracle reads the banks the GPU built: keys come to the host whole, cached
+    outputs are fetched row by row when a hit needs them.
+    """
+    import numpy as np
+    import torch
+    from oracle import llmc_oracle as O
+
+    npf = lambda t: t.detach().float().cpu().numpy()
+
+    class LazyAct:
+        def __init__(self, t):
+            self.t = t
+
+        def __getitem__(self, j):
+            return npf(self.t[int(j)])
+
+    banks = []
+    for b in st.banks:
+        ob = O.Bank(1, cfg.k, 1, 1, cfg.dtype)
+        ob.N, ob.S, ob.d, ob.A = b.n_slots, b.S, b.d, b.n_act_slots
+        ob.fp, ob.inv_norm, ob.valid = npf(b.fp), npf(b.inv_norm), b.valid.cpu().numpy()
+        ob.act_slot = np.arange(b.n_slots, dtype=np.int32)
+        ob.act = LazyAct(b.act)
+        banks.append(ob)
+    wnp = [{k: npf(v) for k, v in w.items()} for w in ws]
+    Pnp = [npf(p) for p in Ps]
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([i.get("num_threads", 1) for i in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    tau32 = float(np.float32(tau))
+    n = max(1, min(n_rows, cfg.B))
+    while True:
+        x = npf(h0[:n])
+        t = time.perf_counter()
+        _, res = O.infer(x, banks, Pnp, [None] * cfg.n_layers, wnp, cfg.arch, cfg.n_heads, cfg.ln_eps, cfg.gelu,
+                         tau=tau32, out_dtype=cfg.dtype)
+        dt = time.perf_counter() - t
+        if dt >= 8.0 or n >= cfg.B:
+            break
+        n = min(cfg.B, max(n + 1, int(n * min(8.0, 12.0 / max(dt, 1e-3)))))
+    hits = sum(int(r.hit.sum()) for r in res)
+    return {"value": round(n / dt, 4), "unit": "seq/s", "cores": int(cores), "kind": "oracle",
+            "sample": "first %d of %d sequences of the batch through all %d layers at tau=%s against the GPU-built "
+                      "banks (%d of %d row-layers hit), %.1f s" % (n, cfg.B, cfg.n_layers, tau, hits,
+                                                                   n * cfg.n_layers, dt)}
+
+
+if __name__ == "__main__":
+    main()

@@ -278,6 +278,22 @@ llmc_status_t llmc_layer_forward_gated(const llmc_layer_desc_t* layer, llmc_bank
                                        size_t workspace_bytes, llmc_stream_t stream);
 size_t llmc_layer_workspace_bytes(const llmc_layer_desc_t* layer, int32_t B, int32_t S, int32_t k);
 
+/* ---- measurement aid ------------------------------------------------------------- */
+
+/*
+ * Per-kernel timing with HIP events recorded on the launch stream around every kernel
+ * the library enqueues.  llmc_profile_begin creates `max_records` event pairs (it
+ * allocates; call it outside any timed or captured region) and switches recording on;
+ * launches beyond max_records are not recorded.  llmc_profile_report synchronises the
+ * device and writes one text line per kernel name, "name count total_ms", into buf
+ * (NUL-terminated, truncated to cap), restarts the record count and returns the number
+ * of records it read.  llmc_profile_end switches recording off and destroys the events.
+ * Recording perturbs back-to-back launches slightly: time whole steps with it off.
+ */
+llmc_status_t llmc_profile_begin(int32_t max_records);
+int32_t llmc_profile_report(char* buf, size_t cap);
+llmc_status_t llmc_profile_end(void);
+
 /* ---- misc ---------------------------------------------------------------------- */
 
 const char* llmc_last_error(void); /* thread-local, never NULL */

@@ -1,9 +1,14 @@
 // C ABI of libllmc.so: argument validation (before any HIP call) and the host-side
 // orchestration of the gated layer, which only enqueues kernels on the caller's stream.
+#include <algorithm>
 #include <stdarg.h>
 #include <stdio.h>
 #include <string.h>
+#include <atomic>
+#include <map>
 #include <new>
+#include <string>
+#include <vector>
 #include "common.h"
 
 namespace llmc {
@@ -19,6 +24,23 @@ llmc_status_t set_error(llmc_status_t st, const char* fmt, ...) {
 }
 llmc_status_t hip_error(hipError_t e, const char* what) {
   return set_error(LLMC_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+// ---- per-kernel event timing ---------------------------------------------------------------
+struct ProfRec { const char* name; hipEvent_t a, b; };
+static std::vector<ProfRec> g_prof;
+static std::atomic<int> g_prof_used{0};
+static std::atomic<bool> g_prof_on{false};
+
+ProfScope::ProfScope(const char* name, hipStream_t s) : rec(-1), st(s) {
+  if (!g_prof_on.load(std::memory_order_relaxed)) return;
+  const int i = g_prof_used.fetch_add(1);
+  if (i >= (int)g_prof.size()) return;
+  g_prof[i].name = name;
+  if (hipEventRecord(g_prof[i].a, st) == hipSuccess) rec = i;
+}
+ProfScope::~ProfScope() {
+  if (rec >= 0) (void)hipEventRecord(g_prof[rec].b, st);
 }
 
 static bool dtype_ok(int dt) { return dt == LLMC_F32 || dt == LLMC_BF16; }
@@ -199,6 +221,63 @@ llmc_status_t llmc_gather_hits(const llmc_bank_t* bank, const int32_t* d_idx, co
   REQUIRE(n_max > 0 && n_max <= 65535, LLMC_ERR_SHAPE, "n_max=%d out of range 1..65535", n_max);
   REQUIRE(aligned16(d_h_out), LLMC_ERR_SHAPE, "output must be 16-byte aligned");
   return launch_gather(bank, d_idx, d_rows, d_n, n_max, d_h_out, (hipStream_t)stream);
+}
+
+llmc_status_t llmc_profile_begin(int32_t max_records) {
+  REQUIRE(max_records > 0 && max_records <= (1 << 20), LLMC_ERR_INVALID_ARG, "max_records out of range");
+  REQUIRE(!g_prof_on.load() && g_prof.empty(), LLMC_ERR_INVALID_ARG, "profiling already on");
+  g_prof.resize(max_records);
+  for (int i = 0; i < max_records; ++i) {
+    g_prof[i].name = nullptr;
+    hipError_t e = hipEventCreate(&g_prof[i].a);
+    if (e == hipSuccess) {
+      e = hipEventCreate(&g_prof[i].b);
+      if (e != hipSuccess) (void)hipEventDestroy(g_prof[i].a);
+    }
+    if (e != hipSuccess) {
+      g_prof.resize(i);
+      llmc_profile_end();
+      return hip_error(e, "hipEventCreate");
+    }
+  }
+  g_prof_used.store(0);
+  g_prof_on.store(true);
+  return LLMC_OK;
+}
+
+int32_t llmc_profile_report(char* buf, size_t cap) {
+  if (!buf || cap == 0) return 0;
+  buf[0] = 0;
+  (void)hipDeviceSynchronize();
+  const int n = std::min((int)g_prof.size(), g_prof_used.load());
+  std::map<std::string, std::pair<int, double>> agg;
+  for (int i = 0; i < n; ++i) {
+    float ms = 0.f;
+    if (!g_prof[i].name || hipEventElapsedTime(&ms, g_prof[i].a, g_prof[i].b) != hipSuccess) continue;
+    auto& a = agg[g_prof[i].name];
+    a.first += 1;
+    a.second += ms;
+  }
+  size_t off = 0;
+  for (auto& kv : agg) {
+    int w = snprintf(buf + off, cap - off, "%s %d %.6f\n", kv.first.c_str(), kv.second.first, kv.second.second);
+    if (w < 0 || (size_t)w >= cap - off) break;
+    off += (size_t)w;
+  }
+  g_prof_used.store(0);
+  return n;
+}
+
+llmc_status_t llmc_profile_end(void) {
+  g_prof_on.store(false);
+  (void)hipDeviceSynchronize();
+  for (auto& r : g_prof) {
+    (void)hipEventDestroy(r.a);
+    (void)hipEventDestroy(r.b);
+  }
+  g_prof.clear();
+  g_prof_used.store(0);
+  return LLMC_OK;
 }
 
 size_t llmc_layer_workspace_bytes(const llmc_layer_desc_t* layer, int32_t B, int32_t S, int32_t k) {

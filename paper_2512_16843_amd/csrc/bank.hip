@@ -167,8 +167,8 @@ __global__ __launch_bounds__(kCopyThreads) void insert_kernel(
 llmc_status_t launch_bank_refresh(llmc_bank* bank, hipStream_t st) {
   const int N = bank->desc.n_slots;
   const int n_pad = (int)align_up((size_t)N, 256);
-  hipLaunchKernelGGL(refresh_kernel, dim3((n_pad + 255) / 256), dim3(256), 0, st, bank->desc.d_valid,
-                     bank->desc.d_inv_norm, N, n_pad, bank->d_binv_eff);
+  { ProfScope ps_("refresh_kernel", st); hipLaunchKernelGGL(refresh_kernel, dim3((n_pad + 255) / 256), dim3(256), 0, st, bank->desc.d_valid,
+                     bank->desc.d_inv_norm, N, n_pad, bank->d_binv_eff); }
   LLMC_LAUNCH_CHECK("refresh_kernel");
   return LLMC_OK;
 }
@@ -177,25 +177,25 @@ llmc_status_t launch_bank_insert(llmc_bank* bank, const void* d_fp, const float*
                                  const int32_t* d_rows, const int32_t* d_m, int m_max, uint64_t tick,
                                  int32_t* d_slots_out, int32_t* d_counters, hipStream_t st) {
   const llmc_bank_desc_t& D = bank->desc;
-  hipLaunchKernelGGL(select_kernel, dim3(1), dim3(kSelThreads), (size_t)m_max * sizeof(uint64_t), st, D.d_valid,
+  { ProfScope ps_("select_kernel", st); hipLaunchKernelGGL(select_kernel, dim3(1), dim3(kSelThreads), (size_t)m_max * sizeof(uint64_t), st, D.d_valid,
                      D.d_last_used, D.n_slots, d_m, m_max, 0, D.policy == LLMC_EVICT_LRU ? 1 : 0, d_slots_out,
-                     bank->d_binv_eff);
+                     bank->d_binv_eff); }
   LLMC_LAUNCH_CHECK("select_kernel");
   const size_t e = elem_size(D.dtype);
   const size_t vec_per_seq = (size_t)D.S * D.d * e / 16, vec_per_key = (size_t)D.k * e / 16;
   const size_t per_wg = (size_t)kCopyThreads * kCopyVecPerThread;
   dim3 grid((unsigned)((vec_per_seq + per_wg - 1) / per_wg), m_max);
-  hipLaunchKernelGGL(insert_kernel, grid, dim3(kCopyThreads), 0, st, (const u32x4_t*)d_fp, d_inv, (const u32x4_t*)d_act,
+  { ProfScope ps_("insert_kernel", st); hipLaunchKernelGGL(insert_kernel, grid, dim3(kCopyThreads), 0, st, (const u32x4_t*)d_fp, d_inv, (const u32x4_t*)d_act,
                      d_rows, d_m, m_max, d_slots_out, (u32x4_t*)D.d_fp, D.d_inv_norm, (u32x4_t*)D.d_act, D.d_act_slot,
-                     D.d_last_used, D.d_hits, D.d_valid, bank->d_binv_eff, vec_per_key, vec_per_seq, tick, d_counters);
+                     D.d_last_used, D.d_hits, D.d_valid, bank->d_binv_eff, vec_per_key, vec_per_seq, tick, d_counters); }
   LLMC_LAUNCH_CHECK("insert_kernel");
   return LLMC_OK;
 }
 
 llmc_status_t launch_bank_evict(llmc_bank* bank, const int32_t* d_m, int m_max, int32_t* d_victims, hipStream_t st) {
   const llmc_bank_desc_t& D = bank->desc;
-  hipLaunchKernelGGL(select_kernel, dim3(1), dim3(kSelThreads), (size_t)m_max * sizeof(uint64_t), st, D.d_valid,
-                     D.d_last_used, D.n_slots, d_m, m_max, 1, 1, d_victims, bank->d_binv_eff);
+  { ProfScope ps_("select_kernel", st); hipLaunchKernelGGL(select_kernel, dim3(1), dim3(kSelThreads), (size_t)m_max * sizeof(uint64_t), st, D.d_valid,
+                     D.d_last_used, D.n_slots, d_m, m_max, 1, 1, d_victims, bank->d_binv_eff); }
   LLMC_LAUNCH_CHECK("select_kernel");
   return LLMC_OK;
 }

@@ -108,6 +108,14 @@ llmc_status_t hip_error(hipError_t e, const char* what);
     if (s_ != LLMC_OK) return s_;                        \
   } while (0)
 
+// Optional per-kernel timing: brackets one launch with two events on its stream.
+struct ProfScope {
+  ProfScope(const char* name, hipStream_t st);
+  ~ProfScope();
+  int rec;
+  hipStream_t st;
+};
+
 static inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 static inline size_t elem_size(int dtype) { return dtype == LLMC_F32 ? 4 : 2; }

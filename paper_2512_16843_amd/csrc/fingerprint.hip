@@ -156,12 +156,12 @@ static llmc_status_t fingerprint_t(const T* h, int B, int S, int d, const T* P, 
   const int R = G >= 256 ? 1 : 256 / G;
   const int n_chunks = pool_chunks(S);
   dim3 grid(n_chunks, B);
-  hipLaunchKernelGGL(pool_kernel<T>, grid, dim3(G * R), (size_t)R * d * sizeof(float), st, h, S, d, G, R, partial,
-                     n_chunks);
+  { ProfScope ps_("pool_kernel", st); hipLaunchKernelGGL(pool_kernel<T>, grid, dim3(G * R), (size_t)R * d * sizeof(float), st, h, S, d, G, R, partial,
+                     n_chunks); }
   LLMC_LAUNCH_CHECK("pool_kernel");
   const int split = k <= 256 ? kProjSplit : (k <= 512 ? 2 : 1);
-  hipLaunchKernelGGL(project_kernel<T>, dim3(B), dim3(k * split), (size_t)(d + split * k) * sizeof(float), st,
-                     partial, n_chunks, S, d, P, bias, k, split, fp, inv);
+  { ProfScope ps_("project_kernel", st); hipLaunchKernelGGL(project_kernel<T>, dim3(B), dim3(k * split), (size_t)(d + split * k) * sizeof(float), st,
+                     partial, n_chunks, S, d, P, bias, k, split, fp, inv); }
   LLMC_LAUNCH_CHECK("project_kernel");
   return LLMC_OK;
 }
@@ -179,9 +179,9 @@ llmc_status_t launch_inv_norm(const void* d_fp, int64_t n, int k, int dtype, flo
   const int rows_per_block = 4;
   const unsigned blocks = (unsigned)((n + rows_per_block - 1) / rows_per_block);
   if (dtype == LLMC_F32)
-    hipLaunchKernelGGL(inv_norm_kernel<float>, dim3(blocks), dim3(256), 0, st, (const float*)d_fp, n, k, d_out);
+    { ProfScope ps_("inv_norm_kernel", st); hipLaunchKernelGGL(inv_norm_kernel<float>, dim3(blocks), dim3(256), 0, st, (const float*)d_fp, n, k, d_out); }
   else
-    hipLaunchKernelGGL(inv_norm_kernel<bf16_t>, dim3(blocks), dim3(256), 0, st, (const bf16_t*)d_fp, n, k, d_out);
+    { ProfScope ps_("inv_norm_kernel", st); hipLaunchKernelGGL(inv_norm_kernel<bf16_t>, dim3(blocks), dim3(256), 0, st, (const bf16_t*)d_fp, n, k, d_out); }
   LLMC_LAUNCH_CHECK("inv_norm_kernel");
   return LLMC_OK;
 }

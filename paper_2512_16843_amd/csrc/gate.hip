@@ -112,8 +112,8 @@ llmc_status_t launch_compact(const uint8_t* d_hit, const int32_t* d_idx, const f
                              int B, float tau, int32_t* d_hit_rows, int32_t* d_miss_rows, int32_t* d_counters,
                              llmc_bank* bank, uint32_t flags, uint64_t tick, hipStream_t st) {
   const int touch = (flags & LLMC_UPDATE_LRU) ? 1 : 0;
-  hipLaunchKernelGGL(compact_kernel, dim3(1), dim3(1024), 0, st, d_hit, d_idx, d_sim, d_near_tie, B, tau, d_hit_rows,
-                     d_miss_rows, d_counters, bank->desc.d_last_used, bank->desc.d_hits, touch, tick);
+  { ProfScope ps_("compact_kernel", st); hipLaunchKernelGGL(compact_kernel, dim3(1), dim3(1024), 0, st, d_hit, d_idx, d_sim, d_near_tie, B, tau, d_hit_rows,
+                     d_miss_rows, d_counters, bank->desc.d_last_used, bank->desc.d_hits, touch, tick); }
   LLMC_LAUNCH_CHECK("compact_kernel");
   return LLMC_OK;
 }
@@ -121,8 +121,8 @@ llmc_status_t launch_compact(const uint8_t* d_hit, const int32_t* d_idx, const f
 llmc_status_t launch_all_miss(int B, int32_t* d_miss_rows, int32_t* d_counters, int32_t* d_idx, float* d_sim,
                               uint8_t* d_hit, hipStream_t st) {
   const int n = B > LLMC_CNT_WORDS ? B : LLMC_CNT_WORDS;
-  hipLaunchKernelGGL(all_miss_kernel, dim3((n + 255) / 256), dim3(256), 0, st, B, d_miss_rows, d_counters, d_idx, d_sim,
-                     d_hit);
+  { ProfScope ps_("all_miss_kernel", st); hipLaunchKernelGGL(all_miss_kernel, dim3((n + 255) / 256), dim3(256), 0, st, B, d_miss_rows, d_counters, d_idx, d_sim,
+                     d_hit); }
   LLMC_LAUNCH_CHECK("all_miss_kernel");
   return LLMC_OK;
 }
@@ -133,8 +133,8 @@ llmc_status_t launch_gather(const llmc_bank* bank, const int32_t* d_idx, const i
   const size_t vec_per_seq = (size_t)D.S * D.d * elem_size(D.dtype) / 16;
   const size_t per_wg = (size_t)kGatherThreads * kGatherVecPerThread;
   dim3 grid((unsigned)((vec_per_seq + per_wg - 1) / per_wg), n_max);
-  hipLaunchKernelGGL(gather_kernel, grid, dim3(kGatherThreads), 0, st, (const u32x4_t*)D.d_act, D.d_act_slot, d_idx,
-                     d_rows, d_n, n_max, vec_per_seq, (u32x4_t*)d_h_out);
+  { ProfScope ps_("gather_kernel", st); hipLaunchKernelGGL(gather_kernel, grid, dim3(kGatherThreads), 0, st, (const u32x4_t*)D.d_act, D.d_act_slot, d_idx,
+                     d_rows, d_n, n_max, vec_per_seq, (u32x4_t*)d_h_out); }
   LLMC_LAUNCH_CHECK("gather_kernel");
   return LLMC_OK;
 }

@@ -170,11 +170,11 @@ static llmc_status_t launch_gemm(const GemmArgs& g, int dtype, hipStream_t st) {
   if (dtype == LLMC_BF16) {
     const int tiles_n = (g.N + GemmCfg::BN - 1) / GemmCfg::BN;
     const int tiles_m = (g.max_seqs * g.S + GemmCfg::BM - 1) / GemmCfg::BM;
-    hipLaunchKernelGGL(gemm_bf16_kernel, dim3((unsigned)tiles_m * tiles_n), dim3(GemmCfg::THREADS), 0, st, g, tiles_n);
+    { ProfScope ps_("gemm_bf16_kernel", st); hipLaunchKernelGGL(gemm_bf16_kernel, dim3((unsigned)tiles_m * tiles_n), dim3(GemmCfg::THREADS), 0, st, g, tiles_n); }
   } else {
     const int tiles_n = (g.N + 63) / 64;
     const int tiles_m = (g.max_seqs * g.S + 63) / 64;
-    hipLaunchKernelGGL(gemm_f32_kernel, dim3((unsigned)tiles_m * tiles_n), dim3(256), 0, st, g, tiles_n);
+    { ProfScope ps_("gemm_f32_kernel", st); hipLaunchKernelGGL(gemm_f32_kernel, dim3((unsigned)tiles_m * tiles_n), dim3(256), 0, st, g, tiles_n); }
   }
   LLMC_LAUNCH_CHECK("gemm");
   return LLMC_OK;
@@ -241,13 +241,17 @@ static llmc_status_t launch_ln(const void* in, const int32_t* in_rows, void* out
   constexpr int VEC = Vec16<T>::N;
   const int nvec = d / VEC;
   const unsigned blocks = (unsigned)((max_seqs * S + 3) / 4);
-#define LN_CASE(MV)                                                                                          \
-  hipLaunchKernelGGL((layernorm_kernel<T, MV>), dim3(blocks), dim3(256), 0, st, (const T*)in, d, in_rows,  \
-                     (T*)out, d, out_rows, (const T*)gamma, (const T*)beta, eps, d, S, count, max_seqs)
-  if (nvec <= 64) LN_CASE(1);
-  else if (nvec <= 128) LN_CASE(2);
-  else if (nvec <= 256) LN_CASE(4);
-  else if (nvec <= 512) LN_CASE(8);
+#define LN_CASE(MV)                                                                                     \
+  {                                                                                                     \
+    ProfScope ps_("layernorm_kernel", st);                                                              \
+    hipLaunchKernelGGL((layernorm_kernel<T, MV>), dim3(blocks), dim3(256), 0, st, (const T*)in, d,      \
+                       in_rows, (T*)out, d, out_rows, (const T*)gamma, (const T*)beta, eps, d, S, count, \
+                       max_seqs);                                                                       \
+  }
+  if (nvec <= 64) LN_CASE(1)
+  else if (nvec <= 128) LN_CASE(2)
+  else if (nvec <= 256) LN_CASE(4)
+  else if (nvec <= 512) LN_CASE(8)
   else return set_error(LLMC_ERR_SHAPE, "LayerNorm width %d too large", d);
 #undef LN_CASE
   LLMC_LAUNCH_CHECK("layernorm");
@@ -334,11 +338,11 @@ static llmc_status_t launch_attention(const void* qkv, void* ctx, int S, int d, 
   const float scale = 1.0f / sqrtf((float)(d / n_heads));
   dim3 grid((S + 127) / 128, n_heads, max_seqs);
   if (causal)
-    hipLaunchKernelGGL((attention_kernel<T, true>), grid, dim3(128), 0, st, (const T*)qkv, (T*)ctx, S, d, scale, count,
-                       max_seqs);
+    { ProfScope ps_("attention_kernel", st); hipLaunchKernelGGL((attention_kernel<T, true>), grid, dim3(128), 0, st, (const T*)qkv, (T*)ctx, S, d, scale, count,
+                       max_seqs); }
   else
-    hipLaunchKernelGGL((attention_kernel<T, false>), grid, dim3(128), 0, st, (const T*)qkv, (T*)ctx, S, d, scale,
-                       count, max_seqs);
+    { ProfScope ps_("attention_kernel", st); hipLaunchKernelGGL((attention_kernel<T, false>), grid, dim3(128), 0, st, (const T*)qkv, (T*)ctx, S, d, scale,
+                       count, max_seqs); }
   LLMC_LAUNCH_CHECK("attention");
   return LLMC_OK;
 }

@@ -244,19 +244,19 @@ llmc_status_t launch_match(const llmc_bank* bank, const void* d_fp, const float*
   if (D.dtype == LLMC_BF16) {
     split_plan(N, B, &ns, &per);
     dim3 grid(ns, (B + MatchCfg::BN - 1) / MatchCfg::BN);
-    hipLaunchKernelGGL(match_bf16_kernel, grid, dim3(MatchCfg::THREADS), 0, st, (const uint16_t*)D.d_fp,
-                       bank->d_binv_eff, N, K, (const uint16_t*)d_fp, B, per, partial);
+    { ProfScope ps_("match_bf16_kernel", st); hipLaunchKernelGGL(match_bf16_kernel, grid, dim3(MatchCfg::THREADS), 0, st, (const uint16_t*)D.d_fp,
+                       bank->d_binv_eff, N, K, (const uint16_t*)d_fp, B, per, partial); }
     LLMC_LAUNCH_CHECK("match_bf16_kernel");
-    hipLaunchKernelGGL((match_finalize_kernel<bf16_t>), dim3((B + 3) / 4), dim3(256), 0, st, partial, ns,
+    { ProfScope ps_("match_finalize_kernel", st); hipLaunchKernelGGL((match_finalize_kernel<bf16_t>), dim3((B + 3) / 4), dim3(256), 0, st, partial, ns,
                        (const bf16_t*)D.d_fp, D.d_inv_norm, D.d_valid, N, K, (const bf16_t*)d_fp, d_inv, B, tau, d_idx,
-                       d_sim, d_hit, d_near_tie);
+                       d_sim, d_hit, d_near_tie); }
   } else {
-    hipLaunchKernelGGL(match_f32_kernel, dim3(B), dim3(256), (size_t)K * sizeof(float) + 256 * sizeof(Top2), st,
-                       (const float*)D.d_fp, bank->d_binv_eff, N, K, (const float*)d_fp, partial);
+    { ProfScope ps_("match_f32_kernel", st); hipLaunchKernelGGL(match_f32_kernel, dim3(B), dim3(256), (size_t)K * sizeof(float) + 256 * sizeof(Top2), st,
+                       (const float*)D.d_fp, bank->d_binv_eff, N, K, (const float*)d_fp, partial); }
     LLMC_LAUNCH_CHECK("match_f32_kernel");
-    hipLaunchKernelGGL((match_finalize_kernel<float>), dim3((B + 3) / 4), dim3(256), 0, st, partial, 1,
+    { ProfScope ps_("match_finalize_kernel", st); hipLaunchKernelGGL((match_finalize_kernel<float>), dim3((B + 3) / 4), dim3(256), 0, st, partial, 1,
                        (const float*)D.d_fp, D.d_inv_norm, D.d_valid, N, K, (const float*)d_fp, d_inv, B, tau, d_idx,
-                       d_sim, d_hit, d_near_tie);
+                       d_sim, d_hit, d_near_tie); }
   }
   LLMC_LAUNCH_CHECK("match_finalize_kernel");
   return LLMC_OK;

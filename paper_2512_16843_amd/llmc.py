@@ -28,7 +28,8 @@ EXPORTS = [
     "llmc_bank_create", "llmc_bank_destroy", "llmc_bank_refresh", "llmc_bank_insert", "llmc_bank_evict",
     "llmc_fingerprint", "llmc_fingerprint_workspace_bytes", "llmc_inv_norm", "llmc_match",
     "llmc_match_workspace_bytes", "llmc_gather_hits", "llmc_layer_forward_gated",
-    "llmc_layer_workspace_bytes", "llmc_last_error", "llmc_version",
+    "llmc_layer_workspace_bytes", "llmc_profile_begin", "llmc_profile_report", "llmc_profile_end",
+    "llmc_last_error", "llmc_version",
 ]
 
 
@@ -94,6 +95,10 @@ def lib() -> C.CDLL:
                                                u32, u64, vp, vp, C.POINTER(GateOut), vp, sz, vp]
         L.llmc_layer_workspace_bytes.argtypes = [C.POINTER(LayerDesc), i32, i32, i32]
         L.llmc_layer_workspace_bytes.restype = sz
+        L.llmc_profile_begin.argtypes = [i32]
+        L.llmc_profile_report.argtypes = [C.c_char_p, sz]
+        L.llmc_profile_report.restype = i32
+        L.llmc_profile_end.argtypes = []
         for name in EXPORTS:
             fn = getattr(L, name)
             if fn.restype is C.c_int:
@@ -294,6 +299,25 @@ def llmc_layer_forward_gated(layer: Layer, bank: Optional[Bank], proj: Optional[
         C.byref(ld), bank.handle if bank is not None else None, C.byref(fpd), _ptr(h_in), _ptr(h_out), B, S, tau,
         flags, tick, _ptr(fp_given), _ptr(inv_norm_given), C.byref(go) if go is not None else None,
         _ptr(workspace), workspace.numel(), _stream(stream)))
+
+
+def llmc_profile_begin(max_records: int) -> None:
+    _check(lib().llmc_profile_begin(max_records))
+
+
+def llmc_profile_report() -> Dict[str, tuple]:
+    """{kernel name: (launch count, total milliseconds)} since the last report."""
+    buf = C.create_string_buffer(1 << 16)
+    lib().llmc_profile_report(buf, len(buf))
+    out = {}
+    for line in buf.value.decode().splitlines():
+        name, cnt, ms = line.split()
+        out[name] = (int(cnt), float(ms))
+    return out
+
+
+def llmc_profile_end() -> None:
+    _check(lib().llmc_profile_end())
 
 
 def layer_from_weights(cfg, w: Dict[str, torch.Tensor], device="cuda") -> Layer:
