@@ -1,0 +1,146 @@
+// Linear layer  out = act(A * W^T + bias) (+ residual)  on the bf16 matrix cores, with the
+// row gather / scatter of the miss path fused into operand loads and the epilogue.
+#pragma once
+#include "common.h"
+#include "mma.h"
+
+namespace llmc {
+
+// compact token -> row of a [B*S, *] array through an optional sequence list
+__device__ __forceinline__ int64_t map_row(const int32_t* rows, int r, int S) {
+  if (!rows) return r;
+  const int q = r / S;
+  return (int64_t)rows[q] * S + (r - q * S);
+}
+
+__device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752440f)); }
+__device__ __forceinline__ float gelu_tanh(float x) {
+  const float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
+  return 0.5f * x * (1.0f + tanhf(u));
+}
+
+struct GemmArgs {
+  const void* A; int lda;          // [rows, K]
+  const void* W;                   // [N, K]
+  const void* bias;                // [N] or null
+  const void* resid; int ldr;      // [rows, N] or null
+  void* out; int ldo;              // [rows, N]
+  int N, K, S;
+  const int32_t* count;            // device: number of sequences; null = max_seqs
+  int max_seqs;
+  const int32_t* a_rows;           // sequence list applied to A rows, or null
+  const int32_t* r_rows;           // ... to residual rows
+  const int32_t* o_rows;           // ... to output rows
+  int act;                         // 0 none, 1 GELU erf, 2 GELU tanh
+};
+
+__device__ __forceinline__ float apply_act(float v, int act) {
+  if (act == 1) return gelu_erf(v);
+  if (act == 2) return gelu_tanh(v);
+  return v;
+}
+
+// ---- bf16 GEMM on the matrix cores -------------------------------------------------------
+// bias, activation, residual and (scattered) store of one block's accumulators
+template <class C>
+__device__ __forceinline__ void gemm_epilogue(const GemmArgs& g, f32x16_t (&acc)[C::FM][C::FN], int m0, int n0, int M) {
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / C::WN, wn = wave % C::WN;
+  const uint16_t* bias = (const uint16_t*)g.bias;
+  const uint16_t* resid = (const uint16_t*)g.resid;
+  uint16_t* out = (uint16_t*)g.out;
+#pragma unroll
+  for (int j = 0; j < C::FN; ++j) {
+    const int n = n0 + wn * (C::BN / C::WN) + j * 32 + (lane & 31);
+    if (n >= g.N) continue;
+    const float bv = bias ? bf16_to_f32(bias[n]) : 0.f;
+#pragma unroll
+    for (int i = 0; i < C::FM; ++i) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int m = m0 + wm * (C::BM / C::WM) + i * 32 + frag_row(lane, r);
+        if (m >= M) continue;
+        float v = apply_act(acc[i][j][r] + bv, g.act);
+        if (resid) v += bf16_to_f32(resid[map_row(g.r_rows, m, g.S) * g.ldr + n]);
+        out[map_row(g.o_rows, m, g.S) * g.ldo + n] = f32_to_bf16(v);
+      }
+    }
+  }
+}
+
+template <class C>
+__global__ __launch_bounds__(C::THREADS) void gemm_bf16_kernel(GemmArgs g, int tiles_n) {
+  __shared__ __attribute__((aligned(16))) uint16_t lds[C::LDS_BYTES / 2];
+  const int n_seq = g.count ? min(*g.count, g.max_seqs) : g.max_seqs;
+  const int M = n_seq * g.S;
+  const int tile_m = blockIdx.x / tiles_n, tile_n = blockIdx.x % tiles_n;
+  const int m0 = tile_m * C::BM, n0 = tile_n * C::BN;
+  if (m0 >= M) return;
+  const int tid = threadIdx.x;
+  const uint16_t* A = (const uint16_t*)g.A;
+  const uint16_t* W = (const uint16_t*)g.W;
+  const uint16_t* a_ptr[C::NLOAD_A];
+  const uint16_t* b_ptr[C::NLOAD_B];
+#pragma unroll
+  for (int i = 0; i < C::NLOAD_A; ++i) {
+    const int v = tid + i * C::THREADS;
+    const int r = min(m0 + v / C::VEC_PER_ROW, M - 1);
+    a_ptr[i] = A + map_row(g.a_rows, r, g.S) * g.lda + (v % C::VEC_PER_ROW) * 8;
+  }
+#pragma unroll
+  for (int i = 0; i < C::NLOAD_B; ++i) {
+    const int v = tid + i * C::THREADS;
+    const int r = min(n0 + v / C::VEC_PER_ROW, g.N - 1);
+    b_ptr[i] = W + (size_t)r * g.K + (v % C::VEC_PER_ROW) * 8;
+  }
+  f32x16_t acc[C::FM][C::FN];
+#pragma unroll
+  for (int i = 0; i < C::FM; ++i)
+#pragma unroll
+    for (int j = 0; j < C::FN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+  mma_block<C>(a_ptr, b_ptr, g.K, lds, acc);
+
+  gemm_epilogue<C>(g, acc, m0, n0, M);
+}
+
+// Same contract, main loop with direct global -> LDS loads (C is a DmaCfg); K % 64 == 0.
+template <class C>
+__global__ __launch_bounds__(C::THREADS) void gemm_bf16_dma_kernel(GemmArgs g, int tiles_n) {
+  extern __shared__ __attribute__((aligned(16))) uint16_t lds_dyn[];
+  const int n_seq = g.count ? min(*g.count, g.max_seqs) : g.max_seqs;
+  const int M = n_seq * g.S;
+  const int tile_m = blockIdx.x / tiles_n, tile_n = blockIdx.x % tiles_n;
+  const int m0 = tile_m * C::BM, n0 = tile_n * C::BN;
+  if (m0 >= M) return;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const uint16_t* A = (const uint16_t*)g.A;
+  const uint16_t* W = (const uint16_t*)g.W;
+  const uint16_t* a_ptr[C::A_INSTR];
+  const uint16_t* b_ptr[C::B_INSTR];
+#pragma unroll
+  for (int j = 0; j < C::A_INSTR; ++j) {
+    const int tr = C::load_row(j, wave, lane);
+    const int r = min(m0 + tr, M - 1);
+    a_ptr[j] = A + map_row(g.a_rows, r, g.S) * g.lda + C::load_chunk(tr, lane) * 8;
+  }
+#pragma unroll
+  for (int j = 0; j < C::B_INSTR; ++j) {
+    const int tr = C::load_row(j, wave, lane);
+    const int r = min(n0 + tr, g.N - 1);
+    b_ptr[j] = W + (size_t)r * g.K + C::load_chunk(tr, lane) * 8;
+  }
+  f32x16_t acc[C::FM][C::FN];
+#pragma unroll
+  for (int i = 0; i < C::FM; ++i)
+#pragma unroll
+    for (int j = 0; j < C::FN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+  mma_block_dma<C>(a_ptr, b_ptr, g.K, lds_dyn, acc);
+  gemm_epilogue<C>(g, acc, m0, n0, M);
+}
+
+}  // namespace llmc

@@ -11,104 +11,11 @@
 // fp32 runs; LayerNorm with one wavefront per token; softmax attention with an online
 // softmax over 32-key tiles.
 #include "common.h"
-#include "mma.h"
+#include "gemm.h"
 
 namespace llmc {
 
-// compact token -> row of a [B*S, *] array through an optional sequence list
-__device__ __forceinline__ int64_t map_row(const int32_t* rows, int r, int S) {
-  if (!rows) return r;
-  const int q = r / S;
-  return (int64_t)rows[q] * S + (r - q * S);
-}
-
-__device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752440f)); }
-__device__ __forceinline__ float gelu_tanh(float x) {
-  const float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
-  return 0.5f * x * (1.0f + tanhf(u));
-}
-
-struct GemmArgs {
-  const void* A; int lda;          // [rows, K]
-  const void* W;                   // [N, K]
-  const void* bias;                // [N] or null
-  const void* resid; int ldr;      // [rows, N] or null
-  void* out; int ldo;              // [rows, N]
-  int N, K, S;
-  const int32_t* count;            // device: number of sequences; null = max_seqs
-  int max_seqs;
-  const int32_t* a_rows;           // sequence list applied to A rows, or null
-  const int32_t* r_rows;           // ... to residual rows
-  const int32_t* o_rows;           // ... to output rows
-  int act;                         // 0 none, 1 GELU erf, 2 GELU tanh
-};
-
-__device__ __forceinline__ float apply_act(float v, int act) {
-  if (act == 1) return gelu_erf(v);
-  if (act == 2) return gelu_tanh(v);
-  return v;
-}
-
-// ---- bf16 GEMM on the matrix cores -------------------------------------------------------
 typedef MmaCfg<128, 128, 32, 2, 2> GemmCfg;
-
-__global__ __launch_bounds__(GemmCfg::THREADS) void gemm_bf16_kernel(GemmArgs g, int tiles_n) {
-  using C = GemmCfg;
-  __shared__ __attribute__((aligned(16))) uint16_t lds[C::LDS_BYTES / 2];
-  const int n_seq = g.count ? min(*g.count, g.max_seqs) : g.max_seqs;
-  const int M = n_seq * g.S;
-  const int tile_m = blockIdx.x / tiles_n, tile_n = blockIdx.x % tiles_n;
-  const int m0 = tile_m * C::BM, n0 = tile_n * C::BN;
-  if (m0 >= M) return;
-  const int tid = threadIdx.x;
-  const uint16_t* A = (const uint16_t*)g.A;
-  const uint16_t* W = (const uint16_t*)g.W;
-  const uint16_t* a_ptr[C::NLOAD_A];
-  const uint16_t* b_ptr[C::NLOAD_B];
-#pragma unroll
-  for (int i = 0; i < C::NLOAD_A; ++i) {
-    const int v = tid + i * C::THREADS;
-    const int r = min(m0 + v / C::VEC_PER_ROW, M - 1);
-    a_ptr[i] = A + map_row(g.a_rows, r, g.S) * g.lda + (v % C::VEC_PER_ROW) * 8;
-  }
-#pragma unroll
-  for (int i = 0; i < C::NLOAD_B; ++i) {
-    const int v = tid + i * C::THREADS;
-    const int r = min(n0 + v / C::VEC_PER_ROW, g.N - 1);
-    b_ptr[i] = W + (size_t)r * g.K + (v % C::VEC_PER_ROW) * 8;
-  }
-  f32x16_t acc[C::FM][C::FN];
-#pragma unroll
-  for (int i = 0; i < C::FM; ++i)
-#pragma unroll
-    for (int j = 0; j < C::FN; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-  mma_block<C>(a_ptr, b_ptr, g.K, lds, acc);
-
-  const int lane = tid & 63, wave = tid >> 6;
-  const int wm = wave / C::WN, wn = wave % C::WN;
-  const uint16_t* bias = (const uint16_t*)g.bias;
-  const uint16_t* resid = (const uint16_t*)g.resid;
-  uint16_t* out = (uint16_t*)g.out;
-#pragma unroll
-  for (int j = 0; j < C::FN; ++j) {
-    const int n = n0 + wn * (C::BN / C::WN) + j * 32 + (lane & 31);
-    if (n >= g.N) continue;
-    const float bv = bias ? bf16_to_f32(bias[n]) : 0.f;
-#pragma unroll
-    for (int i = 0; i < C::FM; ++i) {
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int m = m0 + wm * (C::BM / C::WM) + i * 32 + frag_row(lane, r);
-        if (m >= M) continue;
-        float v = apply_act(acc[i][j][r] + bv, g.act);
-        if (resid) v += bf16_to_f32(resid[map_row(g.r_rows, m, g.S) * g.ldr + n]);
-        out[map_row(g.o_rows, m, g.S) * g.ldo + n] = f32_to_bf16(v);
-      }
-    }
-  }
-}
 
 // ---- fp32 GEMM, plain FMA: 64x64 tile, 16-wide k step, 4x4 outputs per thread ------------------
 __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmArgs g, int tiles_n) {
@@ -166,15 +73,36 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmArgs g, int tiles_n) 
   }
 }
 
+// 128 x 128 block, 8 wavefronts (2 x 4), ring of four 64-column stages filled by direct-to-LDS loads
+typedef DmaCfg<128, 128, 2, 4, 4> GemmDmaCfg;
+
 static llmc_status_t launch_gemm(const GemmArgs& g, int dtype, hipStream_t st) {
   if (dtype == LLMC_BF16) {
-    const int tiles_n = (g.N + GemmCfg::BN - 1) / GemmCfg::BN;
-    const int tiles_m = (g.max_seqs * g.S + GemmCfg::BM - 1) / GemmCfg::BM;
-    { ProfScope ps_("gemm_bf16_kernel", st); hipLaunchKernelGGL(gemm_bf16_kernel, dim3((unsigned)tiles_m * tiles_n), dim3(GemmCfg::THREADS), 0, st, g, tiles_n); }
+    if (g.K % 64 == 0) {
+      using C = GemmDmaCfg;
+      static bool attr_set = false;   // raising the dynamic-LDS limit is a per-function setting, done once
+      if (!attr_set) {
+        LLMC_HIP(hipFuncSetAttribute((const void*)gemm_bf16_dma_kernel<C>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                     (int)C::LDS_BYTES));
+        attr_set = true;
+      }
+      const int tiles_n = (g.N + C::BN - 1) / C::BN;
+      const int tiles_m = (g.max_seqs * g.S + C::BM - 1) / C::BM;
+      ProfScope ps_("gemm_bf16_kernel", st);
+      hipLaunchKernelGGL(gemm_bf16_dma_kernel<C>, dim3((unsigned)tiles_m * tiles_n), dim3(C::THREADS), C::LDS_BYTES, st,
+                         g, tiles_n);
+    } else {
+      const int tiles_n = (g.N + GemmCfg::BN - 1) / GemmCfg::BN;
+      const int tiles_m = (g.max_seqs * g.S + GemmCfg::BM - 1) / GemmCfg::BM;
+      ProfScope ps_("gemm_bf16_kernel", st);
+      hipLaunchKernelGGL(gemm_bf16_kernel<GemmCfg>, dim3((unsigned)tiles_m * tiles_n), dim3(GemmCfg::THREADS), 0, st, g,
+                         tiles_n);
+    }
   } else {
     const int tiles_n = (g.N + 63) / 64;
     const int tiles_m = (g.max_seqs * g.S + 63) / 64;
-    { ProfScope ps_("gemm_f32_kernel", st); hipLaunchKernelGGL(gemm_f32_kernel, dim3((unsigned)tiles_m * tiles_n), dim3(256), 0, st, g, tiles_n); }
+    ProfScope ps_("gemm_f32_kernel", st);
+    hipLaunchKernelGGL(gemm_f32_kernel, dim3((unsigned)tiles_m * tiles_n), dim3(256), 0, st, g, tiles_n);
   }
   LLMC_LAUNCH_CHECK("gemm");
   return LLMC_OK;

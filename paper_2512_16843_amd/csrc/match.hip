@@ -128,6 +128,155 @@ __global__ __launch_bounds__(MatchCfg::THREADS) void match_bf16_kernel(
   }
 }
 
+// ---- streaming variant: queries stay in registers, the bank streams through LDS ------------------
+// A workgroup of 8 wavefronts owns 512 query columns (64 per wavefront, held as B-operand
+// fragments in registers for the whole kernel) and walks a range of 64-row bank tiles.  Tiles
+// arrive by direct global -> LDS loads into a ring of stages; all wavefronts read the same
+// bank fragments from LDS, so LDS traffic is one tile read per wavefront and no query is ever
+// re-fetched.  Rows of a tile are 2*K bytes; their 16-byte chunks are XOR-swizzled by the row
+// number so that the 16-byte fragment reads of 16 consecutive rows fall on distinct banks.
+template <int K_>
+struct StreamCfg {
+  static constexpr int K = K_, KS = K / 16, CHUNKS = K / 8, ROWB = K * 2;
+  static constexpr int NW = 8, THREADS = NW * 64, FM = 2, FN = 2;
+  static constexpr int RB = FM * 32;                 // bank rows per tile
+  static constexpr int QW = FN * 32, QB = NW * QW;   // queries per wavefront / workgroup
+  static constexpr int ROWS_PER_INSTR = 1024 / ROWB; // tile rows filled by one wavefront load
+  static constexpr int L = RB / ROWS_PER_INSTR / NW + 1;   // loads per lane per stage: tile blocks + the norms
+  static constexpr int TILE_ELEMS = RB * K;
+  static constexpr int STAGE_ELEMS = TILE_ELEMS + NW * RB * 2;   // + one fp32 copy of the tile's inverse norms per wavefront
+  static constexpr int STAGES = (K >= 256) ? 4 : 3;
+  static constexpr size_t LDS_BYTES = (size_t)STAGES * STAGE_ELEMS * 2;
+  static_assert(K == 64 || K == 128 || K == 256, "supported key lengths");
+  static_assert(L >= 2 && (RB / ROWS_PER_INSTR) % NW == 0 && RB == 64, "load tiling");
+  __device__ static __forceinline__ int swz(int row) { return ROWB >= 256 ? (row & 15) : ((row >> 1) & 7); }
+};
+
+// grid: 1-D, see launch_match for the workgroup -> (split, query block) map
+template <int K_>
+__global__ __launch_bounds__(StreamCfg<K_>::THREADS) void match_stream_kernel(
+    const uint16_t* __restrict__ bank, const float* __restrict__ binv_eff, int N, const uint16_t* __restrict__ queries,
+    int B, int n_qb, int n_split, int tiles_per_split, Top2* __restrict__ partial) {
+  using C = StreamCfg<K_>;
+  extern __shared__ __attribute__((aligned(16))) uint16_t lds_dyn[];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  // workgroups are dealt round-robin to the 8 XCDs: keep the query blocks of one bank split on
+  // one XCD and adjacent in time, so that its L2 serves the bank tiles to all of them
+  const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
+  const int split = (local / n_qb) * 8 + xcd, qb = local % n_qb;
+  if (split >= n_split) return;
+  const int n_tiles = (N + C::RB - 1) / C::RB;
+  const int t_begin = split * tiles_per_split;
+  const int t_end = min(n_tiles, t_begin + tiles_per_split);
+  const int q_base = qb * C::QB + wave * C::QW;
+
+  // this lane's part of every load of a stage: tile row and (swizzled) chunk
+  int ld_row[C::L - 1], ld_off[C::L - 1];
+#pragma unroll
+  for (int j = 0; j < C::L - 1; ++j) {
+    const int blk = j * C::NW + wave;                       // 1 KiB block of the stage
+    const int row = blk * C::ROWS_PER_INSTR + lane / C::CHUNKS;
+    ld_row[j] = row;
+    ld_off[j] = ((lane % C::CHUNKS) ^ C::swz(row)) * 8;
+  }
+  auto issue = [&](int t) {
+    uint16_t* st = lds_dyn + ((t - t_begin) % C::STAGES) * C::STAGE_ELEMS;
+#pragma unroll
+    for (int j = 0; j < C::L - 1; ++j) {
+      const int r = min(t * C::RB + ld_row[j], N - 1);
+      __builtin_amdgcn_global_load_lds(LLMC_GPTR(bank + (size_t)r * C::K + ld_off[j]),
+                                       LLMC_LPTR(st + (j * C::NW + wave) * 512), 16, 0, 0);
+    }
+    // the tile's 64 inverse norms (the mirror is padded with NaN past N), one private copy per wavefront
+    __builtin_amdgcn_global_load_lds(LLMC_GPTR(binv_eff + (size_t)t * C::RB + lane),
+                                     LLMC_LPTR(st + C::TILE_ELEMS + wave * C::RB * 2), 4, 0, 0);
+  };
+#pragma unroll
+  for (int s = 0; s < C::STAGES - 1; ++s)
+    if (t_begin + s < t_end) issue(t_begin + s);
+
+  // query fragments: column (lane % 32) of fragment j, k = ks * 16 + (lane / 32) * 8 .. + 8
+  bf16x8_t bq[C::FN][C::KS];
+#pragma unroll
+  for (int j = 0; j < C::FN; ++j) {
+    const int q = min(q_base + j * 32 + (lane & 31), B - 1);
+    const uint16_t* qp = queries + (size_t)q * C::K + (lane >> 5) * 8;
+#pragma unroll
+    for (int ks = 0; ks < C::KS; ++ks) bq[j][ks] = *reinterpret_cast<const bf16x8_t*>(qp + ks * 16);
+  }
+  Top2 best[C::FN];
+#pragma unroll
+  for (int j = 0; j < C::FN; ++j) best[j] = top2_empty();
+  const int frag_off = (lane & 31) * C::K;
+  const int fsw = C::swz(lane & 31), half = lane >> 5;
+
+  for (int t = t_begin; t < t_end; ++t) {
+    const int ahead = min(C::STAGES - 2, t_end - 1 - t);
+    if (ahead <= 0) LLMC_WAIT_VM(0);
+    else if (ahead == 1) LLMC_WAIT_VM(C::L);
+    else LLMC_WAIT_VM(2 * C::L);
+    dma::barrier();
+    if (t + C::STAGES - 1 < t_end) issue(t + C::STAGES - 1);
+    const uint16_t* stage = lds_dyn + ((t - t_begin) % C::STAGES) * C::STAGE_ELEMS;
+    const uint16_t* st = stage + frag_off;
+    const float* sbinv = reinterpret_cast<const float*>(stage + C::TILE_ELEMS + wave * C::RB * 2);
+    f32x16_t acc[C::FM][C::FN];
+#pragma unroll
+    for (int i = 0; i < C::FM; ++i)
+#pragma unroll
+      for (int j = 0; j < C::FN; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < C::KS; ++ks) {
+      bf16x8_t fa[C::FM];
+#pragma unroll
+      for (int i = 0; i < C::FM; ++i)
+        fa[i] = *reinterpret_cast<const bf16x8_t*>(st + i * 32 * C::K + (((ks * 2 + half) ^ fsw) * 8));
+#pragma unroll
+      for (int i = 0; i < C::FM; ++i)
+#pragma unroll
+        for (int j = 0; j < C::FN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], bq[j][ks], acc[i][j], 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < C::FM; ++i) {
+      const int rb = t * C::RB + i * 32;
+      const int g = (rb >> 5) * 2 + half;
+      float bi[16];
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const float4 v4 = *reinterpret_cast<const float4*>(sbinv + i * 32 + half * 4 + 8 * c);
+        bi[4 * c] = v4.x; bi[4 * c + 1] = v4.y; bi[4 * c + 2] = v4.z; bi[4 * c + 3] = v4.w;
+      }
+#pragma unroll
+      for (int j = 0; j < C::FN; ++j) {
+        float mx = acc[i][j][0] * bi[0];
+#pragma unroll
+        for (int r = 1; r < 16; ++r) mx = fmaxf(mx, acc[i][j][r] * bi[r]);
+        if (mx > best[j].v1) {
+          best[j].v2 = best[j].v1; best[j].g2 = best[j].g1; best[j].v1 = mx; best[j].g1 = g;
+        } else if (mx > best[j].v2) {
+          best[j].v2 = mx; best[j].g2 = g;
+        }
+      }
+    }
+  }
+  // the two lane halves saw different rows of the same query column
+#pragma unroll
+  for (int j = 0; j < C::FN; ++j) {
+    Top2 o;
+    o.v1 = __shfl_xor(best[j].v1, 32, 64); o.g1 = __shfl_xor(best[j].g1, 32, 64);
+    o.v2 = __shfl_xor(best[j].v2, 32, 64); o.g2 = __shfl_xor(best[j].g2, 32, 64);
+    Top2 m = best[j];
+    top2_push(m, o.v1, o.g1);
+    top2_push(m, o.v2, o.g2);
+    const int q = q_base + j * 32 + (lane & 31);
+    if (half == 0 && q < B) partial[(size_t)split * B + q] = m;
+  }
+}
+
 // fp32 keys: plain FMA.  grid (B); thread t scans groups t, t + 256, ...
 __global__ __launch_bounds__(256) void match_f32_kernel(const float* __restrict__ bank,
                                                         const float* __restrict__ binv_eff, int N, int K,
@@ -227,11 +376,51 @@ static void split_plan(int N, int B, int* n_split, int* tiles_per_split) {
   *n_split = (tiles + per - 1) / per;
 }
 
+// streaming kernel: about four workgroups per compute unit, at most 1024 splits
+static void stream_plan(int N, int B, int RB, int QB, int* n_qb, int* n_split, int* tiles_per_split) {
+  const int tiles = (N + RB - 1) / RB;
+  const int qb = (B + QB - 1) / QB;
+  int want = (1024 + qb - 1) / qb;
+  if (want > tiles) want = tiles;
+  if (want > 1024) want = 1024;
+  if (want < 1) want = 1;
+  const int per = (tiles + want - 1) / want;
+  *n_qb = qb;
+  *tiles_per_split = per;
+  *n_split = (tiles + per - 1) / per;
+}
+
+static bool use_stream(int k) { return k == 64 || k == 128 || k == 256; }
+
 size_t match_ws_bytes(int n_slots, int k, int dtype, int B) {
-  (void)k;
-  int ns = 1, per = 1;
-  if (dtype == LLMC_BF16) split_plan(n_slots, B, &ns, &per);
+  int ns = 1, per = 1, nqb = 1;
+  if (dtype == LLMC_BF16) {
+    if (use_stream(k)) stream_plan(n_slots, B, 64, 512, &nqb, &ns, &per);
+    else split_plan(n_slots, B, &ns, &per);
+  }
   return align_up((size_t)ns * B * sizeof(Top2), 256);
+}
+
+template <int K_>
+static llmc_status_t launch_stream(const llmc_bank* bank, const void* d_fp, int B, Top2* partial, int* ns_out,
+                                   hipStream_t st) {
+  using C = StreamCfg<K_>;
+  const llmc_bank_desc_t& D = bank->desc;
+  static bool attr_set = false;
+  if (!attr_set) {
+    LLMC_HIP(hipFuncSetAttribute((const void*)match_stream_kernel<K_>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                 (int)C::LDS_BYTES));
+    attr_set = true;
+  }
+  int nqb, ns, per;
+  stream_plan(D.n_slots, B, C::RB, C::QB, &nqb, &ns, &per);
+  const int groups = (ns + 7) / 8;                 // splits are dealt to the 8 XCDs
+  const unsigned grid = (unsigned)groups * nqb * 8;
+  ProfScope ps_("match_stream_kernel", st);
+  hipLaunchKernelGGL(match_stream_kernel<K_>, dim3(grid), dim3(C::THREADS), C::LDS_BYTES, st, (const uint16_t*)D.d_fp,
+                     bank->d_binv_eff, D.n_slots, (const uint16_t*)d_fp, B, nqb, ns, per, partial);
+  *ns_out = ns;
+  return LLMC_OK;
 }
 
 llmc_status_t launch_match(const llmc_bank* bank, const void* d_fp, const float* d_inv, int B, float tau,
@@ -242,11 +431,18 @@ llmc_status_t launch_match(const llmc_bank* bank, const void* d_fp, const float*
   Top2* partial = (Top2*)ws;
   int ns = 1, per = 1;
   if (D.dtype == LLMC_BF16) {
-    split_plan(N, B, &ns, &per);
-    dim3 grid(ns, (B + MatchCfg::BN - 1) / MatchCfg::BN);
-    { ProfScope ps_("match_bf16_kernel", st); hipLaunchKernelGGL(match_bf16_kernel, grid, dim3(MatchCfg::THREADS), 0, st, (const uint16_t*)D.d_fp,
-                       bank->d_binv_eff, N, K, (const uint16_t*)d_fp, B, per, partial); }
-    LLMC_LAUNCH_CHECK("match_bf16_kernel");
+    if (use_stream(K)) {
+      if (K == 256) LLMC_TRY(launch_stream<256>(bank, d_fp, B, partial, &ns, st));
+      else if (K == 128) LLMC_TRY(launch_stream<128>(bank, d_fp, B, partial, &ns, st));
+      else LLMC_TRY(launch_stream<64>(bank, d_fp, B, partial, &ns, st));
+      LLMC_LAUNCH_CHECK("match_stream_kernel");
+    } else {
+      split_plan(N, B, &ns, &per);
+      dim3 grid(ns, (B + MatchCfg::BN - 1) / MatchCfg::BN);
+      { ProfScope ps_("match_bf16_kernel", st); hipLaunchKernelGGL(match_bf16_kernel, grid, dim3(MatchCfg::THREADS), 0, st, (const uint16_t*)D.d_fp,
+                         bank->d_binv_eff, N, K, (const uint16_t*)d_fp, B, per, partial); }
+      LLMC_LAUNCH_CHECK("match_bf16_kernel");
+    }
     { ProfScope ps_("match_finalize_kernel", st); hipLaunchKernelGGL((match_finalize_kernel<bf16_t>), dim3((B + 3) / 4), dim3(256), 0, st, partial, ns,
                        (const bf16_t*)D.d_fp, D.d_inv_norm, D.d_valid, N, K, (const bf16_t*)d_fp, d_inv, B, tau, d_idx,
                        d_sim, d_hit, d_near_tie); }

@@ -25,7 +25,7 @@ template <int BM_, int BN_, int BK_, int WM_, int WN_>
 struct MmaCfg {
   static constexpr int BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_;
   static constexpr int THREADS = WM * WN * 64;
-  static constexpr int LDS_STRIDE = BK + 8;             // bf16 elements; +16 B keeps 16-lane groups on distinct banks
+  static constexpr int LDS_STRIDE = BK + 8;             // bf16 elements; +16 B keeps 8- and 16-lane groups on distinct banks
   static constexpr int FM = BM / WM / 32, FN = BN / WN / 32;
   static constexpr int VEC_PER_ROW = BK / 8;
   static constexpr int NLOAD_A = BM * VEC_PER_ROW / THREADS;
@@ -39,6 +39,7 @@ struct MmaCfg {
 
 // a_ptr[i] / b_ptr[i]: global address of this thread's i-th 16-byte vector at k = 0
 // (row already resolved and clamped by the caller).  K must be a multiple of BK.
+// On return every wavefront has passed a barrier after its last LDS read.
 template <class C>
 __device__ __forceinline__ void mma_block(const uint16_t* const (&a_ptr)[C::NLOAD_A],
                                           const uint16_t* const (&b_ptr)[C::NLOAD_B], int K, uint16_t* lds,
@@ -73,6 +74,7 @@ __device__ __forceinline__ void mma_block(const uint16_t* const (&a_ptr)[C::NLOA
 
   const int a_read = (wm * (C::BM / C::WM) + (lane & 31)) * C::LDS_STRIDE + (lane >> 5) * 8;
   const int b_read = (wn * (C::BN / C::WN) + (lane & 31)) * C::LDS_STRIDE + (lane >> 5) * 8;
+  constexpr int KS = C::BK / 16;
   const int nk = K / C::BK;
   for (int kt = 0; kt < nk; ++kt) {
     const int cur = kt & 1;
@@ -84,20 +86,29 @@ __device__ __forceinline__ void mma_block(const uint16_t* const (&a_ptr)[C::NLOA
 #pragma unroll
       for (int i = 0; i < C::NLOAD_B; ++i) rb[i] = *reinterpret_cast<const uint4*>(b_ptr[i] + ko);
     }
+    const uint16_t* pa = sA[cur] + a_read;
+    const uint16_t* pb = sB[cur] + b_read;
+    bf16x8_t fa[2][C::FM], fb[2][C::FN];
 #pragma unroll
-    for (int ks = 0; ks < C::BK / 16; ++ks) {
-      bf16x8_t fa[C::FM], fb[C::FN];
+    for (int i = 0; i < C::FM; ++i) fa[0][i] = *reinterpret_cast<const bf16x8_t*>(pa + i * 32 * C::LDS_STRIDE);
 #pragma unroll
-      for (int i = 0; i < C::FM; ++i)
-        fa[i] = *reinterpret_cast<const bf16x8_t*>(sA[cur] + a_read + i * 32 * C::LDS_STRIDE + ks * 16);
+    for (int j = 0; j < C::FN; ++j) fb[0][j] = *reinterpret_cast<const bf16x8_t*>(pb + j * 32 * C::LDS_STRIDE);
 #pragma unroll
-      for (int j = 0; j < C::FN; ++j)
-        fb[j] = *reinterpret_cast<const bf16x8_t*>(sB[cur] + b_read + j * 32 * C::LDS_STRIDE + ks * 16);
+    for (int ks = 0; ks < KS; ++ks) {
+      const int c = ks & 1, n = c ^ 1;
+      if (ks + 1 < KS) {
+#pragma unroll
+        for (int i = 0; i < C::FM; ++i)
+          fa[n][i] = *reinterpret_cast<const bf16x8_t*>(pa + i * 32 * C::LDS_STRIDE + (ks + 1) * 16);
+#pragma unroll
+        for (int j = 0; j < C::FN; ++j)
+          fb[n][j] = *reinterpret_cast<const bf16x8_t*>(pb + j * 32 * C::LDS_STRIDE + (ks + 1) * 16);
+      }
 #pragma unroll
       for (int i = 0; i < C::FM; ++i)
 #pragma unroll
         for (int j = 0; j < C::FN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[c][i], fb[c][j], acc[i][j], 0, 0, 0);
     }
     if (more) {
 #pragma unroll
@@ -107,6 +118,107 @@ __device__ __forceinline__ void mma_block(const uint16_t* const (&a_ptr)[C::NLOA
     }
     __syncthreads();
   }
+}
+
+// ---------------------------------------------------------------------------------------
+// Main loop with direct global -> LDS loads (global_load_lds_dwordx4) and a ring of
+// STAGES tile buffers, so that STAGES - 1 tiles of 64 k-columns are in flight while one is
+// being multiplied.  No registers are spent on staging.
+//
+// One load instruction of a wavefront fills 8 tile rows of 128 bytes: lane i writes the
+// 16-byte slot i of that 1 KiB block.  To keep the later 16-byte fragment reads free of
+// bank conflicts the 16-byte chunks of a row are stored XOR-swizzled: chunk c of tile row
+// r lives in slot c ^ (r % 8) of its row.  The permutation is applied on the global side
+// (each lane chooses which chunk it fetches).
+//
+// The compiler does not order these loads against LDS reads, so ordering is explicit:
+// s_waitcnt vmcnt(n) for the wave's own loads, then a workgroup barrier.
+namespace dma {
+#define LLMC_GPTR(p) ((const void __attribute__((address_space(1)))*)(p))
+#define LLMC_LPTR(p) ((void __attribute__((address_space(3)))*)(p))
+#define LLMC_WAIT_VM(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
+
+__device__ __forceinline__ void barrier() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
+}  // namespace dma
+
+template <int BM_, int BN_, int WM_, int WN_, int STAGES_>
+struct DmaCfg {
+  static constexpr int BM = BM_, BN = BN_, BK = 64, WM = WM_, WN = WN_, STAGES = STAGES_;
+  static constexpr int NW = WM * WN, THREADS = NW * 64;
+  static constexpr int FM = BM / WM / 32, FN = BN / WN / 32;
+  static constexpr int A_INSTR = BM / 8 / NW, B_INSTR = BN / 8 / NW;     // loads per lane per stage
+  static constexpr int L = A_INSTR + B_INSTR;
+  static constexpr int STAGE_ELEMS = (BM + BN) * BK;
+  static constexpr size_t LDS_BYTES = (size_t)STAGES * STAGE_ELEMS * 2;
+  static_assert(BM % (WM * 32) == 0 && BN % (WN * 32) == 0, "wave tiling");
+  static_assert((BM / 8) % NW == 0 && (BN / 8) % NW == 0, "load tiling");
+  static_assert(STAGES >= 2 && STAGES <= 4 && 3 * L <= 63, "pipeline depth");
+  // tile row and k-chunk fetched by `lane` of `wave` in its j-th load of a stage
+  __device__ static __forceinline__ int load_row(int j, int wave, int lane) { return (j * NW + wave) * 8 + (lane >> 3); }
+  __device__ static __forceinline__ int load_chunk(int row, int lane) { return (lane & 7) ^ (row & 7); }
+};
+
+// a_ptr[j] / b_ptr[j]: global address (k = 0) of the 16-byte chunk that this lane fetches in
+// its j-th A / B load: row load_row(j, wave, lane) of the tile (resolved and clamped by the
+// caller), element offset load_chunk(row, lane) * 8.  K must be a multiple of 64.
+template <class C>
+__device__ __forceinline__ void mma_block_dma(const uint16_t* const (&a_ptr)[C::A_INSTR],
+                                              const uint16_t* const (&b_ptr)[C::B_INSTR], int K, uint16_t* lds,
+                                              f32x16_t (&acc)[C::FM][C::FN]) {
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wm = wave / C::WN, wn = wave % C::WN;
+  const int nk = K / C::BK;
+
+  auto issue = [&](int kt) {
+    uint16_t* st = lds + (kt % C::STAGES) * C::STAGE_ELEMS;
+    const int ko = kt * C::BK;
+#pragma unroll
+    for (int j = 0; j < C::A_INSTR; ++j)
+      __builtin_amdgcn_global_load_lds(LLMC_GPTR(a_ptr[j] + ko), LLMC_LPTR(st + (j * C::NW + wave) * 8 * C::BK), 16, 0, 0);
+#pragma unroll
+    for (int j = 0; j < C::B_INSTR; ++j)
+      __builtin_amdgcn_global_load_lds(LLMC_GPTR(b_ptr[j] + ko),
+                                       LLMC_LPTR(st + C::BM * C::BK + (j * C::NW + wave) * 8 * C::BK), 16, 0, 0);
+  };
+#pragma unroll
+  for (int s = 0; s < C::STAGES - 1; ++s)
+    if (s < nk) issue(s);
+
+  // fragment read offsets (elements): row * 64 + ((chunk ^ (row & 7)) * 8), row & 7 == lane & 7
+  const int a_row = (wm * (C::BM / C::WM) + (lane & 31)) * C::BK;
+  const int b_row = C::BM * C::BK + (wn * (C::BN / C::WN) + (lane & 31)) * C::BK;
+  int sw[4];
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) sw[ks] = (((ks * 2 + (lane >> 5)) ^ (lane & 7)) * 8);
+
+  for (int kt = 0; kt < nk; ++kt) {
+    const int ahead = min(C::STAGES - 2, nk - 1 - kt);
+    if (ahead <= 0) LLMC_WAIT_VM(0);
+    else if (ahead == 1) LLMC_WAIT_VM(C::L);
+    else LLMC_WAIT_VM(2 * C::L);
+    dma::barrier();
+    if (kt + C::STAGES - 1 < nk) issue(kt + C::STAGES - 1);
+    const uint16_t* st = lds + (kt % C::STAGES) * C::STAGE_ELEMS;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      bf16x8_t fa[C::FM], fb[C::FN];
+#pragma unroll
+      for (int i = 0; i < C::FM; ++i) fa[i] = *reinterpret_cast<const bf16x8_t*>(st + a_row + i * 32 * C::BK + sw[ks]);
+#pragma unroll
+      for (int j = 0; j < C::FN; ++j) fb[j] = *reinterpret_cast<const bf16x8_t*>(st + b_row + j * 32 * C::BK + sw[ks]);
+#pragma unroll
+      for (int i = 0; i < C::FM; ++i)
+#pragma unroll
+        for (int j = 0; j < C::FN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+    }
+  }
+  dma::barrier();   // every wavefront is done reading before the caller reuses the LDS
 }
 
 }  // namespace llmc
