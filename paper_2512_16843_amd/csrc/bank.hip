@@ -110,7 +110,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(uint8_t* valid, con
 
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 constexpr int kCopyThreads = 256;
-constexpr int kCopyVecPerThread = 8;
+constexpr int kCopyVecPerThread = 4;
 
 // grid (chunks, m_max): entry i stores row r = rows[i] (or i) of fp / inv_norm / act into slots[i]
 __global__ __launch_bounds__(kCopyThreads) void insert_kernel(

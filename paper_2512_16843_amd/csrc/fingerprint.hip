@@ -8,12 +8,12 @@
 // rounds to the bank's element type and stores 1/|rounded key|.
 // Every reduction order depends on S, d and k only, so a sequence's key is the same
 // bits wherever it sits in whatever batch.
+#include <algorithm>
 #include "common.h"
 
 namespace llmc {
 
 constexpr int kTokChunk = 32;   // tokens per pooling workgroup
-constexpr int kProjSplit = 4;   // groups that split the d-loop of the projection
 
 static inline int pool_chunks(int S) { return (S + kTokChunk - 1) / kTokChunk; }
 
@@ -32,15 +32,16 @@ __global__ void pool_kernel(const T* __restrict__ h, int S, int d, int G, int R,
 #pragma unroll
   for (int i = 0; i < VEC; ++i) acc[i] = 0.f;
   int t = t0 + r;
-  // four rows in flight per thread, added in ascending token order
-  for (; t + 3 * R < t1; t += 4 * R) {
-    float v0[VEC], v1[VEC], v2[VEC], v3[VEC];
-    Vec16<T>::load(base + (size_t)t * d, v0);
-    Vec16<T>::load(base + (size_t)(t + R) * d, v1);
-    Vec16<T>::load(base + (size_t)(t + 2 * R) * d, v2);
-    Vec16<T>::load(base + (size_t)(t + 3 * R) * d, v3);
+  // eight rows in flight per thread, added in ascending token order
+  constexpr int U = 8;
+  for (; t + (U - 1) * R < t1; t += U * R) {
+    float v[U][VEC];
 #pragma unroll
-    for (int i = 0; i < VEC; ++i) acc[i] = (((acc[i] + v0[i]) + v1[i]) + v2[i]) + v3[i];
+    for (int u = 0; u < U; ++u) Vec16<T>::load(base + (size_t)(t + u * R) * d, v[u]);
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) acc[i] += v[u][i];
   }
   for (; t < t1; t += R) {
     float v0[VEC];
@@ -62,12 +63,13 @@ __global__ void pool_kernel(const T* __restrict__ h, int S, int d, int G, int R,
   }
 }
 
-// grid (B); block k * kProjSplit threads (k <= 256) -- thread (j, part) owns output j over a quarter of d
+// grid (B); block CG * PARTS threads: thread (cg, part) owns the four output columns 4*cg .. 4*cg+3
+// over the part-th slice of d; slices are then added in ascending order.
 template <typename T>
-__global__ void project_kernel(const float* __restrict__ partial, int n_chunks, int S, int d,
-                               const T* __restrict__ P, const float* __restrict__ bias, int k, int split,
-                               T* __restrict__ fp_out, float* __restrict__ inv_out) {
-  extern __shared__ float sm[];   // p[d] | v[split][k]
+__global__ __launch_bounds__(1024) void project_kernel(const float* __restrict__ partial, int n_chunks, int S, int d,
+                                                       const T* __restrict__ P, const float* __restrict__ bias, int k,
+                                                       int parts, T* __restrict__ fp_out, float* __restrict__ inv_out) {
+  extern __shared__ float sm[];   // p[d] | v[parts][k]
   float* p = sm;
   float* vpart = sm + d;
   __shared__ double wsum[16];
@@ -82,26 +84,60 @@ __global__ void project_kernel(const float* __restrict__ partial, int n_chunks, 
     p[i] = s * inv_S;
   }
   __syncthreads();
-  const int j = threadIdx.x % k, part = threadIdx.x / k;
   {
-    const int per = (d + split - 1) / split;
+    const int cgs = k / 4;
+    const int cg = threadIdx.x % cgs, part = threadIdx.x / cgs;
+    const int per = (d + parts - 1) / parts;
     const int i0 = part * per, i1 = min(d, i0 + per);
-    float v = 0.f;
-#pragma unroll 8
-    for (int i = i0; i < i1; ++i) v = fmaf(p[i], Elem<T>::load(P + (size_t)i * k + j), v);
-    vpart[part * k + j] = v;
+    float v[4] = {0.f, 0.f, 0.f, 0.f};
+    // sixteen rows of P in flight per thread; the sums run in ascending row order
+    constexpr int U = 16;
+    auto unpack = [](const T* src, float* w) {
+      if (sizeof(T) == 2) {
+        const uint2 u = *reinterpret_cast<const uint2*>(src);
+        w[0] = __uint_as_float(u.x << 16); w[1] = __uint_as_float(u.x & 0xFFFF0000u);
+        w[2] = __uint_as_float(u.y << 16); w[3] = __uint_as_float(u.y & 0xFFFF0000u);
+      } else {
+        const float4 u = *reinterpret_cast<const float4*>(src);
+        w[0] = u.x; w[1] = u.y; w[2] = u.z; w[3] = u.w;
+      }
+    };
+    const T* col = P + cg * 4;
+    int i = i0;
+    for (; i + U <= i1; i += U) {
+      float w[U][4];
+#pragma unroll
+      for (int u = 0; u < U; ++u) unpack(col + (size_t)(i + u) * k, w[u]);
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const float pi = p[i + u];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = fmaf(pi, w[u][e], v[e]);
+      }
+    }
+    for (; i < i1; ++i) {
+      float w[4];
+      unpack(col + (size_t)i * k, w);
+      const float pi = p[i];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) v[e] = fmaf(pi, w[e], v[e]);
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) vpart[part * k + cg * 4 + e] = v[e];
   }
   __syncthreads();
+  const int j = threadIdx.x;
+  const bool own = j < k;
   float v = 0.f;
-  if (part == 0) {
+  if (own) {
     v = vpart[j];
-    for (int s = 1; s < split; ++s) v += vpart[s * k + j];
+    for (int s = 1; s < parts; ++s) v += vpart[s * k + j];
     if (bias) v += bias[j];
   }
   // |v|^2 in fp64: lanes of each wave, then waves in order
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int n_waves_k = (k + 63) / 64;
-  double sq = (part == 0) ? (double)v * (double)v : 0.0;
+  double sq = own ? (double)v * (double)v : 0.0;
   sq = wave_sum(sq);
   if (lane == 0 && wave < 16) wsum[wave] = sq;
   __syncthreads();
@@ -113,11 +149,11 @@ __global__ void project_kernel(const float* __restrict__ partial, int n_chunks, 
   }
   __syncthreads();
   float q = 0.f;
-  if (part == 0) {
+  if (own) {
     q = Elem<T>::round(v * s_scale);
     Elem<T>::store(fp_out + (size_t)b * k + j, q);
   }
-  double sq2 = (part == 0) ? (double)q * (double)q : 0.0;
+  double sq2 = own ? (double)q * (double)q : 0.0;
   sq2 = wave_sum(sq2);
   __syncthreads();
   if (lane == 0 && wave < 16) wsum[wave] = sq2;
@@ -153,15 +189,20 @@ static llmc_status_t fingerprint_t(const T* h, int B, int S, int d, const T* P, 
                                    T* fp, float* inv, float* partial, hipStream_t st) {
   constexpr int VEC = Vec16<T>::N;
   const int G = d / VEC;
-  const int R = G >= 256 ? 1 : 256 / G;
+  const int R = G <= 512 ? 2 : 1;   // token rows split over thread groups; depends on d only
   const int n_chunks = pool_chunks(S);
   dim3 grid(n_chunks, B);
   { ProfScope ps_("pool_kernel", st); hipLaunchKernelGGL(pool_kernel<T>, grid, dim3(G * R), (size_t)R * d * sizeof(float), st, h, S, d, G, R, partial,
                      n_chunks); }
   LLMC_LAUNCH_CHECK("pool_kernel");
-  const int split = k <= 256 ? kProjSplit : (k <= 512 ? 2 : 1);
-  { ProfScope ps_("project_kernel", st); hipLaunchKernelGGL(project_kernel<T>, dim3(B), dim3(k * split), (size_t)(d + split * k) * sizeof(float), st,
-                     partial, n_chunks, S, d, P, bias, k, split, fp, inv); }
+  // slices of d per output column group; depends on k only.  k <= 1024 gives at least k threads.
+  const int cgs = k / 4;
+  const int parts = std::max(1, std::min(1024 / cgs, 16));
+  {
+    ProfScope ps_("project_kernel", st);
+    hipLaunchKernelGGL(project_kernel<T>, dim3(B), dim3(std::max(cgs * parts, k)),
+                       (size_t)(d + parts * k) * sizeof(float), st, partial, n_chunks, S, d, P, bias, k, parts, fp, inv);
+  }
   LLMC_LAUNCH_CHECK("project_kernel");
   return LLMC_OK;
 }

@@ -78,7 +78,7 @@ __global__ void all_miss_kernel(int B, int32_t* miss_rows, int32_t* counters, in
 // Copy of cached outputs: grid (chunks, n_max); every thread moves 16-byte vectors.
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 constexpr int kGatherThreads = 256;
-constexpr int kGatherVecPerThread = 8;   // 32 KiB per workgroup
+constexpr int kGatherVecPerThread = 4;   // 16 KiB per workgroup: the launch shape that streamed fastest
 
 __global__ __launch_bounds__(kGatherThreads) void gather_kernel(const u32x4_t* __restrict__ act, const int32_t* act_slot,
                                                                 const int32_t* __restrict__ idx,

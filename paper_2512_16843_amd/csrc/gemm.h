@@ -13,10 +13,25 @@ __device__ __forceinline__ int64_t map_row(const int32_t* rows, int r, int S) {
   return (int64_t)rows[q] * S + (r - q * S);
 }
 
-__device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752440f)); }
+// erf by the five-term rational approximation of Abramowitz & Stegun 7.1.26
+// (absolute error below 1.5e-7), with the hardware reciprocal and exponential
+__device__ __forceinline__ float erf_as(float x) {
+  const float ax = fabsf(x);
+  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, ax, 1.0f));
+  float p = fmaf(1.061405429f, t, -1.453152027f);
+  p = fmaf(p, t, 1.421413741f);
+  p = fmaf(p, t, -0.284496736f);
+  p = fmaf(p, t, 0.254829592f);
+  const float e = __expf(-ax * ax);
+  const float r = fmaf(-p * t, e, 1.0f);
+  return copysignf(r, x);
+}
+__device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.0f + erf_as(x * 0.70710678118654752440f)); }
 __device__ __forceinline__ float gelu_tanh(float x) {
   const float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
-  return 0.5f * x * (1.0f + tanhf(u));
+  // tanh(u) = 1 - 2 / (1 + e^{2u}); e^{2u} = inf gives 1, 0 gives -1
+  const float th = 1.0f - 2.0f * __builtin_amdgcn_rcpf(1.0f + __expf(2.0f * u));
+  return 0.5f * x * (1.0f + th);
 }
 
 struct GemmArgs {
@@ -74,10 +89,12 @@ __global__ __launch_bounds__(C::THREADS) void gemm_bf16_kernel(GemmArgs g, int t
   __shared__ __attribute__((aligned(16))) uint16_t lds[C::LDS_BYTES / 2];
   const int n_seq = g.count ? min(*g.count, g.max_seqs) : g.max_seqs;
   const int M = n_seq * g.S;
-  const int tile_m = blockIdx.x / tiles_n, tile_n = blockIdx.x % tiles_n;
-  const int m0 = tile_m * C::BM, n0 = tile_n * C::BN;
-  if (m0 >= M) return;
+  const int total = ((M + C::BM - 1) / C::BM) * tiles_n;
   const int tid = threadIdx.x;
+  // the grid is capped: a workgroup walks tiles blockIdx.x, blockIdx.x + gridDim.x, ...
+  for (int tile = blockIdx.x; tile < total; tile += gridDim.x) {
+  const int tile_m = tile / tiles_n, tile_n = tile % tiles_n;
+  const int m0 = tile_m * C::BM, n0 = tile_n * C::BN;
   const uint16_t* A = (const uint16_t*)g.A;
   const uint16_t* W = (const uint16_t*)g.W;
   const uint16_t* a_ptr[C::NLOAD_A];
@@ -102,8 +119,65 @@ __global__ __launch_bounds__(C::THREADS) void gemm_bf16_kernel(GemmArgs g, int t
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
   mma_block<C>(a_ptr, b_ptr, g.K, lds, acc);
-
   gemm_epilogue<C>(g, acc, m0, n0, M);
+  }
+}
+
+// Epilogue through LDS: the accumulators are laid out as an fp32 [BM][BN + 8] block, then every
+// thread takes 8 consecutive columns of a row, so that bias, residual and output move as
+// 16-byte vectors along rows.  `stage` must hold BM * (BN + 8) floats and be free of readers.
+template <class C>
+__device__ __forceinline__ void gemm_epilogue_lds(const GemmArgs& g, f32x16_t (&acc)[C::FM][C::FN], int m0, int n0,
+                                                  int M, float* stage) {
+  constexpr int STRIDE = C::BN + 8;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / C::WN, wn = wave % C::WN;
+#pragma unroll
+  for (int i = 0; i < C::FM; ++i)
+#pragma unroll
+    for (int j = 0; j < C::FN; ++j) {
+      float* p = stage + (wm * (C::BM / C::WM) + i * 32) * STRIDE + wn * (C::BN / C::WN) + j * 32 + (lane & 31);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) p[frag_row(lane, r) * STRIDE] = acc[i][j][r];
+    }
+  __syncthreads();
+  const uint16_t* bias = (const uint16_t*)g.bias;
+  const uint16_t* resid = (const uint16_t*)g.resid;
+  uint16_t* out = (uint16_t*)g.out;
+  constexpr int GROUPS_PER_ROW = C::BN / 8;
+  for (int idx = tid; idx < C::BM * GROUPS_PER_ROW; idx += C::THREADS) {
+    const int row = idx / GROUPS_PER_ROW, c8 = (idx % GROUPS_PER_ROW) * 8;
+    const int m = m0 + row, n = n0 + c8;
+    if (m >= M || n >= g.N) continue;
+    float v[8];
+    const float4 lo = *reinterpret_cast<const float4*>(stage + row * STRIDE + c8);
+    const float4 hi = *reinterpret_cast<const float4*>(stage + row * STRIDE + c8 + 4);
+    v[0] = lo.x; v[1] = lo.y; v[2] = lo.z; v[3] = lo.w; v[4] = hi.x; v[5] = hi.y; v[6] = hi.z; v[7] = hi.w;
+    if (bias) {
+      float b[8];
+      Vec16<bf16_t>::load(reinterpret_cast<const bf16_t*>(bias + n), b);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] += b[e];
+    }
+    if (g.act) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] = apply_act(v[e], g.act);
+    }
+    if (resid) {
+      float rr[8];
+      Vec16<bf16_t>::load(reinterpret_cast<const bf16_t*>(resid + map_row(g.r_rows, m, g.S) * g.ldr + n), rr);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] += rr[e];
+    }
+    Vec16<bf16_t>::store(reinterpret_cast<bf16_t*>(out + map_row(g.o_rows, m, g.S) * g.ldo + n), v);
+  }
+  __syncthreads();
+}
+
+template <class C>
+constexpr size_t gemm_dma_smem_bytes() {
+  return C::LDS_BYTES > (size_t)C::BM * (C::BN + 8) * 4 ? C::LDS_BYTES : (size_t)C::BM * (C::BN + 8) * 4;
 }
 
 // Same contract, main loop with direct global -> LDS loads (C is a DmaCfg); K % 64 == 0.
@@ -112,10 +186,11 @@ __global__ __launch_bounds__(C::THREADS) void gemm_bf16_dma_kernel(GemmArgs g, i
   extern __shared__ __attribute__((aligned(16))) uint16_t lds_dyn[];
   const int n_seq = g.count ? min(*g.count, g.max_seqs) : g.max_seqs;
   const int M = n_seq * g.S;
-  const int tile_m = blockIdx.x / tiles_n, tile_n = blockIdx.x % tiles_n;
-  const int m0 = tile_m * C::BM, n0 = tile_n * C::BN;
-  if (m0 >= M) return;
+  const int total = ((M + C::BM - 1) / C::BM) * tiles_n;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (int tile = blockIdx.x; tile < total; tile += gridDim.x) {
+  const int tile_m = tile / tiles_n, tile_n = tile % tiles_n;
+  const int m0 = tile_m * C::BM, n0 = tile_n * C::BN;
   const uint16_t* A = (const uint16_t*)g.A;
   const uint16_t* W = (const uint16_t*)g.W;
   const uint16_t* a_ptr[C::A_INSTR];
@@ -140,7 +215,8 @@ __global__ __launch_bounds__(C::THREADS) void gemm_bf16_dma_kernel(GemmArgs g, i
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
   mma_block_dma<C>(a_ptr, b_ptr, g.K, lds_dyn, acc);
-  gemm_epilogue<C>(g, acc, m0, n0, M);
+  gemm_epilogue_lds<C>(g, acc, m0, n0, M, reinterpret_cast<float*>(lds_dyn));
+  }
 }
 
 }  // namespace llmc

@@ -11,11 +11,18 @@
 // fp32 runs; LayerNorm with one wavefront per token; softmax attention with an online
 // softmax over 32-key tiles.
 #include "common.h"
+#include <algorithm>
 #include "gemm.h"
+#include "attention.h"
 
 namespace llmc {
 
 typedef MmaCfg<128, 128, 32, 2, 2> GemmCfg;
+
+// Launches are sized for the worst case (every sequence a miss) but capped: workgroups walk
+// their tiles / rows with a grid stride and read the real count on the device, so a layer
+// with few or no misses costs a small, fixed number of idle workgroups.
+constexpr int kMaxGrid = 512;
 
 // ---- fp32 GEMM, plain FMA: 64x64 tile, 16-wide k step, 4x4 outputs per thread ------------------
 __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmArgs g, int tiles_n) {
@@ -73,8 +80,9 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmArgs g, int tiles_n) 
   }
 }
 
-// 128 x 128 block, 8 wavefronts (2 x 4), ring of four 64-column stages filled by direct-to-LDS loads
-typedef DmaCfg<128, 128, 2, 4, 4> GemmDmaCfg;
+// 128 x 128 block, 8 wavefronts (2 x 4), two 64-column stages filled by direct-to-LDS loads: 68 KiB of LDS,
+// so two workgroups share a compute unit and one's epilogue overlaps the other's main loop
+typedef DmaCfg<128, 128, 2, 4, 2> GemmDmaCfg;
 
 static llmc_status_t launch_gemm(const GemmArgs& g, int dtype, hipStream_t st) {
   if (dtype == LLMC_BF16) {
@@ -83,20 +91,20 @@ static llmc_status_t launch_gemm(const GemmArgs& g, int dtype, hipStream_t st) {
       static bool attr_set = false;   // raising the dynamic-LDS limit is a per-function setting, done once
       if (!attr_set) {
         LLMC_HIP(hipFuncSetAttribute((const void*)gemm_bf16_dma_kernel<C>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                     (int)C::LDS_BYTES));
+                                     (int)gemm_dma_smem_bytes<C>()));
         attr_set = true;
       }
       const int tiles_n = (g.N + C::BN - 1) / C::BN;
       const int tiles_m = (g.max_seqs * g.S + C::BM - 1) / C::BM;
       ProfScope ps_("gemm_bf16_kernel", st);
-      hipLaunchKernelGGL(gemm_bf16_dma_kernel<C>, dim3((unsigned)tiles_m * tiles_n), dim3(C::THREADS), C::LDS_BYTES, st,
-                         g, tiles_n);
+      hipLaunchKernelGGL(gemm_bf16_dma_kernel<C>, dim3(std::min(tiles_m * tiles_n, kMaxGrid)), dim3(C::THREADS),
+                         gemm_dma_smem_bytes<C>(), st, g, tiles_n);
     } else {
       const int tiles_n = (g.N + GemmCfg::BN - 1) / GemmCfg::BN;
       const int tiles_m = (g.max_seqs * g.S + GemmCfg::BM - 1) / GemmCfg::BM;
       ProfScope ps_("gemm_bf16_kernel", st);
-      hipLaunchKernelGGL(gemm_bf16_kernel<GemmCfg>, dim3((unsigned)tiles_m * tiles_n), dim3(GemmCfg::THREADS), 0, st, g,
-                         tiles_n);
+      hipLaunchKernelGGL(gemm_bf16_kernel<GemmCfg>, dim3(std::min(tiles_m * tiles_n, kMaxGrid)), dim3(GemmCfg::THREADS),
+                         0, st, g, tiles_n);
     }
   } else {
     const int tiles_n = (g.N + 63) / 64;
@@ -117,10 +125,9 @@ __global__ __launch_bounds__(256) void layernorm_kernel(const T* __restrict__ in
   constexpr int VEC = Vec16<T>::N;
   const int n_seq = count ? min(*count, max_seqs) : max_seqs;
   const int M = n_seq * S;
-  const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (r >= M) return;
   const int lane = threadIdx.x & 63;
   const int nvec = d / VEC;
+  for (int r = blockIdx.x * 4 + (threadIdx.x >> 6); r < M; r += gridDim.x * 4) {
   const T* src = in + map_row(in_rows, r, S) * ld_in;
   float x[MAXV][VEC];
   float s = 0.f;
@@ -160,6 +167,7 @@ __global__ __launch_bounds__(256) void layernorm_kernel(const T* __restrict__ in
       Vec16<T>::store(dst + v * VEC, y);
     }
   }
+  }
 }
 
 template <typename T>
@@ -168,7 +176,7 @@ static llmc_status_t launch_ln(const void* in, const int32_t* in_rows, void* out
                                int max_seqs, hipStream_t st) {
   constexpr int VEC = Vec16<T>::N;
   const int nvec = d / VEC;
-  const unsigned blocks = (unsigned)((max_seqs * S + 3) / 4);
+  const unsigned blocks = (unsigned)std::min((max_seqs * S + 3) / 4, 2 * kMaxGrid);
 #define LN_CASE(MV)                                                                                     \
   {                                                                                                     \
     ProfScope ps_("layernorm_kernel", st);                                                              \
@@ -264,13 +272,28 @@ template <typename T>
 static llmc_status_t launch_attention(const void* qkv, void* ctx, int S, int d, int n_heads, bool causal,
                                       const int32_t* count, int max_seqs, hipStream_t st) {
   const float scale = 1.0f / sqrtf((float)(d / n_heads));
-  dim3 grid((S + 127) / 128, n_heads, max_seqs);
-  if (causal)
-    { ProfScope ps_("attention_kernel", st); hipLaunchKernelGGL((attention_kernel<T, true>), grid, dim3(128), 0, st, (const T*)qkv, (T*)ctx, S, d, scale, count,
-                       max_seqs); }
-  else
-    { ProfScope ps_("attention_kernel", st); hipLaunchKernelGGL((attention_kernel<T, false>), grid, dim3(128), 0, st, (const T*)qkv, (T*)ctx, S, d, scale,
-                       count, max_seqs); }
+  if (sizeof(T) == 2) {
+    // bf16: matrix-core kernel, base-2 softmax with log2(e) folded into the score scale
+    const float scale_log2e = scale * 1.4426950408889634f;
+    const int items = ((S + AttnCfg::QB - 1) / AttnCfg::QB) * n_heads * max_seqs;
+    const dim3 grid(std::min(items, 2 * kMaxGrid));
+    ProfScope ps_("attention_kernel", st);
+    if (causal)
+      hipLaunchKernelGGL(attention_mfma_kernel<true>, grid, dim3(AttnCfg::THREADS), 0, st, (const uint16_t*)qkv,
+                         (uint16_t*)ctx, S, d, n_heads, scale_log2e, count, max_seqs);
+    else
+      hipLaunchKernelGGL(attention_mfma_kernel<false>, grid, dim3(AttnCfg::THREADS), 0, st, (const uint16_t*)qkv,
+                         (uint16_t*)ctx, S, d, n_heads, scale_log2e, count, max_seqs);
+  } else {
+    dim3 grid((S + 127) / 128, n_heads, max_seqs);
+    ProfScope ps_("attention_kernel", st);
+    if (causal)
+      hipLaunchKernelGGL((attention_kernel<T, true>), grid, dim3(128), 0, st, (const T*)qkv, (T*)ctx, S, d, scale, count,
+                         max_seqs);
+    else
+      hipLaunchKernelGGL((attention_kernel<T, false>), grid, dim3(128), 0, st, (const T*)qkv, (T*)ctx, S, d, scale,
+                         count, max_seqs);
+  }
   LLMC_LAUNCH_CHECK("attention");
   return LLMC_OK;
 }

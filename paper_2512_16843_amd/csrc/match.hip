@@ -312,13 +312,17 @@ __global__ __launch_bounds__(256) void match_f32_kernel(const float* __restrict_
   }
 }
 
-// one wavefront per query
+// One wavefront per query: merge the partial results of all bank splits, then decide the
+// winner exactly.  The 64 lanes evaluate the 16 rows of a candidate group at once, 4 lanes
+// per row, each over a quarter of the key in fp64; the four partial sums are added in a
+// fixed order, and a butterfly picks the largest cosine (lowest slot among equals).
 template <typename T>
 __global__ __launch_bounds__(256) void match_finalize_kernel(
     const Top2* __restrict__ partial, int n_split, const T* __restrict__ bank, const float* __restrict__ binv,
     const uint8_t* __restrict__ valid, int N, int K, const T* __restrict__ queries, const float* __restrict__ qinv,
     int B, float tau, int32_t* __restrict__ idx_out, float* __restrict__ sim_out, uint8_t* __restrict__ hit_out,
     uint8_t* __restrict__ tie_out) {
+  constexpr int VEC = Vec16<T>::N;
   const int b = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (b >= B) return;
   const int lane = threadIdx.x & 63;
@@ -341,21 +345,39 @@ __global__ __launch_bounds__(256) void match_finalize_kernel(
   // scores so far are |q| * cos; the runner-up counts as tied within 1e-5 in cosine
   const float gap = qi > 0.f ? 1e-5f / qi : 0.f;
   const bool two = t.g2 >= 0 && t.v2 >= t.v1 - gap;
+  const int n_groups = (t.g1 < 0) ? 0 : (two ? 2 : 1);
+  const int r = lane >> 2, part = lane & 3;
+  const int per = K / 4;                       // K is a multiple of 32, so per is a multiple of 8
+  const T* qp = queries + (size_t)b * K + part * per;
   double best = -INFINITY;
   int best_j = -1;
-  const int n_groups = (t.g1 < 0) ? 0 : (two ? 2 : 1);
   for (int c = 0; c < n_groups; ++c) {
     const int g = c == 0 ? t.g1 : t.g2;
-    for (int r = 0; r < 16; ++r) {
-      const int j = group_row(g, r);
-      if (j >= N || !valid[j]) continue;   // uniform across the wavefront
-      double a = 0.0;
-      for (int i = lane; i < K; i += 64)
-        a += (double)Elem<T>::load(queries + (size_t)b * K + i) * (double)Elem<T>::load(bank + (size_t)j * K + i);
-      a = wave_sum(a);
-      const double s = a * qi64 * (double)binv[j];
-      if (s > best || (s == best && j < best_j)) { best = s; best_j = j; }
+    const int j = group_row(g, r);
+    const int jc = min(j, N - 1);            // loads are issued for every lane, validity is applied afterwards
+    const bool ok = j < N && valid[jc] != 0;
+    const double bj = (double)binv[jc];
+    const T* kp = bank + (size_t)jc * K + part * per;
+    double a = 0.0;
+    for (int i = 0; i < per; i += VEC) {
+      float x[VEC], y[VEC];
+      Vec16<T>::load(qp + i, x);
+      Vec16<T>::load(kp + i, y);
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) a += (double)x[e] * (double)y[e];
     }
+    a += __shfl_xor(a, 1, 64);
+    a += __shfl_xor(a, 2, 64);
+    if (ok) {
+      const double s = a * qi64 * bj;
+      if (s > best || (s == best && (best_j < 0 || j < best_j))) { best = s; best_j = j; }
+    }
+  }
+#pragma unroll
+  for (int o = 4; o < 64; o <<= 1) {
+    const double os = __shfl_xor(best, o, 64);
+    const int oj = __shfl_xor(best_j, o, 64);
+    if (oj >= 0 && (best_j < 0 || os > best || (os == best && oj < best_j))) { best = os; best_j = oj; }
   }
   if (lane == 0) {
     idx_out[b] = best_j;

@@ -204,18 +204,28 @@ __device__ __forceinline__ void mma_block_dma(const uint16_t* const (&a_ptr)[C::
     dma::barrier();
     if (kt + C::STAGES - 1 < nk) issue(kt + C::STAGES - 1);
     const uint16_t* st = lds + (kt % C::STAGES) * C::STAGE_ELEMS;
+    // fragments of the next 16-column step are fetched while the current step multiplies
+    bf16x8_t fa[2][C::FM], fb[2][C::FN];
+#pragma unroll
+    for (int i = 0; i < C::FM; ++i) fa[0][i] = *reinterpret_cast<const bf16x8_t*>(st + a_row + i * 32 * C::BK + sw[0]);
+#pragma unroll
+    for (int j = 0; j < C::FN; ++j) fb[0][j] = *reinterpret_cast<const bf16x8_t*>(st + b_row + j * 32 * C::BK + sw[0]);
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
-      bf16x8_t fa[C::FM], fb[C::FN];
+      const int c = ks & 1, n = c ^ 1;
+      if (ks + 1 < 4) {
 #pragma unroll
-      for (int i = 0; i < C::FM; ++i) fa[i] = *reinterpret_cast<const bf16x8_t*>(st + a_row + i * 32 * C::BK + sw[ks]);
+        for (int i = 0; i < C::FM; ++i)
+          fa[n][i] = *reinterpret_cast<const bf16x8_t*>(st + a_row + i * 32 * C::BK + sw[ks + 1]);
 #pragma unroll
-      for (int j = 0; j < C::FN; ++j) fb[j] = *reinterpret_cast<const bf16x8_t*>(st + b_row + j * 32 * C::BK + sw[ks]);
+        for (int j = 0; j < C::FN; ++j)
+          fb[n][j] = *reinterpret_cast<const bf16x8_t*>(st + b_row + j * 32 * C::BK + sw[ks + 1]);
+      }
 #pragma unroll
       for (int i = 0; i < C::FM; ++i)
 #pragma unroll
         for (int j = 0; j < C::FN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[c][i], fb[c][j], acc[i][j], 0, 0, 0);
     }
   }
   dma::barrier();   // every wavefront is done reading before the caller reuses the LDS
