@@ -72,6 +72,7 @@ def main():
     ap.add_argument("--bank", type=int, default=None, help="bank entries per layer (default: the config's 16384)")
     ap.add_argument("--layers", type=int, default=None, help="debug: fewer layers")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-stress", action="store_true", help="skip the 1M-key bank-match stress leg")
     ap.add_argument("--cpu-rows", type=int, default=2, help="sequences of the batch the oracle is timed on")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -190,6 +191,15 @@ def main():
         cpu = cpu_baseline(cfg, st, ws, Ps, h0, args.tau, args.cpu_rows)
         log("cpu oracle: %.3f seq/s on %d threads (%s)" % (cpu["value"], cpu["cores"], cpu["sample"]))
 
+    # ---- bank-match stress shape (1,048,576 keys x 256, 4,096 queries) and its gather ------------------
+    stress = None
+    if not args.no_stress:
+        stress = match_stress(llmc, W)
+        log("match stress: %.1f us -> %.1f TFLOP/s (%.1f%% of bf16 MFMA peak); finalize %.1f us; gather of %d hits "
+            "%.1f us -> %.1f GB/s (%.1f%% of HBM peak)"
+            % (stress["match_us"], stress["match_tflops"], 100 * stress["match_frac_mfma"], stress["finalize_us"],
+               stress["hits"], stress["gather_us"], stress["gather_gbs"], 100 * stress["gather_frac_hbm"]))
+
     # ---- headline: the last GPU work of the run ------------------------------------------------------
     dt_head, cnt_head = run(args.tau, args.steps, args.warmup)
     sweep.append(row_of(args.tau, dt_head, cnt_head))
@@ -224,10 +234,58 @@ def main():
         "sweep": sweep,
         "roofline": roof,
         "kernels": {"headline": prof_head, "no_cache": prof_nocache},
+        "match_stress": stress,
         "cpu_baseline": cpu,
     }
     st.close()
     print(json.dumps(result))
+
+
+def match_stress(llmc, W, iters=10):
+    """Top-1 cosine + threshold over a 1,048,576-key clustered bank for 4,096 queries, then the gather
+    of the matched 384 x 768 outputs for the hits; per-kernel times from the library's HIP events."""
+    import torch
+    N, k, S, d, A, B, tau = 1048576, 256, 384, 768, 4096, 4096, 0.95
+    data = W.make_clustered_bank(4096, 256, k, 0.05, B, seed=5)
+    bank = llmc.Bank(N, k, S, d, torch.bfloat16, "cuda", n_act_slots=A, act_slot=data["cluster"].cuda())
+    bank.fp.copy_(data["bank"])
+    llmc.llmc_inv_norm(bank.fp, bank.inv_norm)
+    bank.valid.fill_(1)
+    bank.act.copy_(torch.randn((A, S, d), device="cuda", dtype=torch.bfloat16))
+    bank.refresh()
+    q = data["queries"].cuda()
+    qinv = torch.empty((B,), dtype=torch.float32, device="cuda")
+    llmc.llmc_inv_norm(q, qinv)
+    idx = torch.empty((B,), dtype=torch.int32, device="cuda")
+    sim = torch.empty((B,), dtype=torch.float32, device="cuda")
+    hit = torch.empty((B,), dtype=torch.uint8, device="cuda")
+    ws = torch.empty((llmc.llmc_match_workspace_bytes(bank, B),), dtype=torch.uint8, device="cuda")
+    out = torch.empty((B, S, d), dtype=torch.bfloat16, device="cuda")
+    llmc.llmc_match(bank, q, qinv, tau, idx, sim, hit, None, ws)
+    rows = torch.nonzero(hit).flatten().int().contiguous()
+    n = torch.tensor([rows.numel()], dtype=torch.int32, device="cuda")
+    llmc.llmc_gather_hits(bank, idx, rows, n, B, out)
+    torch.cuda.synchronize()
+    llmc.llmc_profile_begin(4 * iters)
+    for _ in range(iters):
+        llmc.llmc_match(bank, q, qinv, tau, idx, sim, hit, None, ws)
+        llmc.llmc_gather_hits(bank, idx, rows, n, B, out)
+    rep = llmc.llmc_profile_report()
+    llmc.llmc_profile_end()
+    us = {name: ms * 1e3 / cnt for name, (cnt, ms) in rep.items()}
+    H = int(rows.numel())
+    m_us, g_us = us["match_stream_kernel"], us["gather_kernel"]
+    tfl = 2.0 * B * N * k / m_us / 1e6
+    gbs = 2.0 * H * S * d * 2 / g_us / 1e3
+    bank.close()
+    res = {"workload": "bank-match stress: 1,048,576 bf16 keys x 256 in 4,096 clusters, 4,096 queries, tau 0.95, "
+                       "gather of 384 x 768 bf16 outputs for the hits",
+           "hits": H, "match_us": round(m_us, 2), "match_tflops": round(tfl, 1),
+           "match_frac_mfma": round(tfl / MFMA_BF16_PEAK_TFLOPS, 4), "finalize_us": round(us["match_finalize_kernel"], 2),
+           "gather_us": round(g_us, 2), "gather_gbs": round(gbs, 1), "gather_frac_hbm": round(gbs / HBM_PEAK_GBS, 4)}
+    del bank, out
+    torch.cuda.empty_cache()
+    return res
 
 
 def cpu_baseline(cfg, st, ws, Ps, h0, tau, n_rows):

@@ -135,17 +135,19 @@ __global__ __launch_bounds__(MatchCfg::THREADS) void match_bf16_kernel(
 // bank fragments from LDS, so LDS traffic is one tile read per wavefront and no query is ever
 // re-fetched.  Rows of a tile are 2*K bytes; their 16-byte chunks are XOR-swizzled by the row
 // number so that the 16-byte fragment reads of 16 consecutive rows fall on distinct banks.
-template <int K_>
+template <int K_, int NW_>
 struct StreamCfg {
   static constexpr int K = K_, KS = K / 16, CHUNKS = K / 8, ROWB = K * 2;
-  static constexpr int NW = 8, THREADS = NW * 64, FM = 2, FN = 2;
+  static constexpr int NW = NW_, THREADS = NW * 64, FM = 2, FN = 2;
   static constexpr int RB = FM * 32;                 // bank rows per tile
   static constexpr int QW = FN * 32, QB = NW * QW;   // queries per wavefront / workgroup
   static constexpr int ROWS_PER_INSTR = 1024 / ROWB; // tile rows filled by one wavefront load
   static constexpr int L = RB / ROWS_PER_INSTR / NW + 1;   // loads per lane per stage: tile blocks + the norms
   static constexpr int TILE_ELEMS = RB * K;
   static constexpr int STAGE_ELEMS = TILE_ELEMS + NW * RB * 2;   // + one fp32 copy of the tile's inverse norms per wavefront
-  static constexpr int STAGES = (K >= 256) ? 4 : 3;
+  // 8 wavefronts: one workgroup per compute unit with a deep ring; 4 wavefronts: two independent
+  // workgroups per compute unit (their epilogues and main loops interleave), two stages each
+  static constexpr int STAGES = NW == 8 ? ((K >= 256) ? 4 : 3) : 2;
   static constexpr size_t LDS_BYTES = (size_t)STAGES * STAGE_ELEMS * 2;
   static_assert(K == 64 || K == 128 || K == 256, "supported key lengths");
   static_assert(L >= 2 && (RB / ROWS_PER_INSTR) % NW == 0 && RB == 64, "load tiling");
@@ -153,11 +155,11 @@ struct StreamCfg {
 };
 
 // grid: 1-D, see launch_match for the workgroup -> (split, query block) map
-template <int K_>
-__global__ __launch_bounds__(StreamCfg<K_>::THREADS) void match_stream_kernel(
+template <int K_, int NW_>
+__global__ __launch_bounds__(NW_ * 64) void match_stream_kernel(
     const uint16_t* __restrict__ bank, const float* __restrict__ binv_eff, int N, const uint16_t* __restrict__ queries,
     int B, int n_qb, int n_split, int tiles_per_split, Top2* __restrict__ partial) {
-  using C = StreamCfg<K_>;
+  using C = StreamCfg<K_, NW_>;
   extern __shared__ __attribute__((aligned(16))) uint16_t lds_dyn[];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -228,17 +230,28 @@ __global__ __launch_bounds__(StreamCfg<K_>::THREADS) void match_stream_kernel(
       for (int j = 0; j < C::FN; ++j)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    // bank fragments of step ks + 1 are fetched while step ks multiplies
+    bf16x8_t fa[2][C::FM];
+#pragma unroll
+    for (int i = 0; i < C::FM; ++i)
+      fa[0][i] = *reinterpret_cast<const bf16x8_t*>(st + i * 32 * C::K + ((half ^ fsw) * 8));
+    __builtin_amdgcn_sched_group_barrier(0x100, C::FM, 0);
 #pragma unroll
     for (int ks = 0; ks < C::KS; ++ks) {
-      bf16x8_t fa[C::FM];
+      const int c = ks & 1, n = c ^ 1;
+      if (ks + 1 < C::KS) {
 #pragma unroll
-      for (int i = 0; i < C::FM; ++i)
-        fa[i] = *reinterpret_cast<const bf16x8_t*>(st + i * 32 * C::K + (((ks * 2 + half) ^ fsw) * 8));
+        for (int i = 0; i < C::FM; ++i)
+          fa[n][i] = *reinterpret_cast<const bf16x8_t*>(st + i * 32 * C::K + ((((ks + 1) * 2 + half) ^ fsw) * 8));
+      }
 #pragma unroll
       for (int i = 0; i < C::FM; ++i)
 #pragma unroll
         for (int j = 0; j < C::FN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], bq[j][ks], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[c][i], bq[j][ks], acc[i][j], 0, 0, 0);
+      // keep the order written above: the next step's LDS reads first, then this step's MFMAs
+      __builtin_amdgcn_sched_group_barrier(0x100, C::FM, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, C::FM * C::FN, 0);
     }
 #pragma unroll
     for (int i = 0; i < C::FM; ++i) {
@@ -412,26 +425,29 @@ static void stream_plan(int N, int B, int RB, int QB, int* n_qb, int* n_split, i
   *n_split = (tiles + per - 1) / per;
 }
 
+// Few queries: workgroups of 4 wavefronts (256 query columns), two per compute unit.
+// Many queries: workgroups of 8 wavefronts (512 query columns) with the deep ring.
+static int stream_waves(int B) { return B <= 256 ? 4 : 8; }
 static bool use_stream(int k) { return k == 64 || k == 128 || k == 256; }
 
 size_t match_ws_bytes(int n_slots, int k, int dtype, int B) {
   int ns = 1, per = 1, nqb = 1;
   if (dtype == LLMC_BF16) {
-    if (use_stream(k)) stream_plan(n_slots, B, 64, 512, &nqb, &ns, &per);
+    if (use_stream(k)) stream_plan(n_slots, B, 64, stream_waves(B) * 64, &nqb, &ns, &per);
     else split_plan(n_slots, B, &ns, &per);
   }
   return align_up((size_t)ns * B * sizeof(Top2), 256);
 }
 
-template <int K_>
-static llmc_status_t launch_stream(const llmc_bank* bank, const void* d_fp, int B, Top2* partial, int* ns_out,
-                                   hipStream_t st) {
-  using C = StreamCfg<K_>;
+template <int K_, int NW_>
+static llmc_status_t launch_stream_nw(const llmc_bank* bank, const void* d_fp, int B, Top2* partial, int* ns_out,
+                                      hipStream_t st) {
+  using C = StreamCfg<K_, NW_>;
   const llmc_bank_desc_t& D = bank->desc;
   static bool attr_set = false;
   if (!attr_set) {
-    LLMC_HIP(hipFuncSetAttribute((const void*)match_stream_kernel<K_>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                 (int)C::LDS_BYTES));
+    LLMC_HIP(hipFuncSetAttribute((const void*)(match_stream_kernel<K_, NW_>),
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES));
     attr_set = true;
   }
   int nqb, ns, per;
@@ -439,10 +455,18 @@ static llmc_status_t launch_stream(const llmc_bank* bank, const void* d_fp, int 
   const int groups = (ns + 7) / 8;                 // splits are dealt to the 8 XCDs
   const unsigned grid = (unsigned)groups * nqb * 8;
   ProfScope ps_("match_stream_kernel", st);
-  hipLaunchKernelGGL(match_stream_kernel<K_>, dim3(grid), dim3(C::THREADS), C::LDS_BYTES, st, (const uint16_t*)D.d_fp,
-                     bank->d_binv_eff, D.n_slots, (const uint16_t*)d_fp, B, nqb, ns, per, partial);
+  hipLaunchKernelGGL((match_stream_kernel<K_, NW_>), dim3(grid), dim3(C::THREADS), C::LDS_BYTES, st,
+                     (const uint16_t*)D.d_fp, bank->d_binv_eff, D.n_slots, (const uint16_t*)d_fp, B, nqb, ns, per,
+                     partial);
   *ns_out = ns;
   return LLMC_OK;
+}
+
+template <int K_>
+static llmc_status_t launch_stream(const llmc_bank* bank, const void* d_fp, int B, Top2* partial, int* ns_out,
+                                   hipStream_t st) {
+  if (stream_waves(B) == 4) return launch_stream_nw<K_, 4>(bank, d_fp, B, partial, ns_out, st);
+  return launch_stream_nw<K_, 8>(bank, d_fp, B, partial, ns_out, st);
 }
 
 llmc_status_t launch_match(const llmc_bank* bank, const void* d_fp, const float* d_inv, int B, float tau,
