@@ -26,6 +26,15 @@ METRIC = "seq/s cache-gated 12L d768 forward vs hit rate; match MFMA% + gather H
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 FP32_VALU_PEAK_TFLOPS = 157.3
+CALIB_COPY_BYTES = 256 << 20
+# HBM bytes per launch at the bench shape (64 rows of 384 x 768 bf16), from rocprofv3 --pmc FETCH_SIZE and
+# WRITE_SIZE runs of paper_2512_16843_amd/kernel_bench.py, each scaled by what the counter read for that
+# script's 256 MiB device-to-device copy (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0): see profiles/.
+# Set an entry to None when its kernel changes.
+MEASURED_TRAFFIC_BYTES = {
+    "gather_kernel": (18344.7 * 2.0 + 36898.0) * 1024,    # algorithmic: 2 x 37,748,736
+    "pool_kernel": (18476.3 * 2.0 + 2304.0) * 1024,       # algorithmic: 37,748,736 read
+}
 
 
 def log(msg):
@@ -115,6 +124,15 @@ def main():
     log("banks built: %d sequences x %d layers in %.1f s (%.1f seq/s all-miss with insertion)"
         % (cfg.n_bank, cfg.n_layers, build_s, cfg.n_bank / build_s))
 
+    # a plain device-to-device copy of known size: the reference against which HBM byte counters
+    # (FETCH_SIZE / WRITE_SIZE) of a profiled run are scaled
+    cal_src = torch.full((CALIB_COPY_BYTES,), 7, dtype=torch.uint8, device=dev)
+    cal_dst = torch.empty_like(cal_src)
+    for _ in range(3):
+        cal_dst.copy_(cal_src)
+    torch.cuda.synchronize()
+    del cal_src, cal_dst
+
     # ---- query batch: 60 % perturbed copies of bank sources (3 % of tokens resampled), 40 % fresh ----
     n_dup = int(round(0.6 * cfg.B))
     n_sub = int(round(0.03 * cfg.S))
@@ -184,6 +202,14 @@ def main():
             log("%-9s %-24s %3d launches/step  avg %9.2f us  %8.4f ms/step  %8.2f TFLOP/s %9.1f GB/s"
                 % (tag, name, r["launches_per_step"], r["avg_us"], r["ms_per_step"], r["tflops"], r["gbs"]))
     launches_per_step = sum(r["launches_per_step"] for r in prof_head.values())
+    # Event brackets around single ~15 us kernels add a few us each.  The gather launches of the headline
+    # step (one per layer: that layer's bank, that layer's hit rows) are also replayed back to back between
+    # ONE pair of events on the same stream: that average is the launch duration rocprofv3 reports.
+    hit_head = [int(x) for x in st.hit_counts().numpy()[:, llmc.CNT_HIT]]
+    gather_replay_us = replay_gathers(llmc, st, cfg, reps=20) if sum(hit_head) else None
+    if gather_replay_us:
+        log("gather replay at the headline threshold: %.2f us per launch -> %.1f GB/s"
+            % (gather_replay_us, sum(2.0 * h * cfg.S * cfg.d * 2 for h in hit_head) / cfg.n_layers / gather_replay_us / 1e3))
 
     # ---- CPU oracle on a bounded sample of the same batch (before the headline run) -----------------
     cpu = None
@@ -207,9 +233,17 @@ def main():
     sweep.sort(key=lambda r: (r["tau"] == "no-cache", r["tau"] if r["tau"] != "no-cache" else 9))
     log("library kernel launches per step at the headline threshold: %d" % launches_per_step)
 
-    # the dominant kernel of the headline run decides the roofline object
-    dom = max(prof_head.items(), key=lambda kv: kv[1]["ms_per_step"])
-    name, r = dom
+    # The dominant kernel of the headline run decides the roofline object.  Kernels that had no work at this
+    # hit rate (miss-path launches with zero misses) only show their launch bracket and are not candidates.
+    def has_work(name, r):
+        return r["tflops"] > 0 or r["gbs"] > 0
+    cands = {k: v for k, v in prof_head.items() if has_work(k, v) and not (k == "gemm_bf16_kernel" and v["tflops"] == 0)}
+    name, r = max(cands.items(), key=lambda kv: kv[1]["ms_per_step"])
+    avg_us = r["avg_us"]
+    if name == "gather_kernel" and gather_replay_us:
+        avg_us = gather_replay_us
+        by = sum(2.0 * h * cfg.S * cfg.d * 2 for h in hit_head) / cfg.n_layers
+        r = dict(r, gbs=round(by / avg_us / 1e3, 2), avg_us=round(avg_us, 3))
     if r["bound"] == "mfma":
         roof = {"kernel": name, "bound": "mfma", "achieved": r["tflops"], "peak": MFMA_BF16_PEAK_TFLOPS,
                 "unit": "TFLOP/s", "frac": round(r["tflops"] / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None}
@@ -218,7 +252,7 @@ def main():
                 "unit": "TFLOP/s", "frac": round(r["tflops"] / FP32_VALU_PEAK_TFLOPS, 4), "traffic": None}
     else:
         roof = {"kernel": name, "bound": "hbm", "achieved": r["gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(r["gbs"] / HBM_PEAK_GBS, 4), "traffic": None}
+                "frac": round(r["gbs"] / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(name)}
     roof["avg_launch_us"] = r["avg_us"]
 
     result = {
@@ -239,6 +273,29 @@ def main():
     }
     st.close()
     print(json.dumps(result))
+
+
+def replay_gathers(llmc, st, cfg, reps):
+    """Average duration of the per-layer gather launches of the last forward, replayed back to back."""
+    import torch
+    rows, ns = [], []
+    for g in st.gate:
+        r = torch.nonzero(g.hit).flatten().int().contiguous()
+        rows.append(r if r.numel() else torch.zeros((1,), dtype=torch.int32, device=r.device))
+        ns.append(torch.tensor([r.numel()], dtype=torch.int32, device=r.device))
+    out = st.buf[0]
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    def once():
+        for l in range(cfg.n_layers):
+            llmc.llmc_gather_hits(st.banks[l], st.gate[l].idx, rows[l], ns[l], cfg.B, out)
+    once()
+    torch.cuda.synchronize()
+    a.record()
+    for _ in range(reps):
+        once()
+    b.record()
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) * 1e3 / (reps * cfg.n_layers)
 
 
 def match_stress(llmc, W, iters=10):

@@ -372,7 +372,21 @@ __global__ __launch_bounds__(256) void match_finalize_kernel(
     const double bj = (double)binv[jc];
     const T* kp = bank + (size_t)jc * K + part * per;
     double a = 0.0;
-    for (int i = 0; i < per; i += VEC) {
+    // four 16-byte vectors of the query and of the key in flight; products added in ascending order
+    int i = 0;
+    for (; i + 4 * VEC <= per; i += 4 * VEC) {
+      float x[4][VEC], y[4][VEC];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        Vec16<T>::load(qp + i + u * VEC, x[u]);
+        Vec16<T>::load(kp + i + u * VEC, y[u]);
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) a += (double)x[u][e] * (double)y[u][e];
+    }
+    for (; i < per; i += VEC) {
       float x[VEC], y[VEC];
       Vec16<T>::load(qp + i, x);
       Vec16<T>::load(kp + i, y);

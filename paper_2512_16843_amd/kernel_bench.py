@@ -1,0 +1,101 @@
+#!/usr/bin/env python3
+"""Per-call microbenchmark of the HBM- and MFMA-bound entry points of libllmc.so.
+
+Runs llmc_fingerprint, llmc_match and llmc_gather_hits (through the C ABI) on synthetic
+tensors of a given shape, a few times each, and prints one line per kernel with the
+duration measured by the library's HIP events and the algorithmic GB/s or TFLOP/s.
+It also performs a plain device-to-device copy of known size: when this script is run
+under `rocprofv3 --pmc FETCH_SIZE` (or WRITE_SIZE) that copy is the reference against
+which the byte counters of the other kernels are scaled.
+
+    python -m paper_2512_16843_amd.kernel_bench --B 64 --S 384 --d 768 --k 256 --N 16384
+"""
+import argparse
+import json
+import sys
+
+import torch
+
+from . import llmc
+
+CALIB_COPY_BYTES = 256 << 20
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--B", type=int, default=64)
+    ap.add_argument("--S", type=int, default=384)
+    ap.add_argument("--d", type=int, default=768)
+    ap.add_argument("--k", type=int, default=256)
+    ap.add_argument("--N", type=int, default=16384)
+    ap.add_argument("--act-slots", type=int, default=2048, help="distinct cached-output rows (keys share them)")
+    ap.add_argument("--iters", type=int, default=5)
+    args = ap.parse_args()
+    B, S, d, k, N, A = args.B, args.S, args.d, args.k, args.N, min(args.act_slots, args.N)
+    dev, dt = "cuda", torch.bfloat16
+    torch.manual_seed(0)
+    llmc.lib()
+
+    cal_src = torch.full((CALIB_COPY_BYTES,), 7, dtype=torch.uint8, device=dev)
+    cal_dst = torch.empty_like(cal_src)
+    for _ in range(3):
+        cal_dst.copy_(cal_src)
+    torch.cuda.synchronize()
+
+    # several distinct inputs so that repeated launches do not re-read a cache-resident tensor
+    hs = [torch.randn((B, S, d), device=dev, dtype=torch.float32).to(dt) for _ in range(args.iters)]
+    P = (torch.randn((d, k), device=dev) / k ** 0.5).to(dt)
+    fp = torch.empty((B, k), dtype=dt, device=dev)
+    inv = torch.empty((B,), dtype=torch.float32, device=dev)
+    ws_fp = torch.empty((llmc.llmc_fingerprint_workspace_bytes(B, S, d),), dtype=torch.uint8, device=dev)
+
+    act_slot = (torch.randperm(N, device=dev) % A).int().contiguous()
+    bank = llmc.Bank(N, k, S, d, dt, dev, n_act_slots=A, act_slot=act_slot)
+    bank.fp.copy_(torch.nn.functional.normalize(torch.randn((N, k), device=dev), dim=1).to(dt))
+    llmc.llmc_inv_norm(bank.fp, bank.inv_norm)
+    bank.valid.fill_(1)
+    bank.act.copy_(torch.randn((A, S, d), device=dev, dtype=torch.float32).to(dt))
+    bank.refresh()
+    idx = torch.empty((B,), dtype=torch.int32, device=dev)
+    sim = torch.empty((B,), dtype=torch.float32, device=dev)
+    hit = torch.empty((B,), dtype=torch.uint8, device=dev)
+    ws_m = torch.empty((llmc.llmc_match_workspace_bytes(bank, B),), dtype=torch.uint8, device=dev)
+    out = torch.empty((B, S, d), dtype=dt, device=dev)
+    rows = torch.arange(B, dtype=torch.int32, device=dev)
+    n = torch.tensor([B], dtype=torch.int32, device=dev)
+
+    def step(i):
+        llmc.llmc_fingerprint(hs[i % len(hs)], P, None, fp, inv, ws_fp)
+        llmc.llmc_match(bank, fp, inv, -2.0, idx, sim, hit, None, ws_m)      # tau = -2: every row "hits"
+        llmc.llmc_gather_hits(bank, idx, rows, n, B, out)
+
+    step(0)
+    torch.cuda.synchronize()
+    llmc.llmc_profile_begin(8 * args.iters)
+    for i in range(args.iters):
+        step(i)
+    rep = llmc.llmc_profile_report()
+    llmc.llmc_profile_end()
+    e = 2
+    work = {
+        "pool_kernel": (0.0, float(B) * S * d * e),
+        "project_kernel": (2.0 * B * d * k, d * k * e),
+        "match_stream_kernel": (2.0 * B * N * k, float(N) * k * e),
+        "match_bf16_kernel": (2.0 * B * N * k, float(N) * k * e),
+        "match_finalize_kernel": (0.0, 0.0),
+        "gather_kernel": (0.0, 2.0 * B * S * d * e),
+    }
+    res = {"shape": {"B": B, "S": S, "d": d, "k": k, "N": N, "act_slots": A}, "calib_copy_bytes": CALIB_COPY_BYTES,
+           "kernels": {}}
+    for name, (cnt, ms) in sorted(rep.items()):
+        us = ms * 1e3 / cnt
+        fl, by = work.get(name, (0.0, 0.0))
+        res["kernels"][name] = {"avg_us": round(us, 2), "gbs": round(by / us / 1e3, 1), "tflops": round(fl / us / 1e6, 2),
+                                "algorithmic_bytes": by}
+        print("%-24s avg %9.2f us  %9.1f GB/s  %8.2f TFLOP/s" % (name, us, by / us / 1e3, fl / us / 1e6), file=sys.stderr)
+    bank.close()
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()
