@@ -47,6 +47,7 @@ struct GemmArgs {
   const int32_t* r_rows;           // ... to residual rows
   const int32_t* o_rows;           // ... to output rows
   int act;                         // 0 none, 1 GELU erf, 2 GELU tanh
+  int xcd_chunks;                  // tile -> workgroup map of the direct-to-LDS kernel, see there
 };
 
 __device__ __forceinline__ float apply_act(float v, int act) {
@@ -188,7 +189,16 @@ __global__ __launch_bounds__(C::THREADS) void gemm_bf16_dma_kernel(GemmArgs g, i
   const int M = n_seq * g.S;
   const int total = ((M + C::BM - 1) / C::BM) * tiles_n;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  for (int tile = blockIdx.x; tile < total; tile += gridDim.x) {
+  // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  With xcd_chunks set, XCD x
+  // walks the x-th eighth of the tile list (tiles of one row block are adjacent in it), so the
+  // activation rows of a row block are fetched into one L2 only and shared there by the column
+  // tiles; otherwise workgroups stride over the tile list.  gridDim.x % 8 == 0 when xcd_chunks.
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3, slots = gridDim.x >> 3;
+  const int per_xcd = (total + 7) >> 3;
+  const int n_it = g.xcd_chunks ? per_xcd : total;
+  for (int it = g.xcd_chunks ? slot : (int)blockIdx.x; it < n_it; it += g.xcd_chunks ? slots : (int)gridDim.x) {
+  const int tile = g.xcd_chunks ? xcd * per_xcd + it : it;
+  if (tile >= total) break;
   const int tile_m = tile / tiles_n, tile_n = tile % tiles_n;
   const int m0 = tile_m * C::BM, n0 = tile_n * C::BN;
   const uint16_t* A = (const uint16_t*)g.A;

@@ -96,9 +96,11 @@ static llmc_status_t launch_gemm(const GemmArgs& g, int dtype, hipStream_t st) {
       }
       const int tiles_n = (g.N + C::BN - 1) / C::BN;
       const int tiles_m = (g.max_seqs * g.S + C::BM - 1) / C::BM;
+      GemmArgs a = g;
+      a.xcd_chunks = tiles_n <= 8 ? 1 : 0;   // narrow outputs gain from keeping a row block in one XCD's L2
       ProfScope ps_("gemm_bf16_kernel", st);
-      hipLaunchKernelGGL(gemm_bf16_dma_kernel<C>, dim3(std::min(tiles_m * tiles_n, kMaxGrid)), dim3(C::THREADS),
-                         gemm_dma_smem_bytes<C>(), st, g, tiles_n);
+      hipLaunchKernelGGL(gemm_bf16_dma_kernel<C>, dim3(std::min((tiles_m * tiles_n + 7) & ~7, kMaxGrid)), dim3(C::THREADS),
+                         gemm_dma_smem_bytes<C>(), st, a, tiles_n);
     } else {
       const int tiles_n = (g.N + GemmCfg::BN - 1) / GemmCfg::BN;
       const int tiles_m = (g.max_seqs * g.S + GemmCfg::BM - 1) / GemmCfg::BM;

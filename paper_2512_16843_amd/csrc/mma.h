@@ -210,6 +210,7 @@ __device__ __forceinline__ void mma_block_dma(const uint16_t* const (&a_ptr)[C::
     for (int i = 0; i < C::FM; ++i) fa[0][i] = *reinterpret_cast<const bf16x8_t*>(st + a_row + i * 32 * C::BK + sw[0]);
 #pragma unroll
     for (int j = 0; j < C::FN; ++j) fb[0][j] = *reinterpret_cast<const bf16x8_t*>(st + b_row + j * 32 * C::BK + sw[0]);
+    __builtin_amdgcn_sched_group_barrier(0x100, C::FM + C::FN, 0);
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
       const int c = ks & 1, n = c ^ 1;
@@ -226,6 +227,9 @@ __device__ __forceinline__ void mma_block_dma(const uint16_t* const (&a_ptr)[C::
 #pragma unroll
         for (int j = 0; j < C::FN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[c][i], fb[c][j], acc[i][j], 0, 0, 0);
+      // keep the written order: the next step's LDS reads are issued before this step's MFMAs
+      if (ks + 1 < 4) __builtin_amdgcn_sched_group_barrier(0x100, C::FM + C::FN, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, C::FM * C::FN, 0);
     }
   }
   dma::barrier();   // every wavefront is done reading before the caller reuses the LDS
