@@ -290,6 +290,176 @@ __global__ __launch_bounds__(NW_ * 64) void match_stream_kernel(
   }
 }
 
+// ---- skewed streaming variant for many queries ----------------------------------------------------
+// Same data flow as match_stream_kernel with 8 wavefronts (two per SIMD), but the two
+// wavefronts of a SIMD run the tile loop one half step apart: after the barrier of tile t the
+// "early" wavefront multiplies tile t and then reduces it, while the "late" wavefront first
+// reduces tile t - 1 (held in its accumulators across the barrier) and then multiplies tile t.
+// The vector-ALU reduction of one wavefront therefore runs while the other one owns the matrix
+// pipe, instead of both alternating between the two in step.  A late wavefront still reads the
+// inverse norms of tile t - 1 during tile t, so a ring stage is refilled two barriers after its
+// tile.  Accumulators start as NaN, which the first reduction of a late wavefront drops.
+template <int K_>
+struct SkewCfg : StreamCfg<K_, 8> {
+  using S = StreamCfg<K_, 8>;
+  static constexpr int STAGES = 4;
+  static constexpr size_t LDS_BYTES = (size_t)STAGES * S::STAGE_ELEMS * 2;
+};
+
+template <int K_>
+__global__ __launch_bounds__(512) void match_skew_kernel(
+    const uint16_t* __restrict__ bank, const float* __restrict__ binv_eff, int N, const uint16_t* __restrict__ queries,
+    int B, int n_qb, int n_split, int tiles_per_split, Top2* __restrict__ partial) {
+  using C = SkewCfg<K_>;
+  extern __shared__ __attribute__((aligned(16))) uint16_t lds_dyn[];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const bool late = wave >= C::NW / 2;      // wavefronts w and w + 4 share a SIMD
+  const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
+  const int split = (local / n_qb) * 8 + xcd, qb = local % n_qb;
+  if (split >= n_split) return;
+  const int n_tiles = (N + C::RB - 1) / C::RB;
+  const int t_begin = split * tiles_per_split;
+  const int t_end = min(n_tiles, t_begin + tiles_per_split);
+  const int q_base = qb * C::QB + wave * C::QW;
+
+  // load j of a stage fills tile rows ld_row + j * JSTEP; JSTEP is a multiple of the swizzle period,
+  // so the (swizzled) chunk of this lane is the same for every j
+  constexpr int JSTEP = C::NW * C::ROWS_PER_INSTR;
+  static_assert(JSTEP % 16 == 0, "one swizzled chunk per lane");
+  const int ld_row = wave * C::ROWS_PER_INSTR + lane / C::CHUNKS;
+  const int ld_off = ((lane % C::CHUNKS) ^ C::swz(ld_row)) * 8;
+  auto issue = [&](int t) {
+    uint16_t* st = lds_dyn + ((t - t_begin) % C::STAGES) * C::STAGE_ELEMS;
+#pragma unroll
+    for (int j = 0; j < C::L - 1; ++j) {
+      const int r = min(t * C::RB + ld_row + j * JSTEP, N - 1);
+      __builtin_amdgcn_global_load_lds(LLMC_GPTR(bank + (size_t)r * C::K + ld_off),
+                                       LLMC_LPTR(st + (j * C::NW + wave) * 512), 16, 0, 0);
+    }
+    __builtin_amdgcn_global_load_lds(LLMC_GPTR(binv_eff + (size_t)t * C::RB + lane),
+                                     LLMC_LPTR(st + C::TILE_ELEMS + wave * C::RB * 2), 4, 0, 0);
+  };
+#pragma unroll
+  for (int s = 0; s < C::STAGES - 2; ++s)
+    if (t_begin + s < t_end) issue(t_begin + s);
+
+  bf16x8_t bq[C::FN][C::KS];
+#pragma unroll
+  for (int j = 0; j < C::FN; ++j) {
+    const int q = min(q_base + j * 32 + (lane & 31), B - 1);
+    const uint16_t* qp = queries + (size_t)q * C::K + (lane >> 5) * 8;
+#pragma unroll
+    for (int ks = 0; ks < C::KS; ++ks) bq[j][ks] = *reinterpret_cast<const bf16x8_t*>(qp + ks * 16);
+  }
+  Top2 best[C::FN];
+#pragma unroll
+  for (int j = 0; j < C::FN; ++j) best[j] = top2_empty();
+  const int frag_off = (lane & 31) * C::K;
+  const int fsw = C::swz(lane & 31), half = lane >> 5;
+
+  f32x16_t acc[C::FM][C::FN];
+#pragma unroll
+  for (int i = 0; i < C::FM; ++i)
+#pragma unroll
+    for (int j = 0; j < C::FN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = NAN;
+
+  // running maximum over the accumulators of tile t, scaled by the inverse norms at sb
+  auto reduce = [&](const float* sb, int t) {
+#pragma unroll
+    for (int i = 0; i < C::FM; ++i) {
+      const int g = t * 4 + i * 2 + half;
+      float m[C::FN];
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const float4 v4 = *reinterpret_cast<const float4*>(sb + i * 32 + half * 4 + 8 * c);
+#pragma unroll
+        for (int j = 0; j < C::FN; ++j) {
+          const float p = fmaxf(fmaxf(acc[i][j][4 * c] * v4.x, acc[i][j][4 * c + 1] * v4.y),
+                                fmaxf(acc[i][j][4 * c + 2] * v4.z, acc[i][j][4 * c + 3] * v4.w));
+          m[j] = c == 0 ? p : fmaxf(m[j], p);
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < C::FN; ++j) {
+        const float mx = m[j];
+        const bool b1 = mx > best[j].v1, b2 = mx > best[j].v2;      // NaN compares false
+        const float v2n = b1 ? best[j].v1 : (b2 ? mx : best[j].v2);
+        const int g2n = b1 ? best[j].g1 : (b2 ? g : best[j].g2);
+        best[j].v1 = b1 ? mx : best[j].v1;
+        best[j].g1 = b1 ? g : best[j].g1;
+        best[j].v2 = v2n;
+        best[j].g2 = g2n;
+      }
+    }
+  };
+
+  for (int t = t_begin; t < t_end; ++t) {
+    if (t + 1 < t_end) LLMC_WAIT_VM(C::L);
+    else LLMC_WAIT_VM(0);
+    dma::barrier();
+    if (t + C::STAGES - 2 < t_end) issue(t + C::STAGES - 2);
+    const uint16_t* stage = lds_dyn + ((t - t_begin) % C::STAGES) * C::STAGE_ELEMS;
+    if (late) {
+      const uint16_t* prev = lds_dyn + ((t - t_begin + C::STAGES - 1) % C::STAGES) * C::STAGE_ELEMS;
+      reduce(reinterpret_cast<const float*>(prev + C::TILE_ELEMS + wave * C::RB * 2), t - 1);
+    }
+    const uint16_t* st = stage + frag_off;
+    bf16x8_t fa[2][C::FM];
+#pragma unroll
+    for (int i = 0; i < C::FM; ++i)
+      fa[0][i] = *reinterpret_cast<const bf16x8_t*>(st + i * 32 * C::K + ((half ^ fsw) * 8));
+    __builtin_amdgcn_sched_group_barrier(0x100, C::FM, 0);
+#pragma unroll
+    for (int ks = 0; ks < C::KS; ++ks) {
+      const int c = ks & 1, n = c ^ 1;
+      // the fragments of this step were requested one step ago; waiting for them BEFORE requesting the
+      // next ones keeps the wait from covering a request that has only just been issued
+      __builtin_amdgcn_sched_barrier(0);
+      LLMC_WAIT_LGKM(0);
+      __builtin_amdgcn_sched_barrier(0);
+      if (ks + 1 < C::KS) {
+#pragma unroll
+        for (int i = 0; i < C::FM; ++i)
+          fa[n][i] = *reinterpret_cast<const bf16x8_t*>(st + i * 32 * C::K + ((((ks + 1) * 2 + half) ^ fsw) * 8));
+      }
+#pragma unroll
+      for (int i = 0; i < C::FM; ++i)
+#pragma unroll
+        for (int j = 0; j < C::FN; ++j) {
+          if (ks == 0) {
+            f32x16_t z;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) z[r] = 0.f;
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[c][i], bq[j][ks], z, 0, 0, 0);
+          } else {
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[c][i], bq[j][ks], acc[i][j], 0, 0, 0);
+          }
+        }
+      __builtin_amdgcn_sched_group_barrier(0x100, C::FM, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, C::FM * C::FN, 0);
+    }
+    if (!late) reduce(reinterpret_cast<const float*>(stage + C::TILE_ELEMS + wave * C::RB * 2), t);
+  }
+  if (late) {
+    const uint16_t* stage = lds_dyn + ((t_end - 1 - t_begin) % C::STAGES) * C::STAGE_ELEMS;
+    reduce(reinterpret_cast<const float*>(stage + C::TILE_ELEMS + wave * C::RB * 2), t_end - 1);
+  }
+#pragma unroll
+  for (int j = 0; j < C::FN; ++j) {
+    Top2 o;
+    o.v1 = __shfl_xor(best[j].v1, 32, 64); o.g1 = __shfl_xor(best[j].g1, 32, 64);
+    o.v2 = __shfl_xor(best[j].v2, 32, 64); o.g2 = __shfl_xor(best[j].g2, 32, 64);
+    Top2 m = best[j];
+    top2_push(m, o.v1, o.g1);
+    top2_push(m, o.v2, o.g2);
+    const int q = q_base + j * 32 + (lane & 31);
+    if (half == 0 && q < B) partial[(size_t)split * B + q] = m;
+  }
+}
+
 // fp32 keys: plain FMA.  grid (B); thread t scans groups t, t + 256, ...
 __global__ __launch_bounds__(256) void match_f32_kernel(const float* __restrict__ bank,
                                                         const float* __restrict__ binv_eff, int N, int K,
@@ -480,7 +650,22 @@ template <int K_>
 static llmc_status_t launch_stream(const llmc_bank* bank, const void* d_fp, int B, Top2* partial, int* ns_out,
                                    hipStream_t st) {
   if (stream_waves(B) == 4) return launch_stream_nw<K_, 4>(bank, d_fp, B, partial, ns_out, st);
-  return launch_stream_nw<K_, 8>(bank, d_fp, B, partial, ns_out, st);
+  using C = SkewCfg<K_>;
+  const llmc_bank_desc_t& D = bank->desc;
+  static bool attr_set = false;
+  if (!attr_set) {
+    LLMC_HIP(hipFuncSetAttribute((const void*)(match_skew_kernel<K_>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                 (int)C::LDS_BYTES));
+    attr_set = true;
+  }
+  int nqb, ns, per;
+  stream_plan(D.n_slots, B, C::RB, C::QB, &nqb, &ns, &per);
+  const unsigned grid = (unsigned)((ns + 7) / 8) * nqb * 8;    // splits are dealt to the 8 XCDs
+  ProfScope ps_("match_stream_kernel", st);
+  hipLaunchKernelGGL((match_skew_kernel<K_>), dim3(grid), dim3(512), C::LDS_BYTES, st, (const uint16_t*)D.d_fp,
+                     bank->d_binv_eff, D.n_slots, (const uint16_t*)d_fp, B, nqb, ns, per, partial);
+  *ns_out = ns;
+  return LLMC_OK;
 }
 
 llmc_status_t launch_match(const llmc_bank* bank, const void* d_fp, const float* d_inv, int B, float tau,

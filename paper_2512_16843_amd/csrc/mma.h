@@ -137,6 +137,8 @@ namespace dma {
 #define LLMC_GPTR(p) ((const void __attribute__((address_space(1)))*)(p))
 #define LLMC_LPTR(p) ((void __attribute__((address_space(3)))*)(p))
 #define LLMC_WAIT_VM(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
+// wait until at most n LDS / scalar-memory operations of this wavefront are outstanding (n <= 15)
+#define LLMC_WAIT_LGKM(n) __builtin_amdgcn_s_waitcnt(0xC07F | ((n) << 8))
 
 __device__ __forceinline__ void barrier() {
   asm volatile("" ::: "memory");

@@ -189,7 +189,9 @@ def unit_rows(g, n, k):
     return x / np.linalg.norm(x, axis=1, keepdims=True)
 
 
-@pytest.mark.parametrize("N,B,k", [(1000, 37, 64), (130, 5, 256), (4096, 200, 256), (64, 1, 32)])
+@pytest.mark.parametrize("N,B,k", [(1000, 37, 64), (130, 5, 256), (4096, 200, 256), (64, 1, 32),
+                                   # more than 256 queries: the skewed 8-wavefront kernel, ragged banks, one-tile splits
+                                   (1000, 300, 64), (5000, 513, 128), (130, 260, 256), (70000, 700, 256)])
 def test_match_bf16_random_bank_with_holes(L, N, B, k):
     say(f"match bf16 random N={N} B={B} k={k}")
     g = np.random.Generator(np.random.PCG64(N + B))
