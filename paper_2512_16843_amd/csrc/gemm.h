@@ -124,61 +124,74 @@ __global__ __launch_bounds__(C::THREADS) void gemm_bf16_kernel(GemmArgs g, int t
   }
 }
 
-// Epilogue through LDS: the accumulators are laid out as an fp32 [BM][BN + 8] block, then every
-// thread takes 8 consecutive columns of a row, so that bias, residual and output move as
-// 16-byte vectors along rows.  `stage` must hold BM * (BN + 8) floats and be free of readers.
+// Epilogue through LDS, one wavefront at a time: a wavefront lays one 32-row block of its
+// accumulators out as fp32 [32][FN * 32 + 4] in a region of its own, then its lanes take 8
+// consecutive columns of a row each, so that bias, residual and output move as 16-byte vectors
+// along rows.  No other wavefront touches the region, and LDS operations of one wavefront
+// complete in order, so no barrier is needed between the two halves.  `stage` must hold
+// NW * 32 * (FN * 32 + 4) floats and be free of readers.
 template <class C>
-__device__ __forceinline__ void gemm_epilogue_lds(const GemmArgs& g, f32x16_t (&acc)[C::FM][C::FN], int m0, int n0,
-                                                  int M, float* stage) {
-  constexpr int STRIDE = C::BN + 8;
-  const int tid = threadIdx.x;
-  const int lane = tid & 63, wave = tid >> 6;
+struct WaveEpilogue {
+  static constexpr int COLS = C::FN * 32, STRIDE = COLS + 4, REGION = 32 * STRIDE;   // floats
+  static constexpr int LANES_PER_ROW = COLS / 8, ROWS_PER_PASS = 64 / LANES_PER_ROW;
+  static constexpr size_t BYTES = (size_t)C::NW * REGION * 4;
+  static_assert(64 % LANES_PER_ROW == 0 && 32 % ROWS_PER_PASS == 0, "row vectors tile the block");
+};
+
+template <class C>
+__device__ __forceinline__ void gemm_epilogue_wave(const GemmArgs& g, f32x16_t (&acc)[C::FM][C::FN], int m0, int n0,
+                                                   int M, float* stage) {
+  using E = WaveEpilogue<C>;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wm = wave / C::WN, wn = wave % C::WN;
-#pragma unroll
-  for (int i = 0; i < C::FM; ++i)
-#pragma unroll
-    for (int j = 0; j < C::FN; ++j) {
-      float* p = stage + (wm * (C::BM / C::WM) + i * 32) * STRIDE + wn * (C::BN / C::WN) + j * 32 + (lane & 31);
-#pragma unroll
-      for (int r = 0; r < 16; ++r) p[frag_row(lane, r) * STRIDE] = acc[i][j][r];
-    }
-  __syncthreads();
+  float* region = stage + wave * E::REGION;
   const uint16_t* bias = (const uint16_t*)g.bias;
   const uint16_t* resid = (const uint16_t*)g.resid;
   uint16_t* out = (uint16_t*)g.out;
-  constexpr int GROUPS_PER_ROW = C::BN / 8;
-  for (int idx = tid; idx < C::BM * GROUPS_PER_ROW; idx += C::THREADS) {
-    const int row = idx / GROUPS_PER_ROW, c8 = (idx % GROUPS_PER_ROW) * 8;
-    const int m = m0 + row, n = n0 + c8;
-    if (m >= M || n >= g.N) continue;
-    float v[8];
-    const float4 lo = *reinterpret_cast<const float4*>(stage + row * STRIDE + c8);
-    const float4 hi = *reinterpret_cast<const float4*>(stage + row * STRIDE + c8 + 4);
-    v[0] = lo.x; v[1] = lo.y; v[2] = lo.z; v[3] = lo.w; v[4] = hi.x; v[5] = hi.y; v[6] = hi.z; v[7] = hi.w;
-    if (bias) {
-      float b[8];
-      Vec16<bf16_t>::load(reinterpret_cast<const bf16_t*>(bias + n), b);
+  const int prow = lane / E::LANES_PER_ROW, c8 = (lane % E::LANES_PER_ROW) * 8;
+  const int n = n0 + wn * E::COLS + c8;
+  float bv[8];
 #pragma unroll
-      for (int e = 0; e < 8; ++e) v[e] += b[e];
-    }
-    if (g.act) {
+  for (int e = 0; e < 8; ++e) bv[e] = 0.f;
+  if (bias && n < g.N) Vec16<bf16_t>::load(reinterpret_cast<const bf16_t*>(bias + n), bv);
 #pragma unroll
-      for (int e = 0; e < 8; ++e) v[e] = apply_act(v[e], g.act);
-    }
-    if (resid) {
-      float rr[8];
-      Vec16<bf16_t>::load(reinterpret_cast<const bf16_t*>(resid + map_row(g.r_rows, m, g.S) * g.ldr + n), rr);
+  for (int i = 0; i < C::FM; ++i) {
 #pragma unroll
-      for (int e = 0; e < 8; ++e) v[e] += rr[e];
+    for (int j = 0; j < C::FN; ++j) {
+      float* p = region + j * 32 + (lane & 31);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) p[frag_row(lane, r) * E::STRIDE] = acc[i][j][r];
     }
-    Vec16<bf16_t>::store(reinterpret_cast<bf16_t*>(out + map_row(g.o_rows, m, g.S) * g.ldo + n), v);
+    const int mb = m0 + wm * (C::BM / C::WM) + i * 32;
+#pragma unroll
+    for (int pass = 0; pass < 32 / E::ROWS_PER_PASS; ++pass) {
+      const int row = pass * E::ROWS_PER_PASS + prow;
+      const int m = mb + row;
+      const float4 lo = *reinterpret_cast<const float4*>(region + row * E::STRIDE + c8);
+      const float4 hi = *reinterpret_cast<const float4*>(region + row * E::STRIDE + c8 + 4);
+      if (m >= M || n >= g.N) continue;
+      float v[8] = {lo.x + bv[0], lo.y + bv[1], lo.z + bv[2], lo.w + bv[3],
+                    hi.x + bv[4], hi.y + bv[5], hi.z + bv[6], hi.w + bv[7]};
+      if (g.act) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = apply_act(v[e], g.act);
+      }
+      if (resid) {
+        float rr[8];
+        Vec16<bf16_t>::load(reinterpret_cast<const bf16_t*>(resid + map_row(g.r_rows, m, g.S) * g.ldr + n), rr);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] += rr[e];
+      }
+      Vec16<bf16_t>::store(reinterpret_cast<bf16_t*>(out + map_row(g.o_rows, m, g.S) * g.ldo + n), v);
+    }
   }
-  __syncthreads();
+  dma::barrier();      // the next tile's loads overwrite every region
 }
 
 template <class C>
 constexpr size_t gemm_dma_smem_bytes() {
-  return C::LDS_BYTES > (size_t)C::BM * (C::BN + 8) * 4 ? C::LDS_BYTES : (size_t)C::BM * (C::BN + 8) * 4;
+  return C::LDS_BYTES > WaveEpilogue<C>::BYTES ? C::LDS_BYTES : WaveEpilogue<C>::BYTES;
 }
 
 // Same contract, main loop with direct global -> LDS loads (C is a DmaCfg); K % 64 == 0.
@@ -225,7 +238,7 @@ __global__ __launch_bounds__(C::THREADS) void gemm_bf16_dma_kernel(GemmArgs g, i
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
   mma_block_dma<C>(a_ptr, b_ptr, g.K, lds_dyn, acc);
-  gemm_epilogue_lds<C>(g, acc, m0, n0, M, reinterpret_cast<float*>(lds_dyn));
+  gemm_epilogue_wave<C>(g, acc, m0, n0, M, reinterpret_cast<float*>(lds_dyn));
   }
 }
 

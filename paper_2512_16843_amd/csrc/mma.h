@@ -216,6 +216,11 @@ __device__ __forceinline__ void mma_block_dma(const uint16_t* const (&a_ptr)[C::
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
       const int c = ks & 1, n = c ^ 1;
+      // this step's fragments were requested one step ago: wait for them BEFORE requesting the next
+      // ones, so that the wait never covers a request that has only just been issued
+      __builtin_amdgcn_sched_barrier(0);
+      LLMC_WAIT_LGKM(0);
+      __builtin_amdgcn_sched_barrier(0);
       if (ks + 1 < 4) {
 #pragma unroll
         for (int i = 0; i < C::FM; ++i)
