@@ -80,7 +80,24 @@ __global__ __launch_bounds__(1024) void project_kernel(const float* __restrict__
   for (int i = threadIdx.x; i < d; i += nthreads) {
     const float* src = partial + (size_t)b * n_chunks * d + i;
     float s = 0.f;
-    for (int c = 0; c < n_chunks; ++c) s += src[(size_t)c * d];
+    // eight chunk partials in flight; added in ascending chunk order
+    constexpr int UC = 8;
+    int c = 0;
+    for (; c + UC <= n_chunks; c += UC) {
+      float x[UC];
+#pragma unroll
+      for (int u = 0; u < UC; ++u) x[u] = src[(size_t)(c + u) * d];
+#pragma unroll
+      for (int u = 0; u < UC; ++u) s += x[u];
+    }
+    {
+      float x[UC];
+#pragma unroll
+      for (int u = 0; u < UC; ++u) x[u] = c + u < n_chunks ? src[(size_t)(c + u) * d] : 0.f;
+#pragma unroll
+      for (int u = 0; u < UC; ++u)
+        if (c + u < n_chunks) s += x[u];
+    }
     p[i] = s * inv_S;
   }
   __syncthreads();

@@ -510,10 +510,19 @@ __global__ __launch_bounds__(256) void match_finalize_kernel(
   if (b >= B) return;
   const int lane = threadIdx.x & 63;
   Top2 t = top2_empty();
-  for (int s = lane; s < n_split; s += 64) {
-    const Top2 c = partial[(size_t)s * B + b];
-    top2_push(t, c.v1, c.g1);
-    top2_push(t, c.v2, c.g2);
+  // four partial results in flight per lane, merged in ascending split order
+  for (int s0 = lane; s0 < n_split; s0 += 4 * 64) {
+    Top2 c[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int s = s0 + u * 64;
+      c[u] = s < n_split ? partial[(size_t)s * B + b] : top2_empty();
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      top2_push(t, c[u].v1, c[u].g1);
+      top2_push(t, c[u].v2, c[u].g2);
+    }
   }
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) {
@@ -542,17 +551,17 @@ __global__ __launch_bounds__(256) void match_finalize_kernel(
     const double bj = (double)binv[jc];
     const T* kp = bank + (size_t)jc * K + part * per;
     double a = 0.0;
-    // four 16-byte vectors of the query and of the key in flight; products added in ascending order
+    // eight 16-byte vectors of the query and of the key in flight; products added in ascending order
     int i = 0;
-    for (; i + 4 * VEC <= per; i += 4 * VEC) {
-      float x[4][VEC], y[4][VEC];
+    for (; i + 8 * VEC <= per; i += 8 * VEC) {
+      float x[8][VEC], y[8][VEC];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
+      for (int u = 0; u < 8; ++u) {
         Vec16<T>::load(qp + i + u * VEC, x[u]);
         Vec16<T>::load(kp + i + u * VEC, y[u]);
       }
 #pragma unroll
-      for (int u = 0; u < 4; ++u)
+      for (int u = 0; u < 8; ++u)
 #pragma unroll
         for (int e = 0; e < VEC; ++e) a += (double)x[u][e] * (double)y[u][e];
     }
