@@ -19,6 +19,8 @@ What follows the paper, and where:
 * threshold    -- Section IV-A case equation and Algorithm 1: strict ">".
 * gated layer  -- Section IV-A case equation: cached h_l on a hit, f_l(h_{l-1})
   otherwise; Algorithm 1: store the computed h_l on a miss.
+* sign-bit keys -- Section IV-B (SimHash), Section III-A: the sign of each
+  projection, compared by Hamming distance; cos(pi H / k) stands for the cosine.
 * eviction     -- Section IV-D, first policy: least recently used.
 * f_l          -- Section V-A names the model families; the blocks themselves
   are the textbook post-LN encoder block and pre-LN causal decoder block.
@@ -26,7 +28,9 @@ What follows the paper, and where:
 Pins (see tests/test_oracle_*.py): closed forms for the pooling/projection,
 brute-force nearest neighbour, threshold invariants, tau > 1 == plain forward,
 resubmission hits at similarity 1, torch.nn.functional cross-check of f_l in
-float64, scripted LRU trace against a list-based simulation.  The paper prints
+float64, scripted LRU trace against a list-based simulation; sign-bit keys:
+bit order against a hand-made word, Hamming distance against Python's bit_count,
+the angle law of random hyperplanes, monotone agreement with the cosine match.  The paper prints
 no worked numerical example, so absolute values rest on those pins alone.
 """
 from __future__ import annotations
@@ -246,6 +250,104 @@ def layer_forward(x: np.ndarray, w: Dict[str, np.ndarray], arch: int, n_heads: i
 
 # ----------------------------------------------------------------------------
 # the bank C_l (Section III-B) with insertion and LRU (Sections III-E, IV-D)
+# ----------------------------------------------------------------------------
+# sign-bit keys (Section IV-B "SimHash"; Section III-A "MinHash or SimHash-based
+# techniques"; Section IV-B "compared via cosine similarity or LSH")
+# ----------------------------------------------------------------------------
+#
+# The real-valued key above is the SimHash projection before the sign is taken.
+# Taking the sign of each of the k projections gives a k-bit key; two keys are
+# compared by their Hamming distance H, and cos(pi * H / k) estimates the cosine
+# of the angle between the pooled vectors (each random hyperplane separates two
+# vectors with probability angle / pi).  The threshold of the case equation is
+# applied to that estimate: hit  <=>  cos(pi * H / k) > tau  <=>  H <= max_hamming(tau, k).
+# The paper fixes neither the bit order nor the sign of zero; here bit i of a key
+# is word i // 32, position i % 32 (least significant first), and v_i >= 0 gives 1.
+
+NO_MATCH_DIST = 0x7FFFFFFF
+
+
+def simhash_projection(h: np.ndarray, P: np.ndarray, c: Optional[np.ndarray]) -> np.ndarray:
+    """v = P^T mean_t(h) + c for each sequence, float64 [B, k] (the values whose signs are the key)."""
+    h = np.asarray(h, dtype=np.float64)
+    P = np.asarray(P, dtype=np.float64)
+    p = h.sum(axis=1) / float(h.shape[1])
+    v = p @ P
+    if c is not None:
+        v = v + np.asarray(c, dtype=np.float64)[None, :]
+    return v
+
+
+def pack_bits(bits: np.ndarray) -> np.ndarray:
+    """[.., k] booleans -> [.., k / 32] uint32 words; bit i sits in word i // 32 at position i % 32."""
+    bits = np.asarray(bits).astype(bool)
+    k = bits.shape[-1]
+    assert k % 32 == 0
+    out = np.zeros(bits.shape[:-1] + (k // 32,), dtype=np.uint32)
+    for i in range(k):
+        out[..., i // 32] |= (bits[..., i].astype(np.uint32) << np.uint32(i % 32))
+    return out
+
+
+def unpack_bits(words: np.ndarray, k: int) -> np.ndarray:
+    """Inverse of pack_bits: [.., k / 32] uint32 -> [.., k] booleans."""
+    words = np.asarray(words, dtype=np.uint32)
+    out = np.zeros(words.shape[:-1] + (k,), dtype=bool)
+    for i in range(k):
+        out[..., i] = ((words[..., i // 32] >> np.uint32(i % 32)) & np.uint32(1)).astype(bool)
+    return out
+
+
+def fingerprint_bits(h: np.ndarray, P: np.ndarray, c: Optional[np.ndarray]) -> np.ndarray:
+    """Sign-bit key of each sequence: packed uint32 [B, k / 32]."""
+    return pack_bits(simhash_projection(h, P, c) >= 0.0)
+
+
+def hamming(q_words: np.ndarray, bank_words: np.ndarray, k: int) -> np.ndarray:
+    """Hamming distance of every query key with every bank key, int64 [B, N]."""
+    qb = unpack_bits(q_words, k)
+    bb = unpack_bits(bank_words, k)
+    out = np.zeros((qb.shape[0], bb.shape[0]), dtype=np.int64)
+    for i in range(k):
+        out += (qb[:, i][:, None] != bb[:, i][None, :])
+    return out
+
+
+def match_bits(q_words: np.ndarray, bank_words: np.ndarray, valid: np.ndarray, k: int
+               ) -> Tuple[np.ndarray, np.ndarray]:
+    """Nearest valid bank key per query by Hamming distance: (idx [B] int32, dist [B] int32).
+
+    Lowest slot wins ties.  With no valid entry idx = -1 and dist = NO_MATCH_DIST.
+    """
+    B = np.asarray(q_words).shape[0]
+    valid = np.asarray(valid).astype(bool)
+    if valid.size == 0 or not valid.any():
+        return np.full((B,), -1, np.int32), np.full((B,), NO_MATCH_DIST, np.int32)
+    H = hamming(q_words, bank_words, k)
+    H[:, ~valid] = NO_MATCH_DIST
+    idx = np.argmin(H, axis=1)            # first occurrence of the minimum
+    return idx.astype(np.int32), H[np.arange(B), idx].astype(np.int32)
+
+
+def cosine_estimate(dist: np.ndarray, k: int) -> np.ndarray:
+    """cos(pi * H / k): the cosine that a Hamming distance H between k-bit sign keys stands for."""
+    return np.cos(np.pi * np.asarray(dist, dtype=np.float64) / float(k))
+
+
+def max_hamming(tau: float, k: int) -> int:
+    """Largest H in 0..k with cos(pi * H / k) > tau; -1 if there is none (tau >= 1)."""
+    best = -1
+    for H in range(k + 1):
+        if math.cos(math.pi * H / k) > tau:
+            best = H
+    return best
+
+
+def threshold_bits(idx: np.ndarray, dist: np.ndarray, max_h: int) -> np.ndarray:
+    """Hit iff a valid entry was found within max_h bits."""
+    return (np.asarray(idx) >= 0) & (np.asarray(dist) <= int(max_h))
+
+
 # ----------------------------------------------------------------------------
 
 class Bank:
