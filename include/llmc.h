@@ -240,6 +240,43 @@ llmc_status_t llmc_match(const llmc_bank_t* bank, const void* d_fp, const float*
                          llmc_stream_t stream);
 size_t llmc_match_workspace_bytes(const llmc_bank_t* bank, int32_t B);
 
+/* ---- sign-bit keys (SimHash) and their Hamming match ------------------------------ */
+
+/*
+ * Section IV-B names SimHash as the dimensionality reduction and Section III-A hashing as the
+ * route to cheap comparison: the key is the SIGN of each of the k projections of the pooled
+ * input.  For each sequence b of d_h [B, S, d]:  p = (1/S) sum_t h[b,t,:];  v = P^T p + c;
+ * bit i of the key = (v_i >= 0).  d_bits_out [B, k / 32] uint32: bit i is word i / 32, position
+ * i % 32 (least significant first).  Pooling and projection are those of llmc_fingerprint
+ * (same workspace size, same fixed fp32 accumulation order); k % 32 == 0, k <= 1024.
+ */
+llmc_status_t llmc_fingerprint_bits(const void* d_h, int32_t B, int32_t S, int32_t d, int32_t dtype,
+                                    const void* d_proj, const float* d_bias, int32_t k,
+                                    uint32_t* d_bits_out, void* d_workspace, size_t workspace_bytes,
+                                    llmc_stream_t stream);
+
+/*
+ * Section IV-B "compared via cosine similarity or LSH", with the test of the case equation
+ * (Section IV-A): for each query key the valid bank key at the smallest Hamming distance H;
+ * cos(pi H / k) stands for the cosine of the two pooled inputs, so  sim > tau  becomes
+ * H <= max_hamming  with  max_hamming = llmc_max_hamming(tau, k).
+ *   d_bank_bits [N, k / 32], d_valid [N] (0 = free slot), d_query_bits [B, k / 32]: device, uint32 words as above
+ *   d_idx [B]: nearest valid slot, lowest slot among equal distances, -1 if no slot is valid
+ *   d_dist [B]: its Hamming distance, 0x7FFFFFFF if none;  d_hit [B]: idx >= 0 and dist <= max_hamming
+ *   (d_dist, d_hit may be NULL).  Integer work throughout: results are exact.
+ * d_workspace: at least llmc_match_bits_workspace_bytes(N, k, B) bytes.  Nothing is allocated or synchronised.
+ * Errors: INVALID_ARG (null, sizes <= 0), SHAPE (k % 32 != 0 or k > 1024, N > 2^30), WORKSPACE.
+ */
+llmc_status_t llmc_match_bits(const uint32_t* d_bank_bits, const uint8_t* d_valid, int32_t N, int32_t k,
+                              const uint32_t* d_query_bits, int32_t B, int32_t max_hamming,
+                              int32_t* d_idx, int32_t* d_dist, uint8_t* d_hit, void* d_workspace,
+                              size_t workspace_bytes, llmc_stream_t stream);
+size_t llmc_match_bits_workspace_bytes(int32_t N, int32_t k, int32_t B);
+
+/* Host arithmetic, no device work: the largest H in 0..k with cos(pi * H / k) > tau, evaluated in
+ * binary64 as written; -1 if there is none (tau >= 1) or k <= 0. */
+int32_t llmc_max_hamming(float tau, int32_t k);
+
 /* ---- gather ----------------------------------------------------------------- */
 
 /*

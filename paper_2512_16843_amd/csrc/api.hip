@@ -1,6 +1,7 @@
 // C ABI of libllmc.so: argument validation (before any HIP call) and the host-side
 // orchestration of the gated layer, which only enqueues kernels on the caller's stream.
 #include <algorithm>
+#include <math.h>
 #include <stdarg.h>
 #include <stdio.h>
 #include <string.h>
@@ -186,6 +187,45 @@ llmc_status_t llmc_fingerprint(const void* d_h, int32_t B, int32_t S, int32_t d,
           "fingerprint workspace needs %zu bytes", fingerprint_ws_bytes(B, S, d));
   return launch_fingerprint(d_h, nullptr, B, S, d, dtype, d_proj, d_bias, k, d_fp_out, d_inv_norm_out, d_workspace,
                             (hipStream_t)stream);
+}
+
+llmc_status_t llmc_fingerprint_bits(const void* d_h, int32_t B, int32_t S, int32_t d, int32_t dtype, const void* d_proj,
+                                    const float* d_bias, int32_t k, uint32_t* d_bits_out, void* d_workspace,
+                                    size_t workspace_bytes, llmc_stream_t stream) {
+  REQUIRE(d_h && d_proj && d_bits_out, LLMC_ERR_INVALID_ARG, "NULL argument");
+  LLMC_TRY(check_fp_shape(B, S, d, dtype, k));
+  REQUIRE(aligned16(d_h) && aligned16(d_proj), LLMC_ERR_SHAPE, "arrays must be 16-byte aligned");
+  REQUIRE(d_workspace && workspace_bytes >= fingerprint_ws_bytes(B, S, d), LLMC_ERR_WORKSPACE,
+          "fingerprint workspace needs %zu bytes", fingerprint_ws_bytes(B, S, d));
+  return launch_fingerprint_bits(d_h, B, S, d, dtype, d_proj, d_bias, k, d_bits_out, d_workspace, (hipStream_t)stream);
+}
+
+size_t llmc_match_bits_workspace_bytes(int32_t N, int32_t k, int32_t B) {
+  if (N <= 0 || B <= 0 || k <= 0 || k % 32 != 0 || k > 1024 || N > (1 << 30)) return 0;
+  return match_bits_ws_bytes(N, k, B);
+}
+
+int32_t llmc_max_hamming(float tau, int32_t k) {
+  int32_t best = -1;
+  for (int32_t H = 0; H <= k; ++H)
+    if (cos(3.141592653589793238462643383279502884 * (double)H / (double)k) > (double)tau) best = H;
+  return best;
+}
+
+llmc_status_t llmc_match_bits(const uint32_t* d_bank_bits, const uint8_t* d_valid, int32_t N, int32_t k,
+                              const uint32_t* d_query_bits, int32_t B, int32_t max_hamming, int32_t* d_idx,
+                              int32_t* d_dist, uint8_t* d_hit, void* d_workspace, size_t workspace_bytes,
+                              llmc_stream_t stream) {
+  REQUIRE(d_bank_bits && d_valid && d_query_bits && d_idx, LLMC_ERR_INVALID_ARG, "NULL argument");
+  REQUIRE(N > 0 && B > 0, LLMC_ERR_INVALID_ARG, "N and B must be positive");
+  REQUIRE(k > 0 && k % 32 == 0 && k <= 1024, LLMC_ERR_SHAPE, "k=%d must be a multiple of 32, at most 1024", k);
+  REQUIRE(N <= (1 << 30), LLMC_ERR_SHAPE, "N=%d exceeds 2^30", N);
+  REQUIRE(B <= 65535 * 256, LLMC_ERR_SHAPE, "B=%d too large", B);
+  const size_t need = match_bits_ws_bytes(N, k, B);
+  REQUIRE(d_workspace && workspace_bytes >= need, LLMC_ERR_WORKSPACE, "bit-match workspace needs %zu bytes", need);
+  REQUIRE(((uintptr_t)d_workspace & 255) == 0, LLMC_ERR_SHAPE, "workspace must be 256-byte aligned");
+  return launch_match_bits(d_bank_bits, d_valid, N, k, d_query_bits, B, max_hamming, d_idx, d_dist, d_hit, d_workspace,
+                           (hipStream_t)stream);
 }
 
 llmc_status_t llmc_inv_norm(const void* d_fp, int64_t n, int32_t k, int32_t dtype, float* d_inv_norm_out,

@@ -140,6 +140,12 @@ size_t fingerprint_ws_bytes(int B, int S, int d);
 llmc_status_t launch_fingerprint(const void* d_h, const int32_t* d_rowmap_unused, int B, int S, int d, int dtype,
                                  const void* d_proj, const float* d_bias, int k, void* d_fp, float* d_inv,
                                  void* ws, hipStream_t st);
+llmc_status_t launch_fingerprint_bits(const void* d_h, int B, int S, int d, int dtype, const void* d_proj,
+                                      const float* d_bias, int k, uint32_t* d_bits, void* ws, hipStream_t st);
+size_t match_bits_ws_bytes(int N, int k, int B);
+llmc_status_t launch_match_bits(const uint32_t* d_bank_bits, const uint8_t* d_valid, int N, int k,
+                                const uint32_t* d_query_bits, int B, int max_hamming, int32_t* d_idx, int32_t* d_dist,
+                                uint8_t* d_hit, void* ws, hipStream_t st);
 llmc_status_t launch_inv_norm(const void* d_fp, int64_t n, int k, int dtype, float* d_out, hipStream_t st);
 
 // match.hip

@@ -68,7 +68,8 @@ __global__ void pool_kernel(const T* __restrict__ h, int S, int d, int G, int R,
 template <typename T>
 __global__ __launch_bounds__(1024) void project_kernel(const float* __restrict__ partial, int n_chunks, int S, int d,
                                                        const T* __restrict__ P, const float* __restrict__ bias, int k,
-                                                       int parts, T* __restrict__ fp_out, float* __restrict__ inv_out) {
+                                                       int parts, T* __restrict__ fp_out, float* __restrict__ inv_out,
+                                                       uint32_t* __restrict__ bits_out) {
   extern __shared__ float sm[];   // p[d] | v[parts][k]
   float* p = sm;
   float* vpart = sm + d;
@@ -151,8 +152,15 @@ __global__ __launch_bounds__(1024) void project_kernel(const float* __restrict__
     for (int s = 1; s < parts; ++s) v += vpart[s * k + j];
     if (bias) v += bias[j];
   }
-  // |v|^2 in fp64: lanes of each wave, then waves in order
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (bits_out) {
+    // sign-bit key (Section IV-B, SimHash): bit j = (v_j >= 0), 32 per word, least significant first
+    const unsigned long long m = __ballot(own && v >= 0.f);
+    if (lane == 0 && wave * 64 < k) bits_out[(size_t)b * (k / 32) + wave * 2] = (uint32_t)m;
+    if (lane == 32 && wave * 64 + 32 < k) bits_out[(size_t)b * (k / 32) + wave * 2 + 1] = (uint32_t)(m >> 32);
+    return;
+  }
+  // |v|^2 in fp64: lanes of each wave, then waves in order
   const int n_waves_k = (k + 63) / 64;
   double sq = own ? (double)v * (double)v : 0.0;
   sq = wave_sum(sq);
@@ -203,7 +211,7 @@ size_t fingerprint_ws_bytes(int B, int S, int d) {
 
 template <typename T>
 static llmc_status_t fingerprint_t(const T* h, int B, int S, int d, const T* P, const float* bias, int k,
-                                   T* fp, float* inv, float* partial, hipStream_t st) {
+                                   T* fp, float* inv, uint32_t* bits, float* partial, hipStream_t st) {
   constexpr int VEC = Vec16<T>::N;
   const int G = d / VEC;
   const int R = G <= 512 ? 2 : 1;   // token rows split over thread groups; depends on d only
@@ -218,7 +226,7 @@ static llmc_status_t fingerprint_t(const T* h, int B, int S, int d, const T* P, 
   {
     ProfScope ps_("project_kernel", st);
     hipLaunchKernelGGL(project_kernel<T>, dim3(B), dim3(std::max(cgs * parts, k)),
-                       (size_t)(d + parts * k) * sizeof(float), st, partial, n_chunks, S, d, P, bias, k, parts, fp, inv);
+                       (size_t)(d + parts * k) * sizeof(float), st, partial, n_chunks, S, d, P, bias, k, parts, fp, inv, bits);
   }
   LLMC_LAUNCH_CHECK("project_kernel");
   return LLMC_OK;
@@ -228,8 +236,18 @@ llmc_status_t launch_fingerprint(const void* d_h, const int32_t*, int B, int S, 
                                  const float* d_bias, int k, void* d_fp, float* d_inv, void* ws, hipStream_t st) {
   if (dtype == LLMC_F32)
     return fingerprint_t<float>((const float*)d_h, B, S, d, (const float*)d_proj, d_bias, k, (float*)d_fp, d_inv,
-                                (float*)ws, st);
+                                nullptr, (float*)ws, st);
   return fingerprint_t<bf16_t>((const bf16_t*)d_h, B, S, d, (const bf16_t*)d_proj, d_bias, k, (bf16_t*)d_fp, d_inv,
+                               nullptr, (float*)ws, st);
+}
+
+// same pooling and projection, but the key is the sign of each projection
+llmc_status_t launch_fingerprint_bits(const void* d_h, int B, int S, int d, int dtype, const void* d_proj,
+                                      const float* d_bias, int k, uint32_t* d_bits, void* ws, hipStream_t st) {
+  if (dtype == LLMC_F32)
+    return fingerprint_t<float>((const float*)d_h, B, S, d, (const float*)d_proj, d_bias, k, nullptr, nullptr, d_bits,
+                                (float*)ws, st);
+  return fingerprint_t<bf16_t>((const bf16_t*)d_h, B, S, d, (const bf16_t*)d_proj, d_bias, k, nullptr, nullptr, d_bits,
                                (float*)ws, st);
 }
 

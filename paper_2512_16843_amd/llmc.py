@@ -29,7 +29,8 @@ EXPORTS = [
     "llmc_fingerprint", "llmc_fingerprint_workspace_bytes", "llmc_inv_norm", "llmc_match",
     "llmc_match_workspace_bytes", "llmc_gather_hits", "llmc_layer_forward_gated",
     "llmc_layer_workspace_bytes", "llmc_profile_begin", "llmc_profile_report", "llmc_profile_end",
-    "llmc_last_error", "llmc_version",
+    "llmc_last_error", "llmc_version", "llmc_fingerprint_bits", "llmc_match_bits",
+    "llmc_match_bits_workspace_bytes", "llmc_max_hamming",
 ]
 
 
@@ -95,6 +96,12 @@ def lib() -> C.CDLL:
                                                u32, u64, vp, vp, C.POINTER(GateOut), vp, sz, vp]
         L.llmc_layer_workspace_bytes.argtypes = [C.POINTER(LayerDesc), i32, i32, i32]
         L.llmc_layer_workspace_bytes.restype = sz
+        L.llmc_fingerprint_bits.argtypes = [vp, i32, i32, i32, i32, vp, vp, i32, vp, vp, sz, vp]
+        L.llmc_match_bits.argtypes = [vp, vp, i32, i32, vp, i32, i32, vp, vp, vp, vp, sz, vp]
+        L.llmc_match_bits_workspace_bytes.argtypes = [i32, i32, i32]
+        L.llmc_match_bits_workspace_bytes.restype = sz
+        L.llmc_max_hamming.argtypes = [f32, i32]
+        L.llmc_max_hamming.restype = i32
         L.llmc_profile_begin.argtypes = [i32]
         L.llmc_profile_report.argtypes = [C.c_char_p, sz]
         L.llmc_profile_report.restype = i32
@@ -236,6 +243,33 @@ def llmc_match(bank: Bank, fp: torch.Tensor, inv_norm: torch.Tensor, tau: float,
                workspace: torch.Tensor, stream=None) -> None:
     _check(lib().llmc_match(bank.handle, _ptr(fp), _ptr(inv_norm), fp.shape[0], tau, _ptr(idx), _ptr(sim), _ptr(hit),
                             _ptr(near_tie), _ptr(workspace), workspace.numel(), _stream(stream)))
+
+
+def llmc_fingerprint_bits(h: torch.Tensor, proj: torch.Tensor, bias: Optional[torch.Tensor], bits_out: torch.Tensor,
+                          workspace: torch.Tensor, stream=None) -> None:
+    """Sign-bit keys: bits_out [B, k / 32] int32 (the words' bit patterns)."""
+    B, S, d = h.shape
+    assert bits_out.dtype == torch.int32 and tuple(bits_out.shape) == (B, proj.shape[1] // 32)
+    _check(lib().llmc_fingerprint_bits(_ptr(h), B, S, d, dtype_code(h.dtype), _ptr(proj), _ptr(bias), proj.shape[1],
+                                       _ptr(bits_out), _ptr(workspace), workspace.numel(), _stream(stream)))
+
+
+def llmc_match_bits_workspace_bytes(N: int, k: int, B: int) -> int:
+    return lib().llmc_match_bits_workspace_bytes(N, k, B)
+
+
+def llmc_max_hamming(tau: float, k: int) -> int:
+    return lib().llmc_max_hamming(tau, k)
+
+
+def llmc_match_bits(bank_bits: torch.Tensor, valid: torch.Tensor, query_bits: torch.Tensor, max_hamming: int,
+                    idx: torch.Tensor, dist: Optional[torch.Tensor], hit: Optional[torch.Tensor],
+                    workspace: torch.Tensor, stream=None) -> None:
+    N, W = bank_bits.shape
+    assert bank_bits.dtype == torch.int32 and query_bits.dtype == torch.int32 and query_bits.shape[1] == W
+    _check(lib().llmc_match_bits(_ptr(bank_bits), _ptr(valid), N, W * 32, _ptr(query_bits), query_bits.shape[0],
+                                 max_hamming, _ptr(idx), _ptr(dist), _ptr(hit), _ptr(workspace), workspace.numel(),
+                                 _stream(stream)))
 
 
 def llmc_gather_hits(bank: Bank, idx: torch.Tensor, rows: Optional[torch.Tensor], n: Optional[torch.Tensor],

@@ -102,3 +102,23 @@ def test_gated_layer_validation(lib):
     ld = layer()
     need = lib.llmc_layer_workspace_bytes(C.byref(ld), 2, 4, 0)
     assert need > 2 * 4 * (3 * 128 + 3 * 128 + 512) * 4
+
+
+def test_bit_key_entry_points_validate_and_max_hamming_matches_the_oracle(lib):
+    from oracle import llmc_oracle as O
+    fake = C.c_void_p(4096)
+    assert lib.llmc_match_bits(None, fake, 4, 64, fake, 2, 3, fake, None, None, fake, 1 << 20, None) == llmc.ERR_INVALID_ARG
+    assert lib.llmc_match_bits(fake, fake, 4, 48, fake, 2, 3, fake, None, None, fake, 1 << 20, None) == llmc.ERR_SHAPE
+    assert lib.llmc_match_bits(fake, fake, 4, 2048, fake, 2, 3, fake, None, None, fake, 1 << 20, None) == llmc.ERR_SHAPE
+    assert lib.llmc_match_bits(fake, fake, 0, 64, fake, 2, 3, fake, None, None, fake, 1 << 20, None) == llmc.ERR_INVALID_ARG
+    assert lib.llmc_match_bits(fake, fake, 4, 64, fake, 2, 3, fake, None, None, fake, 8, None) == llmc.ERR_WORKSPACE
+    assert lib.llmc_match_bits_workspace_bytes(4, 48, 2) == 0
+    assert lib.llmc_match_bits_workspace_bytes(1 << 20, 256, 4096) >= (1 << 20) * 4
+    assert lib.llmc_fingerprint_bits(None, 1, 1, 64, 0, fake, None, 32, fake, fake, 1 << 20, None) == llmc.ERR_INVALID_ARG
+    assert lib.llmc_fingerprint_bits(fake, 1, 1, 64, 0, fake, None, 40, fake, fake, 1 << 20, None) == llmc.ERR_SHAPE
+    assert lib.llmc_fingerprint_bits(fake, 1, 1, 64, 0, fake, None, 32, fake, fake, 8, None) == llmc.ERR_WORKSPACE
+    import numpy as np
+    for k in (32, 64, 256, 1024):
+        for tau in (-1.0, -0.5, 0.0, 0.3, 0.82, 0.9, 0.95, 0.98, 0.999, 0.99999, 1.0, 2.0):
+            assert lib.llmc_max_hamming(tau, k) == O.max_hamming(float(np.float32(tau)), k), (tau, k)
+    assert lib.llmc_max_hamming(0.5, 0) == -1

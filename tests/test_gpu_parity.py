@@ -281,6 +281,136 @@ def test_match_clustered_bank_scaled_stress(L):
 
 
 # ---------------------------------------------------------------------------
+# sign-bit keys and their Hamming match (integer work: bit-exact)
+# ---------------------------------------------------------------------------
+
+def words(t):
+    """int32 device tensor of key words -> uint32 numpy"""
+    return t.cpu().numpy().view(np.uint32)
+
+
+@pytest.mark.parametrize("dtype,B,S,d,k,use_bias", [
+    ("f32", 8, 32, 128, 64, False), ("bf16", 5, 37, 768, 256, False), ("bf16", 3, 128, 1024, 512, True),
+    ("f32", 2, 9, 64, 96, True), ("bf16", 70, 16, 192, 32, False),
+])
+def test_fingerprint_bits_match_oracle_signs(L, dtype, B, S, d, k, use_bias):
+    say(f"sign-bit fingerprint {dtype} B={B} S={S} d={d} k={k} bias={use_bias}")
+    g = np.random.Generator(np.random.PCG64(B * 1000 + k))
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    h = torch.from_numpy(g.standard_normal((B, S, d)).astype(np.float32)).to(tdt).cuda()
+    P = torch.from_numpy((g.standard_normal((d, k)) / np.sqrt(k)).astype(np.float32)).to(tdt).cuda()
+    bias = torch.from_numpy(0.05 * g.standard_normal(k).astype(np.float32)).cuda() if use_bias else None
+    bits = torch.empty((B, k // 32), dtype=torch.int32, device="cuda")
+    ws = torch.empty((L.llmc_fingerprint_workspace_bytes(B, S, d),), dtype=torch.uint8, device="cuda")
+    L.llmc_fingerprint_bits(h, P, bias, bits, ws)
+    torch.cuda.synchronize()
+    v = O.simhash_projection(npf(h), npf(P), None if bias is None else npf(bias))
+    want = v >= 0
+    got = O.unpack_bits(words(bits), k)
+    # the sign is decided in the kernel's fp32 arithmetic: projections within 1e-5 of the vector's scale of zero may differ
+    scale = np.sqrt((v * v).mean(axis=1, keepdims=True))
+    near_zero = np.abs(v) < 1e-5 * scale
+    assert np.array_equal(got[~near_zero], want[~near_zero])
+    say(f"  {int(near_zero.sum())} of {v.size} projections near zero, {int((got != want).sum())} signs differ there")
+    # the same input gives the same key wherever it sits
+    bits2 = torch.empty((1, k // 32), dtype=torch.int32, device="cuda")
+    L.llmc_fingerprint_bits(h[B - 1:B].contiguous(), P, bias, bits2, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(bits2[0], bits[B - 1])
+
+
+def run_match_bits(L, bank_bits, valid, q_bits, max_h):
+    N, W = bank_bits.shape
+    B = q_bits.shape[0]
+    idx = torch.empty((B,), dtype=torch.int32, device="cuda")
+    dist = torch.empty((B,), dtype=torch.int32, device="cuda")
+    hit = torch.empty((B,), dtype=torch.uint8, device="cuda")
+    ws = torch.empty((L.llmc_match_bits_workspace_bytes(N, W * 32, B),), dtype=torch.uint8, device="cuda")
+    L.llmc_match_bits(bank_bits, valid, q_bits, max_h, idx, dist, hit, ws)
+    torch.cuda.synchronize()
+    return idx.cpu().numpy(), dist.cpu().numpy(), hit.cpu().numpy().astype(bool)
+
+
+@pytest.mark.parametrize("N,B,k", [(1000, 37, 64), (130, 5, 256), (4099, 300, 256), (64, 1, 32), (777, 260, 128),
+                                   (50000, 513, 512), (333, 9, 96), (2500, 40, 1024)])
+def test_match_bits_is_exact(L, N, B, k):
+    say(f"Hamming match N={N} B={B} k={k}")
+    g = np.random.Generator(np.random.PCG64(N * 7 + B))
+    W_ = k // 32
+    bank = g.integers(0, 2 ** 32, size=(N, W_), dtype=np.uint64).astype(np.uint32)
+    q = g.integers(0, 2 ** 32, size=(B, W_), dtype=np.uint64).astype(np.uint32)
+    valid = (g.random(N) > 0.15).astype(np.uint8)
+    # a third of the queries are bank keys with a few bits flipped (some of FREE slots), some exact duplicates in the bank
+    for b in range(0, B, 3):
+        j = int(g.integers(0, N))
+        q[b] = bank[j]
+        for _ in range(int(g.integers(0, 6))):
+            i = int(g.integers(0, k))
+            q[b, i // 32] ^= np.uint32(1 << (i % 32))
+    if N > 40:
+        bank[N - 1] = bank[3]
+        bank[N // 2] = bank[3]
+        q[B - 1] = bank[3]
+        valid[[3, N // 2, N - 1]] = 1
+    max_h = O.max_hamming(f32(0.95), k)
+    idx, dist, hit = run_match_bits(L, torch.from_numpy(bank.view(np.int32)).cuda(), torch.from_numpy(valid).cuda(),
+                                    torch.from_numpy(q.view(np.int32)).cuda(), max_h)
+    oidx, odist = O.match_bits(q, bank, valid, k)
+    assert np.array_equal(idx, oidx), (np.nonzero(idx != oidx)[0][:8], idx[idx != oidx][:8], oidx[idx != oidx][:8])
+    assert np.array_equal(dist, odist)
+    assert np.array_equal(hit, O.threshold_bits(oidx, odist, max_h))
+    if N > 40:
+        assert idx[B - 1] == 3 and dist[B - 1] == 0 and hit[B - 1]
+    say(f"  {int(hit.sum())} hits within {max_h} bits")
+
+
+def test_match_bits_empty_bank_and_thresholds(L):
+    say("Hamming match: empty bank, max_hamming -1 and k")
+    g = np.random.Generator(np.random.PCG64(12))
+    N, B, k = 300, 7, 64
+    bank = g.integers(0, 2 ** 32, size=(N, 2), dtype=np.uint64).astype(np.uint32)
+    q = bank[:B].copy()
+    tb, tq = torch.from_numpy(bank.view(np.int32)).cuda(), torch.from_numpy(q.view(np.int32)).cuda()
+    idx, dist, hit = run_match_bits(L, tb, torch.zeros(N, dtype=torch.uint8).cuda(), tq, k)
+    assert np.all(idx == -1) and np.all(dist == O.NO_MATCH_DIST) and not hit.any()
+    ones = torch.ones(N, dtype=torch.uint8).cuda()
+    idx, dist, hit = run_match_bits(L, tb, ones, tq, -1)        # tau >= 1: nothing hits, not even an identical key
+    assert np.array_equal(idx, np.arange(B)) and np.all(dist == 0) and not hit.any()
+    idx, dist, hit = run_match_bits(L, tb, ones, tq, k)
+    assert hit.all()
+    v = torch.zeros(N, dtype=torch.uint8)
+    v[N - 1] = 1
+    idx, dist, hit = run_match_bits(L, tb, v.cuda(), tq, k)
+    assert np.all(idx == N - 1)
+
+
+def test_bit_keys_follow_the_cosine_match_on_a_clustered_bank(L):
+    say("sign-bit keys of a clustered bank: the Hamming neighbour lies in the query's cluster, like the cosine neighbour")
+    data = W.make_clustered_bank(64, 128, 256, 0.05, 512, seed=5)
+    keys = data["bank"].cuda()                              # [8192, 256] bf16 unit vectors, 64 clusters
+    qv = data["queries"].cuda()
+    g = np.random.Generator(np.random.PCG64(21))
+    kb = 256
+    P = torch.from_numpy((g.standard_normal((256, kb)) / np.sqrt(kb)).astype(np.float32)).to(torch.bfloat16).cuda()
+    N, B = keys.shape[0], qv.shape[0]
+    ws = torch.empty((L.llmc_fingerprint_workspace_bytes(N, 1, 256),), dtype=torch.uint8, device="cuda")
+    bank_bits = torch.empty((N, kb // 32), dtype=torch.int32, device="cuda")
+    q_bits = torch.empty((B, kb // 32), dtype=torch.int32, device="cuda")
+    L.llmc_fingerprint_bits(keys.view(N, 1, 256), P, None, bank_bits, ws)     # each key as a one-token sequence
+    L.llmc_fingerprint_bits(qv.view(B, 1, 256), P, None, q_bits, ws)
+    max_h = O.max_hamming(f32(0.95), kb)
+    idx, dist, hit = run_match_bits(L, bank_bits, torch.ones(N, dtype=torch.uint8).cuda(), q_bits, max_h)
+    oidx, odist = O.match_bits(words(q_bits), words(bank_bits), np.ones(N, np.uint8), kb)
+    assert np.array_equal(idx, oidx) and np.array_equal(dist, odist)
+    inside = data["q_cluster"].numpy() >= 0
+    cl = data["cluster"].numpy()
+    agree = (cl[idx[inside]] == data["q_cluster"].numpy()[inside]).mean()
+    say(f"  within-cluster queries matched into their cluster: {agree:.3f}; hits {hit[inside].mean():.3f} inside, "
+        f"{hit[~inside].mean():.3f} outside (max_hamming {max_h})")
+    assert agree > 0.99 and hit[inside].mean() > 0.95 and hit[~inside].mean() < 0.01
+
+
+# ---------------------------------------------------------------------------
 # step 4: gather
 # ---------------------------------------------------------------------------
 
