@@ -28,6 +28,7 @@ METRIC = "seq/s cache-gated 12L d768 forward vs hit rate; match MFMA% + gather H
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 FP32_VALU_PEAK_TFLOPS = 157.3
+INT_VALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12      # 32-bit integer vector instructions: one per lane per clock, 39.3 T/s
 CALIB_COPY_BYTES = 256 << 20
 DIAL_TAU = 0.9999
 # HBM bytes per launch at the bench shape (64 rows of 384 x 768 bf16), from rocprofv3 --pmc FETCH_SIZE and
@@ -260,6 +261,12 @@ def main():
             "%.1f us -> %.1f GB/s (%.1f%% of HBM peak)"
             % (stress["match_us"], stress["match_tflops"], 100 * stress["match_frac_mfma"], stress["finalize_us"],
                stress["hits"], stress["gather_us"], stress["gather_gbs"], 100 * stress["gather_frac_hbm"]))
+        sb = stress["sign_bit_keys"]
+        log("sign-bit keys on the same bank (%d bits, %d MB instead of 512): Hamming match %.1f us (+%.1f us) -> %.2f T "
+            "word-ops/s (%.1f%% of the integer vector peak); %d hits; hit rows in the cosine match's cluster %.4f, same "
+            "decision %.4f" % (sb["key_bits"], sb["bank_bytes"] >> 20, sb["match_us"], sb["other_us"],
+                               sb["tera_word_ops_per_s"], 100 * sb["frac_int_valu_peak"], sb["hits"],
+                               sb["same_cluster_as_cosine_match_on_hits"], sb["same_decision_as_cosine_match"]))
 
     # ---- headline: the last GPU work of the run ------------------------------------------------------
     dt_head, cnt_head = run(args.tau, args.steps, args.warmup)
@@ -370,12 +377,52 @@ def match_stress(llmc, W, iters=10):
     m_us, g_us = us["match_stream_kernel"], us["gather_kernel"]
     tfl = 2.0 * B * N * k / m_us / 1e6
     gbs = 2.0 * H * S * d * 2 / g_us / 1e3
+
+    # ---- the same bank and queries as sign-bit keys: each 256-vector is projected by a seeded Gaussian P
+    # [256, 256] and only the signs are kept (32 bytes per key instead of 512); match by Hamming distance ----
+    kb = 256
+    gen = torch.Generator(device="cuda").manual_seed(21)
+    P = (torch.randn((k, kb), generator=gen, device="cuda") / kb ** 0.5).to(torch.bfloat16)
+    bank_bits = torch.empty((N, kb // 32), dtype=torch.int32, device="cuda")
+    q_bits = torch.empty((B, kb // 32), dtype=torch.int32, device="cuda")
+    chunk = 32768
+    ws_f = torch.empty((llmc.llmc_fingerprint_workspace_bytes(chunk, 1, k),), dtype=torch.uint8, device="cuda")
+    for s0 in range(0, N, chunk):
+        llmc.llmc_fingerprint_bits(bank.fp[s0:s0 + chunk].view(-1, 1, k), P, None, bank_bits[s0:s0 + chunk], ws_f)
+    llmc.llmc_fingerprint_bits(q.view(B, 1, k), P, None, q_bits, ws_f)
+    max_h = llmc.llmc_max_hamming(tau, kb)
+    idx_b = torch.empty((B,), dtype=torch.int32, device="cuda")
+    dist_b = torch.empty((B,), dtype=torch.int32, device="cuda")
+    hit_b = torch.empty((B,), dtype=torch.uint8, device="cuda")
+    ws_b = torch.empty((llmc.llmc_match_bits_workspace_bytes(N, kb, B),), dtype=torch.uint8, device="cuda")
+    llmc.llmc_match_bits(bank_bits, bank.valid, q_bits, max_h, idx_b, dist_b, hit_b, ws_b)
+    torch.cuda.synchronize()
+    llmc.llmc_profile_begin(4 * iters)
+    for _ in range(iters):
+        llmc.llmc_match_bits(bank_bits, bank.valid, q_bits, max_h, idx_b, dist_b, hit_b, ws_b)
+    rep_b = llmc.llmc_profile_report()
+    llmc.llmc_profile_end()
+    us_b = {name: ms * 1e3 / cnt for name, (cnt, ms) in rep_b.items()}
+    cluster = data["cluster"].cuda()
+    hb = hit.bool()
+    same_cluster = float((cluster[idx_b.long()] == cluster[idx.long()])[hb].float().mean()) if bool(hb.any()) else 1.0
+    same_decision = float((hit_b == hit).float().mean())
+    word_ops = 2.0 * B * N * (kb // 32)                  # one XOR and one popcount-accumulate per 32 bit pairs
+    bits = {"key_bits": kb, "bank_bytes": N * kb // 8, "max_hamming": int(max_h),
+            "match_us": round(us_b["match_bits_kernel"], 2),
+            "other_us": round(sum(v for n_, v in us_b.items() if n_ != "match_bits_kernel"), 2),
+            "tera_word_ops_per_s": round(word_ops / us_b["match_bits_kernel"] / 1e6, 2),
+            "frac_int_valu_peak": round(word_ops / us_b["match_bits_kernel"] / 1e6 / INT_VALU_PEAK_TOPS, 4),
+            "hits": int(hit_b.sum()), "same_cluster_as_cosine_match_on_hits": round(same_cluster, 4),
+            "same_decision_as_cosine_match": round(same_decision, 4)}
+    del bank_bits, q_bits, ws_f, ws_b
     bank.close()
     res = {"workload": "bank-match stress: 1,048,576 bf16 keys x 256 in 4,096 clusters, 4,096 queries, tau 0.95, "
                        "gather of 384 x 768 bf16 outputs for the hits",
            "hits": H, "match_us": round(m_us, 2), "match_tflops": round(tfl, 1),
            "match_frac_mfma": round(tfl / MFMA_BF16_PEAK_TFLOPS, 4), "finalize_us": round(us["match_finalize_kernel"], 2),
-           "gather_us": round(g_us, 2), "gather_gbs": round(gbs, 1), "gather_frac_hbm": round(gbs / HBM_PEAK_GBS, 4)}
+           "gather_us": round(g_us, 2), "gather_gbs": round(gbs, 1), "gather_frac_hbm": round(gbs / HBM_PEAK_GBS, 4),
+           "sign_bit_keys": bits}
     del bank, out
     torch.cuda.empty_cache()
     return res

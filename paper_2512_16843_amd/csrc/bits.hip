@@ -20,7 +20,7 @@ namespace llmc {
 
 constexpr uint32_t kFreePenalty = 2048;      // above any distance of keys of at most 1024 bits
 constexpr int kBitsThreads = 256;
-constexpr int kRowUnroll = 4;
+constexpr int kRowUnroll = 8;
 
 // pen[j] = 0 for a valid slot, kFreePenalty for a free one and for the padding up to n_pad
 __global__ void bits_penalty_kernel(const uint8_t* __restrict__ valid, int N, int n_pad, uint32_t* __restrict__ pen) {
@@ -42,13 +42,14 @@ __global__ __launch_bounds__(kBitsThreads) void match_bits_kernel(const uint32_t
   const int r1 = min(N, r0 + rows_per_split);
   uint32_t best = 0xFFFFFFFFu;
   for (int r = r0; r < r1; r += kRowUnroll) {
-    // rows past the end are clamped for the key read and carry the padding's penalty
+    // rows past the end are clamped for the key read and carry the penalty of the padding (pen has N + kRowUnroll
+    // entries and r is a multiple of kRowUnroll)
     uint32_t key[kRowUnroll];
 #pragma unroll
     for (int u = 0; u < kRowUnroll; ++u) {
       const int row = r + u;
       const uint32_t* kp = bank + (size_t)min(row, N - 1) * W;
-      uint32_t h = row < r1 ? pen[row] : kFreePenalty;
+      uint32_t h = pen[row];
 #pragma unroll
       for (int w = 0; w < W; ++w) h = __builtin_popcount(q[w] ^ kp[w]) + h;
       key[u] = (h << 20) | (uint32_t)(row - r0);
