@@ -36,59 +36,132 @@ __device__ __forceinline__ bool sel_key(const uint8_t* valid, const uint64_t* la
 
 // mode_evict = 0: slots for insertion (free first, then LRU victims if allow_replace)
 // mode_evict = 1: LRU victims among valid entries; they are invalidated here
+// KPT > 0: every thread keeps its KPT candidate keys in registers (N <= KPT * 1024), so the bank's
+// metadata is read once; KPT == 0: keys are re-read from memory in every pass (any N).
+//
+// Radix select over the bits that actually differ between candidate keys (ticks and slot numbers are
+// small integers, so most of the 64 bits are the same in every key): OR and AND of all keys give the
+// varying bits; digits of up to 11 bits are cut from the highest varying bit downwards.  A wavefront
+// whose lanes all hold the same digit (many entries of one tick) adds its count with one atomic.
+constexpr int kSelDigitBits = 11, kSelBins = 1 << kSelDigitBits;
+
+template <int KPT>
 __global__ __launch_bounds__(kSelThreads) void select_kernel(uint8_t* valid, const uint64_t* __restrict__ last_used,
                                                              int N, const int32_t* d_m, int m_max, int mode_evict,
                                                              int allow_replace, int32_t* __restrict__ slots_out,
                                                              float* binv_eff) {
   extern __shared__ uint64_t list[];      // [m_max]
-  __shared__ unsigned hist[256];
-  __shared__ unsigned s_total, s_count;
-  __shared__ uint64_t s_prefix, s_mask;
+  __shared__ unsigned hist[kSelBins];
+  __shared__ unsigned wave_tot[kSelThreads / 64];
+  __shared__ unsigned s_total, s_count, s_or_lo, s_or_hi, s_and_lo, s_and_hi;
+  __shared__ uint64_t s_prefix;
   __shared__ unsigned s_remaining;
-  const int tid = threadIdx.x;
+  constexpr uint64_t kAbsent = ~0ull;     // larger than every candidate key
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   int m = d_m ? *d_m : m_max;
   m = max(0, min(m, m_max));
-  if (tid == 0) { s_total = 0; s_count = 0; }
+  if (tid == 0) { s_total = 0; s_count = 0; s_or_lo = 0; s_or_hi = 0; s_and_lo = ~0u; s_and_hi = ~0u; }
   __syncthreads();
-  unsigned mine = 0;
-  for (int j = tid; j < N; j += kSelThreads) {
+  const int n_iter = KPT > 0 ? KPT : (N + kSelThreads - 1) / kSelThreads;
+  uint64_t cached[KPT > 0 ? KPT : 1];
+  auto key_at = [&](int u) -> uint64_t {
+    if (KPT > 0) return cached[u];
+    const int j = tid + u * kSelThreads;
     uint64_t key;
-    if (sel_key(valid, last_used, j, mode_evict, allow_replace, &key)) ++mine;
+    return (j < N && sel_key(valid, last_used, j, mode_evict, allow_replace, &key)) ? key : kAbsent;
+  };
+  if (KPT > 0) {
+#pragma unroll
+    for (int u = 0; u < (KPT > 0 ? KPT : 1); ++u) {
+      const int j = tid + u * kSelThreads;
+      uint64_t key;
+      cached[u] = (j < N && sel_key(valid, last_used, j, mode_evict, allow_replace, &key)) ? key : kAbsent;
+    }
   }
-  if (mine) atomicAdd(&s_total, mine);
+  unsigned mine = 0;
+  uint64_t or_k = 0, and_k = ~0ull;
+  for (int u = 0; u < n_iter; ++u) {
+    const uint64_t key = key_at(u);
+    if (key != kAbsent) { ++mine; or_k |= key; and_k &= key; }
+  }
+  // wavefront reduction first: one set of atomics per wavefront
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    mine += __shfl_xor(mine, o, 64);
+    or_k |= ((uint64_t)__shfl_xor((unsigned)(or_k >> 32), o, 64) << 32) | __shfl_xor((unsigned)or_k, o, 64);
+    and_k &= ((uint64_t)__shfl_xor((unsigned)(and_k >> 32), o, 64) << 32) | __shfl_xor((unsigned)and_k, o, 64);
+  }
+  if (lane == 0 && mine) {
+    atomicAdd(&s_total, mine);
+    atomicOr(&s_or_lo, (unsigned)or_k); atomicOr(&s_or_hi, (unsigned)(or_k >> 32));
+    atomicAnd(&s_and_lo, (unsigned)and_k); atomicAnd(&s_and_hi, (unsigned)(and_k >> 32));
+  }
   __syncthreads();
   const int m_eff = min(m, (int)s_total);
   for (int i = m_eff + tid; i < m_max; i += kSelThreads) slots_out[i] = -1;
   if (m_eff == 0) return;
-  if (tid == 0) { s_prefix = 0; s_mask = 0; s_remaining = (unsigned)m_eff; }
-  for (int pass = 7; pass >= 0; --pass) {
-    const int shift = pass * 8;
-    for (int i = tid; i < 256; i += kSelThreads) hist[i] = 0;
+  const uint64_t or_all = ((uint64_t)s_or_hi << 32) | s_or_lo, and_all = ((uint64_t)s_and_hi << 32) | s_and_lo;
+  uint64_t varying = or_all ^ and_all;   // bits on which candidate keys differ
+  uint64_t mask = 0;                     // bits decided so far
+  if (tid == 0) { s_prefix = 0; s_remaining = (unsigned)m_eff; }
+  __syncthreads();
+  while (varying) {
+    const int hi = 63 - __clzll((long long)varying);
+    const int lo = max(0, hi - kSelDigitBits + 1);
+    const uint64_t field = ((hi - lo + 1 >= 64) ? ~0ull : ((1ull << (hi - lo + 1)) - 1ull)) << lo;
+    for (int i = tid; i < kSelBins; i += kSelThreads) hist[i] = 0;
     __syncthreads();
-    const uint64_t prefix = s_prefix, mask = s_mask;
-    for (int j = tid; j < N; j += kSelThreads) {
-      uint64_t key;
-      if (sel_key(valid, last_used, j, mode_evict, allow_replace, &key) && (key & mask) == prefix)
-        atomicAdd(&hist[(unsigned)(key >> shift) & 255u], 1u);
-    }
-    __syncthreads();
-    if (tid == 0) {
-      unsigned cum = 0, rem = s_remaining;
-      int dsel = 255;
-      for (int dgt = 0; dgt < 256; ++dgt) {
-        if (cum + hist[dgt] >= rem) { dsel = dgt; break; }
-        cum += hist[dgt];
+    const uint64_t prefix = s_prefix;
+    for (int u = 0; u < n_iter; ++u) {
+      const uint64_t key = key_at(u);
+      const bool in = key != kAbsent && (key & mask) == prefix;
+      const unsigned dgt = (unsigned)((key & field) >> lo);
+      // one atomic for a wavefront whose participating lanes all hold the same digit
+      const unsigned long long act = __ballot(in);
+      if (act) {
+        const int leader = __ffsll((long long)act) - 1;
+        const unsigned d0 = (unsigned)__builtin_amdgcn_readlane((int)dgt, leader);
+        const unsigned long long same = __ballot(in && dgt == d0);
+        if (same == act) {
+          if (lane == leader) atomicAdd(&hist[d0], (unsigned)__popcll(act));
+        } else if (in) {
+          atomicAdd(&hist[dgt], 1u);
+        }
       }
-      s_remaining = rem - cum;
-      s_prefix = prefix | ((uint64_t)dsel << shift);
-      s_mask = mask | (0xFFull << shift);
     }
+    __syncthreads();
+    {
+      // digit whose cumulative count first reaches the remaining rank: 2 bins per thread, scan over the workgroup
+      const unsigned h0 = hist[2 * tid], h1 = hist[2 * tid + 1];
+      const unsigned own = h0 + h1;
+      unsigned incl = own;
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) {
+        const unsigned v = __shfl_up(incl, o, 64);
+        if (lane >= o) incl += v;
+      }
+      if (lane == 63) wave_tot[wave] = incl;
+      __syncthreads();
+      unsigned base = 0;
+      for (int w = 0; w < wave; ++w) base += wave_tot[w];
+      incl += base;
+      const unsigned rem = s_remaining, before = incl - own;
+      __syncthreads();                                       // everyone has read s_remaining
+      if (before < rem && incl >= rem) {                     // exactly one thread: counts are cumulative
+        const bool first = before + h0 >= rem;
+        s_remaining = rem - (first ? before : before + h0);
+        s_prefix = prefix | ((uint64_t)(2 * tid + (first ? 0 : 1)) << lo);
+      }
+    }
+    mask |= field;
+    varying &= ~field;
     __syncthreads();
   }
-  const uint64_t kth = s_prefix;
-  for (int j = tid; j < N; j += kSelThreads) {
-    uint64_t key;
-    if (sel_key(valid, last_used, j, mode_evict, allow_replace, &key) && key <= kth) {
+  // bits never examined are the same in every candidate key
+  const uint64_t kth = s_prefix | (and_all & ~mask);
+  for (int u = 0; u < n_iter; ++u) {
+    const uint64_t key = key_at(u);
+    if (key != kAbsent && key <= kth) {
       const unsigned p = atomicAdd(&s_count, 1u);
       if (p < (unsigned)m_max) list[p] = key;
     }
@@ -106,6 +179,18 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(uint8_t* valid, con
       binv_eff[slot] = NAN;
     }
   }
+}
+
+static void launch_select(uint8_t* valid, const uint64_t* last_used, int N, const int32_t* d_m, int m_max, int mode_evict,
+                          int allow_replace, int32_t* slots_out, float* binv_eff, hipStream_t st) {
+  const size_t lds = (size_t)m_max * sizeof(uint64_t);
+#define LLMC_SELECT(KPT_) hipLaunchKernelGGL(select_kernel<KPT_>, dim3(1), dim3(kSelThreads), lds, st, valid, last_used, N, \
+                                             d_m, m_max, mode_evict, allow_replace, slots_out, binv_eff)
+  if (N <= 4 * kSelThreads) LLMC_SELECT(4);
+  else if (N <= 16 * kSelThreads) LLMC_SELECT(16);
+  else if (N <= 48 * kSelThreads) LLMC_SELECT(48);
+  else LLMC_SELECT(0);
+#undef LLMC_SELECT
 }
 
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
@@ -177,9 +262,9 @@ llmc_status_t launch_bank_insert(llmc_bank* bank, const void* d_fp, const float*
                                  const int32_t* d_rows, const int32_t* d_m, int m_max, uint64_t tick,
                                  int32_t* d_slots_out, int32_t* d_counters, hipStream_t st) {
   const llmc_bank_desc_t& D = bank->desc;
-  { ProfScope ps_("select_kernel", st); hipLaunchKernelGGL(select_kernel, dim3(1), dim3(kSelThreads), (size_t)m_max * sizeof(uint64_t), st, D.d_valid,
-                     D.d_last_used, D.n_slots, d_m, m_max, 0, D.policy == LLMC_EVICT_LRU ? 1 : 0, d_slots_out,
-                     bank->d_binv_eff); }
+  { ProfScope ps_("select_kernel", st);
+    launch_select(D.d_valid, D.d_last_used, D.n_slots, d_m, m_max, 0, D.policy == LLMC_EVICT_LRU ? 1 : 0, d_slots_out,
+                  bank->d_binv_eff, st); }
   LLMC_LAUNCH_CHECK("select_kernel");
   const size_t e = elem_size(D.dtype);
   const size_t vec_per_seq = (size_t)D.S * D.d * e / 16, vec_per_key = (size_t)D.k * e / 16;
@@ -194,8 +279,8 @@ llmc_status_t launch_bank_insert(llmc_bank* bank, const void* d_fp, const float*
 
 llmc_status_t launch_bank_evict(llmc_bank* bank, const int32_t* d_m, int m_max, int32_t* d_victims, hipStream_t st) {
   const llmc_bank_desc_t& D = bank->desc;
-  { ProfScope ps_("select_kernel", st); hipLaunchKernelGGL(select_kernel, dim3(1), dim3(kSelThreads), (size_t)m_max * sizeof(uint64_t), st, D.d_valid,
-                     D.d_last_used, D.n_slots, d_m, m_max, 1, 1, d_victims, bank->d_binv_eff); }
+  { ProfScope ps_("select_kernel", st);
+    launch_select(D.d_valid, D.d_last_used, D.n_slots, d_m, m_max, 1, 1, d_victims, bank->d_binv_eff, st); }
   LLMC_LAUNCH_CHECK("select_kernel");
   return LLMC_OK;
 }

@@ -624,6 +624,48 @@ def test_bank_insert_and_evict_direct(L):
     bank.close()
 
 
+@pytest.mark.parametrize("N,big_ticks", [(3000, False), (10000, True), (40000, False), (40000, True), (70000, True)])
+def test_slot_selection_at_size(L, N, big_ticks):
+    """Victims and insertion slots over banks of every size class of the selection kernel (keys held in registers
+    up to 49,152 slots, re-read beyond), with ticks that do or do not reach the high bytes of the recency key."""
+    say(f"slot selection N={N} big_ticks={big_ticks}")
+    g = np.random.Generator(np.random.PCG64(N + int(big_ticks)))
+    k, S, d = 32, 1, 64
+    bank = L.Bank(N, k, S, d, torch.bfloat16, "cuda")
+    ob = O.Bank(N, k, S, d, "bf16")
+    valid = (g.random(N) > 0.002).astype(np.uint8)
+    hi = (1 << 31) - 10 if big_ticks else 300
+    lu = g.integers(0, hi, size=N).astype(np.uint64)
+    lu[g.integers(0, N, size=N // 3)] = 7                       # many equal recencies: the slot number decides
+    ob.valid[:] = valid
+    ob.last_used[:] = lu
+    bank.valid.copy_(torch.from_numpy(valid))
+    bank.last_used.copy_(torch.from_numpy(lu.astype(np.int64)))
+    bank.refresh()
+    # eviction of 150 entries
+    vic = torch.empty((256,), dtype=torch.int32, device="cuda")
+    L.llmc_bank_evict(bank, torch.tensor([150], dtype=torch.int32, device="cuda"), 256, vic)
+    torch.cuda.synchronize()
+    assert vic.cpu().tolist() == ob.evict(150) + [-1] * 106
+    assert np.array_equal(bank.valid.cpu().numpy(), ob.valid)
+    # insertion of 400 rows: the free slots (evicted ones included) by ascending index first, then LRU victims
+    m = 400
+    keys = torch.from_numpy(unit_rows(g, m, k).astype(np.float32)).to(torch.bfloat16).cuda()
+    inv = torch.empty((m,), dtype=torch.float32, device="cuda")
+    L.llmc_inv_norm(keys, inv)
+    acts = torch.from_numpy(g.standard_normal((m, S, d)).astype(np.float32)).to(torch.bfloat16).cuda()
+    slots = torch.empty((m,), dtype=torch.int32, device="cuda")
+    counters = torch.zeros((L.CNT_WORDS,), dtype=torch.int32, device="cuda")
+    tick = hi + 1
+    L.llmc_bank_insert(bank, keys, inv, acts, None, None, m, tick, slots, counters)
+    torch.cuda.synchronize()
+    oslots, n_ev = ob.insert(npf(keys), npf(inv), npf(acts), tick)
+    assert slots.cpu().tolist() == oslots
+    assert int(counters[L.CNT_EVICTED]) == n_ev and int(counters[L.CNT_INSERTED]) == m
+    assert np.array_equal(bank.valid.cpu().numpy(), ob.valid)
+    bank.close()
+
+
 def test_insert_without_eviction_drops_and_counts(L):
     say("insert into a full bank with policy NONE")
     g = np.random.Generator(np.random.PCG64(13))
