@@ -359,11 +359,18 @@ class Bank:
     """
 
     def __init__(self, n_slots: int, k: int, S: int, d: int, dtype: str,
-                 n_act_slots: Optional[int] = None, lru: bool = True):
+                 n_act_slots: Optional[int] = None, lru: bool = True, decayed_hits: bool = False,
+                 half_life: int = 0):
         A = n_slots if n_act_slots is None else n_act_slots
         self.N, self.k, self.S, self.d, self.A = n_slots, k, S, d, A
         self.dtype = dtype
-        self.lru = lru
+        self.lru = lru or decayed_hits
+        # staleness-aware replacement (Section IV-D, second policy; Section III-E: frequency-based policy and
+        # temporal decay): entries are ranked by their hit count, which is halved every `half_life` ticks
+        # (0 = never), then by recency, then by slot
+        self.decayed_hits = decayed_hits
+        self.half_life = half_life
+        self.epoch = 0
         self.fp = np.zeros((n_slots, k), dtype=np.float32)
         self.inv_norm = np.zeros((n_slots,), dtype=np.float32)
         self.act = np.zeros((A, S, d), dtype=np.float32)
@@ -371,6 +378,25 @@ class Bank:
         self.last_used = np.zeros((n_slots,), dtype=np.uint64)
         self.hits = np.zeros((n_slots,), dtype=np.uint32)
         self.valid = np.zeros((n_slots,), dtype=np.uint8)
+
+    # -- temporal decay ------------------------------------------------------
+    def advance(self, tick: int) -> None:
+        """Bring the hit counts to the epoch of ``tick`` (epoch = tick // half_life): one halving per epoch
+        gone by, at most 31.  Called with the tick of every update before the update itself."""
+        if not self.decayed_hits or self.half_life <= 0:
+            return
+        e = int(tick) // self.half_life
+        if e > self.epoch:
+            sh = min(31, e - self.epoch)
+            for j in range(self.N):
+                if self.valid[j]:
+                    self.hits[j] = np.uint32(int(self.hits[j]) >> sh)
+            self.epoch = e
+
+    def _victim_key(self, j: int):
+        if self.decayed_hits:
+            return (min(int(self.hits[j]), 65535), int(self.last_used[j]), j)
+        return (int(self.last_used[j]), j)
 
     # -- selection -----------------------------------------------------------
     def select_slots(self, m: int) -> List[int]:
@@ -382,20 +408,20 @@ class Bank:
         if len(out) < m:
             if not self.lru:
                 raise RuntimeError("bank full and eviction disabled")
-            order = sorted((j for j in range(self.N) if self.valid[j]),
-                           key=lambda j: (int(self.last_used[j]), j))
+            order = sorted((j for j in range(self.N) if self.valid[j]), key=self._victim_key)
             out += order[:m - len(out)]
         return out
 
     def lru_victims(self, m: int) -> List[int]:
-        """The ``m`` least recently used valid entries, ascending (last_used, slot)."""
-        order = sorted((j for j in range(self.N) if self.valid[j]),
-                       key=lambda j: (int(self.last_used[j]), j))
+        """The ``m`` first victims among valid entries: ascending (last_used, slot), or with the decayed-hits
+        policy ascending (min(hits, 65535), last_used, slot)."""
+        order = sorted((j for j in range(self.N) if self.valid[j]), key=self._victim_key)
         return order[:m]
 
     # -- updates -------------------------------------------------------------
     def insert(self, q: np.ndarray, qinv: np.ndarray, acts: np.ndarray, tick: int) -> Tuple[List[int], int]:
         """Store ``m`` (key, value) pairs; returns (slots taken, number evicted)."""
+        self.advance(tick)
         m = q.shape[0]
         slots = self.select_slots(m)
         n_evicted = 0
@@ -418,6 +444,7 @@ class Bank:
 
     def touch(self, slots: Sequence[int], tick: int) -> None:
         """Record hits: refresh recency and count the hit."""
+        self.advance(tick)
         for j in slots:
             self.last_used[j] = tick
             self.hits[j] += 1

@@ -164,6 +164,60 @@ def test_lru_victims_are_m_smallest_and_evict_invalidates():
         full.insert(q[:1], O.inv_norm(q[:1]), np.zeros((1, 1, 1), np.float32), 2)
 
 
+def test_decayed_hits_policy_against_an_event_log_simulation():
+    """Staleness-aware replacement: an entry's standing is the number of its hits, each hit weighing 1/2 per
+    epoch gone by (floored at every epoch boundary).  The check keeps, per entry, the raw LOG of hit ticks and
+    recomputes the standing from the log at the moment of each choice, instead of keeping running counters."""
+    half_life = 5
+    N = 6
+    bank = O.Bank(N, 2, 1, 1, "f32", decayed_hits=True, half_life=half_life)
+    r = rng(11)
+    log = {}                                   # slot -> dict(ins=tick, hits=[ticks])
+
+    def standing(slot, now):
+        e_now = now // half_life
+        # replay: a counter that gains 1 per hit and is halved (floor) at every epoch boundary since insertion
+        c, e = 0, log[slot]["ins"] // half_life
+        events = sorted(log[slot]["hits"])
+        for t in events + [None]:
+            target = e_now if t is None else t // half_life
+            while e < target:
+                c //= 2
+                e += 1
+            if t is not None:
+                c += 1
+        last = max([log[slot]["ins"]] + events)
+        return (min(c, 65535), last, slot)
+
+    payload = 0
+    for tick in range(1, 60):
+        live = sorted(log)
+        hit_slots = [int(r.choice(live)) for _ in range(int(r.integers(0, 4)))] if live else []
+        bank.touch(hit_slots, tick)
+        for j in hit_slots:
+            log[j]["hits"].append(tick)
+        if tick % 3 == 0:
+            m = int(r.integers(1, 3))
+            free = [j for j in range(N) if j not in log]
+            order = free + sorted(log, key=lambda j: standing(j, tick))
+            want = order[:m]
+            q = np.ones((m, 2), np.float32)
+            got, n_ev = bank.insert(q, O.inv_norm(q), np.full((m, 1, 1), payload, np.float32), tick)
+            assert got == want, (tick, got, want)
+            assert n_ev == sum(1 for j in want if j in log)
+            for j in want:
+                log[j] = dict(ins=tick, hits=[])
+            payload += 1
+        for j in log:
+            assert int(bank.hits[j]) == standing(j, tick)[0]
+    # with half_life 0 the counts never decay: plain least-frequently-used
+    lfu = O.Bank(3, 2, 1, 1, "f32", decayed_hits=True, half_life=0)
+    q = np.ones((3, 2), np.float32)
+    lfu.insert(q, O.inv_norm(q), np.zeros((3, 1, 1), np.float32), 1)
+    lfu.touch([0, 0, 2], 1000)
+    assert lfu.lru_victims(3) == [1, 2, 0] and int(lfu.hits[0]) == 2
+
+
 # ---- gated layer invariants (Section IV-A, Algorithm 1) ----------------------
 
 def tiny_setup(arch=O.ENCODER_POST_LN, n_src=12, dtype="f32"):
