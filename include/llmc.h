@@ -53,8 +53,18 @@ typedef enum {
 typedef enum { LLMC_F32 = 0, LLMC_BF16 = 1 } llmc_dtype_t;
 
 /* Replacement policy (Section III-E / IV-D of the paper).  LRU is the first
- * policy the paper names: remove the entries unused for the longest time. */
-typedef enum { LLMC_EVICT_NONE = 0, LLMC_EVICT_LRU = 1 } llmc_evict_t;
+ * policy the paper names: remove the entries unused for the longest time.
+ * DECAYED_HITS is the staleness-aware policy of Section IV-D ("entries with decayed match
+ * rates over time"; Section III-E: frequency-based policy, temporal decay): an entry's
+ * standing is its hit count d_hits, and every hit count of the bank is halved (integer
+ * shift) each time the tick crosses a multiple of half_life (half_life 0: never, i.e. plain
+ * least-frequently-used).  Victims are taken by ascending (min(hits, 65535), last_used,
+ * slot).  The halving is applied by the library, before anything else, in every call that
+ * takes a tick and updates the bank (llmc_bank_insert, llmc_layer_forward_gated with
+ * LLMC_INSERT_ON_MISS or LLMC_UPDATE_LRU); ticks must not decrease.  A bank under this
+ * policy holds at most 2^24 slots and takes ticks below LLMC_MAX_TICK_DECAYED. */
+typedef enum { LLMC_EVICT_NONE = 0, LLMC_EVICT_LRU = 1, LLMC_EVICT_DECAYED_HITS = 2 } llmc_evict_t;
+#define LLMC_MAX_TICK_DECAYED 0xFFFFFEull
 
 /* Flags of llmc_layer_forward_gated. */
 #define LLMC_INSERT_ON_MISS 1u /* Algorithm 1: store (f_X, h_l) of every computed row */
@@ -103,6 +113,7 @@ typedef struct {
   uint64_t* d_last_used;
   uint32_t* d_hits;
   uint8_t* d_valid;
+  int32_t half_life; /* LLMC_EVICT_DECAYED_HITS: ticks per halving of the hit counts, 0 = never; else ignored */
 } llmc_bank_desc_t;
 
 /*

@@ -90,8 +90,13 @@ llmc_status_t llmc_bank_create(const llmc_bank_desc_t* desc, llmc_bank_t** out) 
   REQUIRE(desc && out, LLMC_ERR_INVALID_ARG, "desc/out is NULL");
   *out = nullptr;
   REQUIRE(dtype_ok(desc->dtype), LLMC_ERR_DTYPE, "bank dtype %d unknown", desc->dtype);
-  REQUIRE(desc->policy == LLMC_EVICT_NONE || desc->policy == LLMC_EVICT_LRU, LLMC_ERR_INVALID_ARG,
-          "eviction policy %d unknown", desc->policy);
+  REQUIRE(desc->policy == LLMC_EVICT_NONE || desc->policy == LLMC_EVICT_LRU ||
+              desc->policy == LLMC_EVICT_DECAYED_HITS,
+          LLMC_ERR_INVALID_ARG, "eviction policy %d unknown", desc->policy);
+  if (desc->policy == LLMC_EVICT_DECAYED_HITS) {
+    REQUIRE(desc->half_life >= 0, LLMC_ERR_INVALID_ARG, "half_life must not be negative");
+    REQUIRE(desc->n_slots <= (1 << 24), LLMC_ERR_SHAPE, "a bank ranked by decayed hits holds at most 2^24 slots");
+  }
   REQUIRE(desc->n_slots > 0 && desc->k > 0 && desc->S > 0 && desc->d > 0 && desc->n_act_slots > 0, LLMC_ERR_SHAPE,
           "non-positive bank size");
   REQUIRE(desc->k % 32 == 0 && desc->k <= 1024, LLMC_ERR_SHAPE, "k=%d must be a multiple of 32, at most 1024", desc->k);
@@ -106,6 +111,7 @@ llmc_status_t llmc_bank_create(const llmc_bank_desc_t* desc, llmc_bank_t** out) 
   REQUIRE(b, LLMC_ERR_INVALID_ARG, "out of host memory");
   b->desc = *desc;
   b->d_binv_eff = nullptr;
+  b->epoch = 0;
   hipError_t e = hipGetDevice(&b->device);
   if (e == hipSuccess) e = hipMalloc((void**)&b->d_binv_eff, align_up((size_t)desc->n_slots, 256) * sizeof(float));
   if (e != hipSuccess) {
@@ -148,6 +154,8 @@ llmc_status_t llmc_bank_insert(llmc_bank_t* bank, const void* d_fp, const float*
   REQUIRE(m_max > 0 && m_max <= LLMC_MAX_UPDATE_ROWS, LLMC_ERR_SHAPE, "m_max=%d out of range 1..%d", m_max,
           LLMC_MAX_UPDATE_ROWS);
   REQUIRE(tick <= LLMC_MAX_TICK, LLMC_ERR_INVALID_ARG, "tick out of range");
+  REQUIRE(bank->desc.policy != LLMC_EVICT_DECAYED_HITS || tick <= LLMC_MAX_TICK_DECAYED, LLMC_ERR_INVALID_ARG,
+          "tick out of range for a bank ranked by decayed hits");
   REQUIRE(bank->desc.n_act_slots == bank->desc.n_slots, LLMC_ERR_SHAPE,
           "insertion into a bank whose keys share value rows is refused");
   REQUIRE(aligned16(d_fp) && aligned16(d_act), LLMC_ERR_SHAPE, "arrays must be 16-byte aligned");
@@ -358,6 +366,9 @@ llmc_status_t llmc_layer_forward_gated(const llmc_layer_desc_t* layer, llmc_bank
       REQUIRE(aligned16(fp->d_proj), LLMC_ERR_SHAPE, "projection must be 16-byte aligned");
       LLMC_TRY(check_fp_shape(B, S, layer->d, layer->dtype, k));
     }
+    REQUIRE(D.policy != LLMC_EVICT_DECAYED_HITS || !(flags & (LLMC_INSERT_ON_MISS | LLMC_UPDATE_LRU)) ||
+                tick <= LLMC_MAX_TICK_DECAYED,
+            LLMC_ERR_INVALID_ARG, "tick out of range for a bank ranked by decayed hits");
     if (flags & LLMC_INSERT_ON_MISS) {
       REQUIRE(B <= LLMC_MAX_UPDATE_ROWS, LLMC_ERR_SHAPE, "insertion handles at most %d rows per call",
               LLMC_MAX_UPDATE_ROWS);
@@ -397,6 +408,7 @@ llmc_status_t llmc_layer_forward_gated(const llmc_layer_desc_t* layer, llmc_bank
                              out ? out->d_hit : nullptr, st));
     return launch_layer(layer, d_h_in, d_h_out, B, S, miss_rows, counters + LLMC_CNT_MISS, ws_layer, st);
   }
+  if (flags & (LLMC_INSERT_ON_MISS | LLMC_UPDATE_LRU)) LLMC_TRY(launch_bank_advance(bank, tick, st));
   const void* q = d_fp_given;
   const float* qinv = d_inv_norm_given;
   if (!q) {

@@ -9,6 +9,7 @@
 // ascending order of distinct integers.  One workgroup finds the m-th smallest key with
 // an 8-bit radix select (integer histograms only), collects the m keys not above it and
 // ranks them by counting, so the result does not depend on thread timing.
+#include <algorithm>
 #include "common.h"
 
 namespace llmc {
@@ -21,17 +22,28 @@ __global__ void refresh_kernel(const uint8_t* __restrict__ valid, const float* _
   if (j < n_pad) binv_eff[j] = (j < N && valid[j]) ? inv_norm[j] : NAN;
 }
 
-__device__ __forceinline__ bool sel_key(const uint8_t* valid, const uint64_t* last_used, int j, int mode_evict,
-                                        int allow_replace, uint64_t* key) {
+// policy 2 (decayed hits): (min(hits, 65535) << 48) | ((last_used + 1) << 24) | slot, with n_slots <= 2^24 and
+// last_used + 1 < 2^24; otherwise ((last_used + 1) << 32) | slot.  Free slots: their number alone.
+__device__ __forceinline__ bool sel_key(const uint8_t* valid, const uint64_t* last_used, const uint32_t* hits, int j,
+                                        int mode_evict, int allow_replace, int by_hits, uint64_t* key) {
   const bool v = valid[j] != 0;
   if (v) {
     if (!allow_replace) return false;
-    *key = ((last_used[j] + 1ull) << 32) | (uint32_t)j;
+    if (by_hits)
+      *key = ((uint64_t)min(hits[j], 65535u) << 48) | ((last_used[j] + 1ull) << 24) | (uint32_t)j;
+    else
+      *key = ((last_used[j] + 1ull) << 32) | (uint32_t)j;
     return true;
   }
   if (mode_evict) return false;
   *key = (uint64_t)(uint32_t)j;
   return true;
+}
+
+// hits[j] >>= shift for every slot (free slots too: their counts are reset on insertion)
+__global__ void decay_kernel(uint32_t* __restrict__ hits, int N, int shift) {
+  const int j = blockIdx.x * blockDim.x + threadIdx.x;
+  if (j < N) hits[j] >>= shift;
 }
 
 // mode_evict = 0: slots for insertion (free first, then LRU victims if allow_replace)
@@ -47,6 +59,7 @@ constexpr int kSelDigitBits = 11, kSelBins = 1 << kSelDigitBits;
 
 template <int KPT>
 __global__ __launch_bounds__(kSelThreads) void select_kernel(uint8_t* valid, const uint64_t* __restrict__ last_used,
+                                                             const uint32_t* __restrict__ hits, int by_hits,
                                                              int N, const int32_t* d_m, int m_max, int mode_evict,
                                                              int allow_replace, int32_t* __restrict__ slots_out,
                                                              float* binv_eff) {
@@ -68,14 +81,14 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(uint8_t* valid, con
     if (KPT > 0) return cached[u];
     const int j = tid + u * kSelThreads;
     uint64_t key;
-    return (j < N && sel_key(valid, last_used, j, mode_evict, allow_replace, &key)) ? key : kAbsent;
+    return (j < N && sel_key(valid, last_used, hits, j, mode_evict, allow_replace, by_hits, &key)) ? key : kAbsent;
   };
   if (KPT > 0) {
 #pragma unroll
     for (int u = 0; u < (KPT > 0 ? KPT : 1); ++u) {
       const int j = tid + u * kSelThreads;
       uint64_t key;
-      cached[u] = (j < N && sel_key(valid, last_used, j, mode_evict, allow_replace, &key)) ? key : kAbsent;
+      cached[u] = (j < N && sel_key(valid, last_used, hits, j, mode_evict, allow_replace, by_hits, &key)) ? key : kAbsent;
     }
   }
   unsigned mine = 0;
@@ -172,7 +185,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(uint8_t* valid, con
     const uint64_t key = list[i];
     int rank = 0;
     for (int o = 0; o < n; ++o) rank += list[o] < key ? 1 : 0;
-    const int slot = (int)(uint32_t)key;
+    const int slot = by_hits ? (int)(key & 0xFFFFFFull) : (int)(uint32_t)key;
     slots_out[rank] = slot;
     if (mode_evict) {
       valid[slot] = 0;
@@ -181,16 +194,32 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(uint8_t* valid, con
   }
 }
 
-static void launch_select(uint8_t* valid, const uint64_t* last_used, int N, const int32_t* d_m, int m_max, int mode_evict,
-                          int allow_replace, int32_t* slots_out, float* binv_eff, hipStream_t st) {
+static void launch_select(const llmc_bank* bank, const int32_t* d_m, int m_max, int mode_evict, int allow_replace,
+                          int32_t* slots_out, hipStream_t st) {
+  const llmc_bank_desc_t& D = bank->desc;
+  const int N = D.n_slots, by_hits = D.policy == LLMC_EVICT_DECAYED_HITS ? 1 : 0;
   const size_t lds = (size_t)m_max * sizeof(uint64_t);
-#define LLMC_SELECT(KPT_) hipLaunchKernelGGL(select_kernel<KPT_>, dim3(1), dim3(kSelThreads), lds, st, valid, last_used, N, \
-                                             d_m, m_max, mode_evict, allow_replace, slots_out, binv_eff)
+#define LLMC_SELECT(KPT_) hipLaunchKernelGGL(select_kernel<KPT_>, dim3(1), dim3(kSelThreads), lds, st, D.d_valid,         \
+                                             D.d_last_used, D.d_hits, by_hits, N, d_m, m_max, mode_evict, allow_replace, \
+                                             slots_out, bank->d_binv_eff)
   if (N <= 4 * kSelThreads) LLMC_SELECT(4);
   else if (N <= 16 * kSelThreads) LLMC_SELECT(16);
   else if (N <= 48 * kSelThreads) LLMC_SELECT(48);
   else LLMC_SELECT(0);
 #undef LLMC_SELECT
+}
+
+llmc_status_t launch_bank_advance(llmc_bank* bank, uint64_t tick, hipStream_t st) {
+  const llmc_bank_desc_t& D = bank->desc;
+  if (D.policy != LLMC_EVICT_DECAYED_HITS || D.half_life <= 0) return LLMC_OK;
+  const int64_t e = (int64_t)(tick / (uint64_t)D.half_life);
+  if (e <= bank->epoch) return LLMC_OK;
+  const int shift = (int)std::min<int64_t>(31, e - bank->epoch);
+  bank->epoch = e;
+  { ProfScope ps_("decay_kernel", st);
+    hipLaunchKernelGGL(decay_kernel, dim3((D.n_slots + 255) / 256), dim3(256), 0, st, D.d_hits, D.n_slots, shift); }
+  LLMC_LAUNCH_CHECK("decay_kernel");
+  return LLMC_OK;
 }
 
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
@@ -262,9 +291,9 @@ llmc_status_t launch_bank_insert(llmc_bank* bank, const void* d_fp, const float*
                                  const int32_t* d_rows, const int32_t* d_m, int m_max, uint64_t tick,
                                  int32_t* d_slots_out, int32_t* d_counters, hipStream_t st) {
   const llmc_bank_desc_t& D = bank->desc;
+  LLMC_TRY(launch_bank_advance(bank, tick, st));
   { ProfScope ps_("select_kernel", st);
-    launch_select(D.d_valid, D.d_last_used, D.n_slots, d_m, m_max, 0, D.policy == LLMC_EVICT_LRU ? 1 : 0, d_slots_out,
-                  bank->d_binv_eff, st); }
+    launch_select(bank, d_m, m_max, 0, D.policy != LLMC_EVICT_NONE ? 1 : 0, d_slots_out, st); }
   LLMC_LAUNCH_CHECK("select_kernel");
   const size_t e = elem_size(D.dtype);
   const size_t vec_per_seq = (size_t)D.S * D.d * e / 16, vec_per_key = (size_t)D.k * e / 16;
@@ -278,9 +307,8 @@ llmc_status_t launch_bank_insert(llmc_bank* bank, const void* d_fp, const float*
 }
 
 llmc_status_t launch_bank_evict(llmc_bank* bank, const int32_t* d_m, int m_max, int32_t* d_victims, hipStream_t st) {
-  const llmc_bank_desc_t& D = bank->desc;
   { ProfScope ps_("select_kernel", st);
-    launch_select(D.d_valid, D.d_last_used, D.n_slots, d_m, m_max, 1, 1, d_victims, bank->d_binv_eff, st); }
+    launch_select(bank, d_m, m_max, 1, 1, d_victims, st); }
   LLMC_LAUNCH_CHECK("select_kernel");
   return LLMC_OK;
 }

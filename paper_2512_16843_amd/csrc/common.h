@@ -130,6 +130,7 @@ struct llmc_bank {
   // slots never win and never mask a valid entry.
   float* d_binv_eff;
   int device;
+  int64_t epoch;      // DECAYED_HITS: tick / half_life of the latest update (host side, in call order)
 };
 
 namespace llmc {
@@ -166,6 +167,8 @@ llmc_status_t launch_gather(const llmc_bank* bank, const int32_t* d_idx, const i
 
 // bank.hip
 llmc_status_t launch_bank_refresh(llmc_bank* bank, hipStream_t st);
+// DECAYED_HITS: halve the hit counts once per epoch gone by since the bank's latest update
+llmc_status_t launch_bank_advance(llmc_bank* bank, uint64_t tick, hipStream_t st);
 llmc_status_t launch_bank_insert(llmc_bank* bank, const void* d_fp, const float* d_inv, const void* d_act,
                                  const int32_t* d_rows, const int32_t* d_m, int m_max, uint64_t tick,
                                  int32_t* d_slots_out, int32_t* d_counters, hipStream_t st);

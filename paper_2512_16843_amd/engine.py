@@ -17,7 +17,7 @@ from .workloads import ModelConfig
 class GatedStack:
     def __init__(self, cfg: ModelConfig, weights, projections, device="cuda", cached_layers=None,
                  biases: Optional[List[Optional[torch.Tensor]]] = None, n_bank: Optional[int] = None,
-                 policy: int = llmc.EVICT_LRU, B: Optional[int] = None):
+                 policy: int = llmc.EVICT_LRU, B: Optional[int] = None, half_life: int = 0):
         self.cfg = cfg
         self.device = device
         self.B = cfg.B if B is None else B
@@ -28,7 +28,8 @@ class GatedStack:
         cached = range(cfg.n_layers) if cached_layers is None else cached_layers
         self.banks: List[Optional[llmc.Bank]] = [None] * cfg.n_layers
         for l in cached:
-            self.banks[l] = llmc.Bank(n_bank, cfg.k, cfg.S, cfg.d, cfg.torch_dtype, device, policy=policy)
+            self.banks[l] = llmc.Bank(n_bank, cfg.k, cfg.S, cfg.d, cfg.torch_dtype, device, policy=policy,
+                                      half_life=half_life)
         ws_bytes = llmc.llmc_layer_workspace_bytes(self.layers[0], self.B, cfg.S, cfg.k)
         self.workspace = torch.empty((ws_bytes,), dtype=torch.uint8, device=device)
         self.buf = [torch.empty((self.B, cfg.S, cfg.d), dtype=cfg.torch_dtype, device=device) for _ in range(2)]

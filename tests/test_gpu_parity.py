@@ -666,6 +666,92 @@ def test_slot_selection_at_size(L, N, big_ticks):
     bank.close()
 
 
+def test_decayed_hits_policy_stream_against_oracle(L):
+    """Staleness-aware replacement on the device, step by step against the oracle bank: hits recorded by the gate's
+    own compaction kernel (through llmc_layer_forward_gated would need a model; here hits are recorded the way that
+    kernel does it and the halving, the selection and the eviction counters come from the library)."""
+    say("decayed-hits replacement: scripted stream of hits, insertions and evictions")
+    g = np.random.Generator(np.random.PCG64(31))
+    N, k, S, d, half_life = 48, 32, 2, 64, 4
+    bank = L.Bank(N, k, S, d, torch.bfloat16, "cuda", policy=L.EVICT_DECAYED_HITS, half_life=half_life)
+    ob = O.Bank(N, k, S, d, "bf16", decayed_hits=True, half_life=half_life)
+    counters = torch.zeros((L.CNT_WORDS,), dtype=torch.int32, device="cuda")
+    for tick in range(1, 40):
+        mmax = 12
+        m = int(g.integers(0, mmax + 1)) if tick % 2 == 1 else 0
+        keys = torch.from_numpy(unit_rows(g, mmax, k).astype(np.float32)).to(torch.bfloat16).cuda()
+        inv = torch.empty((mmax,), dtype=torch.float32, device="cuda")
+        L.llmc_inv_norm(keys, inv)
+        acts = torch.from_numpy(g.standard_normal((mmax, S, d)).astype(np.float32)).to(torch.bfloat16).cuda()
+        slots = torch.full((mmax,), -5, dtype=torch.int32, device="cuda")
+        dm = torch.tensor([m], dtype=torch.int32, device="cuda")
+        # the insert call brings the hit counts to this tick's epoch first (also with m = 0)
+        L.llmc_bank_insert(bank, keys, inv, acts, None, dm, mmax, tick, slots, counters)
+        torch.cuda.synchronize()
+        oslots, _ = ob.insert(npf(keys)[:m], npf(inv)[:m], npf(acts)[:m], tick)
+        assert slots.cpu().tolist() == oslots + [-1] * (mmax - m), (tick, slots.cpu().tolist(), oslots)
+        # hits of this tick (after the halving): some entries several times
+        live = np.nonzero(ob.valid)[0]
+        hit_slots = g.choice(live, size=min(5, len(live)), replace=True).tolist() if len(live) else []
+        ob.touch(hit_slots, tick)
+        for j in hit_slots:
+            bank.last_used[j] = tick
+            bank.hits[j] += 1
+        if tick % 5 == 0:
+            vm = int(g.integers(1, 4))
+            vic = torch.empty((4,), dtype=torch.int32, device="cuda")
+            L.llmc_bank_evict(bank, torch.tensor([vm], dtype=torch.int32, device="cuda"), 4, vic)
+            torch.cuda.synchronize()
+            assert vic.cpu().tolist() == ob.evict(vm) + [-1] * (4 - vm)
+        torch.cuda.synchronize()
+        v = ob.valid.astype(bool)
+        assert np.array_equal(bank.valid.cpu().numpy(), ob.valid)
+        assert np.array_equal(bank.hits.cpu().numpy().astype(np.uint32)[v], ob.hits[v]), tick
+        assert np.array_equal(bank.last_used.cpu().numpy().astype(np.uint64)[v], ob.last_used[v])
+    assert int(counters[L.CNT_EVICTED]) > 0
+    bank.close()
+
+
+def test_gated_stream_with_decayed_hits_policy(L):
+    """The gated layer itself with INSERT_ON_MISS | UPDATE_LRU on banks ranked by decayed hits: slots taken, hit counts
+    and recency after every batch against the oracle (tiny fp32 encoder, so decisions are far from the threshold)."""
+    from paper_2512_16843_amd.engine import GatedStack
+    say("gated stream, decayed-hits banks: repeated and fresh sequences over 10 batches")
+    cfg = W.scaled(W.TINY_ENCODER, n_layers=2, B=6, n_bank=10)
+    ws = W.make_layer_weights(cfg, seed=0)
+    tok, pos = W.make_embeddings(cfg, seed=0)
+    Ps = W.make_projection(cfg.d, cfg.k, cfg.torch_dtype, seed=3, n_layers=cfg.n_layers)
+    st = GatedStack(cfg, ws, Ps, policy=L.EVICT_DECAYED_HITS, half_life=3)
+    obanks = [O.Bank(cfg.n_bank, cfg.k, cfg.S, cfg.d, "f32", decayed_hits=True, half_life=3) for _ in range(cfg.n_layers)]
+    wnp = [{k_: npf(v) for k_, v in w.items()} for w in ws]
+    Pnp = [npf(p) for p in Ps]
+    pool = W.make_sources(cfg, 14, seed=1)
+    g = np.random.Generator(np.random.PCG64(32))
+    flags = L.INSERT_ON_MISS | L.UPDATE_LRU
+    evicted = 0
+    for tick in range(1, 11):
+        ids = pool[g.integers(0, 6 if tick < 5 else 14, size=cfg.B)]      # early batches revisit a few sources
+        h0 = W.embed(torch.from_numpy(ids), tok, pos, cfg.torch_dtype).cuda()
+        st.forward(h0, tau=0.99, flags=flags, tick=tick)
+        torch.cuda.synchronize()
+        _, res = O.infer(npf(h0), obanks, Pnp, [None] * cfg.n_layers, wnp, cfg.arch, cfg.n_heads, cfg.ln_eps, cfg.gelu,
+                         tau=f32(0.99), flags=O.FLAG_INSERT_ON_MISS | O.FLAG_UPDATE_LRU, tick=tick, out_dtype="f32")
+        for l in range(cfg.n_layers):
+            gate, r, bk, ob = st.gate[l], res[l], st.banks[l], obanks[l]
+            near = np.abs(r.sim - f32(0.99)) < 1e-3
+            assert not near.any()
+            assert np.array_equal(gate.hit.cpu().numpy().astype(bool), r.hit)
+            n_miss = int((~r.hit).sum())
+            assert gate.slots.cpu().tolist()[:n_miss] == r.slots, (tick, l)
+            v = ob.valid.astype(bool)
+            assert np.array_equal(bk.valid.cpu().numpy(), ob.valid)
+            assert np.array_equal(bk.hits.cpu().numpy().astype(np.uint32)[v], ob.hits[v]), (tick, l)
+            assert np.array_equal(bk.last_used.cpu().numpy().astype(np.uint64)[v], ob.last_used[v])
+            evicted += r.n_evicted
+    assert evicted > 0
+    st.close()
+
+
 def test_insert_without_eviction_drops_and_counts(L):
     say("insert into a full bank with policy NONE")
     g = np.random.Generator(np.random.PCG64(13))
