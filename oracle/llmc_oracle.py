@@ -49,6 +49,7 @@ GELU_TANH = 1
 
 FLAG_INSERT_ON_MISS = 1
 FLAG_UPDATE_LRU = 2
+FLAG_REVALIDATE = 4
 
 NORM_FLOOR = 1e-12
 
@@ -464,12 +465,16 @@ class GateResult:
     hit: np.ndarray            # [B] bool
     slots: List[int]           # slots taken by this batch's insertions (ascending miss row order)
     n_evicted: int
+    revalidated: List[int] = None   # hit rows that were re-computed (divergence monitor), ascending
+    divergence: List[float] = None  # their divergence from the cached value
+    refreshed: List[int] = None     # slots whose cached value was replaced by the fresh output
 
 
 def gated_layer(h_in: np.ndarray, bank: Optional[Bank], P: Optional[np.ndarray], c: Optional[np.ndarray],
                 w: Dict[str, np.ndarray], arch: int, n_heads: int, eps: float, gelu_kind: int,
                 tau: float, flags: int = 0, tick: int = 0, out_dtype: Optional[str] = None,
-                fp_override: Optional[Tuple[np.ndarray, np.ndarray]] = None) -> GateResult:
+                fp_override: Optional[Tuple[np.ndarray, np.ndarray]] = None, reval_every: int = 0,
+                drift_bound: float = 0.0) -> GateResult:
     """One trip of Algorithm 1's loop body for a whole batch.
 
     The batch is matched against the bank as it stands on entry; insertions
@@ -479,6 +484,14 @@ def gated_layer(h_in: np.ndarray, bank: Optional[Bank], P: Optional[np.ndarray],
     storage-type values); h_out itself is returned unrounded for miss rows.
     ``fp_override`` supplies (q, qinv) instead of fingerprinting h_in
     (Algorithm 1 taken literally: one fingerprint of the input for all layers).
+
+    Divergence monitor (Section IV-D third item; Section III-E: "differences in successive
+    outputs for a given fingerprint across inference calls"), with FLAG_REVALIDATE and
+    ``reval_every`` = r >= 1: a hit row b with (tick + b) % r == 0 is computed anyway; its
+    output is the fresh f_l(h_in[b]); its divergence is max|fresh - cached| / max|cached|
+    (1e-30 floor); above ``drift_bound`` the entry's cached value is replaced by the fresh
+    output (stored in ``out_dtype``), the key stays.  The row still counts as a hit and is
+    not inserted again.
     """
     h_in = np.asarray(h_in, dtype=np.float64)
     B, S, d = h_in.shape
@@ -494,11 +507,33 @@ def gated_layer(h_in: np.ndarray, bank: Optional[Bank], P: Optional[np.ndarray],
         q, qinv = fingerprint(h_in, P, c, bank.dtype)
     idx, sim = match(q, qinv, bank.fp, bank.inv_norm, bank.valid)
     hit = threshold(sim, tau)
+    revalidated: List[int] = []
+    divergence: List[float] = []
+    refreshed: List[int] = []
     for b in range(B):
         if hit[b]:
             h_out[b] = bank.act[bank.act_slot[idx[b]]]
         else:
             h_out[b] = layer_forward(h_in[b], w, arch, n_heads, eps, gelu_kind)
+    if (flags & FLAG_REVALIDATE) and reval_every >= 1:
+        for b in range(B):
+            if hit[b] and (int(tick) + b) % int(reval_every) == 0:
+                vslot = int(bank.act_slot[idx[b]])
+                cached = np.asarray(bank.act[vslot], dtype=np.float64)
+                fresh = layer_forward(h_in[b], w, arch, n_heads, eps, gelu_kind)
+                div = float(np.abs(fresh - cached).max() / max(float(np.abs(cached).max()), 1e-30))
+                revalidated.append(b)
+                divergence.append(div)
+                h_out[b] = fresh
+        # all comparisons are against the bank as it stood; replacements happen afterwards, in row order
+        for b, div in zip(revalidated, divergence):
+            if div > float(drift_bound):
+                vslot = int(bank.act_slot[idx[b]])
+                val = h_out[b]
+                if out_dtype is not None:
+                    val = round_to_storage(val, out_dtype)
+                bank.act[vslot] = val
+                refreshed.append(int(idx[b]))
     if flags & FLAG_UPDATE_LRU:
         bank.touch([int(idx[b]) for b in range(B) if hit[b]], tick)
     slots: List[int] = []
@@ -510,14 +545,14 @@ def gated_layer(h_in: np.ndarray, bank: Optional[Bank], P: Optional[np.ndarray],
             if out_dtype is not None:
                 vals = round_to_storage(vals, out_dtype)
             slots, n_evicted = bank.insert(q[miss], qinv[miss], vals, tick)
-    return GateResult(h_out, q, qinv, idx, sim, hit, slots, n_evicted)
+    return GateResult(h_out, q, qinv, idx, sim, hit, slots, n_evicted, revalidated, divergence, refreshed)
 
 
 def infer(h0: np.ndarray, banks: Sequence[Optional[Bank]], Ps: Sequence[np.ndarray],
           cs: Sequence[Optional[np.ndarray]], weights: Sequence[Dict[str, np.ndarray]], arch: int,
           n_heads: int, eps: float, gelu_kind: int, tau: float, flags: int = 0, tick: int = 0,
-          out_dtype: Optional[str] = None, single_fingerprint: bool = False
-          ) -> Tuple[np.ndarray, List[GateResult]]:
+          out_dtype: Optional[str] = None, single_fingerprint: bool = False, reval_every: int = 0,
+          drift_bound: float = 0.0) -> Tuple[np.ndarray, List[GateResult]]:
     """Algorithm 1 for a batch: h_0 through all L gated layers.
 
     Default: layer l fingerprints its own input h_{l-1} with P_l.  With
@@ -534,7 +569,7 @@ def infer(h0: np.ndarray, banks: Sequence[Optional[Bank]], Ps: Sequence[np.ndarr
         fp0 = fingerprint(h, Ps[0], cs[0], dt)
     for l, w in enumerate(weights):
         r = gated_layer(h, banks[l], Ps[l], cs[l], w, arch, n_heads, eps, gelu_kind, tau, flags, tick,
-                        out_dtype, fp_override=fp0)
+                        out_dtype, fp_override=fp0, reval_every=reval_every, drift_bound=drift_bound)
         results.append(r)
         h = r.h_out
         if out_dtype is not None:

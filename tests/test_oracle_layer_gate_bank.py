@@ -302,6 +302,45 @@ def test_gate_mixes_hits_and_misses_and_updates_lru():
         r0.h_out[0], O.layer_forward(h0[0], ws[0], cfg.arch, cfg.n_heads, cfg.ln_eps, cfg.gelu))
 
 
+def test_divergence_monitor_recomputes_sampled_hits_and_refreshes_drifted_entries():
+    cfg, ws, tok, pos, Ps, src, h_src = tiny_setup()
+    banks, _, _ = build_banks(cfg, ws, Ps, h_src)
+    bank = banks[0]
+    h = h_src[:cfg.B]                               # resubmitted sources: every row hits at similarity 1
+    plain = np.stack([O.layer_forward(h[b].astype(np.float64), ws[0], cfg.arch, cfg.n_heads, cfg.ln_eps, cfg.gelu)
+                      for b in range(cfg.B)])
+    before = bank.act.copy()
+    # no drift: sampled rows (tick + b) % 2 == 0 are recomputed, equal to the cache, nothing is replaced
+    r = O.gated_layer(h, bank, Ps[0], None, ws[0], cfg.arch, cfg.n_heads, cfg.ln_eps, cfg.gelu, 0.95,
+                      flags=O.FLAG_REVALIDATE, tick=3, reval_every=2, drift_bound=1e-5)
+    assert r.hit.all() and r.revalidated == [b for b in range(cfg.B) if (3 + b) % 2 == 0]
+    assert max(r.divergence) < 1e-6 and r.refreshed == [] and np.array_equal(bank.act, before)   # fp32 storage
+    np.testing.assert_allclose(r.h_out, plain, atol=1e-12)
+    # drift two cached values by hand: one sampled (replaced by the fresh output), one not sampled (left alone)
+    s_sampled, s_other = int(r.idx[1]), int(r.idx[2])
+    bank.act[s_sampled] += 0.5
+    bank.act[s_other] += 0.5
+    drifted = bank.act.copy()
+    r = O.gated_layer(h, bank, Ps[0], None, ws[0], cfg.arch, cfg.n_heads, cfg.ln_eps, cfg.gelu, 0.95,
+                      flags=O.FLAG_REVALIDATE, tick=3, reval_every=2, drift_bound=0.05)
+    assert r.refreshed == [s_sampled]
+    i = r.revalidated.index(1)
+    want = np.abs(plain[1] - drifted[s_sampled]).max() / np.abs(drifted[s_sampled]).max()
+    assert abs(r.divergence[i] - want) < 1e-12 and want > 0.05
+    np.testing.assert_allclose(bank.act[s_sampled], plain[1], atol=1e-6)
+    assert np.array_equal(bank.act[s_other], drifted[s_other])
+    np.testing.assert_allclose(r.h_out[1], plain[1], atol=1e-12)          # the sampled row returns the fresh output
+    assert np.array_equal(r.h_out[2], drifted[s_other])                   # the other one still returns its cache
+    # without the flag, or with reval_every 0, nothing is recomputed; sampled rows are not inserted again
+    r = O.gated_layer(h, bank, Ps[0], None, ws[0], cfg.arch, cfg.n_heads, cfg.ln_eps, cfg.gelu, 0.95,
+                      flags=O.FLAG_INSERT_ON_MISS, tick=4, reval_every=2, drift_bound=0.05)
+    assert r.revalidated == [] and r.slots == []
+    n_valid = int(bank.valid.sum())
+    r = O.gated_layer(h, bank, Ps[0], None, ws[0], cfg.arch, cfg.n_heads, cfg.ln_eps, cfg.gelu, 0.95,
+                      flags=O.FLAG_INSERT_ON_MISS | O.FLAG_REVALIDATE, tick=4, reval_every=1, drift_bound=0.05)
+    assert r.revalidated == list(range(cfg.B)) and r.slots == [] and int(bank.valid.sum()) == n_valid
+
+
 def test_single_fingerprint_mode_reuses_layer_one_key():
     cfg, ws, tok, pos, Ps, src, h_src = tiny_setup()
     banks = [O.Bank(cfg.n_bank, cfg.k, cfg.S, cfg.d, "f32") for _ in range(2)]
