@@ -69,6 +69,13 @@ typedef enum { LLMC_EVICT_NONE = 0, LLMC_EVICT_LRU = 1, LLMC_EVICT_DECAYED_HITS 
 /* Flags of llmc_layer_forward_gated. */
 #define LLMC_INSERT_ON_MISS 1u /* Algorithm 1: store (f_X, h_l) of every computed row */
 #define LLMC_UPDATE_LRU 2u     /* record hits: last_used = tick, hits += 1 */
+#define LLMC_REVALIDATE 4u     /* divergence monitor (Section IV-D, third item; Section III-E): with the bank's
+                                  reval_every = r >= 1, a hit row b with (tick + b) % r == 0 is computed anyway and
+                                  returns the fresh f_l(h_in[b]); its divergence max|fresh - cached| / max|cached| is
+                                  compared with the bank's drift_bound and, if larger, the entry's cached value is
+                                  replaced by the fresh output (the key stays).  When several sampled rows of a batch
+                                  matched one entry, the lowest row alone decides.  Such rows count as hits and are
+                                  not inserted again.  Needs a bank whose keys own their value rows. */
 
 /* Largest tick accepted (recency keys are packed into 32 bits on the device). */
 #define LLMC_MAX_TICK 0x7FFFFFFEull
@@ -84,7 +91,10 @@ enum {
   LLMC_CNT_INSERTED = 4,
   LLMC_CNT_EVICTED = 5,  /* insertions that replaced a valid entry */
   LLMC_CNT_DROPPED = 6,  /* insertions skipped: bank full and policy NONE */
-  LLMC_CNT_WORDS = 8
+  LLMC_CNT_COMPUTED = 7, /* rows that went through f_l: misses + revalidated hits */
+  LLMC_CNT_REVALIDATED = 8, /* hit rows recomputed by the divergence monitor */
+  LLMC_CNT_DIVERGED = 9,    /* of those, entries whose cached value was replaced */
+  LLMC_CNT_WORDS = 12
 };
 
 /*
@@ -114,6 +124,8 @@ typedef struct {
   uint32_t* d_hits;
   uint8_t* d_valid;
   int32_t half_life; /* LLMC_EVICT_DECAYED_HITS: ticks per halving of the hit counts, 0 = never; else ignored */
+  int32_t reval_every; /* LLMC_REVALIDATE: sampling period r of the divergence monitor, 0 = off */
+  float drift_bound;   /* LLMC_REVALIDATE: divergence above which a cached value is replaced */
 } llmc_bank_desc_t;
 
 /*
@@ -311,7 +323,7 @@ llmc_status_t llmc_gather_hits(const llmc_bank_t* bank, const int32_t* d_idx, co
  *   d_h_in, d_h_out [B, S, d], element type of the layer; they must not overlap
  *   d_fp_given / d_inv_norm_given: NULL, or keys [B, k] + norms to use instead of
  *          fingerprinting d_h_in (Algorithm 1 taken literally: one fingerprint of X for all layers)
- *   tau: threshold; flags: LLMC_INSERT_ON_MISS | LLMC_UPDATE_LRU; tick <= LLMC_MAX_TICK
+ *   tau: threshold; flags: LLMC_INSERT_ON_MISS | LLMC_UPDATE_LRU | LLMC_REVALIDATE; tick <= LLMC_MAX_TICK
  *   out: optional per-row results and counters (NULL or any member NULL)
  *   d_workspace: at least llmc_layer_workspace_bytes(layer, B, S, k) bytes
  * The number of misses never visits the host: the miss-path kernels read it on

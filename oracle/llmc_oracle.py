@@ -490,7 +490,8 @@ def gated_layer(h_in: np.ndarray, bank: Optional[Bank], P: Optional[np.ndarray],
     ``reval_every`` = r >= 1: a hit row b with (tick + b) % r == 0 is computed anyway; its
     output is the fresh f_l(h_in[b]); its divergence is max|fresh - cached| / max|cached|
     (1e-30 floor); above ``drift_bound`` the entry's cached value is replaced by the fresh
-    output (stored in ``out_dtype``), the key stays.  The row still counts as a hit and is
+    output (stored in ``out_dtype``), the key stays; if several sampled rows of the batch
+    matched one entry, the lowest row alone decides.  The row still counts as a hit and is
     not inserted again.
     """
     h_in = np.asarray(h_in, dtype=np.float64)
@@ -525,8 +526,13 @@ def gated_layer(h_in: np.ndarray, bank: Optional[Bank], P: Optional[np.ndarray],
                 revalidated.append(b)
                 divergence.append(div)
                 h_out[b] = fresh
-        # all comparisons are against the bank as it stood; replacements happen afterwards, in row order
+        # all comparisons are against the bank as it stood; replacements happen afterwards.  When several
+        # sampled rows matched one entry, the lowest row alone decides about that entry.
+        decided = set()
         for b, div in zip(revalidated, divergence):
+            if int(idx[b]) in decided:
+                continue
+            decided.add(int(idx[b]))
             if div > float(drift_bound):
                 vslot = int(bank.act_slot[idx[b]])
                 val = h_out[b]

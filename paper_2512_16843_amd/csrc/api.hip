@@ -72,8 +72,8 @@ static llmc_status_t check_layer(const llmc_layer_desc_t* L) {
 }
 
 static size_t gate_small_bytes(int B, int k, int dtype) {
-  // keys, inverse norms, idx, sim, hit, tie, hit_rows, miss_rows, slots, counters
-  return align_up((size_t)B * k * elem_size(dtype), 256) + 6 * align_up((size_t)B * 4, 256) +
+  // keys, inverse norms, idx, sim, hit, tie, hit_rows, miss_rows, slots, recomputed-row scratch, counters
+  return align_up((size_t)B * k * elem_size(dtype), 256) + 7 * align_up((size_t)B * 4, 256) +
          2 * align_up((size_t)B, 256) + 256;
 }
 
@@ -349,7 +349,8 @@ llmc_status_t llmc_layer_forward_gated(const llmc_layer_desc_t* layer, llmc_bank
   REQUIRE((int64_t)B * S <= 0x7FFFFFFF / 4, LLMC_ERR_SHAPE, "B*S too large");
   REQUIRE(tau == tau, LLMC_ERR_INVALID_ARG, "tau is NaN");
   REQUIRE(tick <= LLMC_MAX_TICK, LLMC_ERR_INVALID_ARG, "tick out of range");
-  REQUIRE((flags & ~(LLMC_INSERT_ON_MISS | LLMC_UPDATE_LRU)) == 0, LLMC_ERR_INVALID_ARG, "unknown flag bits");
+  REQUIRE((flags & ~(LLMC_INSERT_ON_MISS | LLMC_UPDATE_LRU | LLMC_REVALIDATE)) == 0, LLMC_ERR_INVALID_ARG,
+          "unknown flag bits");
   int k = 0;
   if (bank) {
     const llmc_bank_desc_t& D = bank->desc;
@@ -369,6 +370,12 @@ llmc_status_t llmc_layer_forward_gated(const llmc_layer_desc_t* layer, llmc_bank
     REQUIRE(D.policy != LLMC_EVICT_DECAYED_HITS || !(flags & (LLMC_INSERT_ON_MISS | LLMC_UPDATE_LRU)) ||
                 tick <= LLMC_MAX_TICK_DECAYED,
             LLMC_ERR_INVALID_ARG, "tick out of range for a bank ranked by decayed hits");
+    if (flags & LLMC_REVALIDATE) {
+      REQUIRE(D.reval_every >= 0 && D.drift_bound == D.drift_bound && D.drift_bound >= 0.f, LLMC_ERR_INVALID_ARG,
+              "reval_every and drift_bound must not be negative");
+      REQUIRE(D.n_act_slots == D.n_slots, LLMC_ERR_SHAPE,
+              "the divergence monitor is refused on a bank whose keys share value rows");
+    }
     if (flags & LLMC_INSERT_ON_MISS) {
       REQUIRE(B <= LLMC_MAX_UPDATE_ROWS, LLMC_ERR_SHAPE, "insertion handles at most %d rows per call",
               LLMC_MAX_UPDATE_ROWS);
@@ -391,6 +398,7 @@ llmc_status_t llmc_layer_forward_gated(const llmc_layer_desc_t* layer, llmc_bank
   int32_t* hit_rows = (int32_t*)take((size_t)B * 4);
   int32_t* miss_rows = (int32_t*)take((size_t)B * 4);
   int32_t* slots = (int32_t*)take((size_t)B * 4);
+  int32_t* reval_tmp = (int32_t*)take((size_t)B * 4);
   uint8_t* hit = (uint8_t*)take((size_t)B);
   uint8_t* tie = (uint8_t*)take((size_t)B);
   int32_t* counters = (int32_t*)take(LLMC_CNT_WORDS * 4);
@@ -406,7 +414,7 @@ llmc_status_t llmc_layer_forward_gated(const llmc_layer_desc_t* layer, llmc_bank
   if (!bank) {
     LLMC_TRY(launch_all_miss(B, miss_rows, counters, out ? out->d_idx : nullptr, out ? out->d_sim : nullptr,
                              out ? out->d_hit : nullptr, st));
-    return launch_layer(layer, d_h_in, d_h_out, B, S, miss_rows, counters + LLMC_CNT_MISS, ws_layer, st);
+    return launch_layer(layer, d_h_in, d_h_out, B, S, miss_rows, counters + LLMC_CNT_COMPUTED, ws_layer, st);
   }
   if (flags & (LLMC_INSERT_ON_MISS | LLMC_UPDATE_LRU)) LLMC_TRY(launch_bank_advance(bank, tick, st));
   const void* q = d_fp_given;
@@ -418,9 +426,12 @@ llmc_status_t llmc_layer_forward_gated(const llmc_layer_desc_t* layer, llmc_bank
     qinv = inv;
   }
   LLMC_TRY(launch_match(bank, q, qinv, B, tau, idx, sim, hit, tie, ws_match, st));
-  LLMC_TRY(launch_compact(hit, idx, sim, tie, B, tau, hit_rows, miss_rows, counters, bank, flags, tick, st));
+  LLMC_TRY(launch_compact(hit, idx, sim, tie, B, tau, hit_rows, miss_rows, reval_tmp, counters, bank, flags, tick, st));
   LLMC_TRY(launch_gather(bank, idx, hit_rows, counters + LLMC_CNT_HIT, B, d_h_out, st));
-  LLMC_TRY(launch_layer(layer, d_h_in, d_h_out, B, S, miss_rows, counters + LLMC_CNT_MISS, ws_layer, st));
+  // the rows to compute: the misses, then (divergence monitor) the sampled hit rows, whose copies are overwritten
+  LLMC_TRY(launch_layer(layer, d_h_in, d_h_out, B, S, miss_rows, counters + LLMC_CNT_COMPUTED, ws_layer, st));
+  if ((flags & LLMC_REVALIDATE) && bank->desc.reval_every > 0)
+    LLMC_TRY(launch_divergence(bank, d_h_out, idx, miss_rows, counters, B, st));
   if (flags & LLMC_INSERT_ON_MISS)
     LLMC_TRY(launch_bank_insert(bank, q, qinv, d_h_out, miss_rows, counters + LLMC_CNT_MISS, B, tick, slots, counters,
                                 st));

@@ -158,8 +158,10 @@ llmc_status_t launch_match(const llmc_bank* bank, const void* d_fp, const float*
 // gate.hip
 llmc_status_t launch_compact(const uint8_t* d_hit, const int32_t* d_idx, const float* d_sim,
                              const uint8_t* d_near_tie, int B, float tau, int32_t* d_hit_rows,
-                             int32_t* d_miss_rows, int32_t* d_counters, llmc_bank* bank, uint32_t flags,
-                             uint64_t tick, hipStream_t st);
+                             int32_t* d_miss_rows, int32_t* d_reval_tmp, int32_t* d_counters, llmc_bank* bank,
+                             uint32_t flags, uint64_t tick, hipStream_t st);
+llmc_status_t launch_divergence(llmc_bank* bank, const void* d_h_out, const int32_t* d_idx, const int32_t* d_rows,
+                                int32_t* d_counters, int B, hipStream_t st);
 llmc_status_t launch_all_miss(int B, int32_t* d_miss_rows, int32_t* d_counters, int32_t* d_idx, float* d_sim,
                               uint8_t* d_hit, hipStream_t st);
 llmc_status_t launch_gather(const llmc_bank* bank, const int32_t* d_idx, const int32_t* d_rows,

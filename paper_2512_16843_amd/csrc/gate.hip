@@ -8,34 +8,43 @@ namespace llmc {
 
 // One workgroup of 1024 threads walks the batch in ascending chunks; within a chunk a
 // ballot + popcount gives each row its rank among the hits (and among the misses).
+// Divergence monitor (Section IV-D): with reval_every = r >= 1 a hit row b with (tick + b) % r == 0
+// is also appended, after all misses, to the list of rows to compute: miss_rows holds the misses in
+// ascending order followed by those rows in ascending order; counters[COMPUTED] is the length of that
+// list, counters[MISS] the number of real misses at its head.
 __global__ __launch_bounds__(1024) void compact_kernel(const uint8_t* __restrict__ hit, const int32_t* __restrict__ idx,
                                                        const float* __restrict__ sim, const uint8_t* __restrict__ tie,
                                                        int B, float tau, int32_t* __restrict__ hit_rows,
                                                        int32_t* __restrict__ miss_rows, int32_t* __restrict__ counters,
-                                                       uint64_t* last_used, uint32_t* hits, int touch, uint64_t tick) {
-  __shared__ int wave_hits[16];
-  __shared__ int base_hit, base_miss, s_near_tau, s_near_tie;
+                                                       uint64_t* last_used, uint32_t* hits, int touch, uint64_t tick,
+                                                       int reval_every, int32_t* __restrict__ reval_tmp) {
+  __shared__ int wave_hits[16], wave_reval[16];
+  __shared__ int base_hit, base_miss, base_reval, s_near_tau, s_near_tie;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  if (tid == 0) { base_hit = 0; base_miss = 0; s_near_tau = 0; s_near_tie = 0; }
+  if (tid == 0) { base_hit = 0; base_miss = 0; base_reval = 0; s_near_tau = 0; s_near_tie = 0; }
   __syncthreads();
   for (int c0 = 0; c0 < B; c0 += 1024) {
     const int b = c0 + tid;
     const bool in = b < B;
     const bool h = in && hit[b] != 0;
-    const unsigned long long bal = __ballot(h);
-    const int before = __popcll(bal & ((1ull << lane) - 1ull));
-    if (lane == 0) wave_hits[wave] = __popcll(bal);
+    const bool rv = h && reval_every > 0 && (tick + (uint64_t)b) % (uint64_t)reval_every == 0;
+    const unsigned long long bal = __ballot(h), bal_rv = __ballot(rv);
+    const unsigned long long below = (1ull << lane) - 1ull;
+    const int before = __popcll(bal & below), before_rv = __popcll(bal_rv & below);
+    if (lane == 0) { wave_hits[wave] = __popcll(bal); wave_reval[wave] = __popcll(bal_rv); }
     __syncthreads();
-    int wbase = 0, total = 0;
+    int wbase = 0, total = 0, wbase_rv = 0, total_rv = 0;
     for (int w = 0; w < 16; ++w) {
-      if (w < wave) wbase += wave_hits[w];
+      if (w < wave) { wbase += wave_hits[w]; wbase_rv += wave_reval[w]; }
       total += wave_hits[w];
+      total_rv += wave_reval[w];
     }
     const int n_in = min(1024, B - c0);
     if (in) {
       const int hrank = wbase + before;
       if (h) {
         hit_rows[base_hit + hrank] = b;
+        if (rv) reval_tmp[base_reval + wbase_rv + before_rv] = b;
         if (touch) {
           const int j = idx[b];
           last_used[j] = tick;            // several rows may name one slot: same value
@@ -48,19 +57,83 @@ __global__ __launch_bounds__(1024) void compact_kernel(const uint8_t* __restrict
       if (tie && tie[b]) atomicAdd(&s_near_tie, 1);
     }
     __syncthreads();
-    if (tid == 0) { base_hit += total; base_miss += n_in - total; }
+    if (tid == 0) { base_hit += total; base_miss += n_in - total; base_reval += total_rv; }
     __syncthreads();
   }
+  const int n_miss = base_miss, n_reval = base_reval;
+  for (int i = tid; i < n_reval; i += 1024) miss_rows[n_miss + i] = reval_tmp[i];
   if (tid == 0) {
     counters[LLMC_CNT_HIT] = base_hit;
-    counters[LLMC_CNT_MISS] = base_miss;
+    counters[LLMC_CNT_MISS] = n_miss;
     counters[LLMC_CNT_NEAR_TAU] = s_near_tau;
     counters[LLMC_CNT_NEAR_TIE] = s_near_tie;
     counters[LLMC_CNT_INSERTED] = 0;
     counters[LLMC_CNT_EVICTED] = 0;
     counters[LLMC_CNT_DROPPED] = 0;
-    counters[7] = 0;
+    counters[LLMC_CNT_COMPUTED] = n_miss + n_reval;
+    counters[LLMC_CNT_REVALIDATED] = n_reval;
+    counters[LLMC_CNT_DIVERGED] = 0;
+    counters[10] = 0;
+    counters[11] = 0;
   }
+}
+
+// Divergence monitor, second half: workgroup i takes the i-th recomputed hit row.  It compares the fresh output
+// (already in h_out) with the cached value, max|fresh - cached| / max|cached|, and replaces the cached value when
+// the ratio exceeds the bound -- unless a lower recomputed row of this batch matched the same entry, which then
+// decides alone.  grid (B).
+template <typename T>
+__global__ __launch_bounds__(1024) void divergence_kernel(const T* __restrict__ h_out, T* __restrict__ act,
+                                                          const int32_t* __restrict__ act_slot,
+                                                          const int32_t* __restrict__ idx,
+                                                          const int32_t* __restrict__ rows, int32_t* counters,
+                                                          size_t elems_per_seq, float bound) {
+  constexpr int VEC = Vec16<T>::N;
+  __shared__ float red_d[16], red_c[16];
+  __shared__ int s_owner;
+  const int n_miss = counters[LLMC_CNT_MISS], n_reval = counters[LLMC_CNT_REVALIDATED];
+  const int i = blockIdx.x;
+  if (i >= n_reval) return;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int row = rows[n_miss + i];
+  const int slot = idx[row];
+  if (tid == 0) s_owner = 1;
+  __syncthreads();
+  for (int o = tid; o < i; o += 1024)
+    if (idx[rows[n_miss + o]] == slot) s_owner = 0;
+  __syncthreads();
+  if (!s_owner) return;
+  const int vslot = act_slot ? act_slot[slot] : slot;
+  const T* fresh = h_out + (size_t)row * elems_per_seq;
+  T* cached = act + (size_t)vslot * elems_per_seq;
+  float md = 0.f, mc = 0.f;
+  for (size_t e = (size_t)tid * VEC; e < elems_per_seq; e += (size_t)1024 * VEC) {
+    float f[VEC], c[VEC];
+    Vec16<T>::load(fresh + e, f);
+    Vec16<T>::load(cached + e, c);
+#pragma unroll
+    for (int u = 0; u < VEC; ++u) {
+      md = fmaxf(md, fabsf(f[u] - c[u]));
+      mc = fmaxf(mc, fabsf(c[u]));
+    }
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    md = fmaxf(md, __shfl_xor(md, o, 64));
+    mc = fmaxf(mc, __shfl_xor(mc, o, 64));
+  }
+  if (lane == 0) { red_d[wave] = md; red_c[wave] = mc; }
+  __syncthreads();
+  md = 0.f; mc = 0.f;
+  for (int w = 0; w < 16; ++w) { md = fmaxf(md, red_d[w]); mc = fmaxf(mc, red_c[w]); }
+  const float div = md / fmaxf(mc, 1e-30f);
+  if (!(div > bound)) return;
+  for (size_t e = (size_t)tid * VEC; e < elems_per_seq; e += (size_t)1024 * VEC) {
+    float f[VEC];
+    Vec16<T>::load(fresh + e, f);
+    Vec16<T>::store(cached + e, f);
+  }
+  if (tid == 0) atomicAdd(&counters[LLMC_CNT_DIVERGED], 1);
 }
 
 // uncached layer: every row is a miss
@@ -72,7 +145,7 @@ __global__ void all_miss_kernel(int B, int32_t* miss_rows, int32_t* counters, in
     if (sim) sim[b] = -INFINITY;
     if (hit) hit[b] = 0;
   }
-  if (b < LLMC_CNT_WORDS) counters[b] = b == LLMC_CNT_MISS ? B : 0;
+  if (b < LLMC_CNT_WORDS) counters[b] = (b == LLMC_CNT_MISS || b == LLMC_CNT_COMPUTED) ? B : 0;
 }
 
 // Copy of cached outputs: grid (chunks, n_max); every thread moves 16-byte vectors.
@@ -109,12 +182,29 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(const u32x4_t* _
 }
 
 llmc_status_t launch_compact(const uint8_t* d_hit, const int32_t* d_idx, const float* d_sim, const uint8_t* d_near_tie,
-                             int B, float tau, int32_t* d_hit_rows, int32_t* d_miss_rows, int32_t* d_counters,
-                             llmc_bank* bank, uint32_t flags, uint64_t tick, hipStream_t st) {
+                             int B, float tau, int32_t* d_hit_rows, int32_t* d_miss_rows, int32_t* d_reval_tmp,
+                             int32_t* d_counters, llmc_bank* bank, uint32_t flags, uint64_t tick, hipStream_t st) {
   const int touch = (flags & LLMC_UPDATE_LRU) ? 1 : 0;
+  const int reval_every = (flags & LLMC_REVALIDATE) ? bank->desc.reval_every : 0;
   { ProfScope ps_("compact_kernel", st); hipLaunchKernelGGL(compact_kernel, dim3(1), dim3(1024), 0, st, d_hit, d_idx, d_sim, d_near_tie, B, tau, d_hit_rows,
-                     d_miss_rows, d_counters, bank->desc.d_last_used, bank->desc.d_hits, touch, tick); }
+                     d_miss_rows, d_counters, bank->desc.d_last_used, bank->desc.d_hits, touch, tick, reval_every,
+                     d_reval_tmp); }
   LLMC_LAUNCH_CHECK("compact_kernel");
+  return LLMC_OK;
+}
+
+llmc_status_t launch_divergence(llmc_bank* bank, const void* d_h_out, const int32_t* d_idx, const int32_t* d_rows,
+                                int32_t* d_counters, int B, hipStream_t st) {
+  const llmc_bank_desc_t& D = bank->desc;
+  const size_t elems = (size_t)D.S * D.d;
+  ProfScope ps_("divergence_kernel", st);
+  if (D.dtype == LLMC_F32)
+    hipLaunchKernelGGL(divergence_kernel<float>, dim3(B), dim3(1024), 0, st, (const float*)d_h_out, (float*)D.d_act,
+                       D.d_act_slot, d_idx, d_rows, d_counters, elems, D.drift_bound);
+  else
+    hipLaunchKernelGGL(divergence_kernel<bf16_t>, dim3(B), dim3(1024), 0, st, (const bf16_t*)d_h_out, (bf16_t*)D.d_act,
+                       D.d_act_slot, d_idx, d_rows, d_counters, elems, D.drift_bound);
+  LLMC_LAUNCH_CHECK("divergence_kernel");
   return LLMC_OK;
 }
 

@@ -17,7 +17,8 @@ from .workloads import ModelConfig
 class GatedStack:
     def __init__(self, cfg: ModelConfig, weights, projections, device="cuda", cached_layers=None,
                  biases: Optional[List[Optional[torch.Tensor]]] = None, n_bank: Optional[int] = None,
-                 policy: int = llmc.EVICT_LRU, B: Optional[int] = None, half_life: int = 0):
+                 policy: int = llmc.EVICT_LRU, B: Optional[int] = None, half_life: int = 0, reval_every: int = 0,
+                 drift_bound: float = 0.0):
         self.cfg = cfg
         self.device = device
         self.B = cfg.B if B is None else B
@@ -29,7 +30,7 @@ class GatedStack:
         self.banks: List[Optional[llmc.Bank]] = [None] * cfg.n_layers
         for l in cached:
             self.banks[l] = llmc.Bank(n_bank, cfg.k, cfg.S, cfg.d, cfg.torch_dtype, device, policy=policy,
-                                      half_life=half_life)
+                                      half_life=half_life, reval_every=reval_every, drift_bound=drift_bound)
         ws_bytes = llmc.llmc_layer_workspace_bytes(self.layers[0], self.B, cfg.S, cfg.k)
         self.workspace = torch.empty((ws_bytes,), dtype=torch.uint8, device=device)
         self.buf = [torch.empty((self.B, cfg.S, cfg.d), dtype=cfg.torch_dtype, device=device) for _ in range(2)]

@@ -20,8 +20,9 @@ LLMC_OK = 0
 ERR_INVALID_ARG, ERR_SHAPE, ERR_DTYPE, ERR_BANK_FULL, ERR_WORKSPACE, ERR_HIP = 1, 2, 3, 4, 5, 6
 F32, BF16 = 0, 1
 EVICT_NONE, EVICT_LRU, EVICT_DECAYED_HITS = 0, 1, 2
-INSERT_ON_MISS, UPDATE_LRU = 1, 2
-CNT_HIT, CNT_MISS, CNT_NEAR_TAU, CNT_NEAR_TIE, CNT_INSERTED, CNT_EVICTED, CNT_DROPPED, CNT_WORDS = 0, 1, 2, 3, 4, 5, 6, 8
+INSERT_ON_MISS, UPDATE_LRU, REVALIDATE = 1, 2, 4
+CNT_HIT, CNT_MISS, CNT_NEAR_TAU, CNT_NEAR_TIE, CNT_INSERTED, CNT_EVICTED, CNT_DROPPED = 0, 1, 2, 3, 4, 5, 6
+CNT_COMPUTED, CNT_REVALIDATED, CNT_DIVERGED, CNT_WORDS = 7, 8, 9, 12
 MAX_UPDATE_ROWS = 4096
 
 EXPORTS = [
@@ -39,7 +40,8 @@ class BankDesc(C.Structure):
                 ("n_act_slots", C.c_int32), ("dtype", C.c_int32), ("policy", C.c_int32),
                 ("d_fp", C.c_void_p), ("d_act", C.c_void_p), ("d_inv_norm", C.c_void_p),
                 ("d_act_slot", C.c_void_p), ("d_last_used", C.c_void_p), ("d_hits", C.c_void_p),
-                ("d_valid", C.c_void_p), ("half_life", C.c_int32)]
+                ("d_valid", C.c_void_p), ("half_life", C.c_int32), ("reval_every", C.c_int32),
+                ("drift_bound", C.c_float)]
 
 
 class LayerDesc(C.Structure):
@@ -149,7 +151,8 @@ class Bank:
 
     def __init__(self, n_slots: int, k: int, S: int, d: int, dtype: torch.dtype, device="cuda",
                  n_act_slots: Optional[int] = None, policy: int = EVICT_LRU,
-                 act_slot: Optional[torch.Tensor] = None, half_life: int = 0):
+                 act_slot: Optional[torch.Tensor] = None, half_life: int = 0, reval_every: int = 0,
+                 drift_bound: float = 0.0):
         A = n_slots if n_act_slots is None else n_act_slots
         self.n_slots, self.k, self.S, self.d, self.n_act_slots = n_slots, k, S, d, A
         self.dtype = dtype
@@ -162,13 +165,15 @@ class Bank:
         self.valid = torch.zeros((n_slots,), dtype=torch.uint8, device=device)
         self.policy = policy
         self.half_life = half_life
+        self.reval_every, self.drift_bound = reval_every, drift_bound
         self.handle = None
         self.create()
 
     def desc(self) -> BankDesc:
         return BankDesc(self.n_slots, self.k, self.S, self.d, self.n_act_slots, dtype_code(self.dtype), self.policy,
                         _ptr(self.fp), _ptr(self.act), _ptr(self.inv_norm), _ptr(self.act_slot),
-                        _ptr(self.last_used), _ptr(self.hits), _ptr(self.valid), self.half_life)
+                        _ptr(self.last_used), _ptr(self.hits), _ptr(self.valid), self.half_life, self.reval_every,
+                        self.drift_bound)
 
     def create(self) -> None:
         torch.cuda.synchronize()

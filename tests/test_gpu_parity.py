@@ -752,6 +752,82 @@ def test_gated_stream_with_decayed_hits_policy(L):
     st.close()
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_divergence_monitor_against_oracle(L, dtype):
+    """Sampled hit rows are recomputed; cached values that drifted are replaced by the fresh output, the others
+    stay bit for bit; duplicates of one entry are decided by the lowest row.  Oracle banks are copies of the GPU's."""
+    from paper_2512_16843_amd.engine import GatedStack
+    say(f"divergence monitor {dtype}: drifted and clean cached values, duplicate rows, with and without insertion")
+    cfg = W.scaled(W.TINY_ENCODER, n_layers=2, B=8, n_bank=24) if dtype == "f32" else \
+        W.scaled(W.BERT_BASE, n_layers=2, B=8, S=40, n_bank=24)
+    tol = TOL[dtype]
+    ws = W.make_layer_weights(cfg, seed=0)
+    tok, pos = W.make_embeddings(cfg, seed=0)
+    Ps = W.make_projection(cfg.d, cfg.k, cfg.torch_dtype, seed=3, n_layers=cfg.n_layers)
+    st = GatedStack(cfg, ws, Ps, reval_every=2, drift_bound=0.05)
+    src = W.make_sources(cfg, 16, seed=1)
+    for s0 in (0, 8):
+        st.forward(W.embed(torch.from_numpy(src[s0:s0 + 8]), tok, pos, cfg.torch_dtype).cuda(), tau=2.0,
+                   flags=L.INSERT_ON_MISS, tick=1)
+    torch.cuda.synchronize()
+    wnp = [{k_: npf(v) for k_, v in w.items()} for w in ws]
+    Pnp = [npf(p) for p in Ps]
+    g = np.random.Generator(np.random.PCG64(41))
+    # queries: sources 0..5, source 3 again twice (duplicates of one entry), one fresh sequence
+    ids = np.concatenate([src[[0, 1, 2, 3, 3, 5, 3]], W.make_sources(cfg, 1, seed=9)], axis=0)
+    h0 = W.embed(torch.from_numpy(ids), tok, pos, cfg.torch_dtype).cuda()
+    # drift some cached values of layer 0 on the device: slots of sources 1, 3 and 5
+    for j in (1, 3, 5):
+        st.banks[0].act[j] += torch.from_numpy((0.5 * g.standard_normal((cfg.S, cfg.d))).astype(np.float32)).to(cfg.torch_dtype).cuda()
+    for tick, flags in ((4, L.REVALIDATE | L.UPDATE_LRU), (5, L.REVALIDATE | L.INSERT_ON_MISS)):
+        obanks = [oracle_bank_from_gpu(b, dtype) for b in st.banks]
+        act_before = [b.act.clone() for b in st.banks]
+        outs = st.forward(h0, tau=0.9, flags=flags, tick=tick, keep_all=True)
+        torch.cuda.synchronize()
+        oflags = O.FLAG_REVALIDATE | (O.FLAG_UPDATE_LRU if flags & L.UPDATE_LRU else 0) | \
+            (O.FLAG_INSERT_ON_MISS if flags & L.INSERT_ON_MISS else 0)
+        for l in range(cfg.n_layers):
+            h_prev = h0 if l == 0 else outs[l - 1]
+            ob = obanks[l]
+            r = O.gated_layer(npf(h_prev), ob, Pnp[l], None, wnp[l], cfg.arch, cfg.n_heads, cfg.ln_eps, cfg.gelu,
+                              f32(0.9), flags=oflags, tick=tick, out_dtype=dtype, reval_every=2, drift_bound=0.05)
+            gate, bk = st.gate[l], st.banks[l]
+            assert not (np.abs(r.sim - f32(0.9)) < 1e-3).any()
+            hit = gate.hit.cpu().numpy().astype(bool)
+            assert np.array_equal(hit, r.hit) and np.array_equal(gate.idx.cpu().numpy()[hit], r.idx[hit])
+            cnt = gate.counters.cpu().numpy()
+            assert cnt[L.CNT_REVALIDATED] == len(r.revalidated) and cnt[L.CNT_DIVERGED] == len(r.refreshed), (l, cnt, r.refreshed)
+            assert cnt[L.CNT_COMPUTED] == cnt[L.CNT_MISS] + cnt[L.CNT_REVALIDATED] and cnt[L.CNT_HIT] + cnt[L.CNT_MISS] == cfg.B
+            for d_ in r.divergence:
+                assert abs(d_ - 0.05) > 0.02          # decisions of this test sit far from the bound
+            got = npf(outs[l])
+            for b in range(cfg.B):
+                if hit[b] and b not in r.revalidated:
+                    assert torch.equal(outs[l][b], act_before[l][int(r.idx[b])])
+                else:                                 # computed: misses and recomputed hits
+                    assert rel_err_rows(got[b:b + 1], r.h_out[b:b + 1])[0] < tol, (l, b)
+            after = npf(bk.act)
+            taken = set(r.slots)
+            for j in range(cfg.n_bank):
+                if j in r.refreshed or j in taken:
+                    assert rel_err_rows(after[j:j + 1], np.asarray(ob.act[j:j + 1]))[0] < tol, (l, j)
+                else:
+                    assert torch.equal(bk.act[j], act_before[l][j]), (l, j)
+            if flags & L.INSERT_ON_MISS:
+                assert gate.slots.cpu().tolist()[:int(cnt[L.CNT_MISS])] == r.slots
+            if l == 0:
+                # tick 4 samples rows 0, 2, 4, 6: rows 4 and 6 both matched the drifted entry 3 and row 4 decides;
+                # tick 5 samples the hit rows 1, 3, 5: entries 1 and 5 drifted, entry 3 was replaced one tick earlier
+                assert sorted(r.refreshed) == ([3] if tick == 4 else [1, 5])
+        say(f"  tick {tick}: layer-0 recomputed rows {res_rows(st, L)}, replaced {int(st.gate[0].counters[L.CNT_DIVERGED])}")
+    st.close()
+
+
+def res_rows(st, L):
+    c = st.gate[0].counters.cpu().numpy()
+    return int(c[L.CNT_REVALIDATED])
+
+
 def test_insert_without_eviction_drops_and_counts(L):
     say("insert into a full bank with policy NONE")
     g = np.random.Generator(np.random.PCG64(13))
