@@ -21,6 +21,8 @@ What follows the paper, and where:
   otherwise; Algorithm 1: store the computed h_l on a miss.
 * sign-bit keys -- Section IV-B (SimHash), Section III-A: the sign of each
   projection, compared by Hamming distance; cos(pi H / k) stands for the cosine.
+* compressed values -- Section III-B: cached outputs stored as coefficients on a
+  PCA basis and reconstructed on a hit.
 * eviction     -- Section IV-D, first policy: least recently used.
 * f_l          -- Section V-A names the model families; the blocks themselves
   are the textbook post-LN encoder block and pre-LN causal decoder block.
@@ -361,10 +363,15 @@ class Bank:
 
     def __init__(self, n_slots: int, k: int, S: int, d: int, dtype: str,
                  n_act_slots: Optional[int] = None, lru: bool = True, decayed_hits: bool = False,
-                 half_life: int = 0):
+                 half_life: int = 0, basis: Optional[np.ndarray] = None):
         A = n_slots if n_act_slots is None else n_act_slots
         self.N, self.k, self.S, self.d, self.A = n_slots, k, S, d, A
         self.dtype = dtype
+        # compressed cached values (Section III-B: "optionally compresses cached representations via PCA"):
+        # with a basis U [r, d] (rows = principal directions) an entry stores the coefficients
+        # C = h U^T [S, r] in the bank's storage type, and a hit returns the reconstruction C U
+        self.basis = None if basis is None else np.asarray(basis, dtype=np.float64)
+        self.rank = 0 if basis is None else int(self.basis.shape[0])
         self.lru = lru or decayed_hits
         # staleness-aware replacement (Section IV-D, second policy; Section III-E: frequency-based policy and
         # temporal decay): entries are ranked by their hit count, which is halved every `half_life` ticks
@@ -374,11 +381,24 @@ class Bank:
         self.epoch = 0
         self.fp = np.zeros((n_slots, k), dtype=np.float32)
         self.inv_norm = np.zeros((n_slots,), dtype=np.float32)
-        self.act = np.zeros((A, S, d), dtype=np.float32)
+        self.act = np.zeros((A, S, d if basis is None else self.rank), dtype=np.float32)
         self.act_slot = np.arange(n_slots, dtype=np.int32) if A == n_slots else np.zeros((n_slots,), np.int32)
         self.last_used = np.zeros((n_slots,), dtype=np.uint64)
         self.hits = np.zeros((n_slots,), dtype=np.uint32)
         self.valid = np.zeros((n_slots,), dtype=np.uint8)
+
+    # -- cached values -------------------------------------------------------
+    def encode(self, h: np.ndarray) -> np.ndarray:
+        """What is stored for an output h [S, d]: h itself, or its coefficients on the basis, rounded to storage."""
+        if self.basis is None:
+            return h
+        return round_to_storage(np.asarray(h, dtype=np.float64) @ self.basis.T, self.dtype)
+
+    def value(self, vslot: int) -> np.ndarray:
+        """What a hit on value row ``vslot`` returns: the stored output, or its reconstruction C U (float64)."""
+        if self.basis is None:
+            return self.act[vslot]
+        return np.asarray(self.act[vslot], dtype=np.float64) @ self.basis
 
     # -- temporal decay ------------------------------------------------------
     def advance(self, tick: int) -> None:
@@ -430,7 +450,7 @@ class Bank:
             n_evicted += int(self.valid[j])
             self.fp[j] = q[i]
             self.inv_norm[j] = qinv[i]
-            self.act[self.act_slot[j]] = acts[i]
+            self.act[self.act_slot[j]] = self.encode(acts[i])
             self.last_used[j] = tick
             self.hits[j] = 0
             self.valid[j] = 1
@@ -513,10 +533,11 @@ def gated_layer(h_in: np.ndarray, bank: Optional[Bank], P: Optional[np.ndarray],
     refreshed: List[int] = []
     for b in range(B):
         if hit[b]:
-            h_out[b] = bank.act[bank.act_slot[idx[b]]]
+            h_out[b] = bank.value(int(bank.act_slot[idx[b]]))
         else:
             h_out[b] = layer_forward(h_in[b], w, arch, n_heads, eps, gelu_kind)
     if (flags & FLAG_REVALIDATE) and reval_every >= 1:
+        assert bank.basis is None, "the divergence monitor is not defined for compressed values"
         for b in range(B):
             if hit[b] and (int(tick) + b) % int(reval_every) == 0:
                 vslot = int(bank.act_slot[idx[b]])

@@ -341,6 +341,42 @@ def test_divergence_monitor_recomputes_sampled_hits_and_refreshes_drifted_entrie
     assert r.revalidated == list(range(cfg.B)) and r.slots == [] and int(bank.valid.sum()) == n_valid
 
 
+def test_compressed_values_are_projections_on_the_basis():
+    g = rng(21)
+    S, d, r = 5, 16, 4
+    U, _ = np.linalg.qr(g.standard_normal((d, r)))
+    U = U.T                                              # [r, d], orthonormal rows
+    bank = O.Bank(3, 2, S, d, "f32", basis=U)
+    assert bank.act.shape == (3, S, r)
+    inside = g.standard_normal((S, r)) @ U               # lies in the span: reconstructed exactly (to fp32 storage)
+    outside = g.standard_normal((S, d))
+    q = np.ones((2, 2), np.float32)
+    bank.insert(q, O.inv_norm(q), np.stack([inside, outside]), tick=1)
+    np.testing.assert_allclose(bank.value(0), inside, atol=1e-6)
+    # the reconstruction of a general output is its orthogonal projection: explicit loops
+    want = np.zeros((S, d))
+    for t in range(S):
+        for i in range(r):
+            c = sum(outside[t, j] * U[i, j] for j in range(d))
+            for j in range(d):
+                want[t, j] += c * U[i, j]
+    np.testing.assert_allclose(bank.value(1), want, atol=1e-6)
+    resid = outside - bank.value(1)
+    assert np.abs(resid @ U.T).max() < 1e-6               # what is lost is orthogonal to the basis
+    # a full-rank basis loses nothing; a hit of the gated layer returns the reconstruction
+    full = O.Bank(2, 2, S, d, "f32", basis=np.eye(d))
+    full.insert(q[:1], O.inv_norm(q[:1]), outside[None], tick=1)
+    np.testing.assert_allclose(full.value(0), outside, atol=1e-6)
+    cfg, ws, tok, pos, Ps, src, h_src = tiny_setup()
+    Ub, _ = np.linalg.qr(rng(22).standard_normal((cfg.d, 8)))
+    cb = O.Bank(cfg.n_bank, cfg.k, cfg.S, cfg.d, "f32", basis=Ub.T)
+    r1 = O.gated_layer(h_src[:cfg.B], cb, Ps[0], None, ws[0], cfg.arch, cfg.n_heads, cfg.ln_eps, cfg.gelu, 2.0,
+                       flags=O.FLAG_INSERT_ON_MISS, tick=1)
+    r2 = O.gated_layer(h_src[:cfg.B], cb, Ps[0], None, ws[0], cfg.arch, cfg.n_heads, cfg.ln_eps, cfg.gelu, 0.95)
+    assert r2.hit.all()
+    np.testing.assert_allclose(r2.h_out, (r1.h_out @ Ub) @ Ub.T, atol=1e-5)
+
+
 def test_single_fingerprint_mode_reuses_layer_one_key():
     cfg, ws, tok, pos, Ps, src, h_src = tiny_setup()
     banks = [O.Bank(cfg.n_bank, cfg.k, cfg.S, cfg.d, "f32") for _ in range(2)]
