@@ -126,6 +126,15 @@ typedef struct {
   int32_t half_life; /* LLMC_EVICT_DECAYED_HITS: ticks per halving of the hit counts, 0 = never; else ignored */
   int32_t reval_every; /* LLMC_REVALIDATE: sampling period r of the divergence monitor, 0 = off */
   float drift_bound;   /* LLMC_REVALIDATE: divergence above which a cached value is replaced */
+  /* Compressed cached values (Section III-B: "optionally compresses cached representations via PCA").
+   * rank = 0: d_act holds the outputs themselves, [n_act_slots, S, d].
+   * rank = r > 0: d_basis [r, d] (element type `dtype`, d contiguous, rows = the directions kept) is given, d_act
+   * is [n_act_slots, S, r] and holds the coefficients C = h U^T of each cached output, rounded to `dtype`; a hit
+   * returns the reconstruction C U (rounded to `dtype`).  Both products run on the layer's GEMM kernels.
+   * r % 64 == 0, r <= d; the policy must not be NONE; the divergence monitor is refused.  The basis is read at
+   * llmc_bank_create (the library keeps a transposed copy) and must stay unchanged and alive afterwards. */
+  int32_t rank;
+  const void* d_basis;
 } llmc_bank_desc_t;
 
 /*
@@ -306,7 +315,8 @@ int32_t llmc_max_hamming(float tau, int32_t k);
  * Algorithm 1's reuse step h_l <- h' (Section IV-A, first case): for i < n,
  * copy the cached output of slot d_idx[d_rows[i]] into d_h_out[d_rows[i]].
  *   d_rows [n_max] row numbers, d_n device count (NULL: n = n_max), d_idx [B] slots
- * Exact copy.  d_h_out is [B, S, d] with the bank's S, d and element type.
+ * Exact copy (a bank with compressed values writes the reconstruction C U instead, see llmc_bank_desc_t).
+ * d_h_out is [B, S, d] with the bank's S, d and element type.
  */
 llmc_status_t llmc_gather_hits(const llmc_bank_t* bank, const int32_t* d_idx, const int32_t* d_rows,
                                const int32_t* d_n, int32_t n_max, void* d_h_out, llmc_stream_t stream);

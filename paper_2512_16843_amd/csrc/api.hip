@@ -107,24 +107,44 @@ llmc_status_t llmc_bank_create(const llmc_bank_desc_t* desc, llmc_bank_t** out) 
   REQUIRE(desc->d_fp && desc->d_act && desc->d_inv_norm && desc->d_last_used && desc->d_hits && desc->d_valid,
           LLMC_ERR_INVALID_ARG, "a bank array pointer is NULL");
   REQUIRE(aligned16(desc->d_fp) && aligned16(desc->d_act), LLMC_ERR_SHAPE, "bank arrays must be 16-byte aligned");
+  REQUIRE(desc->rank >= 0, LLMC_ERR_SHAPE, "rank must not be negative");
+  if (desc->rank > 0) {
+    REQUIRE(desc->rank % 64 == 0 && desc->rank <= desc->d, LLMC_ERR_SHAPE,
+            "rank=%d must be a multiple of 64, at most d", desc->rank);
+    REQUIRE(desc->d_basis && aligned16(desc->d_basis), LLMC_ERR_INVALID_ARG, "d_basis is NULL or misaligned");
+    REQUIRE(desc->policy != LLMC_EVICT_NONE, LLMC_ERR_INVALID_ARG, "compressed values need a replacing policy");
+  }
   llmc_bank* b = new (std::nothrow) llmc_bank();
   REQUIRE(b, LLMC_ERR_INVALID_ARG, "out of host memory");
   b->desc = *desc;
   b->d_binv_eff = nullptr;
   b->epoch = 0;
   hipError_t e = hipGetDevice(&b->device);
+  b->d_basis_t = nullptr;
+  b->d_hit_slots = nullptr;
   if (e == hipSuccess) e = hipMalloc((void**)&b->d_binv_eff, align_up((size_t)desc->n_slots, 256) * sizeof(float));
+  if (e == hipSuccess && desc->rank > 0) {
+    e = hipMalloc(&b->d_basis_t, (size_t)desc->rank * desc->d * elem_size(desc->dtype));
+    if (e == hipSuccess) e = hipMalloc((void**)&b->d_hit_slots, 65536 * sizeof(int32_t));
+  }
   if (e != hipSuccess) {
+    (void)hipFree(b->d_binv_eff);
+    (void)hipFree(b->d_basis_t);
+    (void)hipFree(b->d_hit_slots);
     delete b;
     return hip_error(e, "llmc_bank_create: hipMalloc");
   }
   llmc_status_t st = launch_bank_refresh(b, nullptr);
+  if (st == LLMC_OK && desc->rank > 0)
+    st = launch_transpose(desc->d_basis, b->d_basis_t, desc->rank, desc->d, (int)elem_size(desc->dtype), nullptr);
   if (st == LLMC_OK) {
     e = hipStreamSynchronize(nullptr);
     if (e != hipSuccess) st = hip_error(e, "llmc_bank_create: sync");
   }
   if (st != LLMC_OK) {
     (void)hipFree(b->d_binv_eff);
+    (void)hipFree(b->d_basis_t);
+    (void)hipFree(b->d_hit_slots);
     delete b;
     return st;
   }
@@ -136,6 +156,8 @@ llmc_status_t llmc_bank_destroy(llmc_bank_t* bank) {
   if (!bank) return LLMC_OK;
   hipError_t e = hipDeviceSynchronize();
   hipError_t e2 = hipFree(bank->d_binv_eff);
+  (void)hipFree(bank->d_basis_t);
+  (void)hipFree(bank->d_hit_slots);
   delete bank;
   if (e != hipSuccess) return hip_error(e, "llmc_bank_destroy: sync");
   if (e2 != hipSuccess) return hip_error(e2, "llmc_bank_destroy: hipFree");
@@ -159,6 +181,8 @@ llmc_status_t llmc_bank_insert(llmc_bank_t* bank, const void* d_fp, const float*
   REQUIRE(bank->desc.n_act_slots == bank->desc.n_slots, LLMC_ERR_SHAPE,
           "insertion into a bank whose keys share value rows is refused");
   REQUIRE(aligned16(d_fp) && aligned16(d_act), LLMC_ERR_SHAPE, "arrays must be 16-byte aligned");
+  REQUIRE(bank->desc.rank == 0 || m_max <= bank->desc.n_slots, LLMC_ERR_SHAPE,
+          "a bank with compressed values places at most n_slots rows per call");
   return launch_bank_insert(bank, d_fp, d_inv_norm, d_act, d_rows, d_m, m_max, tick, d_slots_out, d_counters,
                             (hipStream_t)stream);
 }
@@ -370,6 +394,10 @@ llmc_status_t llmc_layer_forward_gated(const llmc_layer_desc_t* layer, llmc_bank
     REQUIRE(D.policy != LLMC_EVICT_DECAYED_HITS || !(flags & (LLMC_INSERT_ON_MISS | LLMC_UPDATE_LRU)) ||
                 tick <= LLMC_MAX_TICK_DECAYED,
             LLMC_ERR_INVALID_ARG, "tick out of range for a bank ranked by decayed hits");
+    REQUIRE(!(flags & LLMC_INSERT_ON_MISS) || D.rank == 0 || B <= D.n_slots, LLMC_ERR_SHAPE,
+            "a bank with compressed values places at most n_slots rows per call");
+    REQUIRE(!(flags & LLMC_REVALIDATE) || D.rank == 0, LLMC_ERR_INVALID_ARG,
+            "the divergence monitor is refused on a bank with compressed values");
     if (flags & LLMC_REVALIDATE) {
       REQUIRE(D.reval_every >= 0 && D.drift_bound == D.drift_bound && D.drift_bound >= 0.f, LLMC_ERR_INVALID_ARG,
               "reval_every and drift_bound must not be negative");

@@ -40,6 +40,20 @@ __device__ __forceinline__ bool sel_key(const uint8_t* valid, const uint64_t* la
   return true;
 }
 
+// basis [r, d] -> transposed copy [d, r] (element size e bytes, 2 or 4)
+__global__ void transpose_kernel(const uint8_t* __restrict__ in, uint8_t* __restrict__ out, int r, int d, int e) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= r * d) return;
+  const int a = i / d, b = i % d;
+  for (int x = 0; x < e; ++x) out[((size_t)b * r + a) * e + x] = in[(size_t)i * e + x];
+}
+
+llmc_status_t launch_transpose(const void* in, void* out, int r, int d, int e, hipStream_t st) {
+  hipLaunchKernelGGL(transpose_kernel, dim3((r * d + 255) / 256), dim3(256), 0, st, (const uint8_t*)in, (uint8_t*)out, r, d, e);
+  LLMC_LAUNCH_CHECK("transpose_kernel");
+  return LLMC_OK;
+}
+
 // hits[j] >>= shift for every slot (free slots too: their counts are reset on insertion)
 __global__ void decay_kernel(uint32_t* __restrict__ hits, int N, int shift) {
   const int j = blockIdx.x * blockDim.x + threadIdx.x;
@@ -296,9 +310,15 @@ llmc_status_t launch_bank_insert(llmc_bank* bank, const void* d_fp, const float*
     launch_select(bank, d_m, m_max, 0, D.policy != LLMC_EVICT_NONE ? 1 : 0, d_slots_out, st); }
   LLMC_LAUNCH_CHECK("select_kernel");
   const size_t e = elem_size(D.dtype);
-  const size_t vec_per_seq = (size_t)D.S * D.d * e / 16, vec_per_key = (size_t)D.k * e / 16;
+  if (D.rank > 0) {
+    // compressed values: C = h U^T straight into the slots' value rows (every listed row has a slot: the policy
+    // replaces, and the call places at most n_slots rows)
+    LLMC_TRY(launch_linear(d_act, D.d, d_rows, D.d_basis, nullptr, D.rank, D.d, D.d_act, D.rank, d_slots_out, D.S, d_m,
+                           m_max, D.dtype, st));
+  }
+  const size_t vec_per_seq = D.rank > 0 ? 0 : (size_t)D.S * D.d * e / 16, vec_per_key = (size_t)D.k * e / 16;
   const size_t per_wg = (size_t)kCopyThreads * kCopyVecPerThread;
-  dim3 grid((unsigned)((vec_per_seq + per_wg - 1) / per_wg), m_max);
+  dim3 grid((unsigned)std::max<size_t>(1, (vec_per_seq + per_wg - 1) / per_wg), m_max);
   { ProfScope ps_("insert_kernel", st); hipLaunchKernelGGL(insert_kernel, grid, dim3(kCopyThreads), 0, st, (const u32x4_t*)d_fp, d_inv, (const u32x4_t*)d_act,
                      d_rows, d_m, m_max, d_slots_out, (u32x4_t*)D.d_fp, D.d_inv_norm, (u32x4_t*)D.d_act, D.d_act_slot,
                      D.d_last_used, D.d_hits, D.d_valid, bank->d_binv_eff, vec_per_key, vec_per_seq, tick, d_counters); }

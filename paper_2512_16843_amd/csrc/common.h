@@ -131,6 +131,9 @@ struct llmc_bank {
   float* d_binv_eff;
   int device;
   int64_t epoch;      // DECAYED_HITS: tick / half_life of the latest update (host side, in call order)
+  // compressed values: library-owned transpose [d, rank] of the basis, and a list of value rows per hit (65536 entries)
+  void* d_basis_t;
+  int32_t* d_hit_slots;
 };
 
 namespace llmc {
@@ -169,6 +172,7 @@ llmc_status_t launch_gather(const llmc_bank* bank, const int32_t* d_idx, const i
 
 // bank.hip
 llmc_status_t launch_bank_refresh(llmc_bank* bank, hipStream_t st);
+llmc_status_t launch_transpose(const void* in, void* out, int r, int d, int e, hipStream_t st);
 // DECAYED_HITS: halve the hit counts once per epoch gone by since the bank's latest update
 llmc_status_t launch_bank_advance(llmc_bank* bank, uint64_t tick, hipStream_t st);
 llmc_status_t launch_bank_insert(llmc_bank* bank, const void* d_fp, const float* d_inv, const void* d_act,
@@ -188,6 +192,10 @@ struct LayerWs {
 size_t layer_ws_bytes(const llmc_layer_desc_t* L, int B, int S);
 // Computes f_l for the sequences listed in d_rows[0 .. *d_count) of d_h_in and writes each
 // result to the same row of d_h_out.  d_count / d_rows live on the device.
+// out[o_rows] = A[a_rows] * W^T (+ bias): the layer's GEMM on plain arguments (W [N, K], K contiguous; sequences of S rows)
+llmc_status_t launch_linear(const void* A, int lda, const int32_t* a_rows, const void* W, const void* bias, int N, int K,
+                            void* out, int ldo, const int32_t* o_rows, int S, const int32_t* count, int max_seqs,
+                            int dtype, hipStream_t st);
 llmc_status_t launch_layer(const llmc_layer_desc_t* L, const void* d_h_in, void* d_h_out, int B, int S,
                            const int32_t* d_rows, const int32_t* d_count, void* ws, hipStream_t st);
 

@@ -217,9 +217,29 @@ llmc_status_t launch_all_miss(int B, int32_t* d_miss_rows, int32_t* d_counters, 
   return LLMC_OK;
 }
 
+// value row of the i-th listed hit: act_slot[idx[rows[i]]]
+__global__ void hit_slots_kernel(const int32_t* __restrict__ idx, const int32_t* __restrict__ rows,
+                                 const int32_t* __restrict__ act_slot, const int32_t* count, int n_max,
+                                 int32_t* __restrict__ out) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  const int n = count ? min(*count, n_max) : n_max;
+  if (i >= n) return;
+  const int j = max(idx[rows ? rows[i] : i], 0);
+  out[i] = act_slot ? act_slot[j] : j;
+}
+
 llmc_status_t launch_gather(const llmc_bank* bank, const int32_t* d_idx, const int32_t* d_rows, const int32_t* d_n,
                             int n_max, void* d_h_out, hipStream_t st) {
   const llmc_bank_desc_t& D = bank->desc;
+  if (D.rank > 0) {
+    // compressed values: h_out[rows[i]] = C[value row] * U, one GEMM with K = rank over the listed hits
+    { ProfScope ps_("hit_slots_kernel", st);
+      hipLaunchKernelGGL(hit_slots_kernel, dim3((n_max + 255) / 256), dim3(256), 0, st, d_idx, d_rows, D.d_act_slot, d_n,
+                         n_max, bank->d_hit_slots); }
+    LLMC_LAUNCH_CHECK("hit_slots_kernel");
+    return launch_linear(D.d_act, D.rank, bank->d_hit_slots, bank->d_basis_t, nullptr, D.d, D.rank, d_h_out, D.d, d_rows,
+                         D.S, d_n, n_max, D.dtype, st);
+  }
   const size_t vec_per_seq = (size_t)D.S * D.d * elem_size(D.dtype) / 16;
   const size_t per_wg = (size_t)kGatherThreads * kGatherVecPerThread;
   dim3 grid((unsigned)((vec_per_seq + per_wg - 1) / per_wg), n_max);

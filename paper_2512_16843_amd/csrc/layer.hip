@@ -347,6 +347,16 @@ static llmc_status_t layer_t(const llmc_layer_desc_t* L, const void* h_in, void*
   return LLMC_OK;
 }
 
+llmc_status_t launch_linear(const void* A, int lda, const int32_t* a_rows, const void* W, const void* bias, int N, int K,
+                            void* out, int ldo, const int32_t* o_rows, int S, const int32_t* count, int max_seqs,
+                            int dtype, hipStream_t st) {
+  GemmArgs a{};
+  a.A = A; a.lda = lda; a.a_rows = a_rows; a.W = W; a.bias = bias; a.N = N; a.K = K; a.act = 0;
+  a.resid = nullptr; a.ldr = N; a.r_rows = nullptr; a.out = out; a.ldo = ldo; a.o_rows = o_rows;
+  a.S = S; a.count = count; a.max_seqs = max_seqs;
+  return launch_gemm(a, dtype, st);
+}
+
 llmc_status_t launch_layer(const llmc_layer_desc_t* L, const void* d_h_in, void* d_h_out, int B, int S,
                            const int32_t* d_rows, const int32_t* d_count, void* ws, hipStream_t st) {
   if (L->dtype == LLMC_F32) return layer_t<float>(L, d_h_in, d_h_out, B, S, d_rows, d_count, ws, st);

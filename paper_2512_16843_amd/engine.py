@@ -18,7 +18,7 @@ class GatedStack:
     def __init__(self, cfg: ModelConfig, weights, projections, device="cuda", cached_layers=None,
                  biases: Optional[List[Optional[torch.Tensor]]] = None, n_bank: Optional[int] = None,
                  policy: int = llmc.EVICT_LRU, B: Optional[int] = None, half_life: int = 0, reval_every: int = 0,
-                 drift_bound: float = 0.0):
+                 drift_bound: float = 0.0, bases: Optional[List[Optional[torch.Tensor]]] = None):
         self.cfg = cfg
         self.device = device
         self.B = cfg.B if B is None else B
@@ -30,7 +30,9 @@ class GatedStack:
         self.banks: List[Optional[llmc.Bank]] = [None] * cfg.n_layers
         for l in cached:
             self.banks[l] = llmc.Bank(n_bank, cfg.k, cfg.S, cfg.d, cfg.torch_dtype, device, policy=policy,
-                                      half_life=half_life, reval_every=reval_every, drift_bound=drift_bound)
+                                      half_life=half_life, reval_every=reval_every, drift_bound=drift_bound,
+                                      basis=None if bases is None or bases[l] is None else
+                                      bases[l].to(device).contiguous())
         ws_bytes = llmc.llmc_layer_workspace_bytes(self.layers[0], self.B, cfg.S, cfg.k)
         self.workspace = torch.empty((ws_bytes,), dtype=torch.uint8, device=device)
         self.buf = [torch.empty((self.B, cfg.S, cfg.d), dtype=cfg.torch_dtype, device=device) for _ in range(2)]

@@ -41,7 +41,7 @@ class BankDesc(C.Structure):
                 ("d_fp", C.c_void_p), ("d_act", C.c_void_p), ("d_inv_norm", C.c_void_p),
                 ("d_act_slot", C.c_void_p), ("d_last_used", C.c_void_p), ("d_hits", C.c_void_p),
                 ("d_valid", C.c_void_p), ("half_life", C.c_int32), ("reval_every", C.c_int32),
-                ("drift_bound", C.c_float)]
+                ("drift_bound", C.c_float), ("rank", C.c_int32), ("d_basis", C.c_void_p)]
 
 
 class LayerDesc(C.Structure):
@@ -152,13 +152,15 @@ class Bank:
     def __init__(self, n_slots: int, k: int, S: int, d: int, dtype: torch.dtype, device="cuda",
                  n_act_slots: Optional[int] = None, policy: int = EVICT_LRU,
                  act_slot: Optional[torch.Tensor] = None, half_life: int = 0, reval_every: int = 0,
-                 drift_bound: float = 0.0):
+                 drift_bound: float = 0.0, basis: Optional[torch.Tensor] = None):
         A = n_slots if n_act_slots is None else n_act_slots
         self.n_slots, self.k, self.S, self.d, self.n_act_slots = n_slots, k, S, d, A
         self.dtype = dtype
         self.fp = torch.zeros((n_slots, k), dtype=dtype, device=device)
         self.inv_norm = torch.zeros((n_slots,), dtype=torch.float32, device=device)
-        self.act = torch.zeros((A, S, d), dtype=dtype, device=device)
+        self.basis = basis          # [rank, d]: cached values are stored as coefficients on it
+        self.rank = 0 if basis is None else int(basis.shape[0])
+        self.act = torch.zeros((A, S, d if basis is None else self.rank), dtype=dtype, device=device)
         self.act_slot = act_slot
         self.last_used = torch.zeros((n_slots,), dtype=torch.int64, device=device)   # uint64 bit pattern
         self.hits = torch.zeros((n_slots,), dtype=torch.int32, device=device)        # uint32 bit pattern
@@ -173,7 +175,7 @@ class Bank:
         return BankDesc(self.n_slots, self.k, self.S, self.d, self.n_act_slots, dtype_code(self.dtype), self.policy,
                         _ptr(self.fp), _ptr(self.act), _ptr(self.inv_norm), _ptr(self.act_slot),
                         _ptr(self.last_used), _ptr(self.hits), _ptr(self.valid), self.half_life, self.reval_every,
-                        self.drift_bound)
+                        self.drift_bound, self.rank, _ptr(self.basis))
 
     def create(self) -> None:
         torch.cuda.synchronize()

@@ -828,6 +828,74 @@ def res_rows(st, L):
     return int(c[L.CNT_REVALIDATED])
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_compressed_values_against_oracle(L, dtype):
+    """Banks that store coefficients on a basis: what insertion stores (C = h U^T) and what a hit returns (C U),
+    both against the oracle, through the gated layer and through llmc_gather_hits."""
+    from paper_2512_16843_amd.engine import GatedStack
+    say(f"compressed cached values {dtype}: rank 64 basis, build by insertion, hits return reconstructions")
+    cfg = W.scaled(W.TINY_ENCODER, n_layers=2, B=8, n_bank=24) if dtype == "f32" else \
+        W.scaled(W.BERT_BASE, n_layers=2, B=8, S=40, n_bank=24)
+    tol, r = TOL[dtype], 64
+    g = np.random.Generator(np.random.PCG64(51))
+    ws = W.make_layer_weights(cfg, seed=0)
+    tok, pos = W.make_embeddings(cfg, seed=0)
+    Ps = W.make_projection(cfg.d, cfg.k, cfg.torch_dtype, seed=3, n_layers=cfg.n_layers)
+    bases = []
+    for l in range(cfg.n_layers):
+        Q, _ = np.linalg.qr(g.standard_normal((cfg.d, r)))
+        bases.append(torch.from_numpy(Q.T.astype(np.float32)).to(cfg.torch_dtype).contiguous())
+    st = GatedStack(cfg, ws, Ps, bases=bases)
+    obanks = [O.Bank(cfg.n_bank, cfg.k, cfg.S, cfg.d, dtype, basis=npf(bases[l])) for l in range(cfg.n_layers)]
+    wnp = [{k_: npf(v) for k_, v in w.items()} for w in ws]
+    Pnp = [npf(p) for p in Ps]
+    src = W.make_sources(cfg, 16, seed=1)
+    for tick, s0 in ((1, 0), (2, 8)):
+        h0 = W.embed(torch.from_numpy(src[s0:s0 + 8]), tok, pos, cfg.torch_dtype).cuda()
+        outs = st.forward(h0, tau=2.0, flags=L.INSERT_ON_MISS, tick=tick, keep_all=True)
+        torch.cuda.synchronize()
+        for l in range(cfg.n_layers):
+            h_prev = h0 if l == 0 else outs[l - 1]
+            rr = O.gated_layer(npf(h_prev), obanks[l], Pnp[l], None, wnp[l], cfg.arch, cfg.n_heads, cfg.ln_eps, cfg.gelu,
+                               2.0, flags=O.FLAG_INSERT_ON_MISS, tick=tick, out_dtype=dtype)
+            assert st.gate[l].slots.cpu().tolist() == rr.slots
+            # stored coefficients of the rows just inserted, teacher-forced: the oracle encodes the GPU's own outputs
+            want = obanks[l].encode(npf(outs[l]))
+            got = npf(st.banks[l].act)[rr.slots]
+            assert rel_err_rows(got, want).max() < tol, (l, rel_err_rows(got, want).max())
+            obanks[l].act[rr.slots] = got                 # continue from the GPU's stored coefficients
+    assert st.banks[0].act.shape == (cfg.n_bank, cfg.S, r)
+    # resubmitted sources plus fresh rows: hits return C U
+    ids = np.concatenate([src[[0, 5, 9, 15]], W.make_sources(cfg, 4, seed=9)], axis=0)
+    h0 = W.embed(torch.from_numpy(ids), tok, pos, cfg.torch_dtype).cuda()
+    outs = st.forward(h0, tau=0.9, keep_all=True)
+    torch.cuda.synchronize()
+    for l in range(cfg.n_layers):
+        h_prev = h0 if l == 0 else outs[l - 1]
+        rr = O.gated_layer(npf(h_prev), obanks[l], Pnp[l], None, wnp[l], cfg.arch, cfg.n_heads, cfg.ln_eps, cfg.gelu,
+                           f32(0.9))
+        hit = st.gate[l].hit.cpu().numpy().astype(bool)
+        assert not (np.abs(rr.sim - f32(0.9)) < 1e-3).any()
+        assert np.array_equal(hit, rr.hit) and np.array_equal(st.gate[l].idx.cpu().numpy()[hit], rr.idx[hit])
+        assert hit.sum() >= 4 if l == 0 else True
+        err = rel_err_rows(npf(outs[l]), rr.h_out)
+        assert err.max() < tol, (l, err)
+        say(f"  layer {l}: {int(hit.sum())} hits, max rel err of reconstructed / computed rows {err.max():.2e}")
+    # the gather entry point alone, rows listed out of order, with a device count
+    bank, ob = st.banks[0], obanks[0]
+    idx = torch.tensor([3, 0, 7, 11, 2, 5, 1, 9], dtype=torch.int32, device="cuda")
+    rows = torch.tensor([6, 1, 4, 0, 7], dtype=torch.int32, device="cuda")
+    n = torch.tensor([3], dtype=torch.int32, device="cuda")
+    out = torch.zeros((8, cfg.S, cfg.d), dtype=cfg.torch_dtype, device="cuda")
+    L.llmc_gather_hits(bank, idx, rows, n, 5, out)
+    torch.cuda.synchronize()
+    for b in (6, 1, 4):
+        want = ob.value(int(idx[b]))
+        assert rel_err_rows(npf(out[b:b + 1]), want[None])[0] < tol
+    assert torch.all(out[[0, 2, 3, 5, 7]] == 0)
+    st.close()
+
+
 def test_insert_without_eviction_drops_and_counts(L):
     say("insert into a full bank with policy NONE")
     g = np.random.Generator(np.random.PCG64(13))
