@@ -36,8 +36,8 @@ DIAL_TAU = 0.9999
 # script's 256 MiB device-to-device copy (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0): see profiles/.
 # Set an entry to None when its kernel changes.
 MEASURED_TRAFFIC_BYTES = {
-    "gather_kernel": (18344.7 * 2.0 + 36898.0) * 1024,    # algorithmic: 2 x 37,748,736
-    "pool_kernel": (18476.3 * 2.0 + 2304.0) * 1024,       # algorithmic: 37,748,736 read
+    "gather_kernel": (18347.1 * 2.0 + 36909.5) * 1024,    # algorithmic: 2 x 37,748,736
+    "pool_kernel": (18476.7 * 2.0 + 2304.0) * 1024,       # algorithmic: 37,748,736 read (all 64 rows pooled)
 }
 
 
@@ -45,8 +45,9 @@ def log(msg):
     print("[bench] " + msg, file=sys.stderr, flush=True)
 
 
-def kernel_work(cfg, name, miss, hit, e=2):
-    """Algorithmic flops and bytes of ALL launches of `name` in one step, given per-layer miss/hit counts."""
+def kernel_work(cfg, name, miss, hit, e=2, carry=False):
+    """Algorithmic flops and bytes of ALL launches of `name` in one step, given per-layer miss/hit counts.
+    carry: rows reused at layer l - 1 bring their token mean along and are not pooled at layer l."""
     d, dff, S, B, N, k = cfg.d, cfg.d_ff, cfg.S, cfg.B, cfg.n_bank, cfg.k
     L = len(miss)
     tok = [m * S for m in miss]
@@ -64,7 +65,8 @@ def kernel_work(cfg, name, miss, hit, e=2):
     if name == "gather_kernel":
         return 0.0, sum(2.0 * h * S * d * e for h in hit), "hbm"
     if name == "pool_kernel":
-        return L * float(B) * S * d, L * float(B) * S * d * e, "hbm"
+        rows = float(L * B) if not carry else float(B + sum(B - h for h in hit[:-1]))
+        return rows * S * d, rows * S * d * e, "hbm"
     if name == "project_kernel":
         return L * 2.0 * B * d * k, L * (d * k * e + B * k * e), "hbm"
     if name in ("match_bf16_kernel", "match_stream_kernel"):
@@ -87,6 +89,8 @@ def main():
                          "prefix-sharing queries; bert-large-dynamic: 24 layers with insertion and LRU eviction over a "
                          "stream of stem-sharing batches")
     ap.add_argument("--no-dial", action="store_true", help="skip the hit-rate dial leg")
+    ap.add_argument("--no-carry", action="store_true",
+                    help="banks do not keep the token means of cached outputs (every layer pools every row again)")
     ap.add_argument("--bank", type=int, default=None, help="bank entries per layer (default: the config's 16384)")
     ap.add_argument("--layers", type=int, default=None, help="debug: fewer layers")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -121,7 +125,7 @@ def main():
     tok, pos = tok.to(dev), pos.to(dev)
     Ps = W.make_projection(cfg.d, cfg.k, cfg.torch_dtype, seed=3, n_layers=cfg.n_layers)
     src = W.make_sources(cfg, cfg.n_bank, seed=1)
-    st = GatedStack(cfg, ws, Ps)
+    st = GatedStack(cfg, ws, Ps, keep_means=not args.no_carry)
     log("inputs drawn and %d banks allocated in %.1f s" % (cfg.n_layers, time.time() - t0))
 
     # ---- bank build: all-miss forward with insertion over the source sequences -------------------
@@ -223,7 +227,7 @@ def main():
         hit = [int(x) for x in cnt[:, llmc.CNT_HIT]]
         out = {}
         for name, (n, ms) in rep.items():
-            fl, by, bound = kernel_work(cfg, name, miss, hit)
+            fl, by, bound = kernel_work(cfg, name, miss, hit, carry=not args.no_carry)
             t_step = ms * 1e-3 / steps
             out[name] = {"launches_per_step": n // steps, "avg_us": round(ms * 1e3 / n, 3),
                          "ms_per_step": round(ms / steps, 4), "bound": bound,
@@ -502,7 +506,7 @@ def bench_dynamic(args, llmc, W, GatedStack):
     tok, pos = W.make_embeddings(cfg, seed=0)
     tok, pos = tok.to(dev), pos.to(dev)
     Ps = W.make_projection(cfg.d, cfg.k, cfg.torch_dtype, seed=3, n_layers=cfg.n_layers)
-    st = GatedStack(cfg, ws, Ps)
+    st = GatedStack(cfg, ws, Ps, keep_means=not args.no_carry)
     stream = W.StemStream(cfg, group=4, stem_len=80, n_stems=512, seed=4)
     flags = llmc.INSERT_ON_MISS | llmc.UPDATE_LRU
     tick = 0

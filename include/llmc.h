@@ -135,6 +135,12 @@ typedef struct {
    * llmc_bank_create (the library keeps a transposed copy) and must stay unchanged and alive afterwards. */
   int32_t rank;
   const void* d_basis;
+  /* Optional [n_act_slots, d] fp32, caller-owned: the token mean (1/S) sum_t h[t,:] of each cached output, written
+   * by the library whenever it stores an output (same arithmetic and order as the fingerprint's pooling), read by
+   * llmc_layer_forward_gated to hand the next layer its pooled input without reading the output again.  NULL: not
+   * kept.  Refused together with compressed values.  Entries written into d_act by the caller directly have no
+   * mean until llmc_bank_pool_values() is called. */
+  float* d_act_pool;
 } llmc_bank_desc_t;
 
 /*
@@ -166,6 +172,12 @@ typedef struct {
   const void* d_proj;
   const float* d_bias;
   int32_t k;
+  /* Optional carry from the call that produced this layer's input (see llmc_gate_out_t.d_pooled_out): for a
+   * row b with d_pooled_in_valid[b] != 0, d_pooled_in[b] [d] fp32 is taken as the token mean of d_h_in[b] and the
+   * row is not read again.  The carried mean is the one the library itself computes (same arithmetic, same
+   * order), so keys do not depend on whether a mean was carried.  Both NULL: every row is pooled here. */
+  const float* d_pooled_in;
+  const uint8_t* d_pooled_in_valid;
 } llmc_fp_desc_t;
 
 /* Optional per-row results of the gate; any pointer may be NULL. */
@@ -175,6 +187,12 @@ typedef struct {
   uint8_t* d_hit;      /* [B] 1 = reused, 0 = computed */
   int32_t* d_counters; /* [LLMC_CNT_WORDS], overwritten by the call */
   int32_t* d_slots;    /* [B] slots taken by this call's insertions, in ascending miss-row order */
+  /* Reuse fused with the next layer's pooling: the cached output of a hit is the next layer's input, and its
+   * token mean was stored with it (llmc_bank_desc_t.d_act_pool).  With a bank that has d_act_pool, and both
+   * pointers given, the call writes d_pooled_out[b] [d] fp32 = that stored mean and d_pooled_out_valid[b] = 1 for
+   * every row answered from the bank (0 for computed rows, whose mean the next call computes itself). */
+  float* d_pooled_out;          /* [B, d] */
+  uint8_t* d_pooled_out_valid;  /* [B] */
 } llmc_gate_out_t;
 
 /* ---- bank -------------------------------------------------------------- */
@@ -217,6 +235,10 @@ llmc_status_t llmc_bank_insert(llmc_bank_t* bank, const void* d_fp, const float*
                                const void* d_act, const int32_t* d_rows, const int32_t* d_m,
                                int32_t m_max, uint64_t tick, int32_t* d_slots_out,
                                int32_t* d_counters, llmc_stream_t stream);
+
+/* Recompute d_act_pool from d_act for all value rows (after the caller wrote values directly).
+ * INVALID_ARG if the bank keeps no means. */
+llmc_status_t llmc_bank_pool_values(llmc_bank_t* bank, llmc_stream_t stream);
 
 /*
  * Section IV-D, LRU: invalidate the m least recently used valid entries.

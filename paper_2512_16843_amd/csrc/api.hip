@@ -107,6 +107,10 @@ llmc_status_t llmc_bank_create(const llmc_bank_desc_t* desc, llmc_bank_t** out) 
   REQUIRE(desc->d_fp && desc->d_act && desc->d_inv_norm && desc->d_last_used && desc->d_hits && desc->d_valid,
           LLMC_ERR_INVALID_ARG, "a bank array pointer is NULL");
   REQUIRE(aligned16(desc->d_fp) && aligned16(desc->d_act), LLMC_ERR_SHAPE, "bank arrays must be 16-byte aligned");
+  REQUIRE(!(desc->d_act_pool && desc->rank > 0), LLMC_ERR_INVALID_ARG,
+          "stored token means are refused together with compressed values");
+  REQUIRE(!(desc->d_act_pool && desc->d_act_slot), LLMC_ERR_INVALID_ARG,
+          "stored token means need keys that own their value rows");
   REQUIRE(desc->rank >= 0, LLMC_ERR_SHAPE, "rank must not be negative");
   if (desc->rank > 0) {
     REQUIRE(desc->rank % 64 == 0 && desc->rank <= desc->d, LLMC_ERR_SHAPE,
@@ -185,6 +189,19 @@ llmc_status_t llmc_bank_insert(llmc_bank_t* bank, const void* d_fp, const float*
           "a bank with compressed values places at most n_slots rows per call");
   return launch_bank_insert(bank, d_fp, d_inv_norm, d_act, d_rows, d_m, m_max, tick, d_slots_out, d_counters,
                             (hipStream_t)stream);
+}
+
+llmc_status_t llmc_bank_pool_values(llmc_bank_t* bank, llmc_stream_t stream) {
+  REQUIRE(bank, LLMC_ERR_INVALID_ARG, "bank is NULL");
+  const llmc_bank_desc_t& D = bank->desc;
+  REQUIRE(D.d_act_pool, LLMC_ERR_INVALID_ARG, "the bank keeps no token means");
+  for (int s0 = 0; s0 < D.n_act_slots; s0 += 32768) {
+    const int n = std::min(32768, D.n_act_slots - s0);
+    const char* src = (const char*)D.d_act + (size_t)s0 * D.S * D.d * elem_size(D.dtype);
+    LLMC_TRY(launch_pool_rows(src, n, D.S, D.d, D.dtype, nullptr, nullptr, nullptr, D.d_act_pool + (size_t)s0 * D.d,
+                              (hipStream_t)stream));
+  }
+  return LLMC_OK;
 }
 
 llmc_status_t llmc_bank_evict(llmc_bank_t* bank, const int32_t* d_m, int32_t m_max, int32_t* d_victims_out,
@@ -398,6 +415,8 @@ llmc_status_t llmc_layer_forward_gated(const llmc_layer_desc_t* layer, llmc_bank
             "a bank with compressed values places at most n_slots rows per call");
     REQUIRE(!(flags & LLMC_REVALIDATE) || D.rank == 0, LLMC_ERR_INVALID_ARG,
             "the divergence monitor is refused on a bank with compressed values");
+    REQUIRE(!(flags & LLMC_REVALIDATE) || !D.d_act_pool, LLMC_ERR_INVALID_ARG,
+            "the divergence monitor is refused on a bank that keeps token means");
     if (flags & LLMC_REVALIDATE) {
       REQUIRE(D.reval_every >= 0 && D.drift_bound == D.drift_bound && D.drift_bound >= 0.f, LLMC_ERR_INVALID_ARG,
               "reval_every and drift_bound must not be negative");
@@ -441,21 +460,30 @@ llmc_status_t llmc_layer_forward_gated(const llmc_layer_desc_t* layer, llmc_bank
   }
   if (!bank) {
     LLMC_TRY(launch_all_miss(B, miss_rows, counters, out ? out->d_idx : nullptr, out ? out->d_sim : nullptr,
-                             out ? out->d_hit : nullptr, st));
+                             out ? out->d_hit : nullptr, st, out ? out->d_pooled_out_valid : nullptr));
     return launch_layer(layer, d_h_in, d_h_out, B, S, miss_rows, counters + LLMC_CNT_COMPUTED, ws_layer, st);
   }
   if (flags & (LLMC_INSERT_ON_MISS | LLMC_UPDATE_LRU)) LLMC_TRY(launch_bank_advance(bank, tick, st));
   const void* q = d_fp_given;
   const float* qinv = d_inv_norm_given;
   if (!q) {
+    const bool carried = fp->d_pooled_in && fp->d_pooled_in_valid;
     LLMC_TRY(launch_fingerprint(d_h_in, nullptr, B, S, layer->d, layer->dtype, fp->d_proj, fp->d_bias, k, keys, inv,
-                                ws_fp, st));
+                                ws_fp, st, carried ? fp->d_pooled_in : nullptr,
+                                carried ? fp->d_pooled_in_valid : nullptr));
     q = keys;
     qinv = inv;
   }
   LLMC_TRY(launch_match(bank, q, qinv, B, tau, idx, sim, hit, tie, ws_match, st));
-  LLMC_TRY(launch_compact(hit, idx, sim, tie, B, tau, hit_rows, miss_rows, reval_tmp, counters, bank, flags, tick, st));
-  LLMC_TRY(launch_gather(bank, idx, hit_rows, counters + LLMC_CNT_HIT, B, d_h_out, st));
+  float* pooled_out = nullptr;
+  uint8_t* pooled_valid_out = nullptr;
+  if (out && out->d_pooled_out_valid) {
+    pooled_valid_out = out->d_pooled_out_valid;                       // always written: zeros if nothing is carried
+    if (out->d_pooled_out && bank->desc.d_act_pool) pooled_out = out->d_pooled_out;
+  }
+  LLMC_TRY(launch_compact(hit, idx, sim, tie, B, tau, hit_rows, miss_rows, reval_tmp, counters, bank, flags, tick, st,
+                          pooled_valid_out, pooled_out ? 1 : 0));
+  LLMC_TRY(launch_gather(bank, idx, hit_rows, counters + LLMC_CNT_HIT, B, d_h_out, st, pooled_out));
   // the rows to compute: the misses, then (divergence monitor) the sampled hit rows, whose copies are overwritten
   LLMC_TRY(launch_layer(layer, d_h_in, d_h_out, B, S, miss_rows, counters + LLMC_CNT_COMPUTED, ws_layer, st));
   if ((flags & LLMC_REVALIDATE) && bank->desc.reval_every > 0)

@@ -323,6 +323,9 @@ llmc_status_t launch_bank_insert(llmc_bank* bank, const void* d_fp, const float*
                      d_rows, d_m, m_max, d_slots_out, (u32x4_t*)D.d_fp, D.d_inv_norm, (u32x4_t*)D.d_act, D.d_act_slot,
                      D.d_last_used, D.d_hits, D.d_valid, bank->d_binv_eff, vec_per_key, vec_per_seq, tick, d_counters); }
   LLMC_LAUNCH_CHECK("insert_kernel");
+  // the token mean of every stored output, kept beside it (dropped rows have slot -1 and are skipped)
+  if (D.d_act_pool)
+    LLMC_TRY(launch_pool_rows(d_act, m_max, D.S, D.d, D.dtype, d_rows, d_m, d_slots_out, D.d_act_pool, st));
   return LLMC_OK;
 }
 

@@ -142,8 +142,11 @@ namespace llmc {
 // fingerprint.hip
 size_t fingerprint_ws_bytes(int B, int S, int d);
 llmc_status_t launch_fingerprint(const void* d_h, const int32_t* d_rowmap_unused, int B, int S, int d, int dtype,
-                                 const void* d_proj, const float* d_bias, int k, void* d_fp, float* d_inv,
-                                 void* ws, hipStream_t st);
+                                 const void* d_proj, const float* d_bias, int k, void* d_fp, float* d_inv, void* ws,
+                                 hipStream_t st, const float* pooled_in = nullptr,
+                                 const uint8_t* pooled_valid = nullptr);
+llmc_status_t launch_pool_rows(const void* d_h, int n_max, int S, int d, int dtype, const int32_t* d_rows,
+                               const int32_t* d_count, const int32_t* d_dst, float* d_out, hipStream_t st);
 llmc_status_t launch_fingerprint_bits(const void* d_h, int B, int S, int d, int dtype, const void* d_proj,
                                       const float* d_bias, int k, uint32_t* d_bits, void* ws, hipStream_t st);
 size_t match_bits_ws_bytes(int N, int k, int B);
@@ -162,13 +165,15 @@ llmc_status_t launch_match(const llmc_bank* bank, const void* d_fp, const float*
 llmc_status_t launch_compact(const uint8_t* d_hit, const int32_t* d_idx, const float* d_sim,
                              const uint8_t* d_near_tie, int B, float tau, int32_t* d_hit_rows,
                              int32_t* d_miss_rows, int32_t* d_reval_tmp, int32_t* d_counters, llmc_bank* bank,
-                             uint32_t flags, uint64_t tick, hipStream_t st);
+                             uint32_t flags, uint64_t tick, hipStream_t st, uint8_t* d_pooled_valid_out = nullptr,
+                             int has_pool = 0);
 llmc_status_t launch_divergence(llmc_bank* bank, const void* d_h_out, const int32_t* d_idx, const int32_t* d_rows,
                                 int32_t* d_counters, int B, hipStream_t st);
 llmc_status_t launch_all_miss(int B, int32_t* d_miss_rows, int32_t* d_counters, int32_t* d_idx, float* d_sim,
-                              uint8_t* d_hit, hipStream_t st);
+                              uint8_t* d_hit, hipStream_t st, uint8_t* d_pooled_valid_out = nullptr);
 llmc_status_t launch_gather(const llmc_bank* bank, const int32_t* d_idx, const int32_t* d_rows,
-                            const int32_t* d_n, int n_max, void* d_h_out, hipStream_t st);
+                            const int32_t* d_n, int n_max, void* d_h_out, hipStream_t st,
+                            float* d_pooled_out = nullptr);
 
 // bank.hip
 llmc_status_t launch_bank_refresh(llmc_bank* bank, hipStream_t st);

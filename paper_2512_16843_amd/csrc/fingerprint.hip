@@ -17,17 +17,23 @@ constexpr int kTokChunk = 32;   // tokens per pooling workgroup
 
 static inline int pool_chunks(int S) { return (S + kTokChunk - 1) / kTokChunk; }
 
-// grid (chunks, B); block G*R threads, G = d / VEC column groups, R rows in flight
+// grid (chunks, B); block G*R threads, G = d / VEC column groups, R rows in flight.
+// Entry b of the grid pools sequence rows[b] (or b) of h; entries beyond *count (if given) and sequences with
+// skip[sequence] != 0 (their mean is supplied by the caller) leave at once.  Partials are indexed by entry.
 template <typename T>
 __global__ void pool_kernel(const T* __restrict__ h, int S, int d, int G, int R, float* __restrict__ partial,
-                            int n_chunks) {
+                            int n_chunks, const uint8_t* __restrict__ skip, const int32_t* __restrict__ rows,
+                            const int32_t* __restrict__ count) {
   constexpr int VEC = Vec16<T>::N;
   extern __shared__ float red[];  // [R][d]
   const int b = blockIdx.y, chunk = blockIdx.x;
+  if (count && b >= *count) return;
+  const int seq = rows ? rows[b] : b;
+  if (skip && skip[seq]) return;
   const int g = threadIdx.x % G, r = threadIdx.x / G;
   const int t0 = chunk * kTokChunk;
   const int t1 = min(S, t0 + kTokChunk);
-  const T* base = h + ((size_t)b * S) * d + (size_t)g * VEC;
+  const T* base = h + ((size_t)seq * S) * d + (size_t)g * VEC;
   float acc[VEC];
 #pragma unroll
   for (int i = 0; i < VEC; ++i) acc[i] = 0.f;
@@ -69,7 +75,9 @@ template <typename T>
 __global__ __launch_bounds__(1024) void project_kernel(const float* __restrict__ partial, int n_chunks, int S, int d,
                                                        const T* __restrict__ P, const float* __restrict__ bias, int k,
                                                        int parts, T* __restrict__ fp_out, float* __restrict__ inv_out,
-                                                       uint32_t* __restrict__ bits_out) {
+                                                       uint32_t* __restrict__ bits_out,
+                                                       const float* __restrict__ pooled_in,
+                                                       const uint8_t* __restrict__ pooled_valid) {
   extern __shared__ float sm[];   // p[d] | v[parts][k]
   float* p = sm;
   float* vpart = sm + d;
@@ -78,6 +86,9 @@ __global__ __launch_bounds__(1024) void project_kernel(const float* __restrict__
   const int b = blockIdx.x;
   const int nthreads = blockDim.x;
   const float inv_S = 1.0f / (float)S;
+  if (pooled_valid && pooled_valid[b]) {
+    for (int i = threadIdx.x; i < d; i += nthreads) p[i] = pooled_in[(size_t)b * d + i];
+  } else
   for (int i = threadIdx.x; i < d; i += nthreads) {
     const float* src = partial + (size_t)b * n_chunks * d + i;
     float s = 0.f;
@@ -205,20 +216,84 @@ __global__ void inv_norm_kernel(const T* __restrict__ fp, int64_t n, int k, floa
   if (lane == 0) out[row] = s > 0.0 ? (float)(1.0 / sqrt(s)) : 0.f;
 }
 
+// Token mean of whole sequences with the arithmetic of pool_kernel + the projection's chunk sum, in one
+// workgroup per sequence and without a partials buffer: chunk after chunk, each thread sums its tokens of the
+// chunk, the row groups are combined, and the chunk sums are added in ascending order.  Entry b pools sequence
+// rows[b] (or b) into out[dst[b] or b]; entries beyond *count, and negative destinations, are skipped.
+// grid (n_max); block G*R threads; LDS R*d floats.
+template <typename T>
+__global__ void pool_direct_kernel(const T* __restrict__ h, int S, int d, int G, int R, const int32_t* __restrict__ rows,
+                                   const int32_t* __restrict__ count, const int32_t* __restrict__ dst,
+                                   float* __restrict__ out) {
+  constexpr int VEC = Vec16<T>::N;
+  extern __shared__ float red[];  // [R][d]
+  const int b = blockIdx.x;
+  if (count && b >= *count) return;
+  const int o = dst ? dst[b] : b;
+  if (o < 0) return;
+  const int seq = rows ? rows[b] : b;
+  const int g = threadIdx.x % G, r = threadIdx.x / G;
+  const T* base = h + ((size_t)seq * S) * d + (size_t)g * VEC;
+  float total[VEC];
+#pragma unroll
+  for (int i = 0; i < VEC; ++i) total[i] = 0.f;
+  for (int t0 = 0; t0 < S; t0 += kTokChunk) {
+    const int t1 = min(S, t0 + kTokChunk);
+    float acc[VEC];
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) acc[i] = 0.f;
+    int t = t0 + r;
+    constexpr int U = 8;
+    for (; t + (U - 1) * R < t1; t += U * R) {
+      float v[U][VEC];
+#pragma unroll
+      for (int u = 0; u < U; ++u) Vec16<T>::load(base + (size_t)(t + u * R) * d, v[u]);
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) acc[i] += v[u][i];
+    }
+    for (; t < t1; t += R) {
+      float v0[VEC];
+      Vec16<T>::load(base + (size_t)t * d, v0);
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) acc[i] += v0[i];
+    }
+    __syncthreads();                     // the previous chunk's readers are done
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) red[(size_t)r * d + g * VEC + i] = acc[i];
+    __syncthreads();
+    if (r == 0) {
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) {
+        float s = acc[i];
+        for (int rr = 1; rr < R; ++rr) s += red[(size_t)rr * d + g * VEC + i];
+        total[i] += s;
+      }
+    }
+  }
+  if (r == 0) {
+    const float inv_S = 1.0f / (float)S;
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) out[(size_t)o * d + g * VEC + i] = total[i] * inv_S;
+  }
+}
+
 size_t fingerprint_ws_bytes(int B, int S, int d) {
   return align_up((size_t)B * pool_chunks(S) * d * sizeof(float), 256);
 }
 
 template <typename T>
 static llmc_status_t fingerprint_t(const T* h, int B, int S, int d, const T* P, const float* bias, int k,
-                                   T* fp, float* inv, uint32_t* bits, float* partial, hipStream_t st) {
+                                   T* fp, float* inv, uint32_t* bits, float* partial, const float* pooled_in,
+                                   const uint8_t* pooled_valid, hipStream_t st) {
   constexpr int VEC = Vec16<T>::N;
   const int G = d / VEC;
   const int R = G <= 512 ? 2 : 1;   // token rows split over thread groups; depends on d only
   const int n_chunks = pool_chunks(S);
   dim3 grid(n_chunks, B);
   { ProfScope ps_("pool_kernel", st); hipLaunchKernelGGL(pool_kernel<T>, grid, dim3(G * R), (size_t)R * d * sizeof(float), st, h, S, d, G, R, partial,
-                     n_chunks); }
+                     n_chunks, pooled_valid, (const int32_t*)nullptr, (const int32_t*)nullptr); }
   LLMC_LAUNCH_CHECK("pool_kernel");
   // slices of d per output column group; depends on k only.  k <= 1024 gives at least k threads.
   const int cgs = k / 4;
@@ -226,19 +301,41 @@ static llmc_status_t fingerprint_t(const T* h, int B, int S, int d, const T* P, 
   {
     ProfScope ps_("project_kernel", st);
     hipLaunchKernelGGL(project_kernel<T>, dim3(B), dim3(std::max(cgs * parts, k)),
-                       (size_t)(d + parts * k) * sizeof(float), st, partial, n_chunks, S, d, P, bias, k, parts, fp, inv, bits);
+                       (size_t)(d + parts * k) * sizeof(float), st, partial, n_chunks, S, d, P, bias, k, parts, fp, inv, bits, pooled_in, pooled_valid);
   }
   LLMC_LAUNCH_CHECK("project_kernel");
   return LLMC_OK;
 }
 
 llmc_status_t launch_fingerprint(const void* d_h, const int32_t*, int B, int S, int d, int dtype, const void* d_proj,
-                                 const float* d_bias, int k, void* d_fp, float* d_inv, void* ws, hipStream_t st) {
+                                 const float* d_bias, int k, void* d_fp, float* d_inv, void* ws, hipStream_t st,
+                                 const float* pooled_in, const uint8_t* pooled_valid) {
   if (dtype == LLMC_F32)
     return fingerprint_t<float>((const float*)d_h, B, S, d, (const float*)d_proj, d_bias, k, (float*)d_fp, d_inv,
-                                nullptr, (float*)ws, st);
+                                nullptr, (float*)ws, pooled_in, pooled_valid, st);
   return fingerprint_t<bf16_t>((const bf16_t*)d_h, B, S, d, (const bf16_t*)d_proj, d_bias, k, (bf16_t*)d_fp, d_inv,
-                               nullptr, (float*)ws, st);
+                               nullptr, (float*)ws, pooled_in, pooled_valid, st);
+}
+
+// token means of the sequences rows[0 .. *count) (or 0 .. n_max) of h, written to out[dst[i] or i] [d] fp32
+template <typename T>
+static llmc_status_t pool_rows_t(const T* h, int n_max, int S, int d, const int32_t* rows, const int32_t* count,
+                                 const int32_t* dst, float* out, hipStream_t st) {
+  constexpr int VEC = Vec16<T>::N;
+  const int G = d / VEC;
+  const int R = G <= 512 ? 2 : 1;
+  { ProfScope ps_("pool_direct_kernel", st);
+    hipLaunchKernelGGL(pool_direct_kernel<T>, dim3(n_max), dim3(G * R), (size_t)R * d * sizeof(float), st, h, S, d, G, R,
+                       rows, count, dst, out); }
+  LLMC_LAUNCH_CHECK("pool_direct_kernel");
+  return LLMC_OK;
+}
+
+llmc_status_t launch_pool_rows(const void* d_h, int n_max, int S, int d, int dtype, const int32_t* d_rows,
+                               const int32_t* d_count, const int32_t* d_dst, float* d_out, hipStream_t st) {
+  if (dtype == LLMC_F32)
+    return pool_rows_t<float>((const float*)d_h, n_max, S, d, d_rows, d_count, d_dst, d_out, st);
+  return pool_rows_t<bf16_t>((const bf16_t*)d_h, n_max, S, d, d_rows, d_count, d_dst, d_out, st);
 }
 
 // same pooling and projection, but the key is the sign of each projection
@@ -246,9 +343,9 @@ llmc_status_t launch_fingerprint_bits(const void* d_h, int B, int S, int d, int 
                                       const float* d_bias, int k, uint32_t* d_bits, void* ws, hipStream_t st) {
   if (dtype == LLMC_F32)
     return fingerprint_t<float>((const float*)d_h, B, S, d, (const float*)d_proj, d_bias, k, nullptr, nullptr, d_bits,
-                                (float*)ws, st);
+                                (float*)ws, nullptr, nullptr, st);
   return fingerprint_t<bf16_t>((const bf16_t*)d_h, B, S, d, (const bf16_t*)d_proj, d_bias, k, nullptr, nullptr, d_bits,
-                               (float*)ws, st);
+                               (float*)ws, nullptr, nullptr, st);
 }
 
 llmc_status_t launch_inv_norm(const void* d_fp, int64_t n, int k, int dtype, float* d_out, hipStream_t st) {

@@ -17,7 +17,8 @@ __global__ __launch_bounds__(1024) void compact_kernel(const uint8_t* __restrict
                                                        int B, float tau, int32_t* __restrict__ hit_rows,
                                                        int32_t* __restrict__ miss_rows, int32_t* __restrict__ counters,
                                                        uint64_t* last_used, uint32_t* hits, int touch, uint64_t tick,
-                                                       int reval_every, int32_t* __restrict__ reval_tmp) {
+                                                       int reval_every, int32_t* __restrict__ reval_tmp,
+                                                       uint8_t* __restrict__ pooled_valid_out, int has_pool) {
   __shared__ int wave_hits[16], wave_reval[16];
   __shared__ int base_hit, base_miss, base_reval, s_near_tau, s_near_tie;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -42,6 +43,8 @@ __global__ __launch_bounds__(1024) void compact_kernel(const uint8_t* __restrict
     const int n_in = min(1024, B - c0);
     if (in) {
       const int hrank = wbase + before;
+      // a row answered from the bank carries its stored token mean to the next layer; computed rows do not
+      if (pooled_valid_out) pooled_valid_out[b] = (has_pool && h && !rv) ? 1 : 0;
       if (h) {
         hit_rows[base_hit + hrank] = b;
         if (rv) reval_tmp[base_reval + wbase_rv + before_rv] = b;
@@ -137,10 +140,12 @@ __global__ __launch_bounds__(1024) void divergence_kernel(const T* __restrict__ 
 }
 
 // uncached layer: every row is a miss
-__global__ void all_miss_kernel(int B, int32_t* miss_rows, int32_t* counters, int32_t* idx, float* sim, uint8_t* hit) {
+__global__ void all_miss_kernel(int B, int32_t* miss_rows, int32_t* counters, int32_t* idx, float* sim, uint8_t* hit,
+                                uint8_t* pooled_valid_out) {
   const int b = blockIdx.x * blockDim.x + threadIdx.x;
   if (b < B) {
     miss_rows[b] = b;
+    if (pooled_valid_out) pooled_valid_out[b] = 0;
     if (idx) idx[b] = -1;
     if (sim) sim[b] = -INFINITY;
     if (hit) hit[b] = 0;
@@ -157,7 +162,9 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(const u32x4_t* _
                                                                 const int32_t* __restrict__ idx,
                                                                 const int32_t* __restrict__ rows,
                                                                 const int32_t* __restrict__ count, int n_max,
-                                                                size_t vec_per_seq, u32x4_t* __restrict__ out) {
+                                                                size_t vec_per_seq, u32x4_t* __restrict__ out,
+                                                                const float* __restrict__ act_pool,
+                                                                float* __restrict__ pooled_out, int d) {
   const int n = count ? min(*count, n_max) : n_max;
   const int i = blockIdx.y;
   if (i >= n) return;
@@ -165,6 +172,8 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(const u32x4_t* _
   const int j = idx[b];
   if (j < 0) return;
   const int slot = act_slot ? act_slot[j] : j;
+  if (pooled_out && blockIdx.x == 0)       // the stored token mean of the cached output rides along
+    for (int c = threadIdx.x; c < d; c += kGatherThreads) pooled_out[(size_t)b * d + c] = act_pool[(size_t)slot * d + c];
   const u32x4_t* src = act + (size_t)slot * vec_per_seq;
   u32x4_t* dst = out + (size_t)b * vec_per_seq;
   const size_t v0 = (size_t)blockIdx.x * (kGatherThreads * kGatherVecPerThread) + threadIdx.x;
@@ -183,12 +192,13 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(const u32x4_t* _
 
 llmc_status_t launch_compact(const uint8_t* d_hit, const int32_t* d_idx, const float* d_sim, const uint8_t* d_near_tie,
                              int B, float tau, int32_t* d_hit_rows, int32_t* d_miss_rows, int32_t* d_reval_tmp,
-                             int32_t* d_counters, llmc_bank* bank, uint32_t flags, uint64_t tick, hipStream_t st) {
+                             int32_t* d_counters, llmc_bank* bank, uint32_t flags, uint64_t tick, hipStream_t st,
+                             uint8_t* d_pooled_valid_out, int has_pool) {
   const int touch = (flags & LLMC_UPDATE_LRU) ? 1 : 0;
   const int reval_every = (flags & LLMC_REVALIDATE) ? bank->desc.reval_every : 0;
   { ProfScope ps_("compact_kernel", st); hipLaunchKernelGGL(compact_kernel, dim3(1), dim3(1024), 0, st, d_hit, d_idx, d_sim, d_near_tie, B, tau, d_hit_rows,
                      d_miss_rows, d_counters, bank->desc.d_last_used, bank->desc.d_hits, touch, tick, reval_every,
-                     d_reval_tmp); }
+                     d_reval_tmp, d_pooled_valid_out, has_pool); }
   LLMC_LAUNCH_CHECK("compact_kernel");
   return LLMC_OK;
 }
@@ -209,10 +219,10 @@ llmc_status_t launch_divergence(llmc_bank* bank, const void* d_h_out, const int3
 }
 
 llmc_status_t launch_all_miss(int B, int32_t* d_miss_rows, int32_t* d_counters, int32_t* d_idx, float* d_sim,
-                              uint8_t* d_hit, hipStream_t st) {
+                              uint8_t* d_hit, hipStream_t st, uint8_t* d_pooled_valid_out) {
   const int n = B > LLMC_CNT_WORDS ? B : LLMC_CNT_WORDS;
   { ProfScope ps_("all_miss_kernel", st); hipLaunchKernelGGL(all_miss_kernel, dim3((n + 255) / 256), dim3(256), 0, st, B, d_miss_rows, d_counters, d_idx, d_sim,
-                     d_hit); }
+                     d_hit, d_pooled_valid_out); }
   LLMC_LAUNCH_CHECK("all_miss_kernel");
   return LLMC_OK;
 }
@@ -229,7 +239,7 @@ __global__ void hit_slots_kernel(const int32_t* __restrict__ idx, const int32_t*
 }
 
 llmc_status_t launch_gather(const llmc_bank* bank, const int32_t* d_idx, const int32_t* d_rows, const int32_t* d_n,
-                            int n_max, void* d_h_out, hipStream_t st) {
+                            int n_max, void* d_h_out, hipStream_t st, float* d_pooled_out) {
   const llmc_bank_desc_t& D = bank->desc;
   if (D.rank > 0) {
     // compressed values: h_out[rows[i]] = C[value row] * U, one GEMM with K = rank over the listed hits
@@ -244,7 +254,8 @@ llmc_status_t launch_gather(const llmc_bank* bank, const int32_t* d_idx, const i
   const size_t per_wg = (size_t)kGatherThreads * kGatherVecPerThread;
   dim3 grid((unsigned)((vec_per_seq + per_wg - 1) / per_wg), n_max);
   { ProfScope ps_("gather_kernel", st); hipLaunchKernelGGL(gather_kernel, grid, dim3(kGatherThreads), 0, st, (const u32x4_t*)D.d_act, D.d_act_slot, d_idx,
-                     d_rows, d_n, n_max, vec_per_seq, (u32x4_t*)d_h_out); }
+                     d_rows, d_n, n_max, vec_per_seq, (u32x4_t*)d_h_out, D.d_act_pool,
+                     D.d_act_pool ? d_pooled_out : nullptr, D.d); }
   LLMC_LAUNCH_CHECK("gather_kernel");
   return LLMC_OK;
 }

@@ -18,7 +18,8 @@ class GatedStack:
     def __init__(self, cfg: ModelConfig, weights, projections, device="cuda", cached_layers=None,
                  biases: Optional[List[Optional[torch.Tensor]]] = None, n_bank: Optional[int] = None,
                  policy: int = llmc.EVICT_LRU, B: Optional[int] = None, half_life: int = 0, reval_every: int = 0,
-                 drift_bound: float = 0.0, bases: Optional[List[Optional[torch.Tensor]]] = None):
+                 drift_bound: float = 0.0, bases: Optional[List[Optional[torch.Tensor]]] = None,
+                 keep_means: bool = False):
         self.cfg = cfg
         self.device = device
         self.B = cfg.B if B is None else B
@@ -32,11 +33,13 @@ class GatedStack:
             self.banks[l] = llmc.Bank(n_bank, cfg.k, cfg.S, cfg.d, cfg.torch_dtype, device, policy=policy,
                                       half_life=half_life, reval_every=reval_every, drift_bound=drift_bound,
                                       basis=None if bases is None or bases[l] is None else
-                                      bases[l].to(device).contiguous())
+                                      bases[l].to(device).contiguous(), keep_means=keep_means)
         ws_bytes = llmc.llmc_layer_workspace_bytes(self.layers[0], self.B, cfg.S, cfg.k)
         self.workspace = torch.empty((ws_bytes,), dtype=torch.uint8, device=device)
         self.buf = [torch.empty((self.B, cfg.S, cfg.d), dtype=cfg.torch_dtype, device=device) for _ in range(2)]
-        self.gate = [llmc.GateBuffers(self.B, device) for _ in range(cfg.n_layers)]
+        # keep_means: banks store the token mean of every cached output and a reused row hands it to the next layer
+        self.keep_means = keep_means
+        self.gate = [llmc.GateBuffers(self.B, device, d=cfg.d if keep_means else 0) for _ in range(cfg.n_layers)]
 
     def forward(self, h0: torch.Tensor, tau: float, flags: int = 0, tick: int = 0, keep_all: bool = False,
                 single_fingerprint: bool = False):
@@ -54,8 +57,9 @@ class GatedStack:
             llmc.llmc_fingerprint(h0, self.proj[0], self.bias[0], fp_given, inv_given, self.workspace)
         for l in range(cfg.n_layers):
             out = torch.empty_like(h0) if keep_all else self.buf[l & 1]
+            carry = self.gate[l - 1] if (self.keep_means and l > 0) else None
             llmc.llmc_layer_forward_gated(self.layers[l], self.banks[l], self.proj[l], self.bias[l], h, out, tau,
-                                          flags, tick, self.workspace, self.gate[l], fp_given, inv_given)
+                                          flags, tick, self.workspace, self.gate[l], fp_given, inv_given, carry=carry)
             h = out
             if keep_all:
                 outs.append(out)

@@ -31,7 +31,7 @@ EXPORTS = [
     "llmc_match_workspace_bytes", "llmc_gather_hits", "llmc_layer_forward_gated",
     "llmc_layer_workspace_bytes", "llmc_profile_begin", "llmc_profile_report", "llmc_profile_end",
     "llmc_last_error", "llmc_version", "llmc_fingerprint_bits", "llmc_match_bits",
-    "llmc_match_bits_workspace_bytes", "llmc_max_hamming",
+    "llmc_match_bits_workspace_bytes", "llmc_max_hamming", "llmc_bank_pool_values",
 ]
 
 
@@ -41,7 +41,8 @@ class BankDesc(C.Structure):
                 ("d_fp", C.c_void_p), ("d_act", C.c_void_p), ("d_inv_norm", C.c_void_p),
                 ("d_act_slot", C.c_void_p), ("d_last_used", C.c_void_p), ("d_hits", C.c_void_p),
                 ("d_valid", C.c_void_p), ("half_life", C.c_int32), ("reval_every", C.c_int32),
-                ("drift_bound", C.c_float), ("rank", C.c_int32), ("d_basis", C.c_void_p)]
+                ("drift_bound", C.c_float), ("rank", C.c_int32), ("d_basis", C.c_void_p),
+                ("d_act_pool", C.c_void_p)]
 
 
 class LayerDesc(C.Structure):
@@ -53,12 +54,14 @@ class LayerDesc(C.Structure):
 
 
 class FpDesc(C.Structure):
-    _fields_ = [("d_proj", C.c_void_p), ("d_bias", C.c_void_p), ("k", C.c_int32)]
+    _fields_ = [("d_proj", C.c_void_p), ("d_bias", C.c_void_p), ("k", C.c_int32),
+                ("d_pooled_in", C.c_void_p), ("d_pooled_in_valid", C.c_void_p)]
 
 
 class GateOut(C.Structure):
     _fields_ = [("d_idx", C.c_void_p), ("d_sim", C.c_void_p), ("d_hit", C.c_void_p),
-                ("d_counters", C.c_void_p), ("d_slots", C.c_void_p)]
+                ("d_counters", C.c_void_p), ("d_slots", C.c_void_p), ("d_pooled_out", C.c_void_p),
+                ("d_pooled_out_valid", C.c_void_p)]
 
 
 class LlmcError(RuntimeError):
@@ -86,6 +89,7 @@ def lib() -> C.CDLL:
         L.llmc_bank_refresh.argtypes = [vp, vp]
         L.llmc_bank_insert.argtypes = [vp, vp, vp, vp, vp, vp, i32, u64, vp, vp, vp]
         L.llmc_bank_evict.argtypes = [vp, vp, i32, vp, vp]
+        L.llmc_bank_pool_values.argtypes = [vp, vp]
         L.llmc_fingerprint.argtypes = [vp, i32, i32, i32, i32, vp, vp, i32, vp, vp, vp, sz, vp]
         L.llmc_fingerprint_workspace_bytes.argtypes = [i32, i32, i32]
         L.llmc_fingerprint_workspace_bytes.restype = sz
@@ -152,7 +156,7 @@ class Bank:
     def __init__(self, n_slots: int, k: int, S: int, d: int, dtype: torch.dtype, device="cuda",
                  n_act_slots: Optional[int] = None, policy: int = EVICT_LRU,
                  act_slot: Optional[torch.Tensor] = None, half_life: int = 0, reval_every: int = 0,
-                 drift_bound: float = 0.0, basis: Optional[torch.Tensor] = None):
+                 drift_bound: float = 0.0, basis: Optional[torch.Tensor] = None, keep_means: bool = False):
         A = n_slots if n_act_slots is None else n_act_slots
         self.n_slots, self.k, self.S, self.d, self.n_act_slots = n_slots, k, S, d, A
         self.dtype = dtype
@@ -162,6 +166,8 @@ class Bank:
         self.rank = 0 if basis is None else int(basis.shape[0])
         self.act = torch.zeros((A, S, d if basis is None else self.rank), dtype=dtype, device=device)
         self.act_slot = act_slot
+        # token mean of every cached output (the next layer's pooled input of a hit)
+        self.act_pool = torch.zeros((A, d), dtype=torch.float32, device=device) if keep_means else None
         self.last_used = torch.zeros((n_slots,), dtype=torch.int64, device=device)   # uint64 bit pattern
         self.hits = torch.zeros((n_slots,), dtype=torch.int32, device=device)        # uint32 bit pattern
         self.valid = torch.zeros((n_slots,), dtype=torch.uint8, device=device)
@@ -175,7 +181,7 @@ class Bank:
         return BankDesc(self.n_slots, self.k, self.S, self.d, self.n_act_slots, dtype_code(self.dtype), self.policy,
                         _ptr(self.fp), _ptr(self.act), _ptr(self.inv_norm), _ptr(self.act_slot),
                         _ptr(self.last_used), _ptr(self.hits), _ptr(self.valid), self.half_life, self.reval_every,
-                        self.drift_bound, self.rank, _ptr(self.basis))
+                        self.drift_bound, self.rank, _ptr(self.basis), _ptr(self.act_pool))
 
     def create(self) -> None:
         torch.cuda.synchronize()
@@ -215,6 +221,10 @@ def llmc_bank_insert(bank: Bank, fp: torch.Tensor, inv_norm: torch.Tensor, act: 
                      slots_out: torch.Tensor, counters: Optional[torch.Tensor] = None, stream=None) -> None:
     _check(lib().llmc_bank_insert(bank.handle, _ptr(fp), _ptr(inv_norm), _ptr(act), _ptr(rows), _ptr(m), m_max, tick,
                                   _ptr(slots_out), _ptr(counters), _stream(stream)))
+
+
+def llmc_bank_pool_values(bank: Bank, stream=None) -> None:
+    _check(lib().llmc_bank_pool_values(bank.handle, _stream(stream)))
 
 
 def llmc_bank_evict(bank: Bank, m: Optional[torch.Tensor], m_max: int, victims_out: torch.Tensor, stream=None) -> None:
@@ -317,7 +327,10 @@ def llmc_layer_workspace_bytes(layer: Layer, B: int, S: int, k: int) -> int:
 class GateBuffers:
     """Optional per-row outputs of the gate, allocated once per (B)."""
 
-    def __init__(self, B: int, device="cuda"):
+    def __init__(self, B: int, device="cuda", d: int = 0):
+        # d > 0: also the buffers that carry the token means of reused rows to the next layer
+        self.pooled = torch.zeros((B, d), dtype=torch.float32, device=device) if d > 0 else None
+        self.pooled_valid = torch.zeros((B,), dtype=torch.uint8, device=device) if d > 0 else None
         self.idx = torch.empty((B,), dtype=torch.int32, device=device)
         self.sim = torch.empty((B,), dtype=torch.float32, device=device)
         self.hit = torch.empty((B,), dtype=torch.uint8, device=device)
@@ -325,17 +338,22 @@ class GateBuffers:
         self.slots = torch.empty((B,), dtype=torch.int32, device=device)
 
     def struct(self) -> GateOut:
-        return GateOut(_ptr(self.idx), _ptr(self.sim), _ptr(self.hit), _ptr(self.counters), _ptr(self.slots))
+        return GateOut(_ptr(self.idx), _ptr(self.sim), _ptr(self.hit), _ptr(self.counters), _ptr(self.slots),
+                       _ptr(self.pooled), _ptr(self.pooled_valid))
 
 
 def llmc_layer_forward_gated(layer: Layer, bank: Optional[Bank], proj: Optional[torch.Tensor],
                              bias: Optional[torch.Tensor], h_in: torch.Tensor, h_out: torch.Tensor, tau: float,
                              flags: int, tick: int, workspace: torch.Tensor, out: Optional[GateBuffers] = None,
                              fp_given: Optional[torch.Tensor] = None, inv_norm_given: Optional[torch.Tensor] = None,
-                             stream=None) -> None:
+                             stream=None, carry: Optional["GateBuffers"] = None) -> None:
+    """``carry``: the GateBuffers of the call that produced ``h_in`` (its pooled / pooled_valid are taken as the
+    token means of the rows it answered from its bank)."""
     B, S, _ = h_in.shape
     ld = layer.desc()
-    fpd = FpDesc(_ptr(proj), _ptr(bias), proj.shape[1] if proj is not None else 0)
+    fpd = FpDesc(_ptr(proj), _ptr(bias), proj.shape[1] if proj is not None else 0,
+                 _ptr(carry.pooled) if carry is not None else None,
+                 _ptr(carry.pooled_valid) if carry is not None else None)
     go = out.struct() if out is not None else None
     _check(lib().llmc_layer_forward_gated(
         C.byref(ld), bank.handle if bank is not None else None, C.byref(fpd), _ptr(h_in), _ptr(h_out), B, S, tau,

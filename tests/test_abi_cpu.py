@@ -59,7 +59,7 @@ def test_bank_create_validation(lib):
 
     def desc(**kw):
         base = dict(n_slots=16, k=32, S=4, d=64, n_act_slots=16, dtype=llmc.BF16, policy=llmc.EVICT_LRU,
-                    d_fp=p, d_act=p, d_inv_norm=p, d_act_slot=None, d_last_used=p, d_hits=p, d_valid=p, half_life=0, reval_every=0, drift_bound=0.0, rank=0, d_basis=None)
+                    d_fp=p, d_act=p, d_inv_norm=p, d_act_slot=None, d_last_used=p, d_hits=p, d_valid=p, half_life=0, reval_every=0, drift_bound=0.0, rank=0, d_basis=None, d_act_pool=None)
         base.update(kw)
         return llmc.BankDesc(**base)
 

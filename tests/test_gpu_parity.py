@@ -896,6 +896,56 @@ def test_compressed_values_against_oracle(L, dtype):
     st.close()
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_carried_token_means_change_nothing(L, dtype):
+    """Banks that keep the token mean of every cached output hand it to the next layer for reused rows, which is then
+    not pooled again.  Keys, decisions, similarities and outputs must be the same bits as without the carry, the
+    stored means must be what the pooling arithmetic gives for the stored outputs, and the flags must follow the hits."""
+    from paper_2512_16843_amd.engine import GatedStack
+    say(f"carried token means {dtype}: stack with and without the carry, bit for bit")
+    cfg = W.scaled(W.TINY_ENCODER, n_layers=3, B=8, n_bank=24) if dtype == "f32" else \
+        W.scaled(W.BERT_BASE, n_layers=3, B=8, S=70, n_bank=24)
+    ws = W.make_layer_weights(cfg, seed=0)
+    tok, pos = W.make_embeddings(cfg, seed=0)
+    Ps = W.make_projection(cfg.d, cfg.k, cfg.torch_dtype, seed=3, n_layers=cfg.n_layers)
+    stacks = [GatedStack(cfg, ws, Ps, keep_means=km) for km in (False, True)]
+    src = W.make_sources(cfg, 16, seed=1)
+    fresh = W.make_sources(cfg, 8, seed=9)
+    batches = [(src[0:8], 2.0, L.INSERT_ON_MISS), (src[8:16], 2.0, L.INSERT_ON_MISS),
+               (np.concatenate([src[[0, 5, 9, 15]], fresh[:4]]), 0.9, 0),
+               (np.concatenate([src[[3, 3, 12]], fresh[3:8]]), 0.9, L.INSERT_ON_MISS | L.UPDATE_LRU),   # evicts
+               (np.concatenate([fresh[4:8], src[[1, 2, 14, 7]]]), 0.9, L.UPDATE_LRU)]
+    for tick, (ids, tau, flags) in enumerate(batches, start=1):
+        h0 = W.embed(torch.from_numpy(ids), tok, pos, cfg.torch_dtype).cuda()
+        outs = [st.forward(h0, tau=tau, flags=flags, tick=tick, keep_all=True) for st in stacks]
+        torch.cuda.synchronize()
+        for l in range(cfg.n_layers):
+            a, b = stacks[0].gate[l], stacks[1].gate[l]
+            assert torch.equal(a.hit, b.hit) and torch.equal(a.idx, b.idx) and torch.equal(a.sim, b.sim), (tick, l)
+            assert torch.equal(a.counters, b.counters)
+            assert torch.equal(outs[0][l], outs[1][l]), (tick, l)
+            assert torch.equal(b.pooled_valid, b.hit)
+            assert torch.equal(stacks[0].banks[l].act, stacks[1].banks[l].act)
+            assert torch.equal(stacks[0].banks[l].fp, stacks[1].banks[l].fp)
+            hit_rows = torch.nonzero(b.hit).flatten()
+            if len(hit_rows):
+                want = stacks[1].banks[l].act_pool[b.idx[hit_rows].long()]
+                assert torch.equal(b.pooled[hit_rows], want)
+        say(f"  batch {tick}: hits per layer {[int(g.hit.sum()) for g in stacks[1].gate]}")
+    # stored means = the pooling arithmetic on the stored outputs (recomputed by the library), and = the plain mean
+    bk = stacks[1].banks[1]
+    stored = bk.act_pool.clone()
+    bk.act_pool.zero_()
+    L.llmc_bank_pool_values(bk)
+    torch.cuda.synchronize()
+    v = bk.valid.bool()
+    assert torch.equal(bk.act_pool[v], stored[v])
+    ref = npf(bk.act)[v.cpu().numpy()].astype(np.float64).mean(axis=1)
+    np.testing.assert_allclose(npf(bk.act_pool[v]), ref, rtol=0, atol=1e-5 * max(1.0, np.abs(ref).max()))
+    for st in stacks:
+        st.close()
+
+
 def test_insert_without_eviction_drops_and_counts(L):
     say("insert into a full bank with policy NONE")
     g = np.random.Generator(np.random.PCG64(13))
