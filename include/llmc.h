@@ -25,7 +25,12 @@
  *  - Results for one sequence do not depend on its row in the batch, on B, or
  *    on which other rows hit or miss: every reduction has a fixed order.
  *  - Two calls that touch the same bank, or share a workspace, must not overlap
- *    on different streams.
+ *    on different streams.  A bank handle also carries host-side state (the decay
+ *    epoch of LLMC_EVICT_DECAYED_HITS) and library-owned device scratch (the value-row
+ *    list of a bank with compressed values): calls on one bank must come from one host
+ *    thread at a time, in the order in which their work is to run.
+ *  - llmc_profile_* is process-wide and not synchronised: switch it on and off while
+ *    no other thread is inside the library.
  */
 #ifndef LLMC_H
 #define LLMC_H

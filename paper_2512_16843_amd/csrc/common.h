@@ -1,6 +1,7 @@
 // Internal helpers shared by the llmc kernels (gfx950 only).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <atomic>
 #include <stdint.h>
 #include <stddef.h>
 #include <math.h>
@@ -121,6 +122,20 @@ static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; 
 static inline size_t elem_size(int dtype) { return dtype == LLMC_F32 ? 4 : 2; }
 
 // ---- the bank object ------------------------------------------------------------------
+}  // namespace llmc
+
+namespace llmc {
+// Raise a kernel's dynamic-LDS limit once per device (the setting is per function AND per device).
+// `done` is a per-call-site table; calls on one device from several host threads at once may set it twice, harmlessly.
+inline llmc_status_t ensure_dynamic_lds(const void* fn, size_t bytes, std::atomic<bool>* done) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) dev = 0;
+  if (done[dev].load(std::memory_order_acquire)) return LLMC_OK;
+  hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+  if (e != hipSuccess) return hip_error(e, "hipFuncSetAttribute(MaxDynamicSharedMemorySize)");
+  done[dev].store(true, std::memory_order_release);
+  return LLMC_OK;
+}
 }  // namespace llmc
 
 struct llmc_bank {

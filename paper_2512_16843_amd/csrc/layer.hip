@@ -88,12 +88,8 @@ static llmc_status_t launch_gemm(const GemmArgs& g, int dtype, hipStream_t st) {
   if (dtype == LLMC_BF16) {
     if (g.K % 64 == 0) {
       using C = GemmDmaCfg;
-      static bool attr_set = false;   // raising the dynamic-LDS limit is a per-function setting, done once
-      if (!attr_set) {
-        LLMC_HIP(hipFuncSetAttribute((const void*)gemm_bf16_dma_kernel<C>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                     (int)gemm_dma_smem_bytes<C>()));
-        attr_set = true;
-      }
+      static std::atomic<bool> lds_set[64];
+      LLMC_TRY(ensure_dynamic_lds((const void*)gemm_bf16_dma_kernel<C>, gemm_dma_smem_bytes<C>(), lds_set));
       const int tiles_n = (g.N + C::BN - 1) / C::BN;
       const int tiles_m = (g.max_seqs * g.S + C::BM - 1) / C::BM;
       GemmArgs a = g;

@@ -637,12 +637,8 @@ static llmc_status_t launch_stream_nw(const llmc_bank* bank, const void* d_fp, i
                                       hipStream_t st) {
   using C = StreamCfg<K_, NW_>;
   const llmc_bank_desc_t& D = bank->desc;
-  static bool attr_set = false;
-  if (!attr_set) {
-    LLMC_HIP(hipFuncSetAttribute((const void*)(match_stream_kernel<K_, NW_>),
-                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES));
-    attr_set = true;
-  }
+  static std::atomic<bool> lds_set[64];
+  LLMC_TRY(ensure_dynamic_lds((const void*)(match_stream_kernel<K_, NW_>), C::LDS_BYTES, lds_set));
   int nqb, ns, per;
   stream_plan(D.n_slots, B, C::RB, C::QB, &nqb, &ns, &per);
   const int groups = (ns + 7) / 8;                 // splits are dealt to the 8 XCDs
@@ -661,12 +657,8 @@ static llmc_status_t launch_stream(const llmc_bank* bank, const void* d_fp, int 
   if (stream_waves(B) == 4) return launch_stream_nw<K_, 4>(bank, d_fp, B, partial, ns_out, st);
   using C = SkewCfg<K_>;
   const llmc_bank_desc_t& D = bank->desc;
-  static bool attr_set = false;
-  if (!attr_set) {
-    LLMC_HIP(hipFuncSetAttribute((const void*)(match_skew_kernel<K_>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                 (int)C::LDS_BYTES));
-    attr_set = true;
-  }
+  static std::atomic<bool> lds_set[64];
+  LLMC_TRY(ensure_dynamic_lds((const void*)(match_skew_kernel<K_>), C::LDS_BYTES, lds_set));
   int nqb, ns, per;
   stream_plan(D.n_slots, B, C::RB, C::QB, &nqb, &ns, &per);
   const unsigned grid = (unsigned)((ns + 7) / 8) * nqb * 8;    // splits are dealt to the 8 XCDs
