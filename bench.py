@@ -90,7 +90,8 @@ def main():
                          "stream of stem-sharing batches")
     ap.add_argument("--no-dial", action="store_true", help="skip the hit-rate dial leg")
     ap.add_argument("--no-carry", action="store_true",
-                    help="banks do not keep the token means of cached outputs (every layer pools every row again)")
+                    help="banks keep neither the token mean nor the next-layer key of cached outputs (every layer pools "
+                         "and projects every row again)")
     ap.add_argument("--bank", type=int, default=None, help="bank entries per layer (default: the config's 16384)")
     ap.add_argument("--layers", type=int, default=None, help="debug: fewer layers")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -125,7 +126,7 @@ def main():
     tok, pos = tok.to(dev), pos.to(dev)
     Ps = W.make_projection(cfg.d, cfg.k, cfg.torch_dtype, seed=3, n_layers=cfg.n_layers)
     src = W.make_sources(cfg, cfg.n_bank, seed=1)
-    st = GatedStack(cfg, ws, Ps, keep_means=not args.no_carry)
+    st = GatedStack(cfg, ws, Ps, keep_means=not args.no_carry, keep_next_keys=not args.no_carry)
     log("inputs drawn and %d banks allocated in %.1f s" % (cfg.n_layers, time.time() - t0))
 
     # ---- bank build: all-miss forward with insertion over the source sequences -------------------
@@ -506,7 +507,7 @@ def bench_dynamic(args, llmc, W, GatedStack):
     tok, pos = W.make_embeddings(cfg, seed=0)
     tok, pos = tok.to(dev), pos.to(dev)
     Ps = W.make_projection(cfg.d, cfg.k, cfg.torch_dtype, seed=3, n_layers=cfg.n_layers)
-    st = GatedStack(cfg, ws, Ps, keep_means=not args.no_carry)
+    st = GatedStack(cfg, ws, Ps, keep_means=not args.no_carry, keep_next_keys=not args.no_carry)
     stream = W.StemStream(cfg, group=4, stem_len=80, n_stems=512, seed=4)
     flags = llmc.INSERT_ON_MISS | llmc.UPDATE_LRU
     tick = 0

@@ -146,6 +146,17 @@ typedef struct {
    * kept.  Refused together with compressed values.  Entries written into d_act by the caller directly have no
    * mean until llmc_bank_pool_values() is called. */
   float* d_act_pool;
+  /* Optional, needs d_act_pool: the KEY under which each cached output will be looked up by the next layer, i.e.
+   * its fingerprint under that layer's map (d_next_proj [d, next_k], d_next_bias [next_k] or NULL), kept in
+   * d_next_fp [n_act_slots, next_k] (element type `dtype`) and d_next_inv [n_act_slots].  Written by the library
+   * whenever it stores an output (the same arithmetic as llmc_fingerprint, so the same bits), handed to the next
+   * call through llmc_gate_out_t.d_key_out, which then neither pools nor projects the reused rows.  All NULL: not
+   * kept.  The projection arrays must stay alive and unchanged. */
+  const void* d_next_proj;
+  const float* d_next_bias;
+  int32_t next_k;
+  void* d_next_fp;
+  float* d_next_inv;
 } llmc_bank_desc_t;
 
 /*
@@ -183,6 +194,10 @@ typedef struct {
    * order), so keys do not depend on whether a mean was carried.  Both NULL: every row is pooled here. */
   const float* d_pooled_in;
   const uint8_t* d_pooled_in_valid;
+  /* Optional, with d_pooled_in_valid: finished keys [B, k] + inverse norms [B] of the flagged rows (see
+   * llmc_gate_out_t.d_key_out); those rows are then neither pooled nor projected.  k must be this map's k. */
+  const void* d_key_in;
+  const float* d_key_inv_in;
 } llmc_fp_desc_t;
 
 /* Optional per-row results of the gate; any pointer may be NULL. */
@@ -198,6 +213,10 @@ typedef struct {
    * every row answered from the bank (0 for computed rows, whose mean the next call computes itself). */
   float* d_pooled_out;          /* [B, d] */
   uint8_t* d_pooled_out_valid;  /* [B] */
+  /* With a bank that keeps d_next_fp: the stored next-layer key and inverse norm of every row answered from the
+   * bank (same flags).  d_key_out [B, next_k] in the bank's element type, d_key_inv_out [B]. */
+  void* d_key_out;
+  float* d_key_inv_out;
 } llmc_gate_out_t;
 
 /* ---- bank -------------------------------------------------------------- */
@@ -241,7 +260,8 @@ llmc_status_t llmc_bank_insert(llmc_bank_t* bank, const void* d_fp, const float*
                                int32_t m_max, uint64_t tick, int32_t* d_slots_out,
                                int32_t* d_counters, llmc_stream_t stream);
 
-/* Recompute d_act_pool from d_act for all value rows (after the caller wrote values directly).
+/* Recompute d_act_pool (and d_next_fp / d_next_inv, if kept) from d_act for all value rows (after the caller wrote
+ * values directly).
  * INVALID_ARG if the bank keeps no means. */
 llmc_status_t llmc_bank_pool_values(llmc_bank_t* bank, llmc_stream_t stream);
 

@@ -111,6 +111,14 @@ llmc_status_t llmc_bank_create(const llmc_bank_desc_t* desc, llmc_bank_t** out) 
           "stored token means are refused together with compressed values");
   REQUIRE(!(desc->d_act_pool && desc->d_act_slot), LLMC_ERR_INVALID_ARG,
           "stored token means need keys that own their value rows");
+  if (desc->d_next_fp || desc->d_next_inv || desc->d_next_proj) {
+    REQUIRE(desc->d_next_fp && desc->d_next_inv && desc->d_next_proj && desc->d_act_pool, LLMC_ERR_INVALID_ARG,
+            "stored next-layer keys need d_next_proj, d_next_fp, d_next_inv and d_act_pool");
+    REQUIRE(desc->next_k > 0 && desc->next_k % 32 == 0 && desc->next_k <= 1024, LLMC_ERR_SHAPE,
+            "next_k=%d must be a multiple of 32, at most 1024", desc->next_k);
+    REQUIRE(aligned16(desc->d_next_proj) && aligned16(desc->d_next_fp), LLMC_ERR_SHAPE,
+            "next-layer key arrays must be 16-byte aligned");
+  }
   REQUIRE(desc->rank >= 0, LLMC_ERR_SHAPE, "rank must not be negative");
   if (desc->rank > 0) {
     REQUIRE(desc->rank % 64 == 0 && desc->rank <= desc->d, LLMC_ERR_SHAPE,
@@ -200,6 +208,11 @@ llmc_status_t llmc_bank_pool_values(llmc_bank_t* bank, llmc_stream_t stream) {
     const char* src = (const char*)D.d_act + (size_t)s0 * D.S * D.d * elem_size(D.dtype);
     LLMC_TRY(launch_pool_rows(src, n, D.S, D.d, D.dtype, nullptr, nullptr, nullptr, D.d_act_pool + (size_t)s0 * D.d,
                               (hipStream_t)stream));
+    if (D.d_next_fp)
+      LLMC_TRY(launch_project_rows(D.d_act_pool + (size_t)s0 * D.d, n, D.d, D.dtype, D.d_next_proj, D.d_next_bias,
+                                   D.next_k, nullptr, nullptr,
+                                   (char*)D.d_next_fp + (size_t)s0 * D.next_k * elem_size(D.dtype), D.d_next_inv + s0,
+                                   (hipStream_t)stream));
   }
   return LLMC_OK;
 }
@@ -467,23 +480,31 @@ llmc_status_t llmc_layer_forward_gated(const llmc_layer_desc_t* layer, llmc_bank
   const void* q = d_fp_given;
   const float* qinv = d_inv_norm_given;
   if (!q) {
-    const bool carried = fp->d_pooled_in && fp->d_pooled_in_valid;
+    const bool keys_in = fp->d_key_in && fp->d_key_inv_in && fp->d_pooled_in_valid;
+    const bool carried = (fp->d_pooled_in || keys_in) && fp->d_pooled_in_valid;
     LLMC_TRY(launch_fingerprint(d_h_in, nullptr, B, S, layer->d, layer->dtype, fp->d_proj, fp->d_bias, k, keys, inv,
                                 ws_fp, st, carried ? fp->d_pooled_in : nullptr,
-                                carried ? fp->d_pooled_in_valid : nullptr));
+                                carried ? fp->d_pooled_in_valid : nullptr, keys_in ? fp->d_key_in : nullptr,
+                                keys_in ? fp->d_key_inv_in : nullptr));
     q = keys;
     qinv = inv;
   }
   LLMC_TRY(launch_match(bank, q, qinv, B, tau, idx, sim, hit, tie, ws_match, st));
   float* pooled_out = nullptr;
   uint8_t* pooled_valid_out = nullptr;
+  void* key_out = nullptr;
+  float* key_inv_out = nullptr;
   if (out && out->d_pooled_out_valid) {
     pooled_valid_out = out->d_pooled_out_valid;                       // always written: zeros if nothing is carried
     if (out->d_pooled_out && bank->desc.d_act_pool) pooled_out = out->d_pooled_out;
+    if (pooled_out && out->d_key_out && out->d_key_inv_out && bank->desc.d_next_fp) {
+      key_out = out->d_key_out;
+      key_inv_out = out->d_key_inv_out;
+    }
   }
   LLMC_TRY(launch_compact(hit, idx, sim, tie, B, tau, hit_rows, miss_rows, reval_tmp, counters, bank, flags, tick, st,
                           pooled_valid_out, pooled_out ? 1 : 0));
-  LLMC_TRY(launch_gather(bank, idx, hit_rows, counters + LLMC_CNT_HIT, B, d_h_out, st, pooled_out));
+  LLMC_TRY(launch_gather(bank, idx, hit_rows, counters + LLMC_CNT_HIT, B, d_h_out, st, pooled_out, key_out, key_inv_out));
   // the rows to compute: the misses, then (divergence monitor) the sampled hit rows, whose copies are overwritten
   LLMC_TRY(launch_layer(layer, d_h_in, d_h_out, B, S, miss_rows, counters + LLMC_CNT_COMPUTED, ws_layer, st));
   if ((flags & LLMC_REVALIDATE) && bank->desc.reval_every > 0)

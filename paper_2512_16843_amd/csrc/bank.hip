@@ -326,6 +326,10 @@ llmc_status_t launch_bank_insert(llmc_bank* bank, const void* d_fp, const float*
   // the token mean of every stored output, kept beside it (dropped rows have slot -1 and are skipped)
   if (D.d_act_pool)
     LLMC_TRY(launch_pool_rows(d_act, m_max, D.S, D.d, D.dtype, d_rows, d_m, d_slots_out, D.d_act_pool, st));
+  // ... and the key under which the next layer will look it up
+  if (D.d_next_fp)
+    LLMC_TRY(launch_project_rows(D.d_act_pool, m_max, D.d, D.dtype, D.d_next_proj, D.d_next_bias, D.next_k, d_slots_out,
+                                 d_m, D.d_next_fp, D.d_next_inv, st));
   return LLMC_OK;
 }
 

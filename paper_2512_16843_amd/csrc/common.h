@@ -159,7 +159,11 @@ size_t fingerprint_ws_bytes(int B, int S, int d);
 llmc_status_t launch_fingerprint(const void* d_h, const int32_t* d_rowmap_unused, int B, int S, int d, int dtype,
                                  const void* d_proj, const float* d_bias, int k, void* d_fp, float* d_inv, void* ws,
                                  hipStream_t st, const float* pooled_in = nullptr,
-                                 const uint8_t* pooled_valid = nullptr);
+                                 const uint8_t* pooled_valid = nullptr, const void* key_in = nullptr,
+                                 const float* key_inv_in = nullptr);
+llmc_status_t launch_project_rows(const float* d_means, int n_max, int d, int dtype, const void* d_proj,
+                                  const float* d_bias, int k, const int32_t* d_rows, const int32_t* d_count, void* d_fp,
+                                  float* d_inv, hipStream_t st);
 llmc_status_t launch_pool_rows(const void* d_h, int n_max, int S, int d, int dtype, const int32_t* d_rows,
                                const int32_t* d_count, const int32_t* d_dst, float* d_out, hipStream_t st);
 llmc_status_t launch_fingerprint_bits(const void* d_h, int B, int S, int d, int dtype, const void* d_proj,
@@ -188,7 +192,7 @@ llmc_status_t launch_all_miss(int B, int32_t* d_miss_rows, int32_t* d_counters, 
                               uint8_t* d_hit, hipStream_t st, uint8_t* d_pooled_valid_out = nullptr);
 llmc_status_t launch_gather(const llmc_bank* bank, const int32_t* d_idx, const int32_t* d_rows,
                             const int32_t* d_n, int n_max, void* d_h_out, hipStream_t st,
-                            float* d_pooled_out = nullptr);
+                            float* d_pooled_out = nullptr, void* d_key_out = nullptr, float* d_key_inv_out = nullptr);
 
 // bank.hip
 llmc_status_t launch_bank_refresh(llmc_bank* bank, hipStream_t st);

@@ -77,20 +77,37 @@ __global__ __launch_bounds__(1024) void project_kernel(const float* __restrict__
                                                        int parts, T* __restrict__ fp_out, float* __restrict__ inv_out,
                                                        uint32_t* __restrict__ bits_out,
                                                        const float* __restrict__ pooled_in,
-                                                       const uint8_t* __restrict__ pooled_valid) {
+                                                       const uint8_t* __restrict__ pooled_valid,
+                                                       const T* __restrict__ key_in, const float* __restrict__ key_inv_in,
+                                                       const int32_t* __restrict__ row_map,
+                                                       const int32_t* __restrict__ count) {
+  // Entry e = blockIdx.x works on row b = row_map[e] (or e) of the outputs.  Sources of the token mean of row b:
+  // pooled_in[b] if pooled_in is given and either there are no flags (means kept elsewhere, e.g. beside a bank's
+  // values, possibly through row_map) or pooled_valid[b] is set; else the chunk partials of entry e.  If key_in is given and pooled_valid[b], the finished key
+  // itself was supplied: it is copied and nothing is computed.
   extern __shared__ float sm[];   // p[d] | v[parts][k]
   float* p = sm;
   float* vpart = sm + d;
   __shared__ double wsum[16];
   __shared__ float s_scale;
-  const int b = blockIdx.x;
+  const int entry = blockIdx.x;
+  if (count && entry >= *count) return;
+  const int b = row_map ? row_map[entry] : entry;
+  if (b < 0) return;
   const int nthreads = blockDim.x;
+  const bool given = !row_map && pooled_valid && pooled_valid[b];
+  const bool from_means = pooled_in && (row_map || !pooled_valid || given);   // no flags: every row's mean is supplied
+  if (given && key_in) {
+    for (int i = threadIdx.x; i < k; i += nthreads) fp_out[(size_t)b * k + i] = key_in[(size_t)b * k + i];
+    if (threadIdx.x == 0) inv_out[b] = key_inv_in[b];
+    return;
+  }
   const float inv_S = 1.0f / (float)S;
-  if (pooled_valid && pooled_valid[b]) {
+  if (from_means) {
     for (int i = threadIdx.x; i < d; i += nthreads) p[i] = pooled_in[(size_t)b * d + i];
   } else
   for (int i = threadIdx.x; i < d; i += nthreads) {
-    const float* src = partial + (size_t)b * n_chunks * d + i;
+    const float* src = partial + (size_t)entry * n_chunks * d + i;
     float s = 0.f;
     // eight chunk partials in flight; added in ascending chunk order
     constexpr int UC = 8;
@@ -286,7 +303,8 @@ size_t fingerprint_ws_bytes(int B, int S, int d) {
 template <typename T>
 static llmc_status_t fingerprint_t(const T* h, int B, int S, int d, const T* P, const float* bias, int k,
                                    T* fp, float* inv, uint32_t* bits, float* partial, const float* pooled_in,
-                                   const uint8_t* pooled_valid, hipStream_t st) {
+                                   const uint8_t* pooled_valid, hipStream_t st, const T* key_in = nullptr,
+                                   const float* key_inv_in = nullptr) {
   constexpr int VEC = Vec16<T>::N;
   const int G = d / VEC;
   const int R = G <= 512 ? 2 : 1;   // token rows split over thread groups; depends on d only
@@ -301,7 +319,8 @@ static llmc_status_t fingerprint_t(const T* h, int B, int S, int d, const T* P, 
   {
     ProfScope ps_("project_kernel", st);
     hipLaunchKernelGGL(project_kernel<T>, dim3(B), dim3(std::max(cgs * parts, k)),
-                       (size_t)(d + parts * k) * sizeof(float), st, partial, n_chunks, S, d, P, bias, k, parts, fp, inv, bits, pooled_in, pooled_valid);
+                       (size_t)(d + parts * k) * sizeof(float), st, partial, n_chunks, S, d, P, bias, k, parts, fp, inv, bits, pooled_in, pooled_valid, key_in,
+                       key_inv_in, (const int32_t*)nullptr, (const int32_t*)nullptr);
   }
   LLMC_LAUNCH_CHECK("project_kernel");
   return LLMC_OK;
@@ -309,12 +328,38 @@ static llmc_status_t fingerprint_t(const T* h, int B, int S, int d, const T* P, 
 
 llmc_status_t launch_fingerprint(const void* d_h, const int32_t*, int B, int S, int d, int dtype, const void* d_proj,
                                  const float* d_bias, int k, void* d_fp, float* d_inv, void* ws, hipStream_t st,
-                                 const float* pooled_in, const uint8_t* pooled_valid) {
+                                 const float* pooled_in, const uint8_t* pooled_valid, const void* key_in,
+                                 const float* key_inv_in) {
   if (dtype == LLMC_F32)
     return fingerprint_t<float>((const float*)d_h, B, S, d, (const float*)d_proj, d_bias, k, (float*)d_fp, d_inv,
-                                nullptr, (float*)ws, pooled_in, pooled_valid, st);
+                                nullptr, (float*)ws, pooled_in, pooled_valid, st, (const float*)key_in, key_inv_in);
   return fingerprint_t<bf16_t>((const bf16_t*)d_h, B, S, d, (const bf16_t*)d_proj, d_bias, k, (bf16_t*)d_fp, d_inv,
-                               nullptr, (float*)ws, pooled_in, pooled_valid, st);
+                               nullptr, (float*)ws, pooled_in, pooled_valid, st, (const bf16_t*)key_in, key_inv_in);
+}
+
+// keys of token means kept elsewhere: entry e < *count (or n_max) projects means[rows[e]] into fp[rows[e]], inv[rows[e]]
+template <typename T>
+static llmc_status_t project_rows_t(const float* means, int n_max, int d, const T* P, const float* bias, int k,
+                                    const int32_t* rows, const int32_t* count, T* fp, float* inv, hipStream_t st) {
+  const int cgs = k / 4;
+  const int parts = std::max(1, std::min(1024 / cgs, 16));
+  ProfScope ps_("project_kernel", st);
+  hipLaunchKernelGGL(project_kernel<T>, dim3(n_max), dim3(std::max(cgs * parts, k)),
+                     (size_t)(d + parts * k) * sizeof(float), st, (const float*)nullptr, 0, 1, d, P, bias, k, parts, fp, inv,
+                     (uint32_t*)nullptr, means, (const uint8_t*)nullptr, (const T*)nullptr, (const float*)nullptr, rows,
+                     count);
+  LLMC_LAUNCH_CHECK("project_kernel");
+  return LLMC_OK;
+}
+
+llmc_status_t launch_project_rows(const float* d_means, int n_max, int d, int dtype, const void* d_proj,
+                                  const float* d_bias, int k, const int32_t* d_rows, const int32_t* d_count, void* d_fp,
+                                  float* d_inv, hipStream_t st) {
+  if (dtype == LLMC_F32)
+    return project_rows_t<float>(d_means, n_max, d, (const float*)d_proj, d_bias, k, d_rows, d_count, (float*)d_fp, d_inv,
+                                 st);
+  return project_rows_t<bf16_t>(d_means, n_max, d, (const bf16_t*)d_proj, d_bias, k, d_rows, d_count, (bf16_t*)d_fp,
+                                d_inv, st);
 }
 
 // token means of the sequences rows[0 .. *count) (or 0 .. n_max) of h, written to out[dst[i] or i] [d] fp32

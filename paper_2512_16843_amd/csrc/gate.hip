@@ -164,7 +164,11 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(const u32x4_t* _
                                                                 const int32_t* __restrict__ count, int n_max,
                                                                 size_t vec_per_seq, u32x4_t* __restrict__ out,
                                                                 const float* __restrict__ act_pool,
-                                                                float* __restrict__ pooled_out, int d) {
+                                                                float* __restrict__ pooled_out, int d,
+                                                                const uint32_t* __restrict__ next_fp,
+                                                                const float* __restrict__ next_inv,
+                                                                uint32_t* __restrict__ key_out,
+                                                                float* __restrict__ key_inv_out, int key_words) {
   const int n = count ? min(*count, n_max) : n_max;
   const int i = blockIdx.y;
   if (i >= n) return;
@@ -174,6 +178,11 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(const u32x4_t* _
   const int slot = act_slot ? act_slot[j] : j;
   if (pooled_out && blockIdx.x == 0)       // the stored token mean of the cached output rides along
     for (int c = threadIdx.x; c < d; c += kGatherThreads) pooled_out[(size_t)b * d + c] = act_pool[(size_t)slot * d + c];
+  if (key_out && blockIdx.x == 0) {        // ... and so does the key under which the next layer looks it up
+    for (int c = threadIdx.x; c < key_words; c += kGatherThreads)
+      key_out[(size_t)b * key_words + c] = next_fp[(size_t)slot * key_words + c];
+    if (threadIdx.x == 0) key_inv_out[b] = next_inv[slot];
+  }
   const u32x4_t* src = act + (size_t)slot * vec_per_seq;
   u32x4_t* dst = out + (size_t)b * vec_per_seq;
   const size_t v0 = (size_t)blockIdx.x * (kGatherThreads * kGatherVecPerThread) + threadIdx.x;
@@ -239,7 +248,8 @@ __global__ void hit_slots_kernel(const int32_t* __restrict__ idx, const int32_t*
 }
 
 llmc_status_t launch_gather(const llmc_bank* bank, const int32_t* d_idx, const int32_t* d_rows, const int32_t* d_n,
-                            int n_max, void* d_h_out, hipStream_t st, float* d_pooled_out) {
+                            int n_max, void* d_h_out, hipStream_t st, float* d_pooled_out, void* d_key_out,
+                            float* d_key_inv_out) {
   const llmc_bank_desc_t& D = bank->desc;
   if (D.rank > 0) {
     // compressed values: h_out[rows[i]] = C[value row] * U, one GEMM with K = rank over the listed hits
@@ -255,7 +265,9 @@ llmc_status_t launch_gather(const llmc_bank* bank, const int32_t* d_idx, const i
   dim3 grid((unsigned)((vec_per_seq + per_wg - 1) / per_wg), n_max);
   { ProfScope ps_("gather_kernel", st); hipLaunchKernelGGL(gather_kernel, grid, dim3(kGatherThreads), 0, st, (const u32x4_t*)D.d_act, D.d_act_slot, d_idx,
                      d_rows, d_n, n_max, vec_per_seq, (u32x4_t*)d_h_out, D.d_act_pool,
-                     D.d_act_pool ? d_pooled_out : nullptr, D.d); }
+                     D.d_act_pool ? d_pooled_out : nullptr, D.d, (const uint32_t*)D.d_next_fp, D.d_next_inv,
+                     (D.d_next_fp && d_key_inv_out) ? (uint32_t*)d_key_out : nullptr, d_key_inv_out,
+                     (int)((size_t)D.next_k * elem_size(D.dtype) / 4)); }
   LLMC_LAUNCH_CHECK("gather_kernel");
   return LLMC_OK;
 }

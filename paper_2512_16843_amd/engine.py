@@ -19,7 +19,7 @@ class GatedStack:
                  biases: Optional[List[Optional[torch.Tensor]]] = None, n_bank: Optional[int] = None,
                  policy: int = llmc.EVICT_LRU, B: Optional[int] = None, half_life: int = 0, reval_every: int = 0,
                  drift_bound: float = 0.0, bases: Optional[List[Optional[torch.Tensor]]] = None,
-                 keep_means: bool = False):
+                 keep_means: bool = False, keep_next_keys: bool = False):
         self.cfg = cfg
         self.device = device
         self.B = cfg.B if B is None else B
@@ -29,17 +29,25 @@ class GatedStack:
         n_bank = cfg.n_bank if n_bank is None else n_bank
         cached = range(cfg.n_layers) if cached_layers is None else cached_layers
         self.banks: List[Optional[llmc.Bank]] = [None] * cfg.n_layers
+        cached = list(cached)
+        # keep_next_keys (with keep_means): bank l also stores each cached output's key under layer l + 1's map
+        self.keep_next_keys = keep_next_keys and keep_means
         for l in cached:
+            nxt = l + 1 if (self.keep_next_keys and l + 1 < cfg.n_layers and (l + 1) in cached) else None
             self.banks[l] = llmc.Bank(n_bank, cfg.k, cfg.S, cfg.d, cfg.torch_dtype, device, policy=policy,
                                       half_life=half_life, reval_every=reval_every, drift_bound=drift_bound,
                                       basis=None if bases is None or bases[l] is None else
-                                      bases[l].to(device).contiguous(), keep_means=keep_means)
+                                      bases[l].to(device).contiguous(), keep_means=keep_means,
+                                      next_proj=None if nxt is None else self.proj[nxt],
+                                      next_bias=None if nxt is None else self.bias[nxt])
         ws_bytes = llmc.llmc_layer_workspace_bytes(self.layers[0], self.B, cfg.S, cfg.k)
         self.workspace = torch.empty((ws_bytes,), dtype=torch.uint8, device=device)
         self.buf = [torch.empty((self.B, cfg.S, cfg.d), dtype=cfg.torch_dtype, device=device) for _ in range(2)]
         # keep_means: banks store the token mean of every cached output and a reused row hands it to the next layer
         self.keep_means = keep_means
-        self.gate = [llmc.GateBuffers(self.B, device, d=cfg.d if keep_means else 0) for _ in range(cfg.n_layers)]
+        self.gate = [llmc.GateBuffers(self.B, device, d=cfg.d if keep_means else 0,
+                                      next_k=cfg.k if (self.banks[l] is not None and self.banks[l].next_fp is not None) else 0,
+                                      dtype=cfg.torch_dtype) for l in range(cfg.n_layers)]
 
     def forward(self, h0: torch.Tensor, tau: float, flags: int = 0, tick: int = 0, keep_all: bool = False,
                 single_fingerprint: bool = False):

@@ -42,7 +42,8 @@ class BankDesc(C.Structure):
                 ("d_act_slot", C.c_void_p), ("d_last_used", C.c_void_p), ("d_hits", C.c_void_p),
                 ("d_valid", C.c_void_p), ("half_life", C.c_int32), ("reval_every", C.c_int32),
                 ("drift_bound", C.c_float), ("rank", C.c_int32), ("d_basis", C.c_void_p),
-                ("d_act_pool", C.c_void_p)]
+                ("d_act_pool", C.c_void_p), ("d_next_proj", C.c_void_p), ("d_next_bias", C.c_void_p),
+                ("next_k", C.c_int32), ("d_next_fp", C.c_void_p), ("d_next_inv", C.c_void_p)]
 
 
 class LayerDesc(C.Structure):
@@ -55,13 +56,14 @@ class LayerDesc(C.Structure):
 
 class FpDesc(C.Structure):
     _fields_ = [("d_proj", C.c_void_p), ("d_bias", C.c_void_p), ("k", C.c_int32),
-                ("d_pooled_in", C.c_void_p), ("d_pooled_in_valid", C.c_void_p)]
+                ("d_pooled_in", C.c_void_p), ("d_pooled_in_valid", C.c_void_p), ("d_key_in", C.c_void_p),
+                ("d_key_inv_in", C.c_void_p)]
 
 
 class GateOut(C.Structure):
     _fields_ = [("d_idx", C.c_void_p), ("d_sim", C.c_void_p), ("d_hit", C.c_void_p),
                 ("d_counters", C.c_void_p), ("d_slots", C.c_void_p), ("d_pooled_out", C.c_void_p),
-                ("d_pooled_out_valid", C.c_void_p)]
+                ("d_pooled_out_valid", C.c_void_p), ("d_key_out", C.c_void_p), ("d_key_inv_out", C.c_void_p)]
 
 
 class LlmcError(RuntimeError):
@@ -156,7 +158,8 @@ class Bank:
     def __init__(self, n_slots: int, k: int, S: int, d: int, dtype: torch.dtype, device="cuda",
                  n_act_slots: Optional[int] = None, policy: int = EVICT_LRU,
                  act_slot: Optional[torch.Tensor] = None, half_life: int = 0, reval_every: int = 0,
-                 drift_bound: float = 0.0, basis: Optional[torch.Tensor] = None, keep_means: bool = False):
+                 drift_bound: float = 0.0, basis: Optional[torch.Tensor] = None, keep_means: bool = False,
+                 next_proj: Optional[torch.Tensor] = None, next_bias: Optional[torch.Tensor] = None):
         A = n_slots if n_act_slots is None else n_act_slots
         self.n_slots, self.k, self.S, self.d, self.n_act_slots = n_slots, k, S, d, A
         self.dtype = dtype
@@ -168,6 +171,11 @@ class Bank:
         self.act_slot = act_slot
         # token mean of every cached output (the next layer's pooled input of a hit)
         self.act_pool = torch.zeros((A, d), dtype=torch.float32, device=device) if keep_means else None
+        # the key of every cached output under the NEXT layer's fingerprint map (needs keep_means)
+        self.next_proj, self.next_bias = next_proj, next_bias
+        self.next_k = 0 if next_proj is None else int(next_proj.shape[1])
+        self.next_fp = torch.zeros((A, self.next_k), dtype=dtype, device=device) if next_proj is not None else None
+        self.next_inv = torch.zeros((A,), dtype=torch.float32, device=device) if next_proj is not None else None
         self.last_used = torch.zeros((n_slots,), dtype=torch.int64, device=device)   # uint64 bit pattern
         self.hits = torch.zeros((n_slots,), dtype=torch.int32, device=device)        # uint32 bit pattern
         self.valid = torch.zeros((n_slots,), dtype=torch.uint8, device=device)
@@ -181,7 +189,8 @@ class Bank:
         return BankDesc(self.n_slots, self.k, self.S, self.d, self.n_act_slots, dtype_code(self.dtype), self.policy,
                         _ptr(self.fp), _ptr(self.act), _ptr(self.inv_norm), _ptr(self.act_slot),
                         _ptr(self.last_used), _ptr(self.hits), _ptr(self.valid), self.half_life, self.reval_every,
-                        self.drift_bound, self.rank, _ptr(self.basis), _ptr(self.act_pool))
+                        self.drift_bound, self.rank, _ptr(self.basis), _ptr(self.act_pool), _ptr(self.next_proj),
+                        _ptr(self.next_bias), self.next_k, _ptr(self.next_fp), _ptr(self.next_inv))
 
     def create(self) -> None:
         torch.cuda.synchronize()
@@ -327,10 +336,13 @@ def llmc_layer_workspace_bytes(layer: Layer, B: int, S: int, k: int) -> int:
 class GateBuffers:
     """Optional per-row outputs of the gate, allocated once per (B)."""
 
-    def __init__(self, B: int, device="cuda", d: int = 0):
-        # d > 0: also the buffers that carry the token means of reused rows to the next layer
+    def __init__(self, B: int, device="cuda", d: int = 0, next_k: int = 0, dtype: torch.dtype = torch.bfloat16):
+        # d > 0: also the buffers that carry the token means of reused rows to the next layer;
+        # next_k > 0: and their finished keys under the next layer's fingerprint map
         self.pooled = torch.zeros((B, d), dtype=torch.float32, device=device) if d > 0 else None
         self.pooled_valid = torch.zeros((B,), dtype=torch.uint8, device=device) if d > 0 else None
+        self.key = torch.zeros((B, next_k), dtype=dtype, device=device) if next_k > 0 else None
+        self.key_inv = torch.zeros((B,), dtype=torch.float32, device=device) if next_k > 0 else None
         self.idx = torch.empty((B,), dtype=torch.int32, device=device)
         self.sim = torch.empty((B,), dtype=torch.float32, device=device)
         self.hit = torch.empty((B,), dtype=torch.uint8, device=device)
@@ -339,7 +351,7 @@ class GateBuffers:
 
     def struct(self) -> GateOut:
         return GateOut(_ptr(self.idx), _ptr(self.sim), _ptr(self.hit), _ptr(self.counters), _ptr(self.slots),
-                       _ptr(self.pooled), _ptr(self.pooled_valid))
+                       _ptr(self.pooled), _ptr(self.pooled_valid), _ptr(self.key), _ptr(self.key_inv))
 
 
 def llmc_layer_forward_gated(layer: Layer, bank: Optional[Bank], proj: Optional[torch.Tensor],
@@ -353,7 +365,9 @@ def llmc_layer_forward_gated(layer: Layer, bank: Optional[Bank], proj: Optional[
     ld = layer.desc()
     fpd = FpDesc(_ptr(proj), _ptr(bias), proj.shape[1] if proj is not None else 0,
                  _ptr(carry.pooled) if carry is not None else None,
-                 _ptr(carry.pooled_valid) if carry is not None else None)
+                 _ptr(carry.pooled_valid) if carry is not None else None,
+                 _ptr(carry.key) if carry is not None else None,
+                 _ptr(carry.key_inv) if carry is not None else None)
     go = out.struct() if out is not None else None
     _check(lib().llmc_layer_forward_gated(
         C.byref(ld), bank.handle if bank is not None else None, C.byref(fpd), _ptr(h_in), _ptr(h_out), B, S, tau,

@@ -908,7 +908,8 @@ def test_carried_token_means_change_nothing(L, dtype):
     ws = W.make_layer_weights(cfg, seed=0)
     tok, pos = W.make_embeddings(cfg, seed=0)
     Ps = W.make_projection(cfg.d, cfg.k, cfg.torch_dtype, seed=3, n_layers=cfg.n_layers)
-    stacks = [GatedStack(cfg, ws, Ps, keep_means=km) for km in (False, True)]
+    stacks = [GatedStack(cfg, ws, Ps, keep_means=km, keep_next_keys=kk)
+              for km, kk in ((False, False), (True, False), (True, True))]
     src = W.make_sources(cfg, 16, seed=1)
     fresh = W.make_sources(cfg, 8, seed=9)
     batches = [(src[0:8], 2.0, L.INSERT_ON_MISS), (src[8:16], 2.0, L.INSERT_ON_MISS),
@@ -920,17 +921,20 @@ def test_carried_token_means_change_nothing(L, dtype):
         outs = [st.forward(h0, tau=tau, flags=flags, tick=tick, keep_all=True) for st in stacks]
         torch.cuda.synchronize()
         for l in range(cfg.n_layers):
-            a, b = stacks[0].gate[l], stacks[1].gate[l]
+          for other in (1, 2):
+            a, b = stacks[0].gate[l], stacks[other].gate[l]
             assert torch.equal(a.hit, b.hit) and torch.equal(a.idx, b.idx) and torch.equal(a.sim, b.sim), (tick, l)
             assert torch.equal(a.counters, b.counters)
-            assert torch.equal(outs[0][l], outs[1][l]), (tick, l)
+            assert torch.equal(outs[0][l], outs[other][l]), (tick, l)
             assert torch.equal(b.pooled_valid, b.hit)
-            assert torch.equal(stacks[0].banks[l].act, stacks[1].banks[l].act)
-            assert torch.equal(stacks[0].banks[l].fp, stacks[1].banks[l].fp)
+            assert torch.equal(stacks[0].banks[l].act, stacks[other].banks[l].act)
+            assert torch.equal(stacks[0].banks[l].fp, stacks[other].banks[l].fp)
             hit_rows = torch.nonzero(b.hit).flatten()
             if len(hit_rows):
-                want = stacks[1].banks[l].act_pool[b.idx[hit_rows].long()]
+                want = stacks[other].banks[l].act_pool[b.idx[hit_rows].long()]
                 assert torch.equal(b.pooled[hit_rows], want)
+                if b.key is not None:
+                    assert torch.equal(b.key[hit_rows], stacks[other].banks[l].next_fp[b.idx[hit_rows].long()])
         say(f"  batch {tick}: hits per layer {[int(g.hit.sum()) for g in stacks[1].gate]}")
     # stored means = the pooling arithmetic on the stored outputs (recomputed by the library), and = the plain mean
     bk = stacks[1].banks[1]
@@ -942,6 +946,24 @@ def test_carried_token_means_change_nothing(L, dtype):
     assert torch.equal(bk.act_pool[v], stored[v])
     ref = npf(bk.act)[v.cpu().numpy()].astype(np.float64).mean(axis=1)
     np.testing.assert_allclose(npf(bk.act_pool[v]), ref, rtol=0, atol=1e-5 * max(1.0, np.abs(ref).max()))
+    # stored next-layer keys = the fingerprint of the stored outputs under the next layer's map, bit for bit,
+    # both as written at insertion and as recomputed by llmc_bank_pool_values
+    bk = stacks[2].banks[0]
+    assert bk.next_fp is not None and stacks[2].banks[cfg.n_layers - 1].next_fp is None
+    v = bk.valid.bool()
+    acts = bk.act[v].contiguous()
+    n = acts.shape[0]
+    fp = torch.empty((n, cfg.k), dtype=cfg.torch_dtype, device="cuda")
+    inv = torch.empty((n,), dtype=torch.float32, device="cuda")
+    wsf = torch.empty((L.llmc_fingerprint_workspace_bytes(n, cfg.S, cfg.d),), dtype=torch.uint8, device="cuda")
+    L.llmc_fingerprint(acts, stacks[2].proj[1], None, fp, inv, wsf)
+    torch.cuda.synchronize()
+    assert torch.equal(bk.next_fp[v], fp) and torch.equal(bk.next_inv[v], inv)
+    bk.next_fp.zero_()
+    bk.next_inv.zero_()
+    L.llmc_bank_pool_values(bk)
+    torch.cuda.synchronize()
+    assert torch.equal(bk.next_fp[v], fp) and torch.equal(bk.next_inv[v], inv)
     for st in stacks:
         st.close()
 
