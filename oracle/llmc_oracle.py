@@ -363,8 +363,10 @@ class Bank:
 
     def __init__(self, n_slots: int, k: int, S: int, d: int, dtype: str,
                  n_act_slots: Optional[int] = None, lru: bool = True, decayed_hits: bool = False,
-                 half_life: int = 0, basis: Optional[np.ndarray] = None):
+                 half_life: int = 0, basis: Optional[np.ndarray] = None, key_bits: bool = False):
         A = n_slots if n_act_slots is None else n_act_slots
+        # sign-bit keys: fp holds k / 32 uint32 words per entry, compared by Hamming distance
+        self.key_bits = key_bits
         self.N, self.k, self.S, self.d, self.A = n_slots, k, S, d, A
         self.dtype = dtype
         # compressed cached values (Section III-B: "optionally compresses cached representations via PCA"):
@@ -379,7 +381,7 @@ class Bank:
         self.decayed_hits = decayed_hits
         self.half_life = half_life
         self.epoch = 0
-        self.fp = np.zeros((n_slots, k), dtype=np.float32)
+        self.fp = np.zeros((n_slots, k // 32), dtype=np.uint32) if key_bits else np.zeros((n_slots, k), dtype=np.float32)
         self.inv_norm = np.zeros((n_slots,), dtype=np.float32)
         self.act = np.zeros((A, S, d if basis is None else self.rank), dtype=np.float32)
         self.act_slot = np.arange(n_slots, dtype=np.int32) if A == n_slots else np.zeros((n_slots,), np.int32)
@@ -522,12 +524,20 @@ def gated_layer(h_in: np.ndarray, bank: Optional[Bank], P: Optional[np.ndarray],
             h_out[b] = layer_forward(h_in[b], w, arch, n_heads, eps, gelu_kind)
         return GateResult(h_out, np.zeros((B, 0), np.float32), np.zeros((B,), np.float32),
                           np.full((B,), -1, np.int32), np.full((B,), -np.inf), np.zeros((B,), bool), [], 0)
-    if fp_override is not None:
-        q, qinv = fp_override
+    if bank.key_bits:
+        # sign-bit keys: Hamming match, threshold on the cosine that the distance stands for
+        q = fp_override[0] if fp_override is not None else fingerprint_bits(h_in, P, c)
+        qinv = np.zeros((B,), np.float32)
+        idx, dist = match_bits(q, bank.fp, bank.valid, bank.k)
+        hit = threshold_bits(idx, dist, max_hamming(tau, bank.k))
+        sim = np.where(idx >= 0, cosine_estimate(np.minimum(dist, bank.k), bank.k), -np.inf)
     else:
-        q, qinv = fingerprint(h_in, P, c, bank.dtype)
-    idx, sim = match(q, qinv, bank.fp, bank.inv_norm, bank.valid)
-    hit = threshold(sim, tau)
+        if fp_override is not None:
+            q, qinv = fp_override
+        else:
+            q, qinv = fingerprint(h_in, P, c, bank.dtype)
+        idx, sim = match(q, qinv, bank.fp, bank.inv_norm, bank.valid)
+        hit = threshold(sim, tau)
     revalidated: List[int] = []
     divergence: List[float] = []
     refreshed: List[int] = []

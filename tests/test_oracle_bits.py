@@ -144,3 +144,31 @@ def test_bit_match_finds_the_cosine_neighbour_on_separated_clusters():
     idx_c, sim = O.match(fq, iq, fb, ib, np.ones(n_cl, np.uint8))
     assert np.array_equal(idx_b, idx_c)
     assert np.max(np.abs(O.cosine_estimate(dist, k) - sim)) < 0.15
+
+
+def test_gated_layer_with_sign_bit_bank():
+    """A bank of sign-bit keys in the gate: resubmitted inputs hit at distance 0 and return the stored values,
+    tau >= 1 computes everything, inserted keys are the inputs' sign bits."""
+    g = rng(8)
+    S, d, k, N, B = 4, 32, 64, 10, 6
+    w = {"wqkv": g.standard_normal((3 * d, d)) * 0.05, "bqkv": np.zeros(3 * d), "wo": g.standard_normal((d, d)) * 0.05,
+         "bo": np.zeros(d), "w1": g.standard_normal((2 * d, d)) * 0.05, "b1": np.zeros(2 * d),
+         "w2": g.standard_normal((d, 2 * d)) * 0.05, "b2": np.zeros(d), "ln1_g": np.ones(d), "ln1_b": np.zeros(d),
+         "ln2_g": np.ones(d), "ln2_b": np.zeros(d)}
+    P = g.standard_normal((d, k)) / np.sqrt(k)
+    h = g.standard_normal((B, S, d))
+    bank = O.Bank(N, k, S, d, "f32", key_bits=True)
+    assert bank.fp.shape == (N, 2) and bank.fp.dtype == np.uint32
+    r1 = O.gated_layer(h, bank, P, None, w, O.ENCODER_POST_LN, 2, 1e-5, O.GELU_ERF, 0.95, flags=O.FLAG_INSERT_ON_MISS, tick=1)
+    assert not r1.hit.any() and r1.slots == list(range(B))
+    assert np.array_equal(bank.fp[:B], O.fingerprint_bits(h, P, None))
+    r2 = O.gated_layer(h, bank, P, None, w, O.ENCODER_POST_LN, 2, 1e-5, O.GELU_ERF, 0.95)
+    assert r2.hit.all() and np.array_equal(r2.idx, np.arange(B)) and np.allclose(r2.sim, 1.0)
+    np.testing.assert_allclose(r2.h_out, r1.h_out, atol=1e-6)
+    r3 = O.gated_layer(h, bank, P, None, w, O.ENCODER_POST_LN, 2, 1e-5, O.GELU_ERF, 1.0)
+    assert not r3.hit.any()
+    np.testing.assert_allclose(r3.h_out, r1.h_out, atol=1e-12)
+    # against a bank holding only entry 0, the negated input has every sign flipped: distance k, cosine estimate -1
+    bank.valid[1:] = 0
+    r4 = O.gated_layer(-h[:1], bank, P, None, w, O.ENCODER_POST_LN, 2, 1e-5, O.GELU_ERF, -0.5)
+    assert not r4.hit.any() and r4.idx[0] == 0 and np.allclose(r4.sim, -1.0)
