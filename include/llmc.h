@@ -157,6 +157,12 @@ typedef struct {
   int32_t next_k;
   void* d_next_fp;
   float* d_next_inv;
+  /* key_bits = 1: the keys are SIGN BITS (SimHash, see llmc_fingerprint_bits): d_fp is uint32 [n_slots, k / 32],
+   * d_inv_norm is not used (may be NULL), the match is by Hamming distance and the threshold of
+   * llmc_layer_forward_gated is applied as H <= llmc_max_hamming(tau, k); the similarity reported is cos(pi H / k).
+   * llmc_bank_insert and d_fp_given then take keys in that form (d_inv_norm / d_inv_norm_given ignored);
+   * llmc_match refuses such a bank (use llmc_match_bits).  Refused together with stored next-layer keys. */
+  int32_t key_bits;
 } llmc_bank_desc_t;
 
 /*

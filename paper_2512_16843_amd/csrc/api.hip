@@ -104,8 +104,12 @@ llmc_status_t llmc_bank_create(const llmc_bank_desc_t* desc, llmc_bank_t** out) 
   REQUIRE(desc->n_act_slots <= desc->n_slots, LLMC_ERR_SHAPE, "n_act_slots > n_slots");
   REQUIRE(desc->d_act_slot || desc->n_act_slots == desc->n_slots, LLMC_ERR_SHAPE,
           "identity value map needs n_act_slots == n_slots");
-  REQUIRE(desc->d_fp && desc->d_act && desc->d_inv_norm && desc->d_last_used && desc->d_hits && desc->d_valid,
+  REQUIRE(desc->key_bits == 0 || desc->key_bits == 1, LLMC_ERR_INVALID_ARG, "key_bits must be 0 or 1");
+  REQUIRE(desc->d_fp && desc->d_act && (desc->d_inv_norm || desc->key_bits) && desc->d_last_used && desc->d_hits &&
+              desc->d_valid,
           LLMC_ERR_INVALID_ARG, "a bank array pointer is NULL");
+  REQUIRE(!(desc->key_bits && desc->d_next_fp), LLMC_ERR_INVALID_ARG,
+          "stored next-layer keys are refused on a bank of sign-bit keys");
   REQUIRE(aligned16(desc->d_fp) && aligned16(desc->d_act), LLMC_ERR_SHAPE, "bank arrays must be 16-byte aligned");
   REQUIRE(!(desc->d_act_pool && desc->rank > 0), LLMC_ERR_INVALID_ARG,
           "stored token means are refused together with compressed values");
@@ -134,7 +138,7 @@ llmc_status_t llmc_bank_create(const llmc_bank_desc_t* desc, llmc_bank_t** out) 
   hipError_t e = hipGetDevice(&b->device);
   b->d_basis_t = nullptr;
   b->d_hit_slots = nullptr;
-  if (e == hipSuccess) e = hipMalloc((void**)&b->d_binv_eff, align_up((size_t)desc->n_slots, 256) * sizeof(float));
+  if (e == hipSuccess) e = hipMalloc((void**)&b->d_binv_eff, align_up((size_t)desc->n_slots + 8, 256) * sizeof(float));
   if (e == hipSuccess && desc->rank > 0) {
     e = hipMalloc(&b->d_basis_t, (size_t)desc->rank * desc->d * elem_size(desc->dtype));
     if (e == hipSuccess) e = hipMalloc((void**)&b->d_hit_slots, 65536 * sizeof(int32_t));
@@ -184,7 +188,8 @@ llmc_status_t llmc_bank_refresh(llmc_bank_t* bank, llmc_stream_t stream) {
 llmc_status_t llmc_bank_insert(llmc_bank_t* bank, const void* d_fp, const float* d_inv_norm, const void* d_act,
                                const int32_t* d_rows, const int32_t* d_m, int32_t m_max, uint64_t tick,
                                int32_t* d_slots_out, int32_t* d_counters, llmc_stream_t stream) {
-  REQUIRE(bank && d_fp && d_inv_norm && d_act && d_slots_out, LLMC_ERR_INVALID_ARG, "NULL argument");
+  REQUIRE(bank && d_fp && d_act && d_slots_out, LLMC_ERR_INVALID_ARG, "NULL argument");
+  REQUIRE(d_inv_norm || bank->desc.key_bits, LLMC_ERR_INVALID_ARG, "d_inv_norm is NULL");
   REQUIRE(m_max > 0 && m_max <= LLMC_MAX_UPDATE_ROWS, LLMC_ERR_SHAPE, "m_max=%d out of range 1..%d", m_max,
           LLMC_MAX_UPDATE_ROWS);
   REQUIRE(tick <= LLMC_MAX_TICK, LLMC_ERR_INVALID_ARG, "tick out of range");
@@ -307,6 +312,7 @@ llmc_status_t llmc_match(const llmc_bank_t* bank, const void* d_fp, const float*
                          int32_t* d_idx, float* d_sim, uint8_t* d_hit, uint8_t* d_near_tie, void* d_workspace,
                          size_t workspace_bytes, llmc_stream_t stream) {
   REQUIRE(bank && d_fp && d_inv_norm && d_idx, LLMC_ERR_INVALID_ARG, "NULL argument");
+  REQUIRE(!bank->desc.key_bits, LLMC_ERR_DTYPE, "the bank holds sign-bit keys: use llmc_match_bits");
   REQUIRE(B > 0, LLMC_ERR_INVALID_ARG, "B must be positive");
   REQUIRE(B <= 65535 * 128, LLMC_ERR_SHAPE, "B=%d too large", B);
   REQUIRE(tau == tau, LLMC_ERR_INVALID_ARG, "tau is NaN");
@@ -413,7 +419,7 @@ llmc_status_t llmc_layer_forward_gated(const llmc_layer_desc_t* layer, llmc_bank
             S, layer->d);
     k = D.k;
     if (d_fp_given) {
-      REQUIRE(d_inv_norm_given, LLMC_ERR_INVALID_ARG, "given keys need their inverse norms");
+      REQUIRE(d_inv_norm_given || D.key_bits, LLMC_ERR_INVALID_ARG, "given keys need their inverse norms");
       REQUIRE(aligned16(d_fp_given), LLMC_ERR_SHAPE, "given keys must be 16-byte aligned");
     } else {
       REQUIRE(fp && fp->d_proj, LLMC_ERR_INVALID_ARG, "fingerprint descriptor is NULL");
@@ -479,7 +485,15 @@ llmc_status_t llmc_layer_forward_gated(const llmc_layer_desc_t* layer, llmc_bank
   if (flags & (LLMC_INSERT_ON_MISS | LLMC_UPDATE_LRU)) LLMC_TRY(launch_bank_advance(bank, tick, st));
   const void* q = d_fp_given;
   const float* qinv = d_inv_norm_given;
-  if (!q) {
+  const bool bits = bank->desc.key_bits != 0;
+  if (!q && bits) {
+    // sign-bit keys (the words live in the key buffer); carried token means are honoured, carried keys are not
+    const bool carried = fp->d_pooled_in && fp->d_pooled_in_valid;
+    LLMC_TRY(launch_fingerprint_bits(d_h_in, B, S, layer->d, layer->dtype, fp->d_proj, fp->d_bias, k, (uint32_t*)keys,
+                                     ws_fp, st, carried ? fp->d_pooled_in : nullptr,
+                                     carried ? fp->d_pooled_in_valid : nullptr));
+    q = keys;
+  } else if (!q) {
     const bool keys_in = fp->d_key_in && fp->d_key_inv_in && fp->d_pooled_in_valid;
     const bool carried = (fp->d_pooled_in || keys_in) && fp->d_pooled_in_valid;
     LLMC_TRY(launch_fingerprint(d_h_in, nullptr, B, S, layer->d, layer->dtype, fp->d_proj, fp->d_bias, k, keys, inv,
@@ -489,7 +503,14 @@ llmc_status_t llmc_layer_forward_gated(const llmc_layer_desc_t* layer, llmc_bank
     q = keys;
     qinv = inv;
   }
-  LLMC_TRY(launch_match(bank, q, qinv, B, tau, idx, sim, hit, tie, ws_match, st));
+  if (bits) {
+    LLMC_TRY(launch_match_bits((const uint32_t*)bank->desc.d_fp, bank->desc.d_valid, bank->desc.n_slots, k,
+                               (const uint32_t*)q, B, llmc_max_hamming(tau, k), idx, nullptr, hit, ws_match, st,
+                               (const uint32_t*)bank->d_binv_eff, sim));
+    tie = nullptr;
+  } else {
+    LLMC_TRY(launch_match(bank, q, qinv, B, tau, idx, sim, hit, tie, ws_match, st));
+  }
   float* pooled_out = nullptr;
   uint8_t* pooled_valid_out = nullptr;
   void* key_out = nullptr;

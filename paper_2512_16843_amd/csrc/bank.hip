@@ -16,10 +16,17 @@ namespace llmc {
 
 constexpr int kSelThreads = 1024;
 
+// The library's per-slot mirror: for real-valued keys the inverse norm of a valid slot and NaN for a free one;
+// for sign-bit keys the start value of the popcount chain, 0 for a valid slot and kBitsFreePenalty for a free one.
+constexpr uint32_t kBitsFreePenalty = 2048;
+
 __global__ void refresh_kernel(const uint8_t* __restrict__ valid, const float* __restrict__ inv_norm, int N, int n_pad,
-                               float* __restrict__ binv_eff) {
+                               float* __restrict__ binv_eff, int key_bits) {
   const int j = blockIdx.x * blockDim.x + threadIdx.x;
-  if (j < n_pad) binv_eff[j] = (j < N && valid[j]) ? inv_norm[j] : NAN;
+  if (j >= n_pad) return;
+  const bool v = j < N && valid[j];
+  if (key_bits) reinterpret_cast<uint32_t*>(binv_eff)[j] = v ? 0u : kBitsFreePenalty;
+  else binv_eff[j] = v ? inv_norm[j] : NAN;
 }
 
 // policy 2 (decayed hits): (min(hits, 65535) << 48) | ((last_used + 1) << 24) | slot, with n_slots <= 2^24 and
@@ -76,7 +83,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(uint8_t* valid, con
                                                              const uint32_t* __restrict__ hits, int by_hits,
                                                              int N, const int32_t* d_m, int m_max, int mode_evict,
                                                              int allow_replace, int32_t* __restrict__ slots_out,
-                                                             float* binv_eff) {
+                                                             float* binv_eff, uint32_t free_mark) {
   extern __shared__ uint64_t list[];      // [m_max]
   __shared__ unsigned hist[kSelBins];
   __shared__ unsigned wave_tot[kSelThreads / 64];
@@ -203,7 +210,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(uint8_t* valid, con
     slots_out[rank] = slot;
     if (mode_evict) {
       valid[slot] = 0;
-      binv_eff[slot] = NAN;
+      reinterpret_cast<uint32_t*>(binv_eff)[slot] = free_mark;     // NaN, or the popcount penalty of a free slot
     }
   }
 }
@@ -215,7 +222,7 @@ static void launch_select(const llmc_bank* bank, const int32_t* d_m, int m_max, 
   const size_t lds = (size_t)m_max * sizeof(uint64_t);
 #define LLMC_SELECT(KPT_) hipLaunchKernelGGL(select_kernel<KPT_>, dim3(1), dim3(kSelThreads), lds, st, D.d_valid,         \
                                              D.d_last_used, D.d_hits, by_hits, N, d_m, m_max, mode_evict, allow_replace, \
-                                             slots_out, bank->d_binv_eff)
+                                             slots_out, bank->d_binv_eff, D.key_bits ? kBitsFreePenalty : 0x7FC00000u)
   if (N <= 4 * kSelThreads) LLMC_SELECT(4);
   else if (N <= 16 * kSelThreads) LLMC_SELECT(16);
   else if (N <= 48 * kSelThreads) LLMC_SELECT(48);
@@ -245,8 +252,8 @@ __global__ __launch_bounds__(kCopyThreads) void insert_kernel(
     const u32x4_t* __restrict__ fp_src, const float* __restrict__ inv_src, const u32x4_t* __restrict__ act_src,
     const int32_t* __restrict__ rows, const int32_t* d_m, int m_max, const int32_t* __restrict__ slots,
     u32x4_t* __restrict__ bank_fp, float* bank_inv, u32x4_t* __restrict__ bank_act, const int32_t* act_slot,
-    uint64_t* last_used, uint32_t* hits, uint8_t* valid, float* binv_eff, size_t vec_per_key, size_t vec_per_seq,
-    uint64_t tick, int32_t* counters) {
+    uint64_t* last_used, uint32_t* hits, uint8_t* valid, float* binv_eff, size_t words_per_key, size_t vec_per_seq,
+    uint64_t tick, int32_t* counters, int key_bits) {
   int m = d_m ? *d_m : m_max;
   m = max(0, min(m, m_max));
   const int i = blockIdx.y;
@@ -274,13 +281,18 @@ __global__ __launch_bounds__(kCopyThreads) void insert_kernel(
     if (v < vec_per_seq) __builtin_nontemporal_store(regs[u], dst + v);
   }
   if (first) {
-    for (size_t v = threadIdx.x; v < vec_per_key; v += kCopyThreads)
-      bank_fp[(size_t)slot * vec_per_key + v] = fp_src[(size_t)r * vec_per_key + v];
+    const uint32_t* ksrc = reinterpret_cast<const uint32_t*>(fp_src) + (size_t)r * words_per_key;
+    uint32_t* kdst = reinterpret_cast<uint32_t*>(bank_fp) + (size_t)slot * words_per_key;
+    for (size_t v = threadIdx.x; v < words_per_key; v += kCopyThreads) kdst[v] = ksrc[v];
     if (threadIdx.x == 0) {
-      const float inv = inv_src[r];
       const bool was = valid[slot] != 0;
-      bank_inv[slot] = inv;
-      binv_eff[slot] = inv;
+      if (key_bits) {
+        reinterpret_cast<uint32_t*>(binv_eff)[slot] = 0u;
+      } else {
+        const float inv = inv_src[r];
+        bank_inv[slot] = inv;
+        binv_eff[slot] = inv;
+      }
       last_used[slot] = tick;
       hits[slot] = 0;
       valid[slot] = 1;
@@ -294,9 +306,9 @@ __global__ __launch_bounds__(kCopyThreads) void insert_kernel(
 
 llmc_status_t launch_bank_refresh(llmc_bank* bank, hipStream_t st) {
   const int N = bank->desc.n_slots;
-  const int n_pad = (int)align_up((size_t)N, 256);
+  const int n_pad = (int)align_up((size_t)N + 8, 256);      // the mirror's allocated length
   { ProfScope ps_("refresh_kernel", st); hipLaunchKernelGGL(refresh_kernel, dim3((n_pad + 255) / 256), dim3(256), 0, st, bank->desc.d_valid,
-                     bank->desc.d_inv_norm, N, n_pad, bank->d_binv_eff); }
+                     bank->desc.d_inv_norm, N, n_pad, bank->d_binv_eff, bank->desc.key_bits); }
   LLMC_LAUNCH_CHECK("refresh_kernel");
   return LLMC_OK;
 }
@@ -316,12 +328,14 @@ llmc_status_t launch_bank_insert(llmc_bank* bank, const void* d_fp, const float*
     LLMC_TRY(launch_linear(d_act, D.d, d_rows, D.d_basis, nullptr, D.rank, D.d, D.d_act, D.rank, d_slots_out, D.S, d_m,
                            m_max, D.dtype, st));
   }
-  const size_t vec_per_seq = D.rank > 0 ? 0 : (size_t)D.S * D.d * e / 16, vec_per_key = (size_t)D.k * e / 16;
+  const size_t vec_per_seq = D.rank > 0 ? 0 : (size_t)D.S * D.d * e / 16;
+  const size_t words_per_key = D.key_bits ? (size_t)D.k / 32 : (size_t)D.k * e / 4;
   const size_t per_wg = (size_t)kCopyThreads * kCopyVecPerThread;
   dim3 grid((unsigned)std::max<size_t>(1, (vec_per_seq + per_wg - 1) / per_wg), m_max);
   { ProfScope ps_("insert_kernel", st); hipLaunchKernelGGL(insert_kernel, grid, dim3(kCopyThreads), 0, st, (const u32x4_t*)d_fp, d_inv, (const u32x4_t*)d_act,
                      d_rows, d_m, m_max, d_slots_out, (u32x4_t*)D.d_fp, D.d_inv_norm, (u32x4_t*)D.d_act, D.d_act_slot,
-                     D.d_last_used, D.d_hits, D.d_valid, bank->d_binv_eff, vec_per_key, vec_per_seq, tick, d_counters); }
+                     D.d_last_used, D.d_hits, D.d_valid, bank->d_binv_eff, words_per_key, vec_per_seq, tick, d_counters,
+                     D.key_bits); }
   LLMC_LAUNCH_CHECK("insert_kernel");
   // the token mean of every stored output, kept beside it (dropped rows have slot -1 and are skipped)
   if (D.d_act_pool)

@@ -87,7 +87,8 @@ __global__ __launch_bounds__(kBitsThreads) void match_bits_generic_kernel(const 
 // lowest slot is kept among equals), then apply the threshold
 __global__ void match_bits_finalize_kernel(const uint32_t* __restrict__ partial, int n_split, int rows_per_split, int B,
                                            int max_hamming, int32_t* __restrict__ idx_out,
-                                           int32_t* __restrict__ dist_out, uint8_t* __restrict__ hit_out) {
+                                           int32_t* __restrict__ dist_out, uint8_t* __restrict__ hit_out,
+                                           float* __restrict__ sim_out, int k) {
   const int b = blockIdx.x * blockDim.x + threadIdx.x;
   if (b >= B) return;
   uint32_t best_h = 0xFFFFFFFFu;
@@ -110,6 +111,8 @@ __global__ void match_bits_finalize_kernel(const uint32_t* __restrict__ partial,
   idx_out[b] = found ? best_row : -1;
   if (dist_out) dist_out[b] = found ? (int32_t)best_h : 0x7FFFFFFF;
   if (hit_out) hit_out[b] = (found && (int32_t)best_h <= max_hamming) ? 1 : 0;
+  // the cosine that the distance stands for (informative: the decision above is the integer one)
+  if (sim_out) sim_out[b] = found ? cosf(3.14159265358979323846f * (float)best_h / (float)k) : -INFINITY;
 }
 
 static void bits_plan(int N, int B, int* n_split, int* rows_per_split) {
@@ -131,17 +134,22 @@ size_t match_bits_ws_bytes(int N, int k, int B) {
   return align_up((size_t)ns * B * sizeof(uint32_t), 256) + align_up((size_t)(N + kRowUnroll) * sizeof(uint32_t), 256);
 }
 
+// d_pen: ready-made penalty words [N + kRowUnroll] (a bank's mirror), or NULL to derive them from d_valid into ws
 llmc_status_t launch_match_bits(const uint32_t* d_bank_bits, const uint8_t* d_valid, int N, int k,
                                 const uint32_t* d_query_bits, int B, int max_hamming, int32_t* d_idx, int32_t* d_dist,
-                                uint8_t* d_hit, void* ws, hipStream_t st) {
+                                uint8_t* d_hit, void* ws, hipStream_t st, const uint32_t* d_pen, float* d_sim) {
   int ns, per;
   bits_plan(N, B, &ns, &per);
   uint32_t* partial = (uint32_t*)ws;
-  uint32_t* pen = (uint32_t*)((char*)ws + align_up((size_t)ns * B * sizeof(uint32_t), 256));
-  const int n_pad = N + kRowUnroll;
-  { ProfScope ps_("bits_penalty_kernel", st);
-    hipLaunchKernelGGL(bits_penalty_kernel, dim3((n_pad + 255) / 256), dim3(256), 0, st, d_valid, N, n_pad, pen); }
-  LLMC_LAUNCH_CHECK("bits_penalty_kernel");
+  const uint32_t* pen = d_pen;
+  if (!pen) {
+    uint32_t* mine = (uint32_t*)((char*)ws + align_up((size_t)ns * B * sizeof(uint32_t), 256));
+    const int n_pad = N + kRowUnroll;
+    { ProfScope ps_("bits_penalty_kernel", st);
+      hipLaunchKernelGGL(bits_penalty_kernel, dim3((n_pad + 255) / 256), dim3(256), 0, st, d_valid, N, n_pad, mine); }
+    LLMC_LAUNCH_CHECK("bits_penalty_kernel");
+    pen = mine;
+  }
   const int W = k / 32;
   dim3 grid(ns, (B + kBitsThreads - 1) / kBitsThreads);
   {
@@ -160,7 +168,7 @@ llmc_status_t launch_match_bits(const uint32_t* d_bank_bits, const uint8_t* d_va
   LLMC_LAUNCH_CHECK("match_bits_kernel");
   { ProfScope ps_("match_bits_finalize_kernel", st);
     hipLaunchKernelGGL(match_bits_finalize_kernel, dim3((B + 255) / 256), dim3(256), 0, st, partial, ns, per, B,
-                       max_hamming, d_idx, d_dist, d_hit); }
+                       max_hamming, d_idx, d_dist, d_hit, d_sim, k); }
   LLMC_LAUNCH_CHECK("match_bits_finalize_kernel");
   return LLMC_OK;
 }

@@ -167,11 +167,13 @@ llmc_status_t launch_project_rows(const float* d_means, int n_max, int d, int dt
 llmc_status_t launch_pool_rows(const void* d_h, int n_max, int S, int d, int dtype, const int32_t* d_rows,
                                const int32_t* d_count, const int32_t* d_dst, float* d_out, hipStream_t st);
 llmc_status_t launch_fingerprint_bits(const void* d_h, int B, int S, int d, int dtype, const void* d_proj,
-                                      const float* d_bias, int k, uint32_t* d_bits, void* ws, hipStream_t st);
+                                      const float* d_bias, int k, uint32_t* d_bits, void* ws, hipStream_t st,
+                                      const float* pooled_in = nullptr, const uint8_t* pooled_valid = nullptr);
 size_t match_bits_ws_bytes(int N, int k, int B);
 llmc_status_t launch_match_bits(const uint32_t* d_bank_bits, const uint8_t* d_valid, int N, int k,
                                 const uint32_t* d_query_bits, int B, int max_hamming, int32_t* d_idx, int32_t* d_dist,
-                                uint8_t* d_hit, void* ws, hipStream_t st);
+                                uint8_t* d_hit, void* ws, hipStream_t st, const uint32_t* d_pen = nullptr,
+                                float* d_sim = nullptr);
 llmc_status_t launch_inv_norm(const void* d_fp, int64_t n, int k, int dtype, float* d_out, hipStream_t st);
 
 // match.hip

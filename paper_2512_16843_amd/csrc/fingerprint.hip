@@ -385,12 +385,13 @@ llmc_status_t launch_pool_rows(const void* d_h, int n_max, int S, int d, int dty
 
 // same pooling and projection, but the key is the sign of each projection
 llmc_status_t launch_fingerprint_bits(const void* d_h, int B, int S, int d, int dtype, const void* d_proj,
-                                      const float* d_bias, int k, uint32_t* d_bits, void* ws, hipStream_t st) {
+                                      const float* d_bias, int k, uint32_t* d_bits, void* ws, hipStream_t st,
+                                      const float* pooled_in, const uint8_t* pooled_valid) {
   if (dtype == LLMC_F32)
     return fingerprint_t<float>((const float*)d_h, B, S, d, (const float*)d_proj, d_bias, k, nullptr, nullptr, d_bits,
-                                (float*)ws, nullptr, nullptr, st);
+                                (float*)ws, pooled_in, pooled_valid, st);
   return fingerprint_t<bf16_t>((const bf16_t*)d_h, B, S, d, (const bf16_t*)d_proj, d_bias, k, nullptr, nullptr, d_bits,
-                               (float*)ws, nullptr, nullptr, st);
+                               (float*)ws, pooled_in, pooled_valid, st);
 }
 
 llmc_status_t launch_inv_norm(const void* d_fp, int64_t n, int k, int dtype, float* d_out, hipStream_t st) {

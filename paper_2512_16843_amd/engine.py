@@ -19,7 +19,7 @@ class GatedStack:
                  biases: Optional[List[Optional[torch.Tensor]]] = None, n_bank: Optional[int] = None,
                  policy: int = llmc.EVICT_LRU, B: Optional[int] = None, half_life: int = 0, reval_every: int = 0,
                  drift_bound: float = 0.0, bases: Optional[List[Optional[torch.Tensor]]] = None,
-                 keep_means: bool = False, keep_next_keys: bool = False):
+                 keep_means: bool = False, keep_next_keys: bool = False, key_bits: bool = False):
         self.cfg = cfg
         self.device = device
         self.B = cfg.B if B is None else B
@@ -31,7 +31,7 @@ class GatedStack:
         self.banks: List[Optional[llmc.Bank]] = [None] * cfg.n_layers
         cached = list(cached)
         # keep_next_keys (with keep_means): bank l also stores each cached output's key under layer l + 1's map
-        self.keep_next_keys = keep_next_keys and keep_means
+        self.keep_next_keys = keep_next_keys and keep_means and not key_bits
         for l in cached:
             nxt = l + 1 if (self.keep_next_keys and l + 1 < cfg.n_layers and (l + 1) in cached) else None
             self.banks[l] = llmc.Bank(n_bank, cfg.k, cfg.S, cfg.d, cfg.torch_dtype, device, policy=policy,
@@ -39,7 +39,7 @@ class GatedStack:
                                       basis=None if bases is None or bases[l] is None else
                                       bases[l].to(device).contiguous(), keep_means=keep_means,
                                       next_proj=None if nxt is None else self.proj[nxt],
-                                      next_bias=None if nxt is None else self.bias[nxt])
+                                      next_bias=None if nxt is None else self.bias[nxt], key_bits=key_bits)
         ws_bytes = llmc.llmc_layer_workspace_bytes(self.layers[0], self.B, cfg.S, cfg.k)
         self.workspace = torch.empty((ws_bytes,), dtype=torch.uint8, device=device)
         self.buf = [torch.empty((self.B, cfg.S, cfg.d), dtype=cfg.torch_dtype, device=device) for _ in range(2)]

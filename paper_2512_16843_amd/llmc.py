@@ -43,7 +43,8 @@ class BankDesc(C.Structure):
                 ("d_valid", C.c_void_p), ("half_life", C.c_int32), ("reval_every", C.c_int32),
                 ("drift_bound", C.c_float), ("rank", C.c_int32), ("d_basis", C.c_void_p),
                 ("d_act_pool", C.c_void_p), ("d_next_proj", C.c_void_p), ("d_next_bias", C.c_void_p),
-                ("next_k", C.c_int32), ("d_next_fp", C.c_void_p), ("d_next_inv", C.c_void_p)]
+                ("next_k", C.c_int32), ("d_next_fp", C.c_void_p), ("d_next_inv", C.c_void_p),
+                ("key_bits", C.c_int32)]
 
 
 class LayerDesc(C.Structure):
@@ -159,11 +160,14 @@ class Bank:
                  n_act_slots: Optional[int] = None, policy: int = EVICT_LRU,
                  act_slot: Optional[torch.Tensor] = None, half_life: int = 0, reval_every: int = 0,
                  drift_bound: float = 0.0, basis: Optional[torch.Tensor] = None, keep_means: bool = False,
-                 next_proj: Optional[torch.Tensor] = None, next_bias: Optional[torch.Tensor] = None):
+                 next_proj: Optional[torch.Tensor] = None, next_bias: Optional[torch.Tensor] = None,
+                 key_bits: bool = False):
         A = n_slots if n_act_slots is None else n_act_slots
         self.n_slots, self.k, self.S, self.d, self.n_act_slots = n_slots, k, S, d, A
         self.dtype = dtype
-        self.fp = torch.zeros((n_slots, k), dtype=dtype, device=device)
+        self.key_bits = key_bits          # keys are sign bits: int32 words [n_slots, k / 32]
+        self.fp = torch.zeros((n_slots, k // 32), dtype=torch.int32, device=device) if key_bits else \
+            torch.zeros((n_slots, k), dtype=dtype, device=device)
         self.inv_norm = torch.zeros((n_slots,), dtype=torch.float32, device=device)
         self.basis = basis          # [rank, d]: cached values are stored as coefficients on it
         self.rank = 0 if basis is None else int(basis.shape[0])
@@ -190,7 +194,7 @@ class Bank:
                         _ptr(self.fp), _ptr(self.act), _ptr(self.inv_norm), _ptr(self.act_slot),
                         _ptr(self.last_used), _ptr(self.hits), _ptr(self.valid), self.half_life, self.reval_every,
                         self.drift_bound, self.rank, _ptr(self.basis), _ptr(self.act_pool), _ptr(self.next_proj),
-                        _ptr(self.next_bias), self.next_k, _ptr(self.next_fp), _ptr(self.next_inv))
+                        _ptr(self.next_bias), self.next_k, _ptr(self.next_fp), _ptr(self.next_inv), 1 if self.key_bits else 0)
 
     def create(self) -> None:
         torch.cuda.synchronize()

@@ -60,7 +60,7 @@ def test_bank_create_validation(lib):
     def desc(**kw):
         base = dict(n_slots=16, k=32, S=4, d=64, n_act_slots=16, dtype=llmc.BF16, policy=llmc.EVICT_LRU,
                     d_fp=p, d_act=p, d_inv_norm=p, d_act_slot=None, d_last_used=p, d_hits=p, d_valid=p, half_life=0, reval_every=0, drift_bound=0.0, rank=0, d_basis=None, d_act_pool=None, d_next_proj=None, d_next_bias=None, next_k=0, d_next_fp=None,
-                    d_next_inv=None)
+                    d_next_inv=None, key_bits=0)
         base.update(kw)
         return llmc.BankDesc(**base)
 
@@ -74,6 +74,8 @@ def test_bank_create_validation(lib):
     assert lib.llmc_bank_create(C.byref(desc(policy=5)), C.byref(out)) == llmc.ERR_INVALID_ARG
     assert lib.llmc_bank_create(C.byref(desc(d_next_proj=p, d_next_fp=p, d_next_inv=p, next_k=32)), C.byref(out)) == llmc.ERR_INVALID_ARG   # no means
     assert lib.llmc_bank_create(C.byref(desc(d_act_pool=p, d_next_proj=p, d_next_fp=p, d_next_inv=p, next_k=40)), C.byref(out)) == llmc.ERR_SHAPE
+    assert lib.llmc_bank_create(C.byref(desc(key_bits=2)), C.byref(out)) == llmc.ERR_INVALID_ARG
+    assert lib.llmc_bank_create(C.byref(desc(d_inv_norm=None)), C.byref(out)) == llmc.ERR_INVALID_ARG
     assert lib.llmc_bank_create(C.byref(desc(rank=32, d_basis=p)), C.byref(out)) == llmc.ERR_SHAPE
     assert lib.llmc_bank_create(C.byref(desc(rank=128, d_basis=p)), C.byref(out)) == llmc.ERR_SHAPE            # above d = 64
     assert lib.llmc_bank_create(C.byref(desc(rank=64, d_basis=None)), C.byref(out)) == llmc.ERR_INVALID_ARG

@@ -968,6 +968,77 @@ def test_carried_token_means_change_nothing(L, dtype):
         st.close()
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_gated_stack_with_sign_bit_banks(L, dtype):
+    """Banks of sign-bit keys inside the gated layer: keys, matched slots, distances' cosines, decisions, slots taken
+    and outputs against the oracle, layer by layer with the GPU's own layer inputs and bank arrays."""
+    from paper_2512_16843_amd.engine import GatedStack
+    say(f"gated stack with sign-bit banks {dtype}: build by insertion, resubmissions, near-duplicates, eviction")
+    cfg = W.scaled(W.TINY_ENCODER, n_layers=2, B=8, n_bank=20) if dtype == "f32" else \
+        W.scaled(W.BERT_BASE, n_layers=2, B=8, S=48, n_bank=20)
+    tol = TOL[dtype]
+    ws = W.make_layer_weights(cfg, seed=0)
+    tok, pos = W.make_embeddings(cfg, seed=0)
+    Ps = W.make_projection(cfg.d, cfg.k, cfg.torch_dtype, seed=3, n_layers=cfg.n_layers)
+    st = GatedStack(cfg, ws, Ps, key_bits=True, keep_means=True)
+    wnp = [{k_: npf(v) for k_, v in w.items()} for w in ws]
+    Pnp = [npf(p) for p in Ps]
+    src = W.make_sources(cfg, 16, seed=1)
+    near, _ = W.make_substitution_queries(W.scaled(cfg, B=4), src, n_dup=4, n_subst=1, seed=5)
+    fresh = W.make_sources(cfg, 8, seed=9)
+    batches = [(src[0:8], 0.9, L.INSERT_ON_MISS), (src[8:16], 0.9, L.INSERT_ON_MISS),
+               (np.concatenate([src[[0, 5, 9, 15]], near]), 0.9, L.UPDATE_LRU),
+               (np.concatenate([src[[2, 2]], fresh[:6]]), 0.9, L.INSERT_ON_MISS | L.UPDATE_LRU),      # evicts
+               (np.concatenate([fresh[:4], src[[1, 3, 7, 11]]]), 1.0, 0)]                             # tau 1: nothing hits
+    total_hits = 0
+    for tick, (ids, tau, flags) in enumerate(batches, start=1):
+        h0 = W.embed(torch.from_numpy(ids), tok, pos, cfg.torch_dtype).cuda()
+        pre = []
+        for b in st.banks:
+            ob = O.Bank(b.n_slots, b.k, b.S, b.d, dtype, key_bits=True)
+            ob.fp = b.fp.cpu().numpy().view(np.uint32).copy()
+            ob.act = npf(b.act)
+            ob.valid = b.valid.cpu().numpy().copy()
+            ob.last_used = b.last_used.cpu().numpy().astype(np.uint64)
+            ob.hits = b.hits.cpu().numpy().astype(np.uint32)
+            pre.append(ob)
+        outs = st.forward(h0, tau=tau, flags=flags, tick=tick, keep_all=True)
+        torch.cuda.synchronize()
+        oflags = (O.FLAG_UPDATE_LRU if flags & L.UPDATE_LRU else 0) | (O.FLAG_INSERT_ON_MISS if flags & L.INSERT_ON_MISS else 0)
+        for l in range(cfg.n_layers):
+            h_prev = npf(h0 if l == 0 else outs[l - 1])
+            ob = pre[l]
+            # the sign of a projection within 1e-5 of the vector's scale of zero may be decided differently in fp32
+            v = O.simhash_projection(h_prev, Pnp[l], None)
+            shaky = (np.abs(v) < 1e-5 * np.sqrt((v * v).mean(axis=1, keepdims=True))).any(axis=1)
+            r = O.gated_layer(h_prev, ob, Pnp[l], None, wnp[l], cfg.arch, cfg.n_heads, cfg.ln_eps, cfg.gelu, f32(tau),
+                              flags=oflags, tick=tick, out_dtype=dtype)
+            assert not shaky.any()
+            g, bk = st.gate[l], st.banks[l]
+            hit = g.hit.cpu().numpy().astype(bool)
+            assert np.array_equal(hit, r.hit), (tick, l)
+            assert np.array_equal(g.idx.cpu().numpy(), r.idx), (tick, l)
+            np.testing.assert_allclose(npf(g.sim), r.sim, atol=1e-6)
+            n_miss = int((~hit).sum())
+            if flags & L.INSERT_ON_MISS:
+                assert g.slots.cpu().tolist()[:n_miss] == r.slots
+                assert np.array_equal(bk.fp.cpu().numpy().view(np.uint32)[r.slots], r.q[~hit])
+            assert np.array_equal(bk.valid.cpu().numpy(), ob.valid)
+            vmask = ob.valid.astype(bool)
+            assert np.array_equal(bk.last_used.cpu().numpy().astype(np.uint64)[vmask], ob.last_used[vmask])
+            assert np.array_equal(bk.hits.cpu().numpy().astype(np.uint32)[vmask], ob.hits[vmask])
+            got = npf(outs[l])
+            for b in range(cfg.B):
+                if hit[b]:
+                    assert torch.equal(outs[l][b], torch.from_numpy(np.asarray(r.h_out[b], dtype=np.float32)).to(cfg.torch_dtype).cuda())
+                else:
+                    assert rel_err_rows(got[b:b + 1], r.h_out[b:b + 1])[0] < tol, (tick, l, b)
+            total_hits += int(hit.sum())
+        say(f"  batch {tick} (tau {tau}): hits per layer {[int(x.hit.sum()) for x in st.gate]}")
+    assert total_hits > 0
+    st.close()
+
+
 def test_insert_without_eviction_drops_and_counts(L):
     say("insert into a full bank with policy NONE")
     g = np.random.Generator(np.random.PCG64(13))
