@@ -68,7 +68,8 @@ def kernel_work(cfg, name, miss, hit, e=2, carry=False):
         rows = float(L * B) if not carry else float(B + sum(B - h for h in hit[:-1]))
         return rows * S * d, rows * S * d * e, "hbm"
     if name == "project_kernel":
-        return L * 2.0 * B * d * k, L * (d * k * e + B * k * e), "hbm"
+        rows = float(L * B) if not carry else float(B + sum(B - h for h in hit[:-1]))      # carried keys are copied
+        return 2.0 * rows * d * k, L * (d * k * e + B * k * e), "hbm"
     if name in ("match_bf16_kernel", "match_stream_kernel"):
         return L * 2.0 * B * N * k, L * float(N) * k * e, "hbm" if B < 300 else "mfma"
     if name == "match_finalize_kernel":
