@@ -100,7 +100,7 @@ def main():
     ap.add_argument("--cpu-rows", type=int, default=2, help="sequences of the batch the oracle is timed on")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (the path is single-device); --gpus %d is not supported"
+        print("bench.py: the path runs on ONE GPU (it is single-device); --gpus %d is not supported"
               % args.gpus, file=sys.stderr)
         sys.exit(2)
 
