@@ -332,6 +332,38 @@ def match_bits(q_words: np.ndarray, bank_words: np.ndarray, valid: np.ndarray, k
     return idx.astype(np.int32), H[np.arange(B), idx].astype(np.int32)
 
 
+def lsh_candidates(q_words: np.ndarray, bank_words: np.ndarray, valid: np.ndarray, k: int) -> np.ndarray:
+    """Bucketed lookup (Section IV-B "LSH", Section III-A "sub-linear comparison cost"): the key is cut into
+    k / 16 bands of 16 bits (band b = bits 16 b .. 16 b + 15); a bank entry is a CANDIDATE for a query iff it is
+    valid and at least one band is equal in both keys.  Returns the boolean [B, N] candidate matrix."""
+    q16 = np.asarray(q_words, dtype=np.uint32)
+    b16 = np.asarray(bank_words, dtype=np.uint32)
+    valid = np.asarray(valid).astype(bool)
+    cand = np.zeros((q16.shape[0], b16.shape[0]), dtype=bool)
+    for band in range(k // 16):
+        w, sh = band // 2, np.uint32(16 * (band % 2))
+        qv = (q16[:, w] >> sh) & np.uint32(0xFFFF)
+        bv = (b16[:, w] >> sh) & np.uint32(0xFFFF)
+        cand |= (qv[:, None] == bv[None, :])
+    return cand & valid[None, :]
+
+
+def match_bits_lsh(q_words: np.ndarray, bank_words: np.ndarray, valid: np.ndarray, k: int
+                   ) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """Nearest CANDIDATE by Hamming distance: (idx, dist, number of distinct candidates).  Lowest slot wins ties;
+    no candidate: idx -1, dist NO_MATCH_DIST.  The result equals match_bits whenever the true nearest entry shares
+    a whole band with the query, which is what makes the lookup sub-linear: only bucket members are compared."""
+    cand = lsh_candidates(q_words, bank_words, valid, k)
+    B = cand.shape[0]
+    H = hamming(q_words, bank_words, k)
+    H[~cand] = NO_MATCH_DIST
+    idx = np.argmin(H, axis=1)
+    dist = H[np.arange(B), idx]
+    none = ~cand.any(axis=1)
+    idx = np.where(none, -1, idx)
+    return idx.astype(np.int32), dist.astype(np.int32), cand.sum(axis=1).astype(np.int32)
+
+
 def cosine_estimate(dist: np.ndarray, k: int) -> np.ndarray:
     """cos(pi * H / k): the cosine that a Hamming distance H between k-bit sign keys stands for."""
     return np.cos(np.pi * np.asarray(dist, dtype=np.float64) / float(k))

@@ -172,3 +172,38 @@ def test_gated_layer_with_sign_bit_bank():
     bank.valid[1:] = 0
     r4 = O.gated_layer(-h[:1], bank, P, None, w, O.ENCODER_POST_LN, 2, 1e-5, O.GELU_ERF, -0.5)
     assert not r4.hit.any() and r4.idx[0] == 0 and np.allclose(r4.sim, -1.0)
+
+
+def test_lsh_buckets_candidates_by_explicit_loops_and_agreement_with_the_full_match():
+    g = rng(9)
+    k, N, B = 64, 300, 20
+    bank = g.integers(0, 2 ** 32, size=(N, 2), dtype=np.uint64).astype(np.uint32)
+    q = g.integers(0, 2 ** 32, size=(B, 2), dtype=np.uint64).astype(np.uint32)
+    valid = (g.random(N) > 0.1).astype(np.uint8)
+    for b in range(0, B, 2):                      # near-duplicates: a few flipped bits leave most bands intact
+        j = int(g.integers(0, N))
+        q[b] = bank[j]
+        for _ in range(3):
+            i = int(g.integers(0, k))
+            q[b, i // 32] ^= np.uint32(1 << (i % 32))
+    cand = O.lsh_candidates(q, bank, valid, k)
+    bits_q, bits_b = O.unpack_bits(q, k), O.unpack_bits(bank, k)
+    for b in range(B):
+        for j in range(N):
+            share = any(np.array_equal(bits_q[b, 16 * t:16 * t + 16], bits_b[j, 16 * t:16 * t + 16]) for t in range(k // 16))
+            assert cand[b, j] == (share and bool(valid[j]))
+    idx, dist, n = O.match_bits_lsh(q, bank, valid, k)
+    fidx, fdist = O.match_bits(q, bank, valid, k)
+    assert np.array_equal(n, cand.sum(axis=1))
+    for b in range(B):
+        if n[b] == 0:
+            assert idx[b] == -1 and dist[b] == O.NO_MATCH_DIST
+        else:
+            js = np.nonzero(cand[b])[0]
+            hs = [int(O.hamming(q[b:b + 1], bank[j:j + 1], k)[0, 0]) for j in js]
+            assert dist[b] == min(hs) and idx[b] == js[int(np.argmin(hs))]
+        if fidx[b] >= 0 and cand[b, fidx[b]]:     # the true nearest shares a band: the bucketed lookup finds it
+            assert idx[b] == fidx[b] and dist[b] == fdist[b]
+    near = np.arange(0, B, 2)
+    ok = valid[fidx[near]] == 1
+    assert np.array_equal(idx[near][fdist[near] <= 3], fidx[near][fdist[near] <= 3])
