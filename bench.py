@@ -273,6 +273,12 @@ def main():
             "decision %.4f" % (sb["key_bits"], sb["bank_bytes"] >> 20, sb["match_us"], sb["other_us"],
                                sb["tera_word_ops_per_s"], 100 * sb["frac_int_valu_peak"], sb["hits"],
                                sb["same_cluster_as_cosine_match_on_hits"], sb["same_decision_as_cosine_match"]))
+        ls = sb["lsh"]
+        log("bucketed lookup (%d bands of 16 bits, index %d MB): build %.1f us, lookup of 4096 queries %.1f us; bucket "
+            "members visited per query: median %d, max %d of 1,048,576; same slot as the full Hamming match on hits %.4f, "
+            "same decision %.4f" % (ls["bands"], ls["index_bytes"] >> 20, ls["build_us"], ls["match_us"],
+                                    ls["visited_per_query_median"], ls["visited_per_query_max"],
+                                    ls["same_slot_as_full_match_on_hits"], ls["same_decision_as_full_match"]))
 
     # ---- headline: the last GPU work of the run ------------------------------------------------------
     dt_head, cnt_head = run(args.tau, args.steps, args.warmup)
@@ -409,6 +415,32 @@ def match_stress(llmc, W, iters=10):
     rep_b = llmc.llmc_profile_report()
     llmc.llmc_profile_end()
     us_b = {name: ms * 1e3 / cnt for name, (cnt, ms) in rep_b.items()}
+    # bucketed lookup over the same bit keys: 16 bands of 16 bits, compare only with bucket members
+    index = torch.empty((llmc.llmc_lsh_index_bytes(N, kb),), dtype=torch.uint8, device="cuda")
+    idx_l = torch.empty((B,), dtype=torch.int32, device="cuda")
+    dist_l = torch.empty((B,), dtype=torch.int32, device="cuda")
+    hit_l = torch.empty((B,), dtype=torch.uint8, device="cuda")
+    visited = torch.empty((B,), dtype=torch.int32, device="cuda")
+    llmc.llmc_lsh_build(bank_bits, bank.valid, index)
+    llmc.llmc_match_bits_lsh(bank_bits, index, q_bits, max_h, idx_l, dist_l, hit_l, visited)
+    torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    ev[0].record()
+    for _ in range(iters):
+        llmc.llmc_lsh_build(bank_bits, bank.valid, index)
+    ev[1].record()
+    for _ in range(iters):
+        llmc.llmc_match_bits_lsh(bank_bits, index, q_bits, max_h, idx_l, dist_l, hit_l, visited)
+    ev[2].record()
+    torch.cuda.synchronize()
+    hb_ = hit_b.bool()
+    lsh = {"bands": kb // 16, "index_bytes": int(index.numel()),
+           "build_us": round(ev[0].elapsed_time(ev[1]) * 1e3 / iters, 1),
+           "match_us": round(ev[1].elapsed_time(ev[2]) * 1e3 / iters, 1),
+           "visited_per_query_median": int(visited.float().median()), "visited_per_query_max": int(visited.max()),
+           "same_slot_as_full_match_on_hits": round(float((idx_l == idx_b)[hb_].float().mean()), 4) if bool(hb_.any()) else 1.0,
+           "same_decision_as_full_match": round(float((hit_l == hit_b).float().mean()), 4)}
+    del index
     cluster = data["cluster"].cuda()
     hb = hit.bool()
     same_cluster = float((cluster[idx_b.long()] == cluster[idx.long()])[hb].float().mean()) if bool(hb.any()) else 1.0
@@ -420,7 +452,7 @@ def match_stress(llmc, W, iters=10):
             "tera_word_ops_per_s": round(word_ops / us_b["match_bits_kernel"] / 1e6, 2),
             "frac_int_valu_peak": round(word_ops / us_b["match_bits_kernel"] / 1e6 / INT_VALU_PEAK_TOPS, 4),
             "hits": int(hit_b.sum()), "same_cluster_as_cosine_match_on_hits": round(same_cluster, 4),
-            "same_decision_as_cosine_match": round(same_decision, 4)}
+            "same_decision_as_cosine_match": round(same_decision, 4), "lsh": lsh}
     del bank_bits, q_bits, ws_f, ws_b
     bank.close()
     res = {"workload": "bank-match stress: 1,048,576 bf16 keys x 256 in 4,096 clusters, 4,096 queries, tau 0.95, "

@@ -358,6 +358,25 @@ llmc_status_t llmc_match_bits(const uint32_t* d_bank_bits, const uint8_t* d_vali
                               size_t workspace_bytes, llmc_stream_t stream);
 size_t llmc_match_bits_workspace_bytes(int32_t N, int32_t k, int32_t B);
 
+/*
+ * Bucketed lookup of sign-bit keys (Section IV-B "LSH"; Section III-A "sub-linear comparison cost").  The key is
+ * cut into k / 16 bands of 16 bits (band b = bits 16 b .. 16 b + 15).  llmc_lsh_build groups the valid slots of a
+ * bank by the value of each band into d_index (caller-owned, llmc_lsh_index_bytes(N, k) bytes, 256-byte aligned);
+ * it must be called again after the bank's keys or validity change.  llmc_match_bits_lsh compares a query only with
+ * the slots that share at least one whole band with it and returns the nearest of those (lowest slot among equal
+ * distances; -1 / 0x7FFFFFFF if there is none): the exact nearest neighbour whenever that neighbour shares a band
+ * with the query, at a cost that grows with the bucket sizes and not with N.
+ *   d_compared [B] (optional): bucket members visited per query (a slot in several of its buckets counts each time)
+ * k must be 64, 128, 256 or 512.  Errors: INVALID_ARG, SHAPE, WORKSPACE (index too small).
+ */
+size_t llmc_lsh_index_bytes(int32_t N, int32_t k);
+llmc_status_t llmc_lsh_build(const uint32_t* d_bank_bits, const uint8_t* d_valid, int32_t N, int32_t k,
+                             void* d_index, size_t index_bytes, llmc_stream_t stream);
+llmc_status_t llmc_match_bits_lsh(const uint32_t* d_bank_bits, int32_t N, int32_t k, const void* d_index,
+                                  size_t index_bytes, const uint32_t* d_query_bits, int32_t B,
+                                  int32_t max_hamming, int32_t* d_idx, int32_t* d_dist, uint8_t* d_hit,
+                                  int32_t* d_compared, llmc_stream_t stream);
+
 /* Host arithmetic, no device work: the largest H in 0..k with cos(pi * H / k) > tau, evaluated in
  * binary64 as written; -1 if there is none (tau >= 1) or k <= 0. */
 int32_t llmc_max_hamming(float tau, int32_t k);

@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libllmc.so")
-SOURCES = ["api.hip", "fingerprint.hip", "match.hip", "bits.hip", "gate.hip", "bank.hip", "layer.hip"]
+SOURCES = ["api.hip", "fingerprint.hip", "match.hip", "bits.hip", "lsh.hip", "gate.hip", "bank.hip", "layer.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

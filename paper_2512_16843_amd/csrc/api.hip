@@ -272,6 +272,36 @@ size_t llmc_match_bits_workspace_bytes(int32_t N, int32_t k, int32_t B) {
   return match_bits_ws_bytes(N, k, B);
 }
 
+static bool lsh_k_ok(int k) { return k == 64 || k == 128 || k == 256 || k == 512; }
+
+size_t llmc_lsh_index_bytes(int32_t N, int32_t k) {
+  if (N <= 0 || N > (1 << 30) || !lsh_k_ok(k)) return 0;
+  return lsh_index_bytes(N, k);
+}
+
+llmc_status_t llmc_lsh_build(const uint32_t* d_bank_bits, const uint8_t* d_valid, int32_t N, int32_t k, void* d_index,
+                             size_t index_bytes, llmc_stream_t stream) {
+  REQUIRE(d_bank_bits && d_valid && d_index, LLMC_ERR_INVALID_ARG, "NULL argument");
+  REQUIRE(N > 0 && N <= (1 << 30), LLMC_ERR_INVALID_ARG, "N out of range");
+  REQUIRE(lsh_k_ok(k), LLMC_ERR_SHAPE, "bucketed lookup supports k = 64, 128, 256 or 512 bits");
+  REQUIRE(((uintptr_t)d_index & 255) == 0, LLMC_ERR_SHAPE, "index must be 256-byte aligned");
+  REQUIRE(index_bytes >= lsh_index_bytes(N, k), LLMC_ERR_WORKSPACE, "index needs %zu bytes", lsh_index_bytes(N, k));
+  return launch_lsh_build(d_bank_bits, d_valid, N, k, d_index, (hipStream_t)stream);
+}
+
+llmc_status_t llmc_match_bits_lsh(const uint32_t* d_bank_bits, int32_t N, int32_t k, const void* d_index,
+                                  size_t index_bytes, const uint32_t* d_query_bits, int32_t B, int32_t max_hamming,
+                                  int32_t* d_idx, int32_t* d_dist, uint8_t* d_hit, int32_t* d_compared,
+                                  llmc_stream_t stream) {
+  REQUIRE(d_bank_bits && d_index && d_query_bits && d_idx, LLMC_ERR_INVALID_ARG, "NULL argument");
+  REQUIRE(N > 0 && N <= (1 << 30) && B > 0, LLMC_ERR_INVALID_ARG, "N or B out of range");
+  REQUIRE(lsh_k_ok(k), LLMC_ERR_SHAPE, "bucketed lookup supports k = 64, 128, 256 or 512 bits");
+  REQUIRE(((uintptr_t)d_index & 255) == 0, LLMC_ERR_SHAPE, "index must be 256-byte aligned");
+  REQUIRE(index_bytes >= lsh_index_bytes(N, k), LLMC_ERR_WORKSPACE, "index needs %zu bytes", lsh_index_bytes(N, k));
+  return launch_lsh_match(d_bank_bits, N, k, d_index, d_query_bits, B, max_hamming, d_idx, d_dist, d_hit, d_compared,
+                          (hipStream_t)stream);
+}
+
 int32_t llmc_max_hamming(float tau, int32_t k) {
   int32_t best = -1;
   for (int32_t H = 0; H <= k; ++H)

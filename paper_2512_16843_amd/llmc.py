@@ -32,6 +32,7 @@ EXPORTS = [
     "llmc_layer_workspace_bytes", "llmc_profile_begin", "llmc_profile_report", "llmc_profile_end",
     "llmc_last_error", "llmc_version", "llmc_fingerprint_bits", "llmc_match_bits",
     "llmc_match_bits_workspace_bytes", "llmc_max_hamming", "llmc_bank_pool_values",
+    "llmc_lsh_index_bytes", "llmc_lsh_build", "llmc_match_bits_lsh",
 ]
 
 
@@ -110,6 +111,10 @@ def lib() -> C.CDLL:
         L.llmc_match_bits_workspace_bytes.argtypes = [i32, i32, i32]
         L.llmc_match_bits_workspace_bytes.restype = sz
         L.llmc_max_hamming.argtypes = [f32, i32]
+        L.llmc_lsh_index_bytes.argtypes = [i32, i32]
+        L.llmc_lsh_index_bytes.restype = sz
+        L.llmc_lsh_build.argtypes = [vp, vp, i32, i32, vp, sz, vp]
+        L.llmc_match_bits_lsh.argtypes = [vp, i32, i32, vp, sz, vp, i32, i32, vp, vp, vp, vp, vp]
         L.llmc_max_hamming.restype = i32
         L.llmc_profile_begin.argtypes = [i32]
         L.llmc_profile_report.argtypes = [C.c_char_p, sz]
@@ -301,6 +306,24 @@ def llmc_match_bits(bank_bits: torch.Tensor, valid: torch.Tensor, query_bits: to
     _check(lib().llmc_match_bits(_ptr(bank_bits), _ptr(valid), N, W * 32, _ptr(query_bits), query_bits.shape[0],
                                  max_hamming, _ptr(idx), _ptr(dist), _ptr(hit), _ptr(workspace), workspace.numel(),
                                  _stream(stream)))
+
+
+def llmc_lsh_index_bytes(N: int, k: int) -> int:
+    return lib().llmc_lsh_index_bytes(N, k)
+
+
+def llmc_lsh_build(bank_bits: torch.Tensor, valid: torch.Tensor, index: torch.Tensor, stream=None) -> None:
+    N, W = bank_bits.shape
+    _check(lib().llmc_lsh_build(_ptr(bank_bits), _ptr(valid), N, W * 32, _ptr(index), index.numel(), _stream(stream)))
+
+
+def llmc_match_bits_lsh(bank_bits: torch.Tensor, index: torch.Tensor, query_bits: torch.Tensor, max_hamming: int,
+                        idx: torch.Tensor, dist: Optional[torch.Tensor], hit: Optional[torch.Tensor],
+                        compared: Optional[torch.Tensor] = None, stream=None) -> None:
+    N, W = bank_bits.shape
+    _check(lib().llmc_match_bits_lsh(_ptr(bank_bits), N, W * 32, _ptr(index), index.numel(), _ptr(query_bits),
+                                     query_bits.shape[0], max_hamming, _ptr(idx), _ptr(dist), _ptr(hit), _ptr(compared),
+                                     _stream(stream)))
 
 
 def llmc_gather_hits(bank: Bank, idx: torch.Tensor, rows: Optional[torch.Tensor], n: Optional[torch.Tensor],

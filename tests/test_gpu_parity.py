@@ -384,6 +384,59 @@ def test_match_bits_empty_bank_and_thresholds(L):
     assert np.all(idx == N - 1)
 
 
+@pytest.mark.parametrize("N,B,k", [(3000, 50, 64), (777, 9, 128), (20000, 300, 256), (5000, 33, 512)])
+def test_lsh_bucketed_match_is_exact_against_the_oracle(L, N, B, k):
+    say(f"bucketed Hamming lookup N={N} B={B} k={k}")
+    g = np.random.Generator(np.random.PCG64(N + k))
+    W_ = k // 32
+    bank = g.integers(0, 2 ** 32, size=(N, W_), dtype=np.uint64).astype(np.uint32)
+    # few distinct values in band 0 of many keys: big buckets, candidates without being near
+    bank[: N // 2, 0] = (bank[: N // 2, 0] & np.uint32(0xFFFF0000)) | np.uint32(0x1234)
+    q = g.integers(0, 2 ** 32, size=(B, W_), dtype=np.uint64).astype(np.uint32)
+    valid = (g.random(N) > 0.15).astype(np.uint8)
+    for b in range(0, B, 2):
+        j = int(g.integers(0, N))
+        q[b] = bank[j]
+        for _ in range(int(g.integers(0, 5))):
+            i = int(g.integers(0, k))
+            q[b, i // 32] ^= np.uint32(1 << (i % 32))
+    q[1, 0] = (q[1, 0] & np.uint32(0xFFFF0000)) | np.uint32(0x1234)     # falls into the big bucket
+    tb = torch.from_numpy(bank.view(np.int32)).cuda()
+    tq = torch.from_numpy(q.view(np.int32)).cuda()
+    tv = torch.from_numpy(valid).cuda()
+    index = torch.empty((L.llmc_lsh_index_bytes(N, k),), dtype=torch.uint8, device="cuda")
+    L.llmc_lsh_build(tb, tv, index)
+    idx = torch.empty((B,), dtype=torch.int32, device="cuda")
+    dist = torch.empty((B,), dtype=torch.int32, device="cuda")
+    hit = torch.empty((B,), dtype=torch.uint8, device="cuda")
+    cmpd = torch.empty((B,), dtype=torch.int32, device="cuda")
+    max_h = O.max_hamming(f32(0.95), k)
+    L.llmc_match_bits_lsh(tb, index, tq, max_h, idx, dist, hit, cmpd)
+    torch.cuda.synchronize()
+    oidx, odist, _ = O.match_bits_lsh(q, bank, valid, k)
+    assert np.array_equal(idx.cpu().numpy(), oidx)
+    assert np.array_equal(dist.cpu().numpy(), odist)
+    assert np.array_equal(hit.cpu().numpy().astype(bool), O.threshold_bits(oidx, odist, max_h))
+    # bucket members visited: over the bands, the valid slots equal to the query in that band
+    want = np.zeros(B, np.int64)
+    for band in range(k // 16):
+        w, sh = band // 2, np.uint32(16 * (band % 2))
+        qv = (q[:, w] >> sh) & np.uint32(0xFFFF)
+        bv = (bank[:, w] >> sh) & np.uint32(0xFFFF)
+        want += ((qv[:, None] == bv[None, :]) & (valid[None, :] == 1)).sum(axis=1)
+    assert np.array_equal(cmpd.cpu().numpy(), want)
+    # rebuilt after a change of validity, the lookup follows
+    valid2 = valid.copy()
+    gone = oidx[oidx >= 0][:5]
+    valid2[gone] = 0
+    L.llmc_lsh_build(tb, torch.from_numpy(valid2).cuda(), index)
+    L.llmc_match_bits_lsh(tb, index, tq, max_h, idx, dist, hit, None)
+    torch.cuda.synchronize()
+    oidx2, odist2, _ = O.match_bits_lsh(q, bank, valid2, k)
+    assert np.array_equal(idx.cpu().numpy(), oidx2) and np.array_equal(dist.cpu().numpy(), odist2)
+    say(f"  {int((oidx >= 0).sum())} of {B} queries have candidates; visited per query: median {int(np.median(want))}, max {int(want.max())} of {N}")
+
+
 def test_bit_keys_follow_the_cosine_match_on_a_clustered_bank(L):
     say("sign-bit keys of a clustered bank: the Hamming neighbour lies in the query's cluster, like the cosine neighbour")
     data = W.make_clustered_bank(64, 128, 256, 0.05, 512, seed=5)
