@@ -240,6 +240,7 @@ static llmc_status_t check_fp_shape(int B, int S, int d, int dtype, int k) {
   REQUIRE(B > 0 && S > 0 && d > 0 && k > 0, LLMC_ERR_INVALID_ARG, "non-positive size");
   REQUIRE(B <= 65535, LLMC_ERR_SHAPE, "B=%d exceeds 65535", B);
   REQUIRE(d % 64 == 0 && d <= 8192, LLMC_ERR_SHAPE, "d=%d must be a multiple of 64, at most 8192", d);
+  REQUIRE((size_t)d * elem_size(dtype) <= 16384, LLMC_ERR_SHAPE, "d=%d is too wide for fp32 pooling (at most 4096)", d);
   REQUIRE(k % 32 == 0 && k <= 1024, LLMC_ERR_SHAPE, "k=%d must be a multiple of 32, at most 1024", k);
   return LLMC_OK;
 }

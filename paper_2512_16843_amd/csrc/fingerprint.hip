@@ -3,7 +3,7 @@
 // key that the bank stores (Section III-A).
 //
 // Two kernels.  pool_kernel streams h once (HBM-bound): a workgroup owns one
-// (sequence, 32-token chunk) and leaves an fp32 partial sum per feature.
+// (sequence, 64-token chunk) and leaves an fp32 partial sum per feature.
 // project_kernel adds the partials in chunk order, applies P and c, normalises,
 // rounds to the bank's element type and stores 1/|rounded key|.
 // Every reduction order depends on S, d and k only, so a sequence's key is the same
@@ -13,7 +13,11 @@
 
 namespace llmc {
 
-constexpr int kTokChunk = 32;   // tokens per pooling workgroup
+constexpr int kTokChunk = 64;   // tokens per pooling workgroup
+
+// token rows of a chunk are dealt to R thread groups (row t goes to group t % R); R depends on d and the element
+// type only, so the summation order -- and with it every key -- does not depend on the batch
+static inline int pool_row_groups(int G) { return std::max(1, std::min(8, 1024 / G)); }
 
 static inline int pool_chunks(int S) { return (S + kTokChunk - 1) / kTokChunk; }
 
@@ -60,12 +64,14 @@ __global__ void pool_kernel(const T* __restrict__ h, int S, int d, int G, int R,
   __syncthreads();
   if (r == 0) {
     float* out = partial + ((size_t)b * n_chunks + chunk) * d + g * VEC;
+    float s[VEC];
 #pragma unroll
     for (int i = 0; i < VEC; ++i) {
-      float s = acc[i];
-      for (int rr = 1; rr < R; ++rr) s += red[(size_t)rr * d + g * VEC + i];
-      out[i] = s;
+      s[i] = acc[i];
+      for (int rr = 1; rr < R; ++rr) s[i] += red[(size_t)rr * d + g * VEC + i];
     }
+#pragma unroll
+    for (int i = 0; i < VEC; i += 4) *reinterpret_cast<float4*>(out + i) = make_float4(s[i], s[i + 1], s[i + 2], s[i + 3]);
   }
 }
 
@@ -307,7 +313,7 @@ static llmc_status_t fingerprint_t(const T* h, int B, int S, int d, const T* P, 
                                    const float* key_inv_in = nullptr) {
   constexpr int VEC = Vec16<T>::N;
   const int G = d / VEC;
-  const int R = G <= 512 ? 2 : 1;   // token rows split over thread groups; depends on d only
+  const int R = pool_row_groups(G);
   const int n_chunks = pool_chunks(S);
   dim3 grid(n_chunks, B);
   { ProfScope ps_("pool_kernel", st); hipLaunchKernelGGL(pool_kernel<T>, grid, dim3(G * R), (size_t)R * d * sizeof(float), st, h, S, d, G, R, partial,
@@ -368,7 +374,7 @@ static llmc_status_t pool_rows_t(const T* h, int n_max, int S, int d, const int3
                                  const int32_t* dst, float* out, hipStream_t st) {
   constexpr int VEC = Vec16<T>::N;
   const int G = d / VEC;
-  const int R = G <= 512 ? 2 : 1;
+  const int R = pool_row_groups(G);
   { ProfScope ps_("pool_direct_kernel", st);
     hipLaunchKernelGGL(pool_direct_kernel<T>, dim3(n_max), dim3(G * R), (size_t)R * d * sizeof(float), st, h, S, d, G, R,
                        rows, count, dst, out); }
