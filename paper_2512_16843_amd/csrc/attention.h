@@ -27,9 +27,7 @@ struct AttnCfg {
 
 typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
 
-__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
-  return (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(b) << 16);
-}
+__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) { return f32x2_to_bf16x2(a, b); }
 
 // qkv [T, 3d] (compact token rows), ctx [T, d].  1-D grid, capped: workgroups walk the
 // (sequence, head, query block) items with a grid stride; sequences beyond *count are skipped.

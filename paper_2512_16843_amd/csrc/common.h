@@ -18,12 +18,15 @@ struct bf16_t {
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) {
   return __uint_as_float(((uint32_t)b) << 16);
 }
-// round to nearest, ties to even; NaN stays NaN
-__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x40u);
-  u += 0x7FFFu + ((u >> 16) & 1u);
-  return (uint16_t)(u >> 16);
+// round to nearest, ties to even; NaN stays NaN.  Written as conversions to the compiler's bfloat type, which
+// gfx950 performs in hardware, two values per instruction (same bits as the integer add-and-shift formula,
+// ties, infinities and denormals included).
+typedef __bf16 llmc_bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float llmc_f32x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) { return __builtin_bit_cast(uint16_t, (__bf16)f); }
+__device__ __forceinline__ uint32_t f32x2_to_bf16x2(float lo, float hi) {
+  const llmc_f32x2_t v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, llmc_bf16x2_t));
 }
 
 template <typename T> struct Elem;
@@ -66,8 +69,7 @@ template <> struct Vec16<bf16_t> {
   __device__ static __forceinline__ void store(bf16_t* p, const float* in) {
     uint32_t w[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-      w[i] = (uint32_t)f32_to_bf16(in[2 * i]) | ((uint32_t)f32_to_bf16(in[2 * i + 1]) << 16);
+    for (int i = 0; i < 4; ++i) w[i] = f32x2_to_bf16x2(in[2 * i], in[2 * i + 1]);
     *reinterpret_cast<uint4*>(p) = make_uint4(w[0], w[1], w[2], w[3]);
   }
 };
