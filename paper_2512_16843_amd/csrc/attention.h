@@ -115,34 +115,39 @@ __global__ __launch_bounds__(AttnCfg::THREADS) void attention_mfma_kernel(const 
       // ---- online softmax over this lane's 32 keys (base-2 exponent, scale folded in) ----
       const int kv0 = t * C::KT;
       const bool edge = (kv0 + C::KT > S) || (CAUSAL && kv0 + C::KT > q0 + wave * 32);
+      // the maximum is taken over the raw scores (the scale is positive), the scale enters the exponent as one fma
       float mx = -INFINITY;
 #pragma unroll
       for (int f = 0; f < 2; ++f)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          float v = s[f][r] * scale_log2e;
+          float v = s[f][r];
           if (edge) {
             const int kv = kv0 + f * 32 + frag_row(lane, r);
             if (kv >= S || (CAUSAL && kv > q_lane)) v = -INFINITY;
+            s[f][r] = v;
           }
-          s[f][r] = v;
           mx = fmaxf(mx, v);
         }
       mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      const float m_new = fmaxf(m_run, mx);          // finite: key 0 is visible to every query
-      const float corr = __builtin_amdgcn_exp2f(m_run - m_new);
+      const float m_new = fmaxf(m_run, mx * scale_log2e);          // finite: key 0 is visible to every query
+      // the accumulators are rescaled only when some query of the wavefront met a larger score
+      if (__any(m_new > m_run)) {
+        const float corr = __builtin_amdgcn_exp2f(m_run - m_new);
+        l_run *= corr;
+#pragma unroll
+        for (int f = 0; f < 2; ++f)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) o[f][r] *= corr;
+      }
       m_run = m_new;
-      l_run *= corr;
-#pragma unroll
-      for (int f = 0; f < 2; ++f)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) o[f][r] *= corr;
       uint32_t pk[2][8];
 #pragma unroll
       for (int f = 0; f < 2; ++f)
 #pragma unroll
         for (int r = 0; r < 16; r += 2) {
-          const float p0 = __builtin_amdgcn_exp2f(s[f][r] - m_new), p1 = __builtin_amdgcn_exp2f(s[f][r + 1] - m_new);
+          const float p0 = __builtin_amdgcn_exp2f(fmaf(s[f][r], scale_log2e, -m_new));
+          const float p1 = __builtin_amdgcn_exp2f(fmaf(s[f][r + 1], scale_log2e, -m_new));
           l_run += p0 + p1;
           pk[f][r >> 1] = pack_bf16x2(p0, p1);
         }
