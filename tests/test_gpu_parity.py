@@ -1092,6 +1092,47 @@ def test_gated_stack_with_sign_bit_banks(L, dtype):
     st.close()
 
 
+def test_forward_can_be_captured_in_a_graph_and_replayed(L):
+    """The per-layer call only enqueues kernels (no allocation, no memset, no host read-back), so a whole forward can
+    be recorded in a HIP graph.  Every replay, with eager work and synchronisations in between, must give the eager
+    result bit for bit, also after the input buffer's contents changed."""
+    from paper_2512_16843_amd.engine import GatedStack
+    say("graph capture of a 3-layer gated forward (carried means and keys): three replays against eager")
+    cfg = W.scaled(W.BERT_BASE, n_layers=3, B=8, S=64, n_bank=32)
+    ws = W.make_layer_weights(cfg, seed=0)
+    tok, pos = W.make_embeddings(cfg, seed=0)
+    Ps = W.make_projection(cfg.d, cfg.k, cfg.torch_dtype, seed=3, n_layers=cfg.n_layers)
+    st = GatedStack(cfg, ws, Ps, keep_means=True, keep_next_keys=True)
+    src = W.make_sources(cfg, 16, seed=1)
+    for s0 in (0, 8):
+        st.forward(W.embed(torch.from_numpy(src[s0:s0 + 8]), tok, pos, cfg.torch_dtype).cuda(), tau=2.0,
+                   flags=L.INSERT_ON_MISS, tick=1)
+    fresh = W.make_sources(cfg, 8, seed=9)
+    inputs = [np.concatenate([src[[0, 3, 9, 12]], fresh[:4]]), np.concatenate([fresh[4:8], src[[1, 2, 14, 15]]]),
+              src[8:16]]
+    h_static = torch.empty((cfg.B, cfg.S, cfg.d), dtype=cfg.torch_dtype, device="cuda")
+    h_static.copy_(W.embed(torch.from_numpy(inputs[0]), tok, pos, cfg.torch_dtype))
+    st.forward(h_static, tau=0.9)                       # warm-up outside the capture (first-use settings)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        out_static = st.forward(h_static, tau=0.9)
+    torch.cuda.synchronize()
+    for ids in inputs:
+        h = W.embed(torch.from_numpy(ids), tok, pos, cfg.torch_dtype).cuda()
+        eager = st.forward(h, tau=0.9).clone()
+        eager_hits = torch.stack([g.hit.clone() for g in st.gate])
+        torch.cuda.synchronize()
+        junk = torch.randn(1 << 20, device="cuda").sum()          # unrelated eager work between replays
+        h_static.copy_(h)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out_static, eager)
+        assert torch.equal(torch.stack([g.hit for g in st.gate]), eager_hits)
+        del junk
+    st.close()
+
+
 def test_insert_without_eviction_drops_and_counts(L):
     say("insert into a full bank with policy NONE")
     g = np.random.Generator(np.random.PCG64(13))
