@@ -94,6 +94,10 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(uint8_t* valid, con
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   int m = d_m ? *d_m : m_max;
   m = max(0, min(m, m_max));
+  if (m == 0) {                           // nothing to place: the bank's metadata is not even read
+    for (int i = tid; i < m_max; i += kSelThreads) slots_out[i] = -1;
+    return;
+  }
   if (tid == 0) { s_total = 0; s_count = 0; s_or_lo = 0; s_or_hi = 0; s_and_lo = ~0u; s_and_hi = ~0u; }
   __syncthreads();
   const int n_iter = KPT > 0 ? KPT : (N + kSelThreads - 1) / kSelThreads;
