@@ -82,6 +82,11 @@ typedef enum { LLMC_EVICT_NONE = 0, LLMC_EVICT_LRU = 1, LLMC_EVICT_DECAYED_HITS 
                                   matched one entry, the lowest row alone decides.  Such rows count as hits and are
                                   not inserted again.  Needs a bank whose keys own their value rows. */
 
+#define LLMC_HINT_MOSTLY_CARRIED 8u /* a hint about cost, never about results: the caller expects nearly every row to arrive
+                                       with a carried mean or key (llmc_fp_desc_t), so the separate pooling launch is
+                                       dropped and the few other rows are pooled inside the projection's workgroups
+                                       (one workgroup per row: slower per row, one launch fewer).  Same bits either way. */
+
 /* Largest tick accepted (recency keys are packed into 32 bits on the device). */
 #define LLMC_MAX_TICK 0x7FFFFFFEull
 /* Largest number of rows one insert/evict call may place. */
@@ -405,7 +410,8 @@ llmc_status_t llmc_gather_hits(const llmc_bank_t* bank, const int32_t* d_idx, co
  *   d_h_in, d_h_out [B, S, d], element type of the layer; they must not overlap
  *   d_fp_given / d_inv_norm_given: NULL, or keys [B, k] + norms to use instead of
  *          fingerprinting d_h_in (Algorithm 1 taken literally: one fingerprint of X for all layers)
- *   tau: threshold; flags: LLMC_INSERT_ON_MISS | LLMC_UPDATE_LRU | LLMC_REVALIDATE; tick <= LLMC_MAX_TICK
+ *   tau: threshold; flags: LLMC_INSERT_ON_MISS | LLMC_UPDATE_LRU | LLMC_REVALIDATE | LLMC_HINT_MOSTLY_CARRIED;
+ *          tick <= LLMC_MAX_TICK
  *   out: optional per-row results and counters (NULL or any member NULL)
  *   d_workspace: at least llmc_layer_workspace_bytes(layer, B, S, k) bytes
  * The number of misses never visits the host: the miss-path kernels read it on

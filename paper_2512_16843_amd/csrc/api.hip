@@ -440,7 +440,8 @@ llmc_status_t llmc_layer_forward_gated(const llmc_layer_desc_t* layer, llmc_bank
   REQUIRE((int64_t)B * S <= 0x7FFFFFFF / 4, LLMC_ERR_SHAPE, "B*S too large");
   REQUIRE(tau == tau, LLMC_ERR_INVALID_ARG, "tau is NaN");
   REQUIRE(tick <= LLMC_MAX_TICK, LLMC_ERR_INVALID_ARG, "tick out of range");
-  REQUIRE((flags & ~(LLMC_INSERT_ON_MISS | LLMC_UPDATE_LRU | LLMC_REVALIDATE)) == 0, LLMC_ERR_INVALID_ARG,
+  REQUIRE((flags & ~(LLMC_INSERT_ON_MISS | LLMC_UPDATE_LRU | LLMC_REVALIDATE | LLMC_HINT_MOSTLY_CARRIED)) == 0,
+          LLMC_ERR_INVALID_ARG,
           "unknown flag bits");
   int k = 0;
   if (bank) {
@@ -522,7 +523,8 @@ llmc_status_t llmc_layer_forward_gated(const llmc_layer_desc_t* layer, llmc_bank
     const bool carried = fp->d_pooled_in && fp->d_pooled_in_valid;
     LLMC_TRY(launch_fingerprint_bits(d_h_in, B, S, layer->d, layer->dtype, fp->d_proj, fp->d_bias, k, (uint32_t*)keys,
                                      ws_fp, st, carried ? fp->d_pooled_in : nullptr,
-                                     carried ? fp->d_pooled_in_valid : nullptr));
+                                     carried ? fp->d_pooled_in_valid : nullptr,
+                                     (flags & LLMC_HINT_MOSTLY_CARRIED) != 0));
     q = keys;
   } else if (!q) {
     const bool keys_in = fp->d_key_in && fp->d_key_inv_in && fp->d_pooled_in_valid;
@@ -530,7 +532,7 @@ llmc_status_t llmc_layer_forward_gated(const llmc_layer_desc_t* layer, llmc_bank
     LLMC_TRY(launch_fingerprint(d_h_in, nullptr, B, S, layer->d, layer->dtype, fp->d_proj, fp->d_bias, k, keys, inv,
                                 ws_fp, st, carried ? fp->d_pooled_in : nullptr,
                                 carried ? fp->d_pooled_in_valid : nullptr, keys_in ? fp->d_key_in : nullptr,
-                                keys_in ? fp->d_key_inv_in : nullptr));
+                                keys_in ? fp->d_key_inv_in : nullptr, (flags & LLMC_HINT_MOSTLY_CARRIED) != 0));
     q = keys;
     qinv = inv;
   }

@@ -162,7 +162,7 @@ llmc_status_t launch_fingerprint(const void* d_h, const int32_t* d_rowmap_unused
                                  const void* d_proj, const float* d_bias, int k, void* d_fp, float* d_inv, void* ws,
                                  hipStream_t st, const float* pooled_in = nullptr,
                                  const uint8_t* pooled_valid = nullptr, const void* key_in = nullptr,
-                                 const float* key_inv_in = nullptr);
+                                 const float* key_inv_in = nullptr, bool few_uncarried = false);
 llmc_status_t launch_project_rows(const float* d_means, int n_max, int d, int dtype, const void* d_proj,
                                   const float* d_bias, int k, const int32_t* d_rows, const int32_t* d_count, void* d_fp,
                                   float* d_inv, hipStream_t st);
@@ -170,7 +170,8 @@ llmc_status_t launch_pool_rows(const void* d_h, int n_max, int S, int d, int dty
                                const int32_t* d_count, const int32_t* d_dst, float* d_out, hipStream_t st);
 llmc_status_t launch_fingerprint_bits(const void* d_h, int B, int S, int d, int dtype, const void* d_proj,
                                       const float* d_bias, int k, uint32_t* d_bits, void* ws, hipStream_t st,
-                                      const float* pooled_in = nullptr, const uint8_t* pooled_valid = nullptr);
+                                      const float* pooled_in = nullptr, const uint8_t* pooled_valid = nullptr,
+                                      bool few_uncarried = false);
 size_t match_bits_ws_bytes(int N, int k, int B);
 size_t lsh_index_bytes(int N, int k);
 llmc_status_t launch_lsh_build(const uint32_t* d_bank_bits, const uint8_t* d_valid, int N, int k, void* d_index,

@@ -75,6 +75,62 @@ __global__ void pool_kernel(const T* __restrict__ h, int S, int d, int G, int R,
   }
 }
 
+// Sum over the tokens of one whole sequence with the arithmetic of pool_kernel + the projection's chunk sum, by one
+// workgroup and without a partials buffer: chunk after chunk, each thread sums its tokens of the chunk, the row
+// groups are combined, and the chunk sums are added in ascending order.  Every thread of the workgroup must call
+// it (it contains barriers); threads tid >= G * R only take part in those.  On return the threads of row group 0
+// (tid < G) hold in `total` the sums of their column group.  red: LDS, R * d floats.
+template <typename T>
+__device__ __forceinline__ void pool_sequence(const T* __restrict__ seq, int S, int d, int G, int R, float* red,
+                                              float (&total)[Vec16<T>::N]) {
+  constexpr int VEC = Vec16<T>::N;
+  const int tid = threadIdx.x;
+  const bool active = tid < G * R;
+  const int g = tid % G, r = tid / G;
+  const T* base = seq + (size_t)g * VEC;
+#pragma unroll
+  for (int i = 0; i < VEC; ++i) total[i] = 0.f;
+  for (int t0 = 0; t0 < S; t0 += kTokChunk) {
+    const int t1 = min(S, t0 + kTokChunk);
+    float acc[VEC];
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) acc[i] = 0.f;
+    if (active) {
+      int t = t0 + r;
+      constexpr int U = 8;
+      for (; t + (U - 1) * R < t1; t += U * R) {
+        float v[U][VEC];
+#pragma unroll
+        for (int u = 0; u < U; ++u) Vec16<T>::load(base + (size_t)(t + u * R) * d, v[u]);
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+          for (int i = 0; i < VEC; ++i) acc[i] += v[u][i];
+      }
+      for (; t < t1; t += R) {
+        float v0[VEC];
+        Vec16<T>::load(base + (size_t)t * d, v0);
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) acc[i] += v0[i];
+      }
+    }
+    __syncthreads();                     // the previous chunk's readers are done
+    if (active) {
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) red[(size_t)r * d + g * VEC + i] = acc[i];
+    }
+    __syncthreads();
+    if (active && r == 0) {
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) {
+        float s = acc[i];
+        for (int rr = 1; rr < R; ++rr) s += red[(size_t)rr * d + g * VEC + i];
+        total[i] += s;
+      }
+    }
+  }
+}
+
 // grid (B); block CG * PARTS threads: thread (cg, part) owns the four output columns 4*cg .. 4*cg+3
 // over the part-th slice of d; slices are then added in ascending order.
 template <typename T>
@@ -86,7 +142,10 @@ __global__ __launch_bounds__(1024) void project_kernel(const float* __restrict__
                                                        const uint8_t* __restrict__ pooled_valid,
                                                        const T* __restrict__ key_in, const float* __restrict__ key_inv_in,
                                                        const int32_t* __restrict__ row_map,
-                                                       const int32_t* __restrict__ count) {
+                                                       const int32_t* __restrict__ count,
+                                                       const T* __restrict__ h_inline, int G, int R) {
+  // With h_inline (needs blockDim >= G * R and LDS for R * d more floats): a row whose mean is not supplied is
+  // pooled here, by this workgroup, with pool_sequence -- no partials, no separate pooling launch.
   // Entry e = blockIdx.x works on row b = row_map[e] (or e) of the outputs.  Sources of the token mean of row b:
   // pooled_in[b] if pooled_in is given and either there are no flags (means kept elsewhere, e.g. beside a bank's
   // values, possibly through row_map) or pooled_valid[b] is set; else the chunk partials of entry e.  If key_in is given and pooled_valid[b], the finished key
@@ -111,6 +170,14 @@ __global__ __launch_bounds__(1024) void project_kernel(const float* __restrict__
   const float inv_S = 1.0f / (float)S;
   if (from_means) {
     for (int i = threadIdx.x; i < d; i += nthreads) p[i] = pooled_in[(size_t)b * d + i];
+  } else if (h_inline) {
+    constexpr int VEC = Vec16<T>::N;
+    float total[VEC];
+    pool_sequence<T>(h_inline + ((size_t)b * S) * d, S, d, G, R, vpart + (size_t)parts * k, total);
+    if ((int)threadIdx.x < G) {
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) p[threadIdx.x * VEC + i] = total[i] * inv_S;
+    }
   } else
   for (int i = threadIdx.x; i < d; i += nthreads) {
     const float* src = partial + (size_t)entry * n_chunks * d + i;
@@ -239,11 +306,8 @@ __global__ void inv_norm_kernel(const T* __restrict__ fp, int64_t n, int k, floa
   if (lane == 0) out[row] = s > 0.0 ? (float)(1.0 / sqrt(s)) : 0.f;
 }
 
-// Token mean of whole sequences with the arithmetic of pool_kernel + the projection's chunk sum, in one
-// workgroup per sequence and without a partials buffer: chunk after chunk, each thread sums its tokens of the
-// chunk, the row groups are combined, and the chunk sums are added in ascending order.  Entry b pools sequence
-// rows[b] (or b) into out[dst[b] or b]; entries beyond *count, and negative destinations, are skipped.
-// grid (n_max); block G*R threads; LDS R*d floats.
+// Token means of whole sequences, one workgroup each.  Entry b pools sequence rows[b] (or b) into out[dst[b] or b];
+// entries beyond *count, and negative destinations, are skipped.  grid (n_max); block G*R threads; LDS R*d floats.
 template <typename T>
 __global__ void pool_direct_kernel(const T* __restrict__ h, int S, int d, int G, int R, const int32_t* __restrict__ rows,
                                    const int32_t* __restrict__ count, const int32_t* __restrict__ dst,
@@ -255,50 +319,12 @@ __global__ void pool_direct_kernel(const T* __restrict__ h, int S, int d, int G,
   const int o = dst ? dst[b] : b;
   if (o < 0) return;
   const int seq = rows ? rows[b] : b;
-  const int g = threadIdx.x % G, r = threadIdx.x / G;
-  const T* base = h + ((size_t)seq * S) * d + (size_t)g * VEC;
   float total[VEC];
-#pragma unroll
-  for (int i = 0; i < VEC; ++i) total[i] = 0.f;
-  for (int t0 = 0; t0 < S; t0 += kTokChunk) {
-    const int t1 = min(S, t0 + kTokChunk);
-    float acc[VEC];
-#pragma unroll
-    for (int i = 0; i < VEC; ++i) acc[i] = 0.f;
-    int t = t0 + r;
-    constexpr int U = 8;
-    for (; t + (U - 1) * R < t1; t += U * R) {
-      float v[U][VEC];
-#pragma unroll
-      for (int u = 0; u < U; ++u) Vec16<T>::load(base + (size_t)(t + u * R) * d, v[u]);
-#pragma unroll
-      for (int u = 0; u < U; ++u)
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) acc[i] += v[u][i];
-    }
-    for (; t < t1; t += R) {
-      float v0[VEC];
-      Vec16<T>::load(base + (size_t)t * d, v0);
-#pragma unroll
-      for (int i = 0; i < VEC; ++i) acc[i] += v0[i];
-    }
-    __syncthreads();                     // the previous chunk's readers are done
-#pragma unroll
-    for (int i = 0; i < VEC; ++i) red[(size_t)r * d + g * VEC + i] = acc[i];
-    __syncthreads();
-    if (r == 0) {
-#pragma unroll
-      for (int i = 0; i < VEC; ++i) {
-        float s = acc[i];
-        for (int rr = 1; rr < R; ++rr) s += red[(size_t)rr * d + g * VEC + i];
-        total[i] += s;
-      }
-    }
-  }
-  if (r == 0) {
+  pool_sequence<T>(h + ((size_t)seq * S) * d, S, d, G, R, red, total);
+  if ((int)threadIdx.x < G) {
     const float inv_S = 1.0f / (float)S;
 #pragma unroll
-    for (int i = 0; i < VEC; ++i) out[(size_t)o * d + g * VEC + i] = total[i] * inv_S;
+    for (int i = 0; i < VEC; ++i) out[(size_t)o * d + threadIdx.x * VEC + i] = total[i] * inv_S;
   }
 }
 
@@ -310,23 +336,32 @@ template <typename T>
 static llmc_status_t fingerprint_t(const T* h, int B, int S, int d, const T* P, const float* bias, int k,
                                    T* fp, float* inv, uint32_t* bits, float* partial, const float* pooled_in,
                                    const uint8_t* pooled_valid, hipStream_t st, const T* key_in = nullptr,
-                                   const float* key_inv_in = nullptr) {
+                                   const float* key_inv_in = nullptr, bool few_uncarried = false) {
   constexpr int VEC = Vec16<T>::N;
   const int G = d / VEC;
   const int R = pool_row_groups(G);
   const int n_chunks = pool_chunks(S);
-  dim3 grid(n_chunks, B);
-  { ProfScope ps_("pool_kernel", st); hipLaunchKernelGGL(pool_kernel<T>, grid, dim3(G * R), (size_t)R * d * sizeof(float), st, h, S, d, G, R, partial,
-                     n_chunks, pooled_valid, (const int32_t*)nullptr, (const int32_t*)nullptr); }
-  LLMC_LAUNCH_CHECK("pool_kernel");
   // slices of d per output column group; depends on k only.  k <= 1024 gives at least k threads.
   const int cgs = k / 4;
   const int parts = std::max(1, std::min(1024 / cgs, 16));
+  const int threads = std::max(cgs * parts, k);
+  // When the caller expects nearly every row to arrive with its mean or key (a carry from the producing call), the
+  // projection's workgroups pool the few others themselves (same arithmetic, see pool_sequence) and the pooling
+  // launch is dropped.  Otherwise every uncarried row is pooled by the dedicated, wider kernel.
+  const bool inline_pool = few_uncarried && pooled_valid != nullptr && threads >= G * R &&
+                           (size_t)(d + parts * k + R * d) * sizeof(float) <= 64 * 1024;
+  if (!inline_pool) {
+    dim3 grid(n_chunks, B);
+    { ProfScope ps_("pool_kernel", st); hipLaunchKernelGGL(pool_kernel<T>, grid, dim3(G * R), (size_t)R * d * sizeof(float), st, h, S, d, G, R, partial,
+                       n_chunks, pooled_valid, (const int32_t*)nullptr, (const int32_t*)nullptr); }
+    LLMC_LAUNCH_CHECK("pool_kernel");
+  }
   {
     ProfScope ps_("project_kernel", st);
-    hipLaunchKernelGGL(project_kernel<T>, dim3(B), dim3(std::max(cgs * parts, k)),
-                       (size_t)(d + parts * k) * sizeof(float), st, partial, n_chunks, S, d, P, bias, k, parts, fp, inv, bits, pooled_in, pooled_valid, key_in,
-                       key_inv_in, (const int32_t*)nullptr, (const int32_t*)nullptr);
+    hipLaunchKernelGGL(project_kernel<T>, dim3(B), dim3(threads),
+                       (size_t)(d + parts * k + (inline_pool ? R * d : 0)) * sizeof(float), st, partial, n_chunks, S, d, P,
+                       bias, k, parts, fp, inv, bits, pooled_in, pooled_valid, key_in, key_inv_in, (const int32_t*)nullptr,
+                       (const int32_t*)nullptr, inline_pool ? h : (const T*)nullptr, G, R);
   }
   LLMC_LAUNCH_CHECK("project_kernel");
   return LLMC_OK;
@@ -335,12 +370,14 @@ static llmc_status_t fingerprint_t(const T* h, int B, int S, int d, const T* P, 
 llmc_status_t launch_fingerprint(const void* d_h, const int32_t*, int B, int S, int d, int dtype, const void* d_proj,
                                  const float* d_bias, int k, void* d_fp, float* d_inv, void* ws, hipStream_t st,
                                  const float* pooled_in, const uint8_t* pooled_valid, const void* key_in,
-                                 const float* key_inv_in) {
+                                 const float* key_inv_in, bool few_uncarried) {
   if (dtype == LLMC_F32)
     return fingerprint_t<float>((const float*)d_h, B, S, d, (const float*)d_proj, d_bias, k, (float*)d_fp, d_inv,
-                                nullptr, (float*)ws, pooled_in, pooled_valid, st, (const float*)key_in, key_inv_in);
+                                nullptr, (float*)ws, pooled_in, pooled_valid, st, (const float*)key_in, key_inv_in,
+                                few_uncarried);
   return fingerprint_t<bf16_t>((const bf16_t*)d_h, B, S, d, (const bf16_t*)d_proj, d_bias, k, (bf16_t*)d_fp, d_inv,
-                               nullptr, (float*)ws, pooled_in, pooled_valid, st, (const bf16_t*)key_in, key_inv_in);
+                               nullptr, (float*)ws, pooled_in, pooled_valid, st, (const bf16_t*)key_in, key_inv_in,
+                               few_uncarried);
 }
 
 // keys of token means kept elsewhere: entry e < *count (or n_max) projects means[rows[e]] into fp[rows[e]], inv[rows[e]]
@@ -353,7 +390,7 @@ static llmc_status_t project_rows_t(const float* means, int n_max, int d, const 
   hipLaunchKernelGGL(project_kernel<T>, dim3(n_max), dim3(std::max(cgs * parts, k)),
                      (size_t)(d + parts * k) * sizeof(float), st, (const float*)nullptr, 0, 1, d, P, bias, k, parts, fp, inv,
                      (uint32_t*)nullptr, means, (const uint8_t*)nullptr, (const T*)nullptr, (const float*)nullptr, rows,
-                     count);
+                     count, (const T*)nullptr, 0, 0);
   LLMC_LAUNCH_CHECK("project_kernel");
   return LLMC_OK;
 }
@@ -392,12 +429,12 @@ llmc_status_t launch_pool_rows(const void* d_h, int n_max, int S, int d, int dty
 // same pooling and projection, but the key is the sign of each projection
 llmc_status_t launch_fingerprint_bits(const void* d_h, int B, int S, int d, int dtype, const void* d_proj,
                                       const float* d_bias, int k, uint32_t* d_bits, void* ws, hipStream_t st,
-                                      const float* pooled_in, const uint8_t* pooled_valid) {
+                                      const float* pooled_in, const uint8_t* pooled_valid, bool few_uncarried) {
   if (dtype == LLMC_F32)
     return fingerprint_t<float>((const float*)d_h, B, S, d, (const float*)d_proj, d_bias, k, nullptr, nullptr, d_bits,
-                                (float*)ws, pooled_in, pooled_valid, st);
+                                (float*)ws, pooled_in, pooled_valid, st, nullptr, nullptr, few_uncarried);
   return fingerprint_t<bf16_t>((const bf16_t*)d_h, B, S, d, (const bf16_t*)d_proj, d_bias, k, nullptr, nullptr, d_bits,
-                               (float*)ws, pooled_in, pooled_valid, st);
+                               (float*)ws, pooled_in, pooled_valid, st, nullptr, nullptr, few_uncarried);
 }
 
 llmc_status_t launch_inv_norm(const void* d_fp, int64_t n, int k, int dtype, float* d_out, hipStream_t st) {

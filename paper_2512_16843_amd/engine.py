@@ -45,9 +45,31 @@ class GatedStack:
         self.buf = [torch.empty((self.B, cfg.S, cfg.d), dtype=cfg.torch_dtype, device=device) for _ in range(2)]
         # keep_means: banks store the token mean of every cached output and a reused row hands it to the next layer
         self.keep_means = keep_means
+        self._hint = [False] * cfg.n_layers
+        self._stat_host = torch.zeros((cfg.n_layers, llmc.CNT_WORDS), dtype=torch.int32).pin_memory() if keep_means else None
+        self.counters_all = torch.zeros((cfg.n_layers, llmc.CNT_WORDS), dtype=torch.int32, device=device)
+        self._stat_event = None
         self.gate = [llmc.GateBuffers(self.B, device, d=cfg.d if keep_means else 0,
                                       next_k=cfg.k if (self.banks[l] is not None and self.banks[l].next_fp is not None) else 0,
-                                      dtype=cfg.torch_dtype) for l in range(cfg.n_layers)]
+                                      dtype=cfg.torch_dtype, counters=self.counters_all[l]) for l in range(cfg.n_layers)]
+
+    def _update_hints(self) -> None:
+        """Launch-shape hints from the hit counts of an EARLIER forward, read without waiting: when the copy that a
+        previous call started has landed, layers whose producer answered every row from its bank get
+        LLMC_HINT_MOSTLY_CARRIED (a single uncarried row costs a whole one-workgroup pooling, about what the
+        dropped launch saves several times over) (cost only: results do not depend on it)."""
+        if self._stat_event is not None and self._stat_event.query():
+            hits = self._stat_host[:, llmc.CNT_HIT].tolist()
+            for l in range(1, self.cfg.n_layers):
+                self._hint[l] = hits[l - 1] >= self.B
+            self._stat_event = None
+
+    def _start_stats(self) -> None:
+        if self._stat_event is not None or torch.cuda.is_current_stream_capturing():
+            return
+        self._stat_host.copy_(self.counters_all, non_blocking=True)      # one small device-to-host copy, not waited for
+        self._stat_event = torch.cuda.Event()
+        self._stat_event.record()
 
     def forward(self, h0: torch.Tensor, tau: float, flags: int = 0, tick: int = 0, keep_all: bool = False,
                 single_fingerprint: bool = False):
@@ -63,19 +85,24 @@ class GatedStack:
             fp_given = torch.empty((B, cfg.k), dtype=cfg.torch_dtype, device=self.device)
             inv_given = torch.empty((B,), dtype=torch.float32, device=self.device)
             llmc.llmc_fingerprint(h0, self.proj[0], self.bias[0], fp_given, inv_given, self.workspace)
+        if self.keep_means:
+            self._update_hints()
         for l in range(cfg.n_layers):
             out = torch.empty_like(h0) if keep_all else self.buf[l & 1]
             carry = self.gate[l - 1] if (self.keep_means and l > 0) else None
+            fl = flags | (llmc.HINT_MOSTLY_CARRIED if (carry is not None and self._hint[l]) else 0)
             llmc.llmc_layer_forward_gated(self.layers[l], self.banks[l], self.proj[l], self.bias[l], h, out, tau,
-                                          flags, tick, self.workspace, self.gate[l], fp_given, inv_given, carry=carry)
+                                          fl, tick, self.workspace, self.gate[l], fp_given, inv_given, carry=carry)
             h = out
             if keep_all:
                 outs.append(out)
+        if self.keep_means:
+            self._start_stats()
         return outs if keep_all else h
 
     def hit_counts(self) -> torch.Tensor:
         """[L, CNT_WORDS] device counters of the last forward (one host sync)."""
-        return torch.stack([g.counters for g in self.gate]).cpu()
+        return self.counters_all.cpu()
 
     def close(self):
         for b in self.banks:

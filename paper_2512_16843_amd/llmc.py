@@ -20,7 +20,7 @@ LLMC_OK = 0
 ERR_INVALID_ARG, ERR_SHAPE, ERR_DTYPE, ERR_BANK_FULL, ERR_WORKSPACE, ERR_HIP = 1, 2, 3, 4, 5, 6
 F32, BF16 = 0, 1
 EVICT_NONE, EVICT_LRU, EVICT_DECAYED_HITS = 0, 1, 2
-INSERT_ON_MISS, UPDATE_LRU, REVALIDATE = 1, 2, 4
+INSERT_ON_MISS, UPDATE_LRU, REVALIDATE, HINT_MOSTLY_CARRIED = 1, 2, 4, 8
 CNT_HIT, CNT_MISS, CNT_NEAR_TAU, CNT_NEAR_TIE, CNT_INSERTED, CNT_EVICTED, CNT_DROPPED = 0, 1, 2, 3, 4, 5, 6
 CNT_COMPUTED, CNT_REVALIDATED, CNT_DIVERGED, CNT_WORDS = 7, 8, 9, 12
 MAX_UPDATE_ROWS = 4096
@@ -363,7 +363,8 @@ def llmc_layer_workspace_bytes(layer: Layer, B: int, S: int, k: int) -> int:
 class GateBuffers:
     """Optional per-row outputs of the gate, allocated once per (B)."""
 
-    def __init__(self, B: int, device="cuda", d: int = 0, next_k: int = 0, dtype: torch.dtype = torch.bfloat16):
+    def __init__(self, B: int, device="cuda", d: int = 0, next_k: int = 0, dtype: torch.dtype = torch.bfloat16,
+                 counters: Optional[torch.Tensor] = None):
         # d > 0: also the buffers that carry the token means of reused rows to the next layer;
         # next_k > 0: and their finished keys under the next layer's fingerprint map
         self.pooled = torch.zeros((B, d), dtype=torch.float32, device=device) if d > 0 else None
@@ -373,7 +374,8 @@ class GateBuffers:
         self.idx = torch.empty((B,), dtype=torch.int32, device=device)
         self.sim = torch.empty((B,), dtype=torch.float32, device=device)
         self.hit = torch.empty((B,), dtype=torch.uint8, device=device)
-        self.counters = torch.zeros((CNT_WORDS,), dtype=torch.int32, device=device)
+        # the counters may be a row of a caller's [layers, CNT_WORDS] block, so that one copy fetches all layers
+        self.counters = torch.zeros((CNT_WORDS,), dtype=torch.int32, device=device) if counters is None else counters
         self.slots = torch.empty((B,), dtype=torch.int32, device=device)
 
     def struct(self) -> GateOut:
