@@ -87,6 +87,15 @@ typedef enum { LLMC_EVICT_NONE = 0, LLMC_EVICT_LRU = 1, LLMC_EVICT_DECAYED_HITS 
                                        dropped and the few other rows are pooled inside the projection's workgroups
                                        (one workgroup per row: slower per row, one launch fewer).  Same bits either way. */
 
+#define LLMC_DEFER_COPY 16u    /* rows answered from the bank are NOT copied into d_h_out; out->d_ref_out[b] receives the
+                                  value row of the matched entry instead (-1 for computed rows, whose d_h_out row is
+                                  written as usual).  The content of such a row is bank->d_act[d_ref_out[b]] until
+                                  someone needs it: the next layer's call (llmc_fp_desc_t.d_ref_in) copies it only if it
+                                  has to compute that row, and llmc_materialize copies what is still outstanding at the
+                                  end.  A row that keeps hitting is thus never copied.  Needs out->d_ref_out; refused
+                                  with LLMC_INSERT_ON_MISS and LLMC_REVALIDATE (the bank must not change while rows
+                                  refer to it) and on banks with compressed values. */
+
 /* Largest tick accepted (recency keys are packed into 32 bits on the device). */
 #define LLMC_MAX_TICK 0x7FFFFFFEull
 /* Largest number of rows one insert/evict call may place. */
@@ -209,6 +218,13 @@ typedef struct {
    * llmc_gate_out_t.d_key_out); those rows are then neither pooled nor projected.  k must be this map's k. */
   const void* d_key_in;
   const float* d_key_inv_in;
+  /* Optional, from a producing call made with LLMC_DEFER_COPY: d_ref_in[b] >= 0 says that row b of d_h_in was not
+   * written and stands for value row d_ref_in[b] of prev_bank (the producing layer's bank, which must keep
+   * next-layer keys under THIS map: d_next_fp).  The key of such a row is taken from there.  If the row has to be
+   * computed, this call first copies prev_bank's value row into d_h_in[b]: with d_ref_in the buffer behind d_h_in
+   * is written to, its const notwithstanding.  The carry pointers above are ignored when d_ref_in is given. */
+  const llmc_bank_t* prev_bank;
+  const int32_t* d_ref_in;
 } llmc_fp_desc_t;
 
 /* Optional per-row results of the gate; any pointer may be NULL. */
@@ -228,6 +244,7 @@ typedef struct {
    * bank (same flags).  d_key_out [B, next_k] in the bank's element type, d_key_inv_out [B]. */
   void* d_key_out;
   float* d_key_inv_out;
+  int32_t* d_ref_out;           /* [B], written with LLMC_DEFER_COPY: value row of the matched entry, or -1 */
 } llmc_gate_out_t;
 
 /* ---- bank -------------------------------------------------------------- */
@@ -398,6 +415,11 @@ int32_t llmc_max_hamming(float tau, int32_t k);
 llmc_status_t llmc_gather_hits(const llmc_bank_t* bank, const int32_t* d_idx, const int32_t* d_rows,
                                const int32_t* d_n, int32_t n_max, void* d_h_out, llmc_stream_t stream);
 
+/* Copy the rows that LLMC_DEFER_COPY left outstanding: d_h[b] = bank->d_act[d_ref[b]] for d_ref[b] >= 0 (other rows
+ * untouched).  d_h [B, S, d] with the bank's S, d and element type. */
+llmc_status_t llmc_materialize(const llmc_bank_t* bank, const int32_t* d_ref, int32_t B, void* d_h,
+                               llmc_stream_t stream);
+
 /* ---- the gated layer ---------------------------------------------------------- */
 
 /*
@@ -410,7 +432,8 @@ llmc_status_t llmc_gather_hits(const llmc_bank_t* bank, const int32_t* d_idx, co
  *   d_h_in, d_h_out [B, S, d], element type of the layer; they must not overlap
  *   d_fp_given / d_inv_norm_given: NULL, or keys [B, k] + norms to use instead of
  *          fingerprinting d_h_in (Algorithm 1 taken literally: one fingerprint of X for all layers)
- *   tau: threshold; flags: LLMC_INSERT_ON_MISS | LLMC_UPDATE_LRU | LLMC_REVALIDATE | LLMC_HINT_MOSTLY_CARRIED;
+ *   tau: threshold; flags: LLMC_INSERT_ON_MISS | LLMC_UPDATE_LRU | LLMC_REVALIDATE | LLMC_HINT_MOSTLY_CARRIED |
+ *          LLMC_DEFER_COPY;
  *          tick <= LLMC_MAX_TICK
  *   out: optional per-row results and counters (NULL or any member NULL)
  *   d_workspace: at least llmc_layer_workspace_bytes(layer, B, S, k) bytes

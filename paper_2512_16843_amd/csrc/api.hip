@@ -362,6 +362,15 @@ llmc_status_t llmc_gather_hits(const llmc_bank_t* bank, const int32_t* d_idx, co
   return launch_gather(bank, d_idx, d_rows, d_n, n_max, d_h_out, (hipStream_t)stream);
 }
 
+llmc_status_t llmc_materialize(const llmc_bank_t* bank, const int32_t* d_ref, int32_t B, void* d_h,
+                               llmc_stream_t stream) {
+  REQUIRE(bank && d_ref && d_h, LLMC_ERR_INVALID_ARG, "NULL argument");
+  REQUIRE(B > 0 && B <= 65535, LLMC_ERR_SHAPE, "B=%d out of range 1..65535", B);
+  REQUIRE(aligned16(d_h), LLMC_ERR_SHAPE, "output must be 16-byte aligned");
+  REQUIRE(bank->desc.rank == 0, LLMC_ERR_INVALID_ARG, "the bank holds compressed values");
+  return launch_materialize(bank, d_ref, nullptr, nullptr, B, d_h, (hipStream_t)stream);
+}
+
 llmc_status_t llmc_profile_begin(int32_t max_records) {
   REQUIRE(max_records > 0 && max_records <= (1 << 20), LLMC_ERR_INVALID_ARG, "max_records out of range");
   REQUIRE(!g_prof_on.load() && g_prof.empty(), LLMC_ERR_INVALID_ARG, "profiling already on");
@@ -440,7 +449,7 @@ llmc_status_t llmc_layer_forward_gated(const llmc_layer_desc_t* layer, llmc_bank
   REQUIRE((int64_t)B * S <= 0x7FFFFFFF / 4, LLMC_ERR_SHAPE, "B*S too large");
   REQUIRE(tau == tau, LLMC_ERR_INVALID_ARG, "tau is NaN");
   REQUIRE(tick <= LLMC_MAX_TICK, LLMC_ERR_INVALID_ARG, "tick out of range");
-  REQUIRE((flags & ~(LLMC_INSERT_ON_MISS | LLMC_UPDATE_LRU | LLMC_REVALIDATE | LLMC_HINT_MOSTLY_CARRIED)) == 0,
+  REQUIRE((flags & ~(LLMC_INSERT_ON_MISS | LLMC_UPDATE_LRU | LLMC_REVALIDATE | LLMC_HINT_MOSTLY_CARRIED | LLMC_DEFER_COPY)) == 0,
           LLMC_ERR_INVALID_ARG,
           "unknown flag bits");
   int k = 0;
@@ -468,6 +477,19 @@ llmc_status_t llmc_layer_forward_gated(const llmc_layer_desc_t* layer, llmc_bank
             "the divergence monitor is refused on a bank with compressed values");
     REQUIRE(!(flags & LLMC_REVALIDATE) || !D.d_act_pool, LLMC_ERR_INVALID_ARG,
             "the divergence monitor is refused on a bank that keeps token means");
+    if (flags & LLMC_DEFER_COPY) {
+      REQUIRE(out && out->d_ref_out, LLMC_ERR_INVALID_ARG, "LLMC_DEFER_COPY needs out->d_ref_out");
+      REQUIRE(!(flags & (LLMC_INSERT_ON_MISS | LLMC_REVALIDATE)), LLMC_ERR_INVALID_ARG,
+              "LLMC_DEFER_COPY is refused with LLMC_INSERT_ON_MISS and LLMC_REVALIDATE");
+      REQUIRE(D.rank == 0, LLMC_ERR_INVALID_ARG, "LLMC_DEFER_COPY is refused on a bank with compressed values");
+    }
+    if (!d_fp_given && fp && fp->d_ref_in) {
+      REQUIRE(fp->prev_bank, LLMC_ERR_INVALID_ARG, "d_ref_in needs prev_bank");
+      const llmc_bank_desc_t& Pb = fp->prev_bank->desc;
+      REQUIRE(Pb.d_next_fp && Pb.next_k == D.k && Pb.dtype == D.dtype && !D.key_bits, LLMC_ERR_SHAPE,
+              "prev_bank must keep next-layer keys of this bank's length and type");
+      REQUIRE(Pb.S == S && Pb.d == layer->d && Pb.rank == 0, LLMC_ERR_SHAPE, "prev_bank's value shape does not fit");
+    }
     if (flags & LLMC_REVALIDATE) {
       REQUIRE(D.reval_every >= 0 && D.drift_bound == D.drift_bound && D.drift_bound >= 0.f, LLMC_ERR_INVALID_ARG,
               "reval_every and drift_bound must not be negative");
@@ -526,6 +548,14 @@ llmc_status_t llmc_layer_forward_gated(const llmc_layer_desc_t* layer, llmc_bank
                                      carried ? fp->d_pooled_in_valid : nullptr,
                                      (flags & LLMC_HINT_MOSTLY_CARRIED) != 0));
     q = keys;
+  } else if (!q && fp->d_ref_in) {
+    // rows that are references to the producing layer's bank take their key from its stored next-layer keys
+    const llmc_bank_desc_t& Pb = fp->prev_bank->desc;
+    LLMC_TRY(launch_fingerprint(d_h_in, nullptr, B, S, layer->d, layer->dtype, fp->d_proj, fp->d_bias, k, keys, inv,
+                                ws_fp, st, nullptr, nullptr, Pb.d_next_fp, Pb.d_next_inv,
+                                (flags & LLMC_HINT_MOSTLY_CARRIED) != 0, fp->d_ref_in));
+    q = keys;
+    qinv = inv;
   } else if (!q) {
     const bool keys_in = fp->d_key_in && fp->d_key_inv_in && fp->d_pooled_in_valid;
     const bool carried = (fp->d_pooled_in || keys_in) && fp->d_pooled_in_valid;
@@ -557,8 +587,13 @@ llmc_status_t llmc_layer_forward_gated(const llmc_layer_desc_t* layer, llmc_bank
     }
   }
   LLMC_TRY(launch_compact(hit, idx, sim, tie, B, tau, hit_rows, miss_rows, reval_tmp, counters, bank, flags, tick, st,
-                          pooled_valid_out, pooled_out ? 1 : 0));
-  LLMC_TRY(launch_gather(bank, idx, hit_rows, counters + LLMC_CNT_HIT, B, d_h_out, st, pooled_out, key_out, key_inv_out));
+                          pooled_valid_out, pooled_out ? 1 : 0, (flags & LLMC_DEFER_COPY) ? out->d_ref_out : nullptr));
+  // rows to compute that arrived as references get their content now (the only reader of a referenced row)
+  if (!d_fp_given && fp && fp->d_ref_in)
+    LLMC_TRY(launch_materialize(fp->prev_bank, fp->d_ref_in, miss_rows, counters + LLMC_CNT_COMPUTED, B,
+                                const_cast<void*>(d_h_in), st));
+  if (!(flags & LLMC_DEFER_COPY))
+    LLMC_TRY(launch_gather(bank, idx, hit_rows, counters + LLMC_CNT_HIT, B, d_h_out, st, pooled_out, key_out, key_inv_out));
   // the rows to compute: the misses, then (divergence monitor) the sampled hit rows, whose copies are overwritten
   LLMC_TRY(launch_layer(layer, d_h_in, d_h_out, B, S, miss_rows, counters + LLMC_CNT_COMPUTED, ws_layer, st));
   if ((flags & LLMC_REVALIDATE) && bank->desc.reval_every > 0)

@@ -162,7 +162,8 @@ llmc_status_t launch_fingerprint(const void* d_h, const int32_t* d_rowmap_unused
                                  const void* d_proj, const float* d_bias, int k, void* d_fp, float* d_inv, void* ws,
                                  hipStream_t st, const float* pooled_in = nullptr,
                                  const uint8_t* pooled_valid = nullptr, const void* key_in = nullptr,
-                                 const float* key_inv_in = nullptr, bool few_uncarried = false);
+                                 const float* key_inv_in = nullptr, bool few_uncarried = false,
+                                 const int32_t* key_index = nullptr);
 llmc_status_t launch_project_rows(const float* d_means, int n_max, int d, int dtype, const void* d_proj,
                                   const float* d_bias, int k, const int32_t* d_rows, const int32_t* d_count, void* d_fp,
                                   float* d_inv, hipStream_t st);
@@ -196,7 +197,9 @@ llmc_status_t launch_compact(const uint8_t* d_hit, const int32_t* d_idx, const f
                              const uint8_t* d_near_tie, int B, float tau, int32_t* d_hit_rows,
                              int32_t* d_miss_rows, int32_t* d_reval_tmp, int32_t* d_counters, llmc_bank* bank,
                              uint32_t flags, uint64_t tick, hipStream_t st, uint8_t* d_pooled_valid_out = nullptr,
-                             int has_pool = 0);
+                             int has_pool = 0, int32_t* d_ref_out = nullptr);
+llmc_status_t launch_materialize(const llmc_bank* bank, const int32_t* d_ref, const int32_t* d_rows, const int32_t* d_n,
+                                 int n_max, void* d_h, hipStream_t st);
 llmc_status_t launch_divergence(llmc_bank* bank, const void* d_h_out, const int32_t* d_idx, const int32_t* d_rows,
                                 int32_t* d_counters, int B, hipStream_t st);
 llmc_status_t launch_all_miss(int B, int32_t* d_miss_rows, int32_t* d_counters, int32_t* d_idx, float* d_sim,

@@ -27,13 +27,14 @@ static inline int pool_chunks(int S) { return (S + kTokChunk - 1) / kTokChunk; }
 template <typename T>
 __global__ void pool_kernel(const T* __restrict__ h, int S, int d, int G, int R, float* __restrict__ partial,
                             int n_chunks, const uint8_t* __restrict__ skip, const int32_t* __restrict__ rows,
-                            const int32_t* __restrict__ count) {
+                            const int32_t* __restrict__ count, const int32_t* __restrict__ skip_ref) {
   constexpr int VEC = Vec16<T>::N;
   extern __shared__ float red[];  // [R][d]
   const int b = blockIdx.y, chunk = blockIdx.x;
   if (count && b >= *count) return;
   const int seq = rows ? rows[b] : b;
   if (skip && skip[seq]) return;
+  if (skip_ref && skip_ref[seq] >= 0) return;      // the row is a reference to a cached output, its key is stored
   const int g = threadIdx.x % G, r = threadIdx.x / G;
   const int t0 = chunk * kTokChunk;
   const int t1 = min(S, t0 + kTokChunk);
@@ -143,7 +144,8 @@ __global__ __launch_bounds__(1024) void project_kernel(const float* __restrict__
                                                        const T* __restrict__ key_in, const float* __restrict__ key_inv_in,
                                                        const int32_t* __restrict__ row_map,
                                                        const int32_t* __restrict__ count,
-                                                       const T* __restrict__ h_inline, int G, int R) {
+                                                       const T* __restrict__ h_inline, int G, int R,
+                                                       const int32_t* __restrict__ key_index) {
   // With h_inline (needs blockDim >= G * R and LDS for R * d more floats): a row whose mean is not supplied is
   // pooled here, by this workgroup, with pool_sequence -- no partials, no separate pooling launch.
   // Entry e = blockIdx.x works on row b = row_map[e] (or e) of the outputs.  Sources of the token mean of row b:
@@ -160,11 +162,14 @@ __global__ __launch_bounds__(1024) void project_kernel(const float* __restrict__
   const int b = row_map ? row_map[entry] : entry;
   if (b < 0) return;
   const int nthreads = blockDim.x;
-  const bool given = !row_map && pooled_valid && pooled_valid[b];
-  const bool from_means = pooled_in && (row_map || !pooled_valid || given);   // no flags: every row's mean is supplied
+  // key_index: row b is a reference to entry key_index[b] of a bank (negative: not a reference), and key_in /
+  // key_inv_in are that bank's stored keys; without it, carried keys sit at row b and pooled_valid flags them
+  const int ksrc = key_index ? key_index[b] : b;
+  const bool given = !row_map && (key_index ? ksrc >= 0 : (pooled_valid && pooled_valid[b]));
+  const bool from_means = pooled_in && (row_map || (!pooled_valid && !key_index) || (given && !key_index));
   if (given && key_in) {
-    for (int i = threadIdx.x; i < k; i += nthreads) fp_out[(size_t)b * k + i] = key_in[(size_t)b * k + i];
-    if (threadIdx.x == 0) inv_out[b] = key_inv_in[b];
+    for (int i = threadIdx.x; i < k; i += nthreads) fp_out[(size_t)b * k + i] = key_in[(size_t)ksrc * k + i];
+    if (threadIdx.x == 0) inv_out[b] = key_inv_in[ksrc];
     return;
   }
   const float inv_S = 1.0f / (float)S;
@@ -336,7 +341,8 @@ template <typename T>
 static llmc_status_t fingerprint_t(const T* h, int B, int S, int d, const T* P, const float* bias, int k,
                                    T* fp, float* inv, uint32_t* bits, float* partial, const float* pooled_in,
                                    const uint8_t* pooled_valid, hipStream_t st, const T* key_in = nullptr,
-                                   const float* key_inv_in = nullptr, bool few_uncarried = false) {
+                                   const float* key_inv_in = nullptr, bool few_uncarried = false,
+                                   const int32_t* key_index = nullptr) {
   constexpr int VEC = Vec16<T>::N;
   const int G = d / VEC;
   const int R = pool_row_groups(G);
@@ -348,12 +354,12 @@ static llmc_status_t fingerprint_t(const T* h, int B, int S, int d, const T* P, 
   // When the caller expects nearly every row to arrive with its mean or key (a carry from the producing call), the
   // projection's workgroups pool the few others themselves (same arithmetic, see pool_sequence) and the pooling
   // launch is dropped.  Otherwise every uncarried row is pooled by the dedicated, wider kernel.
-  const bool inline_pool = few_uncarried && pooled_valid != nullptr && threads >= G * R &&
+  const bool inline_pool = few_uncarried && (pooled_valid != nullptr || key_index != nullptr) && threads >= G * R &&
                            (size_t)(d + parts * k + R * d) * sizeof(float) <= 64 * 1024;
   if (!inline_pool) {
     dim3 grid(n_chunks, B);
     { ProfScope ps_("pool_kernel", st); hipLaunchKernelGGL(pool_kernel<T>, grid, dim3(G * R), (size_t)R * d * sizeof(float), st, h, S, d, G, R, partial,
-                       n_chunks, pooled_valid, (const int32_t*)nullptr, (const int32_t*)nullptr); }
+                       n_chunks, pooled_valid, (const int32_t*)nullptr, (const int32_t*)nullptr, key_index); }
     LLMC_LAUNCH_CHECK("pool_kernel");
   }
   {
@@ -361,7 +367,7 @@ static llmc_status_t fingerprint_t(const T* h, int B, int S, int d, const T* P, 
     hipLaunchKernelGGL(project_kernel<T>, dim3(B), dim3(threads),
                        (size_t)(d + parts * k + (inline_pool ? R * d : 0)) * sizeof(float), st, partial, n_chunks, S, d, P,
                        bias, k, parts, fp, inv, bits, pooled_in, pooled_valid, key_in, key_inv_in, (const int32_t*)nullptr,
-                       (const int32_t*)nullptr, inline_pool ? h : (const T*)nullptr, G, R);
+                       (const int32_t*)nullptr, inline_pool ? h : (const T*)nullptr, G, R, key_index);
   }
   LLMC_LAUNCH_CHECK("project_kernel");
   return LLMC_OK;
@@ -370,14 +376,14 @@ static llmc_status_t fingerprint_t(const T* h, int B, int S, int d, const T* P, 
 llmc_status_t launch_fingerprint(const void* d_h, const int32_t*, int B, int S, int d, int dtype, const void* d_proj,
                                  const float* d_bias, int k, void* d_fp, float* d_inv, void* ws, hipStream_t st,
                                  const float* pooled_in, const uint8_t* pooled_valid, const void* key_in,
-                                 const float* key_inv_in, bool few_uncarried) {
+                                 const float* key_inv_in, bool few_uncarried, const int32_t* key_index) {
   if (dtype == LLMC_F32)
     return fingerprint_t<float>((const float*)d_h, B, S, d, (const float*)d_proj, d_bias, k, (float*)d_fp, d_inv,
                                 nullptr, (float*)ws, pooled_in, pooled_valid, st, (const float*)key_in, key_inv_in,
-                                few_uncarried);
+                                few_uncarried, key_index);
   return fingerprint_t<bf16_t>((const bf16_t*)d_h, B, S, d, (const bf16_t*)d_proj, d_bias, k, (bf16_t*)d_fp, d_inv,
                                nullptr, (float*)ws, pooled_in, pooled_valid, st, (const bf16_t*)key_in, key_inv_in,
-                               few_uncarried);
+                               few_uncarried, key_index);
 }
 
 // keys of token means kept elsewhere: entry e < *count (or n_max) projects means[rows[e]] into fp[rows[e]], inv[rows[e]]
@@ -390,7 +396,7 @@ static llmc_status_t project_rows_t(const float* means, int n_max, int d, const 
   hipLaunchKernelGGL(project_kernel<T>, dim3(n_max), dim3(std::max(cgs * parts, k)),
                      (size_t)(d + parts * k) * sizeof(float), st, (const float*)nullptr, 0, 1, d, P, bias, k, parts, fp, inv,
                      (uint32_t*)nullptr, means, (const uint8_t*)nullptr, (const T*)nullptr, (const float*)nullptr, rows,
-                     count, (const T*)nullptr, 0, 0);
+                     count, (const T*)nullptr, 0, 0, (const int32_t*)nullptr);
   LLMC_LAUNCH_CHECK("project_kernel");
   return LLMC_OK;
 }

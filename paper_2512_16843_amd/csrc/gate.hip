@@ -18,7 +18,9 @@ __global__ __launch_bounds__(1024) void compact_kernel(const uint8_t* __restrict
                                                        int32_t* __restrict__ miss_rows, int32_t* __restrict__ counters,
                                                        uint64_t* last_used, uint32_t* hits, int touch, uint64_t tick,
                                                        int reval_every, int32_t* __restrict__ reval_tmp,
-                                                       uint8_t* __restrict__ pooled_valid_out, int has_pool) {
+                                                       uint8_t* __restrict__ pooled_valid_out, int has_pool,
+                                                       int32_t* __restrict__ ref_out,
+                                                       const int32_t* __restrict__ act_slot) {
   __shared__ int wave_hits[16], wave_reval[16];
   __shared__ int base_hit, base_miss, base_reval, s_near_tau, s_near_tie;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -45,6 +47,11 @@ __global__ __launch_bounds__(1024) void compact_kernel(const uint8_t* __restrict
       const int hrank = wbase + before;
       // a row answered from the bank carries its stored token mean to the next layer; computed rows do not
       if (pooled_valid_out) pooled_valid_out[b] = (has_pool && h && !rv) ? 1 : 0;
+      // deferred copy: a reused row is only a reference to the value row of its entry
+      if (ref_out) {
+        const int j = (h && !rv) ? idx[b] : -1;
+        ref_out[b] = j < 0 ? -1 : (act_slot ? act_slot[j] : j);
+      }
       if (h) {
         hit_rows[base_hit + hrank] = b;
         if (rv) reval_tmp[base_reval + wbase_rv + before_rv] = b;
@@ -158,7 +165,7 @@ typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 constexpr int kGatherThreads = 256;
 constexpr int kGatherVecPerThread = 4;   // 16 KiB per workgroup: the launch shape that streamed fastest
 
-__global__ __launch_bounds__(kGatherThreads) void gather_kernel(const u32x4_t* __restrict__ act, const int32_t* act_slot,
+__device__ __forceinline__ void gather_body(const u32x4_t* __restrict__ act, const int32_t* act_slot,
                                                                 const int32_t* __restrict__ idx,
                                                                 const int32_t* __restrict__ rows,
                                                                 const int32_t* __restrict__ count, int n_max,
@@ -202,12 +209,12 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(const u32x4_t* _
 llmc_status_t launch_compact(const uint8_t* d_hit, const int32_t* d_idx, const float* d_sim, const uint8_t* d_near_tie,
                              int B, float tau, int32_t* d_hit_rows, int32_t* d_miss_rows, int32_t* d_reval_tmp,
                              int32_t* d_counters, llmc_bank* bank, uint32_t flags, uint64_t tick, hipStream_t st,
-                             uint8_t* d_pooled_valid_out, int has_pool) {
+                             uint8_t* d_pooled_valid_out, int has_pool, int32_t* d_ref_out) {
   const int touch = (flags & LLMC_UPDATE_LRU) ? 1 : 0;
   const int reval_every = (flags & LLMC_REVALIDATE) ? bank->desc.reval_every : 0;
   { ProfScope ps_("compact_kernel", st); hipLaunchKernelGGL(compact_kernel, dim3(1), dim3(1024), 0, st, d_hit, d_idx, d_sim, d_near_tie, B, tau, d_hit_rows,
                      d_miss_rows, d_counters, bank->desc.d_last_used, bank->desc.d_hits, touch, tick, reval_every,
-                     d_reval_tmp, d_pooled_valid_out, has_pool); }
+                     d_reval_tmp, d_pooled_valid_out, has_pool, d_ref_out, bank->desc.d_act_slot); }
   LLMC_LAUNCH_CHECK("compact_kernel");
   return LLMC_OK;
 }
@@ -235,6 +242,21 @@ llmc_status_t launch_all_miss(int B, int32_t* d_miss_rows, int32_t* d_counters, 
   LLMC_LAUNCH_CHECK("all_miss_kernel");
   return LLMC_OK;
 }
+
+#define LLMC_GATHER_PARAMS                                                                                         \
+  const u32x4_t *__restrict__ act, const int32_t *act_slot, const int32_t *__restrict__ idx,                       \
+      const int32_t *__restrict__ rows, const int32_t *__restrict__ count, int n_max, size_t vec_per_seq,           \
+      u32x4_t *__restrict__ out, const float *__restrict__ act_pool, float *__restrict__ pooled_out, int d,         \
+      const uint32_t *__restrict__ next_fp, const float *__restrict__ next_inv, uint32_t *__restrict__ key_out,     \
+      float *__restrict__ key_inv_out, int key_words
+#define LLMC_GATHER_ARGS                                                                                             \
+  act, act_slot, idx, rows, count, n_max, vec_per_seq, out, act_pool, pooled_out, d, next_fp, next_inv, key_out,   \
+      key_inv_out, key_words
+// the reuse step of a call: copies of cached outputs for the rows answered from the bank
+__global__ __launch_bounds__(kGatherThreads) void gather_kernel(LLMC_GATHER_PARAMS) { gather_body(LLMC_GATHER_ARGS); }
+// the same copy for rows that arrived as references (deferred copies): a separate name, so that traces tell the
+// usually empty just-in-time copies from the reuse step
+__global__ __launch_bounds__(kGatherThreads) void materialize_kernel(LLMC_GATHER_PARAMS) { gather_body(LLMC_GATHER_ARGS); }
 
 // value row of the i-th listed hit: act_slot[idx[rows[i]]]
 __global__ void hit_slots_kernel(const int32_t* __restrict__ idx, const int32_t* __restrict__ rows,
@@ -269,6 +291,22 @@ llmc_status_t launch_gather(const llmc_bank* bank, const int32_t* d_idx, const i
                      (D.d_next_fp && d_key_inv_out) ? (uint32_t*)d_key_out : nullptr, d_key_inv_out,
                      (int)((size_t)D.next_k * elem_size(D.dtype) / 4)); }
   LLMC_LAUNCH_CHECK("gather_kernel");
+  return LLMC_OK;
+}
+
+// copy of referenced value rows: out[rows[i] or i] = act[ref[...]] for the listed rows whose reference is >= 0
+llmc_status_t launch_materialize(const llmc_bank* bank, const int32_t* d_ref, const int32_t* d_rows, const int32_t* d_n,
+                                 int n_max, void* d_h, hipStream_t st) {
+  const llmc_bank_desc_t& D = bank->desc;
+  const size_t vec_per_seq = (size_t)D.S * D.d * elem_size(D.dtype) / 16;
+  const size_t per_wg = (size_t)kGatherThreads * kGatherVecPerThread;
+  dim3 grid((unsigned)((vec_per_seq + per_wg - 1) / per_wg), n_max);
+  { ProfScope ps_("materialize_kernel", st);
+    hipLaunchKernelGGL(materialize_kernel, grid, dim3(kGatherThreads), 0, st, (const u32x4_t*)D.d_act,
+                       (const int32_t*)nullptr, d_ref, d_rows, d_n, n_max, vec_per_seq, (u32x4_t*)d_h, (const float*)nullptr,
+                       (float*)nullptr, D.d, (const uint32_t*)nullptr, (const float*)nullptr, (uint32_t*)nullptr,
+                       (float*)nullptr, 0); }
+  LLMC_LAUNCH_CHECK("materialize_kernel");
   return LLMC_OK;
 }
 

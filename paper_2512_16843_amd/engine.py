@@ -46,6 +46,7 @@ class GatedStack:
         # keep_means: banks store the token mean of every cached output and a reused row hands it to the next layer
         self.keep_means = keep_means
         self._hint = [False] * cfg.n_layers
+        self._deferred = [False] * cfg.n_layers
         self._stat_host = torch.zeros((cfg.n_layers, llmc.CNT_WORDS), dtype=torch.int32).pin_memory() if keep_means else None
         self.counters_all = torch.zeros((cfg.n_layers, llmc.CNT_WORDS), dtype=torch.int32, device=device)
         self._stat_event = None
@@ -72,9 +73,13 @@ class GatedStack:
         self._stat_event.record()
 
     def forward(self, h0: torch.Tensor, tau: float, flags: int = 0, tick: int = 0, keep_all: bool = False,
-                single_fingerprint: bool = False):
+                single_fingerprint: bool = False, defer: Optional[bool] = None):
         """Run all layers; returns h_L (a view of an internal buffer) or, with
-        ``keep_all``, the list [h_1 .. h_L] as fresh tensors."""
+        ``keep_all``, the list [h_1 .. h_L] as fresh tensors.
+
+        ``defer`` (default: on when the banks keep next-layer keys and the call neither inserts nor revalidates):
+        reused rows are handed from layer to layer as references to the bank entry that answered them and are
+        copied only where a later layer has to compute them, and once at the end."""
         cfg = self.cfg
         B = h0.shape[0]
         assert B == self.B and h0.is_contiguous()
@@ -87,18 +92,55 @@ class GatedStack:
             llmc.llmc_fingerprint(h0, self.proj[0], self.bias[0], fp_given, inv_given, self.workspace)
         if self.keep_means:
             self._update_hints()
+        can_defer = (self.keep_next_keys and not keep_all and not single_fingerprint and
+                     not (flags & (llmc.INSERT_ON_MISS | llmc.REVALIDATE)))
+        defer = can_defer if defer is None else (defer and can_defer)
+        prev = None                      # the bank whose entries the rows of h may refer to
+        self._deferred = [False] * cfg.n_layers
         for l in range(cfg.n_layers):
             out = torch.empty_like(h0) if keep_all else self.buf[l & 1]
+            if out.data_ptr() == h.data_ptr():
+                out = self.buf[(l & 1) ^ 1]
             carry = self.gate[l - 1] if (self.keep_means and l > 0) else None
             fl = flags | (llmc.HINT_MOSTLY_CARRIED if (carry is not None and self._hint[l]) else 0)
-            llmc.llmc_layer_forward_gated(self.layers[l], self.banks[l], self.proj[l], self.bias[l], h, out, tau,
-                                          fl, tick, self.workspace, self.gate[l], fp_given, inv_given, carry=carry)
+            bank = self.banks[l]
+            # a row may stay a reference across this layer only if this layer's bank stores the key that the
+            # next layer needs; the last layer (and a layer before an uncached one) copies as usual
+            defer_here = defer and bank is not None and bank.next_fp is not None
+            if prev is not None and (bank is None or bank.key_bits):
+                llmc.llmc_materialize(prev, self.gate[l - 1].ref, h)          # this layer cannot take references
+                prev = None
+            llmc.llmc_layer_forward_gated(self.layers[l], bank, self.proj[l], self.bias[l], h, out, tau,
+                                          fl | (llmc.DEFER_COPY if defer_here else 0), tick, self.workspace,
+                                          self.gate[l], fp_given, inv_given, carry=carry, prev_bank=prev)
+            prev = bank if defer_here else None
+            self._deferred[l] = defer_here
             h = out
             if keep_all:
                 outs.append(out)
+        if prev is not None:
+            llmc.llmc_materialize(prev, self.gate[cfg.n_layers - 1].ref, h)
         if self.keep_means:
             self._start_stats()
         return outs if keep_all else h
+
+    def copied_rows(self):
+        """(plain, just_in_time): rows of cached outputs that the last forward copied in the reuse step of layers that
+        did not defer, and rows that travelled as references and were copied because a later layer had to compute
+        them or because they were still outstanding at the end (one host sync)."""
+        plain = jit = 0
+        L = self.cfg.n_layers
+        for l in range(L):
+            if self.banks[l] is None:
+                continue
+            g = self.gate[l]
+            if not self._deferred[l]:
+                plain += int(g.hit.sum())
+            elif l + 1 < L:
+                jit += int(((g.ref >= 0) & (self.gate[l + 1].hit == 0)).sum())
+            else:
+                jit += int((g.ref >= 0).sum())
+        return plain, jit
 
     def hit_counts(self) -> torch.Tensor:
         """[L, CNT_WORDS] device counters of the last forward (one host sync)."""

@@ -20,7 +20,7 @@ LLMC_OK = 0
 ERR_INVALID_ARG, ERR_SHAPE, ERR_DTYPE, ERR_BANK_FULL, ERR_WORKSPACE, ERR_HIP = 1, 2, 3, 4, 5, 6
 F32, BF16 = 0, 1
 EVICT_NONE, EVICT_LRU, EVICT_DECAYED_HITS = 0, 1, 2
-INSERT_ON_MISS, UPDATE_LRU, REVALIDATE, HINT_MOSTLY_CARRIED = 1, 2, 4, 8
+INSERT_ON_MISS, UPDATE_LRU, REVALIDATE, HINT_MOSTLY_CARRIED, DEFER_COPY = 1, 2, 4, 8, 16
 CNT_HIT, CNT_MISS, CNT_NEAR_TAU, CNT_NEAR_TIE, CNT_INSERTED, CNT_EVICTED, CNT_DROPPED = 0, 1, 2, 3, 4, 5, 6
 CNT_COMPUTED, CNT_REVALIDATED, CNT_DIVERGED, CNT_WORDS = 7, 8, 9, 12
 MAX_UPDATE_ROWS = 4096
@@ -32,7 +32,7 @@ EXPORTS = [
     "llmc_layer_workspace_bytes", "llmc_profile_begin", "llmc_profile_report", "llmc_profile_end",
     "llmc_last_error", "llmc_version", "llmc_fingerprint_bits", "llmc_match_bits",
     "llmc_match_bits_workspace_bytes", "llmc_max_hamming", "llmc_bank_pool_values",
-    "llmc_lsh_index_bytes", "llmc_lsh_build", "llmc_match_bits_lsh",
+    "llmc_lsh_index_bytes", "llmc_lsh_build", "llmc_match_bits_lsh", "llmc_materialize",
 ]
 
 
@@ -59,13 +59,14 @@ class LayerDesc(C.Structure):
 class FpDesc(C.Structure):
     _fields_ = [("d_proj", C.c_void_p), ("d_bias", C.c_void_p), ("k", C.c_int32),
                 ("d_pooled_in", C.c_void_p), ("d_pooled_in_valid", C.c_void_p), ("d_key_in", C.c_void_p),
-                ("d_key_inv_in", C.c_void_p)]
+                ("d_key_inv_in", C.c_void_p), ("prev_bank", C.c_void_p), ("d_ref_in", C.c_void_p)]
 
 
 class GateOut(C.Structure):
     _fields_ = [("d_idx", C.c_void_p), ("d_sim", C.c_void_p), ("d_hit", C.c_void_p),
                 ("d_counters", C.c_void_p), ("d_slots", C.c_void_p), ("d_pooled_out", C.c_void_p),
-                ("d_pooled_out_valid", C.c_void_p), ("d_key_out", C.c_void_p), ("d_key_inv_out", C.c_void_p)]
+                ("d_pooled_out_valid", C.c_void_p), ("d_key_out", C.c_void_p), ("d_key_inv_out", C.c_void_p),
+                ("d_ref_out", C.c_void_p)]
 
 
 class LlmcError(RuntimeError):
@@ -94,6 +95,7 @@ def lib() -> C.CDLL:
         L.llmc_bank_insert.argtypes = [vp, vp, vp, vp, vp, vp, i32, u64, vp, vp, vp]
         L.llmc_bank_evict.argtypes = [vp, vp, i32, vp, vp]
         L.llmc_bank_pool_values.argtypes = [vp, vp]
+        L.llmc_materialize.argtypes = [vp, vp, i32, vp, vp]
         L.llmc_fingerprint.argtypes = [vp, i32, i32, i32, i32, vp, vp, i32, vp, vp, vp, sz, vp]
         L.llmc_fingerprint_workspace_bytes.argtypes = [i32, i32, i32]
         L.llmc_fingerprint_workspace_bytes.restype = sz
@@ -326,6 +328,10 @@ def llmc_match_bits_lsh(bank_bits: torch.Tensor, index: torch.Tensor, query_bits
                                      _stream(stream)))
 
 
+def llmc_materialize(bank: Bank, ref: torch.Tensor, h: torch.Tensor, stream=None) -> None:
+    _check(lib().llmc_materialize(bank.handle, _ptr(ref), h.shape[0], _ptr(h), _stream(stream)))
+
+
 def llmc_gather_hits(bank: Bank, idx: torch.Tensor, rows: Optional[torch.Tensor], n: Optional[torch.Tensor],
                      n_max: int, h_out: torch.Tensor, stream=None) -> None:
     _check(lib().llmc_gather_hits(bank.handle, _ptr(idx), _ptr(rows), _ptr(n), n_max, _ptr(h_out), _stream(stream)))
@@ -371,6 +377,8 @@ class GateBuffers:
         self.pooled_valid = torch.zeros((B,), dtype=torch.uint8, device=device) if d > 0 else None
         self.key = torch.zeros((B, next_k), dtype=dtype, device=device) if next_k > 0 else None
         self.key_inv = torch.zeros((B,), dtype=torch.float32, device=device) if next_k > 0 else None
+        # deferred copies: value row of the entry that answered a row, -1 where the row was written
+        self.ref = torch.full((B,), -1, dtype=torch.int32, device=device)
         self.idx = torch.empty((B,), dtype=torch.int32, device=device)
         self.sim = torch.empty((B,), dtype=torch.float32, device=device)
         self.hit = torch.empty((B,), dtype=torch.uint8, device=device)
@@ -380,23 +388,27 @@ class GateBuffers:
 
     def struct(self) -> GateOut:
         return GateOut(_ptr(self.idx), _ptr(self.sim), _ptr(self.hit), _ptr(self.counters), _ptr(self.slots),
-                       _ptr(self.pooled), _ptr(self.pooled_valid), _ptr(self.key), _ptr(self.key_inv))
+                       _ptr(self.pooled), _ptr(self.pooled_valid), _ptr(self.key), _ptr(self.key_inv), _ptr(self.ref))
 
 
 def llmc_layer_forward_gated(layer: Layer, bank: Optional[Bank], proj: Optional[torch.Tensor],
                              bias: Optional[torch.Tensor], h_in: torch.Tensor, h_out: torch.Tensor, tau: float,
                              flags: int, tick: int, workspace: torch.Tensor, out: Optional[GateBuffers] = None,
                              fp_given: Optional[torch.Tensor] = None, inv_norm_given: Optional[torch.Tensor] = None,
-                             stream=None, carry: Optional["GateBuffers"] = None) -> None:
+                             stream=None, carry: Optional["GateBuffers"] = None,
+                             prev_bank: Optional[Bank] = None) -> None:
     """``carry``: the GateBuffers of the call that produced ``h_in`` (its pooled / pooled_valid are taken as the
-    token means of the rows it answered from its bank)."""
+    token means of the rows it answered from its bank).  ``prev_bank``: that call was made with DEFER_COPY on this
+    bank; carry.ref then says which rows of ``h_in`` are references to its value rows."""
     B, S, _ = h_in.shape
     ld = layer.desc()
     fpd = FpDesc(_ptr(proj), _ptr(bias), proj.shape[1] if proj is not None else 0,
                  _ptr(carry.pooled) if carry is not None else None,
                  _ptr(carry.pooled_valid) if carry is not None else None,
                  _ptr(carry.key) if carry is not None else None,
-                 _ptr(carry.key_inv) if carry is not None else None)
+                 _ptr(carry.key_inv) if carry is not None else None,
+                 prev_bank.handle if prev_bank is not None else None,
+                 _ptr(carry.ref) if (prev_bank is not None and carry is not None) else None)
     go = out.struct() if out is not None else None
     _check(lib().llmc_layer_forward_gated(
         C.byref(ld), bank.handle if bank is not None else None, C.byref(fpd), _ptr(h_in), _ptr(h_out), B, S, tau,

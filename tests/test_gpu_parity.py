@@ -963,6 +963,7 @@ def test_carried_token_means_change_nothing(L, dtype):
     Ps = W.make_projection(cfg.d, cfg.k, cfg.torch_dtype, seed=3, n_layers=cfg.n_layers)
     stacks = [GatedStack(cfg, ws, Ps, keep_means=km, keep_next_keys=kk)
               for km, kk in ((False, False), (True, False), (True, True))]
+    final = []
     src = W.make_sources(cfg, 16, seed=1)
     fresh = W.make_sources(cfg, 8, seed=9)
     batches = [(src[0:8], 2.0, L.INSERT_ON_MISS), (src[8:16], 2.0, L.INSERT_ON_MISS),
@@ -973,6 +974,22 @@ def test_carried_token_means_change_nothing(L, dtype):
         h0 = W.embed(torch.from_numpy(ids), tok, pos, cfg.torch_dtype).cuda()
         outs = [st.forward(h0, tau=tau, flags=flags, tick=tick, keep_all=True) for st in stacks]
         torch.cuda.synchronize()
+        if not (flags & L.INSERT_ON_MISS):
+            # the same batch once more without keeping every layer: reused rows travel as references (deferred
+            # copies) through the stack with stored keys; final output, decisions and slots must be the same bits
+            y_plain = stacks[0].forward(h0, tau=tau, flags=flags, tick=tick).clone()
+            hits_plain = [g.hit.clone() for g in stacks[0].gate]
+            idx_plain = [g.idx.clone() for g in stacks[0].gate]
+            y_defer = stacks[2].forward(h0, tau=tau, flags=flags, tick=tick).clone()
+            torch.cuda.synchronize()
+            assert torch.equal(y_plain, y_defer), tick
+            for l in range(cfg.n_layers):
+                assert torch.equal(hits_plain[l], stacks[2].gate[l].hit) and torch.equal(idx_plain[l], stacks[2].gate[l].idx)
+            refs = [int((g.ref >= 0).sum()) for g in stacks[2].gate]
+            final.append(refs)
+            y_off = stacks[2].forward(h0, tau=tau, flags=flags, tick=tick, defer=False).clone()
+            torch.cuda.synchronize()
+            assert torch.equal(y_plain, y_off)
         for l in range(cfg.n_layers):
           for other in (1, 2):
             a, b = stacks[0].gate[l], stacks[other].gate[l]
@@ -999,6 +1016,27 @@ def test_carried_token_means_change_nothing(L, dtype):
     assert torch.equal(bk.act_pool[v], stored[v])
     ref = npf(bk.act)[v.cpu().numpy()].astype(np.float64).mean(axis=1)
     np.testing.assert_allclose(npf(bk.act_pool[v]), ref, rtol=0, atol=1e-5 * max(1.0, np.abs(ref).max()))
+    # a row that is a reference and then has to be computed: free two entries of layer 2's banks, so that rows which
+    # hit at layer 1 miss at layer 2 (their input is copied from layer 1's bank just in time) and hit again at layer 3
+    ids, tau, _ = batches[2]
+    h0 = W.embed(torch.from_numpy(ids), tok, pos, cfg.torch_dtype).cuda()
+    stacks[0].forward(h0, tau=tau)
+    torch.cuda.synchronize()
+    gone = stacks[0].gate[1].idx[:2].long().cpu()
+    for st in stacks:
+        st.banks[1].valid[gone.cuda()] = 0
+        st.banks[1].refresh()
+    y_plain = stacks[0].forward(h0, tau=tau).clone()
+    pattern = [int(g.hit.sum()) for g in stacks[0].gate]
+    y_defer = stacks[2].forward(h0, tau=tau).clone()
+    torch.cuda.synchronize()
+    assert pattern[1] <= pattern[0] - 2 and pattern[2] >= pattern[1], pattern      # some references had to be computed
+    assert torch.equal(y_plain, y_defer)
+    for l in range(cfg.n_layers):
+        assert torch.equal(stacks[0].gate[l].hit, stacks[2].gate[l].hit)
+    say(f"  with two entries of layer 2 freed: hits per layer {pattern}, deferred run equal")
+    say(f"  rows left as references per layer in the deferred runs: {final}")
+    assert any(sum(r) > 0 for r in final)
     # stored next-layer keys = the fingerprint of the stored outputs under the next layer's map, bit for bit,
     # both as written at insertion and as recomputed by llmc_bank_pool_values
     bk = stacks[2].banks[0]
