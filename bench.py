@@ -9,6 +9,9 @@ Banks are built first by the library's own all-miss + insert path.
 --workload selects the GPT-2-small-shaped decoder or the BERT-large-shaped stack
 with dynamic banks instead; the default is the configuration the metric is quoted on.
 
+Timed steps are replays of a HIP graph that records exactly one step's library launches
+(--no-graph enqueues them from Python instead).
+
 Prints ONE JSON line: whole-job sequences/s at the headline threshold, the sweep over
 thresholds with measured hit rates, the roofline of the dominant kernel (per-kernel
 durations from HIP events recorded on the launch stream), and the CPU oracle timed on
@@ -347,7 +350,9 @@ def main():
                                   cfg.S, cfg.n_bank, cfg.k, recipe),
                    "tau": args.tau,
                    "hit_rate": round(float(cnt_head[:, llmc.CNT_HIT].sum()) / (cfg.B * cfg.n_layers), 4),
-                   "bank_build_s": round(build_s, 2), "launches_per_step": launches_per_step},
+                   "bank_build_s": round(build_s, 2), "launches_per_step": launches_per_step,
+                   "timed_steps": "eager launches from Python" if args.no_graph else "replays of a HIP graph of one step",
+                   "carried_keys_and_deferred_copies": not args.no_carry},
         "sweep": sweep,
         "dial": dial,
         "roofline": roof,
