@@ -16,6 +16,7 @@
 // ties).  The reported similarity is that fp64 cosine.
 #include "common.h"
 #include "mma.h"
+#include "compact.h"
 
 namespace llmc {
 
@@ -593,6 +594,118 @@ __global__ __launch_bounds__(256) void match_finalize_kernel(
   }
 }
 
+// ---- small batches: the exact decision and the compaction in one launch ------------------------------------
+// One workgroup of 1024 threads for B <= 64 queries, 16 lanes per query.  Same arithmetic as match_finalize_kernel:
+// the partial results of the bank splits are merged, then lane r of a query evaluates row r of the best candidate
+// group (and of the runner-up when within 1e-5) in fp64 -- the four quarter sums of the key that the four lanes of
+// the stand-alone kernel hold are formed one after the other and added as (s0 + s1) + (s2 + s3), so the reported
+// similarity is the same bits -- and a butterfly over the 16 lanes picks the winner.  The rows' results then go
+// through compact_rows without leaving the workgroup.
+template <typename T>
+__global__ __launch_bounds__(1024) void match_decide_kernel(
+    const Top2* __restrict__ partial, int n_split, const T* __restrict__ bank, const float* __restrict__ binv,
+    const uint8_t* __restrict__ valid, int N, int K, const T* __restrict__ queries, const float* __restrict__ qinv,
+    int B, float tau, int32_t* __restrict__ idx_out, float* __restrict__ sim_out, uint8_t* __restrict__ hit_out,
+    int32_t* __restrict__ hit_rows, int32_t* __restrict__ miss_rows, int32_t* __restrict__ counters,
+    uint64_t* last_used, uint32_t* hits, int touch, uint64_t tick, int reval_every, int32_t* __restrict__ reval_tmp,
+    uint8_t* __restrict__ pooled_valid_out, int has_pool, int32_t* __restrict__ ref_out,
+    const int32_t* __restrict__ act_slot) {
+  constexpr int VEC = Vec16<T>::N;
+  __shared__ int32_t s_idx[64];
+  __shared__ float s_sim[64];
+  __shared__ uint8_t s_hit[64], s_tie[64];
+  const int b = threadIdx.x >> 4, r = threadIdx.x & 15;
+  if (b < B) {
+    Top2 t = top2_empty();
+    // eight partial results in flight per lane, merged in ascending split order
+    for (int s0 = r; s0 < n_split; s0 += 8 * 16) {
+      Top2 c[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int s = s0 + u * 16;
+        c[u] = s < n_split ? partial[(size_t)s * B + b] : top2_empty();
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        top2_push(t, c[u].v1, c[u].g1);
+        top2_push(t, c[u].v2, c[u].g2);
+      }
+    }
+#pragma unroll
+    for (int o = 8; o > 0; o >>= 1) {
+      Top2 c;
+      c.v1 = __shfl_xor(t.v1, o, 64); c.g1 = __shfl_xor(t.g1, o, 64);
+      c.v2 = __shfl_xor(t.v2, o, 64); c.g2 = __shfl_xor(t.g2, o, 64);
+      top2_push(t, c.v1, c.g1);
+      top2_push(t, c.v2, c.g2);
+    }
+    const float qi = qinv[b];
+    const double qi64 = (double)qi;
+    const float gap = qi > 0.f ? 1e-5f / qi : 0.f;
+    const bool two = t.g2 >= 0 && t.v2 >= t.v1 - gap;
+    const int n_groups = (t.g1 < 0) ? 0 : (two ? 2 : 1);
+    const int per = K / 4;
+    double best = -INFINITY;
+    int best_j = -1;
+    for (int c = 0; c < n_groups; ++c) {
+      const int g = c == 0 ? t.g1 : t.g2;
+      const int j = group_row(g, r);
+      const int jc = min(j, N - 1);
+      const bool ok = j < N && valid[jc] != 0;
+      const double bj = (double)binv[jc];
+      double quarter[4];
+#pragma unroll
+      for (int part = 0; part < 4; ++part) {
+        const T* qp = queries + (size_t)b * K + part * per;
+        const T* kp = bank + (size_t)jc * K + part * per;
+        double a = 0.0;
+        int i = 0;
+        for (; i + 8 * VEC <= per; i += 8 * VEC) {
+          float x[8][VEC], y[8][VEC];
+#pragma unroll
+          for (int u = 0; u < 8; ++u) {
+            Vec16<T>::load(qp + i + u * VEC, x[u]);
+            Vec16<T>::load(kp + i + u * VEC, y[u]);
+          }
+#pragma unroll
+          for (int u = 0; u < 8; ++u)
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) a += (double)x[u][e] * (double)y[u][e];
+        }
+        for (; i < per; i += VEC) {
+          float x[VEC], y[VEC];
+          Vec16<T>::load(qp + i, x);
+          Vec16<T>::load(kp + i, y);
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) a += (double)x[e] * (double)y[e];
+        }
+        quarter[part] = a;
+      }
+      const double a = (quarter[0] + quarter[1]) + (quarter[2] + quarter[3]);
+      if (ok) {
+        const double s = a * qi64 * bj;
+        if (s > best || (s == best && (best_j < 0 || j < best_j))) { best = s; best_j = j; }
+      }
+    }
+#pragma unroll
+    for (int o = 1; o < 16; o <<= 1) {
+      const double os = __shfl_xor(best, o, 64);
+      const int oj = __shfl_xor(best_j, o, 64);
+      if (oj >= 0 && (best_j < 0 || os > best || (os == best && oj < best_j))) { best = os; best_j = oj; }
+    }
+    if (r == 0) {
+      const uint8_t h = (best_j >= 0 && best > (double)tau) ? 1 : 0;
+      s_idx[b] = best_j; s_sim[b] = (float)best; s_hit[b] = h; s_tie[b] = two ? 1 : 0;
+      idx_out[b] = best_j;
+      if (sim_out) sim_out[b] = (float)best;
+      if (hit_out) hit_out[b] = h;
+    }
+  }
+  __syncthreads();
+  compact_rows(s_hit, s_idx, s_sim, s_tie, B, tau, hit_rows, miss_rows, counters, last_used, hits, touch, tick,
+               reval_every, reval_tmp, pooled_valid_out, has_pool, ref_out, act_slot);
+}
+
 static void split_plan(int N, int B, int* n_split, int* tiles_per_split) {
   const int tiles = (N + MatchCfg::BM - 1) / MatchCfg::BM;
   const int qb = (B + MatchCfg::BN - 1) / MatchCfg::BN;
@@ -666,6 +779,61 @@ static llmc_status_t launch_stream(const llmc_bank* bank, const void* d_fp, int 
   hipLaunchKernelGGL((match_skew_kernel<K_>), dim3(grid), dim3(512), C::LDS_BYTES, st, (const uint16_t*)D.d_fp,
                      bank->d_binv_eff, D.n_slots, (const uint16_t*)d_fp, B, nqb, ns, per, partial);
   *ns_out = ns;
+  return LLMC_OK;
+}
+
+// the bulk pass only: per-(split, query) candidates in ws; *ns_out splits
+static llmc_status_t launch_match_bulk(const llmc_bank* bank, const void* d_fp, int B, void* ws, int* ns_out,
+                                       hipStream_t st) {
+  const llmc_bank_desc_t& D = bank->desc;
+  const int N = D.n_slots, K = D.k;
+  Top2* partial = (Top2*)ws;
+  int ns = 1, per = 1;
+  if (D.dtype == LLMC_BF16) {
+    if (use_stream(K)) {
+      if (K == 256) LLMC_TRY(launch_stream<256>(bank, d_fp, B, partial, &ns, st));
+      else if (K == 128) LLMC_TRY(launch_stream<128>(bank, d_fp, B, partial, &ns, st));
+      else LLMC_TRY(launch_stream<64>(bank, d_fp, B, partial, &ns, st));
+      LLMC_LAUNCH_CHECK("match_stream_kernel");
+    } else {
+      split_plan(N, B, &ns, &per);
+      dim3 grid(ns, (B + MatchCfg::BN - 1) / MatchCfg::BN);
+      { ProfScope ps_("match_bf16_kernel", st); hipLaunchKernelGGL(match_bf16_kernel, grid, dim3(MatchCfg::THREADS), 0, st, (const uint16_t*)D.d_fp,
+                         bank->d_binv_eff, N, K, (const uint16_t*)d_fp, B, per, partial); }
+      LLMC_LAUNCH_CHECK("match_bf16_kernel");
+    }
+  } else {
+    { ProfScope ps_("match_f32_kernel", st); hipLaunchKernelGGL(match_f32_kernel, dim3(B), dim3(256), (size_t)K * sizeof(float) + 256 * sizeof(Top2), st,
+                       (const float*)D.d_fp, bank->d_binv_eff, N, K, (const float*)d_fp, partial); }
+    LLMC_LAUNCH_CHECK("match_f32_kernel");
+  }
+  *ns_out = ns;
+  return LLMC_OK;
+}
+
+// match + threshold + compaction for a small batch (B <= 64): the bulk pass, then ONE launch that decides exactly
+// and compacts (the work of match_finalize_kernel and compact_kernel)
+llmc_status_t launch_match_decide(llmc_bank* bank, const void* d_fp, const float* d_inv, int B, float tau, int32_t* d_idx,
+                                  float* d_sim, uint8_t* d_hit, void* ws, int32_t* d_hit_rows, int32_t* d_miss_rows,
+                                  int32_t* d_reval_tmp, int32_t* d_counters, uint32_t flags, uint64_t tick,
+                                  uint8_t* d_pooled_valid_out, int has_pool, int32_t* d_ref_out, hipStream_t st) {
+  const llmc_bank_desc_t& D = bank->desc;
+  int ns = 1;
+  LLMC_TRY(launch_match_bulk(bank, d_fp, B, ws, &ns, st));
+  const int touch = (flags & LLMC_UPDATE_LRU) ? 1 : 0;
+  const int reval_every = (flags & LLMC_REVALIDATE) ? D.reval_every : 0;
+  ProfScope ps_("match_decide_kernel", st);
+  if (D.dtype == LLMC_BF16)
+    hipLaunchKernelGGL((match_decide_kernel<bf16_t>), dim3(1), dim3(1024), 0, st, (const Top2*)ws, ns, (const bf16_t*)D.d_fp,
+                       D.d_inv_norm, D.d_valid, D.n_slots, D.k, (const bf16_t*)d_fp, d_inv, B, tau, d_idx, d_sim, d_hit,
+                       d_hit_rows, d_miss_rows, d_counters, D.d_last_used, D.d_hits, touch, tick, reval_every, d_reval_tmp,
+                       d_pooled_valid_out, has_pool, d_ref_out, D.d_act_slot);
+  else
+    hipLaunchKernelGGL((match_decide_kernel<float>), dim3(1), dim3(1024), 0, st, (const Top2*)ws, 1, (const float*)D.d_fp,
+                       D.d_inv_norm, D.d_valid, D.n_slots, D.k, (const float*)d_fp, d_inv, B, tau, d_idx, d_sim, d_hit,
+                       d_hit_rows, d_miss_rows, d_counters, D.d_last_used, D.d_hits, touch, tick, reval_every, d_reval_tmp,
+                       d_pooled_valid_out, has_pool, d_ref_out, D.d_act_slot);
+  LLMC_LAUNCH_CHECK("match_decide_kernel");
   return LLMC_OK;
 }
 
