@@ -245,6 +245,11 @@ typedef struct {
   void* d_key_out;
   float* d_key_inv_out;
   int32_t* d_ref_out;           /* [B], written with LLMC_DEFER_COPY: value row of the matched entry, or -1 */
+  /* The keys the rows were matched with, [B, k] in the bank's key form (element type `dtype`, or uint32 words for a
+   * bank of sign-bit keys), and their inverse norms [B] (real-valued keys only): whatever their source was --
+   * computed here, carried, or taken from the producing bank's stored keys.  Not written when d_fp_given is used. */
+  void* d_fp_used;
+  float* d_inv_norm_used;
 } llmc_gate_out_t;
 
 /* ---- bank -------------------------------------------------------------- */

@@ -506,6 +506,7 @@ llmc_status_t llmc_layer_forward_gated(const llmc_layer_desc_t* layer, llmc_bank
   const size_t need = llmc_layer_workspace_bytes(layer, B, S, k);
   REQUIRE(d_workspace && workspace_bytes >= need, LLMC_ERR_WORKSPACE, "layer workspace needs %zu bytes", need);
   REQUIRE(aligned16(d_workspace), LLMC_ERR_SHAPE, "workspace must be 16-byte aligned");
+  REQUIRE(!out || !out->d_fp_used || aligned16(out->d_fp_used), LLMC_ERR_SHAPE, "d_fp_used must be 16-byte aligned");
 
   hipStream_t st = (hipStream_t)stream;
   char* p = (char*)d_workspace;
@@ -530,6 +531,8 @@ llmc_status_t llmc_layer_forward_gated(const llmc_layer_desc_t* layer, llmc_bank
     if (out->d_hit) hit = out->d_hit;
     if (out->d_counters) counters = out->d_counters;
     if (out->d_slots) slots = out->d_slots;
+    if (out->d_fp_used) keys = out->d_fp_used;
+    if (out->d_inv_norm_used) inv = out->d_inv_norm_used;
   }
   if (!bank) {
     LLMC_TRY(launch_all_miss(B, miss_rows, counters, out ? out->d_idx : nullptr, out ? out->d_sim : nullptr,

@@ -19,7 +19,8 @@ class GatedStack:
                  biases: Optional[List[Optional[torch.Tensor]]] = None, n_bank: Optional[int] = None,
                  policy: int = llmc.EVICT_LRU, B: Optional[int] = None, half_life: int = 0, reval_every: int = 0,
                  drift_bound: float = 0.0, bases: Optional[List[Optional[torch.Tensor]]] = None,
-                 keep_means: bool = False, keep_next_keys: bool = False, key_bits: bool = False):
+                 keep_means: bool = False, keep_next_keys: bool = False, key_bits: bool = False,
+                 expose_keys: bool = False):
         self.cfg = cfg
         self.device = device
         self.B = cfg.B if B is None else B
@@ -52,7 +53,9 @@ class GatedStack:
         self._stat_event = None
         self.gate = [llmc.GateBuffers(self.B, device, d=cfg.d if keep_means else 0,
                                       next_k=cfg.k if (self.banks[l] is not None and self.banks[l].next_fp is not None) else 0,
-                                      dtype=cfg.torch_dtype, counters=self.counters_all[l]) for l in range(cfg.n_layers)]
+                                      dtype=cfg.torch_dtype, counters=self.counters_all[l],
+                                      k_used=cfg.k if expose_keys else 0, key_bits=key_bits)
+                     for l in range(cfg.n_layers)]
 
     def _update_hints(self) -> None:
         """Launch-shape hints from the hit counts of an EARLIER forward, read without waiting: when the copy that a

@@ -66,7 +66,7 @@ class GateOut(C.Structure):
     _fields_ = [("d_idx", C.c_void_p), ("d_sim", C.c_void_p), ("d_hit", C.c_void_p),
                 ("d_counters", C.c_void_p), ("d_slots", C.c_void_p), ("d_pooled_out", C.c_void_p),
                 ("d_pooled_out_valid", C.c_void_p), ("d_key_out", C.c_void_p), ("d_key_inv_out", C.c_void_p),
-                ("d_ref_out", C.c_void_p)]
+                ("d_ref_out", C.c_void_p), ("d_fp_used", C.c_void_p), ("d_inv_norm_used", C.c_void_p)]
 
 
 class LlmcError(RuntimeError):
@@ -370,7 +370,7 @@ class GateBuffers:
     """Optional per-row outputs of the gate, allocated once per (B)."""
 
     def __init__(self, B: int, device="cuda", d: int = 0, next_k: int = 0, dtype: torch.dtype = torch.bfloat16,
-                 counters: Optional[torch.Tensor] = None):
+                 counters: Optional[torch.Tensor] = None, k_used: int = 0, key_bits: bool = False):
         # d > 0: also the buffers that carry the token means of reused rows to the next layer;
         # next_k > 0: and their finished keys under the next layer's fingerprint map
         self.pooled = torch.zeros((B, d), dtype=torch.float32, device=device) if d > 0 else None
@@ -385,10 +385,16 @@ class GateBuffers:
         # the counters may be a row of a caller's [layers, CNT_WORDS] block, so that one copy fetches all layers
         self.counters = torch.zeros((CNT_WORDS,), dtype=torch.int32, device=device) if counters is None else counters
         self.slots = torch.empty((B,), dtype=torch.int32, device=device)
+        # k_used > 0: the keys the rows were matched with (and their inverse norms) are written here
+        self.fp_used = None if k_used <= 0 else (
+            torch.zeros((B, k_used // 32), dtype=torch.int32, device=device) if key_bits else
+            torch.zeros((B, k_used), dtype=dtype, device=device))
+        self.inv_used = torch.zeros((B,), dtype=torch.float32, device=device) if k_used > 0 else None
 
     def struct(self) -> GateOut:
         return GateOut(_ptr(self.idx), _ptr(self.sim), _ptr(self.hit), _ptr(self.counters), _ptr(self.slots),
-                       _ptr(self.pooled), _ptr(self.pooled_valid), _ptr(self.key), _ptr(self.key_inv), _ptr(self.ref))
+                       _ptr(self.pooled), _ptr(self.pooled_valid), _ptr(self.key), _ptr(self.key_inv), _ptr(self.ref),
+                       _ptr(self.fp_used), _ptr(self.inv_used))
 
 
 def llmc_layer_forward_gated(layer: Layer, bank: Optional[Bank], proj: Optional[torch.Tensor],

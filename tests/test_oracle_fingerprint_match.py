@@ -193,3 +193,65 @@ def test_threshold_strict_and_monotone():
         if prev is not None:
             assert h <= prev
         prev = h
+
+
+# ---- near-tie sets: the slots a parity test may accept besides the oracle's own index ---------
+
+def plane_keys(cosines):
+    """Unit keys (cos t, sin t, 0, 0) in fp64, so that the similarity to the query (1, 0, 0, 0) is cos t."""
+    c = np.asarray(cosines, dtype=np.float64)
+    return np.stack([c, np.sqrt(1.0 - c * c), np.zeros_like(c), np.zeros_like(c)], axis=1)
+
+
+def test_near_tie_sets_on_a_hand_made_bank():
+    # slot:      0 best      1 best - 1e-6   2 invalid, above all   3 best - 1e-5   4 far      5 = slot 0 again
+    cosines = [0.9,          0.9 - 1e-6,     0.99,                  0.9 - 1e-5,     0.1,       0.9]
+    bank = plane_keys(cosines)
+    valid = np.array([1, 1, 0, 1, 1, 1], np.uint8)
+    q = np.array([[1.0, 0.0, 0.0, 0.0]])
+    one = np.ones(1, np.float32)
+    binv = np.ones(6, np.float32)
+    # default gap 2e-6: the two slots 1e-6 apart and the exact duplicate, not the one 1e-5 below, never the invalid one
+    assert O.near_tie_sets(q, one, bank, binv, valid)[0].tolist() == [0, 1, 5]
+    # a wider gap takes the slot 1e-5 below in; the best is still defined by VALID slots only
+    assert O.near_tie_sets(q, one, bank, binv, valid, gap=2e-5)[0].tolist() == [0, 1, 3, 5]
+    # gap 0 keeps exact ties only (the boundary is inclusive)
+    assert O.near_tie_sets(q, one, bank, binv, valid, gap=0.0)[0].tolist() == [0, 5]
+    # just below / just above a distance: 1e-6 apart is outside a gap of 0.9e-6 and inside one of 1.1e-6
+    assert O.near_tie_sets(q, one, bank, binv, valid, gap=0.9e-6)[0].tolist() == [0, 5]
+    assert O.near_tie_sets(q, one, bank, binv, valid, gap=1.1e-6)[0].tolist() == [0, 1, 5]
+    # with slot 2 valid it is the best and stands alone
+    valid2 = np.ones(6, np.uint8)
+    assert O.near_tie_sets(q, one, bank, binv, valid2)[0].tolist() == [2]
+    # the oracle's own match index is always a member, and is the lowest member on exact ties
+    idx, _ = O.match(q, one, bank, binv, valid)
+    assert idx[0] == 0
+
+
+@pytest.mark.parametrize("seed", [0, 1])
+def test_near_tie_sets_equal_brute_force(seed):
+    r = rng(40 + seed)
+    N, B, k = 60, 7, 8
+    bank = O.round_to_bf16(r.standard_normal((N, k)))
+    bank[20] = bank[3]                           # an exact duplicate
+    q = O.round_to_bf16(bank[[3, 11, 40]] + 1e-3 * r.standard_normal((3, k)))
+    q = np.concatenate([q, O.round_to_bf16(r.standard_normal((B - 3, k)))])
+    valid = (r.random(N) > 0.15).astype(np.uint8)
+    valid[[3, 20]] = 1
+    binv, qinv = O.inv_norm(bank), O.inv_norm(q)
+    for gap in (2e-6, 1e-2, 0.3):
+        sets = O.near_tie_sets(q, qinv, bank, binv, valid, gap=gap)
+        for b in range(B):
+            sims = {}
+            for j in range(N):
+                if valid[j]:
+                    dot = math.fsum(float(q[b, t]) * float(bank[j, t]) for t in range(k))
+                    sims[j] = dot * float(qinv[b]) * float(binv[j])
+            best = max(sims.values())
+            want = sorted(j for j, s in sims.items() if s >= best - gap)
+            # rows whose distance to the boundary is below the rounding noise of the two summation orders are not
+            # decidable this way; none occur with these seeds
+            assert all(abs((best - s) - gap) > 1e-12 for s in sims.values())
+            assert sets[b].tolist() == want, (gap, b)
+    assert len(O.near_tie_sets(q, qinv, bank, binv, valid, gap=0.3)[0]) >= 2      # slot 3 and its duplicate at least
+    assert any(len(s_) > 2 for s_ in O.near_tie_sets(q, qinv, bank, binv, valid, gap=0.3))
