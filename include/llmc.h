@@ -457,14 +457,16 @@ size_t llmc_layer_workspace_bytes(const llmc_layer_desc_t* layer, int32_t B, int
 /* ---- measurement aid ------------------------------------------------------------- */
 
 /*
- * Per-kernel timing with HIP events recorded on the launch stream around every kernel
- * the library enqueues.  llmc_profile_begin creates `max_records` event pairs (it
- * allocates; call it outside any timed or captured region) and switches recording on;
- * launches beyond max_records are not recorded.  llmc_profile_report synchronises the
- * device and writes one text line per kernel name, "name count total_ms", into buf
- * (NUL-terminated, truncated to cap), restarts the record count and returns the number
- * of records it read.  llmc_profile_end switches recording off and destroys the events.
- * Recording perturbs back-to-back launches slightly: time whole steps with it off.
+ * Per-kernel timing with HIP events on the launch stream: while recording is on, every kernel
+ * the library enqueues is launched with a start and a stop event of its own (hipExtLaunchKernel),
+ * which carry the begin and the end of that kernel's execution on the device, i.e. the duration a
+ * kernel trace reports for the dispatch (gaps between dispatches are not included).
+ * llmc_profile_begin creates `max_records` event pairs (it allocates; call it outside any timed or
+ * captured region) and switches recording on; launches beyond max_records are not recorded.
+ * llmc_profile_report synchronises the device and writes one text line per kernel name,
+ * "name count total_ms", into buf (NUL-terminated, truncated to cap), restarts the record count and
+ * returns the number of records it read.  llmc_profile_end switches recording off and destroys the
+ * events.  Do not record inside a stream capture; time whole steps with recording off.
  */
 llmc_status_t llmc_profile_begin(int32_t max_records);
 int32_t llmc_profile_report(char* buf, size_t cap);

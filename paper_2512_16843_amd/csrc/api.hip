@@ -33,16 +33,20 @@ static std::vector<ProfRec> g_prof;
 static std::atomic<int> g_prof_used{0};
 static std::atomic<bool> g_prof_on{false};
 
-ProfScope::ProfScope(const char* name, hipStream_t s) : rec(-1), st(s) {
+static thread_local ProfScope* g_prof_cur = nullptr;
+ProfScope* prof_current() { return g_prof_cur; }
+
+ProfScope::ProfScope(const char* name, hipStream_t) : rec(-1), a(nullptr), b(nullptr), outer(g_prof_cur) {
+  g_prof_cur = this;
   if (!g_prof_on.load(std::memory_order_relaxed)) return;
   const int i = g_prof_used.fetch_add(1);
   if (i >= (int)g_prof.size()) return;
   g_prof[i].name = name;
-  if (hipEventRecord(g_prof[i].a, st) == hipSuccess) rec = i;
+  a = g_prof[i].a;
+  b = g_prof[i].b;
+  rec = i;
 }
-ProfScope::~ProfScope() {
-  if (rec >= 0) (void)hipEventRecord(g_prof[rec].b, st);
-}
+ProfScope::~ProfScope() { g_prof_cur = outer; }
 
 static bool dtype_ok(int dt) { return dt == LLMC_F32 || dt == LLMC_BF16; }
 

@@ -56,7 +56,7 @@ __global__ void transpose_kernel(const uint8_t* __restrict__ in, uint8_t* __rest
 }
 
 llmc_status_t launch_transpose(const void* in, void* out, int r, int d, int e, hipStream_t st) {
-  hipLaunchKernelGGL(transpose_kernel, dim3((r * d + 255) / 256), dim3(256), 0, st, (const uint8_t*)in, (uint8_t*)out, r, d, e);
+  LLMC_KERNEL_GGL(transpose_kernel, dim3((r * d + 255) / 256), dim3(256), 0, st, (const uint8_t*)in, (uint8_t*)out, r, d, e);
   LLMC_LAUNCH_CHECK("transpose_kernel");
   return LLMC_OK;
 }
@@ -224,7 +224,7 @@ static void launch_select(const llmc_bank* bank, const int32_t* d_m, int m_max, 
   const llmc_bank_desc_t& D = bank->desc;
   const int N = D.n_slots, by_hits = D.policy == LLMC_EVICT_DECAYED_HITS ? 1 : 0;
   const size_t lds = (size_t)m_max * sizeof(uint64_t);
-#define LLMC_SELECT(KPT_) hipLaunchKernelGGL(select_kernel<KPT_>, dim3(1), dim3(kSelThreads), lds, st, D.d_valid,         \
+#define LLMC_SELECT(KPT_) LLMC_KERNEL_GGL(select_kernel<KPT_>, dim3(1), dim3(kSelThreads), lds, st, D.d_valid,         \
                                              D.d_last_used, D.d_hits, by_hits, N, d_m, m_max, mode_evict, allow_replace, \
                                              slots_out, bank->d_binv_eff, D.key_bits ? kBitsFreePenalty : 0x7FC00000u)
   if (N <= 4 * kSelThreads) LLMC_SELECT(4);
@@ -242,7 +242,7 @@ llmc_status_t launch_bank_advance(llmc_bank* bank, uint64_t tick, hipStream_t st
   const int shift = (int)std::min<int64_t>(31, e - bank->epoch);
   bank->epoch = e;
   { ProfScope ps_("decay_kernel", st);
-    hipLaunchKernelGGL(decay_kernel, dim3((D.n_slots + 255) / 256), dim3(256), 0, st, D.d_hits, D.n_slots, shift); }
+    LLMC_KERNEL_GGL(decay_kernel, dim3((D.n_slots + 255) / 256), dim3(256), 0, st, D.d_hits, D.n_slots, shift); }
   LLMC_LAUNCH_CHECK("decay_kernel");
   return LLMC_OK;
 }
@@ -311,7 +311,7 @@ __global__ __launch_bounds__(kCopyThreads) void insert_kernel(
 llmc_status_t launch_bank_refresh(llmc_bank* bank, hipStream_t st) {
   const int N = bank->desc.n_slots;
   const int n_pad = (int)align_up((size_t)N + 8, 256);      // the mirror's allocated length
-  { ProfScope ps_("refresh_kernel", st); hipLaunchKernelGGL(refresh_kernel, dim3((n_pad + 255) / 256), dim3(256), 0, st, bank->desc.d_valid,
+  { ProfScope ps_("refresh_kernel", st); LLMC_KERNEL_GGL(refresh_kernel, dim3((n_pad + 255) / 256), dim3(256), 0, st, bank->desc.d_valid,
                      bank->desc.d_inv_norm, N, n_pad, bank->d_binv_eff, bank->desc.key_bits); }
   LLMC_LAUNCH_CHECK("refresh_kernel");
   return LLMC_OK;
@@ -336,7 +336,7 @@ llmc_status_t launch_bank_insert(llmc_bank* bank, const void* d_fp, const float*
   const size_t words_per_key = D.key_bits ? (size_t)D.k / 32 : (size_t)D.k * e / 4;
   const size_t per_wg = (size_t)kCopyThreads * kCopyVecPerThread;
   dim3 grid((unsigned)std::max<size_t>(1, (vec_per_seq + per_wg - 1) / per_wg), m_max);
-  { ProfScope ps_("insert_kernel", st); hipLaunchKernelGGL(insert_kernel, grid, dim3(kCopyThreads), 0, st, (const u32x4_t*)d_fp, d_inv, (const u32x4_t*)d_act,
+  { ProfScope ps_("insert_kernel", st); LLMC_KERNEL_GGL(insert_kernel, grid, dim3(kCopyThreads), 0, st, (const u32x4_t*)d_fp, d_inv, (const u32x4_t*)d_act,
                      d_rows, d_m, m_max, d_slots_out, (u32x4_t*)D.d_fp, D.d_inv_norm, (u32x4_t*)D.d_act, D.d_act_slot,
                      D.d_last_used, D.d_hits, D.d_valid, bank->d_binv_eff, words_per_key, vec_per_seq, tick, d_counters,
                      D.key_bits); }

@@ -146,7 +146,7 @@ llmc_status_t launch_match_bits(const uint32_t* d_bank_bits, const uint8_t* d_va
     uint32_t* mine = (uint32_t*)((char*)ws + align_up((size_t)ns * B * sizeof(uint32_t), 256));
     const int n_pad = N + kRowUnroll;
     { ProfScope ps_("bits_penalty_kernel", st);
-      hipLaunchKernelGGL(bits_penalty_kernel, dim3((n_pad + 255) / 256), dim3(256), 0, st, d_valid, N, n_pad, mine); }
+      LLMC_KERNEL_GGL(bits_penalty_kernel, dim3((n_pad + 255) / 256), dim3(256), 0, st, d_valid, N, n_pad, mine); }
     LLMC_LAUNCH_CHECK("bits_penalty_kernel");
     pen = mine;
   }
@@ -154,20 +154,20 @@ llmc_status_t launch_match_bits(const uint32_t* d_bank_bits, const uint8_t* d_va
   dim3 grid(ns, (B + kBitsThreads - 1) / kBitsThreads);
   {
     ProfScope ps_("match_bits_kernel", st);
-#define LLMC_BITS_CASE(W_) hipLaunchKernelGGL(match_bits_kernel<W_>, grid, dim3(kBitsThreads), 0, st, d_bank_bits, pen, \
+#define LLMC_BITS_CASE(W_) LLMC_KERNEL_GGL(match_bits_kernel<W_>, grid, dim3(kBitsThreads), 0, st, d_bank_bits, pen, \
                                               N, d_query_bits, B, per, partial)
     if (W == 2) LLMC_BITS_CASE(2);
     else if (W == 4) LLMC_BITS_CASE(4);
     else if (W == 8) LLMC_BITS_CASE(8);
     else if (W == 16) LLMC_BITS_CASE(16);
     else
-      hipLaunchKernelGGL(match_bits_generic_kernel, grid, dim3(kBitsThreads), (size_t)W * kBitsThreads * sizeof(uint32_t),
+      LLMC_KERNEL_GGL(match_bits_generic_kernel, grid, dim3(kBitsThreads), (size_t)W * kBitsThreads * sizeof(uint32_t),
                          st, d_bank_bits, pen, N, W, d_query_bits, B, per, partial);
 #undef LLMC_BITS_CASE
   }
   LLMC_LAUNCH_CHECK("match_bits_kernel");
   { ProfScope ps_("match_bits_finalize_kernel", st);
-    hipLaunchKernelGGL(match_bits_finalize_kernel, dim3((B + 255) / 256), dim3(256), 0, st, partial, ns, per, B,
+    LLMC_KERNEL_GGL(match_bits_finalize_kernel, dim3((B + 255) / 256), dim3(256), 0, st, partial, ns, per, B,
                        max_hamming, d_idx, d_dist, d_hit, d_sim, k); }
   LLMC_LAUNCH_CHECK("match_bits_finalize_kernel");
   return LLMC_OK;

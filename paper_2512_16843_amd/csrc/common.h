@@ -1,6 +1,7 @@
 // Internal helpers shared by the llmc kernels (gfx950 only).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <atomic>
 #include <stdint.h>
 #include <stddef.h>
@@ -105,19 +106,32 @@ llmc_status_t hip_error(hipError_t e, const char* what);
     hipError_t e_ = hipGetLastError();                   \
     if (e_ != hipSuccess) return hip_error(e_, what);    \
   } while (0)
+#define LLMC_KERNEL_GGL(KERNEL, GRID, BLOCK, LDS, ST, ...)                                              \
+  do {                                                                                                   \
+    ::llmc::ProfScope* p_ = ::llmc::prof_current();                                                      \
+    if (p_ && p_->rec >= 0)                                                                              \
+      hipExtLaunchKernelGGL(KERNEL, GRID, BLOCK, (std::uint32_t)(LDS), ST, p_->a, p_->b, 0, __VA_ARGS__); \
+    else                                                                                                 \
+      hipLaunchKernelGGL(KERNEL, GRID, BLOCK, LDS, ST, __VA_ARGS__);                                     \
+  } while (0)
 #define LLMC_TRY(expr)                                   \
   do {                                                   \
     llmc_status_t s_ = (expr);                           \
     if (s_ != LLMC_OK) return s_;                        \
   } while (0)
 
-// Optional per-kernel timing: brackets one launch with two events on its stream.
+// Optional per-kernel timing.  A ProfScope names the launch that follows it; while recording is on it claims a pair
+// of events, and LLMC_KERNEL_GGL hands them to the launch itself (hipExtLaunchKernelGGL), so that the pair carries
+// the start and the end of that kernel's execution on the device -- the duration a kernel trace reports -- and
+// not the gaps between dispatches.  One launch per scope.
 struct ProfScope {
   ProfScope(const char* name, hipStream_t st);
   ~ProfScope();
   int rec;
-  hipStream_t st;
+  hipEvent_t a, b;
+  ProfScope* outer;
 };
+ProfScope* prof_current();
 
 static inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }

@@ -358,13 +358,13 @@ static llmc_status_t fingerprint_t(const T* h, int B, int S, int d, const T* P, 
                            (size_t)(d + parts * k + R * d) * sizeof(float) <= 64 * 1024;
   if (!inline_pool) {
     dim3 grid(n_chunks, B);
-    { ProfScope ps_("pool_kernel", st); hipLaunchKernelGGL(pool_kernel<T>, grid, dim3(G * R), (size_t)R * d * sizeof(float), st, h, S, d, G, R, partial,
+    { ProfScope ps_("pool_kernel", st); LLMC_KERNEL_GGL(pool_kernel<T>, grid, dim3(G * R), (size_t)R * d * sizeof(float), st, h, S, d, G, R, partial,
                        n_chunks, pooled_valid, (const int32_t*)nullptr, (const int32_t*)nullptr, key_index); }
     LLMC_LAUNCH_CHECK("pool_kernel");
   }
   {
     ProfScope ps_("project_kernel", st);
-    hipLaunchKernelGGL(project_kernel<T>, dim3(B), dim3(threads),
+    LLMC_KERNEL_GGL(project_kernel<T>, dim3(B), dim3(threads),
                        (size_t)(d + parts * k + (inline_pool ? R * d : 0)) * sizeof(float), st, partial, n_chunks, S, d, P,
                        bias, k, parts, fp, inv, bits, pooled_in, pooled_valid, key_in, key_inv_in, (const int32_t*)nullptr,
                        (const int32_t*)nullptr, inline_pool ? h : (const T*)nullptr, G, R, key_index);
@@ -393,7 +393,7 @@ static llmc_status_t project_rows_t(const float* means, int n_max, int d, const 
   const int cgs = k / 4;
   const int parts = std::max(1, std::min(1024 / cgs, 16));
   ProfScope ps_("project_kernel", st);
-  hipLaunchKernelGGL(project_kernel<T>, dim3(n_max), dim3(std::max(cgs * parts, k)),
+  LLMC_KERNEL_GGL(project_kernel<T>, dim3(n_max), dim3(std::max(cgs * parts, k)),
                      (size_t)(d + parts * k) * sizeof(float), st, (const float*)nullptr, 0, 1, d, P, bias, k, parts, fp, inv,
                      (uint32_t*)nullptr, means, (const uint8_t*)nullptr, (const T*)nullptr, (const float*)nullptr, rows,
                      count, (const T*)nullptr, 0, 0, (const int32_t*)nullptr);
@@ -419,7 +419,7 @@ static llmc_status_t pool_rows_t(const T* h, int n_max, int S, int d, const int3
   const int G = d / VEC;
   const int R = pool_row_groups(G);
   { ProfScope ps_("pool_direct_kernel", st);
-    hipLaunchKernelGGL(pool_direct_kernel<T>, dim3(n_max), dim3(G * R), (size_t)R * d * sizeof(float), st, h, S, d, G, R,
+    LLMC_KERNEL_GGL(pool_direct_kernel<T>, dim3(n_max), dim3(G * R), (size_t)R * d * sizeof(float), st, h, S, d, G, R,
                        rows, count, dst, out); }
   LLMC_LAUNCH_CHECK("pool_direct_kernel");
   return LLMC_OK;
@@ -447,9 +447,9 @@ llmc_status_t launch_inv_norm(const void* d_fp, int64_t n, int k, int dtype, flo
   const int rows_per_block = 4;
   const unsigned blocks = (unsigned)((n + rows_per_block - 1) / rows_per_block);
   if (dtype == LLMC_F32)
-    { ProfScope ps_("inv_norm_kernel", st); hipLaunchKernelGGL(inv_norm_kernel<float>, dim3(blocks), dim3(256), 0, st, (const float*)d_fp, n, k, d_out); }
+    { ProfScope ps_("inv_norm_kernel", st); LLMC_KERNEL_GGL(inv_norm_kernel<float>, dim3(blocks), dim3(256), 0, st, (const float*)d_fp, n, k, d_out); }
   else
-    { ProfScope ps_("inv_norm_kernel", st); hipLaunchKernelGGL(inv_norm_kernel<bf16_t>, dim3(blocks), dim3(256), 0, st, (const bf16_t*)d_fp, n, k, d_out); }
+    { ProfScope ps_("inv_norm_kernel", st); LLMC_KERNEL_GGL(inv_norm_kernel<bf16_t>, dim3(blocks), dim3(256), 0, st, (const bf16_t*)d_fp, n, k, d_out); }
   LLMC_LAUNCH_CHECK("inv_norm_kernel");
   return LLMC_OK;
 }

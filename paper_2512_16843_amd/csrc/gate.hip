@@ -145,7 +145,7 @@ llmc_status_t launch_compact(const uint8_t* d_hit, const int32_t* d_idx, const f
                              uint8_t* d_pooled_valid_out, int has_pool, int32_t* d_ref_out) {
   const int touch = (flags & LLMC_UPDATE_LRU) ? 1 : 0;
   const int reval_every = (flags & LLMC_REVALIDATE) ? bank->desc.reval_every : 0;
-  { ProfScope ps_("compact_kernel", st); hipLaunchKernelGGL(compact_kernel, dim3(1), dim3(1024), 0, st, d_hit, d_idx, d_sim, d_near_tie, B, tau, d_hit_rows,
+  { ProfScope ps_("compact_kernel", st); LLMC_KERNEL_GGL(compact_kernel, dim3(1), dim3(1024), 0, st, d_hit, d_idx, d_sim, d_near_tie, B, tau, d_hit_rows,
                      d_miss_rows, d_counters, bank->desc.d_last_used, bank->desc.d_hits, touch, tick, reval_every,
                      d_reval_tmp, d_pooled_valid_out, has_pool, d_ref_out, bank->desc.d_act_slot); }
   LLMC_LAUNCH_CHECK("compact_kernel");
@@ -158,10 +158,10 @@ llmc_status_t launch_divergence(llmc_bank* bank, const void* d_h_out, const int3
   const size_t elems = (size_t)D.S * D.d;
   ProfScope ps_("divergence_kernel", st);
   if (D.dtype == LLMC_F32)
-    hipLaunchKernelGGL(divergence_kernel<float>, dim3(B), dim3(1024), 0, st, (const float*)d_h_out, (float*)D.d_act,
+    LLMC_KERNEL_GGL(divergence_kernel<float>, dim3(B), dim3(1024), 0, st, (const float*)d_h_out, (float*)D.d_act,
                        D.d_act_slot, d_idx, d_rows, d_counters, elems, D.drift_bound);
   else
-    hipLaunchKernelGGL(divergence_kernel<bf16_t>, dim3(B), dim3(1024), 0, st, (const bf16_t*)d_h_out, (bf16_t*)D.d_act,
+    LLMC_KERNEL_GGL(divergence_kernel<bf16_t>, dim3(B), dim3(1024), 0, st, (const bf16_t*)d_h_out, (bf16_t*)D.d_act,
                        D.d_act_slot, d_idx, d_rows, d_counters, elems, D.drift_bound);
   LLMC_LAUNCH_CHECK("divergence_kernel");
   return LLMC_OK;
@@ -170,7 +170,7 @@ llmc_status_t launch_divergence(llmc_bank* bank, const void* d_h_out, const int3
 llmc_status_t launch_all_miss(int B, int32_t* d_miss_rows, int32_t* d_counters, int32_t* d_idx, float* d_sim,
                               uint8_t* d_hit, hipStream_t st, uint8_t* d_pooled_valid_out) {
   const int n = B > LLMC_CNT_WORDS ? B : LLMC_CNT_WORDS;
-  { ProfScope ps_("all_miss_kernel", st); hipLaunchKernelGGL(all_miss_kernel, dim3((n + 255) / 256), dim3(256), 0, st, B, d_miss_rows, d_counters, d_idx, d_sim,
+  { ProfScope ps_("all_miss_kernel", st); LLMC_KERNEL_GGL(all_miss_kernel, dim3((n + 255) / 256), dim3(256), 0, st, B, d_miss_rows, d_counters, d_idx, d_sim,
                      d_hit, d_pooled_valid_out); }
   LLMC_LAUNCH_CHECK("all_miss_kernel");
   return LLMC_OK;
@@ -209,7 +209,7 @@ llmc_status_t launch_gather(const llmc_bank* bank, const int32_t* d_idx, const i
   if (D.rank > 0) {
     // compressed values: h_out[rows[i]] = C[value row] * U, one GEMM with K = rank over the listed hits
     { ProfScope ps_("hit_slots_kernel", st);
-      hipLaunchKernelGGL(hit_slots_kernel, dim3((n_max + 255) / 256), dim3(256), 0, st, d_idx, d_rows, D.d_act_slot, d_n,
+      LLMC_KERNEL_GGL(hit_slots_kernel, dim3((n_max + 255) / 256), dim3(256), 0, st, d_idx, d_rows, D.d_act_slot, d_n,
                          n_max, bank->d_hit_slots); }
     LLMC_LAUNCH_CHECK("hit_slots_kernel");
     return launch_linear(D.d_act, D.rank, bank->d_hit_slots, bank->d_basis_t, nullptr, D.d, D.rank, d_h_out, D.d, d_rows,
@@ -218,7 +218,7 @@ llmc_status_t launch_gather(const llmc_bank* bank, const int32_t* d_idx, const i
   const size_t vec_per_seq = (size_t)D.S * D.d * elem_size(D.dtype) / 16;
   const size_t per_wg = (size_t)kGatherThreads * kGatherVecPerThread;
   dim3 grid((unsigned)((vec_per_seq + per_wg - 1) / per_wg), n_max);
-  { ProfScope ps_("gather_kernel", st); hipLaunchKernelGGL(gather_kernel, grid, dim3(kGatherThreads), 0, st, (const u32x4_t*)D.d_act, D.d_act_slot, d_idx,
+  { ProfScope ps_("gather_kernel", st); LLMC_KERNEL_GGL(gather_kernel, grid, dim3(kGatherThreads), 0, st, (const u32x4_t*)D.d_act, D.d_act_slot, d_idx,
                      d_rows, d_n, n_max, vec_per_seq, (u32x4_t*)d_h_out, D.d_act_pool,
                      D.d_act_pool ? d_pooled_out : nullptr, D.d, (const uint32_t*)D.d_next_fp, D.d_next_inv,
                      (D.d_next_fp && d_key_inv_out) ? (uint32_t*)d_key_out : nullptr, d_key_inv_out,
@@ -235,7 +235,7 @@ llmc_status_t launch_materialize(const llmc_bank* bank, const int32_t* d_ref, co
   const size_t per_wg = (size_t)kGatherThreads * kGatherVecPerThread;
   dim3 grid((unsigned)((vec_per_seq + per_wg - 1) / per_wg), n_max);
   { ProfScope ps_("materialize_kernel", st);
-    hipLaunchKernelGGL(materialize_kernel, grid, dim3(kGatherThreads), 0, st, (const u32x4_t*)D.d_act,
+    LLMC_KERNEL_GGL(materialize_kernel, grid, dim3(kGatherThreads), 0, st, (const u32x4_t*)D.d_act,
                        (const int32_t*)nullptr, d_ref, d_rows, d_n, n_max, vec_per_seq, (u32x4_t*)d_h, (const float*)nullptr,
                        (float*)nullptr, D.d, (const uint32_t*)nullptr, (const float*)nullptr, (uint32_t*)nullptr,
                        (float*)nullptr, 0); }

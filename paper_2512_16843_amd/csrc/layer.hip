@@ -95,20 +95,20 @@ static llmc_status_t launch_gemm(const GemmArgs& g, int dtype, hipStream_t st) {
       GemmArgs a = g;
       a.xcd_chunks = tiles_n <= 8 ? 1 : 0;   // narrow outputs gain from keeping a row block in one XCD's L2
       ProfScope ps_("gemm_bf16_kernel", st);
-      hipLaunchKernelGGL(gemm_bf16_dma_kernel<C>, dim3(std::min((tiles_m * tiles_n + 7) & ~7, kMaxGrid)), dim3(C::THREADS),
+      LLMC_KERNEL_GGL(gemm_bf16_dma_kernel<C>, dim3(std::min((tiles_m * tiles_n + 7) & ~7, kMaxGrid)), dim3(C::THREADS),
                          gemm_dma_smem_bytes<C>(), st, a, tiles_n);
     } else {
       const int tiles_n = (g.N + GemmCfg::BN - 1) / GemmCfg::BN;
       const int tiles_m = (g.max_seqs * g.S + GemmCfg::BM - 1) / GemmCfg::BM;
       ProfScope ps_("gemm_bf16_kernel", st);
-      hipLaunchKernelGGL(gemm_bf16_kernel<GemmCfg>, dim3(std::min(tiles_m * tiles_n, kMaxGrid)), dim3(GemmCfg::THREADS),
+      LLMC_KERNEL_GGL(gemm_bf16_kernel<GemmCfg>, dim3(std::min(tiles_m * tiles_n, kMaxGrid)), dim3(GemmCfg::THREADS),
                          0, st, g, tiles_n);
     }
   } else {
     const int tiles_n = (g.N + 63) / 64;
     const int tiles_m = (g.max_seqs * g.S + 63) / 64;
     ProfScope ps_("gemm_f32_kernel", st);
-    hipLaunchKernelGGL(gemm_f32_kernel, dim3((unsigned)tiles_m * tiles_n), dim3(256), 0, st, g, tiles_n);
+    LLMC_KERNEL_GGL(gemm_f32_kernel, dim3((unsigned)tiles_m * tiles_n), dim3(256), 0, st, g, tiles_n);
   }
   LLMC_LAUNCH_CHECK("gemm");
   return LLMC_OK;
@@ -178,7 +178,7 @@ static llmc_status_t launch_ln(const void* in, const int32_t* in_rows, void* out
 #define LN_CASE(MV)                                                                                     \
   {                                                                                                     \
     ProfScope ps_("layernorm_kernel", st);                                                              \
-    hipLaunchKernelGGL((layernorm_kernel<T, MV>), dim3(blocks), dim3(256), 0, st, (const T*)in, d,      \
+    LLMC_KERNEL_GGL((layernorm_kernel<T, MV>), dim3(blocks), dim3(256), 0, st, (const T*)in, d,      \
                        in_rows, (T*)out, d, out_rows, (const T*)gamma, (const T*)beta, eps, d, S, count, \
                        max_seqs);                                                                       \
   }
@@ -277,19 +277,19 @@ static llmc_status_t launch_attention(const void* qkv, void* ctx, int S, int d, 
     const dim3 grid(std::min(items, 2 * kMaxGrid));
     ProfScope ps_("attention_kernel", st);
     if (causal)
-      hipLaunchKernelGGL(attention_mfma_kernel<true>, grid, dim3(AttnCfg::THREADS), 0, st, (const uint16_t*)qkv,
+      LLMC_KERNEL_GGL(attention_mfma_kernel<true>, grid, dim3(AttnCfg::THREADS), 0, st, (const uint16_t*)qkv,
                          (uint16_t*)ctx, S, d, n_heads, scale_log2e, count, max_seqs);
     else
-      hipLaunchKernelGGL(attention_mfma_kernel<false>, grid, dim3(AttnCfg::THREADS), 0, st, (const uint16_t*)qkv,
+      LLMC_KERNEL_GGL(attention_mfma_kernel<false>, grid, dim3(AttnCfg::THREADS), 0, st, (const uint16_t*)qkv,
                          (uint16_t*)ctx, S, d, n_heads, scale_log2e, count, max_seqs);
   } else {
     dim3 grid((S + 127) / 128, n_heads, max_seqs);
     ProfScope ps_("attention_kernel", st);
     if (causal)
-      hipLaunchKernelGGL((attention_kernel<T, true>), grid, dim3(128), 0, st, (const T*)qkv, (T*)ctx, S, d, scale, count,
+      LLMC_KERNEL_GGL((attention_kernel<T, true>), grid, dim3(128), 0, st, (const T*)qkv, (T*)ctx, S, d, scale, count,
                          max_seqs);
     else
-      hipLaunchKernelGGL((attention_kernel<T, false>), grid, dim3(128), 0, st, (const T*)qkv, (T*)ctx, S, d, scale,
+      LLMC_KERNEL_GGL((attention_kernel<T, false>), grid, dim3(128), 0, st, (const T*)qkv, (T*)ctx, S, d, scale,
                          count, max_seqs);
   }
   LLMC_LAUNCH_CHECK("attention");

@@ -152,17 +152,17 @@ llmc_status_t launch_lsh_build(const uint32_t* d_bank_bits, const uint8_t* d_val
   const size_t n_cnt = (size_t)L.bands * kLshValues, n_pairs = (size_t)N * L.bands;
   const int W = k / 32;
   { ProfScope ps_("lsh_zero_kernel", st);
-    hipLaunchKernelGGL(lsh_zero_kernel, dim3((unsigned)((n_cnt + 255) / 256)), dim3(256), 0, st, cursor, n_cnt); }
+    LLMC_KERNEL_GGL(lsh_zero_kernel, dim3((unsigned)((n_cnt + 255) / 256)), dim3(256), 0, st, cursor, n_cnt); }
   LLMC_LAUNCH_CHECK("lsh_zero_kernel");
   { ProfScope ps_("lsh_count_kernel", st);
-    hipLaunchKernelGGL(lsh_count_kernel, dim3((unsigned)((n_pairs + 255) / 256)), dim3(256), 0, st, d_bank_bits, d_valid, N,
+    LLMC_KERNEL_GGL(lsh_count_kernel, dim3((unsigned)((n_pairs + 255) / 256)), dim3(256), 0, st, d_bank_bits, d_valid, N,
                        W, L.bands, cursor); }
   LLMC_LAUNCH_CHECK("lsh_count_kernel");
   { ProfScope ps_("lsh_scan_kernel", st);
-    hipLaunchKernelGGL(lsh_scan_kernel, dim3(L.bands), dim3(1024), 0, st, cursor, start); }
+    LLMC_KERNEL_GGL(lsh_scan_kernel, dim3(L.bands), dim3(1024), 0, st, cursor, start); }
   LLMC_LAUNCH_CHECK("lsh_scan_kernel");
   { ProfScope ps_("lsh_scatter_kernel", st);
-    hipLaunchKernelGGL(lsh_scatter_kernel, dim3((unsigned)((n_pairs + 255) / 256)), dim3(256), 0, st, d_bank_bits, d_valid,
+    LLMC_KERNEL_GGL(lsh_scatter_kernel, dim3((unsigned)((n_pairs + 255) / 256)), dim3(256), 0, st, d_bank_bits, d_valid,
                        N, W, L.bands, cursor, order); }
   LLMC_LAUNCH_CHECK("lsh_scatter_kernel");
   return LLMC_OK;
@@ -176,7 +176,7 @@ llmc_status_t launch_lsh_match(const uint32_t* d_bank_bits, int N, int k, const 
   const int32_t* order = (const int32_t*)((const char*)d_index + L.off_order);
   const dim3 grid((B + 3) / 4), block(256);
   ProfScope ps_("lsh_match_kernel", st);
-#define LLMC_LSH_CASE(W_) hipLaunchKernelGGL(lsh_match_kernel<W_>, grid, block, 0, st, d_bank_bits, N, start, order, \
+#define LLMC_LSH_CASE(W_) LLMC_KERNEL_GGL(lsh_match_kernel<W_>, grid, block, 0, st, d_bank_bits, N, start, order, \
                                              d_query_bits, B, max_hamming, d_idx, d_dist, d_hit, d_compared)
   switch (k / 32) {
     case 2: LLMC_LSH_CASE(2); break;

@@ -757,7 +757,7 @@ static llmc_status_t launch_stream_nw(const llmc_bank* bank, const void* d_fp, i
   const int groups = (ns + 7) / 8;                 // splits are dealt to the 8 XCDs
   const unsigned grid = (unsigned)groups * nqb * 8;
   ProfScope ps_("match_stream_kernel", st);
-  hipLaunchKernelGGL((match_stream_kernel<K_, NW_>), dim3(grid), dim3(C::THREADS), C::LDS_BYTES, st,
+  LLMC_KERNEL_GGL((match_stream_kernel<K_, NW_>), dim3(grid), dim3(C::THREADS), C::LDS_BYTES, st,
                      (const uint16_t*)D.d_fp, bank->d_binv_eff, D.n_slots, (const uint16_t*)d_fp, B, nqb, ns, per,
                      partial);
   *ns_out = ns;
@@ -776,7 +776,7 @@ static llmc_status_t launch_stream(const llmc_bank* bank, const void* d_fp, int 
   stream_plan(D.n_slots, B, C::RB, C::QB, &nqb, &ns, &per);
   const unsigned grid = (unsigned)((ns + 7) / 8) * nqb * 8;    // splits are dealt to the 8 XCDs
   ProfScope ps_("match_stream_kernel", st);
-  hipLaunchKernelGGL((match_skew_kernel<K_>), dim3(grid), dim3(512), C::LDS_BYTES, st, (const uint16_t*)D.d_fp,
+  LLMC_KERNEL_GGL((match_skew_kernel<K_>), dim3(grid), dim3(512), C::LDS_BYTES, st, (const uint16_t*)D.d_fp,
                      bank->d_binv_eff, D.n_slots, (const uint16_t*)d_fp, B, nqb, ns, per, partial);
   *ns_out = ns;
   return LLMC_OK;
@@ -798,12 +798,12 @@ static llmc_status_t launch_match_bulk(const llmc_bank* bank, const void* d_fp, 
     } else {
       split_plan(N, B, &ns, &per);
       dim3 grid(ns, (B + MatchCfg::BN - 1) / MatchCfg::BN);
-      { ProfScope ps_("match_bf16_kernel", st); hipLaunchKernelGGL(match_bf16_kernel, grid, dim3(MatchCfg::THREADS), 0, st, (const uint16_t*)D.d_fp,
+      { ProfScope ps_("match_bf16_kernel", st); LLMC_KERNEL_GGL(match_bf16_kernel, grid, dim3(MatchCfg::THREADS), 0, st, (const uint16_t*)D.d_fp,
                          bank->d_binv_eff, N, K, (const uint16_t*)d_fp, B, per, partial); }
       LLMC_LAUNCH_CHECK("match_bf16_kernel");
     }
   } else {
-    { ProfScope ps_("match_f32_kernel", st); hipLaunchKernelGGL(match_f32_kernel, dim3(B), dim3(256), (size_t)K * sizeof(float) + 256 * sizeof(Top2), st,
+    { ProfScope ps_("match_f32_kernel", st); LLMC_KERNEL_GGL(match_f32_kernel, dim3(B), dim3(256), (size_t)K * sizeof(float) + 256 * sizeof(Top2), st,
                        (const float*)D.d_fp, bank->d_binv_eff, N, K, (const float*)d_fp, partial); }
     LLMC_LAUNCH_CHECK("match_f32_kernel");
   }
@@ -824,12 +824,12 @@ llmc_status_t launch_match_decide(llmc_bank* bank, const void* d_fp, const float
   const int reval_every = (flags & LLMC_REVALIDATE) ? D.reval_every : 0;
   ProfScope ps_("match_decide_kernel", st);
   if (D.dtype == LLMC_BF16)
-    hipLaunchKernelGGL((match_decide_kernel<bf16_t>), dim3(1), dim3(1024), 0, st, (const Top2*)ws, ns, (const bf16_t*)D.d_fp,
+    LLMC_KERNEL_GGL((match_decide_kernel<bf16_t>), dim3(1), dim3(1024), 0, st, (const Top2*)ws, ns, (const bf16_t*)D.d_fp,
                        D.d_inv_norm, D.d_valid, D.n_slots, D.k, (const bf16_t*)d_fp, d_inv, B, tau, d_idx, d_sim, d_hit,
                        d_hit_rows, d_miss_rows, d_counters, D.d_last_used, D.d_hits, touch, tick, reval_every, d_reval_tmp,
                        d_pooled_valid_out, has_pool, d_ref_out, D.d_act_slot);
   else
-    hipLaunchKernelGGL((match_decide_kernel<float>), dim3(1), dim3(1024), 0, st, (const Top2*)ws, 1, (const float*)D.d_fp,
+    LLMC_KERNEL_GGL((match_decide_kernel<float>), dim3(1), dim3(1024), 0, st, (const Top2*)ws, 1, (const float*)D.d_fp,
                        D.d_inv_norm, D.d_valid, D.n_slots, D.k, (const float*)d_fp, d_inv, B, tau, d_idx, d_sim, d_hit,
                        d_hit_rows, d_miss_rows, d_counters, D.d_last_used, D.d_hits, touch, tick, reval_every, d_reval_tmp,
                        d_pooled_valid_out, has_pool, d_ref_out, D.d_act_slot);
@@ -853,18 +853,18 @@ llmc_status_t launch_match(const llmc_bank* bank, const void* d_fp, const float*
     } else {
       split_plan(N, B, &ns, &per);
       dim3 grid(ns, (B + MatchCfg::BN - 1) / MatchCfg::BN);
-      { ProfScope ps_("match_bf16_kernel", st); hipLaunchKernelGGL(match_bf16_kernel, grid, dim3(MatchCfg::THREADS), 0, st, (const uint16_t*)D.d_fp,
+      { ProfScope ps_("match_bf16_kernel", st); LLMC_KERNEL_GGL(match_bf16_kernel, grid, dim3(MatchCfg::THREADS), 0, st, (const uint16_t*)D.d_fp,
                          bank->d_binv_eff, N, K, (const uint16_t*)d_fp, B, per, partial); }
       LLMC_LAUNCH_CHECK("match_bf16_kernel");
     }
-    { ProfScope ps_("match_finalize_kernel", st); hipLaunchKernelGGL((match_finalize_kernel<bf16_t>), dim3((B + 3) / 4), dim3(256), 0, st, partial, ns,
+    { ProfScope ps_("match_finalize_kernel", st); LLMC_KERNEL_GGL((match_finalize_kernel<bf16_t>), dim3((B + 3) / 4), dim3(256), 0, st, partial, ns,
                        (const bf16_t*)D.d_fp, D.d_inv_norm, D.d_valid, N, K, (const bf16_t*)d_fp, d_inv, B, tau, d_idx,
                        d_sim, d_hit, d_near_tie); }
   } else {
-    { ProfScope ps_("match_f32_kernel", st); hipLaunchKernelGGL(match_f32_kernel, dim3(B), dim3(256), (size_t)K * sizeof(float) + 256 * sizeof(Top2), st,
+    { ProfScope ps_("match_f32_kernel", st); LLMC_KERNEL_GGL(match_f32_kernel, dim3(B), dim3(256), (size_t)K * sizeof(float) + 256 * sizeof(Top2), st,
                        (const float*)D.d_fp, bank->d_binv_eff, N, K, (const float*)d_fp, partial); }
     LLMC_LAUNCH_CHECK("match_f32_kernel");
-    { ProfScope ps_("match_finalize_kernel", st); hipLaunchKernelGGL((match_finalize_kernel<float>), dim3((B + 3) / 4), dim3(256), 0, st, partial, 1,
+    { ProfScope ps_("match_finalize_kernel", st); LLMC_KERNEL_GGL((match_finalize_kernel<float>), dim3((B + 3) / 4), dim3(256), 0, st, partial, 1,
                        (const float*)D.d_fp, D.d_inv_norm, D.d_valid, N, K, (const float*)d_fp, d_inv, B, tau, d_idx,
                        d_sim, d_hit, d_near_tie); }
   }

@@ -67,6 +67,25 @@ def oracle_view(bank, dtype="bf16"):
     return ob
 
 
+def release(st):
+    """Close the banks and drop their arrays."""
+    st.close()
+    st.banks = []
+    st.buf = []
+    st.workspace = None
+
+
+@pytest.fixture
+def made():
+    """Stacks a test creates are released when it ends, also when it fails (a failed test's traceback keeps its frame,
+    and with it a hundred GB of banks, alive)."""
+    stacks = []
+    yield stacks
+    for st in stacks:
+        release(st)
+    torch.cuda.empty_cache()
+
+
 def build_banks(L, st, cfg, src, tok, pos):
     src_t = torch.from_numpy(src).cuda()
     for s in range(0, src.shape[0], cfg.B):
@@ -75,116 +94,260 @@ def build_banks(L, st, cfg, src, tok, pos):
     torch.cuda.synchronize()
 
 
-def sampled_teacher_forced(L, st, cfg, ws, Ps, h0, tau, rows, layers):
-    """Oracle on `rows` of the batch at `layers`, fed the GPU's own h_{l-1} and bank arrays."""
+def bf16_steps(a, b):
+    """Distance between two arrays of bf16 values (held in float32) in steps of the bf16 number line."""
+    def ordinal(x):
+        bits = (np.ascontiguousarray(x, dtype=np.float32).view(np.uint32) >> 16).astype(np.int64)
+        mag = bits & 0x7FFF
+        return np.where(bits & 0x8000, -mag, mag)
+    return np.abs(ordinal(a) - ordinal(b))
+
+
+def key_codes_close(q_gpu, q_oracle):
+    """The GPU pools and projects in fp32 (fixed order), the oracle in fp64, and both round the normalised vector to
+    bf16: an element's code may land one bf16 step apart.  For elements near zero a bf16 step is smaller than the
+    fp32 noise of the sums they come from (about 1e-6 of the largest term, more after a centring offset has
+    cancelled the common component), so there the bound is absolute: 1e-5 of the unit vector."""
+    return bool(((bf16_steps(q_gpu, q_oracle) <= 1) | (np.abs(q_gpu - q_oracle) <= 1e-5)).all())
+
+
+def check_layer_decisions(g, bank, h_prev, P, c, tau, dtype="bf16"):
+    """Every row of one layer against the oracle.  g: the layer's gate buffers (with the keys the rows were matched
+    with); bank: the layer's bank (device); h_prev: the layer's input as the GPU holds it.  Returns a dict of counts.
+
+    1. the GPU's keys against the oracle's fingerprint of h_prev: the normalised vector is rounded to the bank type,
+       and the GPU accumulates in fp32, so a code may differ by one bf16 step and by no more;
+    2. the oracle's match fed the GPU's keys: similarity to 1e-5, slot exact (or inside the oracle's near-tie set,
+       counted), decision exact except for rows within 1e-3 of the threshold (counted);
+    3. the oracle's match on its OWN keys: decisions outside the 1e-3 band must agree as well."""
+    fp, inv, valid = npf(bank.fp), npf(bank.inv_norm), bank.valid.cpu().numpy()
+    hp = npf(h_prev)
+    q_o, qinv_o = O.fingerprint(hp, npf(P), None if c is None else npf(c), dtype)
+    q_g, qinv_g = npf(g.fp_used), npf(g.inv_used)
+    if dtype == "bf16":
+        steps = bf16_steps(q_g, q_o)
+        assert key_codes_close(q_g, q_o), (steps.max(), np.abs(q_g - q_o).max())
+        key_mismatch = int((steps > 0).sum())
+    else:
+        assert np.abs(q_g - q_o).max() < 1e-6
+        key_mismatch = int((q_g != q_o).sum())
+    np.testing.assert_allclose(qinv_g, O.inv_norm(q_g), rtol=3e-7, atol=0)
+    hit = g.hit.cpu().numpy().astype(bool)
+    idx = g.idx.cpu().numpy()
+    sim = npf(g.sim).astype(np.float64)
+    tau32 = f32(tau)
+    idx_o, sim_o = O.match(q_g, qinv_g, fp, inv, valid)
+    np.testing.assert_allclose(sim, sim_o, rtol=0, atol=1e-5)
+    near = np.abs(sim_o - tau32) < 1e-3
+    hit_o = O.threshold(sim_o, tau32)
+    assert np.array_equal(hit[~near], hit_o[~near])
+    ties = O.near_tie_sets(q_g, qinv_g, fp, inv, valid)
+    multi = np.array([len(t) > 1 for t in ties])
+    assert np.array_equal(idx[~multi], idx_o[~multi]), (idx, idx_o)
+    for b in np.nonzero(multi)[0]:
+        assert idx[b] in ties[b]
+    # the oracle on its own keys
+    idx_2, sim_2 = O.match(q_o, qinv_o, fp, inv, valid)
+    near2 = np.abs(sim_2 - tau32) < 1e-3
+    assert np.array_equal(hit[~near2], O.threshold(sim_2, tau32)[~near2])
+    return dict(hits=int(hit.sum()), near_tau=int(near.sum()), near_tie=int(multi.sum()), key_codes_off_by_one=key_mismatch,
+                idx_differs_with_oracle_keys=int((idx_2 != idx).sum()), max_sim_dev_with_oracle_keys=float(np.abs(sim_2 - sim).max()))
+
+
+def check_layer_outputs(L, cfg, g, bank, h_prev, out, w, rows_to_compute):
+    """Reused rows are exact copies of the cached values (all of them); the listed computed rows against f_l."""
+    hit = g.hit.bool()
+    if hit.any():
+        rows_h = torch.nonzero(hit).flatten()
+        slots = g.idx[rows_h].long()
+        if bank.act_slot is not None:
+            slots = bank.act_slot[slots].long()
+        for r0 in range(0, len(rows_h), 16):
+            assert torch.equal(out[rows_h[r0:r0 + 16]], bank.act[slots[r0:r0 + 16]])
+    wnp = {k: npf(v) for k, v in w.items()}
+    err = 0.0
+    for b in rows_to_compute:
+        assert not bool(hit[b])
+        want = O.layer_forward(npf(h_prev[b]), wnp, cfg.arch, cfg.n_heads, cfg.ln_eps, cfg.gelu)
+        err = max(err, float(rel_err_rows(npf(out[b:b + 1]), want[None])[0]))
+    assert err < TOL_BF16, err
+    return err
+
+
+def snapshot(st):
+    return [dict(idx=g.idx.clone(), sim=g.sim.clone(), hit=g.hit.clone(), key=g.fp_used.clone(), inv=g.inv_used.clone(),
+                 cnt=g.counters.clone()) for g in st.gate]
+
+
+def same_snapshots(a, b):
+    for l, (x, y) in enumerate(zip(a, b)):
+        for k in x:
+            assert torch.equal(x[k], y[k]), (l, k)
+
+
+def all_rows_teacher_forced(L, st, cfg, ws, Ps, cs, h0, tau, miss_rows_per_layer, layers_out):
+    """The oracle on EVERY row of every layer for the decisions, fed the GPU's own layer inputs and bank arrays;
+    outputs: every reused row against the bank, `miss_rows_per_layer` computed rows at the layers `layers_out`."""
     outs = st.forward(h0, tau=tau, keep_all=True)
     torch.cuda.synchronize()
     report = []
-    for l in layers:
-        h_prev = h0 if l == 0 else outs[l - 1]
-        ob = oracle_view(st.banks[l])
-        wnp = {k: npf(v) for k, v in ws[l].items()}
-        r = O.gated_layer(npf(h_prev[rows]), ob, npf(Ps[l]), None, wnp, cfg.arch, cfg.n_heads, cfg.ln_eps, cfg.gelu,
-                          f32(tau))
-        g = st.gate[l]
-        hit = g.hit.cpu().numpy().astype(bool)[rows]
-        idx = g.idx.cpu().numpy()[rows]
-        sim = npf(g.sim)[rows]
-        near = np.abs(r.sim - f32(tau)) < 1e-3
-        ties = O.near_tie_sets(r.q, r.qinv, ob.fp, ob.inv_norm, ob.valid)
-        multi = np.array([len(t) > 1 for t in ties])
-        assert np.array_equal(hit[~near], r.hit[~near]), (l, hit, r.hit, r.sim)
-        ok = ~near & ~multi
-        assert np.array_equal(idx[ok], r.idx[ok]), (l, idx, r.idx)
-        for i in np.nonzero(multi)[0]:
-            assert idx[i] in ties[i]
-        np.testing.assert_allclose(sim, r.sim, atol=2e-4)
-        got = npf(outs[l][rows])
-        err = 0.0
-        for i in range(len(rows)):
-            if hit[i]:
-                assert np.array_equal(got[i], npf(st.banks[l].act[int(idx[i])]))
-            elif not r.hit[i]:
-                err = max(err, float(rel_err_rows(got[i:i + 1], r.h_out[i:i + 1])[0]))
-        assert err < TOL_BF16, (l, err)
-        report.append((l, int(hit.sum()), int(near.sum()), int(multi.sum()), err))
-    # properties over the whole batch, every layer
     for l in range(cfg.n_layers):
+        h_prev = h0 if l == 0 else outs[l - 1]
         g = st.gate[l]
-        hit = g.hit.bool()
+        stats = check_layer_decisions(g, st.banks[l], h_prev, Ps[l], None if cs is None else cs[l], tau)
         cnt = g.counters.cpu()
-        assert int(cnt[L.CNT_HIT]) == int(hit.sum()) and int(cnt[L.CNT_HIT]) + int(cnt[L.CNT_MISS]) == cfg.B
-        if hit.any():
-            rows_h = torch.nonzero(hit).flatten()
-            assert torch.all(st.banks[l].valid[g.idx[rows_h].long()] == 1)
-            pick = rows_h[:: max(1, len(rows_h) // 4)][:4]
-            for b in pick.tolist():
-                assert torch.equal(outs[l][b], st.banks[l].act[int(g.idx[b])])
+        assert int(cnt[L.CNT_HIT]) == stats["hits"] and int(cnt[L.CNT_HIT]) + int(cnt[L.CNT_MISS]) == cfg.B
+        assert torch.all(st.banks[l].valid[g.idx[g.hit.bool()].long()] == 1)
+        miss = torch.nonzero(g.hit == 0).flatten().tolist()
+        pick = miss[:: max(1, len(miss) // miss_rows_per_layer)][:miss_rows_per_layer] if l in layers_out else []
+        stats["max_miss_row_err"] = check_layer_outputs(L, cfg, g, st.banks[l], h_prev, outs[l], ws[l], pick)
+        stats["miss_rows_checked"] = len(pick)
         assert torch.isfinite(outs[l].float()).all()
-    return report
+        report.append(stats)
+    return outs, report
 
 
-def test_bert_base_full_config_sampled(L):
-    from paper_2512_16843_amd.engine import GatedStack
-    cfg = W.BERT_BASE
-    say(f"{cfg.name}: L={cfg.n_layers} B={cfg.B} S={cfg.S} bank {cfg.n_bank}: build + sampled teacher-forced parity")
+def show(tag, report):
+    for l, r in enumerate(report):
+        say("  %s layer %2d: %s" % (tag, l, " ".join("%s=%s" % (k, ("%.2e" % v) if isinstance(v, float) else v)
+                                                       for k, v in r.items())))
+
+
+def bert_base_inputs(cfg):
     ws = W.make_layer_weights(cfg, seed=0)
     tok, pos = W.make_embeddings(cfg, seed=0)
     tok, pos = tok.cuda(), pos.cuda()
     Ps = W.make_projection(cfg.d, cfg.k, cfg.torch_dtype, seed=3, n_layers=cfg.n_layers)
     src = W.make_sources(cfg, cfg.n_bank, seed=1)
-    st = GatedStack(cfg, ws, Ps)
-    build_banks(L, st, cfg, src, tok, pos)
+    return ws, tok, pos, Ps, src
+
+
+def source_batches(cfg, src, tok, pos):
+    src_t = torch.from_numpy(src).cuda()
+    for s in range(0, src.shape[0], cfg.B):
+        yield W.embed(src_t[s:s + cfg.B], tok, pos, cfg.torch_dtype)
+
+
+@pytest.mark.parametrize("variant", ["centred", "uncentred"])
+def test_bert_base_full_config_in_the_benchmark_configuration(L, made, variant):
+    """The configuration the benchmark times: banks that keep token means and next-layer keys, reused rows handed on
+    as references (deferred copies), launch-shape hints settled by earlier forwards, the step replayed from a HIP
+    graph.  Decisions, slots, similarities and keys of all 64 rows at all 12 layers against the oracle; the eager
+    run that keeps every layer's output, the deferred run and the graph replays must agree bit for bit."""
+    from paper_2512_16843_amd.engine import GatedStack
+    from paper_2512_16843_amd.centring import centring_offsets
+    cfg = W.BERT_BASE
+    ws, tok, pos, Ps, src = bert_base_inputs(cfg)
+    cs = None
+    if variant == "centred":
+        say(f"{cfg.name}: centring offsets from an uncached forward of the {cfg.n_bank} sources")
+        cs = centring_offsets(cfg, ws, Ps, source_batches(cfg, src, tok, pos))
+    say(f"{cfg.name} {variant}: bank build (means, next-layer keys), L={cfg.n_layers} B={cfg.B} S={cfg.S} N={cfg.n_bank}")
+    st = GatedStack(cfg, ws, Ps, biases=cs, keep_means=True, keep_next_keys=True, expose_keys=True)
+    made.append(st)
+    for h in source_batches(cfg, src, tok, pos):
+        st.forward(h, tau=2.0, flags=L.INSERT_ON_MISS, tick=1)
+    torch.cuda.synchronize()
     for b in st.banks:
         assert int(b.valid.sum()) == cfg.n_bank
     ids, srcmap = W.make_substitution_queries(cfg, src, n_dup=38, n_subst=12, seed=2)
     h0 = W.embed(torch.from_numpy(ids).cuda(), tok, pos, cfg.torch_dtype)
-    dup = np.nonzero(srcmap >= 0)[0][:2].tolist()
-    fresh = np.nonzero(srcmap < 0)[0][:2].tolist()
-    rows = dup + fresh
-    for tau in (0.98, 2.0):
-        rep = sampled_teacher_forced(L, st, cfg, ws, Ps, h0, tau, rows, layers=[0, 5, 11])
-        for r in rep:
-            say("  tau=%s layer %d: sampled hits %d, near-threshold %d, near-tie %d, max miss-row err %.2e"
-                % ((tau,) + r))
+    for tau in ((0.95,) if variant == "centred" else (0.98, 0.95)):
+        say(f"  tau={tau}: eager warm-up, keep-all run, deferred run, graph replays")
+        for _ in range(3):                      # the hints of a forward come from the counts of an earlier one
+            st.forward(h0, tau=tau)
+            torch.cuda.synchronize()
+        outs, report = all_rows_teacher_forced(L, st, cfg, ws, Ps, cs, h0, tau, miss_rows_per_layer=2, layers_out=(0, 5, 11))
+        show("tau=%s" % tau, report)
+        snap_keep = snapshot(st)
+        y_defer = st.forward(h0, tau=tau).clone()
+        torch.cuda.synchronize()
+        assert any(st._deferred) and (tau > 0.97 or any(st._hint) or variant == "centred")
+        snap_defer = snapshot(st)
+        same_snapshots(snap_keep, snap_defer)
+        assert torch.equal(y_defer, outs[-1])
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            y_static = st.forward(h0, tau=tau)
+        torch.cuda.synchronize()
+        for rep in range(3):
+            for g in st.gate:                   # a replay must rewrite every result
+                g.idx.fill_(-5); g.sim.fill_(-5.0); g.hit.fill_(7); g.fp_used.zero_()
+            y_static.zero_()
+            junk = torch.randn(1 << 20, device="cuda").sum()
+            graph.replay()
+            torch.cuda.synchronize()
+            same_snapshots(snap_keep, snapshot(st))
+            assert torch.equal(y_static, outs[-1]), rep
+            del junk
         hits = st.hit_counts()[:, L.CNT_HIT].numpy()
-        say("  tau=%s hits per layer %s" % (tau, hits.tolist()))
-        if tau < 1:
-            # a row that hit source j at layer l presents source j's next input: hits never decrease
-            assert np.all(np.diff(hits) >= 0)
-            g0 = st.gate[0]
-            hit0 = g0.hit.cpu().numpy().astype(bool)
-            assert np.array_equal(g0.idx.cpu().numpy()[hit0 & (srcmap >= 0)], srcmap[hit0 & (srcmap >= 0)])
-    st.close()
+        say("  tau=%s hits per layer %s; hinted layers %d" % (tau, hits.tolist(), sum(st._hint)))
+        if variant == "uncentred":
+            assert np.all(np.diff(hits) >= 0)       # a row that hit source j presents source j's next input
+        g0 = st.gate[0]
+        hit0 = g0.hit.cpu().numpy().astype(bool)
+        dup = srcmap >= 0
+        assert np.array_equal(g0.idx.cpu().numpy()[hit0 & dup], srcmap[hit0 & dup])
+        if variant == "centred":
+            # the centred key separates the workload: perturbed copies are reused, fresh rows are computed
+            # (a few copies land below 0.95: resampling 3 % of the tokens moves the centred key by more than
+            # the uncentred one, whose common component hides the change)
+            say("  layer 1: %d of %d perturbed copies reused, %d of %d fresh rows reused"
+                % (int(hit0[dup].sum()), int(dup.sum()), int(hit0[~dup].sum()), int((~dup).sum())))
+            assert hit0[dup].sum() >= 30 and not hit0[~dup].any()
+        del outs, graph, y_static
+    release(st)
     del st
     torch.cuda.empty_cache()
 
 
-def test_gpt2_small_full_config_sampled(L):
+def test_bert_base_full_config_plain_banks(L, made):
+    """The same configuration on banks without stored means or keys (every layer pools and projects every row)."""
     from paper_2512_16843_amd.engine import GatedStack
+    cfg = W.BERT_BASE
+    say(f"{cfg.name}: L={cfg.n_layers} B={cfg.B} S={cfg.S} bank {cfg.n_bank}: plain banks, all rows teacher-forced")
+    ws, tok, pos, Ps, src = bert_base_inputs(cfg)
+    st = GatedStack(cfg, ws, Ps, expose_keys=True)
+    made.append(st)
+    build_banks(L, st, cfg, src, tok, pos)
+    ids, srcmap = W.make_substitution_queries(cfg, src, n_dup=38, n_subst=12, seed=2)
+    h0 = W.embed(torch.from_numpy(ids).cuda(), tok, pos, cfg.torch_dtype)
+    for tau in (0.98, 2.0):
+        _, report = all_rows_teacher_forced(L, st, cfg, ws, Ps, None, h0, tau, miss_rows_per_layer=2, layers_out=(0, 11))
+        show("tau=%s" % tau, report)
+    release(st)
+    del st
+    torch.cuda.empty_cache()
+
+
+def test_gpt2_small_full_config_all_rows(L, made):
+    from paper_2512_16843_amd.engine import GatedStack
+    from paper_2512_16843_amd.centring import centring_offsets
     cfg = W.GPT2_SMALL
-    say(f"{cfg.name}: L={cfg.n_layers} B={cfg.B} S={cfg.S} bank {cfg.n_bank}: build + sampled teacher-forced parity")
+    say(f"{cfg.name}: L={cfg.n_layers} B={cfg.B} S={cfg.S} bank {cfg.n_bank}: all 16 rows' decisions, 4 rows' outputs")
     ws = W.make_layer_weights(cfg, seed=0)
     tok, pos = W.make_embeddings(cfg, seed=0)
     tok, pos = tok.cuda(), pos.cuda()
     Ps = W.make_projection(cfg.d, cfg.k, cfg.torch_dtype, seed=3, n_layers=cfg.n_layers)
     src = W.make_sources(cfg, cfg.n_bank, seed=1)
-    st = GatedStack(cfg, ws, Ps)
-    build_banks(L, st, cfg, src, tok, pos)
     ids, srcmap, plen = W.make_prefix_queries(cfg, src, seed=2)
     h0 = W.embed(torch.from_numpy(ids).cuda(), tok, pos, cfg.torch_dtype)
-    for tau in (0.95, 2.0):
-        rep = sampled_teacher_forced(L, st, cfg, ws, Ps, h0, tau, rows=[0, 9], layers=[0, 11])
-        for r in rep:
-            say("  tau=%s layer %d: sampled hits %d, near-threshold %d, near-tie %d, max miss-row err %.2e"
-                % ((tau,) + r))
-        say("  tau=%s hits per layer %s" % (tau, st.hit_counts()[:, L.CNT_HIT].tolist()))
-    st.close()
-    del st
-    torch.cuda.empty_cache()
+    for variant in ("uncentred", "centred"):
+        cs = centring_offsets(cfg, ws, Ps, source_batches(cfg, src, tok, pos)) if variant == "centred" else None
+        st = GatedStack(cfg, ws, Ps, biases=cs, keep_means=True, keep_next_keys=True, expose_keys=True)
+        made.append(st)
+        build_banks(L, st, cfg, src, tok, pos)
+        for tau in ((0.95, 2.0) if variant == "uncentred" else (0.5,)):
+            _, report = all_rows_teacher_forced(L, st, cfg, ws, Ps, cs, h0, tau, miss_rows_per_layer=2,
+                                                layers_out=(0, 5, 11) if tau > 1 else (0, 11))
+            show("%s tau=%s" % (variant, tau), report)
+            say("  %s tau=%s hits per layer %s" % (variant, tau, st.hit_counts()[:, L.CNT_HIT].tolist()))
+        release(st)
+        del st
+        torch.cuda.empty_cache()
 
 
-def test_match_stress_full_size(L):
+def test_match_stress_full_size(L, made):
     say("bank-match stress: 1,048,576 keys x 256, 4,096 queries, threshold 0.95, gather of 384 x 768 outputs")
     data = W.make_clustered_bank(4096, 256, 256, 0.05, 4096, seed=5)
     N, k, S, d, A = 1048576, 256, 384, 768, 4096
@@ -254,7 +417,7 @@ def test_match_stress_full_size(L):
     torch.cuda.empty_cache()
 
 
-def test_bert_large_dynamic_bank_scaled_teacher_forced(L):
+def test_bert_large_dynamic_bank_scaled_teacher_forced(L, made):
     """Insertion + LRU eviction across successive batches of stem-sharing candidates, on a
     scaled copy (2 layers, 96-entry banks, batch 32) that the oracle can follow batch by batch."""
     from paper_2512_16843_amd.engine import GatedStack
@@ -265,6 +428,7 @@ def test_bert_large_dynamic_bank_scaled_teacher_forced(L):
     tok, pos = tok.cuda(), pos.cuda()
     Ps = W.make_projection(cfg.d, cfg.k, cfg.torch_dtype, seed=3, n_layers=cfg.n_layers)
     st = GatedStack(cfg, ws, Ps)
+    made.append(st)
     stream = W.StemStream(cfg, group=4, stem_len=80, n_stems=6, seed=4)
     flags = L.INSERT_ON_MISS | L.UPDATE_LRU
     tau = 0.95
@@ -319,26 +483,26 @@ def test_bert_large_dynamic_bank_scaled_teacher_forced(L):
                 assert torch.equal(bk.act[r.slots[i]], outs[l][int(b)])
         say("  batch %d: hits per layer %s" % (tick, [int(st.gate[l].hit.sum()) for l in range(cfg.n_layers)]))
     assert evicted_total > 0
-    st.close()
+    release(st)
     del st
     torch.cuda.empty_cache()
 
 
-def test_bert_large_full_config_dynamic_properties(L):
+def test_bert_large_full_config_dynamic_properties(L, made):
     """The full 24-layer, 32,768-entry-bank configuration with insertion and eviction active:
     banks pre-filled to capacity, then batches of stem-sharing candidates; checked by invariants."""
     from paper_2512_16843_amd.engine import GatedStack
     cfg = W.BERT_LARGE
     free, total = torch.cuda.mem_get_info()
     need = cfg.n_layers * cfg.n_bank * cfg.S * cfg.d * 2 + (8 << 30)
-    if free < need:
-        pytest.skip("needs %.0f GB of free HBM" % (need / 2 ** 30))
+    assert free >= need, "the full-size dynamic-bank check needs %.0f GB of free HBM, %.0f GB are free" % (need / 2 ** 30, free / 2 ** 30)
     say(f"{cfg.name}: L={cfg.n_layers} B={cfg.B} S={cfg.S} bank {cfg.n_bank}: pre-fill, then 6 batches with eviction")
     ws = W.make_layer_weights(cfg, seed=0)
     tok, pos = W.make_embeddings(cfg, seed=0)
     tok, pos = tok.cuda(), pos.cuda()
     Ps = W.make_projection(cfg.d, cfg.k, cfg.torch_dtype, seed=3, n_layers=cfg.n_layers)
     st = GatedStack(cfg, ws, Ps)
+    made.append(st)
     stream = W.StemStream(cfg, group=4, stem_len=80, n_stems=512, seed=4)
     flags = L.INSERT_ON_MISS | L.UPDATE_LRU
     tick = 0
@@ -381,6 +545,6 @@ def test_bert_large_full_config_dynamic_properties(L):
         say("  batch %d: hit rate %.3f, inserted %d, evicted %d" % (
             step, float(cnt[:, L.CNT_HIT].sum()) / (cfg.B * cfg.n_layers), int(cnt[:, L.CNT_INSERTED].sum()),
             int(cnt[:, L.CNT_EVICTED].sum())))
-    st.close()
+    release(st)
     del st
     torch.cuda.empty_cache()

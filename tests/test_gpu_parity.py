@@ -1238,27 +1238,52 @@ def test_gated_stream_with_insertion_and_lru_eviction(L):
 # bf16, model-sized rows, teacher-forced per layer
 # ---------------------------------------------------------------------------
 
+def bf16_steps(a, b):
+    """Distance between two arrays of bf16 values (held in float32) in steps of the bf16 number line."""
+    def ordinal(x):
+        bits = (np.ascontiguousarray(x, dtype=np.float32).view(np.uint32) >> 16).astype(np.int64)
+        mag = bits & 0x7FFF
+        return np.where(bits & 0x8000, -mag, mag)
+    return np.abs(ordinal(a) - ordinal(b))
+
+
+def key_codes_close(q_gpu, q_oracle):
+    """The GPU pools and projects in fp32 (fixed order), the oracle in fp64, and both round the normalised vector to
+    bf16: an element's code may land one bf16 step apart.  For elements near zero a bf16 step is smaller than the
+    fp32 noise of the sums they come from (about 1e-6 of the largest term, more after a centring offset has
+    cancelled the common component), so there the bound is absolute: 1e-5 of the unit vector."""
+    return bool(((bf16_steps(q_gpu, q_oracle) <= 1) | (np.abs(q_gpu - q_oracle) <= 1e-5)).all())
+
+
 def teacher_forced_check(L, st, cfg, ws, Ps, h0, tau, dtype="bf16"):
+    """Layer by layer with the GPU's own layer inputs and bank arrays.  The GPU's keys (fp32 accumulation) may differ
+    from the oracle's by one bf16 step in a few elements: the codes are bounded separately, and the oracle's match is
+    fed the GPU's keys, so that similarities are compared at 1e-5 and slots exactly."""
     outs = st.forward(h0, tau=tau, keep_all=True)
     torch.cuda.synchronize()
     stats = []
     h_prev = h0
+    tau32 = f32(tau)
     for l in range(cfg.n_layers):
         wnp = {k: npf(v) for k, v in ws[l].items()}
         ob = oracle_bank_from_gpu(st.banks[l], dtype)
-        r = O.gated_layer(npf(h_prev), ob, npf(Ps[l]), None, wnp, cfg.arch, cfg.n_heads, cfg.ln_eps, cfg.gelu, f32(tau))
         g = st.gate[l]
+        q_o, _ = O.fingerprint(npf(h_prev), npf(Ps[l]), None, dtype)
+        q_g, qinv_g = npf(g.fp_used), npf(g.inv_used)
+        steps = bf16_steps(q_g, q_o)
+        assert key_codes_close(q_g, q_o), (steps.max(), np.abs(q_g - q_o).max())
+        r = O.gated_layer(npf(h_prev), ob, None, None, wnp, cfg.arch, cfg.n_heads, cfg.ln_eps, cfg.gelu, tau32,
+                          fp_override=(q_g, qinv_g))
         hit = g.hit.cpu().numpy().astype(bool)
         idx = g.idx.cpu().numpy()
-        near = np.abs(r.sim - f32(tau)) < 1e-3
-        ties = O.near_tie_sets(r.q, r.qinv, ob.fp, ob.inv_norm, ob.valid)
+        near = np.abs(r.sim - tau32) < 1e-3
+        ties = O.near_tie_sets(q_g, qinv_g, ob.fp, ob.inv_norm, ob.valid)
         multi = np.array([len(t) > 1 for t in ties])
         assert np.array_equal(hit[~near], r.hit[~near]), (l, hit, r.hit, r.sim)
-        strict = ~near & ~multi
-        assert np.array_equal(idx[strict], r.idx[strict]), (l, idx, r.idx)
+        assert np.array_equal(idx[~multi], r.idx[~multi]), (l, idx, r.idx)
         for b in np.nonzero(multi)[0]:
             assert idx[b] in ties[b]
-        np.testing.assert_allclose(npf(g.sim), r.sim, atol=2e-4)   # keys differ by a few bf16 steps at most
+        np.testing.assert_allclose(npf(g.sim), r.sim, rtol=0, atol=1e-5)
         got = npf(outs[l])
         for b in range(h0.shape[0]):
             if hit[b]:
@@ -1267,7 +1292,7 @@ def teacher_forced_check(L, st, cfg, ws, Ps, h0, tau, dtype="bf16"):
         err = rel_err_rows(got[miss], r.h_out[miss]) if miss.any() else np.zeros(1)
         assert err.max() < TOL[dtype], (l, err)
         stats.append(dict(layer=l, hits=int(hit.sum()), near_tau=int(near.sum()), near_tie=int(multi.sum()),
-                          max_err=float(err.max())))
+                          key_codes_off_by_one=int((steps > 0).sum()), max_err=float(err.max())))
         h_prev = outs[l]
     return stats
 
@@ -1284,7 +1309,7 @@ def test_model_sized_rows_bf16_teacher_forced(L, which):
     tok, pos = W.make_embeddings(cfg, seed=0)
     Ps = W.make_projection(cfg.d, cfg.k, torch.bfloat16, seed=3, n_layers=cfg.n_layers)
     src = W.make_sources(cfg, cfg.n_bank, seed=1)
-    st = GatedStack(cfg, ws, Ps)
+    st = GatedStack(cfg, ws, Ps, expose_keys=True)
     h_src = W.embed(torch.from_numpy(src), tok, pos, torch.bfloat16).cuda()
     build_banks_gpu(L, st, h_src)
     assert all(torch.all(b.valid == 1) for b in st.banks)
@@ -1297,4 +1322,140 @@ def test_model_sized_rows_bf16_teacher_forced(L, which):
         stats = teacher_forced_check(L, st, cfg, ws, Ps, h0, tau)
         for s in stats:
             say(f"  tau={tau} {s}")
+    st.close()
+
+
+# ---------------------------------------------------------------------------
+# the cost hint with carried AND uncarried rows; Algorithm 1's single fingerprint
+# ---------------------------------------------------------------------------
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("deferred", [False, True])
+def test_cost_hint_with_carried_and_uncarried_rows(L, dtype, deferred):
+    """LLMC_HINT_MOSTLY_CARRIED passed through the C ABI on a batch in which some rows arrive with a carried mean /
+    key (or as references to the producing bank) and some do not: the uncarried rows are then pooled inside the
+    projection's workgroups.  Keys against the oracle's fingerprint of the layer input, and every result against
+    the same call without the hint, bit for bit.  S is not a multiple of the 64-token pooling chunk."""
+    from paper_2512_16843_amd.engine import GatedStack
+    say(f"cost hint with mixed rows, {dtype}, deferred copies {deferred}")
+    cfg = W.scaled(W.TINY_ENCODER, n_layers=3, B=8, S=70, n_bank=24) if dtype == "f32" else \
+        W.scaled(W.BERT_BASE, n_layers=3, B=8, S=150, n_bank=24)
+    ws = W.make_layer_weights(cfg, seed=0)
+    tok, pos = W.make_embeddings(cfg, seed=0)
+    Ps = W.make_projection(cfg.d, cfg.k, cfg.torch_dtype, seed=3, n_layers=cfg.n_layers)
+    st = GatedStack(cfg, ws, Ps, keep_means=True, keep_next_keys=True, expose_keys=True)
+    src = W.make_sources(cfg, 16, seed=1)
+    fresh = W.make_sources(cfg, 8, seed=9)
+    for s0 in (0, 8):
+        st.forward(W.embed(torch.from_numpy(src[s0:s0 + 8]), tok, pos, cfg.torch_dtype).cuda(), tau=2.0,
+                   flags=L.INSERT_ON_MISS, tick=1)
+    ids = np.concatenate([src[[0, 5]], fresh[:3], src[[9, 15]], fresh[3:4]])       # 4 rows hit, 4 rows are computed
+    h0 = W.embed(torch.from_numpy(ids), tok, pos, cfg.torch_dtype).cuda()
+    results = {}
+    for hint in (False, True):
+        st._stat_event = None                      # the engine's own hint logic stays out of the way
+        st._hint = [hint] * cfg.n_layers
+        if deferred:
+            y = st.forward(h0, tau=0.9).clone()
+            outs = None
+        else:
+            outs = st.forward(h0, tau=0.9, keep_all=True)
+            y = outs[-1].clone()
+        torch.cuda.synchronize()
+        assert any(st._deferred) == deferred
+        results[hint] = (y, [dict(idx=g.idx.clone(), sim=g.sim.clone(), hit=g.hit.clone(), key=g.fp_used.clone(),
+                                  inv=g.inv_used.clone()) for g in st.gate], outs)
+    y0, g0, outs0 = results[False]
+    y1, g1, _ = results[True]
+    assert torch.equal(y0, y1)
+    for l in range(cfg.n_layers):
+        for k_ in g0[l]:
+            assert torch.equal(g0[l][k_], g1[l][k_]), (l, k_)
+        n_hit = int(g1[l]["hit"].sum())
+        assert 0 < n_hit < cfg.B                   # carried and uncarried rows in every layer
+    if outs0 is not None:
+        # keys of the hinted run against the oracle's fingerprint of each layer's input
+        for l in range(cfg.n_layers):
+            h_prev = h0 if l == 0 else outs0[l - 1]
+            q_o, qinv_o = O.fingerprint(npf(h_prev), npf(Ps[l]), None, dtype)
+            q_g = npf(g1[l]["key"])
+            if dtype == "bf16":
+                assert key_codes_close(q_g, q_o)
+            else:
+                assert np.abs(q_g - q_o).max() < 1e-6
+            np.testing.assert_allclose(npf(g1[l]["inv"]), O.inv_norm(q_g), rtol=3e-7, atol=0)
+    st.close()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_single_fingerprint_mode_against_oracle(L, dtype):
+    """Algorithm 1 as printed: one fingerprint of the input, reused by every layer (d_fp_given of the C ABI)."""
+    from paper_2512_16843_amd.engine import GatedStack
+    say(f"single-fingerprint mode {dtype}: banks built and queried with the key of h_0 at every layer")
+    cfg = W.scaled(W.TINY_ENCODER, n_layers=3, B=8, n_bank=24) if dtype == "f32" else \
+        W.scaled(W.BERT_BASE, n_layers=3, B=8, S=48, n_bank=24)
+    tol = TOL[dtype]
+    ws = W.make_layer_weights(cfg, seed=0)
+    tok, pos = W.make_embeddings(cfg, seed=0)
+    Ps = W.make_projection(cfg.d, cfg.k, cfg.torch_dtype, seed=3, n_layers=cfg.n_layers)
+    st = GatedStack(cfg, ws, Ps)
+    wnp = [{k_: npf(v) for k_, v in w.items()} for w in ws]
+    Pnp = [npf(p) for p in Ps]
+    obanks = [O.Bank(cfg.n_bank, cfg.k, cfg.S, cfg.d, dtype) for _ in range(cfg.n_layers)]
+    src = W.make_sources(cfg, 16, seed=1)
+    near, _ = W.make_substitution_queries(W.scaled(cfg, B=4), src, n_dup=4, n_subst=1, seed=5)
+    fresh = W.make_sources(cfg, 8, seed=9)
+    batches = [(src[0:8], 2.0, L.INSERT_ON_MISS), (src[8:16], 2.0, L.INSERT_ON_MISS),
+               (np.concatenate([src[[0, 5, 9, 15]], fresh[:4]]), 0.9, 0),
+               (np.concatenate([near, fresh[4:8]]), 0.9, L.INSERT_ON_MISS | L.UPDATE_LRU)]
+    for tick, (ids, tau, flags) in enumerate(batches, start=1):
+        h0 = W.embed(torch.from_numpy(ids), tok, pos, cfg.torch_dtype)
+        outs = st.forward(h0.cuda(), tau=tau, flags=flags, tick=tick, keep_all=True, single_fingerprint=True)
+        torch.cuda.synchronize()
+        oflags = (O.FLAG_UPDATE_LRU if flags & L.UPDATE_LRU else 0) | (O.FLAG_INSERT_ON_MISS if flags & L.INSERT_ON_MISS else 0)
+        # the oracle runs teacher-forced per layer on the GPU's layer inputs.  The one key of the batch: the oracle's
+        # fingerprint of h_0 bounds the GPU's (one step of the storage type at most), and the GPU's key is what
+        # the oracle's layers are fed, so that similarities compare at 1e-5
+        q_o, _ = O.fingerprint(npf(h0), Pnp[0], None, dtype)
+        q_g, qinv_g = run_fingerprint(L, h0.cuda(), Ps[0].cuda(), None)
+        q_g, qinv_g = npf(q_g), npf(qinv_g)
+        if dtype == "bf16":
+            assert key_codes_close(q_g, q_o)
+        else:
+            assert np.abs(q_g - q_o).max() < 1e-6
+        fp0 = (q_g, qinv_g)
+        for l in range(cfg.n_layers):
+            h_prev = npf(h0 if l == 0 else outs[l - 1])
+            ob = obanks[l]
+            pre_fp, pre_inv, pre_valid = ob.fp.copy(), ob.inv_norm.copy(), ob.valid.copy()
+            r = O.gated_layer(h_prev, ob, None, None, wnp[l], cfg.arch, cfg.n_heads, cfg.ln_eps, cfg.gelu, f32(tau),
+                              flags=oflags, tick=tick, out_dtype=dtype, fp_override=fp0)
+            g, bk = st.gate[l], st.banks[l]
+            hit = g.hit.cpu().numpy().astype(bool)
+            near_tau = np.abs(r.sim - f32(tau)) < 1e-3
+            assert not near_tau.any()
+            assert np.array_equal(hit, r.hit), (tick, l)
+            ties = O.near_tie_sets(fp0[0], fp0[1], pre_fp, pre_inv, pre_valid) if pre_valid.any() else None
+            gi = g.idx.cpu().numpy()
+            for b in range(cfg.B):
+                assert gi[b] == r.idx[b] or (ties is not None and gi[b] in ties[b]), (tick, l, b)
+            if pre_valid.any():
+                np.testing.assert_allclose(npf(g.sim), r.sim, rtol=0, atol=1e-5)
+            n_miss = int((~hit).sum())
+            if flags & L.INSERT_ON_MISS:
+                assert g.slots.cpu().tolist()[:n_miss] == r.slots
+            assert np.array_equal(bk.valid.cpu().numpy(), ob.valid)
+            got = npf(outs[l])
+            for b in range(cfg.B):
+                if hit[b]:
+                    assert np.array_equal(got[b], npf(bk.act[int(gi[b])]))
+                else:
+                    assert rel_err_rows(got[b:b + 1], r.h_out[b:b + 1])[0] < tol, (tick, l, b)
+            # keep the two banks' stored arrays identical, so that later hits copy the same numbers
+            v = ob.valid.astype(bool)
+            ob.act[v] = npf(bk.act)[v]
+            ob.fp[v] = npf(bk.fp)[v]
+            ob.inv_norm[v] = npf(bk.inv_norm)[v]
+        say(f"  batch {tick} (tau {tau}): hits per layer {[int(x.hit.sum()) for x in st.gate]}")
+    assert sum(int(x.hit.sum()) for x in st.gate) > 0
     st.close()
