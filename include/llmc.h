@@ -352,6 +352,22 @@ llmc_status_t llmc_match(const llmc_bank_t* bank, const void* d_fp, const float*
                          llmc_stream_t stream);
 size_t llmc_match_workspace_bytes(const llmc_bank_t* bank, int32_t B);
 
+/*
+ * llmc_match for callers that cannot allocate device memory and have no workspace to pass: code running under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and
+ * the same results as llmc_match, but the per-split candidates of the bulk pass go to a fixed scratch array
+ * inside the library (LLMC_MATCH_STATIC_SCRATCH_BYTES of device memory per GPU, held until the process ends)
+ * instead of a caller's workspace.  The call allocates and frees nothing.
+ * Errors: as llmc_match; WORKSPACE if llmc_match_workspace_bytes(bank, B) exceeds the fixed scratch (the
+ * message names both sizes), nothing is enqueued then.
+ * Every call on one GPU shares that GPU's scratch: two such calls must not overlap in time on one GPU
+ * (different streams, or different host threads), or they race on it.  Calls on one stream are ordered and safe.
+ */
+#define LLMC_MATCH_STATIC_SCRATCH_BYTES (4u << 20)
+llmc_status_t llmc_match_noalloc(const llmc_bank_t* bank, const void* d_fp, const float* d_inv_norm,
+                                 int32_t B, float tau, int32_t* d_idx, float* d_sim, uint8_t* d_hit,
+                                 uint8_t* d_near_tie, llmc_stream_t stream);
+
 /* ---- sign-bit keys (SimHash) and their Hamming match ------------------------------ */
 
 /*

@@ -358,6 +358,26 @@ llmc_status_t llmc_match(const llmc_bank_t* bank, const void* d_fp, const float*
                       (hipStream_t)stream);
 }
 
+llmc_status_t llmc_match_noalloc(const llmc_bank_t* bank, const void* d_fp, const float* d_inv_norm, int32_t B,
+                                 float tau, int32_t* d_idx, float* d_sim, uint8_t* d_hit, uint8_t* d_near_tie,
+                                 llmc_stream_t stream) {
+  REQUIRE(bank && d_fp && d_inv_norm && d_idx, LLMC_ERR_INVALID_ARG, "NULL argument");
+  REQUIRE(!bank->desc.key_bits, LLMC_ERR_DTYPE, "the bank holds sign-bit keys: use llmc_match_bits");
+  REQUIRE(B > 0, LLMC_ERR_INVALID_ARG, "B must be positive");
+  REQUIRE(B <= 65535 * 128, LLMC_ERR_SHAPE, "B=%d too large", B);
+  REQUIRE(tau == tau, LLMC_ERR_INVALID_ARG, "tau is NaN");
+  REQUIRE(aligned16(d_fp), LLMC_ERR_SHAPE, "query keys must be 16-byte aligned");
+  const size_t need = match_ws_bytes(bank->desc.n_slots, bank->desc.k, bank->desc.dtype, B);
+  REQUIRE(need <= (size_t)LLMC_MATCH_STATIC_SCRATCH_BYTES, LLMC_ERR_WORKSPACE,
+          "llmc_match_noalloc: %d queries against %d slots need %zu bytes of scratch, the library's fixed scratch "
+          "holds %zu: use llmc_match with a workspace",
+          B, bank->desc.n_slots, need, (size_t)LLMC_MATCH_STATIC_SCRATCH_BYTES);
+  void* ws = nullptr;
+  size_t have = 0;
+  LLMC_TRY(match_static_scratch(&ws, &have));
+  return launch_match(bank, d_fp, d_inv_norm, B, tau, d_idx, d_sim, d_hit, d_near_tie, ws, (hipStream_t)stream);
+}
+
 llmc_status_t llmc_gather_hits(const llmc_bank_t* bank, const int32_t* d_idx, const int32_t* d_rows, const int32_t* d_n,
                                int32_t n_max, void* d_h_out, llmc_stream_t stream) {
   REQUIRE(bank && d_idx && d_h_out, LLMC_ERR_INVALID_ARG, "NULL argument");

@@ -206,6 +206,8 @@ llmc_status_t launch_match(const llmc_bank* bank, const void* d_fp, const float*
                            int32_t* d_idx, float* d_sim, uint8_t* d_hit, uint8_t* d_near_tie, void* ws,
                            hipStream_t st);
 
+llmc_status_t match_static_scratch(void** out, size_t* bytes);
+
 // gate.hip
 llmc_status_t launch_compact(const uint8_t* d_hit, const int32_t* d_idx, const float* d_sim,
                              const uint8_t* d_near_tie, int B, float tau, int32_t* d_hit_rows,

@@ -837,6 +837,30 @@ llmc_status_t launch_match_decide(llmc_bank* bank, const void* d_fp, const float
   return LLMC_OK;
 }
 
+// ---- library-owned scratch for callers that cannot allocate ---------------------------------------------------
+// The per-(split, query) candidates of the bulk pass normally live in a workspace the caller brings.  For callers
+// that can neither allocate nor carry one around, the same kernels can write them into this file-scope device
+// array instead: one copy per GPU, alive until the process ends, shared by every such call on that GPU.
+static __device__ __align__(256) unsigned char scratch[LLMC_MATCH_STATIC_SCRATCH_BYTES];
+
+// Device address of `scratch` on the current device.  In host code the array's name is only a handle for the
+// symbol, never an address a kernel could use; the address is asked for once per device and kept.
+llmc_status_t match_static_scratch(void** out, size_t* bytes) {
+  static std::atomic<void*> ptr[64];
+  int dev = 0;
+  LLMC_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= 64) return set_error(LLMC_ERR_HIP, "device ordinal %d out of range", dev);
+  void* p = ptr[dev].load(std::memory_order_acquire);
+  if (!p) {
+    LLMC_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return set_error(LLMC_ERR_HIP, "hipGetSymbolAddress returned a null address");
+    ptr[dev].store(p, std::memory_order_release);
+  }
+  *out = p;
+  *bytes = sizeof(scratch);
+  return LLMC_OK;
+}
+
 llmc_status_t launch_match(const llmc_bank* bank, const void* d_fp, const float* d_inv, int B, float tau,
                            int32_t* d_idx, float* d_sim, uint8_t* d_hit, uint8_t* d_near_tie, void* ws,
                            hipStream_t st) {

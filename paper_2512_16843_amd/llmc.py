@@ -32,8 +32,9 @@ EXPORTS = [
     "llmc_layer_workspace_bytes", "llmc_profile_begin", "llmc_profile_report", "llmc_profile_end",
     "llmc_last_error", "llmc_version", "llmc_fingerprint_bits", "llmc_match_bits",
     "llmc_match_bits_workspace_bytes", "llmc_max_hamming", "llmc_bank_pool_values",
-    "llmc_lsh_index_bytes", "llmc_lsh_build", "llmc_match_bits_lsh", "llmc_materialize",
+    "llmc_lsh_index_bytes", "llmc_lsh_build", "llmc_match_bits_lsh", "llmc_materialize", "llmc_match_noalloc",
 ]
+MATCH_STATIC_SCRATCH_BYTES = 4 << 20
 
 
 class BankDesc(C.Structure):
@@ -101,6 +102,7 @@ def lib() -> C.CDLL:
         L.llmc_fingerprint_workspace_bytes.restype = sz
         L.llmc_inv_norm.argtypes = [vp, i64, i32, i32, vp, vp]
         L.llmc_match.argtypes = [vp, vp, vp, i32, f32, vp, vp, vp, vp, vp, sz, vp]
+        L.llmc_match_noalloc.argtypes = [vp, vp, vp, i32, f32, vp, vp, vp, vp, vp]
         L.llmc_match_workspace_bytes.argtypes = [vp, i32]
         L.llmc_match_workspace_bytes.restype = sz
         L.llmc_gather_hits.argtypes = [vp, vp, vp, vp, i32, vp, vp]
@@ -281,6 +283,13 @@ def llmc_match(bank: Bank, fp: torch.Tensor, inv_norm: torch.Tensor, tau: float,
                workspace: torch.Tensor, stream=None) -> None:
     _check(lib().llmc_match(bank.handle, _ptr(fp), _ptr(inv_norm), fp.shape[0], tau, _ptr(idx), _ptr(sim), _ptr(hit),
                             _ptr(near_tie), _ptr(workspace), workspace.numel(), _stream(stream)))
+
+
+def llmc_match_noalloc(bank: Bank, fp: torch.Tensor, inv_norm: torch.Tensor, tau: float, idx: torch.Tensor,
+                       sim: Optional[torch.Tensor], hit: Optional[torch.Tensor], near_tie: Optional[torch.Tensor],
+                       stream=None) -> None:
+    _check(lib().llmc_match_noalloc(bank.handle, _ptr(fp), _ptr(inv_norm), fp.shape[0], tau, _ptr(idx), _ptr(sim),
+                                    _ptr(hit), _ptr(near_tie), _stream(stream)))
 
 
 def llmc_fingerprint_bits(h: torch.Tensor, proj: torch.Tensor, bias: Optional[torch.Tensor], bits_out: torch.Tensor,
