@@ -24,6 +24,9 @@ What follows the paper, and where:
 * compressed values -- Section III-B: cached outputs stored as coefficients on a
   PCA basis and reconstructed on a hit.
 * eviction     -- Section IV-D, first policy: least recently used.
+* within-batch reuse -- Algorithm 1 processes inputs one after the other and stores each
+  miss before the next input is looked up; FLAG_DEDUP gives the rows of one batch that
+  behaviour among themselves (pinned against a row-by-row run of the same function).
 * f_l          -- Section V-A names the model families; the blocks themselves
   are the textbook post-LN encoder block and pre-LN causal decoder block.
 
@@ -52,6 +55,7 @@ GELU_TANH = 1
 FLAG_INSERT_ON_MISS = 1
 FLAG_UPDATE_LRU = 2
 FLAG_REVALIDATE = 4
+FLAG_DEDUP = 32
 
 NORM_FLOOR = 1e-12
 
@@ -522,6 +526,7 @@ class GateResult:
     revalidated: List[int] = None   # hit rows that were re-computed (divergence monitor), ascending
     divergence: List[float] = None  # their divergence from the cached value
     refreshed: List[int] = None     # slots whose cached value was replaced by the fresh output
+    follower_of: Dict[int, int] = None  # FLAG_DEDUP: row -> the earlier row of the batch whose fresh entry it reused
 
 
 def gated_layer(h_in: np.ndarray, bank: Optional[Bank], P: Optional[np.ndarray], c: Optional[np.ndarray],
@@ -573,10 +578,33 @@ def gated_layer(h_in: np.ndarray, bank: Optional[Bank], P: Optional[np.ndarray],
     revalidated: List[int] = []
     divergence: List[float] = []
     refreshed: List[int] = []
+    # Within-batch reuse (Algorithm 1 run over the rows of the batch one after the other: a row can hit what an
+    # EARLIER row of the same batch has just stored).  Rows that miss the bank as it stood are taken in ascending
+    # order; a row is a LEADER unless its key is more similar than tau to the key of an earlier leader, in which
+    # case it FOLLOWS the most similar earlier leader (the earliest one among equals): it is not computed, it returns
+    # the leader's stored output, counts as a hit on the leader's new entry and is not stored again.
+    follower_of: Dict[int, int] = {}
+    if (flags & FLAG_DEDUP) and (flags & FLAG_INSERT_ON_MISS):
+        assert not bank.key_bits and bank.basis is None and not (flags & FLAG_REVALIDATE)
+        leaders: List[int] = []
+        q64 = np.asarray(q, dtype=np.float64)
+        for b in range(B):
+            if hit[b]:
+                continue
+            best, best_s = -1, -np.inf
+            for a in leaders:
+                s_ab = float(q64[b] @ q64[a]) * float(qinv[b]) * float(qinv[a])
+                if s_ab > float(tau) and s_ab > best_s:
+                    best, best_s = a, s_ab
+            if best < 0:
+                leaders.append(b)
+            else:
+                follower_of[b] = best
+                sim[b] = best_s
     for b in range(B):
         if hit[b]:
             h_out[b] = bank.value(int(bank.act_slot[idx[b]]))
-        else:
+        elif b not in follower_of:
             h_out[b] = layer_forward(h_in[b], w, arch, n_heads, eps, gelu_kind)
     if (flags & FLAG_REVALIDATE) and reval_every >= 1:
         assert bank.basis is None, "the divergence monitor is not defined for compressed values"
@@ -608,13 +636,23 @@ def gated_layer(h_in: np.ndarray, bank: Optional[Bank], P: Optional[np.ndarray],
     slots: List[int] = []
     n_evicted = 0
     if flags & FLAG_INSERT_ON_MISS:
-        miss = [b for b in range(B) if not hit[b]]
+        miss = [b for b in range(B) if not hit[b] and b not in follower_of]
         if miss:
             vals = h_out[miss]
             if out_dtype is not None:
                 vals = round_to_storage(vals, out_dtype)
             slots, n_evicted = bank.insert(q[miss], qinv[miss], vals, tick)
-    return GateResult(h_out, q, qinv, idx, sim, hit, slots, n_evicted, revalidated, divergence, refreshed)
+        if follower_of:
+            slot_of = {b: j for b, j in zip(miss, slots)}
+            hit = hit.copy()
+            idx = idx.copy()
+            for b, a in sorted(follower_of.items()):
+                j = slot_of[a]
+                h_out[b] = bank.value(int(bank.act_slot[j]))      # the leader's output as stored
+                hit[b] = True
+                idx[b] = j
+                bank.touch([j], tick)
+    return GateResult(h_out, q, qinv, idx, sim, hit, slots, n_evicted, revalidated, divergence, refreshed, follower_of)
 
 
 def infer(h0: np.ndarray, banks: Sequence[Optional[Bank]], Ps: Sequence[np.ndarray],

@@ -411,3 +411,74 @@ def test_workload_generators_are_deterministic_and_shaped():
     st = W.StemStream(W.scaled(W.BERT_LARGE, B=8, S=20, n_layers=1), group=4, stem_len=12, n_stems=5)
     ids, sid = st.next_batch()
     assert np.array_equal(ids[0, :12], ids[3, :12]) and not np.array_equal(ids[0, 12:], ids[1, 12:])
+
+
+# ---- within-batch reuse: Algorithm 1 applied to the rows of a batch one after the other ----------
+
+def test_dedup_equals_algorithm_1_row_by_row():
+    """FLAG_DEDUP against the literal sequential algorithm: the same rows fed one at a time (each miss stored before
+    the next row is looked up).  Keys are hand-made unit vectors in a plane, so every similarity is a known cosine:
+    bank entries at 0 and 90 degrees; batch rows at
+        0 (hits the bank), 200 (fresh: leader), 200 again (exact duplicate: follows), 230 (cos 30 = 0.866 < tau: a
+        second leader), 220 (cos 20 = 0.94 to the first leader, cos 10 = 0.985 to the second: follows the SECOND),
+        90 (hits the bank), 300 (fresh: leader), 205 (follows the first leader)."""
+    cfg, ws, _tok, _pos, Ps, _src, h_src = tiny_setup(n_src=10)
+    wnp = ws[0]
+    tau = 0.9
+    k = cfg.k
+    def key(deg):
+        v = np.zeros((k,), np.float32)
+        v[0], v[1] = math.cos(math.radians(deg)), math.sin(math.radians(deg))
+        return v
+    angles = [0, 200, 200, 230, 220, 90, 300, 205]
+    B = len(angles)
+    q = np.stack([key(a) for a in angles])
+    qinv = O.inv_norm(q)
+    h = rng(5).standard_normal((B, cfg.S, cfg.d))
+    flags = O.FLAG_INSERT_ON_MISS | O.FLAG_UPDATE_LRU
+
+    def fresh_bank():
+        bank = O.Bank(8, k, cfg.S, cfg.d, "f32")
+        seed_keys = np.stack([key(0), key(90)])
+        vals = rng(6).standard_normal((2, cfg.S, cfg.d)).astype(np.float32)
+        bank.insert(seed_keys, O.inv_norm(seed_keys), vals, tick=1)
+        return bank
+
+    # the batch at once, with within-batch reuse
+    bank_b = fresh_bank()
+    r = O.gated_layer(h, bank_b, None, None, wnp, cfg.arch, cfg.n_heads, cfg.ln_eps, cfg.gelu, tau,
+                      flags=flags | O.FLAG_DEDUP, tick=2, out_dtype="f32", fp_override=(q, qinv))
+    assert r.follower_of == {2: 1, 4: 3, 7: 1}
+    assert r.hit.tolist() == [True, False, True, False, True, True, False, True]
+    # row by row: Algorithm 1 as printed
+    bank_s = fresh_bank()
+    seq_hit, seq_idx, seq_out = [], [], []
+    for b in range(B):
+        rb = O.gated_layer(h[b:b + 1], bank_s, None, None, wnp, cfg.arch, cfg.n_heads, cfg.ln_eps, cfg.gelu, tau,
+                           flags=flags, tick=2, out_dtype="f32", fp_override=(q[b:b + 1], qinv[b:b + 1]))
+        seq_hit.append(bool(rb.hit[0]))
+        seq_idx.append(int(rb.idx[0]) if rb.hit[0] else rb.slots[0])
+        seq_out.append(rb.h_out[0])
+    assert r.hit.tolist()[0] and seq_hit == [True, False, True, False, True, True, False, True]
+    # the entry a row ends up associated with: the slot it hit, or the slot it was stored in
+    slot_of_leader = {b: s for b, s in zip([b for b in range(B) if not r.hit[b]], r.slots)}
+    got_idx = [int(r.idx[b]) if r.hit[b] else slot_of_leader[b] for b in range(B)]
+    assert got_idx == seq_idx
+    for b in range(B):
+        want = seq_out[b]
+        if r.hit[b]:
+            want = np.asarray(want, dtype=np.float32)        # reused rows return the value as stored
+        np.testing.assert_allclose(r.h_out[b], want, rtol=0, atol=1e-6)
+    # and the banks end up identical: keys, validity, recency, hit counts, values
+    assert np.array_equal(bank_b.valid, bank_s.valid) and np.array_equal(bank_b.fp, bank_s.fp)
+    assert np.array_equal(bank_b.last_used, bank_s.last_used) and np.array_equal(bank_b.hits, bank_s.hits)
+    assert np.array_equal(bank_b.act, bank_s.act)
+    assert bank_b.hits[:2].tolist() == [1, 1] and int(bank_b.valid.sum()) == 5
+    # similarities reported for followers are those to the leader's key
+    np.testing.assert_allclose([r.sim[2], r.sim[4], r.sim[7]],
+                               [1.0, math.cos(math.radians(10)), math.cos(math.radians(5))], atol=1e-6)
+    # without the flag the same batch stores every miss (five rows, the snapshot semantics)
+    bank_n = fresh_bank()
+    rn = O.gated_layer(h, bank_n, None, None, wnp, cfg.arch, cfg.n_heads, cfg.ln_eps, cfg.gelu, tau,
+                       flags=flags, tick=2, out_dtype="f32", fp_override=(q, qinv))
+    assert int((~rn.hit).sum()) == 6 and len(rn.slots) == 6 and rn.follower_of == {}
