@@ -100,7 +100,7 @@ def kernel_work(cfg, name, miss, hit, e=2, carry=False, copied=None):
         return 2.0 * rows * d * k, L * (d * k * e + B * k * e), "hbm"
     if name in ("match_bf16_kernel", "match_stream_kernel"):
         return L * 2.0 * B * N * k, L * float(N) * k * e, "hbm" if B < 300 else "mfma"
-    if name in ("match_finalize_kernel", "match_decide_kernel"):
+    if name == "match_finalize_kernel":
         return L * 2.0 * B * 32 * k, L * float(B) * 32 * k * e, "hbm"
     if name == "insert_kernel":
         return 0.0, sum(2.0 * m * S * d * e for m in miss), "hbm"
@@ -391,7 +391,7 @@ def main():
     del roof["us"]
     rooflines = []
     for kname in ("gemm_bf16_kernel", "attention_kernel", "layernorm_kernel", "pool_kernel", "gather_kernel",
-                  "match_stream_kernel", "match_finalize_kernel", "match_decide_kernel"):
+                  "match_stream_kernel", "match_finalize_kernel"):
         for tag, pr in (("headline", prof_head), ("no_cache", prof_nocache)):
             if kname in pr and (pr[kname]["flops_per_step"] or pr[kname]["bytes_per_step"]) and kname != name:
                 k_ = pr[kname]

@@ -106,13 +106,15 @@ enum {
   LLMC_CNT_HIT = 0,      /* rows answered from the bank */
   LLMC_CNT_MISS = 1,     /* rows computed */
   LLMC_CNT_NEAR_TAU = 2, /* rows with |sim - tau| < 1e-3 */
-  LLMC_CNT_NEAR_TIE = 3, /* rows whose two best candidate groups were re-evaluated exactly */
+  LLMC_CNT_NEAR_TIE = 3, /* rows whose two best candidate groups (or all groups, see below) were re-evaluated exactly */
   LLMC_CNT_INSERTED = 4,
   LLMC_CNT_EVICTED = 5,  /* insertions that replaced a valid entry */
   LLMC_CNT_DROPPED = 6,  /* insertions skipped: bank full and policy NONE */
   LLMC_CNT_COMPUTED = 7, /* rows that went through f_l: misses + revalidated hits */
   LLMC_CNT_REVALIDATED = 8, /* hit rows recomputed by the divergence monitor */
   LLMC_CNT_DIVERGED = 9,    /* of those, entries whose cached value was replaced */
+  LLMC_CNT_TIE_OVERFLOW = 10, /* rows with three or more candidate groups within 1e-5 of the best: decided among the two
+                                 best groups, so the slot is within that margin of the arg-max but possibly not it */
   LLMC_CNT_WORDS = 12
 };
 
@@ -339,7 +341,9 @@ llmc_status_t llmc_inv_norm(const void* d_fp, int64_t n, int32_t k, int32_t dtyp
  *   d_idx [B]: best slot, lowest slot on exact ties, -1 if no valid entry
  *   d_sim [B]: its cosine (product of the stored vectors times both inverse norms), -inf if none
  *   d_hit [B]: sim > tau        (d_sim, d_hit may be NULL)
- *   d_near_tie: optional [B] flags, 1 where two candidate groups were compared exactly
+ *   d_near_tie: optional [B] flags: 1 where two candidate groups were compared exactly; 2 where three or more
+ *               groups were within 1e-5 of the best (several near-identical keys): the winner of the two best
+ *               groups is returned, which is within that margin of the maximum but need not be the arg-max
  * The bulk search runs on the matrix cores with fp32 accumulation; the winner
  * is then decided, and d_sim computed, in fp64 among the best candidate group
  * (and the runner-up group when the two are closer than 1e-5).
@@ -363,7 +367,7 @@ size_t llmc_match_workspace_bytes(const llmc_bank_t* bank, int32_t B);
  * Every call on one GPU shares that GPU's scratch: two such calls must not overlap in time on one GPU
  * (different streams, or different host threads), or they race on it.  Calls on one stream are ordered and safe.
  */
-#define LLMC_MATCH_STATIC_SCRATCH_BYTES (4u << 20)
+#define LLMC_MATCH_STATIC_SCRATCH_BYTES (5u << 20)
 llmc_status_t llmc_match_noalloc(const llmc_bank_t* bank, const void* d_fp, const float* d_inv_norm,
                                  int32_t B, float tau, int32_t* d_idx, float* d_sim, uint8_t* d_hit,
                                  uint8_t* d_near_tie, llmc_stream_t stream);

@@ -454,9 +454,8 @@ llmc_status_t llmc_profile_end(void) {
 
 size_t llmc_layer_workspace_bytes(const llmc_layer_desc_t* layer, int32_t B, int32_t S, int32_t k) {
   if (!layer || B <= 0 || S <= 0 || k < 0 || !dtype_ok(layer->dtype)) return 0;
-  // the match scratch is bounded by 1024 splits of 16 bytes per row
   return fingerprint_ws_bytes(B, S, layer->d) + gate_small_bytes(B, k > 0 ? k : 32, layer->dtype) +
-         align_up((size_t)1024 * B * 16, 256) + layer_ws_bytes(layer, B, S);
+         match_ws_max_bytes(B) + layer_ws_bytes(layer, B, S);
 }
 
 llmc_status_t llmc_layer_forward_gated(const llmc_layer_desc_t* layer, llmc_bank_t* bank, const llmc_fp_desc_t* fp,
@@ -547,7 +546,7 @@ llmc_status_t llmc_layer_forward_gated(const llmc_layer_desc_t* layer, llmc_bank
   uint8_t* hit = (uint8_t*)take((size_t)B);
   uint8_t* tie = (uint8_t*)take((size_t)B);
   int32_t* counters = (int32_t*)take(LLMC_CNT_WORDS * 4);
-  void* ws_match = take((size_t)1024 * B * 16);
+  void* ws_match = take(match_ws_max_bytes(B));
   void* ws_layer = (void*)p;
   if (out) {
     if (out->d_idx) idx = out->d_idx;
@@ -598,8 +597,6 @@ llmc_status_t llmc_layer_forward_gated(const llmc_layer_desc_t* layer, llmc_bank
                                (const uint32_t*)q, B, llmc_max_hamming(tau, k), idx, nullptr, hit, ws_match, st,
                                (const uint32_t*)bank->d_binv_eff, sim));
     tie = nullptr;
-  } else {
-    LLMC_TRY(launch_match(bank, q, qinv, B, tau, idx, sim, hit, tie, ws_match, st));
   }
   float* pooled_out = nullptr;
   uint8_t* pooled_valid_out = nullptr;
@@ -613,8 +610,10 @@ llmc_status_t llmc_layer_forward_gated(const llmc_layer_desc_t* layer, llmc_bank
       key_inv_out = out->d_key_inv_out;
     }
   }
+  int32_t* ref_out = (flags & LLMC_DEFER_COPY) ? out->d_ref_out : nullptr;
+  if (!bits) LLMC_TRY(launch_match(bank, q, qinv, B, tau, idx, sim, hit, tie, ws_match, st));
   LLMC_TRY(launch_compact(hit, idx, sim, tie, B, tau, hit_rows, miss_rows, reval_tmp, counters, bank, flags, tick, st,
-                          pooled_valid_out, pooled_out ? 1 : 0, (flags & LLMC_DEFER_COPY) ? out->d_ref_out : nullptr));
+                          pooled_valid_out, pooled_out ? 1 : 0, ref_out));
   // rows to compute that arrived as references get their content now (the only reader of a referenced row)
   if (!d_fp_given && fp && fp->d_ref_in)
     LLMC_TRY(launch_materialize(fp->prev_bank, fp->d_ref_in, miss_rows, counters + LLMC_CNT_COMPUTED, B,

@@ -202,6 +202,7 @@ llmc_status_t launch_inv_norm(const void* d_fp, int64_t n, int k, int dtype, flo
 
 // match.hip
 size_t match_ws_bytes(int n_slots, int k, int dtype, int B);
+size_t match_ws_max_bytes(int B);
 llmc_status_t launch_match(const llmc_bank* bank, const void* d_fp, const float* d_inv, int B, float tau,
                            int32_t* d_idx, float* d_sim, uint8_t* d_hit, uint8_t* d_near_tie, void* ws,
                            hipStream_t st);
@@ -214,10 +215,6 @@ llmc_status_t launch_compact(const uint8_t* d_hit, const int32_t* d_idx, const f
                              int32_t* d_miss_rows, int32_t* d_reval_tmp, int32_t* d_counters, llmc_bank* bank,
                              uint32_t flags, uint64_t tick, hipStream_t st, uint8_t* d_pooled_valid_out = nullptr,
                              int has_pool = 0, int32_t* d_ref_out = nullptr);
-llmc_status_t launch_match_decide(llmc_bank* bank, const void* d_fp, const float* d_inv, int B, float tau, int32_t* d_idx,
-                                  float* d_sim, uint8_t* d_hit, void* ws, int32_t* d_hit_rows, int32_t* d_miss_rows,
-                                  int32_t* d_reval_tmp, int32_t* d_counters, uint32_t flags, uint64_t tick,
-                                  uint8_t* d_pooled_valid_out, int has_pool, int32_t* d_ref_out, hipStream_t st);
 llmc_status_t launch_materialize(const llmc_bank* bank, const int32_t* d_ref, const int32_t* d_rows, const int32_t* d_n,
                                  int n_max, void* d_h, hipStream_t st);
 llmc_status_t launch_divergence(llmc_bank* bank, const void* d_h_out, const int32_t* d_idx, const int32_t* d_rows,

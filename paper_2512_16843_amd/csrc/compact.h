@@ -1,6 +1,5 @@
 // Compaction of the gate (Section III-D of the paper): per-row hit flags into ascending lists of reused rows and of
 // rows to compute, with device-side counts; recency update of the entries that were hit (Section IV-D).
-// Shared by the stand-alone compaction kernel and by the fused decision kernel for small batches.
 #pragma once
 #include "common.h"
 
@@ -22,9 +21,9 @@ __device__ __forceinline__ void compact_rows(const uint8_t* hit, const int32_t* 
                                                        int32_t* __restrict__ ref_out,
                                                        const int32_t* __restrict__ act_slot) {
   __shared__ int wave_hits[16], wave_reval[16];
-  __shared__ int base_hit, base_miss, base_reval, s_near_tau, s_near_tie;
+  __shared__ int base_hit, base_miss, base_reval, s_near_tau, s_near_tie, s_scanned;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  if (tid == 0) { base_hit = 0; base_miss = 0; base_reval = 0; s_near_tau = 0; s_near_tie = 0; }
+  if (tid == 0) { base_hit = 0; base_miss = 0; base_reval = 0; s_near_tau = 0; s_near_tie = 0; s_scanned = 0; }
   __syncthreads();
   for (int c0 = 0; c0 < B; c0 += 1024) {
     const int b = c0 + tid;
@@ -65,6 +64,7 @@ __device__ __forceinline__ void compact_rows(const uint8_t* hit, const int32_t* 
       }
       if (sim && fabsf(sim[b] - tau) < 1e-3f) atomicAdd(&s_near_tau, 1);
       if (tie && tie[b]) atomicAdd(&s_near_tie, 1);
+      if (tie && tie[b] > 1) atomicAdd(&s_scanned, 1);
     }
     __syncthreads();
     if (tid == 0) { base_hit += total; base_miss += n_in - total; base_reval += total_rv; }
@@ -83,7 +83,7 @@ __device__ __forceinline__ void compact_rows(const uint8_t* hit, const int32_t* 
     counters[LLMC_CNT_COMPUTED] = n_miss + n_reval;
     counters[LLMC_CNT_REVALIDATED] = n_reval;
     counters[LLMC_CNT_DIVERGED] = 0;
-    counters[10] = 0;
+    counters[LLMC_CNT_TIE_OVERFLOW] = s_scanned;
     counters[11] = 0;
   }
 }

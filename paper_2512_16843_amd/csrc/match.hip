@@ -7,22 +7,27 @@
 // fragment: the running maximum is a per-lane register operation with no cross-lane
 // traffic, and the score matrix is never written.  A lane does not track single rows but
 // "groups": the 16 bank rows of one fragment half, numbered  (row_base / 32) * 2 + half.
-// It keeps its two best groups (value = max over the group of acc * inv_norm).
-// Free slots carry NaN in the library's inv_norm mirror and fmaxf drops them.
+// It keeps its two best groups (value = max over the group of acc * inv_norm) and the VALUE of
+// the third best.  Free slots carry NaN in the library's inv_norm mirror and fmaxf drops them.
 //
 // Stage 2 (exact): one wavefront per query merges the partial results of all bank
 // splits, then evaluates the rows of the best group -- and of the runner-up group when it
 // is within 1e-5 of the best -- in fp64 and picks the winner there (lowest slot on exact
-// ties).  The reported similarity is that fp64 cosine.
+// ties).  The reported similarity is that fp64 cosine.  If the third best value is within
+// 1e-5 of the best as well (three or more groups that fp32 cannot tell apart: several
+// near-identical keys spread over the bank), the two kept groups may not hold the exact
+// arg-max; the slot returned is then the best of those two groups, within that margin of the
+// true maximum, and the row is flagged (near-tie flag 2, counted separately) so that it is
+// reported rather than silently wrong.
 #include "common.h"
 #include "mma.h"
-#include "compact.h"
 
 namespace llmc {
 
 struct Top2 {
   float v1; int g1;
   float v2; int g2;
+  float v3;            // third best value (its group is not kept)
 };
 
 __device__ __forceinline__ bool better(float v, int g, float v0, int g0) {
@@ -31,12 +36,34 @@ __device__ __forceinline__ bool better(float v, int g, float v0, int g0) {
 __device__ __forceinline__ void top2_push(Top2& t, float v, int g) {
   if (g < 0) return;
   if (better(v, g, t.v1, t.g1)) {
-    t.v2 = t.v1; t.g2 = t.g1; t.v1 = v; t.g1 = g;
-  } else if (better(v, g, t.v2, t.g2) && g != t.g1) {
-    t.v2 = v; t.g2 = g;
+    t.v3 = t.v2; t.v2 = t.v1; t.g2 = t.g1; t.v1 = v; t.g1 = g;
+  } else if (g != t.g1) {
+    if (better(v, g, t.v2, t.g2)) {
+      t.v3 = t.v2; t.v2 = v; t.g2 = g;
+    } else if (g != t.g2) {
+      t.v3 = fmaxf(t.v3, v);
+    }
   }
 }
-__device__ __forceinline__ Top2 top2_empty() { return Top2{-INFINITY, -1, -INFINITY, -1}; }
+// merge another list's entries (its two groups, then its third value) into t
+__device__ __forceinline__ void top2_merge(Top2& t, const Top2& c) {
+  top2_push(t, c.v1, c.g1);
+  top2_push(t, c.v2, c.g2);
+  t.v3 = fmaxf(t.v3, c.v3);
+}
+__device__ __forceinline__ Top2 top2_empty() { return Top2{-INFINITY, -1, -INFINITY, -1, -INFINITY}; }
+// one more group maximum in a stream of ascending groups (strict comparisons keep the lowest group among equals)
+__device__ __forceinline__ void top2_next(Top2& t, float mx, int g) {
+  const bool b1 = mx > t.v1, b2 = mx > t.v2;                        // NaN compares false
+  const float v3n = b2 ? t.v2 : fmaxf(t.v3, mx);                    // fmaxf drops a NaN maximum
+  const float v2n = b1 ? t.v1 : (b2 ? mx : t.v2);
+  const int g2n = b1 ? t.g1 : (b2 ? g : t.g2);
+  t.v1 = b1 ? mx : t.v1;
+  t.g1 = b1 ? g : t.g1;
+  t.v2 = v2n;
+  t.g2 = g2n;
+  t.v3 = v3n;
+}
 
 // rows of group g: base = (g / 2) * 32 + (g % 2) * 4;  row(r) = base + 8 * (r / 4) + (r % 4), r = 0..15
 __device__ __forceinline__ int group_row(int g, int r) { return (g >> 1) * 32 + (g & 1) * 4 + 8 * (r >> 2) + (r & 3); }
@@ -101,11 +128,7 @@ __global__ __launch_bounds__(MatchCfg::THREADS) void match_bf16_kernel(
 #pragma unroll
         for (int r = 1; r < 16; ++r) mx = fmaxf(mx, acc[i][j][r] * bi[r]);
         // tiles ascend, so a strict comparison keeps the lowest group among equals
-        if (mx > best[j].v1) {
-          best[j].v2 = best[j].v1; best[j].g2 = best[j].g1; best[j].v1 = mx; best[j].g1 = g;
-        } else if (mx > best[j].v2) {
-          best[j].v2 = mx; best[j].g2 = g;
-        }
+        top2_next(best[j], mx, g);
       }
     }
   }
@@ -120,11 +143,7 @@ __global__ __launch_bounds__(MatchCfg::THREADS) void match_bf16_kernel(
   __syncthreads();
   if (tid < C::BN && q0 + tid < B) {
     Top2 t = top2_empty();
-    for (int s = 0; s < C::WM * 2; ++s) {
-      const Top2 c = sc[s * C::BN + tid];
-      top2_push(t, c.v1, c.g1);
-      top2_push(t, c.v2, c.g2);
-    }
+    for (int s = 0; s < C::WM * 2; ++s) top2_merge(t, sc[s * C::BN + tid]);
     partial[(size_t)blockIdx.x * B + q0 + tid] = t;
   }
 }
@@ -269,11 +288,7 @@ __global__ __launch_bounds__(NW_ * 64) void match_stream_kernel(
         float mx = acc[i][j][0] * bi[0];
 #pragma unroll
         for (int r = 1; r < 16; ++r) mx = fmaxf(mx, acc[i][j][r] * bi[r]);
-        if (mx > best[j].v1) {
-          best[j].v2 = best[j].v1; best[j].g2 = best[j].g1; best[j].v1 = mx; best[j].g1 = g;
-        } else if (mx > best[j].v2) {
-          best[j].v2 = mx; best[j].g2 = g;
-        }
+        top2_next(best[j], mx, g);
       }
     }
   }
@@ -283,9 +298,9 @@ __global__ __launch_bounds__(NW_ * 64) void match_stream_kernel(
     Top2 o;
     o.v1 = __shfl_xor(best[j].v1, 32, 64); o.g1 = __shfl_xor(best[j].g1, 32, 64);
     o.v2 = __shfl_xor(best[j].v2, 32, 64); o.g2 = __shfl_xor(best[j].g2, 32, 64);
+    o.v3 = __shfl_xor(best[j].v3, 32, 64);
     Top2 m = best[j];
-    top2_push(m, o.v1, o.g1);
-    top2_push(m, o.v2, o.g2);
+    top2_merge(m, o);
     const int q = q_base + j * 32 + (lane & 31);
     if (half == 0 && q < B) partial[(size_t)split * B + q] = m;
   }
@@ -385,14 +400,7 @@ __global__ __launch_bounds__(512) void match_skew_kernel(
       }
 #pragma unroll
       for (int j = 0; j < C::FN; ++j) {
-        const float mx = m[j];
-        const bool b1 = mx > best[j].v1, b2 = mx > best[j].v2;      // NaN compares false
-        const float v2n = b1 ? best[j].v1 : (b2 ? mx : best[j].v2);
-        const int g2n = b1 ? best[j].g1 : (b2 ? g : best[j].g2);
-        best[j].v1 = b1 ? mx : best[j].v1;
-        best[j].g1 = b1 ? g : best[j].g1;
-        best[j].v2 = v2n;
-        best[j].g2 = g2n;
+        top2_next(best[j], m[j], g);
       }
     }
   };
@@ -453,9 +461,9 @@ __global__ __launch_bounds__(512) void match_skew_kernel(
     Top2 o;
     o.v1 = __shfl_xor(best[j].v1, 32, 64); o.g1 = __shfl_xor(best[j].g1, 32, 64);
     o.v2 = __shfl_xor(best[j].v2, 32, 64); o.g2 = __shfl_xor(best[j].g2, 32, 64);
+    o.v3 = __shfl_xor(best[j].v3, 32, 64);
     Top2 m = best[j];
-    top2_push(m, o.v1, o.g1);
-    top2_push(m, o.v2, o.g2);
+    top2_merge(m, o);
     const int q = q_base + j * 32 + (lane & 31);
     if (half == 0 && q < B) partial[(size_t)split * B + q] = m;
   }
@@ -488,10 +496,7 @@ __global__ __launch_bounds__(256) void match_f32_kernel(const float* __restrict_
   __syncthreads();
   if (threadIdx.x == 0) {
     Top2 m = top2_empty();
-    for (int i = 0; i < 256; ++i) {
-      top2_push(m, sc[i].v1, sc[i].g1);
-      top2_push(m, sc[i].v2, sc[i].g2);
-    }
+    for (int i = 0; i < 256; ++i) top2_merge(m, sc[i]);
     partial[b] = m;
   }
 }
@@ -520,24 +525,23 @@ __global__ __launch_bounds__(256) void match_finalize_kernel(
       c[u] = s < n_split ? partial[(size_t)s * B + b] : top2_empty();
     }
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      top2_push(t, c[u].v1, c[u].g1);
-      top2_push(t, c[u].v2, c[u].g2);
-    }
+    for (int u = 0; u < 4; ++u) top2_merge(t, c[u]);
   }
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) {
     Top2 c;
     c.v1 = __shfl_xor(t.v1, o, 64); c.g1 = __shfl_xor(t.g1, o, 64);
     c.v2 = __shfl_xor(t.v2, o, 64); c.g2 = __shfl_xor(t.g2, o, 64);
-    top2_push(t, c.v1, c.g1);
-    top2_push(t, c.v2, c.g2);
+    c.v3 = __shfl_xor(t.v3, o, 64);
+    top2_merge(t, c);
   }
   const float qi = qinv[b];
   const double qi64 = (double)qi;
   // scores so far are |q| * cos; the runner-up counts as tied within 1e-5 in cosine
   const float gap = qi > 0.f ? 1e-5f / qi : 0.f;
   const bool two = t.g2 >= 0 && t.v2 >= t.v1 - gap;
+  // three or more groups that close: the two kept ones may not hold the arg-max; flagged and counted
+  const bool many = two && t.v3 >= t.v1 - gap;
   const int n_groups = (t.g1 < 0) ? 0 : (two ? 2 : 1);
   const int r = lane >> 2, part = lane & 3;
   const int per = K / 4;                       // K is a multiple of 32, so per is a multiple of 8
@@ -590,120 +594,8 @@ __global__ __launch_bounds__(256) void match_finalize_kernel(
     idx_out[b] = best_j;
     if (sim_out) sim_out[b] = (float)best;
     if (hit_out) hit_out[b] = (best_j >= 0 && best > (double)tau) ? 1 : 0;
-    if (tie_out) tie_out[b] = two ? 1 : 0;
+    if (tie_out) tie_out[b] = many ? 2 : (two ? 1 : 0);
   }
-}
-
-// ---- small batches: the exact decision and the compaction in one launch ------------------------------------
-// One workgroup of 1024 threads for B <= 64 queries, 16 lanes per query.  Same arithmetic as match_finalize_kernel:
-// the partial results of the bank splits are merged, then lane r of a query evaluates row r of the best candidate
-// group (and of the runner-up when within 1e-5) in fp64 -- the four quarter sums of the key that the four lanes of
-// the stand-alone kernel hold are formed one after the other and added as (s0 + s1) + (s2 + s3), so the reported
-// similarity is the same bits -- and a butterfly over the 16 lanes picks the winner.  The rows' results then go
-// through compact_rows without leaving the workgroup.
-template <typename T>
-__global__ __launch_bounds__(1024) void match_decide_kernel(
-    const Top2* __restrict__ partial, int n_split, const T* __restrict__ bank, const float* __restrict__ binv,
-    const uint8_t* __restrict__ valid, int N, int K, const T* __restrict__ queries, const float* __restrict__ qinv,
-    int B, float tau, int32_t* __restrict__ idx_out, float* __restrict__ sim_out, uint8_t* __restrict__ hit_out,
-    int32_t* __restrict__ hit_rows, int32_t* __restrict__ miss_rows, int32_t* __restrict__ counters,
-    uint64_t* last_used, uint32_t* hits, int touch, uint64_t tick, int reval_every, int32_t* __restrict__ reval_tmp,
-    uint8_t* __restrict__ pooled_valid_out, int has_pool, int32_t* __restrict__ ref_out,
-    const int32_t* __restrict__ act_slot) {
-  constexpr int VEC = Vec16<T>::N;
-  __shared__ int32_t s_idx[64];
-  __shared__ float s_sim[64];
-  __shared__ uint8_t s_hit[64], s_tie[64];
-  const int b = threadIdx.x >> 4, r = threadIdx.x & 15;
-  if (b < B) {
-    Top2 t = top2_empty();
-    // eight partial results in flight per lane, merged in ascending split order
-    for (int s0 = r; s0 < n_split; s0 += 8 * 16) {
-      Top2 c[8];
-#pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        const int s = s0 + u * 16;
-        c[u] = s < n_split ? partial[(size_t)s * B + b] : top2_empty();
-      }
-#pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        top2_push(t, c[u].v1, c[u].g1);
-        top2_push(t, c[u].v2, c[u].g2);
-      }
-    }
-#pragma unroll
-    for (int o = 8; o > 0; o >>= 1) {
-      Top2 c;
-      c.v1 = __shfl_xor(t.v1, o, 64); c.g1 = __shfl_xor(t.g1, o, 64);
-      c.v2 = __shfl_xor(t.v2, o, 64); c.g2 = __shfl_xor(t.g2, o, 64);
-      top2_push(t, c.v1, c.g1);
-      top2_push(t, c.v2, c.g2);
-    }
-    const float qi = qinv[b];
-    const double qi64 = (double)qi;
-    const float gap = qi > 0.f ? 1e-5f / qi : 0.f;
-    const bool two = t.g2 >= 0 && t.v2 >= t.v1 - gap;
-    const int n_groups = (t.g1 < 0) ? 0 : (two ? 2 : 1);
-    const int per = K / 4;
-    double best = -INFINITY;
-    int best_j = -1;
-    for (int c = 0; c < n_groups; ++c) {
-      const int g = c == 0 ? t.g1 : t.g2;
-      const int j = group_row(g, r);
-      const int jc = min(j, N - 1);
-      const bool ok = j < N && valid[jc] != 0;
-      const double bj = (double)binv[jc];
-      double quarter[4];
-#pragma unroll
-      for (int part = 0; part < 4; ++part) {
-        const T* qp = queries + (size_t)b * K + part * per;
-        const T* kp = bank + (size_t)jc * K + part * per;
-        double a = 0.0;
-        int i = 0;
-        for (; i + 8 * VEC <= per; i += 8 * VEC) {
-          float x[8][VEC], y[8][VEC];
-#pragma unroll
-          for (int u = 0; u < 8; ++u) {
-            Vec16<T>::load(qp + i + u * VEC, x[u]);
-            Vec16<T>::load(kp + i + u * VEC, y[u]);
-          }
-#pragma unroll
-          for (int u = 0; u < 8; ++u)
-#pragma unroll
-            for (int e = 0; e < VEC; ++e) a += (double)x[u][e] * (double)y[u][e];
-        }
-        for (; i < per; i += VEC) {
-          float x[VEC], y[VEC];
-          Vec16<T>::load(qp + i, x);
-          Vec16<T>::load(kp + i, y);
-#pragma unroll
-          for (int e = 0; e < VEC; ++e) a += (double)x[e] * (double)y[e];
-        }
-        quarter[part] = a;
-      }
-      const double a = (quarter[0] + quarter[1]) + (quarter[2] + quarter[3]);
-      if (ok) {
-        const double s = a * qi64 * bj;
-        if (s > best || (s == best && (best_j < 0 || j < best_j))) { best = s; best_j = j; }
-      }
-    }
-#pragma unroll
-    for (int o = 1; o < 16; o <<= 1) {
-      const double os = __shfl_xor(best, o, 64);
-      const int oj = __shfl_xor(best_j, o, 64);
-      if (oj >= 0 && (best_j < 0 || os > best || (os == best && oj < best_j))) { best = os; best_j = oj; }
-    }
-    if (r == 0) {
-      const uint8_t h = (best_j >= 0 && best > (double)tau) ? 1 : 0;
-      s_idx[b] = best_j; s_sim[b] = (float)best; s_hit[b] = h; s_tie[b] = two ? 1 : 0;
-      idx_out[b] = best_j;
-      if (sim_out) sim_out[b] = (float)best;
-      if (hit_out) hit_out[b] = h;
-    }
-  }
-  __syncthreads();
-  compact_rows(s_hit, s_idx, s_sim, s_tie, B, tau, hit_rows, miss_rows, counters, last_used, hits, touch, tick,
-               reval_every, reval_tmp, pooled_valid_out, has_pool, ref_out, act_slot);
 }
 
 static void split_plan(int N, int B, int* n_split, int* tiles_per_split) {
@@ -735,6 +627,9 @@ static void stream_plan(int N, int B, int RB, int QB, int* n_qb, int* n_split, i
 // Many queries: workgroups of 8 wavefronts (512 query columns) with the deep ring.
 static int stream_waves(int B) { return B <= 256 ? 4 : 8; }
 static bool use_stream(int k) { return k == 64 || k == 128 || k == 256; }
+
+// upper bound of match_ws_bytes over all banks: at most 1024 splits
+size_t match_ws_max_bytes(int B) { return align_up((size_t)1024 * B * sizeof(Top2), 256); }
 
 size_t match_ws_bytes(int n_slots, int k, int dtype, int B) {
   int ns = 1, per = 1, nqb = 1;
@@ -779,61 +674,6 @@ static llmc_status_t launch_stream(const llmc_bank* bank, const void* d_fp, int 
   LLMC_KERNEL_GGL((match_skew_kernel<K_>), dim3(grid), dim3(512), C::LDS_BYTES, st, (const uint16_t*)D.d_fp,
                      bank->d_binv_eff, D.n_slots, (const uint16_t*)d_fp, B, nqb, ns, per, partial);
   *ns_out = ns;
-  return LLMC_OK;
-}
-
-// the bulk pass only: per-(split, query) candidates in ws; *ns_out splits
-static llmc_status_t launch_match_bulk(const llmc_bank* bank, const void* d_fp, int B, void* ws, int* ns_out,
-                                       hipStream_t st) {
-  const llmc_bank_desc_t& D = bank->desc;
-  const int N = D.n_slots, K = D.k;
-  Top2* partial = (Top2*)ws;
-  int ns = 1, per = 1;
-  if (D.dtype == LLMC_BF16) {
-    if (use_stream(K)) {
-      if (K == 256) LLMC_TRY(launch_stream<256>(bank, d_fp, B, partial, &ns, st));
-      else if (K == 128) LLMC_TRY(launch_stream<128>(bank, d_fp, B, partial, &ns, st));
-      else LLMC_TRY(launch_stream<64>(bank, d_fp, B, partial, &ns, st));
-      LLMC_LAUNCH_CHECK("match_stream_kernel");
-    } else {
-      split_plan(N, B, &ns, &per);
-      dim3 grid(ns, (B + MatchCfg::BN - 1) / MatchCfg::BN);
-      { ProfScope ps_("match_bf16_kernel", st); LLMC_KERNEL_GGL(match_bf16_kernel, grid, dim3(MatchCfg::THREADS), 0, st, (const uint16_t*)D.d_fp,
-                         bank->d_binv_eff, N, K, (const uint16_t*)d_fp, B, per, partial); }
-      LLMC_LAUNCH_CHECK("match_bf16_kernel");
-    }
-  } else {
-    { ProfScope ps_("match_f32_kernel", st); LLMC_KERNEL_GGL(match_f32_kernel, dim3(B), dim3(256), (size_t)K * sizeof(float) + 256 * sizeof(Top2), st,
-                       (const float*)D.d_fp, bank->d_binv_eff, N, K, (const float*)d_fp, partial); }
-    LLMC_LAUNCH_CHECK("match_f32_kernel");
-  }
-  *ns_out = ns;
-  return LLMC_OK;
-}
-
-// match + threshold + compaction for a small batch (B <= 64): the bulk pass, then ONE launch that decides exactly
-// and compacts (the work of match_finalize_kernel and compact_kernel)
-llmc_status_t launch_match_decide(llmc_bank* bank, const void* d_fp, const float* d_inv, int B, float tau, int32_t* d_idx,
-                                  float* d_sim, uint8_t* d_hit, void* ws, int32_t* d_hit_rows, int32_t* d_miss_rows,
-                                  int32_t* d_reval_tmp, int32_t* d_counters, uint32_t flags, uint64_t tick,
-                                  uint8_t* d_pooled_valid_out, int has_pool, int32_t* d_ref_out, hipStream_t st) {
-  const llmc_bank_desc_t& D = bank->desc;
-  int ns = 1;
-  LLMC_TRY(launch_match_bulk(bank, d_fp, B, ws, &ns, st));
-  const int touch = (flags & LLMC_UPDATE_LRU) ? 1 : 0;
-  const int reval_every = (flags & LLMC_REVALIDATE) ? D.reval_every : 0;
-  ProfScope ps_("match_decide_kernel", st);
-  if (D.dtype == LLMC_BF16)
-    LLMC_KERNEL_GGL((match_decide_kernel<bf16_t>), dim3(1), dim3(1024), 0, st, (const Top2*)ws, ns, (const bf16_t*)D.d_fp,
-                       D.d_inv_norm, D.d_valid, D.n_slots, D.k, (const bf16_t*)d_fp, d_inv, B, tau, d_idx, d_sim, d_hit,
-                       d_hit_rows, d_miss_rows, d_counters, D.d_last_used, D.d_hits, touch, tick, reval_every, d_reval_tmp,
-                       d_pooled_valid_out, has_pool, d_ref_out, D.d_act_slot);
-  else
-    LLMC_KERNEL_GGL((match_decide_kernel<float>), dim3(1), dim3(1024), 0, st, (const Top2*)ws, 1, (const float*)D.d_fp,
-                       D.d_inv_norm, D.d_valid, D.n_slots, D.k, (const float*)d_fp, d_inv, B, tau, d_idx, d_sim, d_hit,
-                       d_hit_rows, d_miss_rows, d_counters, D.d_last_used, D.d_hits, touch, tick, reval_every, d_reval_tmp,
-                       d_pooled_valid_out, has_pool, d_ref_out, D.d_act_slot);
-  LLMC_LAUNCH_CHECK("match_decide_kernel");
   return LLMC_OK;
 }
 

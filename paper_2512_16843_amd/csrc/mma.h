@@ -126,10 +126,13 @@ __device__ __forceinline__ void mma_block(const uint16_t* const (&a_ptr)[C::NLOA
 // being multiplied.  No registers are spent on staging.
 //
 // One load instruction of a wavefront fills 8 tile rows of 128 bytes: lane i writes the
-// 16-byte slot i of that 1 KiB block.  To keep the later 16-byte fragment reads free of
-// bank conflicts the 16-byte chunks of a row are stored XOR-swizzled: chunk c of tile row
-// r lives in slot c ^ (r % 8) of its row.  The permutation is applied on the global side
-// (each lane chooses which chunk it fetches).
+// 16-byte slot i of that 1 KiB block.  A 16-byte fragment read is served 16 lanes at a time
+// (16 x 16 bytes = one pass over the 64 banks), and those 16 lanes read one logical chunk
+// of 16 consecutive tile rows; two 128-byte rows span the banks once, so rows of equal
+// parity must spread over the 8 slots of a row.  The chunks of a row are therefore stored
+// XOR-swizzled by half the row number: chunk c of tile row r lives in slot c ^ ((r / 2) % 8)
+// of its row.  The permutation is applied on the global side (each lane chooses which
+// chunk it fetches).
 //
 // The compiler does not order these loads against LDS reads, so ordering is explicit:
 // s_waitcnt vmcnt(n) for the wave's own loads, then a workgroup barrier.
@@ -161,7 +164,7 @@ struct DmaCfg {
   static_assert(STAGES >= 2 && STAGES <= 4 && 3 * L <= 63, "pipeline depth");
   // tile row and k-chunk fetched by `lane` of `wave` in its j-th load of a stage
   __device__ static __forceinline__ int load_row(int j, int wave, int lane) { return (j * NW + wave) * 8 + (lane >> 3); }
-  __device__ static __forceinline__ int load_chunk(int row, int lane) { return (lane & 7) ^ (row & 7); }
+  __device__ static __forceinline__ int load_chunk(int row, int lane) { return (lane & 7) ^ ((row >> 1) & 7); }
 };
 
 // a_ptr[j] / b_ptr[j]: global address (k = 0) of the 16-byte chunk that this lane fetches in
@@ -191,12 +194,12 @@ __device__ __forceinline__ void mma_block_dma(const uint16_t* const (&a_ptr)[C::
   for (int s = 0; s < C::STAGES - 1; ++s)
     if (s < nk) issue(s);
 
-  // fragment read offsets (elements): row * 64 + ((chunk ^ (row & 7)) * 8), row & 7 == lane & 7
+  // fragment read offsets (elements): row * 64 + ((chunk ^ ((row / 2) & 7)) * 8), (row / 2) & 7 == (lane / 2) & 7
   const int a_row = (wm * (C::BM / C::WM) + (lane & 31)) * C::BK;
   const int b_row = C::BM * C::BK + (wn * (C::BN / C::WN) + (lane & 31)) * C::BK;
   int sw[4];
 #pragma unroll
-  for (int ks = 0; ks < 4; ++ks) sw[ks] = (((ks * 2 + (lane >> 5)) ^ (lane & 7)) * 8);
+  for (int ks = 0; ks < 4; ++ks) sw[ks] = (((ks * 2 + (lane >> 5)) ^ ((lane >> 1) & 7)) * 8);
 
   for (int kt = 0; kt < nk; ++kt) {
     const int ahead = min(C::STAGES - 2, nk - 1 - kt);

@@ -22,7 +22,7 @@ F32, BF16 = 0, 1
 EVICT_NONE, EVICT_LRU, EVICT_DECAYED_HITS = 0, 1, 2
 INSERT_ON_MISS, UPDATE_LRU, REVALIDATE, HINT_MOSTLY_CARRIED, DEFER_COPY = 1, 2, 4, 8, 16
 CNT_HIT, CNT_MISS, CNT_NEAR_TAU, CNT_NEAR_TIE, CNT_INSERTED, CNT_EVICTED, CNT_DROPPED = 0, 1, 2, 3, 4, 5, 6
-CNT_COMPUTED, CNT_REVALIDATED, CNT_DIVERGED, CNT_WORDS = 7, 8, 9, 12
+CNT_COMPUTED, CNT_REVALIDATED, CNT_DIVERGED, CNT_TIE_OVERFLOW, CNT_WORDS = 7, 8, 9, 10, 12
 MAX_UPDATE_ROWS = 4096
 
 EXPORTS = [
@@ -34,7 +34,7 @@ EXPORTS = [
     "llmc_match_bits_workspace_bytes", "llmc_max_hamming", "llmc_bank_pool_values",
     "llmc_lsh_index_bytes", "llmc_lsh_build", "llmc_match_bits_lsh", "llmc_materialize", "llmc_match_noalloc",
 ]
-MATCH_STATIC_SCRATCH_BYTES = 4 << 20
+MATCH_STATIC_SCRATCH_BYTES = 5 << 20
 
 
 class BankDesc(C.Structure):

@@ -382,17 +382,24 @@ def test_match_stress_full_size(L, made):
     assert idx_h.min() >= 0 and idx_h.max() < N
     assert np.array_equal(idx_h[inside] // 256, qc[inside])
     assert hit_h[inside].all() and not hit_h[~inside].any()
-    say("  hit rate %.3f, near-tie rows %d" % (hit_h.mean(), int(tie.sum())))
+    tie_h = tie.cpu().numpy()
+    say("  hit rate %.3f, rows with two groups compared exactly %d, rows with three or more groups within 1e-5 "
+        "(flagged, decided among two) %d" % (hit_h.mean(), int((tie_h == 1).sum()), int((tie_h == 2).sum())))
     # oracle on sampled queries, one at a time
     bank_np = npf(bank.fp)
     binv_np = npf(bank.inv_norm)
     valid_np = np.ones(N, np.uint8)
-    sample = list(range(0, B, 128))[:24] + [B - 1]
+    sample = list(range(0, B, 128))[:24] + [B - 1] + np.nonzero(tie_h == 2)[0][:8].tolist()
     qs, qis = npf(q[sample]), npf(qinv[sample])
     oidx, osim = O.match(qs, qis, bank_np, binv_np, valid_np)
     ties = O.near_tie_sets(qs, qis, bank_np, binv_np, valid_np)
+    wide = O.near_tie_sets(qs, qis, bank_np, binv_np, valid_np, gap=2e-5)
     n_multi = 0
     for i, b in enumerate(sample):
+        if tie_h[b] == 2:                       # flagged: within the margin of the maximum, reported
+            n_multi += 1
+            assert idx_h[b] in wide[i] and abs(sim_h[b] - osim[i]) < 2e-5
+            continue
         if len(ties[i]) > 1:
             n_multi += 1
             assert idx_h[b] in ties[i]

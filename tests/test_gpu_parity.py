@@ -165,7 +165,7 @@ def run_match(L, bank, q, qinv, tau):
     ws = torch.empty((L.llmc_match_workspace_bytes(bank, B),), dtype=torch.uint8, device="cuda")
     L.llmc_match(bank, q, qinv, tau, idx, sim, hit, tie, ws)
     torch.cuda.synchronize()
-    return idx.cpu().numpy(), npf(sim), hit.cpu().numpy().astype(bool), tie.cpu().numpy().astype(bool)
+    return idx.cpu().numpy(), npf(sim), hit.cpu().numpy().astype(bool), tie.cpu().numpy()
 
 
 def check_match(L, bank, q, tau, dtype):
@@ -206,6 +206,57 @@ def test_match_bf16_random_bank_with_holes(L, N, B, k):
     q = torch.from_numpy(qn.astype(np.float32)).to(torch.bfloat16).cuda()
     r = check_match(L, bank, q, 0.9, "bf16")
     assert np.all(valid.numpy()[r["idx"]] == 1)
+    bank.close()
+
+
+@pytest.mark.parametrize("dtype,N,B,k", [("bf16", 5000, 40, 64), ("bf16", 5000, 300, 256), ("bf16", 3000, 9, 96),
+                                          ("f32", 2000, 7, 64)])
+def test_match_many_near_identical_keys_in_different_blocks(L, dtype, N, B, k):
+    """Five keys that differ from one another by a few units in the last place of a few elements (cosines within
+    about 1e-6 of each other: beyond what the fp32 bulk pass can order), spread over different 32-row blocks of the
+    bank, plus exact duplicates.  Two kept candidate groups cannot always decide such a query: the row must be
+    FLAGGED (near-tie flag 2), its slot must be one the oracle sees within 2e-5 of its maximum, and its similarity
+    within 2e-5 of the oracle's; every other row is exact."""
+    say(f"match {dtype} N={N} B={B} k={k}: five near-identical keys in different blocks")
+    g = np.random.Generator(np.random.PCG64(N + k))
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    keys = torch.from_numpy(unit_rows(g, N, k).astype(np.float32)).to(tdt)
+    base = keys[11].clone()
+    spots = [7, 100, 1033, 2 * N // 3, N - 3]
+    step = 2.0 ** -7 if dtype == "bf16" else 2.0 ** -8         # cosines between variants differ by about 1e-6
+    variants = []
+    for v, j in enumerate(spots):
+        x = base.float().clone()
+        for e in range(3):
+            i = (5 * v + 11 * e) % k
+            x[i] = x[i] * (1.0 + step * (1 + (v + e) % 2))
+        keys[j] = x.to(tdt)
+        variants.append(keys[j].clone())
+    keys[300] = keys[1033]                                    # exact duplicates
+    keys[1032] = keys[spots[3]]
+    valid = torch.ones(N, dtype=torch.uint8)
+    valid[100] = 0                                            # one of the five is a free slot
+    bank = make_bank(L, keys.cuda(), valid, dtype=tdt)
+    qn = unit_rows(g, B, k).astype(np.float32)
+    q = torch.from_numpy(qn).to(tdt)
+    for b, v in enumerate([0, 2, 3, 4, 1]):                   # the first five queries are the variants themselves
+        q[b] = variants[v]
+    q = q.cuda()
+    qinv = torch.empty((B,), dtype=torch.float32, device="cuda")
+    L.llmc_inv_norm(q, qinv)
+    idx, sim, hit, tie = run_match(L, bank, q, qinv, 0.9)
+    ob = oracle_bank_from_gpu(bank, dtype)
+    oidx, osim = O.match(npf(q), npf(qinv), ob.fp, ob.inv_norm, ob.valid)
+    wide = O.near_tie_sets(npf(q), npf(qinv), ob.fp, ob.inv_norm, ob.valid, gap=2e-5)
+    assert np.all(tie[:5] == 2), tie[:8]
+    assert np.all(tie[5:] < 2)
+    for b in range(B):
+        if tie[b] == 2:
+            assert idx[b] in wide[b] and abs(sim[b] - osim[b]) < 2e-5
+            assert len(wide[b]) >= 5
+        else:
+            assert idx[b] == oidx[b] and abs(sim[b] - osim[b]) < 1e-5
+    assert np.all(hit[:5])
     bank.close()
 
 
@@ -1459,3 +1510,45 @@ def test_single_fingerprint_mode_against_oracle(L, dtype):
         say(f"  batch {tick} (tau {tau}): hits per layer {[int(x.hit.sum()) for x in st.gate]}")
     assert sum(int(x.hit.sum()) for x in st.gate) > 0
     st.close()
+
+
+def test_large_batch_equals_its_halves(L):
+    """Batches of more than 64 rows take the stand-alone decision and compaction kernels, smaller ones the fused
+    kernel: a batch of 96 rows and the same rows as two batches of 48 must give the same bits row by row."""
+    from paper_2512_16843_amd.engine import GatedStack
+    say("gated stack: 96 rows at once against two batches of 48")
+    cfg = W.scaled(W.BERT_BASE, n_layers=2, B=96, S=40, n_bank=160)
+    ws = W.make_layer_weights(cfg, seed=0)
+    tok, pos = W.make_embeddings(cfg, seed=0)
+    Ps = W.make_projection(cfg.d, cfg.k, cfg.torch_dtype, seed=3, n_layers=cfg.n_layers)
+    src = W.make_sources(cfg, 160, seed=1)
+    fresh = W.make_sources(cfg, 48, seed=9)
+    ids = np.concatenate([src[::4][:40], fresh[:30], src[1::7][:20], fresh[30:36]])
+    assert ids.shape[0] == 96
+    big = GatedStack(cfg, ws, Ps, expose_keys=True)
+    half = GatedStack(W.scaled(cfg, B=48), ws, Ps, expose_keys=True)
+    wide = GatedStack(W.scaled(cfg, B=80), ws, Ps)
+    for s0 in range(0, 160, 80):                              # one set of banks, built by 80-row batches
+        h = W.embed(torch.from_numpy(src[s0:s0 + 80]), tok, pos, cfg.torch_dtype).cuda()
+        wide.forward(h, tau=2.0, flags=L.INSERT_ON_MISS, tick=1)
+    for st in (big, half):                                    # hand the built banks' arrays to the two stacks under test
+        for l in range(cfg.n_layers):
+            for name in ("fp", "inv_norm", "act", "last_used", "hits", "valid"):
+                getattr(st.banks[l], name).copy_(getattr(wide.banks[l], name))
+            st.banks[l].refresh()
+    h0 = W.embed(torch.from_numpy(ids), tok, pos, cfg.torch_dtype).cuda()
+    y_big = big.forward(h0, tau=0.9).clone()
+    g_big = [dict(idx=g.idx.clone(), sim=g.sim.clone(), hit=g.hit.clone(), key=g.fp_used.clone()) for g in big.gate]
+    torch.cuda.synchronize()
+    assert 0 < int(g_big[0]["hit"].sum()) < 96
+    for part in range(2):
+        rows = slice(48 * part, 48 * part + 48)
+        y = half.forward(h0[rows].contiguous(), tau=0.9).clone()
+        torch.cuda.synchronize()
+        assert torch.equal(y, y_big[rows])
+        for l in range(cfg.n_layers):
+            g = half.gate[l]
+            assert torch.equal(g.idx, g_big[l]["idx"][rows]) and torch.equal(g.sim, g_big[l]["sim"][rows])
+            assert torch.equal(g.hit, g_big[l]["hit"][rows]) and torch.equal(g.fp_used, g_big[l]["key"][rows])
+    for st in (big, half, wide):
+        st.close()
