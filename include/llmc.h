@@ -96,6 +96,19 @@ typedef enum { LLMC_EVICT_NONE = 0, LLMC_EVICT_LRU = 1, LLMC_EVICT_DECAYED_HITS 
                                   with LLMC_INSERT_ON_MISS and LLMC_REVALIDATE (the bank must not change while rows
                                   refer to it) and on banks with compressed values. */
 
+#define LLMC_DEDUP 32u         /* within-batch reuse: Algorithm 1 handles inputs one after the other and stores each miss
+                                  before the next input is looked up, so an input can hit what an earlier one has just
+                                  stored.  With this flag the rows of a batch that miss the bank get that behaviour among
+                                  themselves: taken in ascending order, a row is a LEADER unless its key is more similar
+                                  than tau to the key of an earlier leader; otherwise it FOLLOWS the most similar earlier
+                                  leader (the earliest among equals): it is not computed, returns the leader's output as
+                                  stored, is reported as a hit on the leader's new entry (d_idx = that slot, d_sim = the
+                                  similarity of the two keys; with LLMC_UPDATE_LRU the entry's hit count grows) and is not
+                                  stored again.  Rows that hit the bank as it stood are untouched.  Needs
+                                  LLMC_INSERT_ON_MISS and a replacing policy; B <= LLMC_MAX_DEDUP_ROWS; refused with
+                                  LLMC_REVALIDATE, compressed values and sign-bit keys. */
+#define LLMC_MAX_DEDUP_ROWS 1024
+
 /* Largest tick accepted (recency keys are packed into 32 bits on the device). */
 #define LLMC_MAX_TICK 0x7FFFFFFEull
 /* Largest number of rows one insert/evict call may place. */
@@ -115,6 +128,7 @@ enum {
   LLMC_CNT_DIVERGED = 9,    /* of those, entries whose cached value was replaced */
   LLMC_CNT_TIE_OVERFLOW = 10, /* rows with three or more candidate groups within 1e-5 of the best: decided among the two
                                  best groups, so the slot is within that margin of the arg-max but possibly not it */
+  LLMC_CNT_DEDUP = 11,      /* LLMC_DEDUP: rows that followed an earlier row of the batch (they are counted as hits too) */
   LLMC_CNT_WORDS = 12
 };
 
@@ -458,7 +472,7 @@ llmc_status_t llmc_materialize(const llmc_bank_t* bank, const int32_t* d_ref, in
  *   d_fp_given / d_inv_norm_given: NULL, or keys [B, k] + norms to use instead of
  *          fingerprinting d_h_in (Algorithm 1 taken literally: one fingerprint of X for all layers)
  *   tau: threshold; flags: LLMC_INSERT_ON_MISS | LLMC_UPDATE_LRU | LLMC_REVALIDATE | LLMC_HINT_MOSTLY_CARRIED |
- *          LLMC_DEFER_COPY;
+ *          LLMC_DEFER_COPY | LLMC_DEDUP;
  *          tick <= LLMC_MAX_TICK
  *   out: optional per-row results and counters (NULL or any member NULL)
  *   d_workspace: at least llmc_layer_workspace_bytes(layer, B, S, k) bytes

@@ -651,7 +651,8 @@ def gated_layer(h_in: np.ndarray, bank: Optional[Bank], P: Optional[np.ndarray],
                 h_out[b] = bank.value(int(bank.act_slot[j]))      # the leader's output as stored
                 hit[b] = True
                 idx[b] = j
-                bank.touch([j], tick)
+                if flags & FLAG_UPDATE_LRU:
+                    bank.touch([j], tick)
     return GateResult(h_out, q, qinv, idx, sim, hit, slots, n_evicted, revalidated, divergence, refreshed, follower_of)
 
 

@@ -455,7 +455,7 @@ llmc_status_t llmc_profile_end(void) {
 size_t llmc_layer_workspace_bytes(const llmc_layer_desc_t* layer, int32_t B, int32_t S, int32_t k) {
   if (!layer || B <= 0 || S <= 0 || k < 0 || !dtype_ok(layer->dtype)) return 0;
   return fingerprint_ws_bytes(B, S, layer->d) + gate_small_bytes(B, k > 0 ? k : 32, layer->dtype) +
-         match_ws_max_bytes(B) + layer_ws_bytes(layer, B, S);
+         match_ws_max_bytes(B) + dedup_ws_bytes(B) + layer_ws_bytes(layer, B, S);
 }
 
 llmc_status_t llmc_layer_forward_gated(const llmc_layer_desc_t* layer, llmc_bank_t* bank, const llmc_fp_desc_t* fp,
@@ -472,7 +472,8 @@ llmc_status_t llmc_layer_forward_gated(const llmc_layer_desc_t* layer, llmc_bank
   REQUIRE((int64_t)B * S <= 0x7FFFFFFF / 4, LLMC_ERR_SHAPE, "B*S too large");
   REQUIRE(tau == tau, LLMC_ERR_INVALID_ARG, "tau is NaN");
   REQUIRE(tick <= LLMC_MAX_TICK, LLMC_ERR_INVALID_ARG, "tick out of range");
-  REQUIRE((flags & ~(LLMC_INSERT_ON_MISS | LLMC_UPDATE_LRU | LLMC_REVALIDATE | LLMC_HINT_MOSTLY_CARRIED | LLMC_DEFER_COPY)) == 0,
+  REQUIRE((flags & ~(LLMC_INSERT_ON_MISS | LLMC_UPDATE_LRU | LLMC_REVALIDATE | LLMC_HINT_MOSTLY_CARRIED | LLMC_DEFER_COPY |
+                     LLMC_DEDUP)) == 0,
           LLMC_ERR_INVALID_ARG,
           "unknown flag bits");
   int k = 0;
@@ -519,6 +520,14 @@ llmc_status_t llmc_layer_forward_gated(const llmc_layer_desc_t* layer, llmc_bank
       REQUIRE(D.n_act_slots == D.n_slots, LLMC_ERR_SHAPE,
               "the divergence monitor is refused on a bank whose keys share value rows");
     }
+    if (flags & LLMC_DEDUP) {
+      REQUIRE(flags & LLMC_INSERT_ON_MISS, LLMC_ERR_INVALID_ARG, "LLMC_DEDUP needs LLMC_INSERT_ON_MISS");
+      REQUIRE(!(flags & LLMC_REVALIDATE), LLMC_ERR_INVALID_ARG, "LLMC_DEDUP is refused with LLMC_REVALIDATE");
+      REQUIRE(B <= LLMC_MAX_DEDUP_ROWS, LLMC_ERR_SHAPE, "LLMC_DEDUP handles at most %d rows per call", LLMC_MAX_DEDUP_ROWS);
+      REQUIRE(D.policy != LLMC_EVICT_NONE, LLMC_ERR_INVALID_ARG, "LLMC_DEDUP needs a replacing policy");
+      REQUIRE(D.rank == 0 && !D.key_bits, LLMC_ERR_INVALID_ARG,
+              "LLMC_DEDUP is refused on banks with compressed values or sign-bit keys");
+    }
     if (flags & LLMC_INSERT_ON_MISS) {
       REQUIRE(B <= LLMC_MAX_UPDATE_ROWS, LLMC_ERR_SHAPE, "insertion handles at most %d rows per call",
               LLMC_MAX_UPDATE_ROWS);
@@ -547,6 +556,7 @@ llmc_status_t llmc_layer_forward_gated(const llmc_layer_desc_t* layer, llmc_bank
   uint8_t* tie = (uint8_t*)take((size_t)B);
   int32_t* counters = (int32_t*)take(LLMC_CNT_WORDS * 4);
   void* ws_match = take(match_ws_max_bytes(B));
+  void* ws_dedup = take(dedup_ws_bytes(B));
   void* ws_layer = (void*)p;
   if (out) {
     if (out->d_idx) idx = out->d_idx;
@@ -620,6 +630,8 @@ llmc_status_t llmc_layer_forward_gated(const llmc_layer_desc_t* layer, llmc_bank
                                 const_cast<void*>(d_h_in), st));
   if (!(flags & LLMC_DEFER_COPY))
     LLMC_TRY(launch_gather(bank, idx, hit_rows, counters + LLMC_CNT_HIT, B, d_h_out, st, pooled_out, key_out, key_inv_out));
+  // within-batch reuse: the rows to compute shrink to the leaders (after the gather, which reads the hit count)
+  if (flags & LLMC_DEDUP) LLMC_TRY(launch_dedup_resolve(q, qinv, k, layer->dtype, B, tau, miss_rows, counters, ws_dedup, st));
   // the rows to compute: the misses, then (divergence monitor) the sampled hit rows, whose copies are overwritten
   LLMC_TRY(launch_layer(layer, d_h_in, d_h_out, B, S, miss_rows, counters + LLMC_CNT_COMPUTED, ws_layer, st));
   if ((flags & LLMC_REVALIDATE) && bank->desc.reval_every > 0)
@@ -627,6 +639,8 @@ llmc_status_t llmc_layer_forward_gated(const llmc_layer_desc_t* layer, llmc_bank
   if (flags & LLMC_INSERT_ON_MISS)
     LLMC_TRY(launch_bank_insert(bank, q, qinv, d_h_out, miss_rows, counters + LLMC_CNT_MISS, B, tick, slots, counters,
                                 st));
+  if (flags & LLMC_DEDUP)
+    LLMC_TRY(launch_dedup_finish(bank, d_h_out, B, slots, idx, sim, hit, counters, flags, ws_dedup, st));
   return LLMC_OK;
 }
 

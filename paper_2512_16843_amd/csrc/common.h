@@ -215,6 +215,14 @@ llmc_status_t launch_compact(const uint8_t* d_hit, const int32_t* d_idx, const f
                              int32_t* d_miss_rows, int32_t* d_reval_tmp, int32_t* d_counters, llmc_bank* bank,
                              uint32_t flags, uint64_t tick, hipStream_t st, uint8_t* d_pooled_valid_out = nullptr,
                              int has_pool = 0, int32_t* d_ref_out = nullptr);
+// within-batch reuse (LLMC_DEDUP): scratch size, the decision among the rows to compute (before the dense block),
+// and the copies / bookkeeping of the followers (after the insertion)
+size_t dedup_ws_bytes(int B);
+llmc_status_t launch_dedup_resolve(const void* d_keys, const float* d_inv, int k, int dtype, int B, float tau,
+                                   int32_t* d_miss_rows, int32_t* d_counters, void* ws, hipStream_t st);
+llmc_status_t launch_dedup_finish(llmc_bank* bank, void* d_h_out, int B, const int32_t* d_slots, int32_t* d_idx,
+                                  float* d_sim, uint8_t* d_hit, int32_t* d_counters, uint32_t flags, void* ws,
+                                  hipStream_t st);
 llmc_status_t launch_materialize(const llmc_bank* bank, const int32_t* d_ref, const int32_t* d_rows, const int32_t* d_n,
                                  int n_max, void* d_h, hipStream_t st);
 llmc_status_t launch_divergence(llmc_bank* bank, const void* d_h_out, const int32_t* d_idx, const int32_t* d_rows,

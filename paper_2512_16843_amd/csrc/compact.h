@@ -84,7 +84,7 @@ __device__ __forceinline__ void compact_rows(const uint8_t* hit, const int32_t* 
     counters[LLMC_CNT_REVALIDATED] = n_reval;
     counters[LLMC_CNT_DIVERGED] = 0;
     counters[LLMC_CNT_TIE_OVERFLOW] = s_scanned;
-    counters[11] = 0;
+    counters[LLMC_CNT_DEDUP] = 0;
   }
 }
 

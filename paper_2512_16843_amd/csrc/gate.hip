@@ -227,6 +227,178 @@ llmc_status_t launch_gather(const llmc_bank* bank, const int32_t* d_idx, const i
   return LLMC_OK;
 }
 
+// ---- within-batch reuse (Algorithm 1 applied to the rows of a batch one after the other) ----------------------
+// The rows that missed the bank are listed in ascending order in miss_rows[0 .. m).  Three steps:
+//   pairs:   S[i][j] = cosine of the stored keys of listed rows i and j (j < i), fp64, one thread per pair;
+//   resolve: one wavefront walks i = 0 .. m - 1: row i FOLLOWS the most similar earlier LEADER with S > tau (the
+//            earliest among equals), else it is a leader itself; the list of rows to compute is rewritten in place to
+//            the leaders, and the counters follow (MISS = COMPUTED = leaders, HIT += followers, DEDUP = followers);
+//   finish:  after the dense block and the insertion, every follower copies its leader's output row and is reported
+//            as a hit on the slot the leader was stored in.
+// Scratch layout (dedup_ws_bytes): S [B * B] fp64 | src_row [B] | fol_rows [B] | fol_rank [B] | fol_sim [B] | n_fol.
+struct DedupWs {
+  double* S;
+  int32_t *src_row, *fol_rows, *fol_rank;
+  float* fol_sim;
+  int32_t* n_fol;
+};
+static DedupWs dedup_ws(void* ws, int B) {
+  char* p = (char*)ws;
+  DedupWs w;
+  w.S = (double*)p;         p += align_up((size_t)B * B * sizeof(double), 256);
+  w.src_row = (int32_t*)p;  p += align_up((size_t)B * 4, 256);
+  w.fol_rows = (int32_t*)p; p += align_up((size_t)B * 4, 256);
+  w.fol_rank = (int32_t*)p; p += align_up((size_t)B * 4, 256);
+  w.fol_sim = (float*)p;    p += align_up((size_t)B * 4, 256);
+  w.n_fol = (int32_t*)p;
+  return w;
+}
+size_t dedup_ws_bytes(int B) {
+  if (B > LLMC_MAX_DEDUP_ROWS) return 0;
+  return align_up((size_t)B * B * sizeof(double), 256) + 4 * align_up((size_t)B * 4, 256) + 256;
+}
+
+// grid (ceil(m_max / 256), m_max): block y is listed row i, thread x is listed row j < i
+template <typename T>
+__global__ __launch_bounds__(256) void dedup_pairs_kernel(const T* __restrict__ keys, const float* __restrict__ inv,
+                                                          int k, const int32_t* __restrict__ rows,
+                                                          const int32_t* __restrict__ counters, int m_max,
+                                                          double* __restrict__ S) {
+  constexpr int VEC = Vec16<T>::N;
+  const int m = min(counters[LLMC_CNT_MISS], m_max);
+  const int i = blockIdx.y, j = blockIdx.x * 256 + threadIdx.x;
+  if (i >= m || j >= i) return;
+  const int bi = rows[i], bj = rows[j];
+  const T* a = keys + (size_t)bi * k;
+  const T* b = keys + (size_t)bj * k;
+  double acc = 0.0;
+  for (int e = 0; e < k; e += VEC) {
+    float x[VEC], y[VEC];
+    Vec16<T>::load(a + e, x);
+    Vec16<T>::load(b + e, y);
+#pragma unroll
+    for (int u = 0; u < VEC; ++u) acc += (double)x[u] * (double)y[u];
+  }
+  S[(size_t)i * m_max + j] = acc * (double)inv[bi] * (double)inv[bj];
+}
+
+// one wavefront; see above
+__global__ __launch_bounds__(64) void dedup_resolve_kernel(const double* __restrict__ S, int m_max, float tau,
+                                                           int32_t* miss_rows, int32_t* counters,
+                                                           int32_t* __restrict__ src_row, int32_t* __restrict__ fol_rows,
+                                                           int32_t* __restrict__ fol_rank, float* __restrict__ fol_sim,
+                                                           int32_t* __restrict__ n_fol_out) {
+  __shared__ int16_t lead_pos[LLMC_MAX_DEDUP_ROWS];     // position among the leaders, -1 for a follower
+  const int lane = threadIdx.x;
+  const int m = min(counters[LLMC_CNT_MISS], m_max);
+  int n_lead = 0, n_fol = 0;
+  for (int i = 0; i < m; ++i) {
+    double best = -INFINITY;
+    int best_j = -1;
+    for (int j = lane; j < i; j += 64) {
+      const double s = S[(size_t)i * m_max + j];
+      if (lead_pos[j] >= 0 && s > (double)tau && (s > best)) { best = s; best_j = j; }     // ascending j: earliest among equals
+    }
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const double os = __shfl_xor(best, o, 64);
+      const int oj = __shfl_xor(best_j, o, 64);
+      if (oj >= 0 && (best_j < 0 || os > best || (os == best && oj < best_j))) { best = os; best_j = oj; }
+    }
+    const int row = miss_rows[i];                       // read before the slot may be overwritten below
+    if (best_j < 0) {
+      if (lane == 0) { lead_pos[i] = (int16_t)n_lead; miss_rows[n_lead] = row; }      // n_lead <= i: in place
+      ++n_lead;
+    } else {
+      if (lane == 0) {
+        lead_pos[i] = -1;
+        fol_rows[n_fol] = row;
+        fol_rank[n_fol] = lead_pos[best_j];
+        fol_sim[n_fol] = (float)best;
+        src_row[row] = miss_rows[lead_pos[best_j]];     // leaders already sit at their final positions
+      }
+      ++n_fol;
+    }
+    __builtin_amdgcn_s_waitcnt(0);                      // this wavefront's LDS and memory writes land before the next row reads them
+    __builtin_amdgcn_wave_barrier();
+  }
+  if (lane == 0) {
+    *n_fol_out = n_fol;
+    counters[LLMC_CNT_MISS] = n_lead;
+    counters[LLMC_CNT_COMPUTED] = n_lead;
+    counters[LLMC_CNT_HIT] += n_fol;
+    counters[LLMC_CNT_DEDUP] = n_fol;
+  }
+}
+
+// grid (chunks, B): entry i < n_fol copies the output row of follower i's leader and records the hit
+__global__ __launch_bounds__(kGatherThreads) void dedup_finish_kernel(
+    u32x4_t* __restrict__ h_out, size_t vec_per_seq, const int32_t* __restrict__ n_fol, int n_max,
+    const int32_t* __restrict__ src_row, const int32_t* __restrict__ fol_rows, const int32_t* __restrict__ fol_rank,
+    const float* __restrict__ fol_sim, const int32_t* __restrict__ slots, int32_t* __restrict__ idx,
+    float* __restrict__ sim, uint8_t* __restrict__ hit, uint32_t* hits, int touch) {
+  const int n = min(*n_fol, n_max);
+  const int i = blockIdx.y;
+  if (i >= n) return;
+  const int b = fol_rows[i];
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    const int slot = slots[fol_rank[i]];
+    idx[b] = slot;
+    if (sim) sim[b] = fol_sim[i];
+    if (hit) hit[b] = 1;
+    if (touch && slot >= 0) atomicAdd(&hits[slot], 1u);
+  }
+  const u32x4_t* src = h_out + (size_t)src_row[b] * vec_per_seq;
+  u32x4_t* dst = h_out + (size_t)b * vec_per_seq;
+  const size_t v0 = (size_t)blockIdx.x * (kGatherThreads * kGatherVecPerThread) + threadIdx.x;
+  u32x4_t r[kGatherVecPerThread];
+#pragma unroll
+  for (int u = 0; u < kGatherVecPerThread; ++u) {
+    const size_t v = v0 + (size_t)u * kGatherThreads;
+    if (v < vec_per_seq) r[u] = src[v];
+  }
+#pragma unroll
+  for (int u = 0; u < kGatherVecPerThread; ++u) {
+    const size_t v = v0 + (size_t)u * kGatherThreads;
+    if (v < vec_per_seq) __builtin_nontemporal_store(r[u], dst + v);
+  }
+}
+
+llmc_status_t launch_dedup_resolve(const void* d_keys, const float* d_inv, int k, int dtype, int B, float tau,
+                                   int32_t* d_miss_rows, int32_t* d_counters, void* ws, hipStream_t st) {
+  const DedupWs w = dedup_ws(ws, B);
+  dim3 grid((B + 255) / 256, B);
+  { ProfScope ps_("dedup_pairs_kernel", st);
+    if (dtype == LLMC_F32)
+      LLMC_KERNEL_GGL(dedup_pairs_kernel<float>, grid, dim3(256), 0, st, (const float*)d_keys, d_inv, k, d_miss_rows,
+                      d_counters, B, w.S);
+    else
+      LLMC_KERNEL_GGL(dedup_pairs_kernel<bf16_t>, grid, dim3(256), 0, st, (const bf16_t*)d_keys, d_inv, k, d_miss_rows,
+                      d_counters, B, w.S); }
+  LLMC_LAUNCH_CHECK("dedup_pairs_kernel");
+  { ProfScope ps_("dedup_resolve_kernel", st);
+    LLMC_KERNEL_GGL(dedup_resolve_kernel, dim3(1), dim3(64), 0, st, w.S, B, tau, d_miss_rows, d_counters, w.src_row,
+                    w.fol_rows, w.fol_rank, w.fol_sim, w.n_fol); }
+  LLMC_LAUNCH_CHECK("dedup_resolve_kernel");
+  return LLMC_OK;
+}
+
+llmc_status_t launch_dedup_finish(llmc_bank* bank, void* d_h_out, int B, const int32_t* d_slots, int32_t* d_idx,
+                                  float* d_sim, uint8_t* d_hit, int32_t* d_counters, uint32_t flags, void* ws,
+                                  hipStream_t st) {
+  const llmc_bank_desc_t& D = bank->desc;
+  const DedupWs w = dedup_ws(ws, B);
+  const size_t vec_per_seq = (size_t)D.S * D.d * elem_size(D.dtype) / 16;
+  const size_t per_wg = (size_t)kGatherThreads * kGatherVecPerThread;
+  dim3 grid((unsigned)((vec_per_seq + per_wg - 1) / per_wg), B);
+  { ProfScope ps_("dedup_finish_kernel", st);
+    LLMC_KERNEL_GGL(dedup_finish_kernel, grid, dim3(kGatherThreads), 0, st, (u32x4_t*)d_h_out, vec_per_seq, w.n_fol, B,
+                    w.src_row, w.fol_rows, w.fol_rank, w.fol_sim, d_slots, d_idx, d_sim, d_hit, D.d_hits,
+                    (flags & LLMC_UPDATE_LRU) ? 1 : 0); }
+  LLMC_LAUNCH_CHECK("dedup_finish_kernel");
+  return LLMC_OK;
+}
+
 // copy of referenced value rows: out[rows[i] or i] = act[ref[...]] for the listed rows whose reference is >= 0
 llmc_status_t launch_materialize(const llmc_bank* bank, const int32_t* d_ref, const int32_t* d_rows, const int32_t* d_n,
                                  int n_max, void* d_h, hipStream_t st) {

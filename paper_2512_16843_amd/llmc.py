@@ -20,9 +20,9 @@ LLMC_OK = 0
 ERR_INVALID_ARG, ERR_SHAPE, ERR_DTYPE, ERR_BANK_FULL, ERR_WORKSPACE, ERR_HIP = 1, 2, 3, 4, 5, 6
 F32, BF16 = 0, 1
 EVICT_NONE, EVICT_LRU, EVICT_DECAYED_HITS = 0, 1, 2
-INSERT_ON_MISS, UPDATE_LRU, REVALIDATE, HINT_MOSTLY_CARRIED, DEFER_COPY = 1, 2, 4, 8, 16
+INSERT_ON_MISS, UPDATE_LRU, REVALIDATE, HINT_MOSTLY_CARRIED, DEFER_COPY, DEDUP = 1, 2, 4, 8, 16, 32
 CNT_HIT, CNT_MISS, CNT_NEAR_TAU, CNT_NEAR_TIE, CNT_INSERTED, CNT_EVICTED, CNT_DROPPED = 0, 1, 2, 3, 4, 5, 6
-CNT_COMPUTED, CNT_REVALIDATED, CNT_DIVERGED, CNT_TIE_OVERFLOW, CNT_WORDS = 7, 8, 9, 10, 12
+CNT_COMPUTED, CNT_REVALIDATED, CNT_DIVERGED, CNT_TIE_OVERFLOW, CNT_DEDUP, CNT_WORDS = 7, 8, 9, 10, 11, 12
 MAX_UPDATE_ROWS = 4096
 
 EXPORTS = [

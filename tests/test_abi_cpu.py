@@ -107,7 +107,7 @@ def test_gated_layer_validation(lib):
     assert call(layer(d_w1=None)) == llmc.ERR_INVALID_ARG
     assert call(layer(), h_out=p) == llmc.ERR_INVALID_ARG        # in-place is refused
     assert call(layer(), tau=float("nan")) == llmc.ERR_INVALID_ARG
-    assert call(layer(), flags=32) == llmc.ERR_INVALID_ARG
+    assert call(layer(), flags=64) == llmc.ERR_INVALID_ARG        # unknown flag bit
     assert call(layer(), tick=1 << 40) == llmc.ERR_INVALID_ARG
     assert call(layer(), B=0) == llmc.ERR_INVALID_ARG
     assert call(layer(), ws_bytes=16) == llmc.ERR_WORKSPACE

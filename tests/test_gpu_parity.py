@@ -1552,3 +1552,74 @@ def test_large_batch_equals_its_halves(L):
             assert torch.equal(g.hit, g_big[l]["hit"][rows]) and torch.equal(g.fp_used, g_big[l]["key"][rows])
     for st in (big, half, wide):
         st.close()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_within_batch_reuse_against_oracle(L, dtype):
+    """LLMC_DEDUP: rows of a batch that miss the bank follow an earlier, similar row of the same batch instead of
+    being computed and stored again (Algorithm 1 applied to the rows in order).  Leaders, followers, slots, counters,
+    bank metadata and outputs against the oracle, layer by layer with the GPU's own layer inputs, keys and bank
+    arrays, over batches that fill the banks and then evict."""
+    from paper_2512_16843_amd.engine import GatedStack
+    say(f"within-batch reuse {dtype}: duplicates and near-duplicates inside batches, insertion + LRU, eviction")
+    cfg = W.scaled(W.TINY_ENCODER, n_layers=2, B=8, n_bank=12) if dtype == "f32" else \
+        W.scaled(W.BERT_BASE, n_layers=2, B=8, S=48, n_bank=12)
+    tol = TOL[dtype]
+    ws = W.make_layer_weights(cfg, seed=0)
+    tok, pos = W.make_embeddings(cfg, seed=0)
+    Ps = W.make_projection(cfg.d, cfg.k, cfg.torch_dtype, seed=3, n_layers=cfg.n_layers)
+    st = GatedStack(cfg, ws, Ps, expose_keys=True)
+    wnp = [{k_: npf(v) for k_, v in w.items()} for w in ws]
+    src = W.make_sources(cfg, 16, seed=1)
+    near, _ = W.make_substitution_queries(W.scaled(cfg, B=4), src[:4], n_dup=4, n_subst=1, seed=5)
+    fresh = W.make_sources(cfg, 12, seed=9)
+    tau = 0.97 if dtype == "f32" else 0.995
+    flags = L.INSERT_ON_MISS | L.UPDATE_LRU | L.DEDUP
+    oflags = O.FLAG_INSERT_ON_MISS | O.FLAG_UPDATE_LRU | O.FLAG_DEDUP
+    batches = [np.stack([src[0], src[0], fresh[0], near[0], fresh[1], fresh[0], src[5], src[5]]),
+               np.stack([src[0], fresh[2], fresh[2], src[5], near[1], near[1], fresh[0], fresh[3]]),
+               np.stack([fresh[4], fresh[5], fresh[4], fresh[6], fresh[7], fresh[5], fresh[8], fresh[4]])]      # evicts
+    total_followers = 0
+    for tick, ids in enumerate(batches, start=1):
+        h0 = W.embed(torch.from_numpy(ids), tok, pos, cfg.torch_dtype).cuda()
+        pre = [oracle_bank_from_gpu(b, dtype) for b in st.banks]
+        outs = st.forward(h0, tau=tau, flags=flags, tick=tick, keep_all=True)
+        torch.cuda.synchronize()
+        for l in range(cfg.n_layers):
+            h_prev = npf(h0 if l == 0 else outs[l - 1])
+            ob, g, bk = pre[l], st.gate[l], st.banks[l]
+            q_g, qinv_g = npf(g.fp_used), npf(g.inv_used)
+            q_o, _ = O.fingerprint(h_prev, npf(Ps[l]), None, dtype)
+            assert key_codes_close(q_g, q_o) if dtype == "bf16" else np.abs(q_g - q_o).max() < 1e-6
+            r = O.gated_layer(h_prev, ob, None, None, wnp[l], cfg.arch, cfg.n_heads, cfg.ln_eps, cfg.gelu, f32(tau),
+                              flags=oflags, tick=tick, out_dtype=dtype, fp_override=(q_g, qinv_g))
+            # no similarity (to the bank or between rows of the batch) sits within 1e-3 of the threshold here
+            pair = O.similarities(q_g, qinv_g, q_g, qinv_g)
+            assert not (np.abs(pair - f32(tau)) < 1e-3).any() and not (np.abs(r.sim - f32(tau)) < 1e-3).any()
+            hit = g.hit.cpu().numpy().astype(bool)
+            assert np.array_equal(hit, r.hit), (tick, l, hit, r.hit)
+            assert np.array_equal(g.idx.cpu().numpy()[hit], r.idx[hit]), (tick, l)
+            np.testing.assert_allclose(npf(g.sim)[hit], r.sim[hit], rtol=0, atol=1e-5)
+            cnt = g.counters.cpu().numpy()
+            n_fol, n_lead = len(r.follower_of), len(r.slots)
+            assert cnt[L.CNT_DEDUP] == n_fol and cnt[L.CNT_MISS] == n_lead and cnt[L.CNT_COMPUTED] == n_lead
+            assert cnt[L.CNT_HIT] == int(hit.sum()) and cnt[L.CNT_INSERTED] == n_lead and cnt[L.CNT_EVICTED] == r.n_evicted
+            assert g.slots.cpu().tolist()[:n_lead] == r.slots
+            assert np.array_equal(bk.valid.cpu().numpy(), ob.valid)
+            v = ob.valid.astype(bool)
+            assert np.array_equal(bk.last_used.cpu().numpy().astype(np.uint64)[v], ob.last_used[v])
+            assert np.array_equal(bk.hits.cpu().numpy().astype(np.uint32)[v], ob.hits[v])
+            got = npf(outs[l])
+            for b in range(cfg.B):
+                if b in r.follower_of:
+                    assert torch.equal(outs[l][b], outs[l][r.follower_of[b]])          # the leader's row, bit for bit
+                    assert torch.equal(outs[l][b], bk.act[int(r.idx[b])])
+                elif hit[b]:
+                    assert np.array_equal(got[b], npf(bk.act[int(r.idx[b])]))
+                else:
+                    assert rel_err_rows(got[b:b + 1], r.h_out[b:b + 1])[0] < tol, (tick, l, b)
+            total_followers += n_fol
+        say(f"  batch {tick}: hits per layer {[int(x.hit.sum()) for x in st.gate]}, "
+            f"followers per layer {[int(x.counters[L.CNT_DEDUP]) for x in st.gate]}")
+    assert total_followers >= 8
+    st.close()
