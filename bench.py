@@ -93,7 +93,8 @@ def kernel_work(cfg, name, miss, hit, e=2, carry=False, copied=None):
     if name == "materialize_kernel":
         return 0.0, 2.0 * float(copied[1] if copied else 0) * S * d * e, "hbm"
     if name == "pool_kernel":
-        rows = float(L * B) if not carry else float(B + sum(B - h for h in hit[:-1]))
+        # stored means carry the reused rows; a post-LayerNorm block pools the rows it computes on the way out
+        rows = float(L * B) if not carry else (float(B) if cfg.arch == 0 else float(B + sum(B - h for h in hit[:-1])))
         return rows * S * d, rows * S * d * e, "hbm"
     if name == "project_kernel":
         rows = float(L * B) if not carry else float(B + sum(B - h for h in hit[:-1]))      # carried keys are copied

@@ -225,9 +225,13 @@ typedef struct {
   const float* d_bias;
   int32_t k;
   /* Optional carry from the call that produced this layer's input (see llmc_gate_out_t.d_pooled_out): for a
-   * row b with d_pooled_in_valid[b] != 0, d_pooled_in[b] [d] fp32 is taken as the token mean of d_h_in[b] and the
+   * row b with d_pooled_in_valid[b] == 1, d_pooled_in[b] [d] fp32 is taken as the token mean of d_h_in[b] and the
    * row is not read again.  The carried mean is the one the library itself computes (same arithmetic, same
-   * order), so keys do not depend on whether a mean was carried.  Both NULL: every row is pooled here. */
+   * order), so keys do not depend on whether a mean was carried.  d_pooled_in_valid[b] == 2 says that the producing
+   * call computed row b and its last LayerNorm already left the row's pooled chunk sums in the fingerprint part of
+   * the workspace: the row is not read again either.  Flag 2 is only meaningful when this call is given the SAME
+   * workspace, with the same B, S and d, as the producing call, and nothing wrote to it in between; a caller that
+   * cannot promise that clears such flags to 0.  Both NULL: every row is pooled here. */
   const float* d_pooled_in;
   const uint8_t* d_pooled_in_valid;
   /* Optional, with d_pooled_in_valid: finished keys [B, k] + inverse norms [B] of the flagged rows (see
@@ -253,7 +257,9 @@ typedef struct {
   /* Reuse fused with the next layer's pooling: the cached output of a hit is the next layer's input, and its
    * token mean was stored with it (llmc_bank_desc_t.d_act_pool).  With a bank that has d_act_pool, and both
    * pointers given, the call writes d_pooled_out[b] [d] fp32 = that stored mean and d_pooled_out_valid[b] = 1 for
-   * every row answered from the bank (0 for computed rows, whose mean the next call computes itself). */
+   * every row answered from the bank.  Computed rows get 0 (the next call pools them itself), or 2 when the block's
+   * last LayerNorm pooled them on the way out (post-LayerNorm blocks: the chunk sums stay in the workspace, see
+   * llmc_fp_desc_t.d_pooled_in_valid). */
   float* d_pooled_out;          /* [B, d] */
   uint8_t* d_pooled_out_valid;  /* [B] */
   /* With a bank that keeps d_next_fp: the stored next-layer key and inverse norm of every row answered from the

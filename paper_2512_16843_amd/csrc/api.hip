@@ -570,7 +570,9 @@ llmc_status_t llmc_layer_forward_gated(const llmc_layer_desc_t* layer, llmc_bank
   if (!bank) {
     LLMC_TRY(launch_all_miss(B, miss_rows, counters, out ? out->d_idx : nullptr, out ? out->d_sim : nullptr,
                              out ? out->d_hit : nullptr, st, out ? out->d_pooled_out_valid : nullptr));
-    return launch_layer(layer, d_h_in, d_h_out, B, S, miss_rows, counters + LLMC_CNT_COMPUTED, ws_layer, st);
+    uint8_t* flags_out = out ? out->d_pooled_out_valid : nullptr;
+    return launch_layer(layer, d_h_in, d_h_out, B, S, miss_rows, counters + LLMC_CNT_COMPUTED, ws_layer, st,
+                        flags_out ? (float*)ws_fp : nullptr, flags_out);
   }
   if (flags & (LLMC_INSERT_ON_MISS | LLMC_UPDATE_LRU)) LLMC_TRY(launch_bank_advance(bank, tick, st));
   const void* q = d_fp_given;
@@ -588,7 +590,7 @@ llmc_status_t llmc_layer_forward_gated(const llmc_layer_desc_t* layer, llmc_bank
     // rows that are references to the producing layer's bank take their key from its stored next-layer keys
     const llmc_bank_desc_t& Pb = fp->prev_bank->desc;
     LLMC_TRY(launch_fingerprint(d_h_in, nullptr, B, S, layer->d, layer->dtype, fp->d_proj, fp->d_bias, k, keys, inv,
-                                ws_fp, st, nullptr, nullptr, Pb.d_next_fp, Pb.d_next_inv,
+                                ws_fp, st, nullptr, fp->d_pooled_in_valid, Pb.d_next_fp, Pb.d_next_inv,
                                 (flags & LLMC_HINT_MOSTLY_CARRIED) != 0, fp->d_ref_in));
     q = keys;
     qinv = inv;
@@ -633,7 +635,9 @@ llmc_status_t llmc_layer_forward_gated(const llmc_layer_desc_t* layer, llmc_bank
   // within-batch reuse: the rows to compute shrink to the leaders (after the gather, which reads the hit count)
   if (flags & LLMC_DEDUP) LLMC_TRY(launch_dedup_resolve(q, qinv, k, layer->dtype, B, tau, miss_rows, counters, ws_dedup, st));
   // the rows to compute: the misses, then (divergence monitor) the sampled hit rows, whose copies are overwritten
-  LLMC_TRY(launch_layer(layer, d_h_in, d_h_out, B, S, miss_rows, counters + LLMC_CNT_COMPUTED, ws_layer, st));
+  // (the last LayerNorm of a post-LayerNorm block also leaves the chunk sums of the computed rows for the next call)
+  LLMC_TRY(launch_layer(layer, d_h_in, d_h_out, B, S, miss_rows, counters + LLMC_CNT_COMPUTED, ws_layer, st,
+                        pooled_valid_out ? (float*)ws_fp : nullptr, pooled_valid_out));
   if ((flags & LLMC_REVALIDATE) && bank->desc.reval_every > 0)
     LLMC_TRY(launch_divergence(bank, d_h_out, idx, miss_rows, counters, B, st));
   if (flags & LLMC_INSERT_ON_MISS)

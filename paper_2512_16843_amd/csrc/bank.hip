@@ -248,8 +248,8 @@ llmc_status_t launch_bank_advance(llmc_bank* bank, uint64_t tick, hipStream_t st
 }
 
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
-constexpr int kCopyThreads = 256;
-constexpr int kCopyVecPerThread = 4;
+constexpr int kCopyThreads = 1024;          // the gather's launch shape, see gate.hip
+constexpr int kCopyVecPerThread = 6;
 
 // grid (chunks, m_max): entry i stores row r = rows[i] (or i) of fp / inv_norm / act into slots[i]
 __global__ __launch_bounds__(kCopyThreads) void insert_kernel(

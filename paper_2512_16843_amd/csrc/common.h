@@ -259,7 +259,10 @@ size_t layer_ws_bytes(const llmc_layer_desc_t* L, int B, int S);
 llmc_status_t launch_linear(const void* A, int lda, const int32_t* a_rows, const void* W, const void* bias, int N, int K,
                             void* out, int ldo, const int32_t* o_rows, int S, const int32_t* count, int max_seqs,
                             int dtype, hipStream_t st);
+// pool_partial / pooled_flags (both or neither): the block's last LayerNorm also leaves the chunk sums of its
+// outputs in the fingerprint's partials buffer and sets pooled_flags[row] = 2 (post-LayerNorm blocks whose rows fit)
 llmc_status_t launch_layer(const llmc_layer_desc_t* L, const void* d_h_in, void* d_h_out, int B, int S,
-                           const int32_t* d_rows, const int32_t* d_count, void* ws, hipStream_t st);
+                           const int32_t* d_rows, const int32_t* d_count, void* ws, hipStream_t st,
+                           float* pool_partial = nullptr, uint8_t* pooled_flags = nullptr);
 
 }  // namespace llmc

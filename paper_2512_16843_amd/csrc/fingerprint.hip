@@ -165,7 +165,10 @@ __global__ __launch_bounds__(1024) void project_kernel(const float* __restrict__
   // key_index: row b is a reference to entry key_index[b] of a bank (negative: not a reference), and key_in /
   // key_inv_in are that bank's stored keys; without it, carried keys sit at row b and pooled_valid flags them
   const int ksrc = key_index ? key_index[b] : b;
-  const bool given = !row_map && (key_index ? ksrc >= 0 : (pooled_valid && pooled_valid[b]));
+  // flags: 1 = the row's mean (or key) is supplied; 2 = the chunk sums of the row are already in `partial` (left there
+  // by the producing call's last LayerNorm), so the row was not pooled by this call but is projected as usual
+  const bool given = !row_map && (key_index ? ksrc >= 0 : (pooled_valid && pooled_valid[b] == 1));
+  const bool has_partials = !row_map && pooled_valid && pooled_valid[b] == 2;
   const bool from_means = pooled_in && (row_map || (!pooled_valid && !key_index) || (given && !key_index));
   if (given && key_in) {
     for (int i = threadIdx.x; i < k; i += nthreads) fp_out[(size_t)b * k + i] = key_in[(size_t)ksrc * k + i];
@@ -175,7 +178,7 @@ __global__ __launch_bounds__(1024) void project_kernel(const float* __restrict__
   const float inv_S = 1.0f / (float)S;
   if (from_means) {
     for (int i = threadIdx.x; i < d; i += nthreads) p[i] = pooled_in[(size_t)b * d + i];
-  } else if (h_inline) {
+  } else if (h_inline && !has_partials) {
     constexpr int VEC = Vec16<T>::N;
     float total[VEC];
     pool_sequence<T>(h_inline + ((size_t)b * S) * d, S, d, G, R, vpart + (size_t)parts * k, total);

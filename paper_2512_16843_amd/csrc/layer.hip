@@ -168,6 +168,112 @@ __global__ __launch_bounds__(256) void layernorm_kernel(const T* __restrict__ in
   }
 }
 
+// ---- the block's LAST LayerNorm with the next layer's pooling folded in ---------------------------------------
+// The output of a post-LayerNorm block is written by this kernel, and the next layer's fingerprint starts by
+// summing exactly these rows over the tokens.  A workgroup owns one (sequence, 64-token chunk): its wavefronts
+// normalise the chunk's tokens (same arithmetic as layernorm_kernel), store them, and keep the ROUNDED outputs in
+// LDS; then the chunk's column sums are formed in the order of the fingerprint's pooling kernel -- token t of the
+// chunk belongs to row group t % R, a group's tokens are added in ascending order starting from zero, and the
+// groups are added in ascending order -- so the partial sums are the bits that kernel would produce, and the
+// sequence is flagged so that the next call does not read its rows again.  grid (chunks, max_seqs).
+constexpr int kLnPoolThreads = 1024;
+constexpr int kLnPoolChunk = 64;             // tokens per pooling chunk: must equal the fingerprint's
+constexpr int kLnPoolTokPerWave = kLnPoolChunk / (kLnPoolThreads / 64);
+
+template <typename T, int MAXV>
+__global__ __launch_bounds__(kLnPoolThreads) void layernorm_pool_kernel(
+    const T* __restrict__ in, int ld_in, T* __restrict__ out, int ld_out, const int32_t* __restrict__ out_rows,
+    const T* __restrict__ gamma, const T* __restrict__ beta, float eps, int d, int S, const int32_t* count, int max_seqs,
+    float* __restrict__ partial, int n_chunks, int R, uint8_t* __restrict__ pooled_flags) {
+  constexpr int VEC = Vec16<T>::N;
+  constexpr int TPW = kLnPoolTokPerWave;
+  extern __shared__ __attribute__((aligned(16))) unsigned char ln_lds[];
+  T* tile = reinterpret_cast<T*>(ln_lds);                 // [kLnPoolChunk][d], the outputs as stored
+  const int n_seq = count ? min(*count, max_seqs) : max_seqs;
+  const int q = blockIdx.y, chunk = blockIdx.x;
+  if (q >= n_seq) return;
+  const int seq = out_rows ? out_rows[q] : q;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int nvec = d / VEC;
+  const int t0 = chunk * kLnPoolChunk, t1 = min(S, t0 + kLnPoolChunk);
+  // a wavefront owns TPW consecutive tokens of the chunk; all their rows are requested before the first is reduced
+  const int tw = t0 + wave * TPW;
+  float x[TPW][MAXV][VEC];
+#pragma unroll
+  for (int u = 0; u < TPW; ++u) {
+    const int t = min(tw + u, S - 1);                     // the block's temporaries are in compact token order
+    const T* src = in + ((size_t)q * S + t) * ld_in;
+#pragma unroll
+    for (int i = 0; i < MAXV; ++i) {
+      const int v = lane + i * 64;
+      if (v < nvec) Vec16<T>::load(src + v * VEC, x[u][i]);
+    }
+  }
+  float gv[MAXV][VEC], bv[MAXV][VEC];
+#pragma unroll
+  for (int i = 0; i < MAXV; ++i) {
+    const int v = lane + i * 64;
+    if (v < nvec) {
+      Vec16<T>::load(gamma + v * VEC, gv[i]);
+      Vec16<T>::load(beta + v * VEC, bv[i]);
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < TPW; ++u) {
+    const int t = tw + u;
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < MAXV; ++i) {
+      const int v = lane + i * 64;
+      if (v < nvec) {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) s += x[u][i][e];
+      }
+    }
+    const float mean = wave_sum(s) / (float)d;
+    float qq = 0.f;
+#pragma unroll
+    for (int i = 0; i < MAXV; ++i) {
+      const int v = lane + i * 64;
+      if (v < nvec) {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+          const float c = x[u][i][e] - mean;
+          qq += c * c;
+        }
+      }
+    }
+    const float rstd = 1.0f / sqrtf(wave_sum(qq) / (float)d + eps);
+    if (t < t1) {
+      T* dst = out + ((size_t)seq * S + t) * ld_out;
+      T* keep = tile + (size_t)(t - t0) * d;
+#pragma unroll
+      for (int i = 0; i < MAXV; ++i) {
+        const int v = lane + i * 64;
+        if (v < nvec) {
+          float y[VEC];
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) y[e] = (x[u][i][e] - mean) * rstd * gv[i][e] + bv[i][e];
+          Vec16<T>::store(dst + v * VEC, y);
+          Vec16<T>::store(keep + v * VEC, y);
+        }
+      }
+    }
+  }
+  __syncthreads();
+  float* po = partial + ((size_t)seq * n_chunks + chunk) * d;
+  for (int c = threadIdx.x; c < d; c += kLnPoolThreads) {
+    float total = 0.f;
+    for (int r = 0; r < R; ++r) {
+      float acc = 0.f;
+      for (int t = t0 + r; t < t1; t += R) acc += Elem<T>::load(tile + (size_t)(t - t0) * d + c);
+      total = r == 0 ? acc : total + acc;
+    }
+    po[c] = total;
+  }
+  if (chunk == 0 && threadIdx.x == 0) pooled_flags[seq] = 2;
+}
+
 template <typename T>
 static llmc_status_t launch_ln(const void* in, const int32_t* in_rows, void* out, const int32_t* out_rows,
                                const void* gamma, const void* beta, float eps, int d, int S, const int32_t* count,
@@ -189,6 +295,38 @@ static llmc_status_t launch_ln(const void* in, const int32_t* in_rows, void* out
   else return set_error(LLMC_ERR_SHAPE, "LayerNorm width %d too large", d);
 #undef LN_CASE
   LLMC_LAUNCH_CHECK("layernorm");
+  return LLMC_OK;
+}
+
+// the fused form needs the chunk's outputs in LDS; wider rows take the plain kernel and the next call pools them
+template <typename T>
+static bool ln_pool_fits(int d) { return (size_t)kLnPoolChunk * d * sizeof(T) <= 128 * 1024 && d / Vec16<T>::N <= 256; }
+
+template <typename T>
+static llmc_status_t launch_ln_pool(const void* in, void* out, const int32_t* out_rows, const void* gamma,
+                                    const void* beta, float eps, int d, int S, const int32_t* count, int max_seqs,
+                                    float* partial, uint8_t* pooled_flags, hipStream_t st) {
+  constexpr int VEC = Vec16<T>::N;
+  const int nvec = d / VEC;
+  const int G = d / VEC;
+  const int R = std::max(1, std::min(8, 1024 / G));        // the pooling kernel's row groups for this width
+  const int n_chunks = (S + kLnPoolChunk - 1) / kLnPoolChunk;
+  const size_t lds = (size_t)kLnPoolChunk * d * sizeof(T);
+  dim3 grid(n_chunks, max_seqs);
+#define LNP_CASE(MV)                                                                                            \
+  {                                                                                                             \
+    static std::atomic<bool> lds_set[64];                                                                       \
+    LLMC_TRY(ensure_dynamic_lds((const void*)(layernorm_pool_kernel<T, MV>), lds, lds_set));                    \
+    ProfScope ps_("layernorm_kernel", st);                                                                      \
+    LLMC_KERNEL_GGL((layernorm_pool_kernel<T, MV>), grid, dim3(kLnPoolThreads), lds, st, (const T*)in, d, (T*)out, \
+                    d, out_rows, (const T*)gamma, (const T*)beta, eps, d, S, count, max_seqs, partial, n_chunks, R,  \
+                    pooled_flags);                                                                              \
+  }
+  if (nvec <= 64) LNP_CASE(1)
+  else if (nvec <= 128) LNP_CASE(2)
+  else LNP_CASE(4)
+#undef LNP_CASE
+  LLMC_LAUNCH_CHECK("layernorm_pool");
   return LLMC_OK;
 }
 
@@ -304,7 +442,8 @@ size_t layer_ws_bytes(const llmc_layer_desc_t* L, int B, int S) {
 
 template <typename T>
 static llmc_status_t layer_t(const llmc_layer_desc_t* L, const void* h_in, void* h_out, int B, int S,
-                             const int32_t* rows, const int32_t* count, void* ws, hipStream_t st) {
+                             const int32_t* rows, const int32_t* count, void* ws, hipStream_t st,
+                             float* pool_partial, uint8_t* pooled_flags) {
   const int d = L->d, dff = L->d_ff;
   const size_t Tn = (size_t)B * S, e = sizeof(T);
   char* p = (char*)ws;
@@ -330,7 +469,11 @@ static llmc_status_t layer_t(const llmc_layer_desc_t* L, const void* h_in, void*
     LLMC_TRY(launch_ln<T>(t0, nullptr, t1, nullptr, L->d_ln1_g, L->d_ln1_b, L->ln_eps, d, S, count, B, st));
     LLMC_TRY(gemm(t1, d, nullptr, L->d_w1, L->d_b1, dff, d, act, nullptr, nullptr, ff, nullptr));
     LLMC_TRY(gemm(ff, dff, nullptr, L->d_w2, L->d_b2, d, dff, 0, t1, nullptr, t0, nullptr));
-    LLMC_TRY(launch_ln<T>(t0, nullptr, h_out, rows, L->d_ln2_g, L->d_ln2_b, L->ln_eps, d, S, count, B, st));
+    if (pool_partial && pooled_flags && ln_pool_fits<T>(d))
+      LLMC_TRY(launch_ln_pool<T>(t0, h_out, rows, L->d_ln2_g, L->d_ln2_b, L->ln_eps, d, S, count, B, pool_partial,
+                                 pooled_flags, st));
+    else
+      LLMC_TRY(launch_ln<T>(t0, nullptr, h_out, rows, L->d_ln2_g, L->d_ln2_b, L->ln_eps, d, S, count, B, st));
   } else {
     LLMC_TRY(launch_ln<T>(h_in, rows, t1, nullptr, L->d_ln1_g, L->d_ln1_b, L->ln_eps, d, S, count, B, st));
     LLMC_TRY(gemm(t1, d, nullptr, L->d_wqkv, L->d_bqkv, 3 * d, d, 0, nullptr, nullptr, qkv, nullptr));
@@ -354,9 +497,11 @@ llmc_status_t launch_linear(const void* A, int lda, const int32_t* a_rows, const
 }
 
 llmc_status_t launch_layer(const llmc_layer_desc_t* L, const void* d_h_in, void* d_h_out, int B, int S,
-                           const int32_t* d_rows, const int32_t* d_count, void* ws, hipStream_t st) {
-  if (L->dtype == LLMC_F32) return layer_t<float>(L, d_h_in, d_h_out, B, S, d_rows, d_count, ws, st);
-  return layer_t<bf16_t>(L, d_h_in, d_h_out, B, S, d_rows, d_count, ws, st);
+                           const int32_t* d_rows, const int32_t* d_count, void* ws, hipStream_t st,
+                           float* pool_partial, uint8_t* pooled_flags) {
+  if (L->dtype == LLMC_F32)
+    return layer_t<float>(L, d_h_in, d_h_out, B, S, d_rows, d_count, ws, st, pool_partial, pooled_flags);
+  return layer_t<bf16_t>(L, d_h_in, d_h_out, B, S, d_rows, d_count, ws, st, pool_partial, pooled_flags);
 }
 
 }  // namespace llmc

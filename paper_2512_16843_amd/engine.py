@@ -47,6 +47,10 @@ class GatedStack:
         # keep_means: banks store the token mean of every cached output and a reused row hands it to the next layer
         self.keep_means = keep_means
         self._hint = [False] * cfg.n_layers
+        # post-LayerNorm blocks leave the pooled chunk sums of the rows they compute for the next call, so with stored
+        # means every row of a later layer normally arrives pooled one way or the other: the pooling launch is dropped
+        # there from the start (rows that do arrive unpooled are pooled inside the projection, same bits)
+        self.auto_hint = keep_means and cfg.arch == 0
         self._deferred = [False] * cfg.n_layers
         self._stat_host = torch.zeros((cfg.n_layers, llmc.CNT_WORDS), dtype=torch.int32).pin_memory() if keep_means else None
         self.counters_all = torch.zeros((cfg.n_layers, llmc.CNT_WORDS), dtype=torch.int32, device=device)
@@ -105,7 +109,7 @@ class GatedStack:
             if out.data_ptr() == h.data_ptr():
                 out = self.buf[(l & 1) ^ 1]
             carry = self.gate[l - 1] if (self.keep_means and l > 0) else None
-            fl = flags | (llmc.HINT_MOSTLY_CARRIED if (carry is not None and self._hint[l]) else 0)
+            fl = flags | (llmc.HINT_MOSTLY_CARRIED if (carry is not None and (self._hint[l] or self.auto_hint)) else 0)
             bank = self.banks[l]
             # a row may stay a reference across this layer only if this layer's bank stores the key that the
             # next layer needs; the last layer (and a layer before an uncached one) copies as usual

@@ -1047,7 +1047,9 @@ def test_carried_token_means_change_nothing(L, dtype):
             assert torch.equal(a.hit, b.hit) and torch.equal(a.idx, b.idx) and torch.equal(a.sim, b.sim), (tick, l)
             assert torch.equal(a.counters, b.counters)
             assert torch.equal(outs[0][l], outs[other][l]), (tick, l)
-            assert torch.equal(b.pooled_valid, b.hit)
+            # reused rows carry their stored mean (flag 1); computed rows of a post-LayerNorm block were pooled by its
+            # last LayerNorm on the way out (flag 2)
+            assert torch.equal(b.pooled_valid, torch.where(b.hit.bool(), 1, 2).to(torch.uint8))
             assert torch.equal(stacks[0].banks[l].act, stacks[other].banks[l].act)
             assert torch.equal(stacks[0].banks[l].fp, stacks[other].banks[l].fp)
             hit_rows = torch.nonzero(b.hit).flatten()
@@ -1405,6 +1407,7 @@ def test_cost_hint_with_carried_and_uncarried_rows(L, dtype, deferred):
     results = {}
     for hint in (False, True):
         st._stat_event = None                      # the engine's own hint logic stays out of the way
+        st.auto_hint = False
         st._hint = [hint] * cfg.n_layers
         if deferred:
             y = st.forward(h0, tau=0.9).clone()
