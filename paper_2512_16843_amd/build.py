@@ -9,9 +9,13 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libllmc.so")
-SOURCES = ["api.hip", "fingerprint.hip", "match.hip", "bits.hip", "lsh.hip", "gate.hip", "bank.hip", "layer.hip"]
+SOURCES = ["api.hip", "fingerprint.hip", "match.hip", "bits.hip", "lsh.hip", "gate.hip", "bank.hip", "layer.hip",
+           "attention.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+# the attention kernel feeds every matrix-instruction result to vector instructions at once: accumulators in VGPRs,
+# and its maxima need no NaN quieting (scores of finite inputs are finite or the -inf of a masked key)
+EXTRA_FLAGS = {"attention.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form", "-fno-honor-nans", "-mno-amdgpu-ieee"]}
 
 
 def _hipcc() -> str:
@@ -38,7 +42,7 @@ def build_library(verbose: bool = False) -> str:
 
     def compile_one(pair):
         src, obj = pair
-        return _run([hipcc, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj])
+        return _run([hipcc, *FLAGS, *EXTRA_FLAGS.get(src, []), "-c", os.path.join(CSRC, src), "-o", obj])
 
     with ThreadPoolExecutor(max_workers=min(6, os.cpu_count() or 1)) as ex:
         for out in ex.map(compile_one, zip(SOURCES, objs)):

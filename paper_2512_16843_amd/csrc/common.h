@@ -261,6 +261,9 @@ llmc_status_t launch_linear(const void* A, int lda, const int32_t* a_rows, const
                             int dtype, hipStream_t st);
 // pool_partial / pooled_flags (both or neither): the block's last LayerNorm also leaves the chunk sums of its
 // outputs in the fingerprint's partials buffer and sets pooled_flags[row] = 2 (post-LayerNorm blocks whose rows fit)
+// bf16 softmax attention on the matrix cores (head size 64): qkv [T, 3d] -> ctx [T, d]; sequences beyond *count skipped
+llmc_status_t launch_attention_bf16(const void* qkv, void* ctx, int S, int d, int n_heads, bool causal,
+                                    const int32_t* count, int max_seqs, hipStream_t st);
 llmc_status_t launch_layer(const llmc_layer_desc_t* L, const void* d_h_in, void* d_h_out, int B, int S,
                            const int32_t* d_rows, const int32_t* d_count, void* ws, hipStream_t st,
                            float* pool_partial = nullptr, uint8_t* pooled_flags = nullptr);

@@ -13,7 +13,6 @@
 #include "common.h"
 #include <algorithm>
 #include "gemm.h"
-#include "attention.h"
 
 namespace llmc {
 
@@ -408,19 +407,8 @@ template <typename T>
 static llmc_status_t launch_attention(const void* qkv, void* ctx, int S, int d, int n_heads, bool causal,
                                       const int32_t* count, int max_seqs, hipStream_t st) {
   const float scale = 1.0f / sqrtf((float)(d / n_heads));
-  if (sizeof(T) == 2) {
-    // bf16: matrix-core kernel, base-2 softmax with log2(e) folded into the score scale
-    const float scale_log2e = scale * 1.4426950408889634f;
-    const int items = ((S + AttnCfg::QB - 1) / AttnCfg::QB) * n_heads * max_seqs;
-    const dim3 grid(std::min(items, 2 * kMaxGrid));
-    ProfScope ps_("attention_kernel", st);
-    if (causal)
-      LLMC_KERNEL_GGL(attention_mfma_kernel<true>, grid, dim3(AttnCfg::THREADS), 0, st, (const uint16_t*)qkv,
-                         (uint16_t*)ctx, S, d, n_heads, scale_log2e, count, max_seqs);
-    else
-      LLMC_KERNEL_GGL(attention_mfma_kernel<false>, grid, dim3(AttnCfg::THREADS), 0, st, (const uint16_t*)qkv,
-                         (uint16_t*)ctx, S, d, n_heads, scale_log2e, count, max_seqs);
-  } else {
+  if (sizeof(T) == 2) return launch_attention_bf16(qkv, ctx, S, d, n_heads, causal, count, max_seqs, st);
+  {
     dim3 grid((S + 127) / 128, n_heads, max_seqs);
     ProfScope ps_("attention_kernel", st);
     if (causal)
