@@ -8,8 +8,10 @@
 //
 // Kernels: linear layers on the bf16 matrix cores (fp32 accumulate) with bias, GELU,
 // residual and row gather/scatter fused into the epilogue; a plain fp32 FMA GEMM for
-// fp32 runs; LayerNorm with one wavefront per token; softmax attention with an online
-// softmax over 32-key tiles.
+// fp32 runs; LayerNorm with one wavefront per token (the last LayerNorm of a post-LN block
+// also leaves the pooled chunk sums of the rows it writes for the next fingerprint); the
+// fp32 softmax attention with one thread per query row.  The bf16 attention on the matrix
+// cores is a translation unit of its own.
 #include "common.h"
 #include <algorithm>
 #include "gemm.h"
@@ -299,7 +301,7 @@ static llmc_status_t launch_ln(const void* in, const int32_t* in_rows, void* out
 
 // the fused form needs the chunk's outputs in LDS; wider rows take the plain kernel and the next call pools them
 template <typename T>
-static bool ln_pool_fits(int d) { return (size_t)kLnPoolChunk * d * sizeof(T) <= 128 * 1024 && d / Vec16<T>::N <= 256; }
+static bool ln_pool_fits(int d) { return (size_t)kLnPoolChunk * d * sizeof(T) <= 128 * 1024 && d / Vec16<T>::N <= 128; }
 
 template <typename T>
 static llmc_status_t launch_ln_pool(const void* in, void* out, const int32_t* out_rows, const void* gamma,
@@ -322,8 +324,7 @@ static llmc_status_t launch_ln_pool(const void* in, void* out, const int32_t* ou
                     pooled_flags);                                                                              \
   }
   if (nvec <= 64) LNP_CASE(1)
-  else if (nvec <= 128) LNP_CASE(2)
-  else LNP_CASE(4)
+  else LNP_CASE(2)
 #undef LNP_CASE
   LLMC_LAUNCH_CHECK("layernorm_pool");
   return LLMC_OK;
