@@ -56,6 +56,7 @@ FLAG_INSERT_ON_MISS = 1
 FLAG_UPDATE_LRU = 2
 FLAG_REVALIDATE = 4
 FLAG_DEDUP = 32
+FLAG_LOOKUP_LSH = 64
 
 NORM_FLOOR = 1e-12
 
@@ -565,7 +566,11 @@ def gated_layer(h_in: np.ndarray, bank: Optional[Bank], P: Optional[np.ndarray],
         # sign-bit keys: Hamming match, threshold on the cosine that the distance stands for
         q = fp_override[0] if fp_override is not None else fingerprint_bits(h_in, P, c)
         qinv = np.zeros((B,), np.float32)
-        idx, dist = match_bits(q, bank.fp, bank.valid, bank.k)
+        if flags & FLAG_LOOKUP_LSH:
+            # bucketed lookup (Section IV-B "LSH"): only slots that share one whole band with the query are compared
+            idx, dist, _ = match_bits_lsh(q, bank.fp, bank.valid, bank.k)
+        else:
+            idx, dist = match_bits(q, bank.fp, bank.valid, bank.k)
         hit = threshold_bits(idx, dist, max_hamming(tau, bank.k))
         sim = np.where(idx >= 0, cosine_estimate(np.minimum(dist, bank.k), bank.k), -np.inf)
     else:

@@ -207,3 +207,50 @@ def test_lsh_buckets_candidates_by_explicit_loops_and_agreement_with_the_full_ma
     near = np.arange(0, B, 2)
     ok = valid[fidx[near]] == 1
     assert np.array_equal(idx[near][fdist[near] <= 3], fidx[near][fdist[near] <= 3])
+
+
+def test_gate_with_bucketed_lookup_sees_only_entries_that_share_a_band():
+    """FLAG_LOOKUP_LSH in the gated layer: the bank is consulted through the band buckets.  Hand-made keys: the query
+    differs from entry 0 by ONE bit in EVERY 16-bit band (distance k / 16, well under the threshold's bound, so the
+    full comparison hits) and from entry 1 by 40 bits that all sit in the first three bands (the other band is intact).
+    The bucketed lookup cannot see entry 0 and answers with entry 1, which is too far: a miss; the full comparison
+    answers with entry 0: a hit."""
+    g = rng(11)
+    S, d, k, N = 4, 32, 64, 6
+    w = {"wqkv": g.standard_normal((3 * d, d)) * 0.05, "bqkv": np.zeros(3 * d), "wo": g.standard_normal((d, d)) * 0.05,
+         "bo": np.zeros(d), "w1": g.standard_normal((2 * d, d)) * 0.05, "b1": np.zeros(2 * d),
+         "w2": g.standard_normal((d, 2 * d)) * 0.05, "b2": np.zeros(d), "ln1_g": np.ones(d), "ln1_b": np.zeros(d),
+         "ln2_g": np.ones(d), "ln2_b": np.zeros(d)}
+    h = g.standard_normal((1, S, d))
+    qbits = g.integers(0, 2, (1, k)).astype(bool)
+    e0 = qbits.copy()
+    e0[0, [3, 16 + 5, 32 + 9, 48 + 1]] ^= True                      # one bit in each of the four bands
+    e1 = qbits.copy()
+    e1[0, np.r_[0:16, 16:32, 32:40]] ^= True                        # 40 bits, band 3 untouched
+    bank = O.Bank(N, k, S, d, "f32", key_bits=True)
+    bank.fp[0], bank.fp[1] = O.pack_bits(e0)[0], O.pack_bits(e1)[0]
+    bank.valid[:2] = 1
+    bank.act[0], bank.act[1] = 1.0, 2.0
+    q = O.pack_bits(qbits)
+    tau = np.float32(0.9)
+    assert O.max_hamming(tau, k) >= 4 and O.max_hamming(tau, k) < 40
+    full = O.gated_layer(h, bank, None, None, w, O.ENCODER_POST_LN, 2, 1e-5, O.GELU_ERF, tau,
+                         fp_override=(q, np.zeros(1, np.float32)))
+    assert full.hit[0] and full.idx[0] == 0 and np.all(full.h_out[0] == 1.0)
+    lsh = O.gated_layer(h, bank, None, None, w, O.ENCODER_POST_LN, 2, 1e-5, O.GELU_ERF, tau,
+                        flags=O.FLAG_LOOKUP_LSH, fp_override=(q, np.zeros(1, np.float32)))
+    assert not lsh.hit[0] and lsh.idx[0] == 1
+    np.testing.assert_allclose(lsh.sim[0], np.cos(np.pi * 40 / k), atol=1e-12)
+    np.testing.assert_allclose(lsh.h_out[0], O.layer_forward(h[0], w, O.ENCODER_POST_LN, 2, 1e-5, O.GELU_ERF), atol=0)
+    # an entry equal to the query in one band and nowhere else is seen; an invalid one is not
+    bank.valid[1] = 0
+    none = O.gated_layer(h, bank, None, None, w, O.ENCODER_POST_LN, 2, 1e-5, O.GELU_ERF, tau,
+                         flags=O.FLAG_LOOKUP_LSH, fp_override=(q, np.zeros(1, np.float32)))
+    assert not none.hit[0] and none.idx[0] == -1 and none.sim[0] == -np.inf
+    # the resubmitted key itself shares every band: both lookups agree on it
+    bank.fp[2] = q[0]
+    bank.valid[2] = 1
+    bank.act[2] = 3.0
+    same = O.gated_layer(h, bank, None, None, w, O.ENCODER_POST_LN, 2, 1e-5, O.GELU_ERF, tau,
+                         flags=O.FLAG_LOOKUP_LSH, fp_override=(q, np.zeros(1, np.float32)))
+    assert same.hit[0] and same.idx[0] == 2 and same.sim[0] == 1.0 and np.all(same.h_out[0] == 3.0)
