@@ -108,6 +108,12 @@ typedef enum { LLMC_EVICT_NONE = 0, LLMC_EVICT_LRU = 1, LLMC_EVICT_DECAYED_HITS 
                                   LLMC_INSERT_ON_MISS and a replacing policy; B <= LLMC_MAX_DEDUP_ROWS; refused with
                                   LLMC_REVALIDATE, compressed values and sign-bit keys. */
 #define LLMC_MAX_DEDUP_ROWS 1024
+#define LLMC_LOOKUP_LSH 64u    /* sign-bit keys only: the lookup goes through the bank's bucket index (d_lsh_index) instead
+                                  of comparing the query with every slot: a query is compared with the slots that share
+                                  one whole 16-bit band with it and gets the nearest of those (see llmc_match_bits_lsh);
+                                  a row whose nearest neighbour shares no band with it is a miss.  The library keeps the
+                                  index current: every call that stores or replaces keys rebuilds it on the device
+                                  before it returns (and does nothing of the kind when the batch stored nothing). */
 
 /* Largest tick accepted (recency keys are packed into 32 bits on the device). */
 #define LLMC_MAX_TICK 0x7FFFFFFEull
@@ -193,6 +199,13 @@ typedef struct {
    * llmc_bank_insert and d_fp_given then take keys in that form (d_inv_norm / d_inv_norm_given ignored);
    * llmc_match refuses such a bank (use llmc_match_bits).  Refused together with stored next-layer keys. */
   int32_t key_bits;
+  /* Optional, key_bits = 1 only: storage for the bucket index of the keys (Section IV-B "LSH"), device memory of
+   * lsh_index_bytes >= llmc_lsh_index_bytes(n_slots, k) bytes, 256-byte aligned, owned by the caller and written by
+   * the library alone: llmc_bank_create and llmc_bank_refresh build it from the keys and validity flags as they
+   * stand, llmc_bank_insert and the insertions of llmc_layer_forward_gated rebuild it after they changed a key.
+   * LLMC_LOOKUP_LSH needs it.  k must be 64, 128, 256 or 512. */
+  void* d_lsh_index;
+  size_t lsh_index_bytes;
 } llmc_bank_desc_t;
 
 /*
@@ -478,7 +491,7 @@ llmc_status_t llmc_materialize(const llmc_bank_t* bank, const int32_t* d_ref, in
  *   d_fp_given / d_inv_norm_given: NULL, or keys [B, k] + norms to use instead of
  *          fingerprinting d_h_in (Algorithm 1 taken literally: one fingerprint of X for all layers)
  *   tau: threshold; flags: LLMC_INSERT_ON_MISS | LLMC_UPDATE_LRU | LLMC_REVALIDATE | LLMC_HINT_MOSTLY_CARRIED |
- *          LLMC_DEFER_COPY | LLMC_DEDUP;
+ *          LLMC_DEFER_COPY | LLMC_DEDUP | LLMC_LOOKUP_LSH;
  *          tick <= LLMC_MAX_TICK
  *   out: optional per-row results and counters (NULL or any member NULL)
  *   d_workspace: at least llmc_layer_workspace_bytes(layer, B, S, k) bytes

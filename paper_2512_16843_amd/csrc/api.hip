@@ -90,6 +90,8 @@ extern "C" {
 const char* llmc_last_error(void) { return g_err; }
 const char* llmc_version(void) { return "llmc 0.1 (gfx950)"; }
 
+static bool lsh_k_ok(int k) { return k == 64 || k == 128 || k == 256 || k == 512; }
+
 llmc_status_t llmc_bank_create(const llmc_bank_desc_t* desc, llmc_bank_t** out) {
   REQUIRE(desc && out, LLMC_ERR_INVALID_ARG, "desc/out is NULL");
   *out = nullptr;
@@ -114,6 +116,13 @@ llmc_status_t llmc_bank_create(const llmc_bank_desc_t* desc, llmc_bank_t** out) 
           LLMC_ERR_INVALID_ARG, "a bank array pointer is NULL");
   REQUIRE(!(desc->key_bits && desc->d_next_fp), LLMC_ERR_INVALID_ARG,
           "stored next-layer keys are refused on a bank of sign-bit keys");
+  if (desc->d_lsh_index) {
+    REQUIRE(desc->key_bits, LLMC_ERR_INVALID_ARG, "a bucket index needs sign-bit keys");
+    REQUIRE(lsh_k_ok(desc->k), LLMC_ERR_SHAPE, "bucketed lookup supports k = 64, 128, 256 or 512 bits");
+    REQUIRE(((uintptr_t)desc->d_lsh_index & 255) == 0, LLMC_ERR_SHAPE, "d_lsh_index must be 256-byte aligned");
+    REQUIRE(desc->lsh_index_bytes >= lsh_index_bytes(desc->n_slots, desc->k), LLMC_ERR_WORKSPACE,
+            "the bucket index needs %zu bytes", lsh_index_bytes(desc->n_slots, desc->k));
+  }
   REQUIRE(aligned16(desc->d_fp) && aligned16(desc->d_act), LLMC_ERR_SHAPE, "bank arrays must be 16-byte aligned");
   REQUIRE(!(desc->d_act_pool && desc->rank > 0), LLMC_ERR_INVALID_ARG,
           "stored token means are refused together with compressed values");
@@ -277,7 +286,6 @@ size_t llmc_match_bits_workspace_bytes(int32_t N, int32_t k, int32_t B) {
   return match_bits_ws_bytes(N, k, B);
 }
 
-static bool lsh_k_ok(int k) { return k == 64 || k == 128 || k == 256 || k == 512; }
 
 size_t llmc_lsh_index_bytes(int32_t N, int32_t k) {
   if (N <= 0 || N > (1 << 30) || !lsh_k_ok(k)) return 0;
@@ -473,7 +481,7 @@ llmc_status_t llmc_layer_forward_gated(const llmc_layer_desc_t* layer, llmc_bank
   REQUIRE(tau == tau, LLMC_ERR_INVALID_ARG, "tau is NaN");
   REQUIRE(tick <= LLMC_MAX_TICK, LLMC_ERR_INVALID_ARG, "tick out of range");
   REQUIRE((flags & ~(LLMC_INSERT_ON_MISS | LLMC_UPDATE_LRU | LLMC_REVALIDATE | LLMC_HINT_MOSTLY_CARRIED | LLMC_DEFER_COPY |
-                     LLMC_DEDUP)) == 0,
+                     LLMC_DEDUP | LLMC_LOOKUP_LSH)) == 0,
           LLMC_ERR_INVALID_ARG,
           "unknown flag bits");
   int k = 0;
@@ -520,6 +528,9 @@ llmc_status_t llmc_layer_forward_gated(const llmc_layer_desc_t* layer, llmc_bank
       REQUIRE(D.n_act_slots == D.n_slots, LLMC_ERR_SHAPE,
               "the divergence monitor is refused on a bank whose keys share value rows");
     }
+    if (flags & LLMC_LOOKUP_LSH)
+      REQUIRE(D.key_bits && D.d_lsh_index, LLMC_ERR_INVALID_ARG,
+              "LLMC_LOOKUP_LSH needs a bank of sign-bit keys created with d_lsh_index");
     if (flags & LLMC_DEDUP) {
       REQUIRE(flags & LLMC_INSERT_ON_MISS, LLMC_ERR_INVALID_ARG, "LLMC_DEDUP needs LLMC_INSERT_ON_MISS");
       REQUIRE(!(flags & LLMC_REVALIDATE), LLMC_ERR_INVALID_ARG, "LLMC_DEDUP is refused with LLMC_REVALIDATE");
@@ -604,7 +615,11 @@ llmc_status_t llmc_layer_forward_gated(const llmc_layer_desc_t* layer, llmc_bank
     q = keys;
     qinv = inv;
   }
-  if (bits) {
+  if (bits && (flags & LLMC_LOOKUP_LSH)) {
+    LLMC_TRY(launch_lsh_match((const uint32_t*)bank->desc.d_fp, bank->desc.n_slots, k, bank->desc.d_lsh_index,
+                              (const uint32_t*)q, B, llmc_max_hamming(tau, k), idx, nullptr, hit, nullptr, st, sim));
+    tie = nullptr;
+  } else if (bits) {
     LLMC_TRY(launch_match_bits((const uint32_t*)bank->desc.d_fp, bank->desc.d_valid, bank->desc.n_slots, k,
                                (const uint32_t*)q, B, llmc_max_hamming(tau, k), idx, nullptr, hit, ws_match, st,
                                (const uint32_t*)bank->d_binv_eff, sim));

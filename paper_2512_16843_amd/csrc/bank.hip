@@ -308,13 +308,21 @@ __global__ __launch_bounds__(kCopyThreads) void insert_kernel(
   }
 }
 
+// the bucket index of a bank of sign-bit keys follows every change of keys or validity; `changed` (device, optional)
+// lets the kernels leave at once when a batch changed nothing
+static llmc_status_t rebuild_lsh_index(const llmc_bank* bank, hipStream_t st, const int32_t* changed) {
+  const llmc_bank_desc_t& D = bank->desc;
+  if (!D.key_bits || !D.d_lsh_index) return LLMC_OK;
+  return launch_lsh_build((const uint32_t*)D.d_fp, D.d_valid, D.n_slots, D.k, D.d_lsh_index, st, changed);
+}
+
 llmc_status_t launch_bank_refresh(llmc_bank* bank, hipStream_t st) {
   const int N = bank->desc.n_slots;
   const int n_pad = (int)align_up((size_t)N + 8, 256);      // the mirror's allocated length
   { ProfScope ps_("refresh_kernel", st); LLMC_KERNEL_GGL(refresh_kernel, dim3((n_pad + 255) / 256), dim3(256), 0, st, bank->desc.d_valid,
                      bank->desc.d_inv_norm, N, n_pad, bank->d_binv_eff, bank->desc.key_bits); }
   LLMC_LAUNCH_CHECK("refresh_kernel");
-  return LLMC_OK;
+  return rebuild_lsh_index(bank, st, nullptr);
 }
 
 llmc_status_t launch_bank_insert(llmc_bank* bank, const void* d_fp, const float* d_inv, const void* d_act,
@@ -348,14 +356,14 @@ llmc_status_t launch_bank_insert(llmc_bank* bank, const void* d_fp, const float*
   if (D.d_next_fp)
     LLMC_TRY(launch_project_rows(D.d_act_pool, m_max, D.d, D.dtype, D.d_next_proj, D.d_next_bias, D.next_k, d_slots_out,
                                  d_m, D.d_next_fp, D.d_next_inv, st));
-  return LLMC_OK;
+  return rebuild_lsh_index(bank, st, d_m);
 }
 
 llmc_status_t launch_bank_evict(llmc_bank* bank, const int32_t* d_m, int m_max, int32_t* d_victims, hipStream_t st) {
   { ProfScope ps_("select_kernel", st);
     launch_select(bank, d_m, m_max, 1, 1, d_victims, st); }
   LLMC_LAUNCH_CHECK("select_kernel");
-  return LLMC_OK;
+  return rebuild_lsh_index(bank, st, d_m);
 }
 
 }  // namespace llmc

@@ -189,11 +189,12 @@ llmc_status_t launch_fingerprint_bits(const void* d_h, int B, int S, int d, int 
                                       bool few_uncarried = false);
 size_t match_bits_ws_bytes(int N, int k, int B);
 size_t lsh_index_bytes(int N, int k);
+// d_changed (optional, device): the index is left as it is when *d_changed == 0
 llmc_status_t launch_lsh_build(const uint32_t* d_bank_bits, const uint8_t* d_valid, int N, int k, void* d_index,
-                               hipStream_t st);
+                               hipStream_t st, const int32_t* d_changed = nullptr);
 llmc_status_t launch_lsh_match(const uint32_t* d_bank_bits, int N, int k, const void* d_index,
                                const uint32_t* d_query_bits, int B, int max_hamming, int32_t* d_idx, int32_t* d_dist,
-                               uint8_t* d_hit, int32_t* d_compared, hipStream_t st);
+                               uint8_t* d_hit, int32_t* d_compared, hipStream_t st, float* d_sim = nullptr);
 llmc_status_t launch_match_bits(const uint32_t* d_bank_bits, const uint8_t* d_valid, int N, int k,
                                 const uint32_t* d_query_bits, int B, int max_hamming, int32_t* d_idx, int32_t* d_dist,
                                 uint8_t* d_hit, void* ws, hipStream_t st, const uint32_t* d_pen = nullptr,

@@ -38,14 +38,16 @@ __device__ __forceinline__ uint32_t band_value(const uint32_t* key, int band) {
   return (key[band >> 1] >> (16 * (band & 1))) & 0xFFFFu;
 }
 
-__global__ void lsh_zero_kernel(uint32_t* p, size_t n) {
+__global__ void lsh_zero_kernel(uint32_t* p, size_t n, const int32_t* __restrict__ changed) {
+  if (changed && *changed == 0) return;
   const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = 0;
 }
 
 // grid over (slot, band): counts[band][value] += 1 for valid slots
 __global__ void lsh_count_kernel(const uint32_t* __restrict__ bank, const uint8_t* __restrict__ valid, int N, int W,
-                                 int bands, uint32_t* __restrict__ counts) {
+                                 int bands, uint32_t* __restrict__ counts, const int32_t* __restrict__ changed) {
+  if (changed && *changed == 0) return;
   const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= (size_t)N * bands) return;
   const int j = (int)(i / bands), b = (int)(i % bands);
@@ -54,9 +56,11 @@ __global__ void lsh_count_kernel(const uint32_t* __restrict__ bank, const uint8_
 }
 
 // one workgroup of 1024 threads per band: start[b][v] = number of slots with a smaller value; cursor = start
-__global__ __launch_bounds__(1024) void lsh_scan_kernel(uint32_t* __restrict__ cursor, uint32_t* __restrict__ start) {
+__global__ __launch_bounds__(1024) void lsh_scan_kernel(uint32_t* __restrict__ cursor, uint32_t* __restrict__ start,
+                                                        const int32_t* __restrict__ changed) {
   __shared__ uint32_t wave_tot[16];
   __shared__ uint32_t carry;
+  if (changed && *changed == 0) return;
   const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   uint32_t* cnt = cursor + (size_t)b * kLshValues;          // counts arrive in the cursor array
   uint32_t* st = start + (size_t)b * (kLshValues + 1);
@@ -87,7 +91,9 @@ __global__ __launch_bounds__(1024) void lsh_scan_kernel(uint32_t* __restrict__ c
 }
 
 __global__ void lsh_scatter_kernel(const uint32_t* __restrict__ bank, const uint8_t* __restrict__ valid, int N, int W,
-                                   int bands, uint32_t* __restrict__ cursor, int32_t* __restrict__ order) {
+                                   int bands, uint32_t* __restrict__ cursor, int32_t* __restrict__ order,
+                                   const int32_t* __restrict__ changed) {
+  if (changed && *changed == 0) return;
   const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= (size_t)N * bands) return;
   const int j = (int)(i / bands), b = (int)(i % bands);
@@ -103,7 +109,8 @@ __global__ __launch_bounds__(256) void lsh_match_kernel(const uint32_t* __restri
                                                         const int32_t* __restrict__ order,
                                                         const uint32_t* __restrict__ queries, int B, int max_hamming,
                                                         int32_t* __restrict__ idx_out, int32_t* __restrict__ dist_out,
-                                                        uint8_t* __restrict__ hit_out, int32_t* __restrict__ compared_out) {
+                                                        uint8_t* __restrict__ hit_out, int32_t* __restrict__ compared_out,
+                                                        float* __restrict__ sim_out) {
   const int b = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (b >= B) return;
   const int lane = threadIdx.x & 63;
@@ -139,12 +146,14 @@ __global__ __launch_bounds__(256) void lsh_match_kernel(const uint32_t* __restri
     idx_out[b] = found ? (int32_t)(uint32_t)best : -1;
     if (dist_out) dist_out[b] = found ? h : 0x7FFFFFFF;
     if (hit_out) hit_out[b] = (found && h <= max_hamming) ? 1 : 0;
+    // the cosine that the distance stands for, as the full comparison reports it
+    if (sim_out) sim_out[b] = found ? cosf(3.14159265358979323846f * (float)h / (float)(32 * W)) : -INFINITY;
     if (compared_out) compared_out[b] = compared;       // bucket members visited (a slot in several buckets counts each time)
   }
 }
 
 llmc_status_t launch_lsh_build(const uint32_t* d_bank_bits, const uint8_t* d_valid, int N, int k, void* d_index,
-                               hipStream_t st) {
+                               hipStream_t st, const int32_t* d_changed) {
   const LshLayout L = lsh_layout(N, k);
   uint32_t* start = (uint32_t*)((char*)d_index + L.off_start);
   uint32_t* cursor = (uint32_t*)((char*)d_index + L.off_cursor);
@@ -152,32 +161,32 @@ llmc_status_t launch_lsh_build(const uint32_t* d_bank_bits, const uint8_t* d_val
   const size_t n_cnt = (size_t)L.bands * kLshValues, n_pairs = (size_t)N * L.bands;
   const int W = k / 32;
   { ProfScope ps_("lsh_zero_kernel", st);
-    LLMC_KERNEL_GGL(lsh_zero_kernel, dim3((unsigned)((n_cnt + 255) / 256)), dim3(256), 0, st, cursor, n_cnt); }
+    LLMC_KERNEL_GGL(lsh_zero_kernel, dim3((unsigned)((n_cnt + 255) / 256)), dim3(256), 0, st, cursor, n_cnt, d_changed); }
   LLMC_LAUNCH_CHECK("lsh_zero_kernel");
   { ProfScope ps_("lsh_count_kernel", st);
     LLMC_KERNEL_GGL(lsh_count_kernel, dim3((unsigned)((n_pairs + 255) / 256)), dim3(256), 0, st, d_bank_bits, d_valid, N,
-                       W, L.bands, cursor); }
+                       W, L.bands, cursor, d_changed); }
   LLMC_LAUNCH_CHECK("lsh_count_kernel");
   { ProfScope ps_("lsh_scan_kernel", st);
-    LLMC_KERNEL_GGL(lsh_scan_kernel, dim3(L.bands), dim3(1024), 0, st, cursor, start); }
+    LLMC_KERNEL_GGL(lsh_scan_kernel, dim3(L.bands), dim3(1024), 0, st, cursor, start, d_changed); }
   LLMC_LAUNCH_CHECK("lsh_scan_kernel");
   { ProfScope ps_("lsh_scatter_kernel", st);
     LLMC_KERNEL_GGL(lsh_scatter_kernel, dim3((unsigned)((n_pairs + 255) / 256)), dim3(256), 0, st, d_bank_bits, d_valid,
-                       N, W, L.bands, cursor, order); }
+                       N, W, L.bands, cursor, order, d_changed); }
   LLMC_LAUNCH_CHECK("lsh_scatter_kernel");
   return LLMC_OK;
 }
 
 llmc_status_t launch_lsh_match(const uint32_t* d_bank_bits, int N, int k, const void* d_index,
                                const uint32_t* d_query_bits, int B, int max_hamming, int32_t* d_idx, int32_t* d_dist,
-                               uint8_t* d_hit, int32_t* d_compared, hipStream_t st) {
+                               uint8_t* d_hit, int32_t* d_compared, hipStream_t st, float* d_sim) {
   const LshLayout L = lsh_layout(N, k);
   const uint32_t* start = (const uint32_t*)((const char*)d_index + L.off_start);
   const int32_t* order = (const int32_t*)((const char*)d_index + L.off_order);
   const dim3 grid((B + 3) / 4), block(256);
   ProfScope ps_("lsh_match_kernel", st);
 #define LLMC_LSH_CASE(W_) LLMC_KERNEL_GGL(lsh_match_kernel<W_>, grid, block, 0, st, d_bank_bits, N, start, order, \
-                                             d_query_bits, B, max_hamming, d_idx, d_dist, d_hit, d_compared)
+                                             d_query_bits, B, max_hamming, d_idx, d_dist, d_hit, d_compared, d_sim)
   switch (k / 32) {
     case 2: LLMC_LSH_CASE(2); break;
     case 4: LLMC_LSH_CASE(4); break;

@@ -20,7 +20,7 @@ class GatedStack:
                  policy: int = llmc.EVICT_LRU, B: Optional[int] = None, half_life: int = 0, reval_every: int = 0,
                  drift_bound: float = 0.0, bases: Optional[List[Optional[torch.Tensor]]] = None,
                  keep_means: bool = False, keep_next_keys: bool = False, key_bits: bool = False,
-                 expose_keys: bool = False):
+                 expose_keys: bool = False, lsh: bool = False):
         self.cfg = cfg
         self.device = device
         self.B = cfg.B if B is None else B
@@ -40,7 +40,8 @@ class GatedStack:
                                       basis=None if bases is None or bases[l] is None else
                                       bases[l].to(device).contiguous(), keep_means=keep_means,
                                       next_proj=None if nxt is None else self.proj[nxt],
-                                      next_bias=None if nxt is None else self.bias[nxt], key_bits=key_bits)
+                                      next_bias=None if nxt is None else self.bias[nxt], key_bits=key_bits,
+                                      lsh=lsh)
         ws_bytes = llmc.llmc_layer_workspace_bytes(self.layers[0], self.B, cfg.S, cfg.k)
         self.workspace = torch.empty((ws_bytes,), dtype=torch.uint8, device=device)
         self.buf = [torch.empty((self.B, cfg.S, cfg.d), dtype=cfg.torch_dtype, device=device) for _ in range(2)]

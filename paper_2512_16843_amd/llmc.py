@@ -20,7 +20,7 @@ LLMC_OK = 0
 ERR_INVALID_ARG, ERR_SHAPE, ERR_DTYPE, ERR_BANK_FULL, ERR_WORKSPACE, ERR_HIP = 1, 2, 3, 4, 5, 6
 F32, BF16 = 0, 1
 EVICT_NONE, EVICT_LRU, EVICT_DECAYED_HITS = 0, 1, 2
-INSERT_ON_MISS, UPDATE_LRU, REVALIDATE, HINT_MOSTLY_CARRIED, DEFER_COPY, DEDUP = 1, 2, 4, 8, 16, 32
+INSERT_ON_MISS, UPDATE_LRU, REVALIDATE, HINT_MOSTLY_CARRIED, DEFER_COPY, DEDUP, LOOKUP_LSH = 1, 2, 4, 8, 16, 32, 64
 CNT_HIT, CNT_MISS, CNT_NEAR_TAU, CNT_NEAR_TIE, CNT_INSERTED, CNT_EVICTED, CNT_DROPPED = 0, 1, 2, 3, 4, 5, 6
 CNT_COMPUTED, CNT_REVALIDATED, CNT_DIVERGED, CNT_TIE_OVERFLOW, CNT_DEDUP, CNT_WORDS = 7, 8, 9, 10, 11, 12
 MAX_UPDATE_ROWS = 4096
@@ -46,7 +46,7 @@ class BankDesc(C.Structure):
                 ("drift_bound", C.c_float), ("rank", C.c_int32), ("d_basis", C.c_void_p),
                 ("d_act_pool", C.c_void_p), ("d_next_proj", C.c_void_p), ("d_next_bias", C.c_void_p),
                 ("next_k", C.c_int32), ("d_next_fp", C.c_void_p), ("d_next_inv", C.c_void_p),
-                ("key_bits", C.c_int32)]
+                ("key_bits", C.c_int32), ("d_lsh_index", C.c_void_p), ("lsh_index_bytes", C.c_size_t)]
 
 
 class LayerDesc(C.Structure):
@@ -170,7 +170,7 @@ class Bank:
                  act_slot: Optional[torch.Tensor] = None, half_life: int = 0, reval_every: int = 0,
                  drift_bound: float = 0.0, basis: Optional[torch.Tensor] = None, keep_means: bool = False,
                  next_proj: Optional[torch.Tensor] = None, next_bias: Optional[torch.Tensor] = None,
-                 key_bits: bool = False):
+                 key_bits: bool = False, lsh: bool = False):
         A = n_slots if n_act_slots is None else n_act_slots
         self.n_slots, self.k, self.S, self.d, self.n_act_slots = n_slots, k, S, d, A
         self.dtype = dtype
@@ -195,6 +195,9 @@ class Bank:
         self.policy = policy
         self.half_life = half_life
         self.reval_every, self.drift_bound = reval_every, drift_bound
+        # bucket index of sign-bit keys (kept current by the library)
+        self.lsh_index = torch.zeros((lib().llmc_lsh_index_bytes(n_slots, k),), dtype=torch.uint8, device=device) \
+            if (lsh and key_bits) else None
         self.handle = None
         self.create()
 
@@ -203,7 +206,8 @@ class Bank:
                         _ptr(self.fp), _ptr(self.act), _ptr(self.inv_norm), _ptr(self.act_slot),
                         _ptr(self.last_used), _ptr(self.hits), _ptr(self.valid), self.half_life, self.reval_every,
                         self.drift_bound, self.rank, _ptr(self.basis), _ptr(self.act_pool), _ptr(self.next_proj),
-                        _ptr(self.next_bias), self.next_k, _ptr(self.next_fp), _ptr(self.next_inv), 1 if self.key_bits else 0)
+                        _ptr(self.next_bias), self.next_k, _ptr(self.next_fp), _ptr(self.next_inv), 1 if self.key_bits else 0,
+                        _ptr(self.lsh_index), 0 if self.lsh_index is None else self.lsh_index.numel())
 
     def create(self) -> None:
         torch.cuda.synchronize()

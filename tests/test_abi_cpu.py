@@ -60,7 +60,7 @@ def test_bank_create_validation(lib):
     def desc(**kw):
         base = dict(n_slots=16, k=32, S=4, d=64, n_act_slots=16, dtype=llmc.BF16, policy=llmc.EVICT_LRU,
                     d_fp=p, d_act=p, d_inv_norm=p, d_act_slot=None, d_last_used=p, d_hits=p, d_valid=p, half_life=0, reval_every=0, drift_bound=0.0, rank=0, d_basis=None, d_act_pool=None, d_next_proj=None, d_next_bias=None, next_k=0, d_next_fp=None,
-                    d_next_inv=None, key_bits=0)
+                    d_next_inv=None, key_bits=0, d_lsh_index=None, lsh_index_bytes=0)
         base.update(kw)
         return llmc.BankDesc(**base)
 
@@ -75,6 +75,15 @@ def test_bank_create_validation(lib):
     assert lib.llmc_bank_create(C.byref(desc(d_next_proj=p, d_next_fp=p, d_next_inv=p, next_k=32)), C.byref(out)) == llmc.ERR_INVALID_ARG   # no means
     assert lib.llmc_bank_create(C.byref(desc(d_act_pool=p, d_next_proj=p, d_next_fp=p, d_next_inv=p, next_k=40)), C.byref(out)) == llmc.ERR_SHAPE
     assert lib.llmc_bank_create(C.byref(desc(key_bits=2)), C.byref(out)) == llmc.ERR_INVALID_ARG
+    # a bucket index: sign-bit keys only, k of 64 / 128 / 256 / 512, 256-byte aligned, large enough
+    need = lib.llmc_lsh_index_bytes(16, 64)
+    aligned = C.c_void_p(1 << 20)
+    assert lib.llmc_bank_create(C.byref(desc(k=64, d_lsh_index=aligned, lsh_index_bytes=need)), C.byref(out)) == llmc.ERR_INVALID_ARG
+    assert lib.llmc_bank_create(C.byref(desc(key_bits=1, d_lsh_index=aligned, lsh_index_bytes=1 << 30)), C.byref(out)) == llmc.ERR_SHAPE
+    assert lib.llmc_bank_create(C.byref(desc(k=64, key_bits=1, d_lsh_index=C.c_void_p((1 << 20) + 16), lsh_index_bytes=need)),
+                                C.byref(out)) == llmc.ERR_SHAPE
+    assert lib.llmc_bank_create(C.byref(desc(k=64, key_bits=1, d_lsh_index=aligned, lsh_index_bytes=need - 1)),
+                                C.byref(out)) == llmc.ERR_WORKSPACE
     assert lib.llmc_bank_create(C.byref(desc(d_inv_norm=None)), C.byref(out)) == llmc.ERR_INVALID_ARG
     assert lib.llmc_bank_create(C.byref(desc(rank=32, d_basis=p)), C.byref(out)) == llmc.ERR_SHAPE
     assert lib.llmc_bank_create(C.byref(desc(rank=128, d_basis=p)), C.byref(out)) == llmc.ERR_SHAPE            # above d = 64
@@ -107,7 +116,7 @@ def test_gated_layer_validation(lib):
     assert call(layer(d_w1=None)) == llmc.ERR_INVALID_ARG
     assert call(layer(), h_out=p) == llmc.ERR_INVALID_ARG        # in-place is refused
     assert call(layer(), tau=float("nan")) == llmc.ERR_INVALID_ARG
-    assert call(layer(), flags=64) == llmc.ERR_INVALID_ARG        # unknown flag bit
+    assert call(layer(), flags=128) == llmc.ERR_INVALID_ARG       # unknown flag bit
     assert call(layer(), tick=1 << 40) == llmc.ERR_INVALID_ARG
     assert call(layer(), B=0) == llmc.ERR_INVALID_ARG
     assert call(layer(), ws_bytes=16) == llmc.ERR_WORKSPACE

@@ -1112,19 +1112,23 @@ def test_carried_token_means_change_nothing(L, dtype):
         st.close()
 
 
+@pytest.mark.parametrize("lsh", [False, True], ids=["full", "bucketed"])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-def test_gated_stack_with_sign_bit_banks(L, dtype):
+def test_gated_stack_with_sign_bit_banks(L, dtype, lsh):
     """Banks of sign-bit keys inside the gated layer: keys, matched slots, distances' cosines, decisions, slots taken
-    and outputs against the oracle, layer by layer with the GPU's own layer inputs and bank arrays."""
+    and outputs against the oracle, layer by layer with the GPU's own layer inputs and bank arrays.  "bucketed": the
+    lookup goes through the bank's band buckets, which the library rebuilds after every batch that stored or
+    replaced keys (insertions into free slots, then evictions)."""
     from paper_2512_16843_amd.engine import GatedStack
-    say(f"gated stack with sign-bit banks {dtype}: build by insertion, resubmissions, near-duplicates, eviction")
+    say(f"gated stack with sign-bit banks {dtype} lsh={lsh}: build by insertion, resubmissions, near-duplicates, eviction")
     cfg = W.scaled(W.TINY_ENCODER, n_layers=2, B=8, n_bank=20) if dtype == "f32" else \
         W.scaled(W.BERT_BASE, n_layers=2, B=8, S=48, n_bank=20)
     tol = TOL[dtype]
     ws = W.make_layer_weights(cfg, seed=0)
     tok, pos = W.make_embeddings(cfg, seed=0)
     Ps = W.make_projection(cfg.d, cfg.k, cfg.torch_dtype, seed=3, n_layers=cfg.n_layers)
-    st = GatedStack(cfg, ws, Ps, key_bits=True, keep_means=True)
+    st = GatedStack(cfg, ws, Ps, key_bits=True, keep_means=True, lsh=lsh)
+    look = L.LOOKUP_LSH if lsh else 0
     wnp = [{k_: npf(v) for k_, v in w.items()} for w in ws]
     Pnp = [npf(p) for p in Ps]
     src = W.make_sources(cfg, 16, seed=1)
@@ -1146,9 +1150,10 @@ def test_gated_stack_with_sign_bit_banks(L, dtype):
             ob.last_used = b.last_used.cpu().numpy().astype(np.uint64)
             ob.hits = b.hits.cpu().numpy().astype(np.uint32)
             pre.append(ob)
-        outs = st.forward(h0, tau=tau, flags=flags, tick=tick, keep_all=True)
+        outs = st.forward(h0, tau=tau, flags=flags | look, tick=tick, keep_all=True)
         torch.cuda.synchronize()
-        oflags = (O.FLAG_UPDATE_LRU if flags & L.UPDATE_LRU else 0) | (O.FLAG_INSERT_ON_MISS if flags & L.INSERT_ON_MISS else 0)
+        oflags = (O.FLAG_UPDATE_LRU if flags & L.UPDATE_LRU else 0) | (O.FLAG_INSERT_ON_MISS if flags & L.INSERT_ON_MISS else 0) \
+            | (O.FLAG_LOOKUP_LSH if lsh else 0)
         for l in range(cfg.n_layers):
             h_prev = npf(h0 if l == 0 else outs[l - 1])
             ob = pre[l]
