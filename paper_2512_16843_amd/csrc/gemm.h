@@ -212,7 +212,16 @@ __global__ __launch_bounds__(C::THREADS) void gemm_bf16_dma_kernel(GemmArgs g, i
   for (int it = g.xcd_chunks ? slot : (int)blockIdx.x; it < n_it; it += g.xcd_chunks ? slots : (int)gridDim.x) {
   const int tile = g.xcd_chunks ? xcd * per_xcd + it : it;
   if (tile >= total) break;
-  const int tile_m = tile / tiles_n, tile_n = tile % tiles_n;
+  int tile_m = tile / tiles_n, tile_n = tile % tiles_n;
+  if (g.xcd_chunks == 2) {
+    // grouped order: the list runs down 8 row blocks before it moves one column tile on, so the 64 tiles that an
+    // XCD's workgroups hold at one time are 8 row blocks x 8 column tiles: 8 + 8 operand panels (3 MB) in its L2
+    const int tiles_m = (M + C::BM - 1) / C::BM;
+    const int group = tile / (8 * tiles_n), in_group = tile % (8 * tiles_n);
+    const int rows_in_group = min(8, tiles_m - group * 8);
+    tile_m = group * 8 + in_group % rows_in_group;
+    tile_n = in_group / rows_in_group;
+  }
   const int m0 = tile_m * C::BM, n0 = tile_n * C::BN;
   const uint16_t* A = (const uint16_t*)g.A;
   const uint16_t* W = (const uint16_t*)g.W;

@@ -94,7 +94,7 @@ static llmc_status_t launch_gemm(const GemmArgs& g, int dtype, hipStream_t st) {
       const int tiles_n = (g.N + C::BN - 1) / C::BN;
       const int tiles_m = (g.max_seqs * g.S + C::BM - 1) / C::BM;
       GemmArgs a = g;
-      a.xcd_chunks = tiles_n <= 8 ? 1 : 0;   // narrow outputs gain from keeping a row block in one XCD's L2
+      a.xcd_chunks = tiles_n <= 8 ? 1 : 2;   // every XCD walks its own eighth of the tile list; wide outputs in grouped order
       ProfScope ps_("gemm_bf16_kernel", st);
       LLMC_KERNEL_GGL(gemm_bf16_dma_kernel<C>, dim3(std::min((tiles_m * tiles_n + 7) & ~7, kMaxGrid)), dim3(C::THREADS),
                          gemm_dma_smem_bytes<C>(), st, a, tiles_n);

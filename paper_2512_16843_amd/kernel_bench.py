@@ -9,6 +9,12 @@ under `rocprofv3 --pmc FETCH_SIZE` (or WRITE_SIZE) that copy is the reference ag
 which the byte counters of the other kernels are scaled.
 
     python -m paper_2512_16843_amd.kernel_bench --B 64 --S 384 --d 768 --k 256 --N 16384
+
+With --dense-rows R it runs, instead, the miss path alone: one post-LayerNorm encoder block
+(d, d / 64 heads, FFN 4 d, erf-GELU) over R sequences of S tokens, i.e. the four linear
+layers, the attention and the two LayerNorms that a cache-gated layer launches for R misses.
+
+    python -m paper_2512_16843_amd.kernel_bench --dense-rows 28
 """
 import argparse
 import json
@@ -30,6 +36,8 @@ def main():
     ap.add_argument("--N", type=int, default=16384)
     ap.add_argument("--act-slots", type=int, default=2048, help="distinct cached-output rows (keys share them)")
     ap.add_argument("--iters", type=int, default=5)
+    ap.add_argument("--dense-rows", type=int, default=0,
+                    help="run the dense block of the miss path over this many sequences instead of the gate's kernels")
     args = ap.parse_args()
     B, S, d, k, N, A = args.B, args.S, args.d, args.k, args.N, min(args.act_slots, args.N)
     dev, dt = "cuda", torch.bfloat16
@@ -41,6 +49,9 @@ def main():
     for _ in range(3):
         cal_dst.copy_(cal_src)
     torch.cuda.synchronize()
+    if args.dense_rows > 0:
+        dense(args)
+        return
 
     # several distinct inputs so that repeated launches do not re-read a cache-resident tensor
     hs = [torch.randn((B, S, d), device=dev, dtype=torch.float32).to(dt) for _ in range(args.iters)]
@@ -94,6 +105,41 @@ def main():
                                 "algorithmic_bytes": by}
         print("%-24s avg %9.2f us  %9.1f GB/s  %8.2f TFLOP/s" % (name, us, by / us / 1e3, fl / us / 1e6), file=sys.stderr)
     bank.close()
+    print(json.dumps(res))
+
+
+def dense(args):
+    from . import workloads as W
+    from .engine import GatedStack
+    R, S, d = args.dense_rows, args.S, args.d
+    cfg = W.scaled(W.BERT_BASE, n_layers=1, B=R, S=S, d=d, n_heads=d // 64, d_ff=4 * d)
+    ws = W.make_layer_weights(cfg, seed=0)
+    Ps = W.make_projection(cfg.d, cfg.k, cfg.torch_dtype, seed=3, n_layers=1)
+    st = GatedStack(cfg, ws, Ps, cached_layers=[])
+    hs = [(torch.randn((R, S, d), device="cuda") * 0.5).to(cfg.torch_dtype) for _ in range(args.iters)]
+    st.forward(hs[0], tau=2.0)
+    torch.cuda.synchronize()
+    llmc.llmc_profile_begin(16 * args.iters)
+    for i in range(args.iters):
+        st.forward(hs[i], tau=2.0)
+    rep = llmc.llmc_profile_report()
+    llmc.llmc_profile_end()
+    T, e = float(R * S), 2
+    work = {   # (flops, bytes) per launch, averaged over the launches of one block
+        "gemm_bf16_kernel": (2.0 * T * d * 12 * d / 4, (T * d * e * (1 + 3 + 1 + 2 + 1 + 4 + 4 + 2) + 12.0 * d * d * e) / 4),
+        "attention_kernel": (4.0 * R * S * S * d, T * d * e * 4),
+        "layernorm_kernel": (8.0 * T * d, 2.0 * T * d * e),
+    }
+    res = {"shape": {"rows": R, "S": S, "d": d, "d_ff": 4 * d}, "calib_copy_bytes": CALIB_COPY_BYTES, "kernels": {}}
+    for name, (cnt, ms) in sorted(rep.items()):
+        us = ms * 1e3 / cnt
+        fl, by = work.get(name, (0.0, 0.0))
+        res["kernels"][name] = {"launches_per_block": cnt // args.iters, "avg_us": round(us, 2),
+                                "gbs": round(by / us / 1e3, 1), "tflops": round(fl / us / 1e6, 2),
+                                "algorithmic_bytes": by}
+        print("%-24s %2d per block  avg %9.2f us  %9.1f GB/s  %8.2f TFLOP/s"
+              % (name, cnt // args.iters, us, by / us / 1e3, fl / us / 1e6), file=sys.stderr)
+    st.close()
     print(json.dumps(res))
 
 

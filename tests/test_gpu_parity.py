@@ -1562,21 +1562,24 @@ def test_large_batch_equals_its_halves(L):
         st.close()
 
 
+@pytest.mark.parametrize("carry", [False, True], ids=["plain", "carried"])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-def test_within_batch_reuse_against_oracle(L, dtype):
+def test_within_batch_reuse_against_oracle(L, dtype, carry):
     """LLMC_DEDUP: rows of a batch that miss the bank follow an earlier, similar row of the same batch instead of
     being computed and stored again (Algorithm 1 applied to the rows in order).  Leaders, followers, slots, counters,
     bank metadata and outputs against the oracle, layer by layer with the GPU's own layer inputs, keys and bank
-    arrays, over batches that fill the banks and then evict."""
+    arrays, over batches that fill the banks and then evict.  "carried": the banks also store token means and
+    next-layer keys, so rows reach the second layer carried (hits), pooled by the block (leaders) or neither
+    (followers, whose rows are written after the block ran)."""
     from paper_2512_16843_amd.engine import GatedStack
-    say(f"within-batch reuse {dtype}: duplicates and near-duplicates inside batches, insertion + LRU, eviction")
+    say(f"within-batch reuse {dtype} carry={carry}: duplicates and near-duplicates inside batches, insertion + LRU, eviction")
     cfg = W.scaled(W.TINY_ENCODER, n_layers=2, B=8, n_bank=12) if dtype == "f32" else \
         W.scaled(W.BERT_BASE, n_layers=2, B=8, S=48, n_bank=12)
     tol = TOL[dtype]
     ws = W.make_layer_weights(cfg, seed=0)
     tok, pos = W.make_embeddings(cfg, seed=0)
     Ps = W.make_projection(cfg.d, cfg.k, cfg.torch_dtype, seed=3, n_layers=cfg.n_layers)
-    st = GatedStack(cfg, ws, Ps, expose_keys=True)
+    st = GatedStack(cfg, ws, Ps, expose_keys=True, keep_means=carry, keep_next_keys=carry)
     wnp = [{k_: npf(v) for k_, v in w.items()} for w in ws]
     src = W.make_sources(cfg, 16, seed=1)
     near, _ = W.make_substitution_queries(W.scaled(cfg, B=4), src[:4], n_dup=4, n_subst=1, seed=5)
