@@ -257,6 +257,51 @@ def layer_forward(x: np.ndarray, w: Dict[str, np.ndarray], arch: int, n_heads: i
 
 
 # ----------------------------------------------------------------------------
+# fingerprint with prefix attention statistics (Section IV-B, second feature)
+# ----------------------------------------------------------------------------
+
+def prefix_attention_mean(h: np.ndarray, w: Dict[str, np.ndarray], arch: int, n_heads: int, eps: float,
+                          n_prefix: int) -> np.ndarray:
+    """Section IV-B lists, beside the token average, the mean of the initial self-attention outputs as a
+    fingerprint feature.  Reading taken here: for each sequence of ``h [B, S, d]`` the layer's own self-attention
+    sub-layer is applied to the first ``n_prefix`` tokens ALONE (they attend to each other only; causal in the
+    decoder block, after LN1 in the pre-LayerNorm block), and its outputs (after the output projection, before
+    the residual) are averaged over those tokens.  Returns a [B, d] float64."""
+    h = np.asarray(h, dtype=np.float64)
+    w = _w64(w)
+    B, S, d = h.shape
+    assert 1 <= n_prefix <= S
+    out = np.empty((B, d), dtype=np.float64)
+    for b in range(B):
+        x = h[b, :n_prefix]
+        if arch == DECODER_PRE_LN:
+            x = layer_norm(x, w["ln1_g"], w["ln1_b"], eps)
+        a = attention(x, w["wqkv"], w["bqkv"], w["wo"], w["bo"], n_heads, causal=(arch == DECODER_PRE_LN))
+        out[b] = a.sum(axis=0) / float(n_prefix)
+    return out
+
+
+def fingerprint_prefix(h: np.ndarray, P2: np.ndarray, c: Optional[np.ndarray], dtype: str, w: Dict[str, np.ndarray],
+                       arch: int, n_heads: int, eps: float, n_prefix: int) -> Tuple[np.ndarray, np.ndarray]:
+    """Fingerprint over the two features of Section IV-B: the token average p [d] and the prefix attention mean
+    a [d], reduced together by one linear map: v = P2^T [p; a] + c with P2 [2 d, k]; normalisation, rounding and
+    the inverse norm as in ``fingerprint``."""
+    h = np.asarray(h, dtype=np.float64)
+    P2 = np.asarray(P2, dtype=np.float64)
+    B, S, d = h.shape
+    assert P2.shape[0] == 2 * d
+    p = h.sum(axis=1) / float(S)
+    a = prefix_attention_mean(h, w, arch, n_heads, eps, n_prefix)
+    v = np.concatenate([p, a], axis=1) @ P2
+    if c is not None:
+        v = v + np.asarray(c, dtype=np.float64)[None, :]
+    nrm = np.sqrt((v * v).sum(axis=1))
+    u = v / np.maximum(nrm, NORM_FLOOR)[:, None]
+    q = round_to_storage(u, dtype)
+    return q, inv_norm(q)
+
+
+# ----------------------------------------------------------------------------
 # the bank C_l (Section III-B) with insertion and LRU (Sections III-E, IV-D)
 # ----------------------------------------------------------------------------
 # sign-bit keys (Section IV-B "SimHash"; Section III-A "MinHash or SimHash-based

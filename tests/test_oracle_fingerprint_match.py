@@ -255,3 +255,102 @@ def test_near_tie_sets_equal_brute_force(seed):
             assert sets[b].tolist() == want, (gap, b)
     assert len(O.near_tie_sets(q, qinv, bank, binv, valid, gap=0.3)[0]) >= 2      # slot 3 and its duplicate at least
     assert any(len(s_) > 2 for s_ in O.near_tie_sets(q, qinv, bank, binv, valid, gap=0.3))
+
+
+# ---- fingerprint with prefix attention statistics (Section IV-B, second feature) ---------------------------
+
+def _toy_block(g, d, scale=0.3):
+    return {"wqkv": g.standard_normal((3 * d, d)) * scale, "bqkv": g.standard_normal(3 * d) * 0.1,
+            "wo": g.standard_normal((d, d)) * scale, "bo": g.standard_normal(d) * 0.1,
+            "w1": g.standard_normal((2 * d, d)) * scale, "b1": np.zeros(2 * d),
+            "w2": g.standard_normal((d, 2 * d)) * scale, "b2": np.zeros(d),
+            "ln1_g": 1.0 + 0.1 * g.standard_normal(d), "ln1_b": 0.1 * g.standard_normal(d),
+            "ln2_g": np.ones(d), "ln2_b": np.zeros(d)}
+
+
+@pytest.mark.parametrize("arch", [O.ENCODER_POST_LN, O.DECODER_PRE_LN])
+def test_prefix_attention_mean_against_the_library_attention(arch):
+    """The prefix feature against torch.nn.functional.multi_head_attention_forward (float64) run on the prefix
+    tokens alone, and -- for the causal block -- against the first rows of the attention over the WHOLE sequence,
+    which a causal mask makes independent of the later tokens."""
+    import torch
+    import torch.nn.functional as F
+    g = rng(21)
+    B, S, d, H, n_p, eps = 3, 12, 16, 2, 5, 1e-5
+    w = _toy_block(g, d)
+    h = g.standard_normal((B, S, d))
+    got = O.prefix_attention_mean(h, w, arch, H, eps, n_p)
+    t = {k: torch.from_numpy(np.asarray(v, dtype=np.float64)) for k, v in w.items()}
+    for b in range(B):
+        x = torch.from_numpy(h[b, :n_p])
+        mask = None
+        if arch == O.DECODER_PRE_LN:
+            x = F.layer_norm(x, (d,), t["ln1_g"], t["ln1_b"], eps)
+            mask = torch.triu(torch.full((n_p, n_p), float("-inf"), dtype=torch.float64), diagonal=1)
+        out, _ = F.multi_head_attention_forward(x.unsqueeze(1), x.unsqueeze(1), x.unsqueeze(1), d, H, t["wqkv"], t["bqkv"],
+                                                None, None, False, 0.0, t["wo"], t["bo"], training=False,
+                                                need_weights=False, attn_mask=mask)
+        np.testing.assert_allclose(got[b], out.squeeze(1).mean(dim=0).numpy(), rtol=0, atol=1e-12)
+    if arch == O.DECODER_PRE_LN:
+        for b in range(B):
+            xl = O.layer_norm(h[b], w["ln1_g"], w["ln1_b"], eps)
+            full = O.attention(xl, w["wqkv"], w["bqkv"], w["wo"], w["bo"], H, causal=True)
+            np.testing.assert_allclose(got[b], full[:n_p].mean(axis=0), rtol=0, atol=1e-12)
+        # ... and so tokens after the prefix do not move the feature at all
+        h2 = h.copy()
+        h2[:, n_p:] = g.standard_normal((B, S - n_p, d))
+        assert np.array_equal(O.prefix_attention_mean(h2, w, arch, H, eps, n_p), got)
+    else:
+        # the bidirectional block: with the whole sequence as prefix the feature is the mean of the block's attention
+        full = O.attention(h[0], w["wqkv"], w["bqkv"], w["wo"], w["bo"], H, causal=False)
+        np.testing.assert_allclose(O.prefix_attention_mean(h[:1], w, arch, H, eps, S)[0], full.mean(axis=0), atol=1e-12)
+
+
+def test_fingerprint_prefix_reduces_to_the_plain_fingerprint_and_to_a_hand_computation():
+    g = rng(22)
+    B, S, d, k, H, n_p = 4, 9, 16, 32, 2, 4
+    w = _toy_block(g, d)
+    h = g.standard_normal((B, S, d))
+    P = g.standard_normal((d, k)) / np.sqrt(k)
+    Pa = g.standard_normal((d, k)) / np.sqrt(k)
+    c = g.standard_normal(k) * 0.05
+    # a zero map for the attention feature: the plain fingerprint, bit for bit
+    q0, i0 = O.fingerprint_prefix(h, np.concatenate([P, np.zeros((d, k))]), c, "f32", w, O.ENCODER_POST_LN, H, 1e-5, n_p)
+    q1, i1 = O.fingerprint(h, P, c, "f32")
+    assert np.array_equal(q0, q1) and np.array_equal(i0, i1)
+    # both features: written out by hand
+    a = O.prefix_attention_mean(h, w, O.ENCODER_POST_LN, H, 1e-5, n_p)
+    v = h.mean(axis=1) @ P + a @ Pa + c
+    u = v / np.linalg.norm(v, axis=1, keepdims=True)
+    q2, i2 = O.fingerprint_prefix(h, np.concatenate([P, Pa]), c, "f32", w, O.ENCODER_POST_LN, H, 1e-5, n_p)
+    np.testing.assert_allclose(q2, u.astype(np.float32), rtol=0, atol=1e-7)
+    np.testing.assert_allclose(i2, 1.0 / np.linalg.norm(q2.astype(np.float64), axis=1), rtol=1e-6)
+    # a dropped or swapped feature would show: the key moves when only the attention map changes
+    q3, _ = O.fingerprint_prefix(h, np.concatenate([P, -Pa]), c, "f32", w, O.ENCODER_POST_LN, H, 1e-5, n_p)
+    assert np.abs(q3 - q2).max() > 1e-3
+    # bf16 storage: the rounded key of the same vector
+    q4, _ = O.fingerprint_prefix(h, np.concatenate([P, Pa]), c, "bf16", w, O.ENCODER_POST_LN, H, 1e-5, n_p)
+    assert np.array_equal(q4, O.round_to_bf16(u))
+
+
+def test_prefix_feature_is_shared_by_inputs_with_a_common_prefix():
+    """What the feature is for: two inputs of a causal model that share their first tokens have the same prefix
+    attention mean whatever follows, while their token averages differ; the key with the attention feature is
+    therefore closer for them than the key without it when the maps weigh the two features alike."""
+    g = rng(23)
+    S, d, k, H, n_p = 16, 16, 64, 2, 6
+    w = _toy_block(g, d)
+    a_in = g.standard_normal((1, S, d))
+    b_in = a_in.copy()
+    b_in[:, n_p:] = g.standard_normal((1, S - n_p, d))
+    fa = O.prefix_attention_mean(a_in, w, O.DECODER_PRE_LN, H, 1e-5, n_p)
+    fb = O.prefix_attention_mean(b_in, w, O.DECODER_PRE_LN, H, 1e-5, n_p)
+    assert np.array_equal(fa, fb)
+    P = g.standard_normal((d, k)) / np.sqrt(k)
+    Pa = 4.0 * g.standard_normal((d, k)) / np.sqrt(k)
+    def cos(x, y):
+        return float((x.astype(np.float64) @ y.astype(np.float64).T)[0, 0] / np.linalg.norm(x) / np.linalg.norm(y))
+    plain = cos(O.fingerprint(a_in, P, None, "f32")[0], O.fingerprint(b_in, P, None, "f32")[0])
+    both = cos(O.fingerprint_prefix(a_in, np.concatenate([P, Pa]), None, "f32", w, O.DECODER_PRE_LN, H, 1e-5, n_p)[0],
+               O.fingerprint_prefix(b_in, np.concatenate([P, Pa]), None, "f32", w, O.DECODER_PRE_LN, H, 1e-5, n_p)[0])
+    assert both > plain
