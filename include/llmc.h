@@ -421,6 +421,28 @@ llmc_status_t llmc_fingerprint_bits(const void* d_h, int32_t B, int32_t S, int32
                                     llmc_stream_t stream);
 
 /*
+ * Section IV-B, the second fingerprint feature ("prefix attention stats": the mean of the initial self-attention
+ * outputs), taken together with the first (the token average) and reduced by ONE linear map:
+ *   p = mean_t h[b, t, :]                                            (as in llmc_fingerprint)
+ *   a = mean_{t < n_prefix} MHA_l(h[b, 0 .. n_prefix, :])[t, :]      the block's own self-attention sub-layer over the
+ *       first n_prefix tokens ALONE (they attend to each other only; after LN1 and causal in the pre-LayerNorm decoder
+ *       block), outputs taken after the output projection and before the residual
+ *   v = P2^T [p; a] + c,  P2 [2 d, k] row-major (rows 0 .. d-1 act on p, rows d .. 2d-1 on a);  key = v / |v| rounded
+ *       to the element type, inv_norm = 1 / |rounded key|, exactly as llmc_fingerprint does.
+ * For a causal block the feature depends on the first n_prefix tokens only, so inputs sharing a prefix share it.
+ *   layer: the block whose attention weights are used (its dtype is the element type of d_h, d_proj2 and d_fp_out)
+ *   d_h [B, S, d], d_proj2 [2 d, k], d_bias [k] fp32 or NULL, d_fp_out [B, k], d_inv_norm_out [B] fp32: device memory
+ *   of the caller; d_workspace: llmc_fingerprint_prefix_workspace_bytes(layer, B, S, n_prefix) bytes, 256-byte aligned.
+ * The keys are for llmc_match / llmc_bank_insert or for llmc_layer_forward_gated's d_fp_given.  Nothing is allocated
+ * or synchronised.  Errors: INVALID_ARG (null, n_prefix outside 1..S), SHAPE (layer, k, alignment), DTYPE, WORKSPACE.
+ */
+llmc_status_t llmc_fingerprint_prefix(const llmc_layer_desc_t* layer, const void* d_h, int32_t B, int32_t S,
+                                      int32_t n_prefix, const void* d_proj2, const float* d_bias, int32_t k,
+                                      void* d_fp_out, float* d_inv_norm_out, void* d_workspace,
+                                      size_t workspace_bytes, llmc_stream_t stream);
+size_t llmc_fingerprint_prefix_workspace_bytes(const llmc_layer_desc_t* layer, int32_t B, int32_t S, int32_t n_prefix);
+
+/*
  * Section IV-B "compared via cosine similarity or LSH", with the test of the case equation
  * (Section IV-A): for each query key the valid bank key at the smallest Hamming distance H;
  * cos(pi H / k) stands for the cosine of the two pooled inputs, so  sim > tau  becomes

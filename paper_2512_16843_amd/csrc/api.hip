@@ -270,6 +270,33 @@ llmc_status_t llmc_fingerprint(const void* d_h, int32_t B, int32_t S, int32_t d,
                             (hipStream_t)stream);
 }
 
+size_t llmc_fingerprint_prefix_workspace_bytes(const llmc_layer_desc_t* layer, int32_t B, int32_t S, int32_t n_prefix) {
+  if (!layer || check_layer(layer) != LLMC_OK || B <= 0 || S <= 0 || n_prefix <= 0 || n_prefix > S) return 0;
+  return align_up((size_t)B * 2 * layer->d * sizeof(float), 256) + prefix_attention_ws_bytes(layer, B, n_prefix);
+}
+
+llmc_status_t llmc_fingerprint_prefix(const llmc_layer_desc_t* layer, const void* d_h, int32_t B, int32_t S,
+                                      int32_t n_prefix, const void* d_proj2, const float* d_bias, int32_t k,
+                                      void* d_fp_out, float* d_inv_norm_out, void* d_workspace, size_t workspace_bytes,
+                                      llmc_stream_t stream) {
+  REQUIRE(layer && d_h && d_proj2 && d_fp_out && d_inv_norm_out, LLMC_ERR_INVALID_ARG, "NULL argument");
+  LLMC_TRY(check_layer(layer));
+  LLMC_TRY(check_fp_shape(B, S, layer->d, layer->dtype, k));
+  REQUIRE(n_prefix >= 1 && n_prefix <= S, LLMC_ERR_INVALID_ARG, "n_prefix=%d must lie in 1..S=%d", n_prefix, S);
+  REQUIRE(2 * layer->d <= 8192, LLMC_ERR_SHAPE, "d=%d: the two features together exceed 8192 values", layer->d);
+  REQUIRE(aligned16(d_h) && aligned16(d_proj2) && aligned16(d_fp_out), LLMC_ERR_SHAPE, "arrays must be 16-byte aligned");
+  const size_t need = llmc_fingerprint_prefix_workspace_bytes(layer, B, S, n_prefix);
+  REQUIRE(d_workspace && workspace_bytes >= need, LLMC_ERR_WORKSPACE, "prefix fingerprint workspace needs %zu bytes", need);
+  REQUIRE(((uintptr_t)d_workspace & 255) == 0, LLMC_ERR_SHAPE, "workspace must be 256-byte aligned");
+  hipStream_t st = (hipStream_t)stream;
+  const int d = layer->d;
+  float* feat = (float*)d_workspace;                                                   // [B, 2 d]: token mean | prefix attention mean
+  void* ws_attn = (char*)d_workspace + align_up((size_t)B * 2 * d * sizeof(float), 256);
+  LLMC_TRY(launch_pool_rows(d_h, B, S, d, layer->dtype, nullptr, nullptr, nullptr, feat, st, 2 * d));
+  LLMC_TRY(launch_prefix_attention_mean(layer, d_h, B, S, n_prefix, ws_attn, feat + d, 2 * d, st));
+  return launch_project_rows(feat, B, 2 * d, layer->dtype, d_proj2, d_bias, k, nullptr, nullptr, d_fp_out, d_inv_norm_out, st);
+}
+
 llmc_status_t llmc_fingerprint_bits(const void* d_h, int32_t B, int32_t S, int32_t d, int32_t dtype, const void* d_proj,
                                     const float* d_bias, int32_t k, uint32_t* d_bits_out, void* d_workspace,
                                     size_t workspace_bytes, llmc_stream_t stream) {

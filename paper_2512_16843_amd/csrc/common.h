@@ -181,8 +181,10 @@ llmc_status_t launch_fingerprint(const void* d_h, const int32_t* d_rowmap_unused
 llmc_status_t launch_project_rows(const float* d_means, int n_max, int d, int dtype, const void* d_proj,
                                   const float* d_bias, int k, const int32_t* d_rows, const int32_t* d_count, void* d_fp,
                                   float* d_inv, hipStream_t st);
+// ld_out: floats between consecutive output rows (0: d)
 llmc_status_t launch_pool_rows(const void* d_h, int n_max, int S, int d, int dtype, const int32_t* d_rows,
-                               const int32_t* d_count, const int32_t* d_dst, float* d_out, hipStream_t st);
+                               const int32_t* d_count, const int32_t* d_dst, float* d_out, hipStream_t st,
+                               int ld_out = 0);
 llmc_status_t launch_fingerprint_bits(const void* d_h, int B, int S, int d, int dtype, const void* d_proj,
                                       const float* d_bias, int k, uint32_t* d_bits, void* ws, hipStream_t st,
                                       const float* pooled_in = nullptr, const uint8_t* pooled_valid = nullptr,
@@ -265,6 +267,11 @@ llmc_status_t launch_linear(const void* A, int lda, const int32_t* a_rows, const
 // bf16 softmax attention on the matrix cores (head size 64): qkv [T, 3d] -> ctx [T, d]; sequences beyond *count skipped
 llmc_status_t launch_attention_bf16(const void* qkv, void* ctx, int S, int d, int n_heads, bool causal,
                                     const int32_t* count, int max_seqs, hipStream_t st);
+// Section IV-B, prefix attention statistics: the block's self-attention sub-layer run over the first n_prefix tokens of
+// every sequence alone; the mean of its outputs over those tokens goes to out[b * ld_out ..] [d] fp32
+size_t prefix_attention_ws_bytes(const llmc_layer_desc_t* L, int B, int n_prefix);
+llmc_status_t launch_prefix_attention_mean(const llmc_layer_desc_t* L, const void* d_h, int B, int S, int n_prefix,
+                                           void* ws, float* d_out, int ld_out, hipStream_t st);
 llmc_status_t launch_layer(const llmc_layer_desc_t* L, const void* d_h_in, void* d_h_out, int B, int S,
                            const int32_t* d_rows, const int32_t* d_count, void* ws, hipStream_t st,
                            float* pool_partial = nullptr, uint8_t* pooled_flags = nullptr);

@@ -319,7 +319,7 @@ __global__ void inv_norm_kernel(const T* __restrict__ fp, int64_t n, int k, floa
 template <typename T>
 __global__ void pool_direct_kernel(const T* __restrict__ h, int S, int d, int G, int R, const int32_t* __restrict__ rows,
                                    const int32_t* __restrict__ count, const int32_t* __restrict__ dst,
-                                   float* __restrict__ out) {
+                                   float* __restrict__ out, int ld_out) {
   constexpr int VEC = Vec16<T>::N;
   extern __shared__ float red[];  // [R][d]
   const int b = blockIdx.x;
@@ -332,7 +332,7 @@ __global__ void pool_direct_kernel(const T* __restrict__ h, int S, int d, int G,
   if ((int)threadIdx.x < G) {
     const float inv_S = 1.0f / (float)S;
 #pragma unroll
-    for (int i = 0; i < VEC; ++i) out[(size_t)o * d + threadIdx.x * VEC + i] = total[i] * inv_S;
+    for (int i = 0; i < VEC; ++i) out[(size_t)o * ld_out + threadIdx.x * VEC + i] = total[i] * inv_S;
   }
 }
 
@@ -414,25 +414,25 @@ llmc_status_t launch_project_rows(const float* d_means, int n_max, int d, int dt
                                 d_inv, st);
 }
 
-// token means of the sequences rows[0 .. *count) (or 0 .. n_max) of h, written to out[dst[i] or i] [d] fp32
+// token means of the sequences rows[0 .. *count) (or 0 .. n_max) of h, written to out[(dst[i] or i) * ld_out ..] fp32
 template <typename T>
 static llmc_status_t pool_rows_t(const T* h, int n_max, int S, int d, const int32_t* rows, const int32_t* count,
-                                 const int32_t* dst, float* out, hipStream_t st) {
+                                 const int32_t* dst, float* out, hipStream_t st, int ld_out) {
   constexpr int VEC = Vec16<T>::N;
   const int G = d / VEC;
   const int R = pool_row_groups(G);
   { ProfScope ps_("pool_direct_kernel", st);
     LLMC_KERNEL_GGL(pool_direct_kernel<T>, dim3(n_max), dim3(G * R), (size_t)R * d * sizeof(float), st, h, S, d, G, R,
-                       rows, count, dst, out); }
+                       rows, count, dst, out, ld_out > 0 ? ld_out : d); }
   LLMC_LAUNCH_CHECK("pool_direct_kernel");
   return LLMC_OK;
 }
 
 llmc_status_t launch_pool_rows(const void* d_h, int n_max, int S, int d, int dtype, const int32_t* d_rows,
-                               const int32_t* d_count, const int32_t* d_dst, float* d_out, hipStream_t st) {
+                               const int32_t* d_count, const int32_t* d_dst, float* d_out, hipStream_t st, int ld_out) {
   if (dtype == LLMC_F32)
-    return pool_rows_t<float>((const float*)d_h, n_max, S, d, d_rows, d_count, d_dst, d_out, st);
-  return pool_rows_t<bf16_t>((const bf16_t*)d_h, n_max, S, d, d_rows, d_count, d_dst, d_out, st);
+    return pool_rows_t<float>((const float*)d_h, n_max, S, d, d_rows, d_count, d_dst, d_out, st, ld_out);
+  return pool_rows_t<bf16_t>((const bf16_t*)d_h, n_max, S, d, d_rows, d_count, d_dst, d_out, st, ld_out);
 }
 
 // same pooling and projection, but the key is the sign of each projection

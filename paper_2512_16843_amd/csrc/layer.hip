@@ -475,6 +475,61 @@ static llmc_status_t layer_t(const llmc_layer_desc_t* L, const void* h_in, void*
   return LLMC_OK;
 }
 
+// ---- prefix attention statistics (Section IV-B): MHA over the first tokens of every sequence ----------------------
+// out[b][t][:] = in[b][t][:] for t < n_prefix; one workgroup per token row, 16-byte vectors
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+__global__ __launch_bounds__(256) void prefix_copy_kernel(const u32x4_t* __restrict__ in, u32x4_t* __restrict__ out,
+                                                          int S, int n_prefix, int vec_per_row) {
+  const int b = blockIdx.x / n_prefix, t = blockIdx.x % n_prefix;
+  const u32x4_t* src = in + ((size_t)b * S + t) * vec_per_row;
+  u32x4_t* dst = out + (size_t)blockIdx.x * vec_per_row;
+  for (int v = threadIdx.x; v < vec_per_row; v += 256) dst[v] = src[v];
+}
+
+size_t prefix_attention_ws_bytes(const llmc_layer_desc_t* L, int B, int n_prefix) {
+  const size_t T = (size_t)B * n_prefix, e = elem_size(L->dtype);
+  return align_up(T * 3 * L->d * e, 256) + 3 * align_up(T * L->d * e, 256);
+}
+
+template <typename T>
+static llmc_status_t prefix_attention_t(const llmc_layer_desc_t* L, const void* h, int B, int S, int n_p, void* ws,
+                                        float* out, int ld_out, hipStream_t st) {
+  const int d = L->d;
+  const size_t Tn = (size_t)B * n_p, e = sizeof(T);
+  char* p = (char*)ws;
+  void* qkv = p; p += align_up(Tn * 3 * d * e, 256);
+  void* x = p;   p += align_up(Tn * d * e, 256);
+  void* ctx = p; p += align_up(Tn * d * e, 256);
+  void* ao = p;
+  { ProfScope ps_("prefix_copy_kernel", st);
+    LLMC_KERNEL_GGL(prefix_copy_kernel, dim3((unsigned)Tn), dim3(256), 0, st, (const u32x4_t*)h, (u32x4_t*)x, S, n_p,
+                    (int)((size_t)d * e / 16)); }
+  LLMC_LAUNCH_CHECK("prefix_copy_kernel");
+  const void* a_in = x;
+  if (L->arch == 1) {       // the pre-LayerNorm block attends over LN1(x)
+    LLMC_TRY(launch_ln<T>(x, nullptr, ctx, nullptr, L->d_ln1_g, L->d_ln1_b, L->ln_eps, d, n_p, nullptr, B, st));
+    a_in = ctx;
+  }
+  GemmArgs g{};
+  g.S = n_p; g.count = nullptr; g.max_seqs = B; g.act = 0; g.resid = nullptr; g.r_rows = nullptr; g.a_rows = nullptr;
+  g.o_rows = nullptr;
+  GemmArgs a = g;
+  a.A = a_in; a.lda = d; a.W = L->d_wqkv; a.bias = L->d_bqkv; a.N = 3 * d; a.K = d; a.ldr = 3 * d; a.out = qkv; a.ldo = 3 * d;
+  LLMC_TRY(launch_gemm(a, L->dtype, st));
+  void* ctx2 = L->arch == 1 ? x : ctx;        // LN1's output has been consumed by the projection above
+  LLMC_TRY(launch_attention<T>(qkv, ctx2, n_p, d, L->n_heads, L->arch == 1, nullptr, B, st));
+  a = g;
+  a.A = ctx2; a.lda = d; a.W = L->d_wo; a.bias = L->d_bo; a.N = d; a.K = d; a.ldr = d; a.out = ao; a.ldo = d;
+  LLMC_TRY(launch_gemm(a, L->dtype, st));
+  return launch_pool_rows(ao, B, n_p, d, L->dtype, nullptr, nullptr, nullptr, out, st, ld_out);
+}
+
+llmc_status_t launch_prefix_attention_mean(const llmc_layer_desc_t* L, const void* d_h, int B, int S, int n_prefix,
+                                           void* ws, float* d_out, int ld_out, hipStream_t st) {
+  if (L->dtype == LLMC_F32) return prefix_attention_t<float>(L, d_h, B, S, n_prefix, ws, d_out, ld_out, st);
+  return prefix_attention_t<bf16_t>(L, d_h, B, S, n_prefix, ws, d_out, ld_out, st);
+}
+
 llmc_status_t launch_linear(const void* A, int lda, const int32_t* a_rows, const void* W, const void* bias, int N, int K,
                             void* out, int ldo, const int32_t* o_rows, int S, const int32_t* count, int max_seqs,
                             int dtype, hipStream_t st) {

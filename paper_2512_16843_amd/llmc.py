@@ -33,6 +33,7 @@ EXPORTS = [
     "llmc_last_error", "llmc_version", "llmc_fingerprint_bits", "llmc_match_bits",
     "llmc_match_bits_workspace_bytes", "llmc_max_hamming", "llmc_bank_pool_values",
     "llmc_lsh_index_bytes", "llmc_lsh_build", "llmc_match_bits_lsh", "llmc_materialize", "llmc_match_noalloc",
+    "llmc_fingerprint_prefix", "llmc_fingerprint_prefix_workspace_bytes",
 ]
 MATCH_STATIC_SCRATCH_BYTES = 5 << 20
 
@@ -110,6 +111,9 @@ def lib() -> C.CDLL:
                                                u32, u64, vp, vp, C.POINTER(GateOut), vp, sz, vp]
         L.llmc_layer_workspace_bytes.argtypes = [C.POINTER(LayerDesc), i32, i32, i32]
         L.llmc_layer_workspace_bytes.restype = sz
+        L.llmc_fingerprint_prefix.argtypes = [vp, vp, i32, i32, i32, vp, vp, i32, vp, vp, vp, sz, vp]
+        L.llmc_fingerprint_prefix_workspace_bytes.argtypes = [vp, i32, i32, i32]
+        L.llmc_fingerprint_prefix_workspace_bytes.restype = sz
         L.llmc_fingerprint_bits.argtypes = [vp, i32, i32, i32, i32, vp, vp, i32, vp, vp, sz, vp]
         L.llmc_match_bits.argtypes = [vp, vp, i32, i32, vp, i32, i32, vp, vp, vp, vp, sz, vp]
         L.llmc_match_bits_workspace_bytes.argtypes = [i32, i32, i32]
@@ -271,6 +275,20 @@ def llmc_fingerprint(h: torch.Tensor, proj: torch.Tensor, bias: Optional[torch.T
     _check(lib().llmc_fingerprint(_ptr(h), B, S, d, dtype_code(h.dtype), _ptr(proj), _ptr(bias), proj.shape[1],
                                   _ptr(fp_out), _ptr(inv_norm_out), _ptr(workspace), workspace.numel(),
                                   _stream(stream)))
+
+
+def llmc_fingerprint_prefix_workspace_bytes(layer: "LayerDesc", B: int, S: int, n_prefix: int) -> int:
+    return lib().llmc_fingerprint_prefix_workspace_bytes(C.byref(layer), B, S, n_prefix)
+
+
+def llmc_fingerprint_prefix(layer: "LayerDesc", h: torch.Tensor, n_prefix: int, proj2: torch.Tensor,
+                            bias: Optional[torch.Tensor], fp_out: torch.Tensor, inv_norm_out: torch.Tensor,
+                            workspace: torch.Tensor, stream=None) -> None:
+    """Keys from the token average and the prefix attention mean together; proj2 is [2 d, k]."""
+    B, S, d = h.shape
+    _check(lib().llmc_fingerprint_prefix(C.byref(layer), _ptr(h), B, S, n_prefix, _ptr(proj2), _ptr(bias),
+                                         proj2.shape[1], _ptr(fp_out), _ptr(inv_norm_out), _ptr(workspace),
+                                         workspace.numel(), _stream(stream)))
 
 
 def llmc_inv_norm(fp: torch.Tensor, out: torch.Tensor, stream=None) -> None:

@@ -143,3 +143,23 @@ def test_bit_key_entry_points_validate_and_max_hamming_matches_the_oracle(lib):
         for tau in (-1.0, -0.5, 0.0, 0.3, 0.82, 0.9, 0.95, 0.98, 0.999, 0.99999, 1.0, 2.0):
             assert lib.llmc_max_hamming(tau, k) == O.max_hamming(float(np.float32(tau)), k), (tau, k)
     assert lib.llmc_max_hamming(0.5, 0) == -1
+
+
+def test_fingerprint_prefix_rejects_bad_arguments(lib):
+    fake = C.c_void_p(1 << 20)
+    w = {n: fake for n in ("d_wqkv", "d_bqkv", "d_wo", "d_bo", "d_w1", "d_b1", "d_w2", "d_b2", "d_ln1_g", "d_ln1_b",
+                           "d_ln2_g", "d_ln2_b")}
+    layer = llmc.LayerDesc(arch=0, d=128, n_heads=2, d_ff=512, gelu=0, ln_eps=1e-5, dtype=llmc.BF16, **w)
+    need = lib.llmc_fingerprint_prefix_workspace_bytes(C.byref(layer), 4, 32, 8)
+    assert need > 4 * 2 * 128 * 4
+    assert lib.llmc_fingerprint_prefix_workspace_bytes(C.byref(layer), 4, 32, 33) == 0          # prefix longer than S
+
+    def call(n_prefix=8, k=64, ws=need, h=fake, B=4, S=32):
+        return lib.llmc_fingerprint_prefix(C.byref(layer), h, B, S, n_prefix, fake, None, k, fake, fake, fake, ws, None)
+
+    assert call(n_prefix=0) == llmc.ERR_INVALID_ARG
+    assert call(n_prefix=33) == llmc.ERR_INVALID_ARG
+    assert call(h=None) == llmc.ERR_INVALID_ARG
+    assert call(k=40) == llmc.ERR_SHAPE
+    assert call(ws=need - 1) == llmc.ERR_WORKSPACE
+    assert call(h=C.c_void_p((1 << 20) + 2)) == llmc.ERR_SHAPE

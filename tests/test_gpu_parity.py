@@ -106,6 +106,64 @@ def test_fingerprint_matches_oracle(L, dtype, B, S, d, k, use_bias):
     np.testing.assert_allclose(npf(inv), qinv, rtol=1e-4)
 
 
+@pytest.mark.parametrize("name,base,kw,n_prefix", [
+    ("f32 encoder", "TINY_ENCODER", dict(B=5, S=32), 8),
+    ("f32 decoder", "TINY_ENCODER", dict(B=4, S=40, arch=1, gelu=1, ln_eps=1e-5), 13),       # ragged prefix, causal, LN1 first
+    ("f32 whole sequence", "TINY_ENCODER", dict(B=3, S=32), 32),
+    ("bf16 bert-base rows", "BERT_BASE", dict(B=6, n_layers=1), 32),
+    ("bf16 gpt2 rows", "GPT2_SMALL", dict(B=3, n_layers=1), 100),                             # not a multiple of the key tile
+])
+def test_fingerprint_with_prefix_attention_statistics_matches_oracle(L, name, base, kw, n_prefix):
+    """llmc_fingerprint_prefix (token average + mean of the block's self-attention outputs over the first tokens,
+    one linear map) against the oracle.  The map of the attention feature is scaled so that both features carry
+    comparable weight in the key.  fp32: 1e-5 absolute on the unit-norm key.  bf16: the attention feature passes
+    through three bf16 products (QKV, softmax-weighted values, output projection), each rounded to 2^-9 relative, so
+    it arrives with about 1e-2 relative error and, carrying about half of the key's length, moves the key's direction by
+    at most about 1e-2: cosine with the oracle's key above 1 - 1e-4, components within 1.5e-3."""
+    say(f"fingerprint with prefix attention statistics: {name}, first {n_prefix} tokens")
+    cfg = W.scaled(getattr(W, base), n_layers=1, **{k_: v for k_, v in kw.items() if k_ != "n_layers"})
+    dtype = cfg.dtype
+    ws = W.make_layer_weights(cfg, seed=0)
+    tok, pos = W.make_embeddings(cfg, seed=0)
+    ids = W.make_sources(cfg, cfg.B, seed=1)
+    h = W.embed(torch.from_numpy(ids), tok, pos, cfg.torch_dtype).cuda()
+    wnp = {k_: npf(v) for k_, v in ws[0].items()}
+    g = np.random.Generator(np.random.PCG64(41))
+    a_ref = O.prefix_attention_mean(npf(h), wnp, cfg.arch, cfg.n_heads, cfg.ln_eps, n_prefix)
+    p_ref = npf(h).astype(np.float64).mean(axis=1)
+    ratio = float(np.linalg.norm(p_ref) / max(np.linalg.norm(a_ref), 1e-30))
+    P2 = np.concatenate([g.standard_normal((cfg.d, cfg.k)), ratio * g.standard_normal((cfg.d, cfg.k))]) / np.sqrt(cfg.k)
+    P2t = torch.from_numpy(P2.astype(np.float32)).to(cfg.torch_dtype).cuda()
+    bias = torch.from_numpy((g.standard_normal(cfg.k) * 0.01 * np.linalg.norm(p_ref[0])).astype(np.float32)).cuda()
+    layer = L.layer_from_weights(cfg, ws[0])
+    fp = torch.empty((cfg.B, cfg.k), dtype=cfg.torch_dtype, device="cuda")
+    inv = torch.empty((cfg.B,), dtype=torch.float32, device="cuda")
+    wsb = torch.empty((L.llmc_fingerprint_prefix_workspace_bytes(layer.desc(), cfg.B, cfg.S, n_prefix),), dtype=torch.uint8,
+                      device="cuda")
+    L.llmc_fingerprint_prefix(layer.desc(), h, n_prefix, P2t, bias, fp, inv, wsb)
+    torch.cuda.synchronize()
+    q, qinv = O.fingerprint_prefix(npf(h), npf(P2t), npf(bias), dtype, wnp, cfg.arch, cfg.n_heads, cfg.ln_eps, n_prefix)
+    got = npf(fp)
+    # the attention feature carries weight: without it the key would be far from the one computed
+    q_plain, _ = O.fingerprint(npf(h), npf(P2t)[:cfg.d], npf(bias), dtype)
+    assert np.abs(q_plain - q).max() > 2e-2
+    err = np.abs(got - q).max()
+    cos = (got.astype(np.float64) * q).sum(axis=1) / np.linalg.norm(got.astype(np.float64), axis=1) / np.linalg.norm(q, axis=1)
+    say(f"  max |key - oracle| {err:.2e}, min cosine {cos.min():.7f}")
+    if dtype == "f32":
+        assert err < 1e-5
+    else:
+        assert err < 1.5e-3 and cos.min() > 1 - 1e-4
+    np.testing.assert_allclose(npf(inv), O.inv_norm(got), rtol=3e-7, atol=0)
+    # the call is a function of each sequence alone
+    if cfg.B >= 3:
+        fp1 = torch.empty((1, cfg.k), dtype=cfg.torch_dtype, device="cuda")
+        inv1 = torch.empty((1,), dtype=torch.float32, device="cuda")
+        L.llmc_fingerprint_prefix(layer.desc(), h[2:3].contiguous(), n_prefix, P2t, bias, fp1, inv1, wsb)
+        torch.cuda.synchronize()
+        assert torch.equal(fp1[0], fp[2]) and torch.equal(inv1[0], inv[2])
+
+
 def test_fingerprint_is_position_and_batch_independent(L):
     say("fingerprint determinism across batch position and size")
     g = np.random.Generator(np.random.PCG64(77))
