@@ -20,10 +20,16 @@ class GatedStack:
                  policy: int = llmc.EVICT_LRU, B: Optional[int] = None, half_life: int = 0, reval_every: int = 0,
                  drift_bound: float = 0.0, bases: Optional[List[Optional[torch.Tensor]]] = None,
                  keep_means: bool = False, keep_next_keys: bool = False, key_bits: bool = False,
-                 expose_keys: bool = False, lsh: bool = False):
+                 expose_keys: bool = False, lsh: bool = False, prefix_tokens: int = 0,
+                 proj2: Optional[List[torch.Tensor]] = None):
         self.cfg = cfg
         self.device = device
         self.B = cfg.B if B is None else B
+        # prefix_tokens > 0: every cached layer is looked up under keys made of the token average AND the mean of the
+        # layer's self-attention outputs over the first prefix_tokens tokens (proj2[l] is [2 d, k])
+        self.prefix_tokens = prefix_tokens
+        assert not (prefix_tokens and (keep_means or key_bits)), "prefix keys are computed per call, nothing is carried"
+        self.proj2 = None if not prefix_tokens else [p.to(device).contiguous() for p in proj2]
         self.layers = [llmc.layer_from_weights(cfg, w, device) for w in weights]
         self.proj = [p.to(device).contiguous() for p in projections]
         self.bias = [None if b is None else b.to(device).contiguous() for b in (biases or [None] * cfg.n_layers)]
@@ -45,6 +51,11 @@ class GatedStack:
         ws_bytes = llmc.llmc_layer_workspace_bytes(self.layers[0], self.B, cfg.S, cfg.k)
         self.workspace = torch.empty((ws_bytes,), dtype=torch.uint8, device=device)
         self.buf = [torch.empty((self.B, cfg.S, cfg.d), dtype=cfg.torch_dtype, device=device) for _ in range(2)]
+        if prefix_tokens:
+            nb = llmc.llmc_fingerprint_prefix_workspace_bytes(self.layers[0].desc(), self.B, cfg.S, prefix_tokens)
+            self.pfx_ws = torch.empty((nb,), dtype=torch.uint8, device=device)
+            self.pfx_fp = [torch.empty((self.B, cfg.k), dtype=cfg.torch_dtype, device=device) for _ in range(cfg.n_layers)]
+            self.pfx_inv = [torch.empty((self.B,), dtype=torch.float32, device=device) for _ in range(cfg.n_layers)]
         # keep_means: banks store the token mean of every cached output and a reused row hands it to the next layer
         self.keep_means = keep_means
         self._hint = [False] * cfg.n_layers
@@ -118,9 +129,14 @@ class GatedStack:
             if prev is not None and (bank is None or bank.key_bits):
                 llmc.llmc_materialize(prev, self.gate[l - 1].ref, h)          # this layer cannot take references
                 prev = None
+            fp_l, inv_l = fp_given, inv_given
+            if self.prefix_tokens and bank is not None and not single_fingerprint:
+                fp_l, inv_l = self.pfx_fp[l], self.pfx_inv[l]
+                llmc.llmc_fingerprint_prefix(self.layers[l].desc(), h, self.prefix_tokens, self.proj2[l], self.bias[l],
+                                             fp_l, inv_l, self.pfx_ws)
             llmc.llmc_layer_forward_gated(self.layers[l], bank, self.proj[l], self.bias[l], h, out, tau,
                                           fl | (llmc.DEFER_COPY if defer_here else 0), tick, self.workspace,
-                                          self.gate[l], fp_given, inv_given, carry=carry, prev_bank=prev)
+                                          self.gate[l], fp_l, inv_l, carry=carry, prev_bank=prev)
             prev = bank if defer_here else None
             self._deferred[l] = defer_here
             h = out

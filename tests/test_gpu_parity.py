@@ -1505,6 +1505,83 @@ def test_cost_hint_with_carried_and_uncarried_rows(L, dtype, deferred):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_gated_decoder_with_prefix_attention_keys(L, dtype):
+    """A causal decoder stack looked up under keys that include the prefix attention statistics (Section IV-B):
+    banks are built from sources, queries share a prefix (a quarter to three quarters of the tokens) with a source and
+    continue with fresh tokens.  Per layer, teacher-forced on the GPU's layer inputs: the keys against the oracle's,
+    then decisions, matched slots, similarities and outputs against the oracle fed those keys.  The feature does what
+    it is for: under these keys a query is closer to its source than under the token average alone."""
+    from paper_2512_16843_amd.engine import GatedStack
+    n_p = 16
+    say(f"gated decoder with prefix attention keys {dtype}: first {n_p} tokens, prefix-sharing queries")
+    if dtype == "f32":
+        cfg = W.scaled(W.TINY_ENCODER, n_layers=2, B=8, S=64, n_bank=24, arch=1, gelu=1, ln_eps=1e-5)
+    else:
+        cfg = W.scaled(W.GPT2_SMALL, n_layers=2, B=8, S=64, n_bank=24)
+    tol = TOL[dtype]
+    ws = W.make_layer_weights(cfg, seed=0)
+    tok, pos = W.make_embeddings(cfg, seed=0)
+    Ps = W.make_projection(cfg.d, cfg.k, cfg.torch_dtype, seed=3, n_layers=cfg.n_layers)
+    Pa = W.make_projection(cfg.d, cfg.k, cfg.torch_dtype, seed=13, n_layers=cfg.n_layers)
+    wnp = [{k_: npf(v) for k_, v in w.items()} for w in ws]
+    src = W.make_sources(cfg, 16, seed=1)
+    qids, qsrc, plen = W.make_prefix_queries(cfg, src, seed=2)
+    assert plen.min() >= n_p
+    # weigh the attention feature like the token average: scale its map by the ratio of the two features' lengths
+    h_src = W.embed(torch.from_numpy(src[:8]), tok, pos, cfg.torch_dtype)
+    a0 = O.prefix_attention_mean(npf(h_src), wnp[0], cfg.arch, cfg.n_heads, cfg.ln_eps, n_p)
+    ratio = float(np.linalg.norm(npf(h_src).astype(np.float64).mean(axis=1)) / np.linalg.norm(a0))
+    P2 = [torch.cat([Ps[l].float(), Pa[l].float() * (2.0 * ratio)]).to(cfg.torch_dtype) for l in range(cfg.n_layers)]
+    st = GatedStack(cfg, ws, Ps, prefix_tokens=n_p, proj2=P2)
+    obanks = [O.Bank(cfg.n_bank, cfg.k, cfg.S, cfg.d, dtype) for _ in range(cfg.n_layers)]
+    batches = [(src[0:8], 2.0, L.INSERT_ON_MISS), (src[8:16], 2.0, L.INSERT_ON_MISS), (qids, 0.8, L.UPDATE_LRU)]
+    for tick, (ids, tau, flags) in enumerate(batches, start=1):
+        h0 = W.embed(torch.from_numpy(ids), tok, pos, cfg.torch_dtype)
+        outs = st.forward(h0.cuda(), tau=tau, flags=flags, tick=tick, keep_all=True)
+        torch.cuda.synchronize()
+        oflags = (O.FLAG_UPDATE_LRU if flags & L.UPDATE_LRU else 0) | (O.FLAG_INSERT_ON_MISS if flags & L.INSERT_ON_MISS else 0)
+        for l in range(cfg.n_layers):
+            h_prev = npf(h0 if l == 0 else outs[l - 1])
+            q_g, qinv_g = npf(st.pfx_fp[l]), npf(st.pfx_inv[l])
+            q_o, _ = O.fingerprint_prefix(h_prev, npf(P2[l]), None, dtype, wnp[l], cfg.arch, cfg.n_heads, cfg.ln_eps, n_p)
+            err = np.abs(q_g - q_o).max()
+            assert err < (1e-5 if dtype == "f32" else 1.5e-3), (tick, l, err)
+            ob = obanks[l]
+            pre_fp, pre_inv, pre_valid = ob.fp.copy(), ob.inv_norm.copy(), ob.valid.copy()
+            r = O.gated_layer(h_prev, ob, None, None, wnp[l], cfg.arch, cfg.n_heads, cfg.ln_eps, cfg.gelu, f32(tau),
+                              flags=oflags, tick=tick, out_dtype=dtype, fp_override=(q_g, qinv_g))
+            g, bk = st.gate[l], st.banks[l]
+            hit = g.hit.cpu().numpy().astype(bool)
+            assert not (np.abs(r.sim - f32(tau)) < 1e-3).any()
+            assert np.array_equal(hit, r.hit), (tick, l)
+            gi = g.idx.cpu().numpy()
+            if pre_valid.any():
+                ties = O.near_tie_sets(q_g, qinv_g, pre_fp, pre_inv, pre_valid)
+                for b in range(cfg.B):
+                    assert gi[b] == r.idx[b] or gi[b] in ties[b], (tick, l, b)
+                np.testing.assert_allclose(npf(g.sim), r.sim, rtol=0, atol=1e-5)
+            assert np.array_equal(bk.valid.cpu().numpy(), ob.valid)
+            if flags & L.INSERT_ON_MISS:
+                assert np.array_equal(npf(bk.fp)[r.slots], q_g[~hit])
+            got = npf(outs[l])
+            for b in range(cfg.B):
+                if hit[b]:
+                    assert np.array_equal(got[b], npf(bk.act[int(gi[b])]))
+                else:
+                    assert rel_err_rows(got[b:b + 1], r.h_out[b:b + 1])[0] < tol, (tick, l, b)
+            if tick == 3 and l == 0:
+                # first layer, queries against their own sources: similarity under both kinds of key
+                s_pfx = O.similarities(q_g, qinv_g, pre_fp, pre_inv)[np.arange(cfg.B), qsrc]
+                q_pl, qi_pl = O.fingerprint(h_prev, npf(Ps[0]), None, dtype)
+                k_pl, ki_pl = O.fingerprint(npf(W.embed(torch.from_numpy(src), tok, pos, cfg.torch_dtype)), npf(Ps[0]), None, dtype)
+                s_plain = O.similarities(q_pl, qi_pl, k_pl, ki_pl)[np.arange(cfg.B), qsrc]
+                say(f"  similarity to the own source: prefix keys {s_pfx.mean():.4f}, token average alone {s_plain.mean():.4f}; "
+                    f"hits {int(hit.sum())} of {cfg.B}")
+                assert s_pfx.mean() > s_plain.mean()
+    st.close()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_single_fingerprint_mode_against_oracle(L, dtype):
     """Algorithm 1 as printed: one fingerprint of the input, reused by every layer (d_fp_given of the C ABI)."""
     from paper_2512_16843_amd.engine import GatedStack
