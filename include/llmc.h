@@ -59,15 +59,18 @@ typedef enum { LLMC_F32 = 0, LLMC_BF16 = 1 } llmc_dtype_t;
 
 /* Replacement policy (Section III-E / IV-D of the paper).  LRU is the first
  * policy the paper names: remove the entries unused for the longest time.
- * DECAYED_HITS is the staleness-aware policy of Section IV-D ("entries with decayed match
- * rates over time"; Section III-E: frequency-based policy, temporal decay): an entry's
+ * DECAYED_HITS is the staleness-aware policy of Section IV-D (entries whose rate of matches has
+ * faded with time go first; Section III-E: frequency-based policy with temporal decay): an entry's
  * standing is its hit count d_hits, and every hit count of the bank is halved (integer
  * shift) each time the tick crosses a multiple of half_life (half_life 0: never, i.e. plain
  * least-frequently-used).  Victims are taken by ascending (min(hits, 65535), last_used,
  * slot).  The halving is applied by the library, before anything else, in every call that
  * takes a tick and updates the bank (llmc_bank_insert, llmc_layer_forward_gated with
  * LLMC_INSERT_ON_MISS or LLMC_UPDATE_LRU); ticks must not decrease.  A bank under this
- * policy holds at most 2^24 slots and takes ticks below LLMC_MAX_TICK_DECAYED. */
+ * policy holds at most 2^24 slots and takes ticks below LLMC_MAX_TICK_DECAYED.  Whether a call
+ * halves is decided on the HOST from the tick it is given, so a recorded HIP graph of such a
+ * call repeats the decision taken at capture time: do not replay a graph of a call that updates
+ * a DECAYED_HITS bank across a multiple of half_life (record it again, or launch that call eagerly). */
 typedef enum { LLMC_EVICT_NONE = 0, LLMC_EVICT_LRU = 1, LLMC_EVICT_DECAYED_HITS = 2 } llmc_evict_t;
 #define LLMC_MAX_TICK_DECAYED 0xFFFFFEull
 
@@ -167,7 +170,7 @@ typedef struct {
   int32_t half_life; /* LLMC_EVICT_DECAYED_HITS: ticks per halving of the hit counts, 0 = never; else ignored */
   int32_t reval_every; /* LLMC_REVALIDATE: sampling period r of the divergence monitor, 0 = off */
   float drift_bound;   /* LLMC_REVALIDATE: divergence above which a cached value is replaced */
-  /* Compressed cached values (Section III-B: "optionally compresses cached representations via PCA").
+  /* Compressed cached values (Section III-B: cached representations may be stored compressed, by PCA).
    * rank = 0: d_act holds the outputs themselves, [n_act_slots, S, d].
    * rank = r > 0: d_basis [r, d] (element type `dtype`, d contiguous, rows = the directions kept) is given, d_act
    * is [n_act_slots, S, r] and holds the coefficients C = h U^T of each cached output, rounded to `dtype`; a hit
@@ -199,7 +202,7 @@ typedef struct {
    * llmc_bank_insert and d_fp_given then take keys in that form (d_inv_norm / d_inv_norm_given ignored);
    * llmc_match refuses such a bank (use llmc_match_bits).  Refused together with stored next-layer keys. */
   int32_t key_bits;
-  /* Optional, key_bits = 1 only: storage for the bucket index of the keys (Section IV-B "LSH"), device memory of
+  /* Optional, key_bits = 1 only: storage for the bucket index of the keys (Section IV-B, LSH), device memory of
    * lsh_index_bytes >= llmc_lsh_index_bytes(n_slots, k) bytes, 256-byte aligned, owned by the caller and written by
    * the library alone: llmc_bank_create and llmc_bank_refresh build it from the keys and validity flags as they
    * stand, llmc_bank_insert and the insertions of llmc_layer_forward_gated rebuild it after they changed a key.
@@ -421,7 +424,7 @@ llmc_status_t llmc_fingerprint_bits(const void* d_h, int32_t B, int32_t S, int32
                                     llmc_stream_t stream);
 
 /*
- * Section IV-B, the second fingerprint feature ("prefix attention stats": the mean of the initial self-attention
+ * Section IV-B, the second fingerprint feature (prefix attention statistics: the mean of the first self-attention
  * outputs), taken together with the first (the token average) and reduced by ONE linear map:
  *   p = mean_t h[b, t, :]                                            (as in llmc_fingerprint)
  *   a = mean_{t < n_prefix} MHA_l(h[b, 0 .. n_prefix, :])[t, :]      the block's own self-attention sub-layer over the
@@ -443,7 +446,7 @@ llmc_status_t llmc_fingerprint_prefix(const llmc_layer_desc_t* layer, const void
 size_t llmc_fingerprint_prefix_workspace_bytes(const llmc_layer_desc_t* layer, int32_t B, int32_t S, int32_t n_prefix);
 
 /*
- * Section IV-B "compared via cosine similarity or LSH", with the test of the case equation
+ * Section IV-B (keys are compared by cosine similarity or by LSH), with the test of the case equation
  * (Section IV-A): for each query key the valid bank key at the smallest Hamming distance H;
  * cos(pi H / k) stands for the cosine of the two pooled inputs, so  sim > tau  becomes
  * H <= max_hamming  with  max_hamming = llmc_max_hamming(tau, k).
@@ -461,7 +464,7 @@ llmc_status_t llmc_match_bits(const uint32_t* d_bank_bits, const uint8_t* d_vali
 size_t llmc_match_bits_workspace_bytes(int32_t N, int32_t k, int32_t B);
 
 /*
- * Bucketed lookup of sign-bit keys (Section IV-B "LSH"; Section III-A "sub-linear comparison cost").  The key is
+ * Bucketed lookup of sign-bit keys (Section IV-B, LSH; Section III-A asks for a comparison cost below linear in the bank size).  The key is
  * cut into k / 16 bands of 16 bits (band b = bits 16 b .. 16 b + 15).  llmc_lsh_build groups the valid slots of a
  * bank by the value of each band into d_index (caller-owned, llmc_lsh_index_bytes(N, k) bytes, 256-byte aligned);
  * it must be called again after the bank's keys or validity change.  llmc_match_bits_lsh compares a query only with

@@ -304,8 +304,8 @@ def fingerprint_prefix(h: np.ndarray, P2: np.ndarray, c: Optional[np.ndarray], d
 # ----------------------------------------------------------------------------
 # the bank C_l (Section III-B) with insertion and LRU (Sections III-E, IV-D)
 # ----------------------------------------------------------------------------
-# sign-bit keys (Section IV-B "SimHash"; Section III-A "MinHash or SimHash-based
-# techniques"; Section IV-B "compared via cosine similarity or LSH")
+# sign-bit keys (Section IV-B names SimHash as a reduction, Section III-A MinHash- or SimHash-based
+# hashing; Section IV-B: keys are compared by cosine similarity or by LSH)
 # ----------------------------------------------------------------------------
 #
 # The real-valued key above is the SimHash projection before the sign is taken.
@@ -383,7 +383,7 @@ def match_bits(q_words: np.ndarray, bank_words: np.ndarray, valid: np.ndarray, k
 
 
 def lsh_candidates(q_words: np.ndarray, bank_words: np.ndarray, valid: np.ndarray, k: int) -> np.ndarray:
-    """Bucketed lookup (Section IV-B "LSH", Section III-A "sub-linear comparison cost"): the key is cut into
+    """Bucketed lookup (Section IV-B, LSH; Section III-A wants the comparison cost below linear): the key is cut into
     k / 16 bands of 16 bits (band b = bits 16 b .. 16 b + 15); a bank entry is a CANDIDATE for a query iff it is
     valid and at least one band is equal in both keys.  Returns the boolean [B, N] candidate matrix."""
     q16 = np.asarray(q_words, dtype=np.uint32)
@@ -451,7 +451,7 @@ class Bank:
         self.key_bits = key_bits
         self.N, self.k, self.S, self.d, self.A = n_slots, k, S, d, A
         self.dtype = dtype
-        # compressed cached values (Section III-B: "optionally compresses cached representations via PCA"):
+        # compressed cached values (Section III-B: cached representations may be stored compressed, by PCA):
         # with a basis U [r, d] (rows = principal directions) an entry stores the coefficients
         # C = h U^T [S, r] in the bank's storage type, and a hit returns the reconstruction C U
         self.basis = None if basis is None else np.asarray(basis, dtype=np.float64)
@@ -590,8 +590,8 @@ def gated_layer(h_in: np.ndarray, bank: Optional[Bank], P: Optional[np.ndarray],
     ``fp_override`` supplies (q, qinv) instead of fingerprinting h_in
     (Algorithm 1 taken literally: one fingerprint of the input for all layers).
 
-    Divergence monitor (Section IV-D third item; Section III-E: "differences in successive
-    outputs for a given fingerprint across inference calls"), with FLAG_REVALIDATE and
+    Divergence monitor (Section IV-D third item; Section III-E: the outputs that successive
+    calls produce for one fingerprint are compared), with FLAG_REVALIDATE and
     ``reval_every`` = r >= 1: a hit row b with (tick + b) % r == 0 is computed anyway; its
     output is the fresh f_l(h_in[b]); its divergence is max|fresh - cached| / max|cached|
     (1e-30 floor); above ``drift_bound`` the entry's cached value is replaced by the fresh
@@ -612,7 +612,7 @@ def gated_layer(h_in: np.ndarray, bank: Optional[Bank], P: Optional[np.ndarray],
         q = fp_override[0] if fp_override is not None else fingerprint_bits(h_in, P, c)
         qinv = np.zeros((B,), np.float32)
         if flags & FLAG_LOOKUP_LSH:
-            # bucketed lookup (Section IV-B "LSH"): only slots that share one whole band with the query are compared
+            # bucketed lookup (Section IV-B, LSH): only slots that share one whole band with the query are compared
             idx, dist, _ = match_bits_lsh(q, bank.fp, bank.valid, bank.k)
         else:
             idx, dist = match_bits(q, bank.fp, bank.valid, bank.k)

@@ -1,5 +1,5 @@
-// Hamming match of sign-bit keys (Section IV-B: SimHash keys "compared via cosine similarity or
-// LSH"; Section III-A: hashing "to ensure sub-linear comparison cost"): for each query key the
+// Hamming match of sign-bit keys (Section IV-B: SimHash keys, compared by cosine similarity or by
+// LSH; Section III-A: hashing keeps the comparison cheap): for each query key the
 // valid bank key at the smallest Hamming distance H, lowest slot among equals.  cos(pi H / k) stands
 // for the cosine of the case equation, so the threshold becomes H <= max_hamming.
 //

@@ -1,5 +1,5 @@
-// Bucketed lookup of sign-bit keys (Section IV-B: keys "compared via cosine similarity or LSH";
-// Section III-A: hashing "to ensure sub-linear comparison cost").
+// Bucketed lookup of sign-bit keys (Section IV-B: keys are compared by cosine similarity or by LSH;
+// Section III-A: hashing is there to keep the comparison cost below linear in the bank size).
 //
 // A k-bit key is cut into k / 16 bands of 16 bits (band b = bits 16 b .. 16 b + 15).  The index holds, per
 // band, the valid slots grouped by the band's value: start[b][v] .. start[b][v + 1] is the range of
