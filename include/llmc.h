@@ -436,8 +436,9 @@ llmc_status_t llmc_fingerprint_bits(const void* d_h, int32_t B, int32_t S, int32
  *   layer: the block whose attention weights are used (its dtype is the element type of d_h, d_proj2 and d_fp_out)
  *   d_h [B, S, d], d_proj2 [2 d, k], d_bias [k] fp32 or NULL, d_fp_out [B, k], d_inv_norm_out [B] fp32: device memory
  *   of the caller; d_workspace: llmc_fingerprint_prefix_workspace_bytes(layer, B, S, n_prefix) bytes, 256-byte aligned.
- * The keys are for llmc_match / llmc_bank_insert or for llmc_layer_forward_gated's d_fp_given.  Nothing is allocated
- * or synchronised.  Errors: INVALID_ARG (null, n_prefix outside 1..S), SHAPE (layer, k, alignment), DTYPE, WORKSPACE.
+ * The keys are for llmc_match / llmc_bank_insert or for llmc_layer_forward_gated's d_fp_given.  On return the first
+ * B * 2 d floats of d_workspace hold the two features of every row, [p; a] row by row (fp32): what a caller needs to
+ * centre the map (c = -P2^T mean[p; a] over the sequences a bank is built from).  Nothing is allocated or synchronised.  Errors: INVALID_ARG (null, n_prefix outside 1..S), SHAPE (layer, k, alignment), DTYPE, WORKSPACE.
  */
 llmc_status_t llmc_fingerprint_prefix(const llmc_layer_desc_t* layer, const void* d_h, int32_t B, int32_t S,
                                       int32_t n_prefix, const void* d_proj2, const float* d_bias, int32_t k,

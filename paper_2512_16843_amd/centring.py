@@ -37,3 +37,39 @@ def centring_offsets(cfg: ModelConfig, weights, projections, batches: Iterable[t
         P = projections[l].to(device).to(torch.float64)
         out.append((-(mu @ P)).to(torch.float32).cpu().contiguous())
     return out
+
+
+def prefix_feature_stats(cfg: ModelConfig, weights, proj2, batches: Iterable[torch.Tensor], n_prefix: int,
+                         device="cuda"):
+    """Mean and spread of the two fingerprint features (token average p, prefix attention mean a) of every layer's
+    input over the sequences a bank is built from.  The features are taken from the library's own call
+    (llmc_fingerprint_prefix leaves [p; a] of every row at the head of its workspace), the layer inputs from an
+    uncached forward.  Returns per layer (mu [2 d] float64 on the host, E|p - mu_p|^2, E|a - mu_a|^2).
+    ``proj2[l]`` [2 d, k] is only there because the call wants a map; the keys it makes are not used."""
+    from . import llmc
+    d = cfg.d
+    plain = GatedStack(cfg, weights, [p[:d] for p in proj2], device=device, cached_layers=[])
+    s1 = [torch.zeros((2 * d,), dtype=torch.float64, device=device) for _ in range(cfg.n_layers)]
+    s2 = [torch.zeros((2 * d,), dtype=torch.float64, device=device) for _ in range(cfg.n_layers)]
+    P2 = [p.to(device).contiguous() for p in proj2]
+    ws = torch.empty((llmc.llmc_fingerprint_prefix_workspace_bytes(plain.layers[0].desc(), cfg.B, cfg.S, n_prefix),),
+                     dtype=torch.uint8, device=device)
+    fp = torch.empty((cfg.B, cfg.k), dtype=cfg.torch_dtype, device=device)
+    inv = torch.empty((cfg.B,), dtype=torch.float32, device=device)
+    n = 0
+    for h0 in batches:
+        outs = plain.forward(h0, tau=2.0, keep_all=True)
+        ins = [h0] + outs[:-1]
+        for l in range(cfg.n_layers):
+            llmc.llmc_fingerprint_prefix(plain.layers[l].desc(), ins[l], n_prefix, P2[l], None, fp, inv, ws)
+            feat = ws[:cfg.B * 2 * d * 4].view(torch.float32).view(cfg.B, 2 * d).to(torch.float64)
+            s1[l] += feat.sum(dim=0)
+            s2[l] += (feat * feat).sum(dim=0)
+        n += h0.shape[0]
+    plain.close()
+    out = []
+    for l in range(cfg.n_layers):
+        mu = s1[l] / float(n)
+        var = (s2[l] / float(n) - mu * mu).clamp_min(0.0)
+        out.append((mu.cpu(), float(var[:d].sum()), float(var[d:].sum())))
+    return out

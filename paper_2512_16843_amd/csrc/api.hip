@@ -272,7 +272,9 @@ llmc_status_t llmc_fingerprint(const void* d_h, int32_t B, int32_t S, int32_t d,
 
 size_t llmc_fingerprint_prefix_workspace_bytes(const llmc_layer_desc_t* layer, int32_t B, int32_t S, int32_t n_prefix) {
   if (!layer || check_layer(layer) != LLMC_OK || B <= 0 || S <= 0 || n_prefix <= 0 || n_prefix > S) return 0;
-  return align_up((size_t)B * 2 * layer->d * sizeof(float), 256) + prefix_attention_ws_bytes(layer, B, n_prefix);
+  // the two features | the dense block over the prefix, which shares its space with the pooling's chunk sums
+  return align_up((size_t)B * 2 * layer->d * sizeof(float), 256) +
+         std::max(prefix_attention_ws_bytes(layer, B, n_prefix), fingerprint_ws_bytes(B, S, layer->d));
 }
 
 llmc_status_t llmc_fingerprint_prefix(const llmc_layer_desc_t* layer, const void* d_h, int32_t B, int32_t S,
@@ -292,7 +294,7 @@ llmc_status_t llmc_fingerprint_prefix(const llmc_layer_desc_t* layer, const void
   const int d = layer->d;
   float* feat = (float*)d_workspace;                                                   // [B, 2 d]: token mean | prefix attention mean
   void* ws_attn = (char*)d_workspace + align_up((size_t)B * 2 * d * sizeof(float), 256);
-  LLMC_TRY(launch_pool_rows(d_h, B, S, d, layer->dtype, nullptr, nullptr, nullptr, feat, st, 2 * d));
+  LLMC_TRY(launch_pool_means(d_h, B, S, d, layer->dtype, ws_attn, feat, 2 * d, st));
   LLMC_TRY(launch_prefix_attention_mean(layer, d_h, B, S, n_prefix, ws_attn, feat + d, 2 * d, st));
   return launch_project_rows(feat, B, 2 * d, layer->dtype, d_proj2, d_bias, k, nullptr, nullptr, d_fp_out, d_inv_norm_out, st);
 }

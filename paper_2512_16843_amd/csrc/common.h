@@ -181,6 +181,9 @@ llmc_status_t launch_fingerprint(const void* d_h, const int32_t* d_rowmap_unused
 llmc_status_t launch_project_rows(const float* d_means, int n_max, int d, int dtype, const void* d_proj,
                                   const float* d_bias, int k, const int32_t* d_rows, const int32_t* d_count, void* d_fp,
                                   float* d_inv, hipStream_t st);
+// token means of B whole sequences, wide form (ws_partials: fingerprint_ws_bytes(B, S, d) bytes), same bits as above
+llmc_status_t launch_pool_means(const void* d_h, int B, int S, int d, int dtype, void* ws_partials, float* d_out,
+                                int ld_out, hipStream_t st);
 // ld_out: floats between consecutive output rows (0: d)
 llmc_status_t launch_pool_rows(const void* d_h, int n_max, int S, int d, int dtype, const int32_t* d_rows,
                                const int32_t* d_count, const int32_t* d_dst, float* d_out, hipStream_t st,

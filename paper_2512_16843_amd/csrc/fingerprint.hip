@@ -389,6 +389,43 @@ llmc_status_t launch_fingerprint(const void* d_h, const int32_t*, int B, int S, 
                                few_uncarried, key_index);
 }
 
+// token means of B whole sequences through the wide pooling kernel: chunk partials first, then one workgroup per
+// sequence adds them in ascending chunk order (the arithmetic of the projection's own chunk sum, so the mean has
+// the bits the fingerprint uses) and writes out[b * ld_out ..] [d]
+__global__ void mean_from_partials_kernel(const float* __restrict__ partial, int n_chunks, int d, float inv_S,
+                                          float* __restrict__ out, int ld_out) {
+  const int b = blockIdx.x;
+  for (int i = threadIdx.x; i < d; i += blockDim.x) {
+    const float* src = partial + (size_t)b * n_chunks * d + i;
+    float s = 0.f;
+    for (int c = 0; c < n_chunks; ++c) s += src[(size_t)c * d];
+    out[(size_t)b * ld_out + i] = s * inv_S;
+  }
+}
+
+template <typename T>
+static llmc_status_t pool_means_t(const T* h, int B, int S, int d, float* partial, float* out, int ld_out, hipStream_t st) {
+  constexpr int VEC = Vec16<T>::N;
+  const int G = d / VEC;
+  const int R = pool_row_groups(G);
+  const int n_chunks = pool_chunks(S);
+  { ProfScope ps_("pool_kernel", st);
+    LLMC_KERNEL_GGL(pool_kernel<T>, dim3(n_chunks, B), dim3(G * R), (size_t)R * d * sizeof(float), st, h, S, d, G, R, partial,
+                    n_chunks, (const uint8_t*)nullptr, (const int32_t*)nullptr, (const int32_t*)nullptr,
+                    (const int32_t*)nullptr); }
+  LLMC_LAUNCH_CHECK("pool_kernel");
+  { ProfScope ps_("mean_from_partials_kernel", st);
+    LLMC_KERNEL_GGL(mean_from_partials_kernel, dim3(B), dim3(256), 0, st, partial, n_chunks, d, 1.0f / (float)S, out, ld_out); }
+  LLMC_LAUNCH_CHECK("mean_from_partials_kernel");
+  return LLMC_OK;
+}
+
+llmc_status_t launch_pool_means(const void* d_h, int B, int S, int d, int dtype, void* ws_partials, float* d_out,
+                                int ld_out, hipStream_t st) {
+  if (dtype == LLMC_F32) return pool_means_t<float>((const float*)d_h, B, S, d, (float*)ws_partials, d_out, ld_out, st);
+  return pool_means_t<bf16_t>((const bf16_t*)d_h, B, S, d, (float*)ws_partials, d_out, ld_out, st);
+}
+
 // keys of token means kept elsewhere: entry e < *count (or n_max) projects means[rows[e]] into fp[rows[e]], inv[rows[e]]
 template <typename T>
 static llmc_status_t project_rows_t(const float* means, int n_max, int d, const T* P, const float* bias, int k,
