@@ -124,24 +124,26 @@ __global__ __launch_bounds__(C::THREADS) void gemm_bf16_kernel(GemmArgs g, int t
   }
 }
 
-// Epilogue through LDS, one wavefront at a time: a wavefront lays one 32-row block of its
-// accumulators out as fp32 [32][FN * 32 + 4] in a region of its own, then its lanes take 8
-// consecutive columns of a row each, so that bias, residual and output move as 16-byte vectors
-// along rows.  No other wavefront touches the region, and LDS operations of one wavefront
-// complete in order, so no barrier is needed between the two halves.  `stage` must hold
-// NW * 32 * (FN * 32 + 4) floats and be free of readers.
+// Epilogue through LDS, one wavefront at a time: a wavefront lays 16 rows of its accumulators (half a fragment:
+// registers 8 h .. 8 h + 7 hold rows 16 h .. 16 h + 15 of it) out as fp32 [16][FN * 32 + 4] in a region of its own,
+// then its lanes take 8 consecutive columns of a row each, so that bias, residual and output move as 16-byte
+// vectors along rows.  No other wavefront touches the region, and LDS operations of one wavefront complete in
+// order, so no barrier is needed between the two halves.  Blocks of 16 rows keep the staging of all wavefronts
+// inside ONE ring stage, so the other stage can already receive the next tile's first loads.  `stage` is that
+// ring stage; no barrier inside or after: the next tile's first barrier comes before anything is loaded into this
+// stage again.
 template <class C>
-struct WaveEpilogue {
-  static constexpr int COLS = C::FN * 32, STRIDE = COLS + 4, REGION = 32 * STRIDE;   // floats
+struct WaveEpilogue16 {
+  static constexpr int COLS = C::FN * 32, STRIDE = COLS + 4, REGION = 16 * STRIDE;   // floats
   static constexpr int LANES_PER_ROW = COLS / 8, ROWS_PER_PASS = 64 / LANES_PER_ROW;
-  static constexpr size_t BYTES = (size_t)C::NW * REGION * 4;
-  static_assert(64 % LANES_PER_ROW == 0 && 32 % ROWS_PER_PASS == 0, "row vectors tile the block");
+  static_assert(64 % LANES_PER_ROW == 0 && 16 % ROWS_PER_PASS == 0, "row vectors tile the block");
+  static_assert((size_t)C::NW * REGION * 4 <= (size_t)C::STAGE_ELEMS * 2, "the staging fits one ring stage");
 };
 
 template <class C>
-__device__ __forceinline__ void gemm_epilogue_wave(const GemmArgs& g, f32x16_t (&acc)[C::FM][C::FN], int m0, int n0,
-                                                   int M, float* stage) {
-  using E = WaveEpilogue<C>;
+__device__ __forceinline__ void gemm_epilogue_wave16(const GemmArgs& g, f32x16_t (&acc)[C::FM][C::FN], int m0, int n0,
+                                                     int M, float* stage) {
+  using E = WaveEpilogue16<C>;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wm = wave / C::WN, wn = wave % C::WN;
@@ -158,96 +160,122 @@ __device__ __forceinline__ void gemm_epilogue_wave(const GemmArgs& g, f32x16_t (
 #pragma unroll
   for (int i = 0; i < C::FM; ++i) {
 #pragma unroll
-    for (int j = 0; j < C::FN; ++j) {
-      float* p = region + j * 32 + (lane & 31);
+    for (int h = 0; h < 2; ++h) {
 #pragma unroll
-      for (int r = 0; r < 16; ++r) p[frag_row(lane, r) * E::STRIDE] = acc[i][j][r];
-    }
-    const int mb = m0 + wm * (C::BM / C::WM) + i * 32;
+      for (int j = 0; j < C::FN; ++j) {
+        float* p = region + j * 32 + (lane & 31);
 #pragma unroll
-    for (int pass = 0; pass < 32 / E::ROWS_PER_PASS; ++pass) {
-      const int row = pass * E::ROWS_PER_PASS + prow;
-      const int m = mb + row;
-      const float4 lo = *reinterpret_cast<const float4*>(region + row * E::STRIDE + c8);
-      const float4 hi = *reinterpret_cast<const float4*>(region + row * E::STRIDE + c8 + 4);
-      if (m >= M || n >= g.N) continue;
-      float v[8] = {lo.x + bv[0], lo.y + bv[1], lo.z + bv[2], lo.w + bv[3],
-                    hi.x + bv[4], hi.y + bv[5], hi.z + bv[6], hi.w + bv[7]};
-      if (g.act) {
-#pragma unroll
-        for (int e = 0; e < 8; ++e) v[e] = apply_act(v[e], g.act);
+        for (int r = 0; r < 8; ++r) p[(frag_row(lane, 8 * h + r) - 16 * h) * E::STRIDE] = acc[i][j][8 * h + r];
       }
-      if (resid) {
-        float rr[8];
-        Vec16<bf16_t>::load(reinterpret_cast<const bf16_t*>(resid + map_row(g.r_rows, m, g.S) * g.ldr + n), rr);
+      const int mb = m0 + wm * (C::BM / C::WM) + i * 32 + h * 16;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) v[e] += rr[e];
+      for (int pass = 0; pass < 16 / E::ROWS_PER_PASS; ++pass) {
+        const int row = pass * E::ROWS_PER_PASS + prow;
+        const int m = mb + row;
+        const float4 lo = *reinterpret_cast<const float4*>(region + row * E::STRIDE + c8);
+        const float4 hi = *reinterpret_cast<const float4*>(region + row * E::STRIDE + c8 + 4);
+        if (m >= M || n >= g.N) continue;
+        float v[8] = {lo.x + bv[0], lo.y + bv[1], lo.z + bv[2], lo.w + bv[3],
+                      hi.x + bv[4], hi.y + bv[5], hi.z + bv[6], hi.w + bv[7]};
+        if (g.act) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) v[e] = apply_act(v[e], g.act);
+        }
+        if (resid) {
+          float rr[8];
+          Vec16<bf16_t>::load(reinterpret_cast<const bf16_t*>(resid + map_row(g.r_rows, m, g.S) * g.ldr + n), rr);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) v[e] += rr[e];
+        }
+        Vec16<bf16_t>::store(reinterpret_cast<bf16_t*>(out + map_row(g.o_rows, m, g.S) * g.ldo + n), v);
       }
-      Vec16<bf16_t>::store(reinterpret_cast<bf16_t*>(out + map_row(g.o_rows, m, g.S) * g.ldo + n), v);
     }
   }
-  dma::barrier();      // the next tile's loads overwrite every region
 }
 
 template <class C>
 constexpr size_t gemm_dma_smem_bytes() {
-  return C::LDS_BYTES > WaveEpilogue<C>::BYTES ? C::LDS_BYTES : WaveEpilogue<C>::BYTES;
+  return C::LDS_BYTES;
 }
 
-// Same contract, main loop with direct global -> LDS loads (C is a DmaCfg); K % 64 == 0.
+// Same contract, main loop with direct global -> LDS loads (C is a DmaCfg with two stages); K % 64 == 0.
+// A workgroup walks its tiles with ONE ring of two stages that runs on across tiles: when the main loop of a tile
+// ends, the first loads of the workgroup's next tile go into the stage that is free, and only then does the epilogue
+// start (its staging lives in the stage the last step has just been read from), so the memory latency of a tile's
+// first step hides behind the previous tile's epilogue instead of standing in front of every tile.
 template <class C>
 __global__ __launch_bounds__(C::THREADS) void gemm_bf16_dma_kernel(GemmArgs g, int tiles_n) {
   extern __shared__ __attribute__((aligned(16))) uint16_t lds_dyn[];
   const int n_seq = g.count ? min(*g.count, g.max_seqs) : g.max_seqs;
   const int M = n_seq * g.S;
-  const int total = ((M + C::BM - 1) / C::BM) * tiles_n;
+  const int tiles_m = (M + C::BM - 1) / C::BM;
+  const int total = tiles_m * tiles_n;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  With xcd_chunks set, XCD x
-  // walks the x-th eighth of the tile list (tiles of one row block are adjacent in it), so the
-  // activation rows of a row block are fetched into one L2 only and shared there by the column
-  // tiles; otherwise workgroups stride over the tile list.  gridDim.x % 8 == 0 when xcd_chunks.
+  // walks the x-th eighth of the tile list, so the operand panels of neighbouring tiles are fetched into one L2
+  // only and shared there; otherwise workgroups stride over the tile list.  gridDim.x % 8 == 0 when xcd_chunks.
+  // xcd_chunks == 1: the list is row-major (the column tiles of a row block are adjacent: narrow outputs);
+  // xcd_chunks == 2: grouped order, the list runs down 8 row blocks before it moves one column tile on, so the 64
+  // tiles that an XCD's workgroups hold at one time are 8 row blocks x 8 column tiles: 16 operand panels (3 MB).
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3, slots = gridDim.x >> 3;
   const int per_xcd = (total + 7) >> 3;
   const int n_it = g.xcd_chunks ? per_xcd : total;
-  for (int it = g.xcd_chunks ? slot : (int)blockIdx.x; it < n_it; it += g.xcd_chunks ? slots : (int)gridDim.x) {
-  const int tile = g.xcd_chunks ? xcd * per_xcd + it : it;
-  if (tile >= total) break;
-  int tile_m = tile / tiles_n, tile_n = tile % tiles_n;
-  if (g.xcd_chunks == 2) {
-    // grouped order: the list runs down 8 row blocks before it moves one column tile on, so the 64 tiles that an
-    // XCD's workgroups hold at one time are 8 row blocks x 8 column tiles: 8 + 8 operand panels (3 MB) in its L2
-    const int tiles_m = (M + C::BM - 1) / C::BM;
-    const int group = tile / (8 * tiles_n), in_group = tile % (8 * tiles_n);
-    const int rows_in_group = min(8, tiles_m - group * 8);
-    tile_m = group * 8 + in_group % rows_in_group;
-    tile_n = in_group / rows_in_group;
-  }
-  const int m0 = tile_m * C::BM, n0 = tile_n * C::BN;
+  const int it_step = g.xcd_chunks ? slots : (int)gridDim.x;
   const uint16_t* A = (const uint16_t*)g.A;
   const uint16_t* W = (const uint16_t*)g.W;
   const uint16_t* a_ptr[C::A_INSTR];
   const uint16_t* b_ptr[C::B_INSTR];
+  int m0 = 0, n0 = 0;
+  // tile of list position `it` (negative: none), and this lane's load addresses for it
+  auto locate = [&](int it) -> bool {
+    if (it >= n_it) return false;
+    const int tile = g.xcd_chunks ? xcd * per_xcd + it : it;
+    if (tile >= total) return false;
+    int tile_m = tile / tiles_n, tile_n = tile % tiles_n;
+    if (g.xcd_chunks == 2) {
+      const int group = tile / (8 * tiles_n), in_group = tile % (8 * tiles_n);
+      const int rows_in_group = min(8, tiles_m - group * 8);
+      tile_m = group * 8 + in_group % rows_in_group;
+      tile_n = in_group / rows_in_group;
+    }
+    m0 = tile_m * C::BM;
+    n0 = tile_n * C::BN;
 #pragma unroll
-  for (int j = 0; j < C::A_INSTR; ++j) {
-    const int tr = C::load_row(j, wave, lane);
-    const int r = min(m0 + tr, M - 1);
-    a_ptr[j] = A + map_row(g.a_rows, r, g.S) * g.lda + C::load_chunk(tr, lane) * 8;
-  }
+    for (int j = 0; j < C::A_INSTR; ++j) {
+      const int tr = C::load_row(j, wave, lane);
+      const int r = min(m0 + tr, M - 1);
+      a_ptr[j] = A + map_row(g.a_rows, r, g.S) * g.lda + C::load_chunk(tr, lane) * 8;
+    }
 #pragma unroll
-  for (int j = 0; j < C::B_INSTR; ++j) {
-    const int tr = C::load_row(j, wave, lane);
-    const int r = min(n0 + tr, g.N - 1);
-    b_ptr[j] = W + (size_t)r * g.K + C::load_chunk(tr, lane) * 8;
-  }
-  f32x16_t acc[C::FM][C::FN];
+    for (int j = 0; j < C::B_INSTR; ++j) {
+      const int tr = C::load_row(j, wave, lane);
+      const int r = min(n0 + tr, g.N - 1);
+      b_ptr[j] = W + (size_t)r * g.K + C::load_chunk(tr, lane) * 8;
+    }
+    return true;
+  };
+  int it = g.xcd_chunks ? slot : (int)blockIdx.x;
+  if (!locate(it)) return;
+  const int nk = g.K / C::BK;
+  int ring = 0;
+  dma_issue<C>(a_ptr, b_ptr, 0, 0, lds_dyn);
+  while (true) {
+    f32x16_t acc[C::FM][C::FN];
 #pragma unroll
-  for (int i = 0; i < C::FM; ++i)
+    for (int i = 0; i < C::FM; ++i)
 #pragma unroll
-    for (int j = 0; j < C::FN; ++j)
+      for (int j = 0; j < C::FN; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-  mma_block_dma<C>(a_ptr, b_ptr, g.K, lds_dyn, acc);
-  gemm_epilogue_wave<C>(g, acc, m0, n0, M, reinterpret_cast<float*>(lds_dyn));
+        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    mma_block_dma_ring<C>(a_ptr, b_ptr, g.K, lds_dyn, acc, ring);
+    const int cur_m0 = m0, cur_n0 = n0;
+    const int last_stage = (ring + nk - 1) & 1;
+    ring += nk;
+    it += it_step;
+    const bool more = locate(it);                       // uniform over the workgroup
+    if (more) dma_issue<C>(a_ptr, b_ptr, 0, ring & 1, lds_dyn);
+    gemm_epilogue_wave16<C>(g, acc, cur_m0, cur_n0, M, reinterpret_cast<float*>(lds_dyn + last_stage * C::STAGE_ELEMS));
+    if (!more) break;
   }
 }
 

@@ -170,31 +170,35 @@ struct DmaCfg {
 // a_ptr[j] / b_ptr[j]: global address (k = 0) of the 16-byte chunk that this lane fetches in
 // its j-th A / B load: row load_row(j, wave, lane) of the tile (resolved and clamped by the
 // caller), element offset load_chunk(row, lane) * 8.  K must be a multiple of 64.
+// The main loop is a ring of two stages that runs on across the tiles of a workgroup.
+// dma_issue: the loads of k-tile kt of the tile that a_ptr / b_ptr describe, into ring stage `stage`.
 template <class C>
-__device__ __forceinline__ void mma_block_dma(const uint16_t* const (&a_ptr)[C::A_INSTR],
-                                              const uint16_t* const (&b_ptr)[C::B_INSTR], int K, uint16_t* lds,
-                                              f32x16_t (&acc)[C::FM][C::FN]) {
+__device__ __forceinline__ void dma_issue(const uint16_t* const (&a_ptr)[C::A_INSTR],
+                                          const uint16_t* const (&b_ptr)[C::B_INSTR], int kt, int stage, uint16_t* lds) {
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  uint16_t* st = lds + stage * C::STAGE_ELEMS;
+  const int ko = kt * C::BK;
+#pragma unroll
+  for (int j = 0; j < C::A_INSTR; ++j)
+    __builtin_amdgcn_global_load_lds(LLMC_GPTR(a_ptr[j] + ko), LLMC_LPTR(st + (j * C::NW + wave) * 8 * C::BK), 16, 0, 0);
+#pragma unroll
+  for (int j = 0; j < C::B_INSTR; ++j)
+    __builtin_amdgcn_global_load_lds(LLMC_GPTR(b_ptr[j] + ko),
+                                     LLMC_LPTR(st + C::BM * C::BK + (j * C::NW + wave) * 8 * C::BK), 16, 0, 0);
+}
+
+// mma_block_dma with the ring position carried by the caller: k-tile 0 of this tile has ALREADY been issued into
+// stage ring % 2 (by the previous tile, before its epilogue, or by the kernel's prologue), k-tile kt lives in stage
+// (ring + kt) % 2.  Ends with a barrier: every wavefront is done reading both stages.
+template <class C>
+__device__ __forceinline__ void mma_block_dma_ring(const uint16_t* const (&a_ptr)[C::A_INSTR],
+                                                   const uint16_t* const (&b_ptr)[C::B_INSTR], int K, uint16_t* lds,
+                                                   f32x16_t (&acc)[C::FM][C::FN], int ring) {
+  static_assert(C::STAGES == 2, "the cross-tile ring has two stages");
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wm = wave / C::WN, wn = wave % C::WN;
   const int nk = K / C::BK;
-
-  auto issue = [&](int kt) {
-    uint16_t* st = lds + (kt % C::STAGES) * C::STAGE_ELEMS;
-    const int ko = kt * C::BK;
-#pragma unroll
-    for (int j = 0; j < C::A_INSTR; ++j)
-      __builtin_amdgcn_global_load_lds(LLMC_GPTR(a_ptr[j] + ko), LLMC_LPTR(st + (j * C::NW + wave) * 8 * C::BK), 16, 0, 0);
-#pragma unroll
-    for (int j = 0; j < C::B_INSTR; ++j)
-      __builtin_amdgcn_global_load_lds(LLMC_GPTR(b_ptr[j] + ko),
-                                       LLMC_LPTR(st + C::BM * C::BK + (j * C::NW + wave) * 8 * C::BK), 16, 0, 0);
-  };
-#pragma unroll
-  for (int s = 0; s < C::STAGES - 1; ++s)
-    if (s < nk) issue(s);
-
-  // fragment read offsets (elements): row * 64 + ((chunk ^ ((row / 2) & 7)) * 8), (row / 2) & 7 == (lane / 2) & 7
   const int a_row = (wm * (C::BM / C::WM) + (lane & 31)) * C::BK;
   const int b_row = C::BM * C::BK + (wn * (C::BN / C::WN) + (lane & 31)) * C::BK;
   int sw[4];
@@ -202,14 +206,10 @@ __device__ __forceinline__ void mma_block_dma(const uint16_t* const (&a_ptr)[C::
   for (int ks = 0; ks < 4; ++ks) sw[ks] = (((ks * 2 + (lane >> 5)) ^ ((lane >> 1) & 7)) * 8);
 
   for (int kt = 0; kt < nk; ++kt) {
-    const int ahead = min(C::STAGES - 2, nk - 1 - kt);
-    if (ahead <= 0) LLMC_WAIT_VM(0);
-    else if (ahead == 1) LLMC_WAIT_VM(C::L);
-    else LLMC_WAIT_VM(2 * C::L);
+    LLMC_WAIT_VM(0);
     dma::barrier();
-    if (kt + C::STAGES - 1 < nk) issue(kt + C::STAGES - 1);
-    const uint16_t* st = lds + (kt % C::STAGES) * C::STAGE_ELEMS;
-    // fragments of the next 16-column step are fetched while the current step multiplies
+    if (kt + 1 < nk) dma_issue<C>(a_ptr, b_ptr, kt + 1, (ring + kt + 1) & 1, lds);
+    const uint16_t* st = lds + ((ring + kt) & 1) * C::STAGE_ELEMS;
     bf16x8_t fa[2][C::FM], fb[2][C::FN];
 #pragma unroll
     for (int i = 0; i < C::FM; ++i) fa[0][i] = *reinterpret_cast<const bf16x8_t*>(st + a_row + i * 32 * C::BK + sw[0]);
@@ -219,8 +219,6 @@ __device__ __forceinline__ void mma_block_dma(const uint16_t* const (&a_ptr)[C::
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
       const int c = ks & 1, n = c ^ 1;
-      // this step's fragments were requested one step ago: wait for them BEFORE requesting the next
-      // ones, so that the wait never covers a request that has only just been issued
       __builtin_amdgcn_sched_barrier(0);
       LLMC_WAIT_LGKM(0);
       __builtin_amdgcn_sched_barrier(0);
@@ -237,12 +235,11 @@ __device__ __forceinline__ void mma_block_dma(const uint16_t* const (&a_ptr)[C::
 #pragma unroll
         for (int j = 0; j < C::FN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[c][i], fb[c][j], acc[i][j], 0, 0, 0);
-      // keep the written order: the next step's LDS reads are issued before this step's MFMAs
       if (ks + 1 < 4) __builtin_amdgcn_sched_group_barrier(0x100, C::FM + C::FN, 0);
       __builtin_amdgcn_sched_group_barrier(0x008, C::FM * C::FN, 0);
     }
   }
-  dma::barrier();   // every wavefront is done reading before the caller reuses the LDS
+  dma::barrier();
 }
 
 }  // namespace llmc
