@@ -142,7 +142,7 @@ struct WaveEpilogue16 {
 
 template <class C>
 __device__ __forceinline__ void gemm_epilogue_wave16(const GemmArgs& g, f32x16_t (&acc)[C::FM][C::FN], int m0, int n0,
-                                                     int M, float* stage) {
+                                                     int M, float* stage, bool wait_before_last) {
   using E = WaveEpilogue16<C>;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -174,20 +174,24 @@ __device__ __forceinline__ void gemm_epilogue_wave16(const GemmArgs& g, f32x16_t
         const int m = mb + row;
         const float4 lo = *reinterpret_cast<const float4*>(region + row * E::STRIDE + c8);
         const float4 hi = *reinterpret_cast<const float4*>(region + row * E::STRIDE + c8 + 4);
-        if (m >= M || n >= g.N) continue;
+        const bool live = m < M && n < g.N;
         float v[8] = {lo.x + bv[0], lo.y + bv[1], lo.z + bv[2], lo.w + bv[3],
                       hi.x + bv[4], hi.y + bv[5], hi.z + bv[6], hi.w + bv[7]};
         if (g.act) {
 #pragma unroll
           for (int e = 0; e < 8; ++e) v[e] = apply_act(v[e], g.act);
         }
-        if (resid) {
+        if (resid && live) {
           float rr[8];
           Vec16<bf16_t>::load(reinterpret_cast<const bf16_t*>(resid + map_row(g.r_rows, m, g.S) * g.ldr + n), rr);
 #pragma unroll
           for (int e = 0; e < 8; ++e) v[e] += rr[e];
         }
-        Vec16<bf16_t>::store(reinterpret_cast<bf16_t*>(out + map_row(g.o_rows, m, g.S) * g.ldo + n), v);
+        // before the LAST stores of the tile: everything this wavefront has in flight has landed, in particular its
+        // loads of the next tile's first step (issued before this epilogue began); the stores below are then the
+        // only traffic outstanding when the next tile's main loop starts, and its first step does not wait for them
+        if (wait_before_last && i == C::FM - 1 && h == 1 && pass == 16 / E::ROWS_PER_PASS - 1) LLMC_WAIT_VM(0);
+        if (live) Vec16<bf16_t>::store(reinterpret_cast<bf16_t*>(out + map_row(g.o_rows, m, g.S) * g.ldo + n), v);
       }
     }
   }
@@ -259,6 +263,7 @@ __global__ __launch_bounds__(C::THREADS) void gemm_bf16_dma_kernel(GemmArgs g, i
   const int nk = g.K / C::BK;
   int ring = 0;
   dma_issue<C>(a_ptr, b_ptr, 0, 0, lds_dyn);
+  LLMC_WAIT_VM(0);
   while (true) {
     f32x16_t acc[C::FM][C::FN];
 #pragma unroll
@@ -274,7 +279,7 @@ __global__ __launch_bounds__(C::THREADS) void gemm_bf16_dma_kernel(GemmArgs g, i
     it += it_step;
     const bool more = locate(it);                       // uniform over the workgroup
     if (more) dma_issue<C>(a_ptr, b_ptr, 0, ring & 1, lds_dyn);
-    gemm_epilogue_wave16<C>(g, acc, cur_m0, cur_n0, M, reinterpret_cast<float*>(lds_dyn + last_stage * C::STAGE_ELEMS));
+    gemm_epilogue_wave16<C>(g, acc, cur_m0, cur_n0, M, reinterpret_cast<float*>(lds_dyn + last_stage * C::STAGE_ELEMS), more);
     if (!more) break;
   }
 }

@@ -187,9 +187,9 @@ __device__ __forceinline__ void dma_issue(const uint16_t* const (&a_ptr)[C::A_IN
                                      LLMC_LPTR(st + C::BM * C::BK + (j * C::NW + wave) * 8 * C::BK), 16, 0, 0);
 }
 
-// mma_block_dma with the ring position carried by the caller: k-tile 0 of this tile has ALREADY been issued into
-// stage ring % 2 (by the previous tile, before its epilogue, or by the kernel's prologue), k-tile kt lives in stage
-// (ring + kt) % 2.  Ends with a barrier: every wavefront is done reading both stages.
+// The main loop with the ring position carried by the caller: k-tile 0 of this tile has ALREADY been issued into
+// stage ring % 2 (by the previous tile, before its epilogue, or by the kernel's prologue) AND waited for by the
+// issuing wavefront; k-tile kt lives in stage (ring + kt) % 2.  Ends with a barrier: every wavefront is done reading both stages.
 template <class C>
 __device__ __forceinline__ void mma_block_dma_ring(const uint16_t* const (&a_ptr)[C::A_INSTR],
                                                    const uint16_t* const (&b_ptr)[C::B_INSTR], int K, uint16_t* lds,
@@ -206,7 +206,9 @@ __device__ __forceinline__ void mma_block_dma_ring(const uint16_t* const (&a_ptr
   for (int ks = 0; ks < 4; ++ks) sw[ks] = (((ks * 2 + (lane >> 5)) ^ ((lane >> 1) & 7)) * 8);
 
   for (int kt = 0; kt < nk; ++kt) {
-    LLMC_WAIT_VM(0);
+    // k-tile 0: the caller has already waited for this wavefront's loads of it (in the kernel's prologue, or late
+    // in the previous tile's epilogue, so that the epilogue's last stores need not drain before the tile starts)
+    if (kt > 0) LLMC_WAIT_VM(0);
     dma::barrier();
     if (kt + 1 < nk) dma_issue<C>(a_ptr, b_ptr, kt + 1, (ring + kt + 1) & 1, lds);
     const uint16_t* st = lds + ((ring + kt) & 1) * C::STAGE_ELEMS;
