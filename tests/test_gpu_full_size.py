@@ -347,6 +347,78 @@ def test_gpt2_small_full_config_all_rows(L, made):
         torch.cuda.empty_cache()
 
 
+def test_gpt2_small_full_config_with_prefix_attention_keys(L, made):
+    """The GPT-2-shaped configuration looked up under keys that include the prefix attention statistics of the first
+    256 tokens (the shortest prefix a query of this workload shares with its source), both features centred on the
+    bank sources and the attention feature weighted as the benchmark does.  All 16 rows at all 12 layers: the GPU's
+    keys against the oracle's (the attention feature passes through three bf16 products, so 1.5e-3 on the unit-norm
+    key), decisions, slots and similarities against the oracle's match fed the GPU's keys (1e-5), reused rows bit-equal
+    to the bank, two computed rows at the first and the last layer against f_l."""
+    from paper_2512_16843_amd.engine import GatedStack
+    from paper_2512_16843_amd.centring import prefix_feature_stats
+    cfg = W.GPT2_SMALL
+    n_p = cfg.S // 4
+    say(f"{cfg.name} with prefix attention keys: first {n_p} tokens, L={cfg.n_layers} B={cfg.B} S={cfg.S} bank {cfg.n_bank}")
+    ws = W.make_layer_weights(cfg, seed=0)
+    tok, pos = W.make_embeddings(cfg, seed=0)
+    tok, pos = tok.cuda(), pos.cuda()
+    Ps = W.make_projection(cfg.d, cfg.k, cfg.torch_dtype, seed=3, n_layers=cfg.n_layers)
+    Pa = W.make_projection(cfg.d, cfg.k, cfg.torch_dtype, seed=13, n_layers=cfg.n_layers)
+    src = W.make_sources(cfg, cfg.n_bank, seed=1)
+    stats = prefix_feature_stats(cfg, ws, [torch.cat([Ps[l], Pa[l]]) for l in range(cfg.n_layers)],
+                                 source_batches(cfg, src, tok, pos), n_p)
+    P2, cs = [], []
+    for l, (mu, var_p, var_a) in enumerate(stats):
+        w_a = 3.0 * (var_p / max(var_a, 1e-30)) ** 0.5
+        p2 = torch.cat([Ps[l].float(), Pa[l].float() * w_a]).to(cfg.torch_dtype)
+        P2.append(p2)
+        cs.append((-(mu @ p2.to(torch.float64))).to(torch.float32).contiguous())
+    st = GatedStack(cfg, ws, Ps, biases=cs, prefix_tokens=n_p, proj2=P2)
+    made.append(st)
+    build_banks(L, st, cfg, src, tok, pos)
+    ids, srcmap, plen = W.make_prefix_queries(cfg, src, seed=2)
+    assert plen.min() >= n_p
+    h0 = W.embed(torch.from_numpy(ids).cuda(), tok, pos, cfg.torch_dtype)
+    tau = 0.95
+    outs = st.forward(h0, tau=tau, keep_all=True)
+    torch.cuda.synchronize()
+    tau32 = f32(tau)
+    total_hits = 0
+    for l in range(cfg.n_layers):
+        h_prev = h0 if l == 0 else outs[l - 1]
+        g, bank = st.gate[l], st.banks[l]
+        wnp = {k_: npf(v) for k_, v in ws[l].items()}
+        q_g, qinv_g = npf(st.pfx_fp[l]), npf(st.pfx_inv[l])
+        q_o, _ = O.fingerprint_prefix(npf(h_prev), npf(P2[l]), npf(cs[l]), "bf16", wnp, cfg.arch, cfg.n_heads, cfg.ln_eps, n_p)
+        key_err = float(np.abs(q_g - q_o).max())
+        assert key_err < 1.5e-3, (l, key_err)
+        np.testing.assert_allclose(qinv_g, O.inv_norm(q_g), rtol=3e-7, atol=0)
+        fp, inv, valid = npf(bank.fp), npf(bank.inv_norm), bank.valid.cpu().numpy()
+        hit = g.hit.cpu().numpy().astype(bool)
+        idx = g.idx.cpu().numpy()
+        idx_o, sim_o = O.match(q_g, qinv_g, fp, inv, valid)
+        np.testing.assert_allclose(npf(g.sim).astype(np.float64), sim_o, rtol=0, atol=1e-5)
+        near = np.abs(sim_o - tau32) < 1e-3
+        assert np.array_equal(hit[~near], O.threshold(sim_o, tau32)[~near])
+        ties = O.near_tie_sets(q_g, qinv_g, fp, inv, valid)
+        for b in range(cfg.B):
+            assert idx[b] == idx_o[b] or idx[b] in ties[b], (l, b)
+        # what the feature is for: a query that hits, hits its own source (the entry built from it)
+        if l == 0:
+            own = npf(bank.fp)[idx[hit]]
+            src_keys, _ = O.fingerprint_prefix(npf(W.embed(torch.from_numpy(src[srcmap[hit]]).cuda(), tok, pos, cfg.torch_dtype)),
+                                               npf(P2[0]), npf(cs[0]), "bf16", wnp, cfg.arch, cfg.n_heads, cfg.ln_eps, n_p)
+            assert np.abs(own - src_keys).max() < 1.5e-3
+        miss = np.nonzero(~hit)[0].tolist()
+        pick = miss[:2] if l in (0, cfg.n_layers - 1) else []
+        err = check_layer_outputs(L, cfg, g, bank, h_prev, outs[l], ws[l], pick)
+        total_hits += int(hit.sum())
+        say("  layer %2d: hits %2d of %d, near tau %d, max |key - oracle key| %.2e, computed rows checked %d (max err %.2e)"
+            % (l, int(hit.sum()), cfg.B, int(near.sum()), key_err, len(pick), err))
+    assert total_hits >= cfg.B * cfg.n_layers // 2
+    release(st)
+
+
 def test_match_stress_full_size(L, made):
     say("bank-match stress: 1,048,576 keys x 256, 4,096 queries, threshold 0.95, gather of 384 x 768 outputs")
     data = W.make_clustered_bank(4096, 256, 256, 0.05, 4096, seed=5)
