@@ -34,6 +34,7 @@ if ROOT not in sys.path:
 METRIC = "seq/s cache-gated 12L d768 forward vs hit rate; match MFMA% + gather HBM GB/s"
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
+MFMA_INT8_PEAK_TOPS = 5000.0
 FP32_VALU_PEAK_TFLOPS = 157.3
 INT_VALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12      # 32-bit integer vector instructions: one per lane per clock, 39.3 T/s
 CALIB_COPY_BYTES = 256 << 20
@@ -559,6 +560,20 @@ def match_stress(llmc, W, iters=10):
     rep_b = llmc.llmc_profile_report()
     llmc.llmc_profile_end()
     us_b = {name: ms * 1e3 / cnt for name, (cnt, ms) in rep_b.items()}
+    # 4,096 queries of 256-bit keys run as an int8 matrix product; 256 queries at a time stay on the vector ALU
+    # (XOR + popcount): time that scan on the first 256 queries for comparison
+    Bv = 256
+    ws_v = torch.empty((llmc.llmc_match_bits_workspace_bytes(N, kb, Bv),), dtype=torch.uint8, device="cuda")
+    qv_bits = q_bits[:Bv].contiguous()
+    llmc.llmc_match_bits(bank_bits, bank.valid, qv_bits, max_h, idx_b[:Bv], dist_b[:Bv], hit_b[:Bv], ws_v)
+    torch.cuda.synchronize()
+    llmc.llmc_profile_begin(4 * iters)
+    for _ in range(iters):
+        llmc.llmc_match_bits(bank_bits, bank.valid, qv_bits, max_h, idx_b[:Bv], dist_b[:Bv], hit_b[:Bv], ws_v)
+    rep_v = llmc.llmc_profile_report()
+    llmc.llmc_profile_end()
+    us_v = {name: ms * 1e3 / cnt for name, (cnt, ms) in rep_v.items()}
+    del ws_v
     # bucketed lookup over the same bit keys: 16 bands of 16 bits, compare only with bucket members
     index = torch.empty((llmc.llmc_lsh_index_bytes(N, kb),), dtype=torch.uint8, device="cuda")
     idx_l = torch.empty((B,), dtype=torch.int32, device="cuda")
@@ -589,17 +604,25 @@ def match_stress(llmc, W, iters=10):
     hb = hit.bool()
     same_cluster = float((cluster[idx_b.long()] == cluster[idx.long()])[hb].float().mean()) if bool(hb.any()) else 1.0
     same_decision = float((hit_b == hit).float().mean())
-    word_ops = 2.0 * B * N * (kb // 32)                  # one XOR and one popcount-accumulate per 32 bit pairs
+    word_ops = 2.0 * Bv * N * (kb // 32)                 # one XOR and one popcount-accumulate per 32 bit pairs
+    int8_ops = 2.0 * B * N * kb                          # the same scan as a product of 0/1 bytes
+    mma_us = us_b["match_bits_mma_kernel"]
     bits = {"key_bits": kb, "bank_bytes": N * kb // 8, "max_hamming": int(max_h),
-            "match_us": round(us_b["match_bits_kernel"], 2),
-            "other_us": round(sum(v for n_, v in us_b.items() if n_ != "match_bits_kernel"), 2),
-            "tera_word_ops_per_s": round(word_ops / us_b["match_bits_kernel"] / 1e6, 2),
-            "frac_int_valu_peak": round(word_ops / us_b["match_bits_kernel"] / 1e6 / INT_VALU_PEAK_TOPS, 4),
+            "match_us": round(mma_us, 2),
+            "other_us": round(sum(v for n_, v in us_b.items() if n_ != "match_bits_mma_kernel"), 2),
+            "int8_peta_ops_per_s": round(int8_ops / mma_us / 1e9, 3),
+            "frac_int8_mfma_peak": round(int8_ops / mma_us / 1e6 / MFMA_INT8_PEAK_TOPS, 4),
+            "vector_scan_256_queries": {
+                "match_us": round(us_v["match_bits_kernel"], 2),
+                "tera_word_ops_per_s": round(word_ops / us_v["match_bits_kernel"] / 1e6, 2),
+                "frac_int_valu_peak": round(word_ops / us_v["match_bits_kernel"] / 1e6 / INT_VALU_PEAK_TOPS, 4)},
             "hits": int(hit_b.sum()), "same_cluster_as_cosine_match_on_hits": round(same_cluster, 4),
             "same_decision_as_cosine_match": round(same_decision, 4), "lsh": lsh}
-    log("sign-bit keys on the same bank (%d bits, %d MB instead of 512): Hamming match %.1f us -> %.2f T word-ops/s "
-        "(%.1f%% of the integer vector peak); bucketed lookup %.1f us (index build %.1f us), same decision %.4f"
-        % (kb, bits["bank_bytes"] >> 20, bits["match_us"], bits["tera_word_ops_per_s"], 100 * bits["frac_int_valu_peak"],
+    log("sign-bit keys on the same bank (%d bits, %d MB instead of 512): Hamming match on the matrix cores %.1f us -> "
+        "%.2f P int8-ops/s (%.1f%% of the int8 peak); vector scan of 256 queries %.1f us (%.1f%% of the integer "
+        "vector peak); bucketed lookup %.1f us (index build %.1f us), same decision %.4f"
+        % (kb, bits["bank_bytes"] >> 20, bits["match_us"], bits["int8_peta_ops_per_s"], 100 * bits["frac_int8_mfma_peak"],
+           us_v["match_bits_kernel"], 100 * bits["vector_scan_256_queries"]["frac_int_valu_peak"],
            lsh["match_us"], lsh["build_us"], lsh["same_decision_as_full_match"]))
     del bank_bits, q_bits, ws_f, ws_b
     bank.close()

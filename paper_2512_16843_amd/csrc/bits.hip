@@ -15,6 +15,7 @@
 // A workgroup of 4 wavefronts owns 256 queries and a range of at most 2^20 bank rows; a second
 // kernel merges the ranges per query in ascending row order.
 #include "common.h"
+#include "mma.h"
 
 namespace llmc {
 
@@ -83,6 +84,183 @@ __global__ __launch_bounds__(kBitsThreads) void match_bits_generic_kernel(const 
   if (bq < B) partial[(size_t)blockIdx.x * B + bq] = best;
 }
 
+// ---- matrix-core variant: many queries, 256-bit keys ------------------------------------------------
+// The number of common set bits of two keys is a dot product of their bits, and
+//   H(q, b) = |q| + |b| - 2 * common(q, b),
+// so the scan becomes an int8 matrix product (v_mfma_i32_32x32x32_i8) of bank rows by queries.
+// Bank bits are expanded to bytes of value 2 on their way into LDS, query bits to bytes of value
+// -128 in registers: the product of two set bits is -256, and an accumulator that STARTS at
+//   start[row] = 128 * (|b_row| + penalty_row) + (row within its 64-row tile)
+// ends at 128 * (H - |q|) + (row within the tile).  The smallest accumulator of a lane is therefore
+// its nearest row, lowest row among equals, and the whole reduction is one three-way minimum per two
+// scores; validity, the key's own popcount and the row number cost no instruction.
+// A workgroup of 4 wavefronts owns 256 queries (64 per wavefront, fragments in registers) and a range
+// of 64-row tiles; two workgroups share a compute unit so that one's expansion and reduction run
+// under the other's matrix instructions.  The bank is read as bits (32 bytes per key).
+typedef int i32x4_t __attribute__((ext_vector_type(4)));
+typedef int i32x16_t __attribute__((ext_vector_type(16)));
+
+struct BitsMma {
+  static constexpr int K = 256, W = 8, RB = 64, NW = 4, THREADS = NW * 64, QW = 64, QB = NW * QW;
+  static constexpr int ROWB = K;                         // one byte per bit
+  static constexpr int TILE_BYTES = RB * ROWB;
+  static constexpr int STAGE_BYTES = TILE_BYTES + RB * 4;   // + the tile's start words
+  static constexpr int LDS_BYTES = 2 * STAGE_BYTES;
+  static constexpr int SCALE = 128;                      // accumulator units per bit of distance
+};
+
+// start[j] for every row of the padded bank (n_pad: a whole number of tiles)
+__global__ void bits_start_kernel(const uint32_t* __restrict__ bank, const uint8_t* __restrict__ valid, int N, int n_pad,
+                                  int32_t* __restrict__ start) {
+  const int j = blockIdx.x * blockDim.x + threadIdx.x;
+  if (j >= n_pad) return;
+  // rows past the end read the last key (as the scan does) and carry the penalty of a free slot
+  const int jr = min(j, N - 1);
+  const uint4* kp = reinterpret_cast<const uint4*>(bank + (size_t)jr * BitsMma::W);
+  const uint4 a = kp[0], b = kp[1];
+  uint32_t h = __builtin_popcount(a.x) + __builtin_popcount(a.y) + __builtin_popcount(a.z) + __builtin_popcount(a.w) +
+               __builtin_popcount(b.x) + __builtin_popcount(b.y) + __builtin_popcount(b.z) + __builtin_popcount(b.w);
+  if (j >= N || valid[j] == 0) h += kFreePenalty;
+  start[j] = (int32_t)(h * BitsMma::SCALE + (uint32_t)(j & (BitsMma::RB - 1)));
+}
+
+// four bits -> four bytes (bit i of t in byte i), each `unit` or 0; unit * 0x204081 must stay below 2^24
+template <uint32_t UNIT>
+__device__ __forceinline__ int spread4(uint32_t t) {
+  return (int)((t * (0x204081u * UNIT)) & (0x01010101u * UNIT));
+}
+
+// grid: 1-D; workgroup -> (split, query block) as in the cosine kernels (the query blocks of a split on one XCD)
+__global__ __launch_bounds__(BitsMma::THREADS, 2) void match_bits_mma_kernel(
+    const uint32_t* __restrict__ bank, const int32_t* __restrict__ start, int N, const uint32_t* __restrict__ queries,
+    int B, int n_qb, int n_split, int tiles_per_split, uint32_t* __restrict__ partial) {
+  using C = BitsMma;
+  extern __shared__ __attribute__((aligned(16))) uint8_t lds_bits[];
+  const int tid = threadIdx.x, lane = tid & 63, half = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
+  const int split = (local / n_qb) * 8 + xcd, qb = local % n_qb;
+  if (split >= n_split) return;
+  const int n_tiles = (N + C::RB - 1) / C::RB;
+  const int t_begin = split * tiles_per_split;
+  const int t_end = min(n_tiles, t_begin + tiles_per_split);
+  const int q_base = qb * C::QB + wave * C::QW;
+
+  // query fragments: column (lane % 32) of fragment j; step ks covers bits 32 ks .. 32 ks + 31, this lane
+  // half's 16 of them as 16 bytes
+  i32x4_t bq[2][C::W];
+  int pq[2];
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int q = min(q_base + j * 32 + (lane & 31), B - 1);
+    const uint4* qp = reinterpret_cast<const uint4*>(queries + (size_t)q * C::W);
+    const uint4 a = qp[0], b = qp[1];
+    const uint32_t w[C::W] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+    pq[j] = 0;
+#pragma unroll
+    for (int ks = 0; ks < C::W; ++ks) {
+      pq[j] += __builtin_popcount(w[ks]);
+      const uint32_t h16 = (w[ks] >> (16 * half)) & 0xFFFFu;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) bq[j][ks][e] = spread4<1>((h16 >> (4 * e)) & 15u) << 7;   // bytes 0x80 = -128
+    }
+  }
+
+  // staging: thread (row, part) expands bits 64 part .. 64 part + 63 of tile row `row` into four 16-byte
+  // chunks; chunks of a row are XOR-swizzled by the row so that fragment reads of 16 rows cover all banks
+  const int s_row = tid >> 2, s_part = tid & 3;
+  auto load_bits = [&](int t) {
+    const int r = min(t * C::RB + s_row, N - 1);
+    return *reinterpret_cast<const uint2*>(bank + (size_t)r * C::W + s_part * 2);
+  };
+  auto expand = [&](uint2 w, int sv, int stage) {
+    uint8_t* st = lds_bits + stage * C::STAGE_BYTES;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const uint32_t h16 = ((c < 2 ? w.x : w.y) >> (16 * (c & 1))) & 0xFFFFu;
+      i32x4_t v;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) v[e] = spread4<2>((h16 >> (4 * e)) & 15u);
+      const int chunk = (s_part * 4 + c) ^ (s_row & 15);
+      *reinterpret_cast<i32x4_t*>(st + s_row * C::ROWB + chunk * 16) = v;
+    }
+    if (tid < C::RB) *reinterpret_cast<int*>(st + C::TILE_BYTES + tid * 4) = sv;
+  };
+  // start has a whole number of tiles, so every thread's read is in bounds (only the first 64 are used)
+  expand(load_bits(t_begin), start[(size_t)t_begin * C::RB + lane], 0);
+  uint2 nb = make_uint2(0u, 0u);
+  int nsv = 0;
+  if (t_begin + 1 < t_end) {
+    nb = load_bits(t_begin + 1);
+    nsv = start[(size_t)(t_begin + 1) * C::RB + lane];
+  }
+
+  int best_v[2] = {0x7FFFFFFF, 0x7FFFFFFF}, best_row[2] = {0, 0};
+  const int frag_off = (lane & 31) * C::ROWB, fsw = lane & 15;
+
+  for (int t = t_begin; t < t_end; ++t) {
+    const int cur = (t - t_begin) & 1;
+    LLMC_WAIT_LGKM(0);                     // this thread's part of tile t is in LDS
+    dma::barrier();                        // ... and everybody's; the other stage is no longer read
+    if (t + 1 < t_end) {
+      expand(nb, nsv, cur ^ 1);
+      if (t + 2 < t_end) {
+        nb = load_bits(t + 2);
+        nsv = start[(size_t)(t + 2) * C::RB + lane];
+      }
+    }
+    const uint8_t* stg = lds_bits + cur * C::STAGE_BYTES;
+    const int* sst = reinterpret_cast<const int*>(stg + C::TILE_BYTES);
+    i32x16_t acc[2][2];
+    i32x16_t c0[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const i32x4_t v = *reinterpret_cast<const i32x4_t*>(sst + i * 32 + half * 4 + 8 * c);
+        c0[i][4 * c] = v[0]; c0[i][4 * c + 1] = v[1]; c0[i][4 * c + 2] = v[2]; c0[i][4 * c + 3] = v[3];
+      }
+#pragma unroll
+    for (int ks = 0; ks < C::W; ++ks) {
+      i32x4_t fa[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+        fa[i] = *reinterpret_cast<const i32x4_t*>(stg + i * 32 * C::ROWB + frag_off + (((ks * 2 + half) ^ fsw) * 16));
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], bq[j][ks], ks == 0 ? c0[i] : acc[i][j], 0, 0, 0);
+    }
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      int m = min(acc[0][j][0], acc[1][j][0]);
+#pragma unroll
+      for (int r = 1; r < 16; ++r) m = min(min(m, acc[0][j][r]), acc[1][j][r]);
+      // tiles ascend: a strictly smaller distance wins, so the lowest row is kept among equals
+      const int v = m >> 7;
+      if (v < best_v[j]) {
+        best_v[j] = v;
+        best_row[j] = t * C::RB + (m & (C::SCALE - 1));
+      }
+    }
+  }
+  // the two lane halves saw different rows of the same query column
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int ov = __shfl_xor(best_v[j], 32, 64), orow = __shfl_xor(best_row[j], 32, 64);
+    if (ov < best_v[j] || (ov == best_v[j] && orow < best_row[j])) {
+      best_v[j] = ov;
+      best_row[j] = orow;
+    }
+    const int q = q_base + j * 32 + (lane & 31);
+    if (half == 0 && q < B) {
+      const uint32_t h = (uint32_t)(pq[j] + best_v[j]);     // the distance (+ the penalty of a free slot)
+      partial[(size_t)split * B + q] = (h << 20) | (uint32_t)(best_row[j] - t_begin * C::RB);
+    }
+  }
+}
+
 // one thread per query: merge the splits in ascending row order (a strictly smaller distance wins, so the
 // lowest slot is kept among equals), then apply the threshold
 __global__ void match_bits_finalize_kernel(const uint32_t* __restrict__ partial, int n_split, int rows_per_split, int B,
@@ -128,16 +306,70 @@ static void bits_plan(int N, int B, int* n_split, int* rows_per_split) {
   *n_split = (N + per - 1) / per;
 }
 
+// the matrix-core scan pays once a query block fills its workgroups and the bank is worth the set-up
+static bool bits_use_mma(int N, int k, int B) { return k == BitsMma::K && B >= 2 * BitsMma::QB && N >= 4096; }
+
+static void bits_mma_plan(int N, int B, int* n_qb, int* n_split, int* tiles_per_split) {
+  const int qb = (B + BitsMma::QB - 1) / BitsMma::QB;
+  const int n_tiles = (N + BitsMma::RB - 1) / BitsMma::RB;
+  int want = (2048 + qb - 1) / qb;                          // about eight workgroups per compute unit
+  want = (want + 7) / 8 * 8;                                // splits are dealt to the 8 XCDs
+  if (want > n_tiles) want = n_tiles;
+  int per = (n_tiles + want - 1) / want;
+  if (per * BitsMma::RB > (1 << 20)) per = (1 << 20) / BitsMma::RB;
+  *n_qb = qb;
+  *tiles_per_split = per;
+  *n_split = (n_tiles + per - 1) / per;
+}
+
 size_t match_bits_ws_bytes(int N, int k, int B) {
   int ns, per;
   bits_plan(N, B, &ns, &per);
-  return align_up((size_t)ns * B * sizeof(uint32_t), 256) + align_up((size_t)(N + kRowUnroll) * sizeof(uint32_t), 256);
+  size_t words = (size_t)N + kRowUnroll;
+  if (bits_use_mma(N, k, B)) {
+    int nqb, ns2, tps;
+    bits_mma_plan(N, B, &nqb, &ns2, &tps);
+    if (ns2 > ns) ns = ns2;
+    words = (size_t)N + BitsMma::RB;
+  }
+  return align_up((size_t)ns * B * sizeof(uint32_t), 256) + align_up(words * sizeof(uint32_t), 256);
 }
 
-// d_pen: ready-made penalty words [N + kRowUnroll] (a bank's mirror), or NULL to derive them from d_valid into ws
+static llmc_status_t launch_match_bits_mma(const uint32_t* d_bank_bits, const uint8_t* d_valid, int N, int k,
+                                           const uint32_t* d_query_bits, int B, int max_hamming, int32_t* d_idx,
+                                           int32_t* d_dist, uint8_t* d_hit, void* ws, hipStream_t st, float* d_sim) {
+  using C = BitsMma;
+  int nqb, ns, tps;
+  bits_mma_plan(N, B, &nqb, &ns, &tps);
+  uint32_t* partial = (uint32_t*)ws;
+  int32_t* start = (int32_t*)((char*)ws + align_up((size_t)ns * B * sizeof(uint32_t), 256));
+  const int n_pad = (N + C::RB - 1) / C::RB * C::RB;
+  { ProfScope ps_("bits_start_kernel", st);
+    LLMC_KERNEL_GGL(bits_start_kernel, dim3((n_pad + 255) / 256), dim3(256), 0, st, d_bank_bits, d_valid, N, n_pad,
+                    start); }
+  LLMC_LAUNCH_CHECK("bits_start_kernel");
+  const int grid = (ns + 7) / 8 * 8 * nqb;
+  { ProfScope ps_("match_bits_mma_kernel", st);
+    LLMC_KERNEL_GGL(match_bits_mma_kernel, dim3(grid), dim3(C::THREADS), (size_t)C::LDS_BYTES, st, d_bank_bits, start,
+                    N, d_query_bits, B, nqb, ns, tps, partial); }
+  LLMC_LAUNCH_CHECK("match_bits_mma_kernel");
+  { ProfScope ps_("match_bits_finalize_kernel", st);
+    LLMC_KERNEL_GGL(match_bits_finalize_kernel, dim3((B + 255) / 256), dim3(256), 0, st, partial, ns, tps * C::RB, B,
+                    max_hamming, d_idx, d_dist, d_hit, d_sim, k); }
+  LLMC_LAUNCH_CHECK("match_bits_finalize_kernel");
+  return LLMC_OK;
+}
+
+// d_pen: ready-made penalty words [N + kRowUnroll] (a bank's mirror), or NULL to derive them from d_valid into ws.
+// The matrix-core scan derives its own start words from d_valid into ws and is taken only when the caller sized
+// ws with match_bits_ws_bytes (d_pen == NULL).
 llmc_status_t launch_match_bits(const uint32_t* d_bank_bits, const uint8_t* d_valid, int N, int k,
                                 const uint32_t* d_query_bits, int B, int max_hamming, int32_t* d_idx, int32_t* d_dist,
                                 uint8_t* d_hit, void* ws, hipStream_t st, const uint32_t* d_pen, float* d_sim) {
+  const bool aligned16 = (((uintptr_t)d_bank_bits | (uintptr_t)d_query_bits) & 15) == 0;   // 16-byte key reads
+  if (!d_pen && aligned16 && bits_use_mma(N, k, B))
+    return launch_match_bits_mma(d_bank_bits, d_valid, N, k, d_query_bits, B, max_hamming, d_idx, d_dist, d_hit, ws, st,
+                                 d_sim);
   int ns, per;
   bits_plan(N, B, &ns, &per);
   uint32_t* partial = (uint32_t*)ws;

@@ -496,6 +496,55 @@ def test_match_stress_full_size(L, made):
     torch.cuda.empty_cache()
 
 
+def test_match_bits_stress_full_size(L, made):
+    say("sign-bit keys at the stress shape: 1,048,576 keys of 256 bits, 4,096 queries; the matrix-core scan against "
+        "the vector scan on every query and against the oracle on sampled ones")
+    data = W.make_clustered_bank(4096, 256, 256, 0.05, 4096, seed=5)
+    N, k, kb = 1048576, 256, 256
+    keys = data["bank"].cuda()
+    q = data["queries"].cuda()
+    B = q.shape[0]
+    gen = torch.Generator(device="cuda").manual_seed(21)
+    Pb = (torch.randn((k, kb), generator=gen, device="cuda") / kb ** 0.5).to(torch.bfloat16)
+    bank_bits = torch.empty((N, kb // 32), dtype=torch.int32, device="cuda")
+    q_bits = torch.empty((B, kb // 32), dtype=torch.int32, device="cuda")
+    chunk = 32768
+    ws_f = torch.empty((L.llmc_fingerprint_workspace_bytes(chunk, 1, k),), dtype=torch.uint8, device="cuda")
+    for s0 in range(0, N, chunk):
+        L.llmc_fingerprint_bits(keys[s0:s0 + chunk].view(-1, 1, k), Pb, None, bank_bits[s0:s0 + chunk], ws_f)
+    L.llmc_fingerprint_bits(q.view(B, 1, k), Pb, None, q_bits, ws_f)
+    max_h = L.llmc_max_hamming(0.95, kb)
+    g = np.random.Generator(np.random.PCG64(77))
+    holes = torch.from_numpy((g.random(N) > 0.3).astype(np.uint8)).cuda()
+    bank_np = bank_bits.cpu().numpy().view(np.uint32)
+    q_np = q_bits.cpu().numpy().view(np.uint32)
+
+    def run(valid, qb):
+        n = qb.shape[0]
+        idx = torch.empty((n,), dtype=torch.int32, device="cuda")
+        dist = torch.empty((n,), dtype=torch.int32, device="cuda")
+        hit = torch.empty((n,), dtype=torch.uint8, device="cuda")
+        ws = torch.empty((L.llmc_match_bits_workspace_bytes(N, kb, n),), dtype=torch.uint8, device="cuda")
+        L.llmc_match_bits(bank_bits, valid, qb, max_h, idx, dist, hit, ws)
+        torch.cuda.synchronize()
+        return idx, dist, hit
+
+    for name, valid in (("every slot valid", torch.ones(N, dtype=torch.uint8, device="cuda")), ("30 % free slots", holes)):
+        idx, dist, hit = run(valid, q_bits)                 # 4,096 queries at once: the matrix-core scan
+        for q0 in range(0, B, 256):                         # 256 at a time: the vector scan
+            i2, d2, h2 = run(valid, q_bits[q0:q0 + 256])
+            assert torch.equal(i2, idx[q0:q0 + 256]) and torch.equal(d2, dist[q0:q0 + 256])
+            assert torch.equal(h2, hit[q0:q0 + 256])
+        sample = list(range(0, B, 256)) + [B - 1]
+        oidx, odist = O.match_bits(q_np[sample], bank_np, valid.cpu().numpy(), kb)
+        assert np.array_equal(idx.cpu().numpy()[sample], oidx) and np.array_equal(dist.cpu().numpy()[sample], odist)
+        assert np.array_equal(hit.cpu().numpy()[sample].astype(bool), O.threshold_bits(oidx, odist, max_h))
+        say("  %s: all 4,096 queries agree between the two scans, %d sampled ones with the oracle; %d hits within %d bits"
+            % (name, len(sample), int(hit.sum()), max_h))
+    del bank_bits, keys
+    torch.cuda.empty_cache()
+
+
 def test_bert_large_dynamic_bank_scaled_teacher_forced(L, made):
     """Insertion + LRU eviction across successive batches of stem-sharing candidates, on a
     scaled copy (2 layers, 96-entry banks, batch 32) that the oracle can follow batch by batch."""

@@ -441,7 +441,9 @@ def run_match_bits(L, bank_bits, valid, q_bits, max_h):
 
 
 @pytest.mark.parametrize("N,B,k", [(1000, 37, 64), (130, 5, 256), (4099, 300, 256), (64, 1, 32), (777, 260, 128),
-                                   (50000, 513, 512), (333, 9, 96), (2500, 40, 1024)])
+                                   (50000, 513, 512), (333, 9, 96), (2500, 40, 1024),
+                                   # many queries of 256-bit keys: the scan runs on the matrix cores
+                                   (4099, 600, 256), (4096, 512, 256), (70001, 1030, 256), (9000, 513, 256)])
 def test_match_bits_is_exact(L, N, B, k):
     say(f"Hamming match N={N} B={B} k={k}")
     g = np.random.Generator(np.random.PCG64(N * 7 + B))
@@ -471,6 +473,44 @@ def test_match_bits_is_exact(L, N, B, k):
     if N > 40:
         assert idx[B - 1] == 3 and dist[B - 1] == 0 and hit[B - 1]
     say(f"  {int(hit.sum())} hits within {max_h} bits")
+
+
+@pytest.mark.parametrize("n_distinct", [1, 5, 64])
+def test_match_bits_with_many_queries_breaks_ties_to_the_lowest_slot(L, n_distinct):
+    say(f"Hamming match on the matrix cores: a bank of {n_distinct} distinct keys repeated through every tile, free slots between")
+    g = np.random.Generator(np.random.PCG64(900 + n_distinct))
+    N, B, k = 6000, 700, 256
+    distinct = g.integers(0, 2 ** 32, size=(n_distinct, 8), dtype=np.uint64).astype(np.uint32)
+    if n_distinct > 1:
+        distinct[1] = 0                       # the all-zero key: no common set bit with anything
+        distinct[2] = 0xFFFFFFFF              # and the all-ones key
+    bank = distinct[g.integers(0, n_distinct, size=N)]
+    valid = (g.random(N) > 0.4).astype(np.uint8)
+    q = distinct[g.integers(0, n_distinct, size=B)].copy()
+    for b in range(0, B, 2):                  # half of the queries a few bits away: equal distances to every copy
+        for _ in range(int(g.integers(1, 9))):
+            i = int(g.integers(0, k))
+            q[b, i // 32] ^= np.uint32(1 << (i % 32))
+    q[B - 1] = 0
+    q[B - 2] = 0xFFFFFFFF
+    max_h = O.max_hamming(f32(0.95), k)
+    idx, dist, hit = run_match_bits(L, torch.from_numpy(bank.view(np.int32)).cuda(), torch.from_numpy(valid).cuda(),
+                                    torch.from_numpy(q.view(np.int32)).cuda(), max_h)
+    oidx, odist = O.match_bits(q, bank, valid, k)
+    assert np.array_equal(idx, oidx), (np.nonzero(idx != oidx)[0][:8], idx[idx != oidx][:8], oidx[idx != oidx][:8])
+    assert np.array_equal(dist, odist)
+    assert np.array_equal(hit, O.threshold_bits(oidx, odist, max_h))
+    # nothing valid at all: every query reports no neighbour, also from this scan
+    idx, dist, hit = run_match_bits(L, torch.from_numpy(bank.view(np.int32)).cuda(),
+                                    torch.zeros(N, dtype=torch.uint8).cuda(), torch.from_numpy(q.view(np.int32)).cuda(), k)
+    assert np.all(idx == -1) and np.all(dist == O.NO_MATCH_DIST) and not hit.any()
+    # one valid slot, the last one
+    v = np.zeros(N, np.uint8)
+    v[N - 1] = 1
+    idx, dist, hit = run_match_bits(L, torch.from_numpy(bank.view(np.int32)).cuda(), torch.from_numpy(v).cuda(),
+                                    torch.from_numpy(q.view(np.int32)).cuda(), k)
+    oidx, odist = O.match_bits(q, bank, v, k)
+    assert np.all(idx == N - 1) and np.array_equal(dist, odist) and hit.all()
 
 
 def test_match_bits_empty_bank_and_thresholds(L):
