@@ -88,25 +88,28 @@ __global__ __launch_bounds__(kBitsThreads) void match_bits_generic_kernel(const 
 // The number of common set bits of two keys is a dot product of their bits, and
 //   H(q, b) = |q| + |b| - 2 * common(q, b),
 // so the scan becomes an int8 matrix product (v_mfma_i32_32x32x32_i8) of bank rows by queries.
-// Bank bits are expanded to bytes of value 2 on their way into LDS, query bits to bytes of value
-// -128 in registers: the product of two set bits is -256, and an accumulator that STARTS at
-//   start[row] = 128 * (|b_row| + penalty_row) + (row within its 64-row tile)
-// ends at 128 * (H - |q|) + (row within the tile).  The smallest accumulator of a lane is therefore
+// Bank bits are expanded to bytes on their way into LDS, query bits in registers.  Bit j of a byte of
+// the key becomes a byte of value 2^j on the bank side (one byte-replicating permute per eight bits and
+// one AND per four) and -128 / 2^j on the query side (+1 for j = 7, where the bank byte reads as -128),
+// so the product of two set bits is -128 wherever they sit, and an accumulator that STARTS at
+//   start[row] = 64 * (|b_row| + penalty_row) + (row within its 64-row tile)
+// ends at 64 * (H - |q|) + (row within the tile).  The smallest accumulator of a lane is therefore
 // its nearest row, lowest row among equals, and the whole reduction is one three-way minimum per two
 // scores; validity, the key's own popcount and the row number cost no instruction.
 // A workgroup of 4 wavefronts owns 256 queries (64 per wavefront, fragments in registers) and a range
-// of 64-row tiles; two workgroups share a compute unit so that one's expansion and reduction run
-// under the other's matrix instructions.  The bank is read as bits (32 bytes per key).
+// of 64-row tiles; three workgroups share a compute unit so that one's expansion and reduction run
+// under the others' matrix instructions.  The bank is read as bits (32 bytes per key).
 typedef int i32x4_t __attribute__((ext_vector_type(4)));
 typedef int i32x16_t __attribute__((ext_vector_type(16)));
 
 struct BitsMma {
   static constexpr int K = 256, W = 8, RB = 64, NW = 4, THREADS = NW * 64, QW = 64, QB = NW * QW;
-  static constexpr int ROWB = K;                         // one byte per bit
+  static constexpr int ROWB = K + 16;                    // one byte per bit; rows padded by one 16-byte chunk, so that
+                                                         // the same chunk of 16 consecutive rows covers all banks
   static constexpr int TILE_BYTES = RB * ROWB;
   static constexpr int STAGE_BYTES = TILE_BYTES + RB * 4;   // + the tile's start words
   static constexpr int LDS_BYTES = 2 * STAGE_BYTES;
-  static constexpr int SCALE = 128;                      // accumulator units per bit of distance
+  static constexpr int SCALE = 64;                       // accumulator units per bit of distance (two set bits: -128)
 };
 
 // start[j] for every row of the padded bank (n_pad: a whole number of tiles)
@@ -124,14 +127,25 @@ __global__ void bits_start_kernel(const uint32_t* __restrict__ bank, const uint8
   start[j] = (int32_t)(h * BitsMma::SCALE + (uint32_t)(j & (BitsMma::RB - 1)));
 }
 
-// four bits -> four bytes (bit i of t in byte i), each `unit` or 0; unit * 0x204081 must stay below 2^24
-template <uint32_t UNIT>
-__device__ __forceinline__ int spread4(uint32_t t) {
-  return (int)((t * (0x204081u * UNIT)) & (0x01010101u * UNIT));
+// byte m of w -> two words of four bytes: byte j of `lo` holds bit j of that byte at its own position
+// (value 2^j), byte j of `hi` holds bit 4 + j (value 2^(4 + j))
+__device__ __forceinline__ void spread_byte(uint32_t w, int m, uint32_t& lo, uint32_t& hi) {
+  const uint32_t r = __builtin_amdgcn_perm(w, w, 0x01010101u * (uint32_t)m);   // the byte, four times
+  lo = r & 0x08040201u;
+  hi = r & 0x80402010u;
+}
+
+// every non-zero byte -> 0xFF
+__device__ __forceinline__ uint32_t bytes_to_mask(uint32_t x) {
+  uint32_t m = 0;
+#pragma unroll
+  for (int b = 0; b < 4; ++b)
+    if ((x >> (8 * b)) & 0xFFu) m |= 0xFFu << (8 * b);
+  return m;
 }
 
 // grid: 1-D; workgroup -> (split, query block) as in the cosine kernels (the query blocks of a split on one XCD)
-__global__ __launch_bounds__(BitsMma::THREADS, 2) void match_bits_mma_kernel(
+__global__ __launch_bounds__(BitsMma::THREADS, 3) void match_bits_mma_kernel(
     const uint32_t* __restrict__ bank, const int32_t* __restrict__ start, int N, const uint32_t* __restrict__ queries,
     int B, int n_qb, int n_split, int tiles_per_split, uint32_t* __restrict__ partial) {
   using C = BitsMma;
@@ -160,15 +174,21 @@ __global__ __launch_bounds__(BitsMma::THREADS, 2) void match_bits_mma_kernel(
 #pragma unroll
     for (int ks = 0; ks < C::W; ++ks) {
       pq[j] += __builtin_popcount(w[ks]);
-      const uint32_t h16 = (w[ks] >> (16 * half)) & 0xFFFFu;
 #pragma unroll
-      for (int e = 0; e < 4; ++e) bq[j][ks][e] = spread4<1>((h16 >> (4 * e)) & 15u) << 7;   // bytes 0x80 = -128
+      for (int m = 0; m < 2; ++m) {
+        uint32_t lo, hi;
+        spread_byte(w[ks], 2 * half + m, lo, hi);
+        // a set bit j of the byte: -128 / 2^j for j < 7, +1 for j = 7
+        bq[j][ks][2 * m] = (int)(bytes_to_mask(lo) & 0xF0E0C080u);
+        bq[j][ks][2 * m + 1] = (int)(bytes_to_mask(hi) & 0x01FEFCF8u);
+      }
     }
   }
 
   // staging: thread (row, part) expands bits 64 part .. 64 part + 63 of tile row `row` into four 16-byte
-  // chunks; chunks of a row are XOR-swizzled by the row so that fragment reads of 16 rows cover all banks
-  const int s_row = tid >> 2, s_part = tid & 3;
+  // chunks.  Lanes are dealt so that any 8 consecutive ones (4 rows x 2 parts) write 8 different chunk
+  // positions and any 16 write 16.
+  const int s_row = ((tid >> 1) & 3) | ((tid >> 4) << 2), s_part = (tid & 1) | (((tid >> 3) & 1) << 1);
   auto load_bits = [&](int t) {
     const int r = min(t * C::RB + s_row, N - 1);
     return *reinterpret_cast<const uint2*>(bank + (size_t)r * C::W + s_part * 2);
@@ -177,12 +197,13 @@ __global__ __launch_bounds__(BitsMma::THREADS, 2) void match_bits_mma_kernel(
     uint8_t* st = lds_bits + stage * C::STAGE_BYTES;
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
-      const uint32_t h16 = ((c < 2 ? w.x : w.y) >> (16 * (c & 1))) & 0xFFFFu;
+      const uint32_t word = c < 2 ? w.x : w.y;
+      uint32_t v0, v1, v2, v3;
+      spread_byte(word, 2 * (c & 1), v0, v1);
+      spread_byte(word, 2 * (c & 1) + 1, v2, v3);
       i32x4_t v;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) v[e] = spread4<2>((h16 >> (4 * e)) & 15u);
-      const int chunk = (s_part * 4 + c) ^ (s_row & 15);
-      *reinterpret_cast<i32x4_t*>(st + s_row * C::ROWB + chunk * 16) = v;
+      v[0] = (int)v0; v[1] = (int)v1; v[2] = (int)v2; v[3] = (int)v3;
+      *reinterpret_cast<i32x4_t*>(st + s_row * C::ROWB + (s_part * 4 + c) * 16) = v;
     }
     if (tid < C::RB) *reinterpret_cast<int*>(st + C::TILE_BYTES + tid * 4) = sv;
   };
@@ -196,7 +217,7 @@ __global__ __launch_bounds__(BitsMma::THREADS, 2) void match_bits_mma_kernel(
   }
 
   int best_v[2] = {0x7FFFFFFF, 0x7FFFFFFF}, best_row[2] = {0, 0};
-  const int frag_off = (lane & 31) * C::ROWB, fsw = lane & 15;
+  const int frag_off = (lane & 31) * C::ROWB + half * 16;
 
   for (int t = t_begin; t < t_end; ++t) {
     const int cur = (t - t_begin) & 1;
@@ -220,17 +241,32 @@ __global__ __launch_bounds__(BitsMma::THREADS, 2) void match_bits_mma_kernel(
         const i32x4_t v = *reinterpret_cast<const i32x4_t*>(sst + i * 32 + half * 4 + 8 * c);
         c0[i][4 * c] = v[0]; c0[i][4 * c + 1] = v[1]; c0[i][4 * c + 2] = v[2]; c0[i][4 * c + 3] = v[3];
       }
+    // bank fragments of step ks + 1 are requested before step ks multiplies
+    i32x4_t fa[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+      fa[0][i] = *reinterpret_cast<const i32x4_t*>(stg + i * 32 * C::ROWB + frag_off);
+    __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
 #pragma unroll
     for (int ks = 0; ks < C::W; ++ks) {
-      i32x4_t fa[2];
+      const int c = ks & 1, n = c ^ 1;
+      // the fragments of this step were requested one step ago: wait for them BEFORE requesting the next
+      // ones, so that the wait does not cover a request that has only just been issued
+      __builtin_amdgcn_sched_barrier(0);
+      LLMC_WAIT_LGKM(0);
+      __builtin_amdgcn_sched_barrier(0);
+      if (ks + 1 < C::W) {
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
-        fa[i] = *reinterpret_cast<const i32x4_t*>(stg + i * 32 * C::ROWB + frag_off + (((ks * 2 + half) ^ fsw) * 16));
+        for (int i = 0; i < 2; ++i)
+          fa[n][i] = *reinterpret_cast<const i32x4_t*>(stg + i * 32 * C::ROWB + frag_off + (ks + 1) * 32);
+      }
 #pragma unroll
       for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], bq[j][ks], ks == 0 ? c0[i] : acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[c][i], bq[j][ks], ks == 0 ? c0[i] : acc[i][j], 0, 0, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
     }
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
@@ -238,7 +274,7 @@ __global__ __launch_bounds__(BitsMma::THREADS, 2) void match_bits_mma_kernel(
 #pragma unroll
       for (int r = 1; r < 16; ++r) m = min(min(m, acc[0][j][r]), acc[1][j][r]);
       // tiles ascend: a strictly smaller distance wins, so the lowest row is kept among equals
-      const int v = m >> 7;
+      const int v = m >> 6;                  // SCALE = 64
       if (v < best_v[j]) {
         best_v[j] = v;
         best_row[j] = t * C::RB + (m & (C::SCALE - 1));
@@ -312,7 +348,7 @@ static bool bits_use_mma(int N, int k, int B) { return k == BitsMma::K && B >= 2
 static void bits_mma_plan(int N, int B, int* n_qb, int* n_split, int* tiles_per_split) {
   const int qb = (B + BitsMma::QB - 1) / BitsMma::QB;
   const int n_tiles = (N + BitsMma::RB - 1) / BitsMma::RB;
-  int want = (2048 + qb - 1) / qb;                          // about eight workgroups per compute unit
+  int want = (3072 + qb - 1) / qb;                          // four rounds of three workgroups per compute unit
   want = (want + 7) / 8 * 8;                                // splits are dealt to the 8 XCDs
   if (want > n_tiles) want = n_tiles;
   int per = (n_tiles + want - 1) / want;

@@ -15,6 +15,11 @@ With --dense-rows R it runs, instead, the miss path alone: one post-LayerNorm en
 layers, the attention and the two LayerNorms that a cache-gated layer launches for R misses.
 
     python -m paper_2512_16843_amd.kernel_bench --dense-rows 28
+
+With --bit-keys it runs, instead, llmc_match_bits over N random sign-bit keys of k bits and B queries
+(half of them bank keys with a few bits flipped).
+
+    python -m paper_2512_16843_amd.kernel_bench --bit-keys --B 4096 --N 1048576 --iters 3
 """
 import argparse
 import json
@@ -38,6 +43,7 @@ def main():
     ap.add_argument("--iters", type=int, default=5)
     ap.add_argument("--dense-rows", type=int, default=0,
                     help="run the dense block of the miss path over this many sequences instead of the gate's kernels")
+    ap.add_argument("--bit-keys", action="store_true", help="run the Hamming match of sign-bit keys instead")
     args = ap.parse_args()
     B, S, d, k, N, A = args.B, args.S, args.d, args.k, args.N, min(args.act_slots, args.N)
     dev, dt = "cuda", torch.bfloat16
@@ -51,6 +57,9 @@ def main():
     torch.cuda.synchronize()
     if args.dense_rows > 0:
         dense(args)
+        return
+    if args.bit_keys:
+        bit_keys(args)
         return
 
     # several distinct inputs so that repeated launches do not re-read a cache-resident tensor
@@ -105,6 +114,40 @@ def main():
                                 "algorithmic_bytes": by}
         print("%-24s avg %9.2f us  %9.1f GB/s  %8.2f TFLOP/s" % (name, us, by / us / 1e3, fl / us / 1e6), file=sys.stderr)
     bank.close()
+    print(json.dumps(res))
+
+
+def bit_keys(args):
+    B, N, k = args.B, args.N, args.k
+    W_ = k // 32
+    bank = torch.randint(-2 ** 31, 2 ** 31, (N, W_), dtype=torch.int64, device="cuda").to(torch.int32)
+    q = torch.randint(-2 ** 31, 2 ** 31, (B, W_), dtype=torch.int64, device="cuda").to(torch.int32)
+    src = torch.randint(0, N, (B // 2,), device="cuda")
+    flips = torch.zeros((B // 2, W_), dtype=torch.int32, device="cuda")
+    flips[:, 0] = 0x00010101                                    # three bits away from a bank key
+    q[: B // 2] = bank[src] ^ flips
+    valid = torch.ones((N,), dtype=torch.uint8, device="cuda")
+    idx = torch.empty((B,), dtype=torch.int32, device="cuda")
+    dist = torch.empty((B,), dtype=torch.int32, device="cuda")
+    hit = torch.empty((B,), dtype=torch.uint8, device="cuda")
+    ws = torch.empty((llmc.llmc_match_bits_workspace_bytes(N, k, B),), dtype=torch.uint8, device="cuda")
+    max_h = llmc.llmc_max_hamming(0.95, k)
+    llmc.llmc_match_bits(bank, valid, q, max_h, idx, dist, hit, ws)
+    torch.cuda.synchronize()
+    llmc.llmc_profile_begin(4 * args.iters)
+    for _ in range(args.iters):
+        llmc.llmc_match_bits(bank, valid, q, max_h, idx, dist, hit, ws)
+    rep = llmc.llmc_profile_report()
+    llmc.llmc_profile_end()
+    res = {"shape": {"B": B, "N": N, "key_bits": k}, "calib_copy_bytes": CALIB_COPY_BYTES,
+           "hits": int(hit.sum()), "kernels": {}}
+    for name, (cnt, ms) in sorted(rep.items()):
+        us = ms * 1e3 / cnt
+        scan = name in ("match_bits_mma_kernel", "match_bits_kernel")
+        ops = 2.0 * B * N * k if scan else 0.0                    # bit pairs compared, as multiply-adds
+        res["kernels"][name] = {"avg_us": round(us, 2), "tera_bit_ops_per_s": round(ops / us / 1e6, 1),
+                                "algorithmic_bytes": float(N) * k / 8 if scan else 0.0}
+        print("%-28s avg %9.2f us  %9.1f T bit-ops/s" % (name, us, ops / us / 1e6), file=sys.stderr)
     print(json.dumps(res))
 
 
