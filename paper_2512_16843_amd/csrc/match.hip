@@ -382,25 +382,33 @@ __global__ __launch_bounds__(512) void match_skew_kernel(
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = NAN;
 
-  // running maximum over the accumulators of tile t, scaled by the inverse norms at sb
+  // running maximum over the accumulators of tile t, scaled by the inverse norms at sb; the maximum of a
+  // fragment's 16 scores is a chain (the fourth product of each group of four is carried into the next link),
+  // so that every link is one three-operand maximum
   auto reduce = [&](const float* sb, int t) {
 #pragma unroll
     for (int i = 0; i < C::FM; ++i) {
       const int g = t * 4 + i * 2 + half;
-      float m[C::FN];
+      float m[C::FN], carry[C::FN];
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
         const float4 v4 = *reinterpret_cast<const float4*>(sb + i * 32 + half * 4 + 8 * c);
 #pragma unroll
         for (int j = 0; j < C::FN; ++j) {
-          const float p = fmaxf(fmaxf(acc[i][j][4 * c] * v4.x, acc[i][j][4 * c + 1] * v4.y),
-                                fmaxf(acc[i][j][4 * c + 2] * v4.z, acc[i][j][4 * c + 3] * v4.w));
-          m[j] = c == 0 ? p : fmaxf(m[j], p);
+          const float p0 = acc[i][j][4 * c] * v4.x, p1 = acc[i][j][4 * c + 1] * v4.y;
+          const float p2 = acc[i][j][4 * c + 2] * v4.z, p3 = acc[i][j][4 * c + 3] * v4.w;
+          if (c == 0) {
+            m[j] = fmaxf(fmaxf(p0, p1), p2);
+          } else {
+            m[j] = fmaxf(fmaxf(m[j], carry[j]), p0);
+            m[j] = fmaxf(fmaxf(m[j], p1), p2);
+          }
+          carry[j] = p3;
         }
       }
 #pragma unroll
       for (int j = 0; j < C::FN; ++j) {
-        top2_next(best[j], m[j], g);
+        top2_next(best[j], fmaxf(m[j], carry[j]), g);
       }
     }
   };
