@@ -454,7 +454,9 @@ size_t llmc_fingerprint_prefix_workspace_bytes(const llmc_layer_desc_t* layer, i
  *   d_bank_bits [N, k / 32], d_valid [N] (0 = free slot), d_query_bits [B, k / 32]: device, uint32 words as above
  *   d_idx [B]: nearest valid slot, lowest slot among equal distances, -1 if no slot is valid
  *   d_dist [B]: its Hamming distance, 0x7FFFFFFF if none;  d_hit [B]: idx >= 0 and dist <= max_hamming
- *   (d_dist, d_hit may be NULL).  Integer work throughout: results are exact.
+ *   (d_dist, d_hit may be NULL).  Integer work throughout: results are exact.  Which kernel scans the bank depends
+ *   on the sizes only (512 queries or more of 256-bit keys in 16-byte aligned arrays: an int8 matrix-core product of
+ *   the expanded bits; otherwise XOR + popcount on the vector ALU); the results do not.
  * d_workspace: at least llmc_match_bits_workspace_bytes(N, k, B) bytes.  Nothing is allocated or synchronised.
  * Errors: INVALID_ARG (null, sizes <= 0), SHAPE (k % 32 != 0 or k > 1024, N > 2^30), WORKSPACE.
  */
