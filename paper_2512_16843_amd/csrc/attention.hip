@@ -62,7 +62,10 @@ __global__ __launch_bounds__(AttnCfg::THREADS) void attention_mfma_kernel(const 
   __shared__ __attribute__((aligned(16))) uint16_t sV[2][C::V_ELEMS];
   const int n_seq = count ? min(*count, max_seqs) : max_seqs;
   const int n_qb = (S + C::QB - 1) / C::QB;
-  const int total = n_seq * n_heads * n_qb;
+  // Causal: query block qb reads qb + 1 key blocks, so a work item is the PAIR (n_qb - 1 - x, x) of query blocks of
+  // one (sequence, head): every item then costs the same number of key tiles and the grid stays balanced.
+  const int per = CAUSAL ? (n_qb + 1) / 2 : n_qb;
+  const int total = n_seq * n_heads * per;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5;
   const size_t ld = 3 * (size_t)d;
   // staging role of this thread, K: rows st_row and st_row + 32, dh chunk of 8
@@ -76,8 +79,14 @@ __global__ __launch_bounds__(AttnCfg::THREADS) void attention_mfma_kernel(const 
   const int fv_off = (lane & 31) * C::V_STRIDE + half * 4;
   const bf16x2_t ones = {(__bf16)1.0f, (__bf16)1.0f};
 
-  for (int item = blockIdx.x; item < total; item += gridDim.x) {
-    const int qb = item % n_qb, head = (item / n_qb) % n_heads, seq = item / (n_qb * n_heads);
+  // one flat loop: step `it` of a workgroup is half it % 2 of its (it / 2)-th item (non-causal: every step an item)
+  for (int it = 0;; ++it) {
+    const int item = blockIdx.x + (CAUSAL ? it >> 1 : it) * gridDim.x;
+    if (item >= total) break;
+    const int x = item % per, head = (item / per) % n_heads, seq = item / (per * n_heads);
+    const bool second = CAUSAL && (it & 1);
+    if (second && n_qb - 1 - x == x) continue;                      // the middle block of an odd count pairs with itself
+    const int qb = CAUSAL ? (second ? x : n_qb - 1 - x) : x;        // the longer block of a pair first
     const int q0 = qb * C::QB;
     const uint16_t* base = qkv + (size_t)seq * S * ld + head * C::DH;
     const int kv_end = CAUSAL ? min(S, q0 + C::QB) : S;
@@ -128,6 +137,9 @@ __global__ __launch_bounds__(AttnCfg::THREADS) void attention_mfma_kernel(const 
     for (int t = 0; t < n_tiles; ++t) {
       const int buf = t & 1;
       if (t + 1 < n_tiles) LLMC_ATTN_LOAD(t + 1)
+      // a key tile that lies wholly behind this wavefront's 32 queries contributes nothing: only stage the next one
+      const bool masked_out = CAUSAL && t * C::KT > q0 + wave * 32 + 31;
+      if (!masked_out) {
       // ---- S^T = K * Q^T for 64 keys x 32 queries ----
       const uint16_t* kf = &sK[buf][fk_off];
       const f32x16_t zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -196,6 +208,7 @@ __global__ __launch_bounds__(AttnCfg::THREADS) void attention_mfma_kernel(const 
         o0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va.v, pb.v, o0, 0, 0, 0);
         o1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vb.v, pb.v, o1, 0, 0, 0);
       }
+      }
       if (t + 1 < n_tiles) LLMC_ATTN_STORE(buf ^ 1)
       __syncthreads();
     }
@@ -228,7 +241,8 @@ llmc_status_t launch_attention_bf16(const void* qkv, void* ctx, int S, int d, in
   if (d != n_heads * AttnCfg::DH) return LLMC_ERR_SHAPE;
   // base-2 softmax with log2(e) folded into the score scale
   const float scale_log2e = (1.0f / sqrtf((float)AttnCfg::DH)) * 1.4426950408889634f;
-  const int items = ((S + AttnCfg::QB - 1) / AttnCfg::QB) * n_heads * max_seqs;
+  const int n_qb = (S + AttnCfg::QB - 1) / AttnCfg::QB;
+  const int items = (causal ? (n_qb + 1) / 2 : n_qb) * n_heads * max_seqs;   // causal: pairs of query blocks
   if (items <= 0) return LLMC_OK;
   const dim3 grid(std::min(items, kMaxAttnGrid));
   ProfScope ps_("attention_kernel", st);
