@@ -197,24 +197,67 @@ __device__ __forceinline__ void gemm_epilogue_wave16(const GemmArgs& g, f32x16_t
   }
 }
 
-template <class C>
+template <class C, class CS>
 constexpr size_t gemm_dma_smem_bytes() {
-  return C::LDS_BYTES;
+  return C::LDS_BYTES > CS::LDS_BYTES ? C::LDS_BYTES : CS::LDS_BYTES;
 }
+
+// at most this many C tiles in a launch: the launch takes CS tiles instead (see the kernel)
+constexpr int kGemmSmallTiles = 256;
 
 // Same contract, main loop with direct global -> LDS loads (C is a DmaCfg with two stages); K % 64 == 0.
 // A workgroup walks its tiles with ONE ring of two stages that runs on across tiles: when the main loop of a tile
 // ends, the first loads of the workgroup's next tile go into the stage that is free, and only then does the epilogue
 // start (its staging lives in the stage the last step has just been read from), so the memory latency of a tile's
 // first step hides behind the previous tile's epilogue instead of standing in front of every tile.
-template <class C>
+// Few rows (the count is read on the device): when the C tiles of a launch would not even give every compute unit
+// one, the launch is cut into the smaller CS tiles instead (same columns, half the rows, so twice as many
+// workgroups have work) and each tile runs its main loop with a deeper ring of its own, because a workgroup that has
+// its compute unit to itself spends a step waiting for that step's loads.  An output element is accumulated over k
+// in the same order by either tiling, so the bits of a row do not depend on how many rows are computed with it.
+template <class C, class CS>
 __global__ __launch_bounds__(C::THREADS) void gemm_bf16_dma_kernel(GemmArgs g, int tiles_n) {
+  static_assert(C::THREADS == CS::THREADS && C::BN == CS::BN, "the two tilings share the launch shape and the column tiles");
   extern __shared__ __attribute__((aligned(16))) uint16_t lds_dyn[];
   const int n_seq = g.count ? min(*g.count, g.max_seqs) : g.max_seqs;
   const int M = n_seq * g.S;
   const int tiles_m = (M + C::BM - 1) / C::BM;
   const int total = tiles_m * tiles_n;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (total <= kGemmSmallTiles) {
+    const int total_s = ((M + CS::BM - 1) / CS::BM) * tiles_n;
+    const uint16_t* A = (const uint16_t*)g.A;
+    const uint16_t* W = (const uint16_t*)g.W;
+    for (int tile = blockIdx.x; tile < total_s; tile += gridDim.x) {
+      const int m0 = (tile / tiles_n) * CS::BM, n0 = (tile % tiles_n) * CS::BN;
+      const uint16_t* a_ptr[CS::A_INSTR];
+      const uint16_t* b_ptr[CS::B_INSTR];
+#pragma unroll
+      for (int j = 0; j < CS::A_INSTR; ++j) {
+        const int tr = CS::load_row(j, wave, lane);
+        const int r = min(m0 + tr, M - 1);
+        a_ptr[j] = A + map_row(g.a_rows, r, g.S) * g.lda + CS::load_chunk(tr, lane) * 8;
+      }
+#pragma unroll
+      for (int j = 0; j < CS::B_INSTR; ++j) {
+        const int tr = CS::load_row(j, wave, lane);
+        const int r = min(n0 + tr, g.N - 1);
+        b_ptr[j] = W + (size_t)r * g.K + CS::load_chunk(tr, lane) * 8;
+      }
+      f32x16_t acc[CS::FM][CS::FN];
+#pragma unroll
+      for (int i = 0; i < CS::FM; ++i)
+#pragma unroll
+        for (int j = 0; j < CS::FN; ++j)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+      mma_block_dma<CS>(a_ptr, b_ptr, g.K, lds_dyn, acc);
+      // every stage is free after the main loop: the staging of the epilogue takes the first one
+      gemm_epilogue_wave16<CS>(g, acc, m0, n0, M, reinterpret_cast<float*>(lds_dyn), false);
+      dma::barrier();             // ... and is read out before the next tile's first loads land there
+    }
+    return;
+  }
   // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  With xcd_chunks set, XCD x
   // walks the x-th eighth of the tile list, so the operand panels of neighbouring tiles are fetched into one L2
   // only and shared there; otherwise workgroups stride over the tile list.  gridDim.x % 8 == 0 when xcd_chunks.

@@ -84,20 +84,26 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmArgs g, int tiles_n) 
 // 128 x 128 block, 8 wavefronts (2 x 4), two 64-column stages filled by direct-to-LDS loads: 68 KiB of LDS,
 // so two workgroups share a compute unit and one's epilogue overlaps the other's main loop
 typedef DmaCfg<128, 128, 2, 4, 2> GemmDmaCfg;
+// with few rows: 64 x 128 blocks, three stages (72 KiB, still two workgroups per compute unit)
+typedef DmaCfg<64, 128, 2, 4, 3> GemmDmaSmallCfg;
 
 static llmc_status_t launch_gemm(const GemmArgs& g, int dtype, hipStream_t st) {
   if (dtype == LLMC_BF16) {
     if (g.K % 64 == 0) {
       using C = GemmDmaCfg;
+      using CS = GemmDmaSmallCfg;
       static std::atomic<bool> lds_set[64];
-      LLMC_TRY(ensure_dynamic_lds((const void*)gemm_bf16_dma_kernel<C>, gemm_dma_smem_bytes<C>(), lds_set));
+      const auto kernel = gemm_bf16_dma_kernel<C, CS>;
+      const size_t lds_bytes = gemm_dma_smem_bytes<C, CS>();
+      LLMC_TRY(ensure_dynamic_lds((const void*)kernel, lds_bytes, lds_set));
       const int tiles_n = (g.N + C::BN - 1) / C::BN;
-      const int tiles_m = (g.max_seqs * g.S + C::BM - 1) / C::BM;
+      // the grid covers the smaller tiling too, which the kernel takes when the rows it finds on the device are few
+      const int tiles_m = (g.max_seqs * g.S + CS::BM - 1) / CS::BM;
       GemmArgs a = g;
       a.xcd_chunks = tiles_n <= 8 ? 1 : 2;   // every XCD walks its own eighth of the tile list; wide outputs in grouped order
       ProfScope ps_("gemm_bf16_kernel", st);
-      LLMC_KERNEL_GGL(gemm_bf16_dma_kernel<C>, dim3(std::min((tiles_m * tiles_n + 7) & ~7, kMaxGrid)), dim3(C::THREADS),
-                         gemm_dma_smem_bytes<C>(), st, a, tiles_n);
+      LLMC_KERNEL_GGL(kernel, dim3(std::min((tiles_m * tiles_n + 7) & ~7, kMaxGrid)), dim3(C::THREADS), lds_bytes, st, a,
+                      tiles_n);
     } else {
       const int tiles_n = (g.N + GemmCfg::BN - 1) / GemmCfg::BN;
       const int tiles_m = (g.max_seqs * g.S + GemmCfg::BM - 1) / GemmCfg::BM;

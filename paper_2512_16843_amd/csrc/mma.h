@@ -244,4 +244,72 @@ __device__ __forceinline__ void mma_block_dma_ring(const uint16_t* const (&a_ptr
   dma::barrier();
 }
 
+// The main loop of ONE tile with a ring of C::STAGES stages of its own (STAGES - 1 steps in flight): for launches
+// with fewer tiles than compute units, where a workgroup has its compute unit to itself and a step's time is the
+// latency of its loads.  Starts and ends with every stage free; ends with a barrier.
+template <class C>
+__device__ __forceinline__ void mma_block_dma(const uint16_t* const (&a_ptr)[C::A_INSTR],
+                                              const uint16_t* const (&b_ptr)[C::B_INSTR], int K, uint16_t* lds,
+                                              f32x16_t (&acc)[C::FM][C::FN]) {
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wm = wave / C::WN, wn = wave % C::WN;
+  const int nk = K / C::BK;
+
+  auto issue = [&](int kt) { dma_issue<C>(a_ptr, b_ptr, kt, kt % C::STAGES, lds); };
+#pragma unroll
+  for (int s = 0; s < C::STAGES - 1; ++s)
+    if (s < nk) issue(s);
+
+  // fragment read offsets (elements): row * 64 + ((chunk ^ ((row / 2) & 7)) * 8), (row / 2) & 7 == (lane / 2) & 7
+  const int a_row = (wm * (C::BM / C::WM) + (lane & 31)) * C::BK;
+  const int b_row = C::BM * C::BK + (wn * (C::BN / C::WN) + (lane & 31)) * C::BK;
+  int sw[4];
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) sw[ks] = (((ks * 2 + (lane >> 5)) ^ ((lane >> 1) & 7)) * 8);
+
+  for (int kt = 0; kt < nk; ++kt) {
+    const int ahead = min(C::STAGES - 2, nk - 1 - kt);
+    if (ahead <= 0) LLMC_WAIT_VM(0);
+    else if (ahead == 1) LLMC_WAIT_VM(C::L);
+    else LLMC_WAIT_VM(2 * C::L);
+    dma::barrier();
+    if (kt + C::STAGES - 1 < nk) issue(kt + C::STAGES - 1);
+    const uint16_t* st = lds + (kt % C::STAGES) * C::STAGE_ELEMS;
+    // fragments of the next 16-column step are fetched while the current step multiplies
+    bf16x8_t fa[2][C::FM], fb[2][C::FN];
+#pragma unroll
+    for (int i = 0; i < C::FM; ++i) fa[0][i] = *reinterpret_cast<const bf16x8_t*>(st + a_row + i * 32 * C::BK + sw[0]);
+#pragma unroll
+    for (int j = 0; j < C::FN; ++j) fb[0][j] = *reinterpret_cast<const bf16x8_t*>(st + b_row + j * 32 * C::BK + sw[0]);
+    __builtin_amdgcn_sched_group_barrier(0x100, C::FM + C::FN, 0);
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      const int c = ks & 1, n = c ^ 1;
+      // this step's fragments were requested one step ago: wait for them BEFORE requesting the next
+      // ones, so that the wait never covers a request that has only just been issued
+      __builtin_amdgcn_sched_barrier(0);
+      LLMC_WAIT_LGKM(0);
+      __builtin_amdgcn_sched_barrier(0);
+      if (ks + 1 < 4) {
+#pragma unroll
+        for (int i = 0; i < C::FM; ++i)
+          fa[n][i] = *reinterpret_cast<const bf16x8_t*>(st + a_row + i * 32 * C::BK + sw[ks + 1]);
+#pragma unroll
+        for (int j = 0; j < C::FN; ++j)
+          fb[n][j] = *reinterpret_cast<const bf16x8_t*>(st + b_row + j * 32 * C::BK + sw[ks + 1]);
+      }
+#pragma unroll
+      for (int i = 0; i < C::FM; ++i)
+#pragma unroll
+        for (int j = 0; j < C::FN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[c][i], fb[c][j], acc[i][j], 0, 0, 0);
+      // keep the written order: the next step's LDS reads are issued before this step's MFMAs
+      if (ks + 1 < 4) __builtin_amdgcn_sched_group_barrier(0x100, C::FM + C::FN, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, C::FM * C::FN, 0);
+    }
+  }
+  dma::barrier();   // every wavefront is done reading before the caller reuses the LDS
+}
+
 }  // namespace llmc

@@ -1737,6 +1737,31 @@ def test_large_batch_equals_its_halves(L):
         st.close()
 
 
+@pytest.mark.parametrize("arch", [0, 1])
+def test_few_rows_and_many_rows_give_the_same_bits(L, arch):
+    """A launch with few rows cuts the linear layers into smaller tiles with a deeper ring than a launch with many:
+    a sequence must come out with the same bits whether it is computed among 64 or among 4."""
+    from paper_2512_16843_amd.engine import GatedStack
+    say(f"plain block arch={arch}: 64 sequences of 128 tokens at once against the first 4 and the last 3 alone")
+    base = W.BERT_BASE if arch == 0 else W.GPT2_SMALL
+    cfg = W.scaled(base, n_layers=2, B=64, S=128)
+    ws = W.make_layer_weights(cfg, seed=5)
+    Ps = W.make_projection(cfg.d, cfg.k, cfg.torch_dtype, seed=3, n_layers=cfg.n_layers)
+    g = torch.Generator(device="cuda").manual_seed(3)
+    h0 = (torch.randn((64, 128, cfg.d), generator=g, device="cuda") * 0.5).to(cfg.torch_dtype)
+    big = GatedStack(cfg, ws, Ps, cached_layers=[])
+    y_big = big.forward(h0, tau=2.0).clone()
+    torch.cuda.synchronize()
+    for rows in (slice(0, 4), slice(61, 64)):
+        n = rows.stop - rows.start
+        few = GatedStack(W.scaled(cfg, B=n), ws, Ps, cached_layers=[])
+        y = few.forward(h0[rows].contiguous(), tau=2.0).clone()
+        torch.cuda.synchronize()
+        assert torch.equal(y, y_big[rows])
+        few.close()
+    big.close()
+
+
 @pytest.mark.parametrize("carry", [False, True], ids=["plain", "carried"])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_within_batch_reuse_against_oracle(L, dtype, carry):
